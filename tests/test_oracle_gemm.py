@@ -1,0 +1,117 @@
+"""Pins for the oracle's GEMM and convolution.  CPU only."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import c_ref, dybit_ref as R
+
+PAIRS = [((4, False), (4, True)), ((8, True), (4, True)), ((6, False), (6, True)),
+         ((8, False), (8, True)), ((4, True), (8, False)), ((2, True), (4, False))]
+
+
+def _codes(rng, shape, fmt):
+    return rng.integers(0, 1 << fmt[0], shape).astype(np.uint8)
+
+
+@pytest.mark.parametrize("a_fmt,w_fmt", PAIRS)
+def test_gemm_vs_exact_loops(a_fmt, w_fmt):
+    rng = np.random.default_rng(1)
+    a = _codes(rng, (5, 12), a_fmt)
+    w = _codes(rng, (4, 12), w_fmt)
+    bias = rng.normal(0, 1, 4).astype(np.float32)
+    sa, sw = np.float32(0.37), np.float32(0.011)
+    for b, relu in ((None, False), (bias, False), (bias, True)):
+        c, d = R.gemm(a, a_fmt, sa, w, w_fmt, sw, b, relu)
+        want = R.gemm_loops(a, a_fmt, sa, w, w_fmt, sw, b, relu)
+        assert np.all(np.abs(c - want) <= 4e-16 * d)       # a few float64 roundings of the scaling
+        cc, dc = c_ref.gemm(a, a_fmt, sa, w, w_fmt, sw, b, relu)
+        assert np.array_equal(cc, c) and np.array_equal(dc, d)
+        assert np.all(d >= np.abs(c) - 1e-12)
+
+
+@pytest.mark.parametrize("a_fmt,w_fmt", PAIRS)
+def test_gemm_vs_float64_matmul_of_dequantized(a_fmt, w_fmt):
+    """Library routine: numpy float64 matmul over the decoded values."""
+    rng = np.random.default_rng(2)
+    a = _codes(rng, (33, 70), a_fmt)
+    w = _codes(rng, (21, 70), w_fmt)
+    sa, sw = np.float32(0.5), np.float32(0.125)            # exact scaling
+    va = R.codebook(*a_fmt)[a] * float(sa)
+    vw = R.codebook(*w_fmt)[w] * float(sw)
+    c, d = R.gemm(a, a_fmt, sa, w, w_fmt, sw)
+    assert np.array_equal(c, va @ vw.T)                    # all partial sums exact in float64
+    assert np.array_equal(d, np.abs(va) @ np.abs(vw).T)
+
+
+def test_gemm_identity_and_popcount():
+    rng = np.random.default_rng(3)
+    a_fmt, w_fmt = (8, True), (4, True)
+    K = 16
+    a = _codes(rng, (9, K), a_fmt)
+    one_w = int(np.where(R.codebook(*w_fmt) == 1.0)[0][0])
+    w = np.zeros((K, K), np.uint8)
+    w[np.arange(K), np.arange(K)] = one_w                  # identity in code space
+    sa, sw = np.float32(0.3), np.float32(2.0)
+    c, _ = R.gemm(a, a_fmt, sa, w, w_fmt, sw)
+    assert np.allclose(c, 2.0 * np.float64(sa) * R.codebook(*a_fmt)[a], rtol=1e-15)
+    # codes restricted to {0, 1.0}: the sum is the popcount of the AND
+    one_a = int(np.where(R.codebook(*a_fmt) == 1.0)[0][0])
+    ba = rng.integers(0, 2, (7, 40)).astype(bool)
+    bw = rng.integers(0, 2, (6, 40)).astype(bool)
+    c, d = R.gemm(np.where(ba, one_a, 0), a_fmt, 1.0, np.where(bw, one_w, 0), w_fmt, 1.0)
+    pop = (ba[:, None, :] & bw[None, :, :]).sum(-1)
+    assert np.array_equal(c, pop) and np.array_equal(d, pop)
+
+
+def test_gemm_k_split_additivity_and_transpose_guard():
+    rng = np.random.default_rng(4)
+    a_fmt, w_fmt = (6, False), (8, True)
+    a = _codes(rng, (8, 48), a_fmt)
+    w = _codes(rng, (5, 48), w_fmt)
+    c, _ = R.gemm(a, a_fmt, 1.0, w, w_fmt, 1.0)
+    c1, _ = R.gemm(a[:, :20], a_fmt, 1.0, w[:, :20], w_fmt, 1.0)
+    c2, _ = R.gemm(a[:, 20:], a_fmt, 1.0, w[:, 20:], w_fmt, 1.0)
+    assert np.array_equal(c, c1 + c2)
+    assert c.shape == (8, 5)                               # [M][N], W given as [N][K]
+    # a single non-zero product lands where it must
+    a0 = np.zeros((3, 4), np.uint8); w0 = np.zeros((2, 4), np.uint8)
+    a0[2, 1] = 1; w0[1, 1] = 1
+    c0, _ = R.gemm(a0, (8, False), 1.0, w0, (8, False), 1.0)
+    assert c0[2, 1] == (1 / 128) ** 2 and np.count_nonzero(c0) == 1
+
+
+@pytest.mark.parametrize("stride,pad,k", [(1, 1, 3), (2, 3, 7), (2, 0, 1), (1, 0, 3)])
+def test_conv2d_vs_torch_float64(stride, pad, k):
+    """Library routine: torch conv2d in float64 over the decoded tensors."""
+    rng = np.random.default_rng(5)
+    x_fmt, w_fmt = (4, False), (4, True)
+    B, H, W, Cin, Cout = 2, 9, 8, 6, 5
+    x = _codes(rng, (B, H, W, Cin), x_fmt)
+    w = _codes(rng, (Cout, k, k, Cin), w_fmt)
+    bias = rng.normal(0, 1, Cout).astype(np.float32)
+    sx, sw = np.float32(0.25), np.float32(0.5)
+    y, d = R.conv2d(x, x_fmt, sx, w, w_fmt, sw, stride, pad, bias, relu=True)
+    vx = torch.from_numpy(R.codebook(*x_fmt)[x] * float(sx)).permute(0, 3, 1, 2)
+    vw = torch.from_numpy(R.codebook(*w_fmt)[w] * float(sw)).permute(0, 3, 1, 2)
+    want = torch.nn.functional.conv2d(vx, vw, torch.from_numpy(bias.astype(np.float64)),
+                                      stride=stride, padding=pad).clamp_min(0).permute(0, 2, 3, 1).numpy()
+    assert y.shape == want.shape
+    assert np.allclose(y, want, rtol=1e-13, atol=1e-13)
+    yc, dc = c_ref.conv2d(x, x_fmt, sx, w, w_fmt, sw, stride, pad, bias, relu=True)
+    assert np.array_equal(yc, y) and np.array_equal(dc, d)
+
+
+def test_c_gemm_matches_numpy_on_config1_shape():
+    from paper_2302_12510_amd import synth
+    cfg = synth.config1()
+    a_fmt, w_fmt = (4, False), (4, True)
+    sa = R.absmax_scale(cfg["A"], *a_fmt)
+    sw = R.absmax_scale(cfg["W"], *w_fmt)
+    qa = R.quantize(cfg["A"], sa, *a_fmt)
+    qw = R.quantize(cfg["W"], sw, *w_fmt)
+    c, d = R.gemm(qa, a_fmt, sa, qw, w_fmt, sw)
+    cc, dc = c_ref.gemm(qa, a_fmt, sa, qw, w_fmt, sw)
+    assert np.array_equal(c, cc) and np.array_equal(d, dc)
+    # the quantized product tracks the float product (sanity of the whole chain)
+    ref = cfg["A"].astype(np.float64) @ cfg["W"].astype(np.float64).T
+    assert np.corrcoef(ref.ravel(), c.ravel())[0, 1] > 0.95
