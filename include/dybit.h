@@ -1,0 +1,125 @@
+/* libdybit: DyBit quantization and DyBit x DyBit matrix products on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every function returns a dybit_status (or a plain value where said);
+ * nothing throws or aborts.  Argument errors are found on the host before any
+ * kernel is launched, so they can be exercised on a machine without a GPU.
+ *
+ * Pointers are tagged [host] or [device].  Device work is asynchronous on the
+ * given stream (a raw hipStream_t; NULL is the default stream).  The caller owns
+ * every buffer; the library allocates no device memory.
+ *
+ * Number format (paper Sec. III-A, Eq. 1, Table I).  An N-bit signed code is a
+ * sign bit followed by m = N-1 magnitude bits; an N-bit unsigned code is m = N
+ * magnitude bits.  Magnitude code c decodes to
+ *     0                         c == 0
+ *     2^(m-1)                   c all ones (Table I: 1111 -> 8)
+ *     c / 2^(m-1)               first bit 0 (fraction only)
+ *     2^(i-1) (1 + x / 2^k)     i leading ones, a zero, then k = m-i-1 fraction bits x
+ * and a signed code to (-1)^s times that.  The pattern sign=1, magnitude=0 decodes
+ * to +0 and is never produced.
+ *
+ * Packed storage.  Codes form a little-endian bit stream: code j occupies bits
+ * [j*bits, (j+1)*bits) of the byte stream, least significant bit first (4-bit:
+ * element 2j in the low nibble of byte j; 6-bit: four codes in three bytes).
+ * Matrix rows start on a byte boundary, so K*bits must be a multiple of 8.
+ */
+#ifndef DYBIT_H
+#define DYBIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DYBIT_OK = 0,
+    DYBIT_ERR_INVALID_ARG = 1,      /* negative or inconsistent size, bad flag value         */
+    DYBIT_ERR_UNSUPPORTED_BITS = 2, /* bits not in {2, 4, 6, 8}, or a format with m < 1       */
+    DYBIT_ERR_BAD_SCALE = 3,        /* a scale that is not a finite, normal, positive float   */
+    DYBIT_ERR_ALIGNMENT = 4,        /* a packed row that does not end on a byte boundary      */
+    DYBIT_ERR_NULL = 5,             /* a required pointer is NULL                             */
+    DYBIT_ERR_HIP = 6               /* the HIP runtime reported an error at launch            */
+} dybit_status;
+
+typedef struct {
+    int32_t bits;      /* 2, 4, 6 or 8                                                        */
+    int32_t is_signed; /* 1: sign + (bits-1) magnitude bits; 0: bits magnitude bits (Table I) */
+} dybit_fmt;
+
+typedef void *dybit_stream; /* a raw hipStream_t */
+
+/* ---- host-only helpers (no GPU needed) ---------------------------------- */
+
+/* Value of every code of a format (Eq. 1, Table I).
+ * values_out [host]: 2^bits floats, indexed by the code.  count_out [host, may be NULL]: 2^bits. */
+dybit_status dybit_codebook(dybit_fmt f, float *values_out, int32_t *count_out);
+
+/* ceil(n * bits / 8); 0 for an unsupported format. */
+size_t dybit_packed_bytes(dybit_fmt f, size_t n);
+
+const char *dybit_status_string(dybit_status s);
+
+/* ---- device entry points -------------------------------------------------- */
+
+/* Per-tensor scale ("precision adjusted at the tensor level", Sec. I):
+ * *scale_out = max|x| / 2^(m-1) as a float; NaNs are ignored; 1.0 when the maximum is 0 or n == 0.
+ * x [device]: n floats.  scale_out [device]: 1 float, written by the call. */
+dybit_status dybit_absmax_scale(const float *x, size_t n, dybit_fmt f, float *scale_out,
+                                dybit_stream stream);
+
+/* Encoder (Sec. III-B) with round-to-nearest: codes_out[j] is the code whose value times
+ * *scale is nearest to x[j] in exact arithmetic, ties to the even magnitude code.  NaN -> code 0;
+ * |x| >= scale * 2^(m-1) (and +-Inf) -> all-ones magnitude; negative x in an unsigned format -> 0;
+ * a zero magnitude never carries the sign bit.
+ * x [device]: n floats, 16-byte aligned.  scale [device]: 1 float.  codes_out [device]:
+ * dybit_packed_bytes(f, n) bytes, 16-byte aligned; unused tail bits of the last byte are zero.
+ * If *scale is not a finite normal positive float nothing is written and the asynchronous
+ * error flag is set (see dybit_get_last_async_error). */
+dybit_status dybit_quantize(const float *x, size_t n, dybit_fmt f, const float *scale,
+                            uint8_t *codes_out, dybit_stream stream);
+
+/* Decoder (Sec. III-B): y_out[j] = (*scale) * value(code j), one float multiply.
+ * codes [device]: packed, 16-byte aligned.  y_out [device]: n floats, 16-byte aligned. */
+dybit_status dybit_dequantize(const uint8_t *codes, size_t n, dybit_fmt f, const float *scale,
+                              float *y_out, dybit_stream stream);
+
+/* Matrix product with floating-point accumulation (Sec. III-B, systolic-array dataflow):
+ *   C[i][j] = (*a_scale)(*w_scale) * sum_k value(A[i][k]) * value(W[j][k])  (+ bias[j])  (ReLU)
+ * Products of decoded values are exact; the sum is accumulated in float.
+ * A_codes [device]: M rows of K packed codes (row stride K*a_fmt.bits/8 bytes).
+ * W_codes [device]: N rows of K packed codes.  Both K-contiguous.
+ * a_scale, w_scale [device]: 1 float each.  bias [device]: N floats or NULL.  relu: 0 or 1.
+ * C [device]: M rows of ldc floats (ldc >= N), only the first N of each row are written.
+ * K*bits must be a multiple of 8 for both operands (DYBIT_ERR_ALIGNMENT otherwise).
+ * M, N or K equal to 0 is valid (K == 0 writes bias / zeros). */
+dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
+                        const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                        const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                        const float *bias, int32_t relu,
+                        float *C, int64_t ldc, dybit_stream stream);
+
+/* Convolution mapped onto the same matrix product (Sec. IV, "GEMM systolic array"), without
+ * materialising the patch matrix: row = (b, ho, wo), column = cout, k = (r, s, cin).
+ * X_codes [device]: [B][H][W][Cin] packed along Cin (pixel stride Cin*x_fmt.bits/8 bytes).
+ * Wt_codes [device]: [Cout][kh][kw][Cin] packed along (kh, kw, Cin).
+ * Y [device]: [B][Ho][Wo][Cout] floats, Ho = (H + 2 pad - kh)/stride + 1 (same for Wo).
+ * Taps outside the image contribute exactly 0.  Cin*bits must be a multiple of 8 for both
+ * formats (DYBIT_ERR_ALIGNMENT otherwise). */
+dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                          int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                          const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                          const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                          const float *bias, int32_t relu,
+                          float *Y, dybit_stream stream);
+
+/* Waits for `stream`, then reports and clears the asynchronous error flag of the current
+ * device: *flag_out [host] is DYBIT_OK or DYBIT_ERR_BAD_SCALE (a quantize, dequantize, gemm or
+ * conv2d kernel since the last call found an unusable scale and wrote nothing). */
+dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYBIT_H */

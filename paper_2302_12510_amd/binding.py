@@ -1,0 +1,163 @@
+"""Thin ctypes binding of libdybit.so: argument marshalling only.
+
+PyTorch-ROCm supplies device memory and streams; every step of the path runs in the
+library's HIP kernels.  Loading fails loudly when the library has not been built: there is
+no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch  # imported first so that the library binds to the HIP runtime torch already loaded
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdybit.so")
+
+OK = 0
+ERR_INVALID_ARG, ERR_UNSUPPORTED_BITS, ERR_BAD_SCALE, ERR_ALIGNMENT, ERR_NULL, ERR_HIP = 1, 2, 3, 4, 5, 6
+
+
+class Fmt(C.Structure):
+    _fields_ = [("bits", C.c_int32), ("is_signed", C.c_int32)]
+
+
+class DybitError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -m paper_2302_12510_amd.build` (needs hipcc); there is no fallback")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, i32, i64 = C.c_void_p, C.c_size_t, C.c_int32, C.c_int64
+        L.dybit_codebook.argtypes = [Fmt, vp, C.POINTER(i32)]
+        L.dybit_packed_bytes.argtypes = [Fmt, sz]
+        L.dybit_packed_bytes.restype = sz
+        L.dybit_status_string.argtypes = [C.c_int]
+        L.dybit_status_string.restype = C.c_char_p
+        L.dybit_absmax_scale.argtypes = [vp, sz, Fmt, vp, vp]
+        L.dybit_quantize.argtypes = [vp, sz, Fmt, vp, vp, vp]
+        L.dybit_dequantize.argtypes = [vp, sz, Fmt, vp, vp, vp]
+        L.dybit_gemm.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, i64, vp]
+        L.dybit_conv2d.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp]
+        L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
+        _lib = L
+    return _lib
+
+
+def fmt(bits: int, signed: bool) -> Fmt:
+    return Fmt(int(bits), int(bool(signed)))
+
+
+def status_string(status: int) -> str:
+    return lib().dybit_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise DybitError(status, where)
+
+
+def _stream(stream=None) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _ptr(t) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("expected a device tensor")
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    return t.data_ptr()
+
+
+# ---- host-only --------------------------------------------------------------
+def dybit_codebook(bits: int, signed: bool):
+    """numpy float32 array of the 2^bits code values."""
+    import numpy as np
+    out = np.zeros(1 << max(bits, 0) if 0 <= bits <= 8 else 1, dtype=np.float32)
+    cnt = C.c_int32(0)
+    _check(lib().dybit_codebook(fmt(bits, signed), out.ctypes.data_as(C.c_void_p), C.byref(cnt)), "dybit_codebook")
+    return out[: cnt.value]
+
+
+def dybit_packed_bytes(bits: int, signed: bool, n: int) -> int:
+    return int(lib().dybit_packed_bytes(fmt(bits, signed), n))
+
+
+# ---- device -----------------------------------------------------------------
+def dybit_absmax_scale(x: torch.Tensor, bits: int, signed: bool, out: torch.Tensor | None = None, stream=None):
+    assert x.dtype == torch.float32
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(lib().dybit_absmax_scale(_ptr(x), x.numel(), fmt(bits, signed), _ptr(out), _stream(stream)),
+           "dybit_absmax_scale")
+    return out
+
+
+def dybit_quantize(x: torch.Tensor, scale: torch.Tensor, bits: int, signed: bool,
+                   out: torch.Tensor | None = None, stream=None):
+    """Packed codes (uint8 tensor of dybit_packed_bytes elements) of a flat float32 tensor."""
+    assert x.dtype == torch.float32 and scale.dtype == torch.float32
+    n = x.numel()
+    if out is None:
+        out = torch.empty(dybit_packed_bytes(bits, signed, n), dtype=torch.uint8, device=x.device)
+    _check(lib().dybit_quantize(_ptr(x), n, fmt(bits, signed), _ptr(scale), _ptr(out), _stream(stream)),
+           "dybit_quantize")
+    return out
+
+
+def dybit_dequantize(codes: torch.Tensor, n: int, scale: torch.Tensor, bits: int, signed: bool,
+                     out: torch.Tensor | None = None, stream=None):
+    assert codes.dtype == torch.uint8
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    _check(lib().dybit_dequantize(_ptr(codes), n, fmt(bits, signed), _ptr(scale), _ptr(out), _stream(stream)),
+           "dybit_dequantize")
+    return out
+
+
+def dybit_gemm(M: int, N: int, K: int, a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale,
+               bias=None, relu: bool = False, out: torch.Tensor | None = None, ldc: int | None = None, stream=None):
+    """C [M][N] float32 = sA sW A W^T (+bias)(ReLU); a_fmt / w_fmt are (bits, signed) pairs."""
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=a_scale.device)
+    if ldc is None:
+        ldc = N
+    _check(lib().dybit_gemm(M, N, K, _ptr(a_codes), fmt(*a_fmt), _ptr(a_scale),
+                            _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), int(bool(relu)),
+                            _ptr(out), ldc, _stream(stream)), "dybit_gemm")
+    return out
+
+
+def dybit_conv2d(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: int, stride: int, pad: int,
+                 x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, bias=None, relu: bool = False,
+                 out: torch.Tensor | None = None, stream=None):
+    """Y [B][Ho][Wo][Cout] float32 from NHWC codes and [Cout][kh][kw][Cin] filter codes."""
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device=x_scale.device)
+    _check(lib().dybit_conv2d(B, H, W, Cin, Cout, kh, kw, stride, pad,
+                              _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
+                              _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), int(bool(relu)),
+                              _ptr(out), _stream(stream)), "dybit_conv2d")
+    return out
+
+
+def dybit_get_last_async_error(stream=None) -> int:
+    flag = C.c_int32(0)
+    _check(lib().dybit_get_last_async_error(C.byref(flag), _stream(stream)), "dybit_get_last_async_error")
+    return int(flag.value)

@@ -1,0 +1,403 @@
+// DyBit x DyBit matrix product and implicit-GEMM convolution for gfx950 (MFMA, fp32 accumulate).
+//
+// Every DyBit value of every supported format is exactly representable in IEEE half precision
+// (at most 7 significant bits, magnitudes 2^-7 .. 2^7), so both operands are decoded to fp16 and
+// multiplied with v_mfma_f32_32x32x16_f16: the products are exact and only the fp32
+// accumulation rounds.  Packed codes are streamed from HBM, decoded through a per-operand
+// lookup table that lives in LDS, staged in LDS as fp16 tiles and consumed by the matrix cores.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dybit_device.h"
+#include "dybit_host.h"
+
+namespace dybit {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct GemmArgs {
+    int64_t M, N, K;                 // conv: M = B*Ho*Wo, N = Cout, K = kh*kw*Cin
+    const uint8_t *A, *W;
+    int a_signed, w_signed;
+    const float *a_scale, *w_scale, *bias;
+    int relu;
+    float *C;
+    int64_t ldc;
+    // convolution geometry (CONV only)
+    int H, Wd, Cin, Ho, Wo, kh, kw, stride, pad;
+};
+
+// ---------------------------------------------------------------------------
+// General kernel: any format pair, any shape.
+// ---------------------------------------------------------------------------
+constexpr int BM = 128, BN = 128, BK = 64;     // tile of C and the K step, in elements
+constexpr int LDK = BK + 8;                    // LDS row pitch in halves (144 B: conflict-free b128 reads)
+constexpr int GEMM_THREADS = 256;              // 4 waves, 2 x 2, each 64 x 64 of C
+constexpr int UNIT = 16;                       // elements decoded at a time (one run along K)
+
+// A "unit" is 16 consecutive codes of one row, held in registers exactly as they are packed in
+// memory: 16 B (8-bit), 12 B (6-bit), 8 B (4-bit) or 4 B (2-bit).
+template <int BITS> struct Unit { uint32_t w[BITS / 2]; };
+
+// Lookup tables (32-bit entries).  8- and 6-bit: indexed by the code, low half = fp16 value.
+// 4-bit: indexed by a packed byte, two fp16 values (low nibble first).  2-bit: indexed by a
+// nibble (two codes), two fp16 values.
+template <int BITS> constexpr int lut_entries() { return BITS == 8 ? 256 : BITS == 6 ? 64 : BITS == 4 ? 256 : 16; }
+
+__device__ __forceinline__ uint32_t half_bits(float v)
+{
+    const _Float16 h = (_Float16)v;            // exact for every DyBit value
+    return (uint32_t) __builtin_bit_cast(uint16_t, h);
+}
+
+template <int BITS>
+__device__ __forceinline__ void build_lut(uint32_t *lut, int is_signed, int tid)
+{
+    for (int e = tid; e < lut_entries<BITS>(); e += GEMM_THREADS) {
+        uint32_t v;
+        if (BITS == 8 || BITS == 6) {
+            v = half_bits(code_value(e, BITS, is_signed));
+        } else {
+            const uint32_t lo = e & ((1u << BITS) - 1), hi = (e >> BITS) & ((1u << BITS) - 1);
+            v = half_bits(code_value(lo, BITS, is_signed)) | (half_bits(code_value(hi, BITS, is_signed)) << 16);
+        }
+        lut[e] = v;
+    }
+}
+
+// 16 codes -> 16 halves (two 128-bit vectors), in K order.
+template <int BITS>
+__device__ __forceinline__ void decode_unit(const Unit<BITS> &u, const uint32_t *lut, u32x4 &lo, u32x4 &hi)
+{
+    uint32_t h[8];
+    if (BITS == 8) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t w = u.w[j >> 1] >> ((j & 1) * 16);
+            h[j] = (lut[w & 0xff] & 0xffffu) | (lut[(w >> 8) & 0xff] << 16);
+        }
+    } else if (BITS == 4) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = lut[(u.w[j >> 2] >> ((j & 3) * 8)) & 0xff];
+    } else if (BITS == 2) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = lut[(u.w[0] >> (j * 4)) & 0xf];
+    } else {  // 6-bit: 96-bit stream
+        const uint64_t s0 = (uint64_t)u.w[0] | ((uint64_t)u.w[1] << 32);        // bits 0..63
+        const uint64_t s1 = (uint64_t)u.w[1] | ((uint64_t)u.w[2] << 32);        // bits 32..95
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t c[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int bit = 6 * (2 * j + t);
+                c[t] = (bit + 6 <= 64) ? (uint32_t)(s0 >> bit) & 63u : (uint32_t)(s1 >> (bit - 32)) & 63u;
+            }
+            h[j] = (lut[c[0]] & 0xffffu) | (lut[c[1]] << 16);
+        }
+    }
+    lo = u32x4{h[0], h[1], h[2], h[3]};
+    hi = u32x4{h[4], h[5], h[6], h[7]};
+}
+
+// One code of a packed row (bounds are the caller's business).
+template <int BITS>
+__device__ __forceinline__ uint32_t fetch_code(const uint8_t *row, int64_t k)
+{
+    const int64_t bit = k * BITS;
+    uint32_t w = row[bit >> 3];
+    if (BITS == 6 && (bit & 7) > 2) w |= (uint32_t)row[(bit >> 3) + 1] << 8;
+    return (w >> (bit & 7)) & ((1u << BITS) - 1);
+}
+
+template <int BITS>
+__device__ __forceinline__ void unit_set_code(Unit<BITS> &u, int e, uint32_t c)
+{
+    const int bit = e * BITS;
+    u.w[bit >> 5] |= c << (bit & 31);
+    if (BITS == 6 && (bit & 31) > 26) u.w[(bit >> 5) + 1] |= c >> (32 - (bit & 31));
+}
+
+template <int BITS>
+__device__ __forceinline__ Unit<BITS> load_unit_vec(const uint8_t *p)
+{
+    Unit<BITS> u;
+    if (BITS == 8) {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(p);
+        u.w[0] = v.x; u.w[1] = v.y; u.w[2] = v.z; u.w[3] = v.w;
+    } else if (BITS == 4) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+        u.w[0] = v.x; u.w[1] = v.y;
+    } else if (BITS == 6) {
+        const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+        u.w[0] = q[0]; u.w[1] = q[1]; u.w[2] = q[2];
+    } else {
+        u.w[0] = *reinterpret_cast<const uint32_t *>(p);
+    }
+    return u;
+}
+
+// Row descriptor of the activation operand: a plain matrix row, or an output pixel of a convolution.
+struct RowA {
+    const uint8_t *base;   // GEMM: start of the row; CONV: start of image b
+    int hi0, wi0;          // CONV: top-left input coordinate of the receptive field
+    bool valid;
+};
+
+template <int BITS, bool CONV, bool VEC>
+__device__ __forceinline__ Unit<BITS> load_unit_A(const GemmArgs &g, const RowA &r, int64_t k0)
+{
+    Unit<BITS> u;
+#pragma unroll
+    for (int i = 0; i < BITS / 2; ++i) u.w[i] = 0;
+    if (!r.valid || k0 >= g.K) return u;
+    if (!CONV) {
+        if (VEC) return load_unit_vec<BITS>(r.base + k0 * BITS / 8);
+        for (int e = 0; e < UNIT && k0 + e < g.K; ++e) unit_set_code<BITS>(u, e, fetch_code<BITS>(r.base, k0 + e));
+        return u;
+    }
+    const int64_t pix_bytes = (int64_t)g.Cin * BITS / 8;
+    if (VEC) {   // the whole unit lies inside one filter tap
+        const int tap = (int)(k0 / g.Cin), c0 = (int)(k0 - (int64_t)tap * g.Cin);
+        const int fr = tap / g.kw, fs = tap - fr * g.kw;
+        const int hi = r.hi0 + fr, wi = r.wi0 + fs;
+        if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.Wd) return u;       // padding: code 0 = 0.0
+        return load_unit_vec<BITS>(r.base + ((int64_t)hi * g.Wd + wi) * pix_bytes + (int64_t)c0 * BITS / 8);
+    }
+    for (int e = 0; e < UNIT && k0 + e < g.K; ++e) {
+        const int64_t k = k0 + e;
+        const int tap = (int)(k / g.Cin), c = (int)(k - (int64_t)tap * g.Cin);
+        const int fr = tap / g.kw, fs = tap - fr * g.kw;
+        const int hi = r.hi0 + fr, wi = r.wi0 + fs;
+        if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.Wd) continue;
+        unit_set_code<BITS>(u, e, fetch_code<BITS>(r.base + ((int64_t)hi * g.Wd + wi) * pix_bytes, c));
+    }
+    return u;
+}
+
+template <int BITS, bool VEC>
+__device__ __forceinline__ Unit<BITS> load_unit_W(const GemmArgs &g, const uint8_t *row, bool valid, int64_t k0)
+{
+    Unit<BITS> u;
+#pragma unroll
+    for (int i = 0; i < BITS / 2; ++i) u.w[i] = 0;
+    if (!valid || k0 >= g.K) return u;
+    if (VEC) return load_unit_vec<BITS>(row + k0 * BITS / 8);
+    for (int e = 0; e < UNIT && k0 + e < g.K; ++e) unit_set_code<BITS>(u, e, fetch_code<BITS>(row, k0 + e));
+    return u;
+}
+
+template <int BA, int BW, bool CONV, bool VEC>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) _Float16 As[BM * LDK];
+    __shared__ __attribute__((aligned(16))) _Float16 Ws[BN * LDK];
+    __shared__ uint32_t lutA[lut_entries<BA>()];
+    __shared__ uint32_t lutW[lut_entries<BW>()];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t tiles_n = (g.N + BN - 1) / BN;
+    const int64_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
+    const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
+
+    build_lut<BA>(lutA, g.a_signed, tid);
+    build_lut<BW>(lutW, g.w_signed, tid);
+
+    // Each thread stages two units of A and two of W per K step: unit id -> (row, quarter of BK).
+    constexpr int UPT = BM * (BK / UNIT) / GEMM_THREADS;   // = 2
+    RowA ra[UPT];
+    const uint8_t *rw[UPT];
+    bool vw[UPT];
+    int urow[UPT], ukq[UPT];
+    const int64_t a_row_bytes = g.K * BA / 8, w_row_bytes = g.K * BW / 8;
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+        const int u = tid + i * GEMM_THREADS;
+        urow[i] = u >> 2;
+        ukq[i] = u & 3;
+        const int64_t m = m0 + urow[i], n = n0 + urow[i];
+        ra[i].valid = m < g.M;
+        if (CONV) {
+            const int64_t mm = ra[i].valid ? m : 0;
+            const int64_t b = mm / ((int64_t)g.Ho * g.Wo);
+            const int rem = (int)(mm - b * g.Ho * g.Wo);
+            const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+            ra[i].base = g.A + b * g.H * g.Wd * ((int64_t)g.Cin * BA / 8);
+            ra[i].hi0 = ho * g.stride - g.pad;
+            ra[i].wi0 = wo * g.stride - g.pad;
+        } else {
+            ra[i].base = g.A + (ra[i].valid ? m : 0) * a_row_bytes;
+            ra[i].hi0 = ra[i].wi0 = 0;
+        }
+        vw[i] = n < g.N;
+        rw[i] = g.W + (vw[i] ? n : 0) * w_row_bytes;
+    }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    Unit<BA> ua[UPT];
+    Unit<BW> uw[UPT];
+    const int64_t ktiles = (g.K + BK - 1) / BK;
+    if (ktiles > 0) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) {
+            ua[i] = load_unit_A<BA, CONV, VEC>(g, ra[i], (int64_t)ukq[i] * UNIT);
+            uw[i] = load_unit_W<BW, VEC>(g, rw[i], vw[i], (int64_t)ukq[i] * UNIT);
+        }
+    }
+    __syncthreads();   // tables ready
+
+    for (int64_t kt = 0; kt < ktiles; ++kt) {
+        // decode the staged units into the LDS tiles
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) {
+            u32x4 lo, hi;
+            decode_unit<BA>(ua[i], lutA, lo, hi);
+            u32x4 *dst = reinterpret_cast<u32x4 *>(&As[urow[i] * LDK + ukq[i] * UNIT]);
+            dst[0] = lo; dst[1] = hi;
+            decode_unit<BW>(uw[i], lutW, lo, hi);
+            dst = reinterpret_cast<u32x4 *>(&Ws[urow[i] * LDK + ukq[i] * UNIT]);
+            dst[0] = lo; dst[1] = hi;
+        }
+        __syncthreads();
+        // fetch the next K step while the matrix cores work on this one
+        if (kt + 1 < ktiles) {
+            const int64_t kb = (kt + 1) * BK;
+#pragma unroll
+            for (int i = 0; i < UPT; ++i) {
+                ua[i] = load_unit_A<BA, CONV, VEC>(g, ra[i], kb + ukq[i] * UNIT);
+                uw[i] = load_unit_W<BW, VEC>(g, rw[i], vw[i], kb + ukq[i] * UNIT);
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            f16x8 fa[2], fw[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                fa[i] = *reinterpret_cast<const f16x8 *>(&As[(wm * 64 + i * 32 + (lane & 31)) * LDK + kk * 16 + (lane >> 5) * 8]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                fw[j] = *reinterpret_cast<const f16x8 *>(&Ws[(wn * 64 + j * 32 + (lane & 31)) * LDK + kk * 16 + (lane >> 5) * 8]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fw[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: scale, bias, ReLU.  Accumulator v of a lane is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
+    const float alpha = (*g.a_scale) * (*g.w_scale);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
+        if (n >= g.N) continue;
+        const float b = g.bias ? g.bias[n] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (m >= g.M) continue;
+                float c = acc[i][j][v] * alpha + b;
+                if (g.relu) c = fmaxf(c, 0.0f);
+                g.C[m * g.ldc + n] = c;
+            }
+        }
+    }
+}
+
+template <int BA, int BW>
+static void launch_gemm(const GemmArgs &g, bool conv, bool vec, hipStream_t st)
+{
+    const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+    const dim3 grid((unsigned)tiles), block(GEMM_THREADS);
+    if (conv) {
+        if (vec) hipLaunchKernelGGL((gemm_kernel<BA, BW, true, true>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((gemm_kernel<BA, BW, true, false>), grid, block, 0, st, g);
+    } else {
+        if (vec) hipLaunchKernelGGL((gemm_kernel<BA, BW, false, true>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((gemm_kernel<BA, BW, false, false>), grid, block, 0, st, g);
+    }
+}
+
+static void dispatch_gemm(const GemmArgs &g, int ba, int bw, bool conv, bool vec, hipStream_t st)
+{
+#define DYBIT_G(A_, W_) case (A_) * 16 + (W_): launch_gemm<A_, W_>(g, conv, vec, st); break
+    switch (ba * 16 + bw) {
+        DYBIT_G(2, 2); DYBIT_G(2, 4); DYBIT_G(2, 6); DYBIT_G(2, 8);
+        DYBIT_G(4, 2); DYBIT_G(4, 4); DYBIT_G(4, 6); DYBIT_G(4, 8);
+        DYBIT_G(6, 2); DYBIT_G(6, 4); DYBIT_G(6, 6); DYBIT_G(6, 8);
+        DYBIT_G(8, 2); DYBIT_G(8, 4); DYBIT_G(8, 6); DYBIT_G(8, 8);
+    }
+#undef DYBIT_G
+}
+
+}  // namespace dybit
+
+using namespace dybit;
+
+extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
+                                   const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                                   const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                                   const float *bias, int32_t relu,
+                                   float *C, int64_t ldc, dybit_stream stream)
+{
+    dybit_status st = check_fmt(a_fmt);
+    if (st == DYBIT_OK) st = check_fmt(w_fmt);
+    if (st != DYBIT_OK) return st;
+    if (M < 0 || N < 0 || K < 0 || ldc < N || (relu != 0 && relu != 1)) return DYBIT_ERR_INVALID_ARG;
+    if ((K * a_fmt.bits) % 8 || (K * w_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
+    if (M == 0 || N == 0) return DYBIT_OK;
+    if (!a_scale || !w_scale || !C || (K && (!A_codes || !W_codes))) return DYBIT_ERR_NULL;
+    GemmArgs g{};
+    g.M = M; g.N = N; g.K = K;
+    g.A = A_codes; g.W = W_codes;
+    g.a_signed = a_fmt.is_signed; g.w_signed = w_fmt.is_signed;
+    g.a_scale = a_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
+    g.C = C; g.ldc = ldc;
+    const bool vec = (K % UNIT == 0) && aligned16(A_codes) && aligned16(W_codes);
+    dispatch_gemm(g, a_fmt.bits, w_fmt.bits, false, vec, (hipStream_t)stream);
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                     int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                     const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                     const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                     const float *bias, int32_t relu,
+                                     float *Y, dybit_stream stream)
+{
+    dybit_status st = check_fmt(x_fmt);
+    if (st == DYBIT_OK) st = check_fmt(w_fmt);
+    if (st != DYBIT_OK) return st;
+    if (B < 0 || H < 1 || W < 1 || Cin < 1 || Cout < 0 || kh < 1 || kw < 1 || stride < 1 || pad < 0 ||
+        (relu != 0 && relu != 1) || H > (1 << 24) || W > (1 << 24) || Cin > (1 << 24))
+        return DYBIT_ERR_INVALID_ARG;
+    if (H + 2 * (int64_t)pad < kh || W + 2 * (int64_t)pad < kw) return DYBIT_ERR_INVALID_ARG;
+    if ((Cin * x_fmt.bits) % 8 || (Cin * w_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    if (B == 0 || Cout == 0) return DYBIT_OK;
+    if (!x_scale || !w_scale || !Y || !X_codes || !Wt_codes) return DYBIT_ERR_NULL;
+    GemmArgs g{};
+    g.M = B * Ho * Wo; g.N = Cout; g.K = (int64_t)kh * kw * Cin;
+    g.A = X_codes; g.W = Wt_codes;
+    g.a_signed = x_fmt.is_signed; g.w_signed = w_fmt.is_signed;
+    g.a_scale = x_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
+    g.C = Y; g.ldc = Cout;
+    g.H = (int)H; g.Wd = (int)W; g.Cin = (int)Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
+    g.kh = kh; g.kw = kw; g.stride = stride; g.pad = pad;
+    const bool vec = (Cin % UNIT == 0) && aligned16(X_codes) && aligned16(Wt_codes);
+    dispatch_gemm(g, x_fmt.bits, w_fmt.bits, true, vec, (hipStream_t)stream);
+    return launch_status();
+}

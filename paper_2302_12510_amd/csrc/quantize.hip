@@ -1,0 +1,432 @@
+// DyBit per-tensor scale, quantize (encoder) and dequantize (decoder) kernels for gfx950,
+// with their C-ABI entry points.  These passes are bound by HBM bandwidth: every load and
+// store is a full-width coalesced vector access and each element is touched once.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "dybit_device.h"
+#include "dybit_host.h"
+
+namespace dybit {
+
+__device__ int g_async_error = 0;
+
+constexpr int kThreads = 256;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// absmax -> scale
+// ---------------------------------------------------------------------------
+// Non-negative floats order like their bit patterns, so the running maximum is kept with an
+// integer atomicMax directly in the output word; NaNs are dropped by fmaxf before that.
+__global__ void absmax_init_kernel(float *scale_out) { *scale_out = 0.0f; }
+
+__global__ __launch_bounds__(kThreads) void absmax_kernel(const float *__restrict__ x, size_t n,
+                                                          float *scale_out)
+{
+    const size_t n4 = n >> 2;
+    const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
+    float mx = 0.0f;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        const f32x4 a = __builtin_nontemporal_load(x4 + i);
+        const f32x4 b = __builtin_nontemporal_load(x4 + i + stride);
+        const f32x4 c = __builtin_nontemporal_load(x4 + i + 2 * stride);
+        const f32x4 d = __builtin_nontemporal_load(x4 + i + 3 * stride);
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+    }
+    for (; i < n4; i += stride) {
+        const f32x4 a = x4[i];
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) mx = fmaxf(mx, fabsf(x[(n4 << 2) + threadIdx.x]));
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if ((threadIdx.x & 63) == 0 && mx > 0.0f)
+        atomicMax(reinterpret_cast<unsigned int *>(scale_out), __float_as_uint(mx));
+}
+
+__global__ void absmax_finish_kernel(float *scale_out, float inv_vmax)
+{
+    const float mx = *scale_out;
+    *scale_out = (mx == 0.0f) ? 1.0f : mx * inv_vmax;   // division by 2^(m-1): exact
+}
+
+// ---------------------------------------------------------------------------
+// quantize
+// ---------------------------------------------------------------------------
+// The result must be the code nearest to x in exact arithmetic, but x / s cannot be formed
+// exactly in float.  Two paths:
+//
+//  fast  q = |x| * fl(1/s) is within 2^-23 (relative) of the true quotient t.  The "real-valued
+//        code" c(t) -- t * 2^(m-1) below 1, 2^m - n(t) above, where n(t) is t's bit pattern
+//        subtracted from a constant (the inverse of magnitude_value) -- is piecewise linear,
+//        continuous, and the decision points are exactly its half-integers.  It is rounded to
+//        G fractional bits with one magic-number addition; unless those bits read exactly
+//        one half, q and t are on the same side of every decision point and the code is the
+//        integer part rounded half up.
+//  exact when the G bits read one half (probability 2^-G), for NaN, and for scales so
+//        extreme that 1/s or the product could leave the normal range: the side of the
+//        decision point is the sign of fma(-s, mid, |x|), which is exact; zero is a tie and
+//        goes to the even code.
+template <int M>
+struct QConst {
+    static constexpr int G = 12;                                       // 2^(M-23) error << 2^-(G+1)
+    static constexpr uint32_t kRecip = (uint32_t)(254 + M - 1) << 23;  // see magnitude_value
+    static constexpr uint32_t kMagic = ((uint32_t)(127 + 23 - G) << 23) | 0x400000u;  // 1.5 * 2^(23-G)
+    static constexpr uint32_t kRound = kMagic + (1u << (G - 1));
+    static constexpr uint32_t kTop = (1u << M) - 1;
+};
+
+// Decision point between magnitude codes j and j+1, as a float (exact: <= 9 significant bits).
+template <int M>
+__device__ __forceinline__ float midpoint_value(uint32_t j)
+{
+    const float h = (float)j + 0.5f;
+    if (j < (1u << (M - 1)))                       // lower neighbour is a pure fraction; so is the
+        return h * __uint_as_float((uint32_t)(127 - (M - 1)) << 23);   // grid up to and including 1.0
+    return __uint_as_float(QConst<M>::kRecip - __float_as_uint((float)(1u << M) - h));
+}
+
+// Exact magnitude code of |x| / s.  ax = |x| (not NaN), s a finite normal positive float.
+template <int M>
+__device__ __noinline__ uint32_t magnitude_exact(float ax, float s)
+{
+    // Scale both by the same power of two so that s2 is in [1, 2): the fma below then cannot
+    // lose its sign to underflow for any |x| near a decision point, and multiplying by a power
+    // of two is exact (an overflow to Inf or an underflow of a negligible |x| keeps the order).
+    const uint32_t sb = __float_as_uint(s);
+    const float p = __uint_as_float((254u - (sb >> 23)) << 23);
+    const float s2 = s * p, ax2 = ax * p;
+    float t = fminf(ax2 / s2, (float)(1u << (M - 1)));
+    float c = (t < 1.0f) ? t * (float)(1u << (M - 1))
+                         : (float)(1u << M) - __uint_as_float(QConst<M>::kRecip - __float_as_uint(t));
+    uint32_t j = min((uint32_t)c, QConst<M>::kTop);
+    // j is within one of the answer; settle it with exact comparisons.
+    while (j < QConst<M>::kTop) {
+        const float r = fmaf(-s2, midpoint_value<M>(j), ax2);            // sign(|x| - s * mid_j), exact
+        if (r > 0.0f || (r == 0.0f && (j & 1u))) ++j; else break;
+    }
+    while (j > 0) {
+        const float r = fmaf(-s2, midpoint_value<M>(j - 1), ax2);
+        if (r < 0.0f || (r == 0.0f && (j & 1u))) --j; else break;
+    }
+    return j;
+}
+
+template <int BITS, bool SIGNED>
+__device__ __forceinline__ uint32_t quantize_exact(float x, float s)
+{
+    constexpr int M = SIGNED ? BITS - 1 : BITS;
+    if (x != x) return 0u;
+    const bool neg = __float_as_uint(x) >> 31;
+    if (!SIGNED && neg) return 0u;
+    const uint32_t j = magnitude_exact<M>(fabsf(x), s);
+    return (SIGNED && neg && j) ? (j | (1u << M)) : j;
+}
+
+// Fast path for one element; sets `redo` when the exact path must decide.
+template <int BITS, bool SIGNED>
+__device__ __forceinline__ uint32_t quantize_fast(float x, float rinv, bool &redo)
+{
+    constexpr int M = SIGNED ? BITS - 1 : BITS;
+    using K = QConst<M>;
+    const float vmax = (float)(1u << (M - 1));
+    const float q = SIGNED ? fminf(fabsf(x) * rinv, vmax) : fminf(fmaxf(x * rinv, 0.0f), vmax);
+    const float lin = q * -(float)(1u << (M - 1));                       // -c
+    const float rec = __uint_as_float(K::kRecip - __float_as_uint(q));   // 2^m - c
+    const float y = (q < 1.0f) ? lin : rec;
+    const uint32_t zb = __float_as_uint(y + __uint_as_float(K::kMagic));
+    redo = ((zb & ((1u << K::G) - 1)) == (1u << (K::G - 1))) | (x != x);
+    uint32_t code = ((K::kRound - zb) >> K::G) & K::kTop;
+    if (SIGNED) code |= (__float_as_uint(x) >> (31 - M)) & (1u << M);
+    return code;
+}
+
+// Clears the sign bit of every field whose magnitude is zero (fields of BITS bits in a word).
+template <int BITS>
+__device__ __forceinline__ uint32_t clear_negative_zero(uint32_t w)
+{
+    constexpr uint32_t ones = BITS == 8 ? 0x01010101u : BITS == 4 ? 0x11111111u : BITS == 2 ? 0x55555555u : 0u;
+    constexpr uint32_t sign = ones << (BITS - 1);
+    constexpr uint32_t magm = sign - ones;
+    const uint32_t t = w & magm;
+    return t | (w & (t + magm) & sign);
+}
+
+struct ScaleInfo {
+    float s, rinv;
+    bool ok, all_exact;
+};
+
+__device__ __forceinline__ ScaleInfo load_scale(const float *scale)
+{
+    ScaleInfo si;
+    si.s = *scale;
+    const uint32_t e = (__float_as_uint(si.s) >> 23) & 0xffu;
+    si.ok = (si.s > 0.0f) && e != 0u && e != 255u;                      // finite, normal, positive
+    si.all_exact = e < 27u || e > 227u;                                 // outside [2^-100, 2^100]
+    si.rinv = 1.0f / si.s;
+    return si;
+}
+
+// 4 consecutive elements per lane per load (coalesced float4), UNROLL loads in flight.
+// Output per load: 4*BITS bits, stored as one 8/16/32-bit word.  BITS in {2, 4, 8}.
+template <int BITS, bool SIGNED, int UNROLL>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restrict__ x, size_t n4,
+                                                            const float *__restrict__ scale,
+                                                            uint8_t *__restrict__ out)
+{
+    using word_t = typename std::conditional<BITS == 8, uint32_t,
+                   typename std::conditional<BITS == 4, uint16_t, uint8_t>::type>::type;
+    const ScaleInfo si = load_scale(scale);
+    if (!si.ok) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        return;
+    }
+    const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
+    word_t *o = reinterpret_cast<word_t *>(out);
+    const size_t per_block = (size_t)kThreads * UNROLL;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
+        f32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t i = base + (size_t)u * kThreads + threadIdx.x;
+            v[u] = (i < n4) ? __builtin_nontemporal_load(x4 + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t i = base + (size_t)u * kThreads + threadIdx.x;
+            const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            uint32_t w = 0;
+            bool any_redo = si.all_exact;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                bool redo;
+                w |= quantize_fast<BITS, SIGNED>(e[k], si.rinv, redo) << (k * BITS);
+                any_redo |= redo;
+            }
+            if (SIGNED) w = clear_negative_zero<BITS>(w);
+            if (any_redo) {
+                w = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) w |= quantize_exact<BITS, SIGNED>(e[k], si.s) << (k * BITS);
+            }
+            if (i < n4) __builtin_nontemporal_store((word_t)w, o + i);
+        }
+    }
+}
+
+// 6-bit: 16 consecutive elements per lane -> 96 bits = three words.
+template <bool SIGNED>
+__global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__restrict__ x, size_t n16,
+                                                             const float *__restrict__ scale,
+                                                             uint8_t *__restrict__ out)
+{
+    const ScaleInfo si = load_scale(scale);
+    if (!si.ok) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        return;
+    }
+    const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
+    uint32_t *o = reinterpret_cast<uint32_t *>(out);
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (size_t)gridDim.x * kThreads) {
+        float e[16];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const f32x4 v = __builtin_nontemporal_load(x4 + 4 * i + u);
+            e[4 * u] = v.x; e[4 * u + 1] = v.y; e[4 * u + 2] = v.z; e[4 * u + 3] = v.w;
+        }
+        uint32_t c[16];
+        bool any_redo = si.all_exact;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            bool redo;
+            c[k] = quantize_fast<6, SIGNED>(e[k], si.rinv, redo);
+            if (SIGNED && (c[k] & 31u) == 0u) c[k] = 0u;
+            any_redo |= redo;
+        }
+        if (any_redo) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) c[k] = quantize_exact<6, SIGNED>(e[k], si.s);
+        }
+        uint64_t lo = 0, hi = 0;   // lo: codes 0..9 (60 bits) + low 4 bits of code 10; hi: rest
+#pragma unroll
+        for (int k = 0; k < 10; ++k) lo |= (uint64_t)c[k] << (6 * k);
+        lo |= (uint64_t)(c[10] & 15u) << 60;
+        hi = c[10] >> 4;
+#pragma unroll
+        for (int k = 11; k < 16; ++k) hi |= (uint64_t)c[k] << (6 * (k - 11) + 2);
+        o[3 * i] = (uint32_t)lo;
+        o[3 * i + 1] = (uint32_t)(lo >> 32);
+        o[3 * i + 2] = (uint32_t)hi;
+    }
+}
+
+// Remainder: one thread per group of 4 elements starting at element `first`; exact path, byte stores.
+template <int BITS, bool SIGNED>
+__global__ void quantize_tail_kernel(const float *__restrict__ x, size_t first, size_t n,
+                                     const float *__restrict__ scale, uint8_t *__restrict__ out)
+{
+    const ScaleInfo si = load_scale(scale);
+    if (!si.ok) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        return;
+    }
+    const size_t e0 = first + 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);
+    if (e0 >= n) return;
+    uint32_t w = 0;
+    int cnt = 0;
+    for (int k = 0; k < 4 && e0 + k < n; ++k, ++cnt) w |= quantize_exact<BITS, SIGNED>(x[e0 + k], si.s) << (k * BITS);
+    const size_t byte0 = e0 * BITS / 8;                                  // e0 is a multiple of 4
+    const int nbytes = (cnt * BITS + 7) / 8;
+    for (int b = 0; b < nbytes; ++b) out[byte0 + b] = (uint8_t)(w >> (8 * b));
+}
+
+// ---------------------------------------------------------------------------
+// dequantize
+// ---------------------------------------------------------------------------
+// Table of s * value(code) in LDS (one multiply per entry, as the definition says); each
+// lane expands 16 packed bytes per iteration.
+template <int BITS>
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t *__restrict__ codes, size_t n,
+                                                              int is_signed, const float *__restrict__ scale,
+                                                              float *__restrict__ y)
+{
+    __shared__ float lut[1 << BITS];
+    const float s = *scale;
+    for (int c = threadIdx.x; c < (1 << BITS); c += kThreads) lut[c] = s * code_value(c, BITS, is_signed);
+    __syncthreads();
+    constexpr int EPG = BITS == 6 ? 4 : 8 / BITS * 4;      // elements per group
+    constexpr int BPG = EPG * BITS / 8;                     // bytes per group: 6-bit 3, others 4
+    const size_t groups = n / EPG;
+    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups; g += (size_t)gridDim.x * kThreads) {
+        uint32_t w;
+        if (BITS == 6) {
+            const uint8_t *p = codes + g * 3;
+            w = p[0] | (p[1] << 8) | (p[2] << 16);
+        } else {
+            w = reinterpret_cast<const uint32_t *>(codes)[g];
+        }
+        float v[EPG];
+#pragma unroll
+        for (int k = 0; k < EPG; ++k) v[k] = lut[(w >> (k * BITS)) & ((1u << BITS) - 1)];
+#pragma unroll
+        for (int k = 0; k < EPG; k += 4)
+            reinterpret_cast<float4 *>(y)[(g * EPG + k) >> 2] = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+    }
+    // remainder (< EPG elements), one thread
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        for (size_t j = groups * EPG; j < n; ++j) {
+            const size_t bit = j * BITS;
+            uint32_t w = codes[bit >> 3];
+            if ((bit & 7) + BITS > 8) w |= (uint32_t)codes[(bit >> 3) + 1] << 8;
+            y[j] = lut[(w >> (bit & 7)) & ((1u << BITS) - 1)];
+        }
+    }
+    (void)BPG;
+}
+
+static int grid_for(size_t work_items, int per_block, int max_blocks)
+{
+    size_t b = (work_items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > (size_t)max_blocks) b = max_blocks;
+    return (int)b;
+}
+
+template <int BITS, bool SIGNED>
+static void launch_quantize(const float *x, size_t n, const float *scale, uint8_t *out, hipStream_t st)
+{
+    constexpr int UNROLL = 4;
+    if (BITS == 6) {
+        const size_t n16 = n / 16;
+        if (n16) hipLaunchKernelGGL((quantize6_kernel<SIGNED>), dim3(grid_for(n16, kThreads, 256 * 16)), dim3(kThreads), 0, st,
+                                    x, n16, scale, out);
+        const size_t first = n16 * 16;
+        if (first < n) {
+            const size_t groups = (n - first + 3) / 4;
+            hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3((unsigned)groups), dim3(1), 0, st, x, first, n, scale, out);
+        }
+    } else {
+        const size_t n4 = n / 4;
+        if (n4) hipLaunchKernelGGL((quantize_kernel<BITS == 6 ? 8 : BITS, SIGNED, UNROLL>),
+                                   dim3(grid_for(n4, kThreads * UNROLL, 256 * 16)), dim3(kThreads), 0, st, x, n4, scale, out);
+        if (n4 * 4 < n)
+            hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3(1), dim3(1), 0, st, x, n4 * 4, n, scale, out);
+    }
+}
+
+}  // namespace dybit
+
+using namespace dybit;
+
+extern "C" dybit_status dybit_absmax_scale(const float *x, size_t n, dybit_fmt f, float *scale_out,
+                                           dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (!scale_out || (!x && n)) return DYBIT_ERR_NULL;
+    if (!aligned16(x)) return DYBIT_ERR_ALIGNMENT;
+    hipStream_t hs = (hipStream_t)stream;
+    hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(1), 0, hs, scale_out);
+    if (n) hipLaunchKernelGGL(absmax_kernel, dim3(grid_for(n / 4 + 1, kThreads * 4, 256 * 8)), dim3(kThreads), 0, hs, x, n, scale_out);
+    const int m = mag_bits(f.bits, f.is_signed);
+    hipLaunchKernelGGL(absmax_finish_kernel, dim3(1), dim3(1), 0, hs, scale_out, 1.0f / (float)(1u << (m - 1)));
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_quantize(const float *x, size_t n, dybit_fmt f, const float *scale,
+                                       uint8_t *codes_out, dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (!scale || ((!x || !codes_out) && n)) return DYBIT_ERR_NULL;
+    if (!aligned16(x) || !aligned16(codes_out)) return DYBIT_ERR_ALIGNMENT;
+    if (n == 0) return DYBIT_OK;
+    hipStream_t hs = (hipStream_t)stream;
+#define DYBIT_Q(B, S) launch_quantize<B, S>(x, n, scale, codes_out, hs)
+    switch (f.bits * 2 + f.is_signed) {
+        case 4: DYBIT_Q(2, false); break;   case 5: DYBIT_Q(2, true); break;
+        case 8: DYBIT_Q(4, false); break;   case 9: DYBIT_Q(4, true); break;
+        case 12: DYBIT_Q(6, false); break;  case 13: DYBIT_Q(6, true); break;
+        case 16: DYBIT_Q(8, false); break;  case 17: DYBIT_Q(8, true); break;
+    }
+#undef DYBIT_Q
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_dequantize(const uint8_t *codes, size_t n, dybit_fmt f, const float *scale,
+                                         float *y_out, dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (!scale || ((!codes || !y_out) && n)) return DYBIT_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(y_out)) return DYBIT_ERR_ALIGNMENT;
+    if (n == 0) return DYBIT_OK;
+    hipStream_t hs = (hipStream_t)stream;
+    const int grid = grid_for(n / 8 + 1, kThreads, 256 * 16);
+    switch (f.bits) {
+        case 2: hipLaunchKernelGGL((dequantize_kernel<2>), dim3(grid), dim3(kThreads), 0, hs, codes, n, f.is_signed, scale, y_out); break;
+        case 4: hipLaunchKernelGGL((dequantize_kernel<4>), dim3(grid), dim3(kThreads), 0, hs, codes, n, f.is_signed, scale, y_out); break;
+        case 6: hipLaunchKernelGGL((dequantize_kernel<6>), dim3(grid), dim3(kThreads), 0, hs, codes, n, f.is_signed, scale, y_out); break;
+        case 8: hipLaunchKernelGGL((dequantize_kernel<8>), dim3(grid), dim3(kThreads), 0, hs, codes, n, f.is_signed, scale, y_out); break;
+    }
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream)
+{
+    if (!flag_out) return DYBIT_ERR_NULL;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DYBIT_ERR_HIP;
+    int v = 0, zero = 0;
+    if (hipMemcpyFromSymbol(&v, HIP_SYMBOL(g_async_error), sizeof(int)) != hipSuccess) return DYBIT_ERR_HIP;
+    if (v && hipMemcpyToSymbol(HIP_SYMBOL(g_async_error), &zero, sizeof(int)) != hipSuccess) return DYBIT_ERR_HIP;
+    *flag_out = v;
+    return DYBIT_OK;
+}

@@ -1,0 +1,102 @@
+"""The C-ABI library loads, exports what include/dybit.h declares, and rejects bad
+arguments on the host before touching a GPU.  CPU only: no compute entry point is
+called with valid arguments here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import dybit_ref as R
+from paper_2302_12510_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dybit.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dybit_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"dybit_codebook", "dybit_quantize", "dybit_dequantize", "dybit_gemm", "dybit_conv2d"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+@pytest.mark.parametrize("bits", [2, 4, 6, 8])
+@pytest.mark.parametrize("signed", [True, False])
+def test_codebook_matches_oracle(bits, signed):
+    got = B.dybit_codebook(bits, signed)
+    want = R.codebook(bits, signed)
+    assert got.dtype == np.float32 and got.size == 1 << bits
+    assert np.array_equal(got.astype(np.float64), want)
+    assert not np.signbit(got[1 << (bits - 1)]) or not signed
+
+
+def test_packed_bytes():
+    for bits in (2, 4, 6, 8):
+        for n in (0, 1, 3, 4, 5, 1000, 2 ** 28):
+            assert B.dybit_packed_bytes(bits, True, n) == R.packed_bytes(n, bits)
+    assert B.dybit_packed_bytes(5, True, 10) == 0
+
+
+def test_status_strings():
+    seen = {B.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def _st(fn, *args):
+    return fn(*args)
+
+
+def test_argument_errors_without_gpu():
+    L = B.lib()
+    f4, f8, bad = B.fmt(4, True), B.fmt(8, False), B.fmt(5, True)
+    p = C.c_void_p(0x1000)          # never dereferenced: all calls below fail validation first
+    odd = C.c_void_p(0x1004)
+    null = C.c_void_p(0)
+    # codebook
+    buf = (C.c_float * 256)()
+    assert L.dybit_codebook(bad, buf, None) == B.ERR_UNSUPPORTED_BITS
+    assert L.dybit_codebook(B.Fmt(4, 2), buf, None) == B.ERR_INVALID_ARG
+    assert L.dybit_codebook(f4, None, None) == B.ERR_NULL
+    # quantize / dequantize / absmax
+    assert L.dybit_quantize(p, 16, bad, p, p, None) == B.ERR_UNSUPPORTED_BITS
+    assert L.dybit_quantize(null, 16, f4, p, p, None) == B.ERR_NULL
+    assert L.dybit_quantize(p, 16, f4, null, p, None) == B.ERR_NULL
+    assert L.dybit_quantize(odd, 16, f4, p, p, None) == B.ERR_ALIGNMENT
+    assert L.dybit_quantize(p, 16, f4, p, odd, None) == B.ERR_ALIGNMENT
+    assert L.dybit_dequantize(p, 16, bad, p, p, None) == B.ERR_UNSUPPORTED_BITS
+    assert L.dybit_dequantize(null, 16, f8, p, p, None) == B.ERR_NULL
+    assert L.dybit_dequantize(p, 16, f8, p, odd, None) == B.ERR_ALIGNMENT
+    assert L.dybit_absmax_scale(p, 16, bad, p, None) == B.ERR_UNSUPPORTED_BITS
+    assert L.dybit_absmax_scale(p, 16, f4, null, None) == B.ERR_NULL
+    assert L.dybit_absmax_scale(odd, 16, f4, p, None) == B.ERR_ALIGNMENT
+    # gemm
+    g = lambda M, N, K, fa=f4, fw=f4, a=p, w=p, sa=p, sw=p, relu=0, c=p, ldc=None: \
+        L.dybit_gemm(M, N, K, a, fa, sa, w, fw, sw, null, relu, c, N if ldc is None else ldc, None)
+    assert g(8, 8, 16, fa=bad) == B.ERR_UNSUPPORTED_BITS
+    assert g(-1, 8, 16) == B.ERR_INVALID_ARG
+    assert g(8, 8, 16, ldc=4) == B.ERR_INVALID_ARG
+    assert g(8, 8, 16, relu=3) == B.ERR_INVALID_ARG
+    assert g(8, 8, 15) == B.ERR_ALIGNMENT                        # 15 nibbles: row not byte-aligned
+    assert g(8, 8, 6, fa=B.fmt(6, True)) == B.ERR_ALIGNMENT      # 36 bits
+    assert g(8, 8, 16, a=null) == B.ERR_NULL
+    assert g(8, 8, 16, sa=null) == B.ERR_NULL
+    assert g(8, 8, 16, c=null) == B.ERR_NULL
+    assert g(0, 8, 16, a=null, w=null, c=null) == B.OK           # empty problem: nothing to do
+    # conv2d
+    cv = lambda Bn=1, H=8, W=8, Cin=16, Cout=8, kh=3, kw=3, s=1, pd=1, fx=f4, fw=f4, x=p, y=p: \
+        L.dybit_conv2d(Bn, H, W, Cin, Cout, kh, kw, s, pd, x, fx, p, p, fw, p, null, 0, y, None)
+    assert cv(fx=bad) == B.ERR_UNSUPPORTED_BITS
+    assert cv(s=0) == B.ERR_INVALID_ARG
+    assert cv(H=2, kh=7, pd=0) == B.ERR_INVALID_ARG
+    assert cv(Cin=3) == B.ERR_ALIGNMENT                          # 12 bits per pixel
+    assert cv(x=null) == B.ERR_NULL
+    assert cv(Bn=0, x=null, y=null) == B.OK
+    assert L.dybit_get_last_async_error(None, None) == B.ERR_NULL
