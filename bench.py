@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the DyBit hot path on one MI355X.
+
+A step is one pass of the path over one batch of seeded synthetic input that is already
+resident in HBM: per-tensor absmax scale of the fp32 activations -> quantize them to DyBit
+codes -> DyBit x DyBit GEMM (decode, MFMA contraction, scale/bias epilogue) against weights
+that were quantized once at set-up.  The default workload is the large configuration the
+targets are quoted on: M = N = K = 8192, 4-bit signed weights (Laplace), 8-bit signed
+activations (Gaussian with 1 % outliers at 10 sigma), followed by the standalone quantize
+of a 2^28-element Laplace tensor at 4 and 8 bits, which is reported separately.
+
+Prints ONE JSON line.  `value` is the effective throughput of the whole step,
+2*M*N*K / step time, in TOPS.  `roofline` describes the GEMM kernel alone (HIP events
+around its launches inside the timed region), `quantize` the HBM-bound quantize pass,
+`cpu_baseline` the plain C oracle timed on the host cores over a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP16_MFMA_TFLOPS = 2500.0   # MI355X dense fp16/bf16 matrix peak
+PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E peak
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
+# scaled by the same counters on a plain copy kernel (see profiles/); None until measured.
+MEASURED_TRAFFIC = {"cfg5": None, "cfg2": None, "cfg1": None}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1"])
+    ap.add_argument("--size", type=int, default=8192, help="M=N=K of the cfg5 GEMM")
+    ap.add_argument("--quantize-log2n", type=int, default=28)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-quantize", action="store_true", help="skip the standalone 2^28 quantize")
+    return ap.parse_args()
+
+
+def time_events(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for s, e in ev:
+        s.record()
+        fn()
+        e.record()
+    torch.cuda.synchronize()
+    ts = sorted(s.elapsed_time(e) for s, e in ev)
+    return float(np.mean(ts)), float(ts[len(ts) // 2])
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2302_12510_amd import binding as B
+    from paper_2302_12510_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+
+    # ---------------- set-up (untimed): inputs to HBM, weights quantized once -----------
+    if args.workload == "cfg5":
+        size = args.size
+        cfg = synth.config5a(size=size)
+        a_fmt, w_fmt = (8, True), (4, True)
+        M = N = K = size
+        A = torch.from_numpy(cfg["A"]).cuda().reshape(-1)
+        Wf = torch.from_numpy(cfg["W"]).cuda().reshape(-1)
+        conv = None
+        name = f"cfg5a GEMM M=N=K={size}, W 4-bit signed Laplace(0,0.02), A 8-bit signed N(0,1)+1% outliers at 10 sigma"
+    elif args.workload == "cfg1":
+        cfg = synth.config1()
+        a_fmt, w_fmt = (4, False), (4, True)
+        M, K = cfg["A"].shape
+        N = cfg["W"].shape[0]
+        A = torch.from_numpy(cfg["A"]).cuda().reshape(-1)
+        Wf = torch.from_numpy(cfg["W"]).cuda().reshape(-1)
+        conv = None
+        name = "cfg1 GEMM 64x64x256, W 4-bit signed, A 4-bit unsigned"
+    else:
+        cfg = synth.config2()
+        a_fmt, w_fmt = (4, False), (4, True)
+        Bn, H, Wd, Cin = cfg["X"].shape
+        Cout, kh, kw, _ = cfg["Wt"].shape
+        M, N, K = Bn * H * Wd, Cout, kh * kw * Cin
+        A = torch.from_numpy(cfg["X"]).cuda().reshape(-1)
+        Wf = torch.from_numpy(cfg["Wt"]).cuda().reshape(-1)
+        conv = (Bn, H, Wd, Cin, Cout, kh, kw, cfg["stride"], cfg["pad"])
+        name = "cfg2 conv 3x3 256->256 on 14x14, batch 64 (M=12544,N=256,K=2304), W 4-bit signed, A 4-bit unsigned"
+
+    sw = B.dybit_absmax_scale(Wf, *w_fmt)
+    qw = B.dybit_quantize(Wf, sw, *w_fmt)
+    del Wf
+    sa = torch.empty(1, dtype=torch.float32, device="cuda")
+    qa = torch.empty(B.dybit_packed_bytes(*a_fmt, A.numel()), dtype=torch.uint8, device="cuda")
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    g0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    g1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+
+    def step(i=None):
+        B.dybit_absmax_scale(A, *a_fmt, out=sa)
+        B.dybit_quantize(A, sa, *a_fmt, out=qa)
+        if i is not None:
+            g0[i].record()
+        if conv is None:
+            B.dybit_gemm(M, N, K, qa, a_fmt, sa, qw, w_fmt, sw, out=C)
+        else:
+            B.dybit_conv2d(*conv, qa, a_fmt, sa, qw, w_fmt, sw, out=C)
+        if i is not None:
+            g1[i].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    assert B.dybit_get_last_async_error() == B.OK
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(g0, g1)]))
+    flops = 2.0 * M * N * K
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "DyBit GEMM effective TOPS (+ quantize GB/s), % of roofline",
+        "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 MFMA inputs (exact), f32 accumulate", "data": "synthetic",
+        "config": {"workload": name, "M": M, "N": N, "K": K, "a_fmt": list(a_fmt), "w_fmt": list(w_fmt),
+                   "step": "absmax + quantize activations + gemm; weights pre-quantized"},
+        "roofline": {"bound": "mfma", "kernel": "dybit gemm_kernel", "achieved": round(gemm_tflops, 2),
+                     "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(gemm_tflops / PEAK_FP16_MFMA_TFLOPS, 4),
+                     "kernel_ms": round(gemm_ms, 4), "traffic": MEASURED_TRAFFIC[args.workload]},
+    }
+
+    # ---------------- activation-side passes of the step, timed alone --------------------
+    nA = A.numel()
+    absmax_ms, _ = time_events(lambda: B.dybit_absmax_scale(A, *a_fmt, out=sa), 10, 2, torch)
+    qa_ms, _ = time_events(lambda: B.dybit_quantize(A, sa, *a_fmt, out=qa), 10, 2, torch)
+    out["step_breakdown_ms"] = {"absmax": round(absmax_ms, 4), "quantize_activations": round(qa_ms, 4),
+                                "gemm": round(gemm_ms, 4)}
+
+    # ---------------- standalone quantize (config 5b) and a copy for reference -----------
+    if args.workload == "cfg5" and not args.no_quantize:
+        del C
+        n = 1 << args.quantize_log2n
+        x = torch.from_numpy(synth.config5b(n=n)).cuda()
+        q = {}
+        for bits in (4, 8):
+            fmt = (bits, True)
+            s = B.dybit_absmax_scale(x, *fmt)
+            codes = torch.empty(B.dybit_packed_bytes(*fmt, n), dtype=torch.uint8, device="cuda")
+            ms, med = time_events(lambda: B.dybit_quantize(x, s, *fmt, out=codes), 20, 3, torch)
+            gbps = (4 + bits / 8) * n / (ms * 1e-3) / 1e9
+            q[f"{bits}bit"] = {"ms": round(ms, 4), "GBps": round(gbps, 1), "frac_of_8TBps": round(gbps / PEAK_HBM_GBPS, 4)}
+            if bits == 8:
+                y = torch.empty(n, dtype=torch.float32, device="cuda")
+                dms, _ = time_events(lambda: B.dybit_dequantize(codes, n, s, *fmt, out=y), 10, 2, torch)
+                q["dequantize_8bit"] = {"ms": round(dms, 4), "GBps": round(5.0 * n / (dms * 1e-3) / 1e9, 1)}
+                del y
+            del codes
+        ams, _ = time_events(lambda: B.dybit_absmax_scale(x, 8, True, out=sa), 10, 2, torch)
+        q["absmax"] = {"ms": round(ams, 4), "GBps": round(4.0 * n / (ams * 1e-3) / 1e9, 1)}
+        y = torch.empty_like(x)
+        cms, _ = time_events(lambda: y.copy_(x), 10, 2, torch)
+        q["torch_copy_reference"] = {"ms": round(cms, 4), "GBps": round(8.0 * n / (cms * 1e-3) / 1e9, 1)}
+        q["n"] = n
+        out["quantize"] = q
+        out["roofline_quantize"] = {"bound": "hbm", "kernel": "dybit quantize_kernel<4,signed>",
+                                    "achieved": q["4bit"]["GBps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                    "frac": q["4bit"]["frac_of_8TBps"], "traffic": None}
+        del x, y
+
+    # ---------------- CPU baseline: the plain C oracle on a bounded sample -----------------
+    if not args.no_cpu_baseline:
+        from oracle import c_ref, dybit_ref as R
+        qa_h = qa.cpu().numpy()
+        qw_h = qw.cpu().numpy()
+        if conv is None:
+            rows = min(M, max(1, int(2.0e11 // (N * K))))       # ~200 GMAC of scalar C
+            a_codes = R.unpack(qa_h[: rows * K * a_fmt[0] // 8], rows * K, a_fmt[0]).reshape(rows, K)
+            w_codes = R.unpack(qw_h, N * K, w_fmt[0]).reshape(N, K)
+            t0 = time.perf_counter()
+            c_ref.gemm(a_codes, a_fmt, sa.item(), w_codes, w_fmt, sw.item(), want_den=False)
+            dt = time.perf_counter() - t0
+            sample = f"first {rows} of {M} rows of the same GEMM (all N, all K)"
+            sflops = 2.0 * rows * N * K
+        else:
+            Bn, H, Wd, Cin, Cout, kh, kw, stride, pad = conv
+            nb = min(Bn, 16)
+            x_codes = R.unpack(qa_h[: nb * H * Wd * Cin * a_fmt[0] // 8], nb * H * Wd * Cin, a_fmt[0]).reshape(nb, H, Wd, Cin)
+            w_codes = R.unpack(qw_h, Cout * kh * kw * Cin, w_fmt[0]).reshape(Cout, kh, kw, Cin)
+            t0 = time.perf_counter()
+            c_ref.conv2d(x_codes, a_fmt, sa.item(), w_codes, w_fmt, sw.item(), stride, pad, want_den=False)
+            dt = time.perf_counter() - t0
+            sample = f"first {nb} of {Bn} images of the same convolution"
+            sflops = 2.0 * (M // Bn * nb) * N * K
+        out["cpu_baseline"] = {"value": round(sflops / dt / 1e12, 5), "unit": "TOPS", "cores": c_ref.num_threads(),
+                               "kind": "oracle", "sample": sample, "seconds": round(dt, 2)}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
