@@ -10,24 +10,13 @@
 
 #include "dybit_device.h"
 #include "dybit_host.h"
+#include "gemm_args.h"
 
 namespace dybit {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-struct GemmArgs {
-    int64_t M, N, K;                 // conv: M = B*Ho*Wo, N = Cout, K = kh*kw*Cin
-    const uint8_t *A, *W;
-    int a_signed, w_signed;
-    const float *a_scale, *w_scale, *bias;
-    int relu;
-    float *C;
-    int64_t ldc;
-    // convolution geometry (CONV only)
-    int H, Wd, Cin, Ho, Wo, kh, kw, stride, pad;
-};
 
 // ---------------------------------------------------------------------------
 // General kernel: any format pair, any shape.
@@ -366,6 +355,9 @@ extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
     g.a_signed = a_fmt.is_signed; g.w_signed = w_fmt.is_signed;
     g.a_scale = a_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
     g.C = C; g.ldc = ldc;
+    g.a_bytes = M * (K * a_fmt.bits / 8);
+    g.w_bytes = N * (K * w_fmt.bits / 8);
+    if (launch_gemm_fast(g, a_fmt.bits, w_fmt.bits, false, (hipStream_t)stream)) return launch_status();
     const bool vec = (K % UNIT == 0) && aligned16(A_codes) && aligned16(W_codes);
     dispatch_gemm(g, a_fmt.bits, w_fmt.bits, false, vec, (hipStream_t)stream);
     return launch_status();
@@ -397,6 +389,9 @@ extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Ci
     g.C = Y; g.ldc = Cout;
     g.H = (int)H; g.Wd = (int)W; g.Cin = (int)Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.stride = stride; g.pad = pad;
+    g.a_bytes = B * H * W * (Cin * x_fmt.bits / 8);
+    g.w_bytes = Cout * (g.K * w_fmt.bits / 8);
+    if (launch_gemm_fast(g, x_fmt.bits, w_fmt.bits, true, (hipStream_t)stream)) return launch_status();
     const bool vec = (Cin % UNIT == 0) && aligned16(X_codes) && aligned16(Wt_codes);
     dispatch_gemm(g, x_fmt.bits, w_fmt.bits, true, vec, (hipStream_t)stream);
     return launch_status();

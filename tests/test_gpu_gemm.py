@@ -172,3 +172,69 @@ def test_config5a_shape_sampled_outputs():
     want, den = R.gemm(qa[rows], a_fmt, sa, qw[cols], w_fmt, sw)
     got = c[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
     assert_within(got, want, den)
+
+
+# ---- large-tile kernel (256 x 256 tiles, in-register decode) -------------------
+FAST_PAIRS = [((8, True), (4, True)), ((4, False), (4, True))]
+
+
+@pytest.fixture
+def force_fast(monkeypatch):
+    monkeypatch.setenv("DYBIT_FAST_MIN_TILES", "1")
+
+
+@pytest.mark.parametrize("a_fmt,w_fmt", FAST_PAIRS)
+@pytest.mark.parametrize("shape", [(2100, 3900, 192), (256, 256, 64), (300, 520, 128), (1, 7, 64), (513, 255, 320)])
+def test_large_tile_kernel_ragged(force_fast, a_fmt, w_fmt, shape):
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + K)
+    qa = random_codes(rng, (M, K), a_fmt)
+    qw = random_codes(rng, (N, K), w_fmt)
+    bias = rng.normal(0, 3, N).astype(np.float32)
+    for b, relu in ((None, False), (bias, True)):
+        got = run_gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, b, relu)
+        want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, b, relu)
+        assert_within(got, want, den)
+
+
+@pytest.mark.parametrize("a_fmt,w_fmt", FAST_PAIRS)
+def test_large_tile_kernel_every_code_pair(force_fast, a_fmt, w_fmt):
+    """Each A code meets each W code exactly once per row pair, so a wrong table entry or a
+    wrong k pairing between the two decoders cannot cancel."""
+    na, nw = 1 << a_fmt[0], 1 << w_fmt[0]
+    K = 64 * ((na * nw + 63) // 64)
+    rng = np.random.default_rng(5)
+    qa = np.zeros((260, K), np.uint8); qw = np.zeros((258, K), np.uint8)
+    for r in range(260):
+        qa[r] = np.resize(np.repeat(np.arange(na), nw), K)
+        qa[r] = np.roll(qa[r], r)
+    for r in range(258):
+        qw[r] = np.resize(np.tile(np.arange(nw), na), K)
+        qw[r] = np.roll(qw[r], 3 * r)
+    got = run_gemm(qa, a_fmt, 1.0, qw, w_fmt, 1.0)
+    want, den = R.gemm(qa, a_fmt, 1.0, qw, w_fmt, 1.0)
+    assert_within(got, want, den)
+    # one-hot rows: a single non-zero code per row pins every decoded value on its own
+    cba, cbw = R.codebook(*a_fmt), R.codebook(*w_fmt)
+    one_w = int(np.where(cbw == 1.0)[0][0])
+    qa1 = np.zeros((na, 64), np.uint8); qw1 = np.zeros((64, 64), np.uint8)
+    for c in range(na):
+        qa1[c, c % 64] = c
+    qw1[np.arange(64), np.arange(64)] = one_w
+    got = run_gemm(qa1, a_fmt, 1.0, qw1, w_fmt, 1.0)
+    want = np.zeros((na, 64)); want[np.arange(na), np.arange(na) % 64] = cba
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+@pytest.mark.parametrize("x_fmt,w_fmt", FAST_PAIRS)
+@pytest.mark.parametrize("geom", [(3, 1, 1), (1, 1, 0), (3, 2, 1)])
+def test_large_tile_kernel_conv(force_fast, x_fmt, w_fmt, geom):
+    k, stride, pad = geom
+    rng = np.random.default_rng(k * 7 + stride)
+    Bn, H, W, Cin, Cout = 3, 13, 11, 64, 300
+    qx = random_codes(rng, (Bn, H, W, Cin), x_fmt)
+    qw = random_codes(rng, (Cout, k, k, Cin), w_fmt)
+    bias = rng.normal(0, 1, Cout).astype(np.float32)
+    got = run_conv(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, True)
+    want, den = R.conv2d(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, True)
+    assert_within(got, want, den)
