@@ -29,8 +29,8 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 256, TN = 256, TK = 64;
 constexpr int THREADS = 256;
-constexpr int ROW_BYTES = TK * 2;                 // one LDS row: 64 halves = 8 chunks of 16 B
-constexpr int STAGE_BYTES = TM * ROW_BYTES;       // 32 KiB per operand per stage
+constexpr int ROW_BYTES = TK * 2 + 16;            // one LDS row: 64 halves = 8 chunks of 16 B, plus 16 B of padding
+constexpr int STAGE_BYTES = TM * ROW_BYTES;       // 36 KiB per operand per stage
 constexpr int LDS_BYTES = 4 * STAGE_BYTES;        // A0 A1 W0 W1
 constexpr uint32_t kOob = 0x80000000u;            // a buffer offset past every supported size: such loads return 0
 
@@ -129,8 +129,9 @@ template <> struct Codec<F4U> {
 //          and decodes to LDS chunks 2 s and 2 s + 1 of that row.
 //   4-bit: 2 loads of 16 B; load j covers row t/2 + 128 j, codes 32 s .. 32 s + 31 (s = t % 2)
 //          and decodes to LDS chunks 4 s .. 4 s + 3.
-// LDS chunk c of row r sits at r * 128 + ((c ^ (r & 7)) * 16): fragment reads (32 consecutive
-// rows, same chunk) and these writes are both free of bank conflicts.
+// LDS chunk c of row r sits at r * 144 + c * 16: the 16 B of padding rotate the banks by one
+// chunk per row, so fragment reads (32 consecutive rows, same chunk) and these writes are both
+// free of bank conflicts, and every address is one base register plus an immediate.
 // ---------------------------------------------------------------------------
 template <int BITS> struct Staging {
     static constexpr int NLOAD = BITS == 8 ? 4 : 2;
@@ -141,29 +142,24 @@ template <int BITS> struct Staging {
 };
 
 template <int FMT>
-__device__ __forceinline__ void decode_quarter(const u32x4 *raw, int quarter, char *lds_tile, u32 wr_base, u32 row_x)
+__device__ __forceinline__ void decode_quarter(const u32x4 *raw, int quarter, char *lds_tile, u32 wr_base)
 {
     using C = Codec<FMT>;
     using S = Staging<C::BITS>;
-    // wr_base: byte address of (row of load 0, chunk 0, unswizzled); row_x = (row & 7) << 4
+    // wr_base: byte address of the first chunk this thread writes in the row of load 0
+    u32 d[8];
+    u32 off;
     if (C::BITS == 8) {
         const u32x4 r = raw[quarter];
-        u32 d[8];
         C::word(r.x, d); C::word(r.y, d + 2); C::word(r.z, d + 4); C::word(r.w, d + 6);
-        const u32 row_off = wr_base + quarter * S::ROWS_PER_LOAD * ROW_BYTES;
-        const u32 c0 = ((threadIdx.x & 3) * 2) << 4;
-        *reinterpret_cast<u32x4 *>(lds_tile + row_off + (c0 ^ row_x)) = u32x4{d[0], d[1], d[2], d[3]};
-        *reinterpret_cast<u32x4 *>(lds_tile + row_off + ((c0 + 16) ^ row_x)) = u32x4{d[4], d[5], d[6], d[7]};
+        off = quarter * S::ROWS_PER_LOAD * ROW_BYTES;
     } else {
         const u32x4 r = raw[quarter >> 1];
-        const u32 w0 = (quarter & 1) ? r.z : r.x, w1 = (quarter & 1) ? r.w : r.y;
-        u32 d[8];
-        C::word(w0, d); C::word(w1, d + 4);
-        const u32 row_off = wr_base + (quarter >> 1) * S::ROWS_PER_LOAD * ROW_BYTES;
-        const u32 c0 = ((threadIdx.x & 1) * 4 + (quarter & 1) * 2) << 4;
-        *reinterpret_cast<u32x4 *>(lds_tile + row_off + (c0 ^ row_x)) = u32x4{d[0], d[1], d[2], d[3]};
-        *reinterpret_cast<u32x4 *>(lds_tile + row_off + ((c0 + 16) ^ row_x)) = u32x4{d[4], d[5], d[6], d[7]};
+        C::word((quarter & 1) ? r.z : r.x, d); C::word((quarter & 1) ? r.w : r.y, d + 4);
+        off = (quarter >> 1) * S::ROWS_PER_LOAD * ROW_BYTES + (quarter & 1) * 32;
     }
+    *reinterpret_cast<u32x4 *>(lds_tile + wr_base + off) = u32x4{d[0], d[1], d[2], d[3]};
+    *reinterpret_cast<u32x4 *>(lds_tile + wr_base + off + 16) = u32x4{d[4], d[5], d[6], d[7]};
 }
 
 template <int FMT_A, int FMT_W, bool CONV>
@@ -245,28 +241,22 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
                 rawA[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off, 0, 0);
             }
         } else {
+            // rows past M start at kOob and stay out of range while k advances
             const u32 koff = (u32)(k0 * CA::BITS / 8);
 #pragma unroll
-            for (int j = 0; j < SA::NLOAD; ++j)
-                rawA[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, okA[j] ? offA[j] + koff : kOob, 0, 0);
+            for (int j = 0; j < SA::NLOAD; ++j) rawA[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, offA[j] + koff, 0, 0);
         }
         const u32 koffw = (u32)(k0 * CW::BITS / 8);
 #pragma unroll
-        for (int j = 0; j < SW::NLOAD; ++j)
-            rawW[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, offW[j] == kOob ? offW[j] : offW[j] + koffw, 0, 0);
+        for (int j = 0; j < SW::NLOAD; ++j) rawW[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, offW[j] + koffw, 0, 0);
     };
 
     // ---- LDS addresses
-    const u32 wrA = (u32)(tid / SA::TPR) * ROW_BYTES, wrA_x = (u32)((tid / SA::TPR) & 7) << 4;
-    const u32 wrW = (u32)(tid / SW::TPR) * ROW_BYTES, wrW_x = (u32)((tid / SW::TPR) & 7) << 4;
-    // fragment reads: row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5), swizzled by row & 7 = lane & 7
-    u32 rdA[4], rdW[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        const u32 chunk = (u32)((2 * kk + (lane >> 5)) ^ (lane & 7)) << 4;
-        rdA[kk] = (u32)(wm * 128 + (lane & 31)) * ROW_BYTES + chunk;
-        rdW[kk] = (u32)(wn * 128 + (lane & 31)) * ROW_BYTES + chunk;
-    }
+    const u32 wrA = (u32)(tid / SA::TPR) * ROW_BYTES + (u32)(tid % SA::TPR) * (128 / SA::TPR);
+    const u32 wrW = (u32)(tid / SW::TPR) * ROW_BYTES + (u32)(tid % SW::TPR) * (128 / SW::TPR);
+    // fragment reads: row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5)
+    const u32 rdA = (u32)(wm * 128 + (lane & 31)) * ROW_BYTES + (u32)(lane >> 5) * 16;
+    const u32 rdW = (u32)(wn * 128 + (lane & 31)) * ROW_BYTES + (u32)(lane >> 5) * 16;
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -284,8 +274,8 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
     if (ktiles > 1) load_tile(1, rawA[1], rawW[1]);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        decode_quarter<FMT_A>(rawA[0], q, ldsA, wrA, wrA_x);
-        decode_quarter<FMT_W>(rawW[0], q, ldsW, wrW, wrW_x);
+        decode_quarter<FMT_A>(rawA[0], q, ldsA, wrA);
+        decode_quarter<FMT_W>(rawW[0], q, ldsW, wrW);
     }
     __syncthreads();
 
@@ -300,17 +290,17 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
         if (FULL) load_tile(kt + 2, rawA[s], rawW[s]);
         f16x8 fa[2][4], fw[2][4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fa[0][i] = *reinterpret_cast<const f16x8 *>(curA + rdA[0] + i * 32 * ROW_BYTES);
+        for (int i = 0; i < 4; ++i) fa[0][i] = *reinterpret_cast<const f16x8 *>(curA + rdA + i * 32 * ROW_BYTES);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fw[0][j] = *reinterpret_cast<const f16x8 *>(curW + rdW[0] + j * 32 * ROW_BYTES);
+        for (int j = 0; j < 4; ++j) fw[0][j] = *reinterpret_cast<const f16x8 *>(curW + rdW + j * 32 * ROW_BYTES);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const int cb = kk & 1, nb = cb ^ 1;
             if (kk < 3) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) fa[nb][i] = *reinterpret_cast<const f16x8 *>(curA + rdA[kk + 1] + i * 32 * ROW_BYTES);
+                for (int i = 0; i < 4; ++i) fa[nb][i] = *reinterpret_cast<const f16x8 *>(curA + rdA + (kk + 1) * 32 + i * 32 * ROW_BYTES);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) fw[nb][j] = *reinterpret_cast<const f16x8 *>(curW + rdW[kk + 1] + j * 32 * ROW_BYTES);
+                for (int j = 0; j < 4; ++j) fw[nb][j] = *reinterpret_cast<const f16x8 *>(curW + rdW + (kk + 1) * 32 + j * 32 * ROW_BYTES);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -318,8 +308,8 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[cb][i], fw[cb][j], acc[i][j], 0, 0, 0);
             if (FULL) {
-                decode_quarter<FMT_A>(rawA[s ^ 1], kk, nxtA, wrA, wrA_x);
-                decode_quarter<FMT_W>(rawW[s ^ 1], kk, nxtW, wrW, wrW_x);
+                decode_quarter<FMT_A>(rawA[s ^ 1], kk, nxtA, wrA);
+                decode_quarter<FMT_W>(rawW[s ^ 1], kk, nxtW, wrW);
             }
             // Interleave: one MFMA, then a handful of decode instructions, with the fragment
             // reads of the next k block early and the tile writes late in the group.

@@ -1,0 +1,119 @@
+"""Chained DyBit inference over a layer list (the ResNet-18 / ResNet-50 workloads).
+
+Per convolution / linear layer, on one stream and without host synchronisation:
+    absmax scale of the fp32 input -> quantize to DyBit codes -> dybit_conv2d against the
+    pre-quantized weights with the folded batch-norm shift as bias (and ReLU) -> fp32 output.
+This is the paper's dataflow with the write-back quantization done as a separate pass
+(Sec. III-B: activations and weights are stored as DyBit codes, partial sums stay FP).
+Residual additions and pooling run on the fp32 tensors with torch ops; they are glue, not
+part of the library.
+
+Formats: weights are signed; an activation tensor is unsigned when it is the output of a
+ReLU or of a pooling of such outputs, signed otherwise (the network input).  Layer-wise
+bitwidths come from a table {layer name: (bits_W, bits_A)}, as the search of Sec. III-C
+would produce.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _pad_channels(cin: int, bits_a: int, bits_w: int) -> int:
+    """Smallest channel count >= cin whose packed pixel ends on a byte boundary for both formats."""
+    c = cin
+    while (c * bits_a) % 8 or (c * bits_w) % 8:
+        c += 1
+    return c
+
+
+class DybitNetwork:
+    def __init__(self, layers, weights, bitwidths, device="cuda"):
+        self.layers = layers
+        self.bitwidths = bitwidths
+        self.device = device
+        self.params = {}
+        for l in layers:
+            if l["op"] not in ("conv", "fc"):
+                continue
+            w, b = weights[l["name"]]
+            bw, ba = bitwidths[l["name"]]
+            cout, kh, kw, cin = w.shape
+            cpad = _pad_channels(cin, ba, bw)
+            if cpad != cin:
+                wp = np.zeros((cout, kh, kw, cpad), dtype=np.float32)
+                wp[..., :cin] = w
+                w = wp
+            wd = torch.from_numpy(np.ascontiguousarray(w)).to(device).reshape(-1)
+            w_fmt = (bw, True)
+            sw = B.dybit_absmax_scale(wd, *w_fmt)
+            qw = B.dybit_quantize(wd, sw, *w_fmt)
+            self.params[l["name"]] = {
+                "w_fmt": w_fmt, "w_scale": sw, "w_codes": qw, "bias": torch.from_numpy(b).to(device),
+                "cin": cin, "cpad": cpad, "cout": cout, "k": kh, "a_bits": ba,
+            }
+
+    def forward(self, x: torch.Tensor, record=None) -> torch.Tensor:
+        """x: NHWC float32 on the device.  `record(name, dict)` receives, per conv/fc layer, the
+        tensors needed to check that layer in isolation (input, scale, codes, raw output)."""
+        acts = {"input": x}
+        nonneg = {"input": False}
+        out = x
+        for l in self.layers:
+            name, op = l["name"], l["op"]
+            src = acts[l["src"]]
+            if op == "maxpool":
+                y = torch.nn.functional.max_pool2d(src.permute(0, 3, 1, 2), l["k"], l["stride"], l["pad"])
+                out = y.permute(0, 2, 3, 1).contiguous()
+                nonneg[name] = nonneg[l["src"]]
+            elif op == "avgpool":
+                out = src.mean(dim=(1, 2), keepdim=True)
+                nonneg[name] = nonneg[l["src"]]
+            else:
+                p = self.params[name]
+                a_fmt = (p["a_bits"], not nonneg[l["src"]])
+                Bn, H, W, C = src.shape
+                if p["cpad"] != C:
+                    src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
+                flat = src.reshape(-1)
+                sa = B.dybit_absmax_scale(flat, *a_fmt)
+                qa = B.dybit_quantize(flat, sa, *a_fmt)
+                fused_relu = bool(l.get("relu")) and not l.get("add")
+                k = p["k"]
+                stride, pad = (l["stride"], l["pad"]) if op == "conv" else (1, 0)
+                y = B.dybit_conv2d(Bn, H, W, p["cpad"], p["cout"], k, k, stride, pad,
+                                   qa, a_fmt, sa, p["w_codes"], p["w_fmt"], p["w_scale"],
+                                   p["bias"], fused_relu)
+                if record is not None:
+                    record(name, {"x": src, "a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "y": y,
+                                  "relu": fused_relu, "stride": stride, "pad": pad, "k": k, **p})
+                out = y
+                if l.get("add"):
+                    out = out + acts[l["add"]]
+                    if l.get("relu"):
+                        out = torch.relu_(out)
+                nonneg[name] = bool(l.get("relu"))
+            acts[name] = out
+        return out.reshape(out.shape[0], -1)
+
+    def gemm_shapes(self, batch: int, hw: int):
+        """(name, M, N, K) of every conv/fc layer for an input of batch x hw x hw (K counted on
+        the real channel count, not the padded one)."""
+        sizes = {"input": hw}
+        shapes = []
+        for l in self.layers:
+            s = sizes[l["src"]]
+            if l["op"] == "maxpool":
+                sizes[l["name"]] = (s + 2 * l["pad"] - l["k"]) // l["stride"] + 1
+            elif l["op"] == "avgpool":
+                sizes[l["name"]] = 1
+            elif l["op"] == "fc":
+                sizes[l["name"]] = 1
+                shapes.append((l["name"], batch, l["cout"], l["cin"]))
+            else:
+                o = (s + 2 * l["pad"] - l["k"]) // l["stride"] + 1
+                sizes[l["name"]] = o
+                shapes.append((l["name"], batch * o * o, l["cout"], l["k"] * l["k"] * l["cin"]))
+        return shapes
