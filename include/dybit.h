@@ -115,8 +115,8 @@ dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t 
                           float *Y, dybit_stream stream);
 
 /* Waits for `stream`, then reports and clears the asynchronous error flag of the current
- * device: *flag_out [host] is DYBIT_OK or DYBIT_ERR_BAD_SCALE (a quantize, dequantize, gemm or
- * conv2d kernel since the last call found an unusable scale and wrote nothing). */
+ * device: *flag_out [host] is DYBIT_OK or DYBIT_ERR_BAD_SCALE (a dybit_quantize kernel since the
+ * last call found an unusable scale and wrote nothing). */
 dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream);
 
 #ifdef __cplusplus

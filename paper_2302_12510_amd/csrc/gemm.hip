@@ -3,8 +3,10 @@
 // Every DyBit value of every supported format is exactly representable in IEEE half precision
 // (at most 7 significant bits, magnitudes 2^-7 .. 2^7), so both operands are decoded to fp16 and
 // multiplied with v_mfma_f32_32x32x16_f16: the products are exact and only the fp32
-// accumulation rounds.  Packed codes are streamed from HBM, decoded through a per-operand
-// lookup table that lives in LDS, staged in LDS as fp16 tiles and consumed by the matrix cores.
+// accumulation rounds.  This file holds the C entry points and the general kernel (any format
+// pair, any shape): packed codes are streamed from HBM, decoded through a per-operand lookup
+// table that lives in LDS, staged in LDS as fp16 tiles and consumed by the matrix cores.  Large
+// 4/8-bit problems are routed to the large-tile kernel of gemm_fast.hip first.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
