@@ -269,7 +269,7 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
     const int64_t ktiles = g.K / TK;
     u32x4 rawA[2][SA::NLOAD], rawW[2][SW::NLOAD];
 
-    // ---- prologue: tile 0 decoded into stage 0, tile 1 in flight
+    // ---- prologue: tile 0 decoded into stage 0, tile 1 in flight, fragments of k block 0 in registers
     load_tile(0, rawA[0], rawW[0]);
     if (ktiles > 1) load_tile(1, rawA[1], rawW[1]);
 #pragma unroll
@@ -279,66 +279,88 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
     }
     __syncthreads();
 
-    // One K step.  FULL steps also decode the next tile into the other LDS stage; the loads of
-    // the tile after that are issued unconditionally (past the end of K they fetch bytes that
-    // are never decoded; past the end of the buffer they return 0).
-    auto step = [&](int64_t kt, auto stage_tag, auto full_tag) {
+    f16x8 fa[2][4], fw[2][4];
+    auto read_frags = [&](const char *tileA, const char *tileW, int kk, int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const f16x8 *>(tileA + rdA + kk * 32 + i * 32 * ROW_BYTES);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fw[buf][j] = *reinterpret_cast<const f16x8 *>(tileW + rdW + kk * 32 + j * 32 * ROW_BYTES);
+    };
+    read_frags(ldsA, ldsW, 0, 0);
+
+    // One K step over LDS stage s.  Four k blocks of 16 MFMAs each; the fragments of a block are
+    // read one block ahead.  The next tile is decoded into the other stage during blocks 0..2,
+    // the workgroup barrier sits before block 3, and the first fragments of the next tile are
+    // requested right after it, so that their LDS latency hides behind the MFMAs of block 3.
+    //   MODE 2: decode the next tile and load the one after;  1: decode only;  0: last tile.
+    auto step = [&](int64_t kt, auto stage_tag, auto mode_tag) {
         constexpr int s = decltype(stage_tag)::value;
-        constexpr bool FULL = decltype(full_tag)::value;
+        constexpr int MODE = decltype(mode_tag)::value;
         const char *curA = ldsA + s * STAGE_BYTES, *curW = ldsW + s * STAGE_BYTES;
         char *nxtA = ldsA + (s ^ 1) * STAGE_BYTES, *nxtW = ldsW + (s ^ 1) * STAGE_BYTES;
-        if (FULL) load_tile(kt + 2, rawA[s], rawW[s]);
-        f16x8 fa[2][4], fw[2][4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fa[0][i] = *reinterpret_cast<const f16x8 *>(curA + rdA + i * 32 * ROW_BYTES);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) fw[0][j] = *reinterpret_cast<const f16x8 *>(curW + rdW + j * 32 * ROW_BYTES);
+        if (MODE == 2) load_tile(kt + 2, rawA[s], rawW[s]);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const int cb = kk & 1, nb = cb ^ 1;
-            if (kk < 3) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) fa[nb][i] = *reinterpret_cast<const f16x8 *>(curA + rdA + (kk + 1) * 32 + i * 32 * ROW_BYTES);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) fw[nb][j] = *reinterpret_cast<const f16x8 *>(curW + rdW + (kk + 1) * 32 + j * 32 * ROW_BYTES);
+            if (kk == 3 && MODE >= 1) {
+                __syncthreads();
+                read_frags(nxtA, nxtW, 0, nb);
+            } else if (kk < 3) {
+                read_frags(curA, curW, kk + 1, nb);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[cb][i], fw[cb][j], acc[i][j], 0, 0, 0);
-            if (FULL) {
-                decode_quarter<FMT_A>(rawA[s ^ 1], kk, nxtA, wrA);
-                decode_quarter<FMT_W>(rawW[s ^ 1], kk, nxtW, wrW);
+            if (MODE >= 1 && kk < 3) {
+                // decode work of the next tile, spread over blocks 0..2 in three near-equal parts
+                if (kk == 0) {
+                    decode_quarter<FMT_A>(rawA[s ^ 1], 0, nxtA, wrA);
+                    decode_quarter<FMT_W>(rawW[s ^ 1], 0, nxtW, wrW);
+                    decode_quarter<FMT_W>(rawW[s ^ 1], 1, nxtW, wrW);
+                } else if (kk == 1) {
+                    decode_quarter<FMT_A>(rawA[s ^ 1], 1, nxtA, wrA);
+                    decode_quarter<FMT_A>(rawA[s ^ 1], 2, nxtA, wrA);
+                } else {
+                    decode_quarter<FMT_A>(rawA[s ^ 1], 3, nxtA, wrA);
+                    decode_quarter<FMT_W>(rawW[s ^ 1], 2, nxtW, wrW);
+                    decode_quarter<FMT_W>(rawW[s ^ 1], 3, nxtW, wrW);
+                }
             }
-            // Interleave: one MFMA, then a handful of decode instructions, with the fragment
-            // reads of the next k block early and the tile writes late in the group.
+            // Order inside the block: the eight fragment reads first, then MFMAs with the decode
+            // arithmetic between them, the tile writes towards the end.
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);                     // DS read x 8
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
-                if (kk < 3 && r < 8) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-                if (FULL) __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);       // VALU
-                if (FULL && r >= 12) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
+                if (MODE >= 1 && kk < 3) __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);   // VALU
+                if (MODE >= 1 && kk < 3 && r >= 3 && (r & 1)) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
     };
     using T0 = std::integral_constant<int, 0>;
     using T1 = std::integral_constant<int, 1>;
-    using Full = std::true_type;
-    using Last = std::false_type;
+    using M0 = std::integral_constant<int, 0>;
+    using M1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
 
+    // tiles 0 .. ktiles-3 in MODE 2, tile ktiles-2 in MODE 1, tile ktiles-1 in MODE 0
     int64_t kt = 0;
-    for (; kt + 2 < ktiles; kt += 2) {
-        step(kt, T0{}, Full{});
-        step(kt + 1, T1{}, Full{});
+    for (; kt + 3 < ktiles; kt += 2) {
+        step(kt, T0{}, M2{});
+        step(kt + 1, T1{}, M2{});
     }
-    if (kt + 1 < ktiles) {
-        step(kt, T0{}, Full{});
-        step(kt + 1, T1{}, Last{});
+    if (kt + 3 == ktiles) {
+        step(kt, T0{}, M2{});
+        step(kt + 1, T1{}, M1{});
+        step(kt + 2, T0{}, M0{});
+    } else if (kt + 2 == ktiles) {
+        step(kt, T0{}, M1{});
+        step(kt + 1, T1{}, M0{});
     } else {
-        step(kt, T0{}, Last{});
+        step(kt, T0{}, M0{});
     }
 
     // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU).  Accumulator v of a lane is row
