@@ -1,14 +1,25 @@
 // Large-tile DyBit matrix product for gfx950: 256 x 256 tile of C per workgroup, K step 64,
-// four waves (one per SIMD) each owning 128 x 128 of C in 256 accumulator registers.
+// eight waves (two per SIMD); wave w owns rows 32 w .. 32 w + 31 of the tile and all 256
+// columns, i.e. 8 accumulator blocks of 32 x 32 in 128 AGPRs.
 //
-// Data path per K step: packed codes come from HBM/L2 with 128-bit buffer loads (two steps
-// ahead), are decoded to fp16 in the vector ALU (no table look-ups: see the codecs below),
-// written once to a double-buffered, XOR-swizzled LDS tile and read back as MFMA fragments by
-// the waves that need them.  The decode of step t+1 is interleaved with the 64 MFMAs of step t.
-//
-// The order of k inside one MFMA does not matter as long as both operands agree, so both
-// codecs emit each group of eight k values in the order (k0,k2,k1,k3,k4,k6,k5,k7): that is
-// the order in which their packed arithmetic produces them for free.
+// Why this shape.  Measured on this chip, a wave issues about one instruction per five cycles
+// and every MFMA occupies the vector-ALU issue port for about twelve of its 32 cycles, so the
+// decode arithmetic (the bulk of the instructions) must be spread over two waves per SIMD and
+// nothing else may compete for issue slots.  LDS stores are the slow LDS operation (about 36
+// cycles per 128-bit store per wave), LDS loads are not.  Hence:
+//   * the activation operand A never touches LDS: every lane fetches the 32 codes of its own
+//     row that its MFMA fragments need (128-bit buffer loads, two K steps ahead), decodes them
+//     in registers and feeds the MFMA directly.  With one 32-row block per wave no A code is
+//     decoded twice.
+//   * the weight operand W is decoded once per workgroup (each thread 32 codes per K step),
+//     stored to a double-buffered LDS tile with one 128-bit store per 8 codes and read back by
+//     all eight waves as MFMA fragments (`ds_read_b128`, rows padded by 16 B: no bank conflicts,
+//     immediate offsets only).
+//   * decode is arithmetic / byte-permute work in the vector ALU, no table look-ups.
+// A lane of k-group g (lane / 32) owns k = 32 g .. 32 g + 31 of every K step; MFMA block kk of
+// a step contracts k = 32 g + 8 kk .. + 7.  The order of k inside an MFMA does not matter as
+// long as both operands agree, so both codecs emit each group of eight k values in the order
+// (k0,k2,k1,k3,k4,k6,k5,k7): that is the order their packed arithmetic produces for free.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -28,10 +39,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int THREADS = 256;
-constexpr int ROW_BYTES = TK * 2 + 16;            // one LDS row: 64 halves = 8 chunks of 16 B, plus 16 B of padding
-constexpr int STAGE_BYTES = TM * ROW_BYTES;       // 36 KiB per operand per stage
-constexpr int LDS_BYTES = 4 * STAGE_BYTES;        // A0 A1 W0 W1
+constexpr int THREADS = 512;
+constexpr int ROW_BYTES = TK * 2 + 16;            // one LDS row of W: 64 halves = 8 chunks of 16 B, plus 16 B of padding
+constexpr int STAGE_BYTES = TN * ROW_BYTES;       // 36 KiB per stage
+constexpr int LDS_BYTES = 2 * STAGE_BYTES;
 constexpr uint32_t kOob = 0x80000000u;            // a buffer offset past every supported size: such loads return 0
 
 enum { F4S = 0, F4U = 1, F8S = 2, F8U = 3 };
@@ -58,6 +69,22 @@ __device__ __forceinline__ u32 recip_decode_pair(u32 h, u32 k2)
 }
 
 template <int FMT> struct Codec;
+
+// Codec<F>::word decodes one 32-bit word; Codec<F>::eight decodes the q-th group of eight codes of
+// a thread's 32 codes (held in BITS / 4 registers of 128 bits) into four registers of two halves.
+template <int FMT>
+__device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
+{
+    using C = Codec<FMT>;
+    if (C::BITS == 8) {
+        const u32x4 r = raw[q >> 1];
+        C::word((q & 1) ? r.z : r.x, d);
+        C::word((q & 1) ? r.w : r.y, d + 2);
+    } else {
+        const u32x4 r = raw[0];
+        C::word(q == 0 ? r.x : q == 1 ? r.y : q == 2 ? r.z : r.w, d);
+    }
+}
 
 template <> struct Codec<F8S> {
     static constexpr int BITS = 8;
@@ -124,56 +151,18 @@ template <> struct Codec<F4U> {
 };
 
 // ---------------------------------------------------------------------------
-// Per-thread staging of one operand tile (256 rows x 64 codes).
-//   8-bit: 4 loads of 16 B; load j covers row t/4 + 64 j, codes 16 s .. 16 s + 15 (s = t % 4)
-//          and decodes to LDS chunks 2 s and 2 s + 1 of that row.
-//   4-bit: 2 loads of 16 B; load j covers row t/2 + 128 j, codes 32 s .. 32 s + 31 (s = t % 2)
-//          and decodes to LDS chunks 4 s .. 4 s + 3.
-// LDS chunk c of row r sits at r * 144 + c * 16: the 16 B of padding rotate the banks by one
-// chunk per row, so fragment reads (32 consecutive rows, same chunk) and these writes are both
-// free of bank conflicts, and every address is one base register plus an immediate.
+// Kernel
 // ---------------------------------------------------------------------------
-template <int BITS> struct Staging {
-    static constexpr int NLOAD = BITS == 8 ? 4 : 2;
-    static constexpr int ROWS_PER_LOAD = TM / NLOAD;
-    static constexpr int TPR = THREADS / ROWS_PER_LOAD;          // threads per row: 4 or 2
-    static constexpr int TILE_K_BYTES = TK * BITS / 8;           // 64 or 32
-    static constexpr int CHUNKS = 8 / TPR;                       // chunks written per load: 2 or 4
-};
-
-template <int FMT>
-__device__ __forceinline__ void decode_quarter(const u32x4 *raw, int quarter, char *lds_tile, u32 wr_base)
-{
-    using C = Codec<FMT>;
-    using S = Staging<C::BITS>;
-    // wr_base: byte address of the first chunk this thread writes in the row of load 0
-    u32 d[8];
-    u32 off;
-    if (C::BITS == 8) {
-        const u32x4 r = raw[quarter];
-        C::word(r.x, d); C::word(r.y, d + 2); C::word(r.z, d + 4); C::word(r.w, d + 6);
-        off = quarter * S::ROWS_PER_LOAD * ROW_BYTES;
-    } else {
-        const u32x4 r = raw[quarter >> 1];
-        C::word((quarter & 1) ? r.z : r.x, d); C::word((quarter & 1) ? r.w : r.y, d + 4);
-        off = (quarter >> 1) * S::ROWS_PER_LOAD * ROW_BYTES + (quarter & 1) * 32;
-    }
-    *reinterpret_cast<u32x4 *>(lds_tile + wr_base + off) = u32x4{d[0], d[1], d[2], d[3]};
-    *reinterpret_cast<u32x4 *>(lds_tile + wr_base + off + 16) = u32x4{d[4], d[5], d[6], d[7]};
-}
-
 template <int FMT_A, int FMT_W, bool CONV>
 __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
-    using SA = Staging<CA::BITS>;
-    using SW = Staging<CW::BITS>;
+    constexpr int NA = CA::BITS / 4, NW = CW::BITS / 4;            // 128-bit loads per thread per K step
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    char *const ldsA = lds, *const ldsW = lds + 2 * STAGE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int kg = lane >> 5;                                        // k-group of the lane
 
     // ---- tile assignment: consecutive workgroup ids go to different XCDs (8 of them); give
     // each XCD a compact 4 x 8 patch of the 16 x 16-tile region that is in flight, so that the
@@ -181,8 +170,7 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
     int tile_m, tile_n;
     {
         const int b = blockIdx.x;
-        const int per_region = 256;
-        const int region = b / per_region, r = b % per_region;
+        const int region = b >> 8, r = b & 255;
         const int xcd = r & 7, i = r >> 3;                         // i: 0..31 inside the XCD
         const int regions_n = (tiles_n + 15) / 16;
         const int rm = region / regions_n, rn = region % regions_n;
@@ -197,189 +185,145 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
     const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
 
-    // ---- per-thread load descriptors
+    // ---- A: the lane's own row, its k-group's half of the K step
     const int a_row_bytes = (int)(g.K * CA::BITS / 8), w_row_bytes = (int)(g.K * CW::BITS / 8);
     const int pix_bytes = CONV ? g.Cin * CA::BITS / 8 : 0;
-    u32 offA[SA::NLOAD];
-    int hi0[SA::NLOAD], wi0[SA::NLOAD];
-    bool okA[SA::NLOAD];
-#pragma unroll
-    for (int j = 0; j < SA::NLOAD; ++j) {
-        const int64_t m = m0 + tid / SA::TPR + j * SA::ROWS_PER_LOAD;
-        okA[j] = m < g.M;
-        const int seg = (tid % SA::TPR) * 16;
-        if (CONV) {
-            const int64_t mm = okA[j] ? m : 0;
-            const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
-            const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
-            const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
-            hi0[j] = ho * g.stride - g.pad;
-            wi0[j] = wo * g.stride - g.pad;
-            offA[j] = (u32)((((int64_t)b * g.H + hi0[j]) * g.Wd + wi0[j]) * pix_bytes + seg);
-        } else {
-            hi0[j] = wi0[j] = 0;
-            offA[j] = okA[j] ? (u32)(m * a_row_bytes + seg) : kOob;
-        }
+    const int64_t m = m0 + wave * 32 + (lane & 31);
+    const bool okA = m < g.M;
+    u32 offA;
+    int hi0 = 0, wi0 = 0;
+    if (CONV) {
+        const int64_t mm = okA ? m : 0;
+        const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
+        const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
+        const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+        hi0 = ho * g.stride - g.pad;
+        wi0 = wo * g.stride - g.pad;
+        offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kg * 16 * NA);
+    } else {
+        offA = okA ? (u32)(m * a_row_bytes + kg * 16 * NA) : kOob;   // rows past M stay out of range as k advances
     }
-    u32 offW[SW::NLOAD];
-#pragma unroll
-    for (int j = 0; j < SW::NLOAD; ++j) {
-        const int64_t n = n0 + tid / SW::TPR + j * SW::ROWS_PER_LOAD;
-        offW[j] = n < g.N ? (u32)(n * w_row_bytes + (tid % SW::TPR) * 16) : kOob;
-    }
+    // ---- W staging: thread t decodes row t / 2, codes 32 (t % 2) .. + 31 of the K step
+    const int64_t nrow = n0 + (tid >> 1);
+    const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + (tid & 1) * 16 * NW) : kOob;
+    const u32 wrW = (u32)(tid >> 1) * ROW_BYTES + (u32)(tid & 1) * 64;          // chunk 4 (t % 2) + q
+    const u32 rdW = (u32)(lane & 31) * ROW_BYTES + (u32)kg * 64;                 // chunk 4 g + kk, block j adds 32 rows
 
-    auto load_tile = [&](int64_t kt, u32x4 *rawA, u32x4 *rawW) {
+    // Tiles at or past ktiles (the prefetch of the last steps, and the padding step when the
+    // number of K steps is odd) are fetched from an out-of-range offset: they read zeros.
+    const int64_t ktiles = g.K / TK;
+    auto load_A = [&](int64_t kt, u32x4 *raw) {
         const int64_t k0 = kt * TK;
+        u32 off;
         if (CONV) {
             const int tap = (int)(k0 / g.Cin), c0 = (int)(k0 - (int64_t)tap * g.Cin);    // uniform
             const int fr = tap / g.kw, fs = tap - fr * g.kw;
-            const int tap_off = (fr * g.Wd + fs) * pix_bytes + c0 * CA::BITS / 8;
-#pragma unroll
-            for (int j = 0; j < SA::NLOAD; ++j) {
-                const bool in = okA[j] && (unsigned)(hi0[j] + fr) < (unsigned)g.H && (unsigned)(wi0[j] + fs) < (unsigned)g.Wd;
-                const u32 off = in ? offA[j] + (u32)tap_off : kOob;            // out of range reads 0 = code 0
-                rawA[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off, 0, 0);
-            }
+            const bool in = okA && (unsigned)(hi0 + fr) < (unsigned)g.H && (unsigned)(wi0 + fs) < (unsigned)g.Wd;
+            off = (in && kt < ktiles) ? offA + (u32)((fr * g.Wd + fs) * pix_bytes + c0 * CA::BITS / 8) : kOob;   // padding reads code 0
         } else {
-            // rows past M start at kOob and stay out of range while k advances
-            const u32 koff = (u32)(k0 * CA::BITS / 8);
-#pragma unroll
-            for (int j = 0; j < SA::NLOAD; ++j) rawA[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, offA[j] + koff, 0, 0);
+            off = kt < ktiles ? offA + (u32)(k0 * CA::BITS / 8) : kOob;
         }
-        const u32 koffw = (u32)(k0 * CW::BITS / 8);
 #pragma unroll
-        for (int j = 0; j < SW::NLOAD; ++j) rawW[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, offW[j] + koffw, 0, 0);
+        for (int p = 0; p < NA; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
+    };
+    auto load_W = [&](int64_t kt, u32x4 *raw) {
+        const u32 off = kt < ktiles ? offW + (u32)(kt * TK * CW::BITS / 8) : kOob;
+#pragma unroll
+        for (int p = 0; p < NW; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + p * 16, 0, 0);
+    };
+    auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
+        u32 d[4];
+        decode_eight<FMT_A>(raw, q, d);
+        return __builtin_bit_cast(f16x8, u32x4{d[0], d[1], d[2], d[3]});
+    };
+    auto stage_W = [&](const u32x4 *raw, int q, char *tile) {
+        u32 d[4];
+        decode_eight<FMT_W>(raw, q, d);
+        *reinterpret_cast<u32x4 *>(tile + wrW + q * 16) = u32x4{d[0], d[1], d[2], d[3]};
+    };
+    auto read_W = [&](const char *tile, int kk, int j) -> f16x8 {
+        return *reinterpret_cast<const f16x8 *>(tile + rdW + kk * 16 + j * 32 * ROW_BYTES);
     };
 
-    // ---- LDS addresses
-    const u32 wrA = (u32)(tid / SA::TPR) * ROW_BYTES + (u32)(tid % SA::TPR) * (128 / SA::TPR);
-    const u32 wrW = (u32)(tid / SW::TPR) * ROW_BYTES + (u32)(tid % SW::TPR) * (128 / SW::TPR);
-    // fragment reads: row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5)
-    const u32 rdA = (u32)(wm * 128 + (lane & 31)) * ROW_BYTES + (u32)(lane >> 5) * 16;
-    const u32 rdW = (u32)(wn * 128 + (lane & 31)) * ROW_BYTES + (u32)(lane >> 5) * 16;
+    f32x16 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
 
-    f32x16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    u32x4 rawA[2][NA], rawW[2][NW];
+    f16x8 fw[8], fa;
 
-    const int64_t ktiles = g.K / TK;
-    u32x4 rawA[2][SA::NLOAD], rawW[2][SW::NLOAD];
-
-    // ---- prologue: tile 0 decoded into stage 0, tile 1 in flight, fragments of k block 0 in registers
-    load_tile(0, rawA[0], rawW[0]);
-    if (ktiles > 1) load_tile(1, rawA[1], rawW[1]);
+    // ---- prologue: W tile 0 decoded into stage 0, A/W tile 1 in flight, first fragments in registers
+    load_A(0, rawA[0]);
+    load_W(0, rawW[0]);
+    load_A(1, rawA[1]);
+    load_W(1, rawW[1]);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        decode_quarter<FMT_A>(rawA[0], q, ldsA, wrA);
-        decode_quarter<FMT_W>(rawW[0], q, ldsW, wrW);
-    }
+    for (int q = 0; q < 4; ++q) stage_W(rawW[0], q, lds);
+    fa = decode_A(rawA[0], 0);
     __syncthreads();
-
-    f16x8 fa[2][4], fw[2][4];
-    auto read_frags = [&](const char *tileA, const char *tileW, int kk, int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const f16x8 *>(tileA + rdA + kk * 32 + i * 32 * ROW_BYTES);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) fw[buf][j] = *reinterpret_cast<const f16x8 *>(tileW + rdW + kk * 32 + j * 32 * ROW_BYTES);
-    };
-    read_frags(ldsA, ldsW, 0, 0);
+    for (int j = 0; j < 8; ++j) fw[j] = read_W(lds, 0, j);
 
-    // One K step over LDS stage s.  Four k blocks of 16 MFMAs each; the fragments of a block are
-    // read one block ahead.  The next tile is decoded into the other stage during blocks 0..2,
-    // the workgroup barrier sits before block 3, and the first fragments of the next tile are
-    // requested right after it, so that their LDS latency hides behind the MFMAs of block 3.
-    //   MODE 2: decode the next tile and load the one after;  1: decode only;  0: last tile.
-    auto step = [&](int64_t kt, auto stage_tag, auto mode_tag) {
+    // One K step over LDS stage s: four k blocks of eight MFMAs.  As soon as an MFMA has issued,
+    // its W fragment register is refilled with the fragment of the next k block.  The next W tile
+    // is decoded into the other stage during blocks 0..2; the workgroup barrier sits before
+    // block 3 and the first fragments of the next tile are requested right after it, so their
+    // LDS latency hides behind the MFMAs of block 3.  The A fragment of block kk + 1 is decoded
+    // during block kk; the A codes of tile kt + 2 are fetched once tile kt's have been consumed.
+    // Every step is the same straight-line code (no tail variants: the accumulators stay in
+    // place), so the last steps decode and prefetch tiles of zeros that nobody reads.
+    auto step = [&](int64_t kt, auto stage_tag) {
         constexpr int s = decltype(stage_tag)::value;
-        constexpr int MODE = decltype(mode_tag)::value;
-        const char *curA = ldsA + s * STAGE_BYTES, *curW = ldsW + s * STAGE_BYTES;
-        char *nxtA = ldsA + (s ^ 1) * STAGE_BYTES, *nxtW = ldsW + (s ^ 1) * STAGE_BYTES;
-        if (MODE == 2) load_tile(kt + 2, rawA[s], rawW[s]);
+        const char *cur = lds + s * STAGE_BYTES;
+        char *nxt = lds + (s ^ 1) * STAGE_BYTES;
+        load_W(kt + 2, rawW[s]);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            const int cb = kk & 1, nb = cb ^ 1;
-            if (kk == 3 && MODE >= 1) {
-                __syncthreads();
-                read_frags(nxtA, nxtW, 0, nb);
-            } else if (kk < 3) {
-                read_frags(curA, curW, kk + 1, nb);
+            if (kk == 3) __syncthreads();
+            const f16x8 fa_cur = fa;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa_cur, fw[j], acc[j], 0, 0, 0);
+                fw[j] = kk < 3 ? read_W(cur, kk + 1, j) : read_W(nxt, 0, j);
             }
+            fa = kk < 3 ? decode_A(rawA[s], kk + 1) : decode_A(rawA[s ^ 1], 0);
+            if (kk == 0) { stage_W(rawW[s ^ 1], 0, nxt); stage_W(rawW[s ^ 1], 1, nxt); }
+            if (kk == 1) stage_W(rawW[s ^ 1], 2, nxt);
+            if (kk == 2) stage_W(rawW[s ^ 1], 3, nxt);
+            if (kk == 2) load_A(kt + 2, rawA[s]);                   // tile kt's codes are fully decoded by now
+            // Issue order inside the block: MFMA, the fragment refill behind it, a share of the
+            // decode arithmetic; the LDS stores of the decoded W chunk come last.
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[cb][i], fw[cb][j], acc[i][j], 0, 0, 0);
-            if (MODE >= 1 && kk < 3) {
-                // decode work of the next tile, spread over blocks 0..2 in three near-equal parts
-                if (kk == 0) {
-                    decode_quarter<FMT_A>(rawA[s ^ 1], 0, nxtA, wrA);
-                    decode_quarter<FMT_W>(rawW[s ^ 1], 0, nxtW, wrW);
-                    decode_quarter<FMT_W>(rawW[s ^ 1], 1, nxtW, wrW);
-                } else if (kk == 1) {
-                    decode_quarter<FMT_A>(rawA[s ^ 1], 1, nxtA, wrA);
-                    decode_quarter<FMT_A>(rawA[s ^ 1], 2, nxtA, wrA);
-                } else {
-                    decode_quarter<FMT_A>(rawA[s ^ 1], 3, nxtA, wrA);
-                    decode_quarter<FMT_W>(rawW[s ^ 1], 2, nxtW, wrW);
-                    decode_quarter<FMT_W>(rawW[s ^ 1], 3, nxtW, wrW);
-                }
-            }
-            // Order inside the block: the eight fragment reads first, then MFMAs with the decode
-            // arithmetic between them, the tile writes towards the end.
-            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);                     // DS read x 8
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 8; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
-                if (MODE >= 1 && kk < 3) __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);   // VALU
-                if (MODE >= 1 && kk < 3 && r >= 3 && (r & 1)) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                 // DS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);                 // VALU
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    using T0 = std::integral_constant<int, 0>;
-    using T1 = std::integral_constant<int, 1>;
-    using M0 = std::integral_constant<int, 0>;
-    using M1 = std::integral_constant<int, 1>;
-    using M2 = std::integral_constant<int, 2>;
-
-    // tiles 0 .. ktiles-3 in MODE 2, tile ktiles-2 in MODE 1, tile ktiles-1 in MODE 0
-    int64_t kt = 0;
-    for (; kt + 3 < ktiles; kt += 2) {
-        step(kt, T0{}, M2{});
-        step(kt + 1, T1{}, M2{});
-    }
-    if (kt + 3 == ktiles) {
-        step(kt, T0{}, M2{});
-        step(kt + 1, T1{}, M1{});
-        step(kt + 2, T0{}, M0{});
-    } else if (kt + 2 == ktiles) {
-        step(kt, T0{}, M1{});
-        step(kt + 1, T1{}, M0{});
-    } else {
-        step(kt, T0{}, M0{});
+    // an odd number of K steps is padded with one step of zeros
+    for (int64_t kt = 0; kt < ktiles; kt += 2) {
+        step(kt, std::integral_constant<int, 0>{});
+        step(kt + 1, std::integral_constant<int, 1>{});
     }
 
     // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU).  Accumulator v of a lane is row
     // 8 (v / 4) + 4 (lane / 32) + v % 4 and column lane % 32 of its 32 x 32 block.
     const float alpha = (*g.a_scale) * (*g.w_scale);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int64_t n = n0 + wn * 128 + j * 32 + (lane & 31);
+    for (int j = 0; j < 8; ++j) {
+        const int64_t n = n0 + j * 32 + (lane & 31);
         const bool n_ok = n < g.N;
         const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                float c = acc[i][j][v] * alpha + b;
-                if (g.relu) c = fmaxf(c, 0.0f);
-                if (n_ok && m < g.M) __builtin_nontemporal_store(c, g.C + m * g.ldc + n);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int64_t mr = m0 + wave * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+            float c = acc[j][v] * alpha + b;
+            if (g.relu) c = fmaxf(c, 0.0f);
+            if (n_ok && mr < g.M) __builtin_nontemporal_store(c, g.C + mr * g.ldc + n);
         }
     }
 }
