@@ -39,7 +39,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int THREADS = 512;
 constexpr int ROW_BYTES = TK * 2 + 16;            // one LDS row of W: 64 halves = 8 chunks of 16 B, plus 16 B of padding
 constexpr int STAGE_BYTES = TN * ROW_BYTES;       // 36 KiB per stage
 constexpr int LDS_BYTES = 2 * STAGE_BYTES;
@@ -76,14 +75,32 @@ template <int FMT>
 __device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
 {
     using C = Codec<FMT>;
-    if (C::BITS == 8) {
+    if constexpr (C::BITS == 8) {
         const u32x4 r = raw[q >> 1];
-        C::word((q & 1) ? r.z : r.x, d);
-        C::word((q & 1) ? r.w : r.y, d + 2);
+        C::two_words((q & 1) ? r.z : r.x, (q & 1) ? r.w : r.y, d);
     } else {
         const u32x4 r = raw[0];
         C::word(q == 0 ? r.x : q == 1 ? r.y : q == 2 ? r.z : r.w, d);
     }
+}
+
+// Four independent copies of the arithmetic decoder, written stage by stage so that no
+// instruction consumes the result of the one just before it (a packed-fp16 result needs a
+// wait state before it can be read).
+__device__ __forceinline__ void recip_decode_4pairs(const u32 *h, u32 k2, u32 *v)
+{
+    const f16x2 m1023 = {(_Float16)-1023.0f, (_Float16)-1023.0f}, two = {(_Float16)2.0f, (_Float16)2.0f},
+                mone = {(_Float16)-1.0f, (_Float16)-1.0f};
+    f16x2 nf[4], L[4];
+    u16x2 rb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) nf[i] = __builtin_bit_cast(f16x2, h[i]) + m1023;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rb[i] = __builtin_bit_cast(u16x2, k2) - __builtin_bit_cast(u16x2, nf[i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) L[i] = __builtin_bit_cast(f16x2, rb[i]) * two + mone;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __builtin_bit_cast(u32, __builtin_elementwise_min(rb[i], __builtin_bit_cast(u16x2, L[i])));
 }
 
 template <> struct Codec<F8S> {
@@ -98,6 +115,21 @@ template <> struct Codec<F8S> {
         d[0] = (v0 & 0x7fff7fffu) | ((w << 8) & 0x80008000u);             // sign bit of bytes 0, 2
         d[1] = (v1 & 0x7fff7fffu) | (w & 0x80008000u);                    // sign bit of bytes 1, 3
     }
+    // 8 codes (two words) -> four registers, the four pairs decoded side by side
+    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
+    {
+        const u32 m0 = ~w0 & 0x7f7f7f7fu, m1 = ~w1 & 0x7f7f7f7fu;
+        u32 h[4], v[4];
+        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
+        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
+        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
+        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
+        recip_decode_4pairs(h, 0x90009000u, v);
+        d[0] = (v[0] & 0x7fff7fffu) | ((w0 << 8) & 0x80008000u);
+        d[1] = (v[1] & 0x7fff7fffu) | (w0 & 0x80008000u);
+        d[2] = (v[2] & 0x7fff7fffu) | ((w1 << 8) & 0x80008000u);
+        d[3] = (v[3] & 0x7fff7fffu) | (w1 & 0x80008000u);
+    }
 };
 
 template <> struct Codec<F8U> {
@@ -109,6 +141,16 @@ template <> struct Codec<F8U> {
         const u32 h1 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04030401u);
         d[0] = recip_decode_pair(h0, 0x94009400u);
         d[1] = recip_decode_pair(h1, 0x94009400u);
+    }
+    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
+    {
+        const u32 m0 = ~w0, m1 = ~w1;
+        u32 h[4];
+        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
+        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
+        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
+        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
+        recip_decode_4pairs(h, 0x94009400u, d);
     }
 };
 
@@ -151,14 +193,17 @@ template <> struct Codec<F4U> {
 };
 
 // ---------------------------------------------------------------------------
-// Kernel
+// Kernel.  RB = 32-row blocks of A per wave: 1 -> eight waves (two per SIMD), 2 -> four waves.
 // ---------------------------------------------------------------------------
-template <int FMT_A, int FMT_W, bool CONV>
-__global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
+template <int FMT_A, int FMT_W, bool CONV, int RB>
+__global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
-    constexpr int NA = CA::BITS / 4, NW = CW::BITS / 4;            // 128-bit loads per thread per K step
+    constexpr int NTHREADS = 512 / RB;
+    constexpr int NA = CA::BITS / 4;                               // 128-bit loads per lane, row block and K step
+    constexpr int WPT = RB;                                        // W k-halves (32 codes) per thread and K step
+    constexpr int NW = CW::BITS / 4;                               // 128-bit loads per k-half
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -185,74 +230,96 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
     const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
 
-    // ---- A: the lane's own row, its k-group's half of the K step
+    // ---- A: the lane's own rows (one per row block), its k-group's half of the K step
     const int a_row_bytes = (int)(g.K * CA::BITS / 8), w_row_bytes = (int)(g.K * CW::BITS / 8);
     const int pix_bytes = CONV ? g.Cin * CA::BITS / 8 : 0;
-    const int64_t m = m0 + wave * 32 + (lane & 31);
-    const bool okA = m < g.M;
-    u32 offA;
-    int hi0 = 0, wi0 = 0;
-    if (CONV) {
-        const int64_t mm = okA ? m : 0;
-        const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
-        const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
-        const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
-        hi0 = ho * g.stride - g.pad;
-        wi0 = wo * g.stride - g.pad;
-        offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kg * 16 * NA);
-    } else {
-        offA = okA ? (u32)(m * a_row_bytes + kg * 16 * NA) : kOob;   // rows past M stay out of range as k advances
+    u32 offA[RB];
+    int hi0[RB], wi0[RB];
+    bool okA[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        const int64_t m = m0 + (wave * RB + i) * 32 + (lane & 31);
+        okA[i] = m < g.M;
+        hi0[i] = wi0[i] = 0;
+        if (CONV) {
+            const int64_t mm = okA[i] ? m : 0;
+            const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
+            const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
+            const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+            hi0[i] = ho * g.stride - g.pad;
+            wi0[i] = wo * g.stride - g.pad;
+            offA[i] = (u32)((((int64_t)b * g.H + hi0[i]) * g.Wd + wi0[i]) * pix_bytes + kg * 16 * NA);
+        } else {
+            offA[i] = okA[i] ? (u32)(m * a_row_bytes + kg * 16 * NA) : kOob;   // rows past M stay out of range as k advances
+        }
     }
-    // ---- W staging: thread t decodes row t / 2, codes 32 (t % 2) .. + 31 of the K step
-    const int64_t nrow = n0 + (tid >> 1);
-    const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + (tid & 1) * 16 * NW) : kOob;
-    const u32 wrW = (u32)(tid >> 1) * ROW_BYTES + (u32)(tid & 1) * 64;          // chunk 4 (t % 2) + q
+    // ---- W staging.  Eight waves: thread t decodes row t / 2, k-half t % 2.  Four waves: row t, both k-halves.
+    const int wrow = RB == 1 ? (tid >> 1) : tid;
+    const int wh0 = RB == 1 ? (tid & 1) : 0;
+    const int64_t nrow = n0 + wrow;
+    const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + wh0 * 16 * NW) : kOob;
+    const u32 wrW = (u32)wrow * ROW_BYTES + (u32)wh0 * 64;                       // chunk 4 h + q
     const u32 rdW = (u32)(lane & 31) * ROW_BYTES + (u32)kg * 64;                 // chunk 4 g + kk, block j adds 32 rows
 
     // Tiles at or past ktiles (the prefetch of the last steps, and the padding step when the
     // number of K steps is odd) are fetched from an out-of-range offset: they read zeros.
     const int64_t ktiles = g.K / TK;
-    auto load_A = [&](int64_t kt, u32x4 *raw) {
+    auto load_A = [&](int64_t kt, u32x4 (*raw)[NA]) {
         const int64_t k0 = kt * TK;
-        u32 off;
+        int tap_off = 0, fr = 0, fs = 0;
         if (CONV) {
             const int tap = (int)(k0 / g.Cin), c0 = (int)(k0 - (int64_t)tap * g.Cin);    // uniform
-            const int fr = tap / g.kw, fs = tap - fr * g.kw;
-            const bool in = okA && (unsigned)(hi0 + fr) < (unsigned)g.H && (unsigned)(wi0 + fs) < (unsigned)g.Wd;
-            off = (in && kt < ktiles) ? offA + (u32)((fr * g.Wd + fs) * pix_bytes + c0 * CA::BITS / 8) : kOob;   // padding reads code 0
-        } else {
-            off = kt < ktiles ? offA + (u32)(k0 * CA::BITS / 8) : kOob;
+            fr = tap / g.kw;
+            fs = tap - fr * g.kw;
+            tap_off = (fr * g.Wd + fs) * pix_bytes + c0 * CA::BITS / 8;
         }
 #pragma unroll
-        for (int p = 0; p < NA; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
+        for (int i = 0; i < RB; ++i) {
+            u32 off;
+            if (CONV) {
+                const bool in = okA[i] && (unsigned)(hi0[i] + fr) < (unsigned)g.H && (unsigned)(wi0[i] + fs) < (unsigned)g.Wd;
+                off = (in && kt < ktiles) ? offA[i] + (u32)tap_off : kOob;            // padding reads code 0
+            } else {
+                off = kt < ktiles ? offA[i] + (u32)(k0 * CA::BITS / 8) : kOob;
+            }
+#pragma unroll
+            for (int p = 0; p < NA; ++p) raw[i][p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
+        }
     };
-    auto load_W = [&](int64_t kt, u32x4 *raw) {
+    auto load_W = [&](int64_t kt, u32x4 (*raw)[NW]) {
         const u32 off = kt < ktiles ? offW + (u32)(kt * TK * CW::BITS / 8) : kOob;
 #pragma unroll
-        for (int p = 0; p < NW; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + p * 16, 0, 0);
+        for (int h = 0; h < WPT; ++h)
+#pragma unroll
+            for (int p = 0; p < NW; ++p) raw[h][p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + (h * NW + p) * 16, 0, 0);
     };
     auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
         u32 d[4];
         decode_eight<FMT_A>(raw, q, d);
         return __builtin_bit_cast(f16x8, u32x4{d[0], d[1], d[2], d[3]});
     };
-    auto stage_W = [&](const u32x4 *raw, int q, char *tile) {
-        u32 d[4];
-        decode_eight<FMT_W>(raw, q, d);
-        *reinterpret_cast<u32x4 *>(tile + wrW + q * 16) = u32x4{d[0], d[1], d[2], d[3]};
+    auto stage_W = [&](u32x4 (*raw)[NW], int q, char *tile) {
+#pragma unroll
+        for (int h = 0; h < WPT; ++h) {
+            u32 d[4];
+            decode_eight<FMT_W>(raw[h], q, d);
+            *reinterpret_cast<u32x4 *>(tile + wrW + h * 64 + q * 16) = u32x4{d[0], d[1], d[2], d[3]};
+        }
     };
     auto read_W = [&](const char *tile, int kk, int j) -> f16x8 {
         return *reinterpret_cast<const f16x8 *>(tile + rdW + kk * 16 + j * 32 * ROW_BYTES);
     };
 
-    f32x16 acc[8];
+    f32x16 acc[RB][8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int i = 0; i < RB; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    u32x4 rawA[2][NA], rawW[2][NW];
-    f16x8 fw[8], fa;
+    u32x4 rawA[2][RB][NA], rawW[2][WPT][NW];
+    f16x8 fw[8], fa[RB];
 
     // ---- prologue: W tile 0 decoded into stage 0, A/W tile 1 in flight, first fragments in registers
     load_A(0, rawA[0]);
@@ -261,19 +328,20 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
     load_W(1, rawW[1]);
 #pragma unroll
     for (int q = 0; q < 4; ++q) stage_W(rawW[0], q, lds);
-    fa = decode_A(rawA[0], 0);
+#pragma unroll
+    for (int i = 0; i < RB; ++i) fa[i] = decode_A(rawA[0][i], 0);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 8; ++j) fw[j] = read_W(lds, 0, j);
 
-    // One K step over LDS stage s: four k blocks of eight MFMAs.  As soon as an MFMA has issued,
-    // its W fragment register is refilled with the fragment of the next k block.  The next W tile
-    // is decoded into the other stage during blocks 0..2; the workgroup barrier sits before
-    // block 3 and the first fragments of the next tile are requested right after it, so their
-    // LDS latency hides behind the MFMAs of block 3.  The A fragment of block kk + 1 is decoded
-    // during block kk; the A codes of tile kt + 2 are fetched once tile kt's have been consumed.
-    // Every step is the same straight-line code (no tail variants: the accumulators stay in
-    // place), so the last steps decode and prefetch tiles of zeros that nobody reads.
+    // One K step over LDS stage s: four k blocks of 8 RB MFMAs.  As soon as the MFMAs that use a
+    // W fragment have issued, its register is refilled with the fragment of the next k block.
+    // The next W tile is decoded into the other stage during blocks 0..2; the workgroup barrier
+    // sits before block 3 and the first fragments of the next tile are requested right after it,
+    // so their LDS latency hides behind the MFMAs of block 3.  The A fragments of block kk + 1
+    // are decoded during block kk; the A codes of tile kt + 2 are fetched once tile kt's have
+    // been consumed.  Every step is the same straight-line code (no tail variants: the
+    // accumulators stay in place), so the last steps decode and prefetch tiles of zeros.
     auto step = [&](int64_t kt, auto stage_tag) {
         constexpr int s = decltype(stage_tag)::value;
         const char *cur = lds + s * STAGE_BYTES;
@@ -282,24 +350,29 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             if (kk == 3) __syncthreads();
-            const f16x8 fa_cur = fa;
+            f16x8 fa_cur[RB];
+#pragma unroll
+            for (int i = 0; i < RB; ++i) fa_cur[i] = fa[i];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa_cur, fw[j], acc[j], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < RB; ++i)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa_cur[i], fw[j], acc[i][j], 0, 0, 0);
                 fw[j] = kk < 3 ? read_W(cur, kk + 1, j) : read_W(nxt, 0, j);
             }
-            fa = kk < 3 ? decode_A(rawA[s], kk + 1) : decode_A(rawA[s ^ 1], 0);
+#pragma unroll
+            for (int i = 0; i < RB; ++i) fa[i] = kk < 3 ? decode_A(rawA[s][i], kk + 1) : decode_A(rawA[s ^ 1][i], 0);
             if (kk == 0) { stage_W(rawW[s ^ 1], 0, nxt); stage_W(rawW[s ^ 1], 1, nxt); }
             if (kk == 1) stage_W(rawW[s ^ 1], 2, nxt);
             if (kk == 2) stage_W(rawW[s ^ 1], 3, nxt);
             if (kk == 2) load_A(kt + 2, rawA[s]);                   // tile kt's codes are fully decoded by now
-            // Issue order inside the block: MFMA, the fragment refill behind it, a share of the
-            // decode arithmetic; the LDS stores of the decoded W chunk come last.
+            // Issue order inside the block: RB MFMAs, the fragment refill behind them, a share of
+            // the decode arithmetic.
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x008, RB, 0);                // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                 // DS read
-                __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);                 // VALU
+                __builtin_amdgcn_sched_group_barrier(0x002, 6 * RB, 0);            // VALU
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -319,27 +392,32 @@ __global__ __launch_bounds__(THREADS) void gemm_fast_kernel(const GemmArgs g, co
         const bool n_ok = n < g.N;
         const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t mr = m0 + wave * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-            float c = acc[j][v] * alpha + b;
-            if (g.relu) c = fmaxf(c, 0.0f);
-            if (n_ok && mr < g.M) __builtin_nontemporal_store(c, g.C + mr * g.ldc + n);
+        for (int i = 0; i < RB; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t mr = m0 + (wave * RB + i) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                float c = acc[i][j][v] * alpha + b;
+                if (g.relu) c = fmaxf(c, 0.0f);
+                if (n_ok && mr < g.M) __builtin_nontemporal_store(c, g.C + mr * g.ldc + n);
+            }
         }
     }
 }
+
+constexpr int kRowBlocks = 1;   // row blocks per wave of the instantiated kernels
 
 template <int FA, int FW>
 static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 {
     const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
     const int regions = ((tiles_m + 15) / 16) * ((tiles_n + 15) / 16);
-    const dim3 grid(regions * 256), block(THREADS);
+    const dim3 grid(regions * 256), block(512 / kRowBlocks);
     if (conv) {
-        auto k = gemm_fast_kernel<FA, FW, true>;
+        auto k = gemm_fast_kernel<FA, FW, true, kRowBlocks>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         hipLaunchKernelGGL(k, grid, block, LDS_BYTES, st, g, tiles_m, tiles_n);
     } else {
-        auto k = gemm_fast_kernel<FA, FW, false>;
+        auto k = gemm_fast_kernel<FA, FW, false, kRowBlocks>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         hipLaunchKernelGGL(k, grid, block, LDS_BYTES, st, g, tiles_m, tiles_n);
     }

@@ -14,6 +14,14 @@ namespace dybit {
 __device__ int g_async_error = 0;
 
 constexpr int kThreads = 256;
+// Tuning knobs of the quantize pass (swept on the device: eight 128-bit loads in flight per lane and
+// a grid that is not capped below about 128 workgroups per compute unit run closest to the HBM rate).
+#ifndef DYBIT_QUANT_UNROLL
+#define DYBIT_QUANT_UNROLL 8
+#endif
+#ifndef DYBIT_QUANT_BLOCKS_PER_CU
+#define DYBIT_QUANT_BLOCKS_PER_CU 128
+#endif
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------
@@ -46,9 +54,16 @@ __global__ __launch_bounds__(kThreads) void absmax_kernel(const float *__restric
         mx = fmaxf(mx, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
     }
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) mx = fmaxf(mx, fabsf(x[(n4 << 2) + threadIdx.x]));
+    // one atomic per workgroup: atomics on a single address serialise in L2 (about 10 ns each)
+    __shared__ float wave_max[kThreads / 64];
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-    if ((threadIdx.x & 63) == 0 && mx > 0.0f)
-        atomicMax(reinterpret_cast<unsigned int *>(scale_out), __float_as_uint(mx));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) mx = fmaxf(mx, wave_max[w]);
+        if (mx > 0.0f) atomicMax(reinterpret_cast<unsigned int *>(scale_out), __float_as_uint(mx));
+    }
 }
 
 __global__ void absmax_finish_kernel(float *scale_out, float inv_vmax)
@@ -343,10 +358,10 @@ static int grid_for(size_t work_items, int per_block, int max_blocks)
 template <int BITS, bool SIGNED>
 static void launch_quantize(const float *x, size_t n, const float *scale, uint8_t *out, hipStream_t st)
 {
-    constexpr int UNROLL = 4;
+    constexpr int UNROLL = DYBIT_QUANT_UNROLL;
     if (BITS == 6) {
         const size_t n16 = n / 16;
-        if (n16) hipLaunchKernelGGL((quantize6_kernel<SIGNED>), dim3(grid_for(n16, kThreads, 256 * 16)), dim3(kThreads), 0, st,
+        if (n16) hipLaunchKernelGGL((quantize6_kernel<SIGNED>), dim3(grid_for(n16, kThreads, 256 * 128)), dim3(kThreads), 0, st,
                                     x, n16, scale, out);
         const size_t first = n16 * 16;
         if (first < n) {
@@ -356,7 +371,7 @@ static void launch_quantize(const float *x, size_t n, const float *scale, uint8_
     } else {
         const size_t n4 = n / 4;
         if (n4) hipLaunchKernelGGL((quantize_kernel<BITS == 6 ? 8 : BITS, SIGNED, UNROLL>),
-                                   dim3(grid_for(n4, kThreads * UNROLL, 256 * 16)), dim3(kThreads), 0, st, x, n4, scale, out);
+                                   dim3(grid_for(n4, kThreads * UNROLL, 256 * DYBIT_QUANT_BLOCKS_PER_CU)), dim3(kThreads), 0, st, x, n4, scale, out);
         if (n4 * 4 < n)
             hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3(1), dim3(1), 0, st, x, n4 * 4, n, scale, out);
     }
@@ -375,7 +390,7 @@ extern "C" dybit_status dybit_absmax_scale(const float *x, size_t n, dybit_fmt f
     if (!aligned16(x)) return DYBIT_ERR_ALIGNMENT;
     hipStream_t hs = (hipStream_t)stream;
     hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(1), 0, hs, scale_out);
-    if (n) hipLaunchKernelGGL(absmax_kernel, dim3(grid_for(n / 4 + 1, kThreads * 4, 256 * 8)), dim3(kThreads), 0, hs, x, n, scale_out);
+    if (n) hipLaunchKernelGGL(absmax_kernel, dim3(grid_for(n / 4 + 1, kThreads * 8, 256 * 4)), dim3(kThreads), 0, hs, x, n, scale_out);
     const int m = mag_bits(f.bits, f.is_signed);
     hipLaunchKernelGGL(absmax_finish_kernel, dim3(1), dim3(1), 0, hs, scale_out, 1.0f / (float)(1u << (m - 1)));
     return launch_status();
@@ -410,7 +425,7 @@ extern "C" dybit_status dybit_dequantize(const uint8_t *codes, size_t n, dybit_f
     if (!aligned16(codes) || !aligned16(y_out)) return DYBIT_ERR_ALIGNMENT;
     if (n == 0) return DYBIT_OK;
     hipStream_t hs = (hipStream_t)stream;
-    const int grid = grid_for(n / 8 + 1, kThreads, 256 * 16);
+    const int grid = grid_for(n / 8 + 1, kThreads, 256 * 128);
     switch (f.bits) {
         case 2: hipLaunchKernelGGL((dequantize_kernel<2>), dim3(grid), dim3(kThreads), 0, hs, codes, n, f.is_signed, scale, y_out); break;
         case 4: hipLaunchKernelGGL((dequantize_kernel<4>), dim3(grid), dim3(kThreads), 0, hs, codes, n, f.is_signed, scale, y_out); break;
