@@ -31,9 +31,11 @@ if ROOT not in sys.path:
 PEAK_FP16_MFMA_TFLOPS = 2500.0   # MI355X dense fp16/bf16 matrix peak
 PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E peak
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
-# scaled by the same counters on a plain copy kernel (see profiles/); None until measured.
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command
+# (profiles/gemm_cfg5a_hbm_traffic.md): FETCH_SIZE * 2 KiB + WRITE_SIZE * 1 KiB, the factors being
+# what the same counters read for a plain 1 GiB copy.  None where not measured.
 MEASURED_TRAFFIC = {"cfg5": None, "cfg2": None, "cfg1": None}
+MEASURED_TRAFFIC_QUANTIZE4 = None
 
 
 def parse():
@@ -155,6 +157,17 @@ def main():
                      "kernel_ms": round(gemm_ms, 4), "traffic": MEASURED_TRAFFIC[args.workload]},
     }
 
+    # ---------------- the matrix cores alone, on decoded values of this workload ------------
+    # (the sustained clock of an MFMA-bound kernel depends on the operand values)
+    vals = B.dybit_dequantize(qa[: 9 * 512 * 8 * a_fmt[0] // 8], 9 * 512 * 8, sa, *a_fmt)
+    ops16 = (vals / sa).to(torch.float16).contiguous()
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    wgs, iters = 256 * 2, 2000
+    fl = B.dybit_diag_mfma_f16(ops16, wgs, iters, sink)
+    mf_ms, _ = time_events(lambda: B.dybit_diag_mfma_f16(ops16, wgs, iters, sink), 5, 1, torch)
+    out["roofline"]["mfma_only_measured_TFLOPs"] = round(fl / (mf_ms * 1e-3) / 1e12, 1)
+    out["roofline"]["frac_of_mfma_only_measured"] = round(gemm_tflops / (fl / (mf_ms * 1e-3) / 1e12), 4)
+
     # ---------------- activation-side passes of the step, timed alone --------------------
     nA = A.numel()
     absmax_ms, _ = time_events(lambda: B.dybit_absmax_scale(A, *a_fmt, out=sa), 10, 2, torch)
@@ -190,7 +203,8 @@ def main():
         out["quantize"] = q
         out["roofline_quantize"] = {"bound": "hbm", "kernel": "dybit quantize_kernel<4,signed>",
                                     "achieved": q["4bit"]["GBps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                    "frac": q["4bit"]["frac_of_8TBps"], "traffic": None}
+                                    "frac": q["4bit"]["frac_of_8TBps"], "traffic": MEASURED_TRAFFIC_QUANTIZE4,
+                                    "frac_of_measured_copy": round(q["4bit"]["GBps"] / q["torch_copy_reference"]["GBps"], 4)}
         del x, y
 
     # ---------------- CPU baseline: the plain C oracle on a bounded sample -----------------

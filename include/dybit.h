@@ -119,6 +119,15 @@ dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t 
  * last call found an unusable scale and wrote nothing). */
 dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream);
 
+/* Measurement aid, not part of the method: runs only fp16 MFMA instructions (the instruction
+ * dybit_gemm uses) on operand values taken from `operands` and reports how many flops the launch
+ * performs, so that a caller can time it and obtain the matrix-core rate this device sustains.
+ * operands [device]: 9 * 512 * 8 halves (73,728 bytes), 16-byte aligned.  workgroups: grid size
+ * (512 threads each).  iters: loop count per wave.  sink [device]: 1 float.  flops_out [host, may
+ * be NULL]. */
+dybit_status dybit_diag_mfma_f16(const void *operands, int32_t workgroups, int32_t iters,
+                                 float *sink, double *flops_out, dybit_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,7 @@ def lib() -> C.CDLL:
         L.dybit_gemm.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, i64, vp]
         L.dybit_conv2d.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
+        L.dybit_diag_mfma_f16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
         _lib = L
     return _lib
 
@@ -161,3 +162,11 @@ def dybit_get_last_async_error(stream=None) -> int:
     flag = C.c_int32(0)
     _check(lib().dybit_get_last_async_error(C.byref(flag), _stream(stream)), "dybit_get_last_async_error")
     return int(flag.value)
+
+
+def dybit_diag_mfma_f16(operands: torch.Tensor, workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Launches the MFMA-only measurement kernel; returns the flops of the launch."""
+    flops = C.c_double(0.0)
+    _check(lib().dybit_diag_mfma_f16(_ptr(operands), workgroups, iters, _ptr(sink), C.byref(flops), _stream(stream)),
+           "dybit_diag_mfma_f16")
+    return float(flops.value)

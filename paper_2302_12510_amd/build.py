@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdybit.so")
-SOURCES = ["host.cpp", "quantize.hip", "gemm.hip", "gemm_fast.hip"]
+SOURCES = ["host.cpp", "quantize.hip", "gemm.hip", "gemm_fast.hip", "diag.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
