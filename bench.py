@@ -34,8 +34,10 @@ PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E peak
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command
 # (profiles/gemm_cfg5a_hbm_traffic.md): FETCH_SIZE * 2 KiB + WRITE_SIZE * 1 KiB, the factors being
 # what the same counters read for a plain 1 GiB copy.  None where not measured.
-MEASURED_TRAFFIC = {"cfg5": None, "cfg2": None, "cfg1": None}
-MEASURED_TRAFFIC_QUANTIZE4 = None
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (units of 2 KiB and 1 KiB on
+# this device, calibrated on a 1 GiB copy); the summaries are under profiles/.
+MEASURED_TRAFFIC = {"cfg5": 262302 * 2048 + 262144 * 1024, "cfg2": None, "cfg1": None}
+MEASURED_TRAFFIC_QUANTIZE4 = 524376 * 2048 + 131072 * 1024
 
 
 def parse():
@@ -151,7 +153,7 @@ def main():
         "vs_baseline": None, "dtype": "f16 MFMA inputs (exact), f32 accumulate", "data": "synthetic",
         "config": {"workload": name, "M": M, "N": N, "K": K, "a_fmt": list(a_fmt), "w_fmt": list(w_fmt),
                    "step": "absmax + quantize activations + gemm; weights pre-quantized"},
-        "roofline": {"bound": "mfma", "kernel": "dybit gemm_kernel", "achieved": round(gemm_tflops, 2),
+        "roofline": {"bound": "mfma", "kernel": "dybit::fast::gemm_fast_kernel" if args.workload == "cfg5" else "dybit::gemm_kernel", "achieved": round(gemm_tflops, 2),
                      "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / PEAK_FP16_MFMA_TFLOPS, 4),
                      "kernel_ms": round(gemm_ms, 4), "traffic": MEASURED_TRAFFIC[args.workload]},
