@@ -8,7 +8,18 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdybit.so")
-SOURCES = ["host.cpp", "quantize.hip", "gemm.hip", "gemm_fast.hip", "diag.hip"]
+# (source, object stem, extra flags): the tiled kernels are compiled once per weight format
+SOURCES = [
+    ("host.cpp", "host", []),
+    ("quantize.hip", "quantize", []),
+    ("gemm.hip", "gemm", []),
+    ("gemm_dispatch.cpp", "gemm_dispatch", []),
+    ("gemm_fast.hip", "gemm_fast_w4", ["-DDYBIT_FAST_W=0"]),
+    ("gemm_fast.hip", "gemm_fast_w8", ["-DDYBIT_FAST_W=2"]),
+    ("gemm_mid.hip", "gemm_mid_w4", ["-DDYBIT_MID_W=0"]),
+    ("gemm_mid.hip", "gemm_mid_w8", ["-DDYBIT_MID_W=2"]),
+    ("diag.hip", "diag", []),
+]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -20,9 +31,10 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(item) -> str:
+    src, stem, extra = item
+    obj = os.path.join(CSRC, stem + ".o")
+    cmd = [_hipcc(), *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     p = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in p.stderr.splitlines() if "not a recognized feature" not in l)
     if p.returncode:

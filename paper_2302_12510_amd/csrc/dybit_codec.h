@@ -1,0 +1,176 @@
+// Decoders from packed DyBit codes to fp16 pairs, entirely in the vector ALU (no table look-ups
+// in memory).  Shared by the tiled matrix-product kernels.
+//
+// Every DyBit value of the 4- and 8-bit formats is exact in fp16.  Both decoders emit each group
+// of eight consecutive k values in the order (k0,k2,k1,k3,k4,k6,k5,k7): that is the order their
+// packed arithmetic produces for free, and a contraction does not care about the order of k as
+// long as both operands agree.
+#ifndef DYBIT_CODEC_H
+#define DYBIT_CODEC_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dybit {
+namespace fast {
+
+typedef uint32_t u32;
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kOob = 0x80000000u;            // a buffer offset past every supported size: such loads return 0
+
+enum { F4S = 0, F4U = 1, F8S = 2, F8U = 3 };
+
+// ---------------------------------------------------------------------------
+// Codecs: packed codes -> fp16 pairs, entirely in the vector ALU.
+// ---------------------------------------------------------------------------
+// Arithmetic decoder for m magnitude bits (used for the 8-bit formats).  With n = 2^m - c:
+//   R = bitcast(K - bits(half(n)))      K = (15 + 15 + m-1) << 10
+// equals the DyBit value for codes with a leading one (see magnitude_value in dybit_device.h),
+// and for codes below that (n >= 2^(m-1)) it equals 1/2 + c/2^m, so the fraction c/2^(m-1) is
+// 2R - 1.  Because 2R - 1 >= R exactly when R >= 1, the value is min(R, 2R - 1) for every code.
+// half(n) comes from the usual trick: the bits 0x6400 | (2^m - 1 - c) are the half 1024 + 2^m-1-c,
+// and subtracting 1023 leaves n.  Both R and 2R-1 are non-negative, so the minimum is taken
+// on the bit patterns (no NaN canonicalisation needed).
+__device__ __forceinline__ u32 recip_decode_pair(u32 h, u32 k2)
+{
+    const f16x2 nf = __builtin_bit_cast(f16x2, h) + (f16x2){(_Float16)-1023.0f, (_Float16)-1023.0f};
+    const u16x2 rb = __builtin_bit_cast(u16x2, k2) - __builtin_bit_cast(u16x2, nf);
+    const f16x2 R = __builtin_bit_cast(f16x2, rb);
+    const f16x2 L = R * (f16x2){(_Float16)2.0f, (_Float16)2.0f} + (f16x2){(_Float16)-1.0f, (_Float16)-1.0f};
+    const u16x2 v = __builtin_elementwise_min(rb, __builtin_bit_cast(u16x2, L));
+    return __builtin_bit_cast(u32, v);
+}
+
+template <int FMT> struct Codec;
+
+// Codec<F>::word decodes one 32-bit word; Codec<F>::eight decodes the q-th group of eight codes of
+// a thread's 32 codes (held in BITS / 4 registers of 128 bits) into four registers of two halves.
+template <int FMT>
+__device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
+{
+    using C = Codec<FMT>;
+    if constexpr (C::BITS == 8) {
+        const u32x4 r = raw[q >> 1];
+        C::two_words((q & 1) ? r.z : r.x, (q & 1) ? r.w : r.y, d);
+    } else {
+        const u32x4 r = raw[0];
+        C::word(q == 0 ? r.x : q == 1 ? r.y : q == 2 ? r.z : r.w, d);
+    }
+}
+
+// Four independent copies of the arithmetic decoder, written stage by stage so that no
+// instruction consumes the result of the one just before it (a packed-fp16 result needs a
+// wait state before it can be read).
+__device__ __forceinline__ void recip_decode_4pairs(const u32 *h, u32 k2, u32 *v)
+{
+    const f16x2 m1023 = {(_Float16)-1023.0f, (_Float16)-1023.0f}, two = {(_Float16)2.0f, (_Float16)2.0f},
+                mone = {(_Float16)-1.0f, (_Float16)-1.0f};
+    f16x2 nf[4], L[4];
+    u16x2 rb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) nf[i] = __builtin_bit_cast(f16x2, h[i]) + m1023;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rb[i] = __builtin_bit_cast(u16x2, k2) - __builtin_bit_cast(u16x2, nf[i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) L[i] = __builtin_bit_cast(f16x2, rb[i]) * two + mone;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __builtin_bit_cast(u32, __builtin_elementwise_min(rb[i], __builtin_bit_cast(u16x2, L[i])));
+}
+
+template <> struct Codec<F8S> {
+    static constexpr int BITS = 8;
+    // 4 codes (k0..k3) -> (k0,k2), (k1,k3)
+    static __device__ __forceinline__ void word(u32 w, u32 *d)
+    {
+        const u32 wm = ~w & 0x7f7f7f7fu;                                   // 127 - c in every byte
+        const u32 h0 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04020400u);
+        const u32 h1 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04030401u);
+        const u32 v0 = recip_decode_pair(h0, 0x90009000u), v1 = recip_decode_pair(h1, 0x90009000u);
+        d[0] = (v0 & 0x7fff7fffu) | ((w << 8) & 0x80008000u);             // sign bit of bytes 0, 2
+        d[1] = (v1 & 0x7fff7fffu) | (w & 0x80008000u);                    // sign bit of bytes 1, 3
+    }
+    // 8 codes (two words) -> four registers, the four pairs decoded side by side
+    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
+    {
+        const u32 m0 = ~w0 & 0x7f7f7f7fu, m1 = ~w1 & 0x7f7f7f7fu;
+        u32 h[4], v[4];
+        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
+        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
+        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
+        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
+        recip_decode_4pairs(h, 0x90009000u, v);
+        d[0] = (v[0] & 0x7fff7fffu) | ((w0 << 8) & 0x80008000u);
+        d[1] = (v[1] & 0x7fff7fffu) | (w0 & 0x80008000u);
+        d[2] = (v[2] & 0x7fff7fffu) | ((w1 << 8) & 0x80008000u);
+        d[3] = (v[3] & 0x7fff7fffu) | (w1 & 0x80008000u);
+    }
+};
+
+template <> struct Codec<F8U> {
+    static constexpr int BITS = 8;
+    static __device__ __forceinline__ void word(u32 w, u32 *d)
+    {
+        const u32 wm = ~w;                                                 // 255 - c in every byte
+        const u32 h0 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04020400u);
+        const u32 h1 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04030401u);
+        d[0] = recip_decode_pair(h0, 0x94009400u);
+        d[1] = recip_decode_pair(h1, 0x94009400u);
+    }
+    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
+    {
+        const u32 m0 = ~w0, m1 = ~w1;
+        u32 h[4];
+        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
+        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
+        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
+        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
+        recip_decode_4pairs(h, 0x94009400u, d);
+    }
+};
+
+// 4-bit formats: every value has at most 3 significant bits, so its half has a zero low byte
+// and the high byte comes from an 8-entry byte table held in two registers (v_perm_b32).
+template <> struct Codec<F4S> {
+    static constexpr int BITS = 4;
+    // 8 codes (k0..k7) -> (k0,k2), (k1,k3), (k4,k6), (k5,k7)
+    static __device__ __forceinline__ void word(u32 w, u32 *d)
+    {
+        // high bytes of 0, .25, .5, .75, 1, 1.5, 2, 4
+        const u32 tlo = 0x3A383400u, thi = 0x44403E3Cu;
+        const u32 pe = __builtin_amdgcn_perm(thi, tlo, w & 0x07070707u);           // k0 k2 k4 k6
+        const u32 po = __builtin_amdgcn_perm(thi, tlo, (w >> 4) & 0x07070707u);    // k1 k3 k5 k7
+        const u32 e = pe | ((w << 4) & 0x80808080u);
+        const u32 o = po | (w & 0x80808080u);
+        d[0] = __builtin_amdgcn_perm(0u, e, 0x010c000cu);
+        d[1] = __builtin_amdgcn_perm(0u, o, 0x010c000cu);
+        d[2] = __builtin_amdgcn_perm(0u, e, 0x030c020cu);
+        d[3] = __builtin_amdgcn_perm(0u, o, 0x030c020cu);
+    }
+};
+
+template <> struct Codec<F4U> {
+    static constexpr int BITS = 4;
+    static __device__ __forceinline__ void word(u32 w, u32 *d)
+    {
+        // high bytes of 0 .. .875 in steps of .125, then 1, 1.25, 1.5, 1.75, 2, 3, 4, 8 (Table I)
+        const u32 alo = 0x36343000u, ahi = 0x3B3A3938u, blo = 0x3F3E3D3Cu, bhi = 0x48444240u;
+        const u32 se = w & 0x07070707u, so = (w >> 4) & 0x07070707u;
+        const u32 me = w & 0x08080808u, mo = w & 0x80808080u;
+        const u32 maske = (me << 5) - (me >> 3), masko = (mo << 1) - (mo >> 7);    // 0xff where bit 3 set
+        const u32 e = (__builtin_amdgcn_perm(bhi, blo, se) & maske) | (__builtin_amdgcn_perm(ahi, alo, se) & ~maske);
+        const u32 o = (__builtin_amdgcn_perm(bhi, blo, so) & masko) | (__builtin_amdgcn_perm(ahi, alo, so) & ~masko);
+        d[0] = __builtin_amdgcn_perm(0u, e, 0x010c000cu);
+        d[1] = __builtin_amdgcn_perm(0u, o, 0x010c000cu);
+        d[2] = __builtin_amdgcn_perm(0u, e, 0x030c020cu);
+        d[3] = __builtin_amdgcn_perm(0u, o, 0x030c020cu);
+    }
+};
+
+}  // namespace fast
+}  // namespace dybit
+#endif

@@ -359,7 +359,7 @@ extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
     g.C = C; g.ldc = ldc;
     g.a_bytes = M * (K * a_fmt.bits / 8);
     g.w_bytes = N * (K * w_fmt.bits / 8);
-    if (launch_gemm_fast(g, a_fmt.bits, w_fmt.bits, false, (hipStream_t)stream)) return launch_status();
+    if (launch_gemm_tiled(g, a_fmt.bits, w_fmt.bits, false, (hipStream_t)stream)) return launch_status();
     const bool vec = (K % UNIT == 0) && aligned16(A_codes) && aligned16(W_codes);
     dispatch_gemm(g, a_fmt.bits, w_fmt.bits, false, vec, (hipStream_t)stream);
     return launch_status();
@@ -393,7 +393,7 @@ extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Ci
     g.kh = kh; g.kw = kw; g.stride = stride; g.pad = pad;
     g.a_bytes = B * H * W * (Cin * x_fmt.bits / 8);
     g.w_bytes = Cout * (g.K * w_fmt.bits / 8);
-    if (launch_gemm_fast(g, x_fmt.bits, w_fmt.bits, true, (hipStream_t)stream)) return launch_status();
+    if (launch_gemm_tiled(g, x_fmt.bits, w_fmt.bits, true, (hipStream_t)stream)) return launch_status();
     const bool vec = (Cin % UNIT == 0) && aligned16(X_codes) && aligned16(Wt_codes);
     dispatch_gemm(g, x_fmt.bits, w_fmt.bits, true, vec, (hipStream_t)stream);
     return launch_status();

@@ -1,0 +1,43 @@
+// Chooses between the tiled MFMA kernels of the DyBit matrix product.
+//
+// Both need 4- or 8-bit operands, signed weights, K (convolution: Cin) a multiple of 64 so that
+// a 64-wide k group is one run of whole 128-bit loads inside one filter tap, 16-byte aligned
+// code buffers, and buffers below 2 GiB (32-bit buffer offsets).  The 256 x 256 kernel does the
+// least decode work per MFMA and is used when its tiles can fill the 256 compute units and N is
+// wide enough for them; the 128 x 128 kernel takes the rest.  The environment variable
+// DYBIT_GEMM_KERNEL = large | mid | general overrides the choice whenever the named kernel's
+// preconditions hold (tests use it to reach a given kernel with small shapes).
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "gemm_args.h"
+
+namespace dybit {
+
+bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hipStream_t st)
+{
+    if ((a_bits != 4 && a_bits != 8) || (w_bits != 4 && w_bits != 8) || !g.w_signed) return false;
+    if (g.M < 1 || g.N < 1 || g.K < 64 || g.K % 64) return false;
+    if (conv && g.Cin % 64) return false;
+    if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W)) & 15) return false;
+    if (g.a_bytes >= 0x7fffffff || g.w_bytes >= 0x7fffffff) return false;
+
+    bool large;
+    const char *force = getenv("DYBIT_GEMM_KERNEL");
+    if (force && !strcmp(force, "general")) return false;
+    if (force && !strcmp(force, "large")) {
+        large = true;
+    } else if (force && !strcmp(force, "mid")) {
+        large = false;
+    } else {
+        // Too few 256 x 256 tiles cannot fill 256 compute units, and a narrow N wastes most of a
+        // 256-wide tile.
+        const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
+        large = g.N > 128 && tiles256 >= 128;
+    }
+    if (large) return w_bits == 4 ? launch_gemm_fast_w0(g, a_bits, conv, st) : launch_gemm_fast_w2(g, a_bits, conv, st);
+    return w_bits == 4 ? launch_gemm_mid_w0(g, a_bits, conv, st) : launch_gemm_mid_w2(g, a_bits, conv, st);
+}
+
+}  // namespace dybit

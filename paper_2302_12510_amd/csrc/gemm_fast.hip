@@ -26,171 +26,21 @@
 
 #include <type_traits>
 
+#include "dybit_codec.h"
 #include "gemm_args.h"
+
+#ifndef DYBIT_FAST_W
+#error "compile with -DDYBIT_FAST_W=<weight format id> (0: 4-bit signed, 2: 8-bit signed)"
+#endif
 
 namespace dybit {
 namespace fast {
 
-typedef uint32_t u32;
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 256, TN = 256, TK = 64;
 constexpr int ROW_BYTES = TK * 2 + 16;            // one LDS row of W: 64 halves = 8 chunks of 16 B, plus 16 B of padding
 constexpr int STAGE_BYTES = TN * ROW_BYTES;       // 36 KiB per stage
 constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-constexpr uint32_t kOob = 0x80000000u;            // a buffer offset past every supported size: such loads return 0
-
-enum { F4S = 0, F4U = 1, F8S = 2, F8U = 3 };
-
-// ---------------------------------------------------------------------------
-// Codecs: packed codes -> fp16 pairs, entirely in the vector ALU.
-// ---------------------------------------------------------------------------
-// Arithmetic decoder for m magnitude bits (used for the 8-bit formats).  With n = 2^m - c:
-//   R = bitcast(K - bits(half(n)))      K = (15 + 15 + m-1) << 10
-// equals the DyBit value for codes with a leading one (see magnitude_value in dybit_device.h),
-// and for codes below that (n >= 2^(m-1)) it equals 1/2 + c/2^m, so the fraction c/2^(m-1) is
-// 2R - 1.  Because 2R - 1 >= R exactly when R >= 1, the value is min(R, 2R - 1) for every code.
-// half(n) comes from the usual trick: the bits 0x6400 | (2^m - 1 - c) are the half 1024 + 2^m-1-c,
-// and subtracting 1023 leaves n.  Both R and 2R-1 are non-negative, so the minimum is taken
-// on the bit patterns (no NaN canonicalisation needed).
-__device__ __forceinline__ u32 recip_decode_pair(u32 h, u32 k2)
-{
-    const f16x2 nf = __builtin_bit_cast(f16x2, h) + (f16x2){(_Float16)-1023.0f, (_Float16)-1023.0f};
-    const u16x2 rb = __builtin_bit_cast(u16x2, k2) - __builtin_bit_cast(u16x2, nf);
-    const f16x2 R = __builtin_bit_cast(f16x2, rb);
-    const f16x2 L = R * (f16x2){(_Float16)2.0f, (_Float16)2.0f} + (f16x2){(_Float16)-1.0f, (_Float16)-1.0f};
-    const u16x2 v = __builtin_elementwise_min(rb, __builtin_bit_cast(u16x2, L));
-    return __builtin_bit_cast(u32, v);
-}
-
-template <int FMT> struct Codec;
-
-// Codec<F>::word decodes one 32-bit word; Codec<F>::eight decodes the q-th group of eight codes of
-// a thread's 32 codes (held in BITS / 4 registers of 128 bits) into four registers of two halves.
-template <int FMT>
-__device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
-{
-    using C = Codec<FMT>;
-    if constexpr (C::BITS == 8) {
-        const u32x4 r = raw[q >> 1];
-        C::two_words((q & 1) ? r.z : r.x, (q & 1) ? r.w : r.y, d);
-    } else {
-        const u32x4 r = raw[0];
-        C::word(q == 0 ? r.x : q == 1 ? r.y : q == 2 ? r.z : r.w, d);
-    }
-}
-
-// Four independent copies of the arithmetic decoder, written stage by stage so that no
-// instruction consumes the result of the one just before it (a packed-fp16 result needs a
-// wait state before it can be read).
-__device__ __forceinline__ void recip_decode_4pairs(const u32 *h, u32 k2, u32 *v)
-{
-    const f16x2 m1023 = {(_Float16)-1023.0f, (_Float16)-1023.0f}, two = {(_Float16)2.0f, (_Float16)2.0f},
-                mone = {(_Float16)-1.0f, (_Float16)-1.0f};
-    f16x2 nf[4], L[4];
-    u16x2 rb[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) nf[i] = __builtin_bit_cast(f16x2, h[i]) + m1023;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) rb[i] = __builtin_bit_cast(u16x2, k2) - __builtin_bit_cast(u16x2, nf[i]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) L[i] = __builtin_bit_cast(f16x2, rb[i]) * two + mone;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = __builtin_bit_cast(u32, __builtin_elementwise_min(rb[i], __builtin_bit_cast(u16x2, L[i])));
-}
-
-template <> struct Codec<F8S> {
-    static constexpr int BITS = 8;
-    // 4 codes (k0..k3) -> (k0,k2), (k1,k3)
-    static __device__ __forceinline__ void word(u32 w, u32 *d)
-    {
-        const u32 wm = ~w & 0x7f7f7f7fu;                                   // 127 - c in every byte
-        const u32 h0 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04020400u);
-        const u32 h1 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04030401u);
-        const u32 v0 = recip_decode_pair(h0, 0x90009000u), v1 = recip_decode_pair(h1, 0x90009000u);
-        d[0] = (v0 & 0x7fff7fffu) | ((w << 8) & 0x80008000u);             // sign bit of bytes 0, 2
-        d[1] = (v1 & 0x7fff7fffu) | (w & 0x80008000u);                    // sign bit of bytes 1, 3
-    }
-    // 8 codes (two words) -> four registers, the four pairs decoded side by side
-    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
-    {
-        const u32 m0 = ~w0 & 0x7f7f7f7fu, m1 = ~w1 & 0x7f7f7f7fu;
-        u32 h[4], v[4];
-        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
-        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
-        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
-        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
-        recip_decode_4pairs(h, 0x90009000u, v);
-        d[0] = (v[0] & 0x7fff7fffu) | ((w0 << 8) & 0x80008000u);
-        d[1] = (v[1] & 0x7fff7fffu) | (w0 & 0x80008000u);
-        d[2] = (v[2] & 0x7fff7fffu) | ((w1 << 8) & 0x80008000u);
-        d[3] = (v[3] & 0x7fff7fffu) | (w1 & 0x80008000u);
-    }
-};
-
-template <> struct Codec<F8U> {
-    static constexpr int BITS = 8;
-    static __device__ __forceinline__ void word(u32 w, u32 *d)
-    {
-        const u32 wm = ~w;                                                 // 255 - c in every byte
-        const u32 h0 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04020400u);
-        const u32 h1 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04030401u);
-        d[0] = recip_decode_pair(h0, 0x94009400u);
-        d[1] = recip_decode_pair(h1, 0x94009400u);
-    }
-    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
-    {
-        const u32 m0 = ~w0, m1 = ~w1;
-        u32 h[4];
-        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
-        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
-        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
-        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
-        recip_decode_4pairs(h, 0x94009400u, d);
-    }
-};
-
-// 4-bit formats: every value has at most 3 significant bits, so its half has a zero low byte
-// and the high byte comes from an 8-entry byte table held in two registers (v_perm_b32).
-template <> struct Codec<F4S> {
-    static constexpr int BITS = 4;
-    // 8 codes (k0..k7) -> (k0,k2), (k1,k3), (k4,k6), (k5,k7)
-    static __device__ __forceinline__ void word(u32 w, u32 *d)
-    {
-        // high bytes of 0, .25, .5, .75, 1, 1.5, 2, 4
-        const u32 tlo = 0x3A383400u, thi = 0x44403E3Cu;
-        const u32 pe = __builtin_amdgcn_perm(thi, tlo, w & 0x07070707u);           // k0 k2 k4 k6
-        const u32 po = __builtin_amdgcn_perm(thi, tlo, (w >> 4) & 0x07070707u);    // k1 k3 k5 k7
-        const u32 e = pe | ((w << 4) & 0x80808080u);
-        const u32 o = po | (w & 0x80808080u);
-        d[0] = __builtin_amdgcn_perm(0u, e, 0x010c000cu);
-        d[1] = __builtin_amdgcn_perm(0u, o, 0x010c000cu);
-        d[2] = __builtin_amdgcn_perm(0u, e, 0x030c020cu);
-        d[3] = __builtin_amdgcn_perm(0u, o, 0x030c020cu);
-    }
-};
-
-template <> struct Codec<F4U> {
-    static constexpr int BITS = 4;
-    static __device__ __forceinline__ void word(u32 w, u32 *d)
-    {
-        // high bytes of 0 .. .875 in steps of .125, then 1, 1.25, 1.5, 1.75, 2, 3, 4, 8 (Table I)
-        const u32 alo = 0x36343000u, ahi = 0x3B3A3938u, blo = 0x3F3E3D3Cu, bhi = 0x48444240u;
-        const u32 se = w & 0x07070707u, so = (w >> 4) & 0x07070707u;
-        const u32 me = w & 0x08080808u, mo = w & 0x80808080u;
-        const u32 maske = (me << 5) - (me >> 3), masko = (mo << 1) - (mo >> 7);    // 0xff where bit 3 set
-        const u32 e = (__builtin_amdgcn_perm(bhi, blo, se) & maske) | (__builtin_amdgcn_perm(ahi, alo, se) & ~maske);
-        const u32 o = (__builtin_amdgcn_perm(bhi, blo, so) & masko) | (__builtin_amdgcn_perm(ahi, alo, so) & ~masko);
-        d[0] = __builtin_amdgcn_perm(0u, e, 0x010c000cu);
-        d[1] = __builtin_amdgcn_perm(0u, o, 0x010c000cu);
-        d[2] = __builtin_amdgcn_perm(0u, e, 0x030c020cu);
-        d[3] = __builtin_amdgcn_perm(0u, o, 0x030c020cu);
-    }
-};
 
 // ---------------------------------------------------------------------------
 // Kernel.  RB = 32-row blocks of A per wave: 1 -> eight waves (two per SIMD), 2 -> four waves.
@@ -209,19 +59,19 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kg = lane >> 5;                                        // k-group of the lane
 
-    // ---- tile assignment: consecutive workgroup ids go to different XCDs (8 of them); give
-    // each XCD a compact 4 x 8 patch of the 16 x 16-tile region that is in flight, so that the
-    // A and W strips it streams are shared inside its own L2.
+    // ---- tile assignment: consecutive workgroup ids go to different XCDs (8 of them, 32 compute
+    // units each).  XCD x takes a contiguous range of a tile order that walks column panels of
+    // 8 tiles row by row, so the 32 tiles it has in flight form a compact 4 x 8 patch whose
+    // A and W strips are shared inside its own L2.  No workgroup is launched without a tile.
     int tile_m, tile_n;
     {
-        const int b = blockIdx.x;
-        const int region = b >> 8, r = b & 255;
-        const int xcd = r & 7, i = r >> 3;                         // i: 0..31 inside the XCD
-        const int regions_n = (tiles_n + 15) / 16;
-        const int rm = region / regions_n, rn = region % regions_n;
-        tile_m = rm * 16 + (xcd >> 1) * 4 + (i >> 3);
-        tile_n = rn * 16 + (xcd & 1) * 8 + (i & 7);
-        if (tile_m >= tiles_m || tile_n >= tiles_n) return;       // uniform per workgroup
+        const int per_xcd = (int)gridDim.x >> 3;
+        const int l = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+        if (l >= tiles_m * tiles_n) return;                       // uniform per workgroup
+        const int panel = l / (tiles_m * 8), r = l - panel * tiles_m * 8;
+        const int width = min(8, tiles_n - panel * 8);             // the last panel may be narrower
+        tile_m = r / width;
+        tile_n = panel * 8 + (r - tile_m * width);
     }
     const int64_t m0 = (int64_t)tile_m * TM, n0 = (int64_t)tile_n * TN;
 
@@ -410,8 +260,7 @@ template <int FA, int FW>
 static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 {
     const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
-    const int regions = ((tiles_m + 15) / 16) * ((tiles_n + 15) / 16);
-    const dim3 grid(regions * 256), block(512 / kRowBlocks);
+    const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8)), block(512 / kRowBlocks);
     if (conv) {
         auto k = gemm_fast_kernel<FA, FW, true, kRowBlocks>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -425,29 +274,20 @@ static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 
 }  // namespace fast
 
-bool launch_gemm_fast(const GemmArgs &g, int a_bits, int w_bits, bool conv, hipStream_t st)
+// One translation unit per weight format (compile time); the entry point's name carries it.
+#define DYBIT_FAST_NAME2(w) launch_gemm_fast_w##w
+#define DYBIT_FAST_NAME(w) DYBIT_FAST_NAME2(w)
+bool DYBIT_FAST_NAME(DYBIT_FAST_W)(const GemmArgs &g, int a_bits, bool conv, hipStream_t st)
 {
     using namespace fast;
-    if ((a_bits != 4 && a_bits != 8) || (w_bits != 4 && w_bits != 8)) return false;
-    if (g.K < TK || g.K % TK) return false;
-    if (conv && g.Cin % TK) return false;                                  // a K step must stay inside one filter tap
-    if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W)) & 15) return false;
-    // 32-bit buffer offsets, including the rows past M / N that the last tiles touch
-    if (g.a_bytes + (int64_t)TM * g.K * a_bits / 8 >= 0x7fffffff || g.w_bytes + (int64_t)TN * g.K * w_bits / 8 >= 0x7fffffff) return false;
-    // Too few large tiles cannot fill 256 compute units; DYBIT_FAST_MIN_TILES overrides the
-    // threshold (tests use it to reach this kernel with small shapes).
-    const char *env = getenv("DYBIT_FAST_MIN_TILES");
-    const int64_t min_tiles = env ? atoll(env) : 128;
-    if (((g.M + TM - 1) / TM) * ((g.N + TN - 1) / TN) < min_tiles) return false;
     const int fa = (a_bits == 8 ? F8S : F4S) + (g.a_signed ? 0 : 1);
-    const int fw = (w_bits == 8 ? F8S : F4S) + (g.w_signed ? 0 : 1);
-#define DYBIT_F(A_, W_) case (A_) * 4 + (W_): launch<A_, W_>(g, conv, st); return true
-    switch (fa * 4 + fw) {
-        DYBIT_F(F8S, F4S);
-        DYBIT_F(F4U, F4S);
+    switch (fa) {
+        case F4S: fast::launch<F4S, DYBIT_FAST_W>(g, conv, st); return true;
+        case F4U: fast::launch<F4U, DYBIT_FAST_W>(g, conv, st); return true;
+        case F8S: fast::launch<F8S, DYBIT_FAST_W>(g, conv, st); return true;
+        case F8U: fast::launch<F8U, DYBIT_FAST_W>(g, conv, st); return true;
         default: return false;
     }
-#undef DYBIT_F
 }
 
 }  // namespace dybit

@@ -1,0 +1,288 @@
+// Mid-size-tile DyBit matrix product for gfx950: 128 x 128 tile of C per workgroup, for shapes
+// that do not have enough 256 x 256 tiles to fill the 256 compute units (the convolution
+// layers of a network, a GEMM with a narrow N).  Two variants, by the number KG of k-groups:
+//
+// KG = 1: four waves, wave w owns rows 32 w .. 32 w + 31 and all 128 columns, K step 64.
+//   Three workgroups fit on a compute unit (three waves per SIMD), so that one workgroup's
+//   decode arithmetic, its prologue and its epilogue overlap the MFMAs of the others.  Used when
+//   there are more tiles than compute units.
+// KG = 2: eight waves, two per SIMD inside one workgroup, for problems with at most one tile per
+//   compute unit.  With a 128 x 128 tile there are only four 32-row strips, so the eight waves
+//   are four row strips x two k-groups: a K step is 128 wide, k-group g contracts
+//   k = 64 g .. 64 g + 63 of it, and the two partial accumulators of a row strip are added
+//   through LDS once, after the K loop.
+// Per wave and K step: four MFMA k blocks of 16 -> 16 MFMAs into 4 accumulator blocks (64
+// registers).
+//
+// Operand paths are those of the large-tile kernel: the activation operand A is fetched by the
+// lane that needs it (its row, its 32 consecutive k) and decoded straight into MFMA fragments;
+// the weight operand W is decoded once per workgroup (each thread 32 codes of one row) into a
+// double-buffered LDS tile (rows padded by 16 B) and read back as fragments by every wave.
+// Codes past K, rows past M / N and filter taps outside the image are fetched from an
+// out-of-range buffer offset and read as code 0 = 0.0, so K only has to be a multiple of 64.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include <type_traits>
+
+#include "dybit_codec.h"
+#include "gemm_args.h"
+
+#ifndef DYBIT_MID_W
+#error "compile with -DDYBIT_MID_W=<weight format id> (0: 4-bit signed, 2: 8-bit signed)"
+#endif
+
+namespace dybit {
+namespace mid {
+
+using namespace fast;
+
+constexpr int TM = 128, TN = 128;
+
+template <int KG> struct Geom {
+    static constexpr int TK = 64 * KG;
+    static constexpr int ROW_BYTES = TK * 2 + 16;         // one LDS row of W: TK halves plus 16 B of padding
+    static constexpr int STAGE_BYTES = TN * ROW_BYTES;    // 18 KiB (KG = 1) or 34 KiB (KG = 2) per stage
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;     // KG = 2: also holds the 64 KiB of partial sums at the end
+};
+static_assert(Geom<2>::LDS_BYTES >= 4 * 4 * 16 * 64 * 4, "reduction buffer must fit in the stages");
+
+template <int FMT_A, int FMT_W, bool CONV, int KG>
+__global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
+{
+    using CA = Codec<FMT_A>;
+    using CW = Codec<FMT_W>;
+    constexpr int TK = Geom<KG>::TK, ROW_BYTES = Geom<KG>::ROW_BYTES, STAGE_BYTES = Geom<KG>::STAGE_BYTES;
+    constexpr int NA = CA::BITS / 4;                               // 128-bit loads per lane and K step
+    constexpr int NW = CW::BITS / 4;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave & 3, kgp = wave >> 2;                        // row strip and k-group of the wave
+    const int kq = lane >> 5;                                        // which 32 k of the k-group's 64 the lane owns
+
+    // ---- tile assignment: consecutive workgroup ids go to different XCDs; give each XCD a
+    // contiguous range of tiles (all column tiles of a row strip together), so that the A rows
+    // it streams are shared inside its own L2.
+    int tile_m, tile_n;
+    {
+        const int per_xcd = (int)gridDim.x >> 3;
+        const int l = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+        if (l >= tiles_m * tiles_n) return;                       // uniform per workgroup
+        tile_m = l / tiles_n;
+        tile_n = l - tile_m * tiles_n;
+    }
+    const int64_t m0 = (int64_t)tile_m * TM, n0 = (int64_t)tile_n * TN;
+
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(g.A), 0, (int)(g.a_bytes > 0x7fffffff ? 0x7fffffff : g.a_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
+
+    // ---- A: the lane's own row, the 32 codes kq of its k-group's 64
+    const int a_row_bytes = (int)(g.K * CA::BITS / 8), w_row_bytes = (int)(g.K * CW::BITS / 8);
+    const int pix_bytes = CONV ? g.Cin * CA::BITS / 8 : 0;
+    u32 offA;
+    int hi0 = 0, wi0 = 0;
+    bool okA;
+    {
+        const int64_t m = m0 + wr * 32 + (lane & 31);
+        okA = m < g.M;
+        if (CONV) {
+            const int64_t mm = okA ? m : 0;
+            const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
+            const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
+            const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+            hi0 = ho * g.stride - g.pad;
+            wi0 = wo * g.stride - g.pad;
+            offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * 16 * NA);
+        } else {
+            offA = okA ? (u32)(m * a_row_bytes + kq * 16 * NA) : kOob;
+        }
+    }
+    // ---- W staging: a row of the K step is TK / 32 = 2 KG runs of 32 codes, one thread each
+    const int wrow = tid / (2 * KG), wq = tid % (2 * KG);
+    const int64_t nrow = n0 + wrow;
+    const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + wq * 16 * NW) : kOob;
+    const u32 wrW = (u32)wrow * ROW_BYTES + (u32)wq * 64;
+    const u32 rdW = (u32)(lane & 31) * ROW_BYTES + (u32)kgp * 128 + (u32)kq * 64;   // block kk adds 16 B, column block j adds 32 rows
+
+    auto load_A = [&](int64_t kt, u32x4 *raw) {
+        const int64_t k0 = kt * TK + kgp * 64;                                          // uniform per wave
+        u32 off;
+        if (CONV) {
+            const int tap = (int)(k0 / g.Cin), c0 = (int)(k0 - (int64_t)tap * g.Cin);
+            const int fr = tap / g.kw, fs = tap - fr * g.kw;
+            const bool in = okA && k0 < g.K && (unsigned)(hi0 + fr) < (unsigned)g.H && (unsigned)(wi0 + fs) < (unsigned)g.Wd;
+            off = in ? offA + (u32)((fr * g.Wd + fs) * pix_bytes + c0 * CA::BITS / 8) : kOob;   // padding reads code 0
+        } else {
+            off = k0 < g.K ? offA + (u32)(k0 * CA::BITS / 8) : kOob;
+        }
+#pragma unroll
+        for (int p = 0; p < NA; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
+    };
+    auto load_W = [&](int64_t kt, u32x4 *raw) {
+        const int64_t k0 = kt * TK + wq * 32;
+        const u32 off = k0 < g.K ? offW + (u32)(kt * TK * CW::BITS / 8) : kOob;
+#pragma unroll
+        for (int p = 0; p < NW; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + p * 16, 0, 0);
+    };
+    auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
+        u32 d[4];
+        decode_eight<FMT_A>(raw, q, d);
+        return __builtin_bit_cast(f16x8, u32x4{d[0], d[1], d[2], d[3]});
+    };
+    auto stage_W = [&](const u32x4 *raw, int q, char *tile) {
+        u32 d[4];
+        decode_eight<FMT_W>(raw, q, d);
+        *reinterpret_cast<u32x4 *>(tile + wrW + q * 16) = u32x4{d[0], d[1], d[2], d[3]};
+    };
+    auto read_W = [&](const char *tile, int kk, int j) -> f16x8 {
+        return *reinterpret_cast<const f16x8 *>(tile + rdW + kk * 16 + j * 32 * ROW_BYTES);
+    };
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+
+    u32x4 rawA[2][NA], rawW[2][NW];
+    f16x8 fw[4], fa;
+
+    // ---- prologue: W tile 0 decoded into stage 0, A/W tile 1 in flight, first fragments in registers
+    load_A(0, rawA[0]);
+    load_W(0, rawW[0]);
+    load_A(1, rawA[1]);
+    load_W(1, rawW[1]);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) stage_W(rawW[0], q, lds);
+    fa = decode_A(rawA[0], 0);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fw[j] = read_W(lds, 0, j);
+
+    // One K step over LDS stage s: four k blocks of four MFMAs.  A W fragment register is refilled
+    // with the next block's fragment right after the MFMA that used it; the next W tile is decoded
+    // into the other stage during blocks 0..2; the workgroup barrier sits before block 3 and the
+    // first fragments of the next tile are requested right after it.  The A fragment of block
+    // kk + 1 is decoded during block kk.  Every step is the same straight-line code, so the last
+    // steps decode and prefetch tiles of zeros.
+    auto step = [&](int64_t kt, auto stage_tag) {
+        constexpr int s = decltype(stage_tag)::value;
+        const char *cur = lds + s * STAGE_BYTES;
+        char *nxt = lds + (s ^ 1) * STAGE_BYTES;
+        load_W(kt + 2, rawW[s]);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk == 3) __syncthreads();
+            const f16x8 fa_cur = fa;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa_cur, fw[j], acc[j], 0, 0, 0);
+                fw[j] = kk < 3 ? read_W(cur, kk + 1, j) : read_W(nxt, 0, j);
+            }
+            fa = kk < 3 ? decode_A(rawA[s], kk + 1) : decode_A(rawA[s ^ 1], 0);
+            if (kk == 0) { stage_W(rawW[s ^ 1], 0, nxt); stage_W(rawW[s ^ 1], 1, nxt); }
+            if (kk == 1) stage_W(rawW[s ^ 1], 2, nxt);
+            if (kk == 2) stage_W(rawW[s ^ 1], 3, nxt);
+            if (kk == 2) load_A(kt + 2, rawA[s]);                   // tile kt's codes are fully decoded by now
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                 // DS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);                // VALU
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    const int64_t ktiles = (g.K + TK - 1) / TK;
+    for (int64_t kt = 0; kt < ktiles; kt += 2) {                   // an odd number of K steps is padded with a step of zeros
+        step(kt, std::integral_constant<int, 0>{});
+        step(kt + 1, std::integral_constant<int, 1>{});
+    }
+
+    // ---- add the two k-groups' partial sums: k-group 1 hands its accumulators over through LDS
+    if constexpr (KG == 2) {
+        __syncthreads();                                            // every fragment read has completed
+        float *red = reinterpret_cast<float *>(lds);
+        if (kgp == 1) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) red[((wr * 4 + j) * 16 + v) * 64 + lane] = acc[j][v];
+        }
+        __syncthreads();
+        if (kgp == 1) return;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][v] += red[((wr * 4 + j) * 16 + v) * 64 + lane];
+    }
+
+    // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU).  Accumulator v of a lane is row
+    // 8 (v / 4) + 4 (lane / 32) + v % 4 and column lane % 32 of its 32 x 32 block.
+    const float alpha = (*g.a_scale) * (*g.w_scale);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t n = n0 + j * 32 + (lane & 31);
+        const bool n_ok = n < g.N;
+        const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t mr = m0 + wr * 32 + 8 * (v >> 2) + 4 * kq + (v & 3);
+            float c = acc[j][v] * alpha + b;
+            if (g.relu) c = fmaxf(c, 0.0f);
+            if (n_ok && mr < g.M) __builtin_nontemporal_store(c, g.C + mr * g.ldc + n);
+        }
+    }
+}
+
+template <int FA, int FW, int KG>
+static void launch_kg(const GemmArgs &g, bool conv, hipStream_t st, int tiles_m, int tiles_n)
+{
+    const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8), 1, 1), block(256 * KG);
+    constexpr int lds_bytes = Geom<KG>::LDS_BYTES;
+    if (conv) {
+        auto k = gemm_mid_kernel<FA, FW, true, KG>;
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, st, g, tiles_m, tiles_n);
+    } else {
+        auto k = gemm_mid_kernel<FA, FW, false, KG>;
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, st, g, tiles_m, tiles_n);
+    }
+}
+
+// More tiles than compute units: small workgroups, three per compute unit.  Otherwise one
+// eight-wave workgroup per compute unit.  DYBIT_MID_KGROUPS = 1 | 2 overrides (tests).
+template <int FA, int FW>
+static void launch(const GemmArgs &g, bool conv, hipStream_t st)
+{
+    const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
+    const char *force = getenv("DYBIT_MID_KGROUPS");
+    const bool one = force ? atoi(force) == 1 : (int64_t)tiles_m * tiles_n > 256;
+    if (one) launch_kg<FA, FW, 1>(g, conv, st, tiles_m, tiles_n);
+    else launch_kg<FA, FW, 2>(g, conv, st, tiles_m, tiles_n);
+}
+
+}  // namespace mid
+
+// One translation unit per weight format (compile time); the entry point's name carries it.
+#define DYBIT_MID_NAME2(w) launch_gemm_mid_w##w
+#define DYBIT_MID_NAME(w) DYBIT_MID_NAME2(w)
+bool DYBIT_MID_NAME(DYBIT_MID_W)(const GemmArgs &g, int a_bits, bool conv, hipStream_t st)
+{
+    using namespace fast;
+    const int fa = (a_bits == 8 ? F8S : F4S) + (g.a_signed ? 0 : 1);
+    switch (fa) {
+        case F4S: mid::launch<F4S, DYBIT_MID_W>(g, conv, st); return true;
+        case F4U: mid::launch<F4U, DYBIT_MID_W>(g, conv, st); return true;
+        case F8S: mid::launch<F8S, DYBIT_MID_W>(g, conv, st); return true;
+        case F8U: mid::launch<F8U, DYBIT_MID_W>(g, conv, st); return true;
+        default: return false;
+    }
+}
+
+}  // namespace dybit

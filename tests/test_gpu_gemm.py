@@ -174,18 +174,25 @@ def test_config5a_shape_sampled_outputs():
     assert_within(got, want, den)
 
 
-# ---- large-tile kernel (256 x 256 tiles, in-register decode) -------------------
-FAST_PAIRS = [((8, True), (4, True)), ((4, False), (4, True))]
+# ---- tiled MFMA kernels (256 x 256 and 128 x 128 tiles, in-register decode) --------
+TILED_PAIRS = [(a, w) for w in ((4, True), (8, True)) for a in ((4, True), (4, False), (8, True), (8, False))]
+KERNELS = ["large", "mid1", "mid2"]      # mid1 / mid2: the 128 x 128 kernel with one / two k-groups
 
 
 @pytest.fixture
-def force_fast(monkeypatch):
-    monkeypatch.setenv("DYBIT_FAST_MIN_TILES", "1")
+def force_kernel(monkeypatch, request):
+    name = request.param
+    if name.startswith("mid") and name != "mid":
+        monkeypatch.setenv("DYBIT_MID_KGROUPS", name[3:])
+        name = "mid"
+    monkeypatch.setenv("DYBIT_GEMM_KERNEL", name)
+    return request.param
 
 
-@pytest.mark.parametrize("a_fmt,w_fmt", FAST_PAIRS)
+@pytest.mark.parametrize("force_kernel", KERNELS, indirect=True)
+@pytest.mark.parametrize("a_fmt,w_fmt", TILED_PAIRS)
 @pytest.mark.parametrize("shape", [(2100, 3900, 192), (256, 256, 64), (300, 520, 128), (1, 7, 64), (513, 255, 320)])
-def test_large_tile_kernel_ragged(force_fast, a_fmt, w_fmt, shape):
+def test_tiled_kernels_ragged(force_kernel, a_fmt, w_fmt, shape):
     M, N, K = shape
     rng = np.random.default_rng(M + N + K)
     qa = random_codes(rng, (M, K), a_fmt)
@@ -197,13 +204,13 @@ def test_large_tile_kernel_ragged(force_fast, a_fmt, w_fmt, shape):
         assert_within(got, want, den)
 
 
-@pytest.mark.parametrize("a_fmt,w_fmt", FAST_PAIRS)
-def test_large_tile_kernel_every_code_pair(force_fast, a_fmt, w_fmt):
+@pytest.mark.parametrize("force_kernel", KERNELS, indirect=True)
+@pytest.mark.parametrize("a_fmt,w_fmt", TILED_PAIRS)
+def test_tiled_kernels_every_code_pair(force_kernel, a_fmt, w_fmt):
     """Each A code meets each W code exactly once per row pair, so a wrong table entry or a
     wrong k pairing between the two decoders cannot cancel."""
     na, nw = 1 << a_fmt[0], 1 << w_fmt[0]
     K = 64 * ((na * nw + 63) // 64)
-    rng = np.random.default_rng(5)
     qa = np.zeros((260, K), np.uint8); qw = np.zeros((258, K), np.uint8)
     for r in range(260):
         qa[r] = np.resize(np.repeat(np.arange(na), nw), K)
@@ -214,9 +221,11 @@ def test_large_tile_kernel_every_code_pair(force_fast, a_fmt, w_fmt):
     got = run_gemm(qa, a_fmt, 1.0, qw, w_fmt, 1.0)
     want, den = R.gemm(qa, a_fmt, 1.0, qw, w_fmt, 1.0)
     assert_within(got, want, den)
-    # one-hot rows: a single non-zero code per row pins every decoded value on its own
+    # one-hot rows: a single non-zero code per row pins every decoded value on its own,
+    # first those of A against a unit weight, then those of W against a unit activation
     cba, cbw = R.codebook(*a_fmt), R.codebook(*w_fmt)
     one_w = int(np.where(cbw == 1.0)[0][0])
+    one_a = int(np.where(cba == 1.0)[0][0])
     qa1 = np.zeros((na, 64), np.uint8); qw1 = np.zeros((64, 64), np.uint8)
     for c in range(na):
         qa1[c, c % 64] = c
@@ -224,11 +233,19 @@ def test_large_tile_kernel_every_code_pair(force_fast, a_fmt, w_fmt):
     got = run_gemm(qa1, a_fmt, 1.0, qw1, w_fmt, 1.0)
     want = np.zeros((na, 64)); want[np.arange(na), np.arange(na) % 64] = cba
     assert np.array_equal(got.astype(np.float64), want)
+    qa2 = np.zeros((64, 64), np.uint8); qw2 = np.zeros((nw, 64), np.uint8)
+    qa2[np.arange(64), np.arange(64)] = one_a
+    for c in range(nw):
+        qw2[c, c % 64] = c
+    got = run_gemm(qa2, a_fmt, 1.0, qw2, w_fmt, 1.0)
+    want = np.zeros((64, nw)); want[np.arange(nw) % 64, np.arange(nw)] = cbw
+    assert np.array_equal(got.astype(np.float64), want)
 
 
-@pytest.mark.parametrize("x_fmt,w_fmt", FAST_PAIRS)
+@pytest.mark.parametrize("force_kernel", KERNELS, indirect=True)
+@pytest.mark.parametrize("x_fmt,w_fmt", TILED_PAIRS)
 @pytest.mark.parametrize("geom", [(3, 1, 1), (1, 1, 0), (3, 2, 1)])
-def test_large_tile_kernel_conv(force_fast, x_fmt, w_fmt, geom):
+def test_tiled_kernels_conv(force_kernel, x_fmt, w_fmt, geom):
     k, stride, pad = geom
     rng = np.random.default_rng(k * 7 + stride)
     Bn, H, W, Cin, Cout = 3, 13, 11, 64, 300
@@ -237,4 +254,28 @@ def test_large_tile_kernel_conv(force_fast, x_fmt, w_fmt, geom):
     bias = rng.normal(0, 1, Cout).astype(np.float32)
     got = run_conv(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, True)
     want, den = R.conv2d(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, True)
+    assert_within(got, want, den)
+
+
+@pytest.mark.parametrize("force_kernel", ["mid1", "mid2"], indirect=True)
+def test_mid_kernel_wide_channels_conv(force_kernel):
+    """Cin = 192: a 128-wide K step straddles two filter taps (each k-group follows its own tap)."""
+    rng = np.random.default_rng(11)
+    x_fmt, w_fmt = (4, False), (4, True)
+    qx = random_codes(rng, (2, 9, 10, 192), x_fmt)
+    qw = random_codes(rng, (130, 3, 3, 192), w_fmt)
+    got = run_conv(qx, x_fmt, 0.3, qw, w_fmt, 0.02, 1, 1)
+    want, den = R.conv2d(qx, x_fmt, 0.3, qw, w_fmt, 0.02, 1, 1)
+    assert_within(got, want, den)
+
+
+@pytest.mark.parametrize("force_kernel", ["general"], indirect=True)
+@pytest.mark.parametrize("a_fmt,w_fmt", [((4, False), (4, True)), ((8, True), (4, True)), ((8, False), (8, True))])
+def test_general_kernel_on_tiled_shapes(force_kernel, a_fmt, w_fmt):
+    """The general kernel's vector path on shapes the tiled kernels would otherwise take."""
+    rng = np.random.default_rng(3)
+    qa = random_codes(rng, (257, 192), a_fmt)
+    qw = random_codes(rng, (129, 192), w_fmt)
+    got = run_gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011)
+    want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011)
     assert_within(got, want, den)
