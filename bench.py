@@ -31,9 +31,6 @@ if ROOT not in sys.path:
 PEAK_FP16_MFMA_TFLOPS = 2500.0   # MI355X dense fp16/bf16 matrix peak
 PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E peak
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command
-# (profiles/gemm_cfg5a_hbm_traffic.md): FETCH_SIZE * 2 KiB + WRITE_SIZE * 1 KiB, the factors being
-# what the same counters read for a plain 1 GiB copy.  None where not measured.
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (units of 2 KiB and 1 KiB on
 # this device, calibrated on a 1 GiB copy); the summaries are under profiles/.
 MEASURED_TRAFFIC = {"cfg5": 262302 * 2048 + 262144 * 1024, "cfg2": None, "cfg1": None}
@@ -45,7 +42,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1", "cfg3", "cfg4"],
+                    help="cfg5 (default): 8192^3 GEMM + 2^28 quantize; cfg1 / cfg2: the small GEMM and the "
+                         "convolution; cfg3 / cfg4: one forward pass of the ResNet-18 / ResNet-50 chains")
+    ap.add_argument("--table", action="store_true",
+                    help="run every configuration in a child process each and print a markdown table")
     ap.add_argument("--size", type=int, default=8192, help="M=N=K of the cfg5 GEMM")
     ap.add_argument("--quantize-log2n", type=int, default=28)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -67,11 +68,101 @@ def time_events(fn, steps, warmup, torch):
     return float(np.mean(ts)), float(ts[len(ts) // 2])
 
 
+def bench_network(args):
+    """Configs 3 and 4: a step is one forward pass of the chained network (per conv / linear layer
+    absmax -> quantize -> dybit_conv2d with bias and ReLU; pooling and residual adds in torch)."""
+    import torch
+    from paper_2302_12510_amd import binding as B
+    from paper_2302_12510_amd import synth
+    from paper_2302_12510_amd.network import DybitNetwork
+
+    torch.cuda.set_device(0)
+    B.lib()
+    if args.workload == "cfg3":
+        layers, batch = synth.resnet18_layers(), 64
+        bits = synth.bitwidths_fixed(layers)
+        name = "cfg3 ResNet-18 forward, batch 64, 224x224; first conv and fc 8-bit, other layers 4-bit W/A"
+    else:
+        layers, batch = synth.resnet50_layers(), 128
+        bits = synth.bitwidths_mixed(layers, 0)
+        name = "cfg4 ResNet-50 forward, batch 128, 224x224; per-layer (W, A) bits drawn from {4,6,8}, seed 0"
+    net = DybitNetwork(layers, synth.network_weights(layers, seed=0), bits)
+    x = torch.from_numpy(synth.network_input(batch, 224, seed=0)).cuda()
+    for _ in range(args.warmup):
+        net.forward(x)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        net.forward(x)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert B.dybit_get_last_async_error() == B.OK
+    shapes = net.gemm_shapes(batch, 224)
+    flops = sum(2.0 * m * n * k for _, m, n, k in shapes)
+    out = {
+        "metric": "DyBit GEMM effective TOPS (+ quantize GB/s), % of roofline",
+        "value": round(flops / (ms * 1e-3) / 1e12, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 MFMA inputs (exact), f32 accumulate", "data": "synthetic",
+        "config": {"workload": name, "gemms": len(shapes), "GMAC": round(flops / 2e9, 1),
+                   "step": "per layer absmax + quantize + conv (bias, ReLU); pooling / residual adds in torch"},
+        "roofline": None,
+    }
+    if not args.no_cpu_baseline:
+        # the oracle's convolution on a few images of one mid-network layer; the forward pass
+        # has the same kind of work throughout, so its rate is what a full oracle pass would run at
+        from oracle import c_ref
+        rng = np.random.default_rng(0)
+        xq = rng.integers(0, 16, (2, 28, 28, 128)).astype(np.uint8)
+        wq = rng.integers(0, 16, (128, 3, 3, 128)).astype(np.uint8)
+        t0 = time.perf_counter()
+        c_ref.conv2d(xq, (4, False), 1.0, wq, (4, True), 1.0, 1, 1, want_den=False)
+        dt = time.perf_counter() - t0
+        rate = 2.0 * 2 * 28 * 28 * 128 * 9 * 128 / dt
+        out["cpu_baseline"] = {"value": round(rate / 1e12, 5), "unit": "TOPS", "cores": c_ref.num_threads(),
+                               "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": "3x3 conv 128->128 on 28x28, 2 images (one layer shape of the network); "
+                                         "a full oracle pass at this rate would take %.0f s" % (flops / rate)}
+    print(json.dumps(out))
+
+
+def table(args):
+    """Every configuration, each in a child process, as one markdown table."""
+    import subprocess
+    rows = []
+    for wl in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+        cmd = [sys.executable, os.path.abspath(__file__), "--workload", wl, "--steps", str(args.steps),
+               "--warmup", str(args.warmup)] + (["--no-cpu-baseline"] if args.no_cpu_baseline else [])
+        p = subprocess.run(cmd, capture_output=True, text=True)
+        if p.returncode:
+            sys.stderr.write(p.stderr)
+            sys.exit(p.returncode)
+        rows.append((wl, json.loads([l for l in p.stdout.splitlines() if l.startswith("{")][-1])))
+    print("| Config | GPU time per step | Effective TOPS / GB/s | Dominant kernel alone | % of roofline | Oracle (cores) |")
+    print("|---|---|---|---|---|---|")
+    for wl, r in rows:
+        rf, cb = r.get("roofline"), r.get("cpu_baseline")
+        kern = "%s: %.4f ms, %.1f TFLOP/s" % (rf["kernel"], rf["kernel_ms"], rf["achieved"]) if rf else "-"
+        frac = "%.1f %% of %.0f TFLOP/s" % (100 * rf["frac"], rf["peak"]) if rf else "-"
+        orc = "%.4f TOPS (%d), %s" % (cb["value"], cb["cores"], cb["sample"]) if cb else "-"
+        print("| %s | %.4f ms | %.3f TOPS | %s | %s | %s |" % (r["config"]["workload"], r["ms_per_step"], r["value"], kern, frac, orc))
+        if "quantize" in r:
+            q = r["quantize"]
+            print("| cfg5b quantize 2^28 fp32, 4-bit / 8-bit | %.4f / %.4f ms | %.0f / %.0f GB/s | quantize_kernel | %.1f %% / %.1f %% of 8000 GB/s (copy: %.0f GB/s) | - |"
+                  % (q["4bit"]["ms"], q["8bit"]["ms"], q["4bit"]["GBps"], q["8bit"]["GBps"],
+                     100 * q["4bit"]["frac_of_8TBps"], 100 * q["8bit"]["frac_of_8TBps"], q["torch_copy_reference"]["GBps"]))
+    print(json.dumps({wl: r for wl, r in rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
+    if args.table:
+        return table(args)
+    if args.workload in ("cfg3", "cfg4"):
+        return bench_network(args)
     import torch
     from paper_2302_12510_amd import binding as B
     from paper_2302_12510_amd import synth
@@ -153,20 +244,24 @@ def main():
         "vs_baseline": None, "dtype": "f16 MFMA inputs (exact), f32 accumulate", "data": "synthetic",
         "config": {"workload": name, "M": M, "N": N, "K": K, "a_fmt": list(a_fmt), "w_fmt": list(w_fmt),
                    "step": "absmax + quantize activations + gemm; weights pre-quantized"},
-        "roofline": {"bound": "mfma", "kernel": "dybit::fast::gemm_fast_kernel" if args.workload == "cfg5" else "dybit::gemm_kernel", "achieved": round(gemm_tflops, 2),
+        "roofline": {"bound": "mfma", "kernel": {"cfg5": "dybit::fast::gemm_fast_kernel (256x256 tiles)", "cfg2": "dybit::mid::gemm_mid_kernel (128x128 tiles, two k-groups)", "cfg1": "dybit::mid::gemm_mid_kernel (128x128 tiles)"}[args.workload], "achieved": round(gemm_tflops, 2),
                      "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / PEAK_FP16_MFMA_TFLOPS, 4),
                      "kernel_ms": round(gemm_ms, 4), "traffic": MEASURED_TRAFFIC[args.workload]},
     }
 
     # ---------------- the matrix cores alone, on decoded values of this workload ------------
-    # (the sustained clock of an MFMA-bound kernel depends on the operand values)
-    vals = B.dybit_dequantize(qa[: 9 * 512 * 8 * a_fmt[0] // 8], 9 * 512 * 8, sa, *a_fmt)
-    ops16 = (vals / sa).to(torch.float16).contiguous()
+    # (the sustained clock of an MFMA-bound kernel depends on the operand values: the A operand of
+    # the instruction gets activation values, the B operands weight values, as in the product)
+    def sample(q, fmt, s, need):
+        n = min(need, q.numel() * 8 // fmt[0])
+        v = B.dybit_dequantize(q[: n * fmt[0] // 8], n, s, *fmt) / s
+        return v.repeat((need + n - 1) // n)[:need]
+    ops16 = torch.cat([sample(qa, a_fmt, sa, 512 * 8), sample(qw, w_fmt, sw, 8 * 512 * 8)]).to(torch.float16).contiguous()
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
     wgs, iters = 256 * 2, 2000
     fl = B.dybit_diag_mfma_f16(ops16, wgs, iters, sink)
-    mf_ms, _ = time_events(lambda: B.dybit_diag_mfma_f16(ops16, wgs, iters, sink), 5, 1, torch)
+    mf_ms, _ = time_events(lambda: B.dybit_diag_mfma_f16(ops16, wgs, iters, sink), 5, 2, torch)
     out["roofline"]["mfma_only_measured_TFLOPs"] = round(fl / (mf_ms * 1e-3) / 1e12, 1)
     out["roofline"]["frac_of_mfma_only_measured"] = round(gemm_tflops / (fl / (mf_ms * 1e-3) / 1e12), 4)
 

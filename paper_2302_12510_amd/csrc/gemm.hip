@@ -99,7 +99,10 @@ __device__ __forceinline__ uint32_t fetch_code(const uint8_t *row, int64_t k)
 {
     const int64_t bit = k * BITS;
     uint32_t w = row[bit >> 3];
-    if (BITS == 6 && (bit & 7) > 2) w |= (uint32_t)row[(bit >> 3) + 1] << 8;
+    // a 6-bit code that starts past bit 2 of its byte continues in the next one; otherwise the same
+    // byte is read again (its copy lands above the field and is masked off): no branch, no read
+    // past the code's own bytes
+    if (BITS == 6) w |= (uint32_t)row[(bit >> 3) + ((bit & 7) > 2 ? 1 : 0)] << 8;
     return (w >> (bit & 7)) & ((1u << BITS) - 1);
 }
 
@@ -130,6 +133,26 @@ __device__ __forceinline__ Unit<BITS> load_unit_vec(const uint8_t *p)
     return u;
 }
 
+// 16 consecutive codes of a packed row fetched one by one (rows whose length or alignment rules
+// out vector loads); codes past K read as 0.  Every fetch is issued before any is used.
+template <int BITS>
+__device__ __forceinline__ Unit<BITS> load_unit_elems(const uint8_t *row, int64_t k0, int64_t K)
+{
+    Unit<BITS> u;
+#pragma unroll
+    for (int i = 0; i < BITS / 2; ++i) u.w[i] = 0;
+    uint32_t code[UNIT];
+#pragma unroll
+    for (int e = 0; e < UNIT; ++e) {
+        const bool in = k0 + e < K;
+        const uint32_t v = fetch_code<BITS>(row, in ? k0 + e : k0);
+        code[e] = in ? v : 0u;
+    }
+#pragma unroll
+    for (int e = 0; e < UNIT; ++e) unit_set_code<BITS>(u, e, code[e]);
+    return u;
+}
+
 // Row descriptor of the activation operand: a plain matrix row, or an output pixel of a convolution.
 struct RowA {
     const uint8_t *base;   // GEMM: start of the row; CONV: start of image b
@@ -146,8 +169,7 @@ __device__ __forceinline__ Unit<BITS> load_unit_A(const GemmArgs &g, const RowA 
     if (!r.valid || k0 >= g.K) return u;
     if (!CONV) {
         if (VEC) return load_unit_vec<BITS>(r.base + k0 * BITS / 8);
-        for (int e = 0; e < UNIT && k0 + e < g.K; ++e) unit_set_code<BITS>(u, e, fetch_code<BITS>(r.base, k0 + e));
-        return u;
+        return load_unit_elems<BITS>(r.base, k0, g.K);
     }
     const int64_t pix_bytes = (int64_t)g.Cin * BITS / 8;
     if (VEC) {   // the whole unit lies inside one filter tap
@@ -157,14 +179,26 @@ __device__ __forceinline__ Unit<BITS> load_unit_A(const GemmArgs &g, const RowA 
         if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.Wd) return u;       // padding: code 0 = 0.0
         return load_unit_vec<BITS>(r.base + ((int64_t)hi * g.Wd + wi) * pix_bytes + (int64_t)c0 * BITS / 8);
     }
-    for (int e = 0; e < UNIT && k0 + e < g.K; ++e) {
-        const int64_t k = k0 + e;
-        const int tap = (int)(k / g.Cin), c = (int)(k - (int64_t)tap * g.Cin);
-        const int fr = tap / g.kw, fs = tap - fr * g.kw;
+    // (filter row, filter column, channel) of k0 once, then counted up element by element.  All
+    // 16 fetches are issued before any is used (an element outside the image or past K fetches
+    // the image's first code and is then dropped), so their latencies overlap.
+    const int k32 = (int)k0, kend = (int)g.K;                          // K = kh kw Cin fits an int
+    int tap = k32 / g.Cin, c = k32 - tap * g.Cin;
+    int fr = tap / g.kw, fs = tap - fr * g.kw;
+    uint32_t code[UNIT];
+#pragma unroll
+    for (int e = 0; e < UNIT; ++e) {
         const int hi = r.hi0 + fr, wi = r.wi0 + fs;
-        if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.Wd) continue;
-        unit_set_code<BITS>(u, e, fetch_code<BITS>(r.base + ((int64_t)hi * g.Wd + wi) * pix_bytes, c));
+        const bool in = k32 + e < kend && (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.Wd;
+        const uint32_t v = fetch_code<BITS>(r.base + (in ? ((int64_t)hi * g.Wd + wi) * pix_bytes : 0), in ? c : 0);
+        code[e] = in ? v : 0u;
+        if (++c == g.Cin) {
+            c = 0;
+            if (++fs == g.kw) { fs = 0; ++fr; }
+        }
     }
+#pragma unroll
+    for (int e = 0; e < UNIT; ++e) unit_set_code<BITS>(u, e, code[e]);
     return u;
 }
 
@@ -176,8 +210,7 @@ __device__ __forceinline__ Unit<BITS> load_unit_W(const GemmArgs &g, const uint8
     for (int i = 0; i < BITS / 2; ++i) u.w[i] = 0;
     if (!valid || k0 >= g.K) return u;
     if (VEC) return load_unit_vec<BITS>(row + k0 * BITS / 8);
-    for (int e = 0; e < UNIT && k0 + e < g.K; ++e) unit_set_code<BITS>(u, e, fetch_code<BITS>(row, k0 + e));
-    return u;
+    return load_unit_elems<BITS>(row, k0, g.K);
 }
 
 template <int BA, int BW, bool CONV, bool VEC>
@@ -379,6 +412,7 @@ extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Ci
         (relu != 0 && relu != 1) || H > (1 << 24) || W > (1 << 24) || Cin > (1 << 24))
         return DYBIT_ERR_INVALID_ARG;
     if (H + 2 * (int64_t)pad < kh || W + 2 * (int64_t)pad < kw) return DYBIT_ERR_INVALID_ARG;
+    if ((int64_t)kh * kw > (1 << 24) || (int64_t)kh * kw * Cin > 0x7fffffff) return DYBIT_ERR_INVALID_ARG;   // K fits an int
     if ((Cin * x_fmt.bits) % 8 || (Cin * w_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
     const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
     if (B == 0 || Cout == 0) return DYBIT_OK;
