@@ -322,6 +322,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
 
     // epilogue: scale, bias, ReLU.  Accumulator v of a lane is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
     const float alpha = (*g.a_scale) * (*g.w_scale);
+    float mx = 0.0f;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
@@ -336,9 +337,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
                 float c = acc[i][j][v] * alpha + b;
                 if (g.relu) c = fmaxf(c, 0.0f);
                 g.C[m * g.ldc + n] = c;
+                mx = fmaxf(mx, fabsf(c));
             }
         }
     }
+    if (g.absmax_bits) fold_absmax(g.absmax_bits, mx);   // uniform branch: every lane of the wave takes part
 }
 
 template <int BA, int BW>
@@ -371,11 +374,11 @@ static void dispatch_gemm(const GemmArgs &g, int ba, int bw, bool conv, bool vec
 
 using namespace dybit;
 
-extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
-                                   const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
-                                   const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
-                                   const float *bias, int32_t relu,
-                                   float *C, int64_t ldc, dybit_stream stream)
+static dybit_status gemm_impl(int64_t M, int64_t N, int64_t K,
+                              const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                              const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                              const float *bias, int32_t relu,
+                              float *C, int64_t ldc, float *c_absmax, dybit_stream stream)
 {
     dybit_status st = check_fmt(a_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
@@ -390,6 +393,7 @@ extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
     g.a_signed = a_fmt.is_signed; g.w_signed = w_fmt.is_signed;
     g.a_scale = a_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
     g.C = C; g.ldc = ldc;
+    g.absmax_bits = reinterpret_cast<uint32_t *>(c_absmax);
     g.a_bytes = M * (K * a_fmt.bits / 8);
     g.w_bytes = N * (K * w_fmt.bits / 8);
     if (launch_gemm_tiled(g, a_fmt.bits, w_fmt.bits, false, (hipStream_t)stream)) return launch_status();
@@ -398,12 +402,31 @@ extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
     return launch_status();
 }
 
-extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
-                                     int32_t kh, int32_t kw, int32_t stride, int32_t pad,
-                                     const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
-                                     const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
-                                     const float *bias, int32_t relu,
-                                     float *Y, dybit_stream stream)
+extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
+                                   const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                                   const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                                   const float *bias, int32_t relu,
+                                   float *C, int64_t ldc, dybit_stream stream)
+{
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, bias, relu, C, ldc, nullptr, stream);
+}
+
+extern "C" dybit_status dybit_gemm_absmax(int64_t M, int64_t N, int64_t K,
+                                          const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                                          const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                                          const float *bias, int32_t relu,
+                                          float *C, int64_t ldc, float *c_absmax, dybit_stream stream)
+{
+    if (!c_absmax) return DYBIT_ERR_NULL;
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, bias, relu, C, ldc, c_absmax, stream);
+}
+
+static dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                const float *bias, int32_t relu,
+                                float *Y, float *y_absmax, dybit_stream stream)
 {
     dybit_status st = check_fmt(x_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
@@ -423,6 +446,7 @@ extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Ci
     g.a_signed = x_fmt.is_signed; g.w_signed = w_fmt.is_signed;
     g.a_scale = x_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
     g.C = Y; g.ldc = Cout;
+    g.absmax_bits = reinterpret_cast<uint32_t *>(y_absmax);
     g.H = (int)H; g.Wd = (int)W; g.Cin = (int)Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.stride = stride; g.pad = pad;
     g.a_bytes = B * H * W * (Cin * x_fmt.bits / 8);
@@ -431,4 +455,27 @@ extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Ci
     const bool vec = (Cin % UNIT == 0) && aligned16(X_codes) && aligned16(Wt_codes);
     dispatch_gemm(g, x_fmt.bits, w_fmt.bits, true, vec, (hipStream_t)stream);
     return launch_status();
+}
+
+extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                     int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                     const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                     const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                     const float *bias, int32_t relu,
+                                     float *Y, dybit_stream stream)
+{
+    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale,
+                       bias, relu, Y, nullptr, stream);
+}
+
+extern "C" dybit_status dybit_conv2d_absmax(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                            int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                            const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                            const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                            const float *bias, int32_t relu,
+                                            float *Y, float *y_absmax, dybit_stream stream)
+{
+    if (!y_absmax) return DYBIT_ERR_NULL;
+    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale,
+                       bias, relu, Y, y_absmax, stream);
 }

@@ -11,6 +11,7 @@ struct GemmArgs {
     int a_signed, w_signed;
     const float *a_scale, *w_scale, *bias;
     int relu;
+    uint32_t *absmax_bits;           // optional: running max |C| of the written values, as float bits (atomic max)
     float *C;
     int64_t ldc;
     // convolution geometry (conv only)
@@ -29,5 +30,23 @@ bool launch_gemm_mid_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st
 // Picks a tiled kernel for the problem (gemm_dispatch.cpp).  Returns false when the problem does
 // not meet their preconditions; the caller then uses the general kernel.
 bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hipStream_t st);
+
+// Folds a lane's maximum of |c| into the running maximum: wave reduction, then at most one atomic
+// per wave.  Non-negative floats order like their bit patterns; fmaxf has already dropped NaNs.
+// Atomics on one address serialise (about 10 ns each), and a large layer has tens of thousands of
+// waves, so a wave first reads the word (at device scope, from L2) and only competes when it would
+// raise it: the running maximum of a sequence is raised only about log(count) times.  A stale read
+// can only cause a needless atomic, never a wrong result.
+#ifdef __HIPCC__
+__device__ __forceinline__ void fold_absmax(uint32_t *absmax_bits, float mx)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    if ((threadIdx.x & 63) == 0) {
+        const uint32_t bits = __float_as_uint(mx);
+        if (bits > __hip_atomic_load(absmax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(absmax_bits, bits);
+    }
+}
+#endif
 
 }  // namespace dybit

@@ -236,6 +236,7 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
     // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU).  Accumulator v of a lane is row
     // 8 (v / 4) + 4 (lane / 32) + v % 4 and column lane % 32 of its 32 x 32 block.
     const float alpha = (*g.a_scale) * (*g.w_scale);
+    float mx = 0.0f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int64_t n = n0 + j * 32 + (lane & 31);
@@ -248,10 +249,14 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
                 const int64_t mr = m0 + (wave * RB + i) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
                 float c = acc[i][j][v] * alpha + b;
                 if (g.relu) c = fmaxf(c, 0.0f);
-                if (n_ok && mr < g.M) __builtin_nontemporal_store(c, g.C + mr * g.ldc + n);
+                if (n_ok && mr < g.M) {
+                    __builtin_nontemporal_store(c, g.C + mr * g.ldc + n);
+                    mx = fmaxf(mx, fabsf(c));
+                }
             }
         }
     }
+    if (g.absmax_bits) fold_absmax(g.absmax_bits, mx);
 }
 
 constexpr int kRowBlocks = 1;   // row blocks per wave of the instantiated kernels

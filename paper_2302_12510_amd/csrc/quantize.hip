@@ -66,6 +66,12 @@ __global__ __launch_bounds__(kThreads) void absmax_kernel(const float *__restric
     }
 }
 
+__global__ void absmax_to_scale_kernel(const float *absmax, float *scale_out, float inv_vmax)
+{
+    const float mx = *absmax;
+    *scale_out = (mx == 0.0f) ? 1.0f : mx * inv_vmax;   // division by 2^(m-1): exact
+}
+
 __global__ void absmax_finish_kernel(float *scale_out, float inv_vmax)
 {
     const float mx = *scale_out;
@@ -393,6 +399,17 @@ extern "C" dybit_status dybit_absmax_scale(const float *x, size_t n, dybit_fmt f
     if (n) hipLaunchKernelGGL(absmax_kernel, dim3(grid_for(n / 4 + 1, kThreads * 8, 256 * 4)), dim3(kThreads), 0, hs, x, n, scale_out);
     const int m = mag_bits(f.bits, f.is_signed);
     hipLaunchKernelGGL(absmax_finish_kernel, dim3(1), dim3(1), 0, hs, scale_out, 1.0f / (float)(1u << (m - 1)));
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_scale_from_absmax(const float *absmax, dybit_fmt f, float *scale_out, dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (!absmax || !scale_out) return DYBIT_ERR_NULL;
+    const int m = mag_bits(f.bits, f.is_signed);
+    hipLaunchKernelGGL(absmax_to_scale_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, absmax, scale_out,
+                       1.0f / (float)(1u << (m - 1)));
     return launch_status();
 }
 

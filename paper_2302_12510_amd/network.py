@@ -4,7 +4,10 @@ Per convolution / linear layer, on one stream and without host synchronisation:
     absmax scale of the fp32 input -> quantize to DyBit codes -> dybit_conv2d against the
     pre-quantized weights with the folded batch-norm shift as bias (and ReLU) -> fp32 output.
 This is the paper's dataflow with the write-back quantization done as a separate pass
-(Sec. III-B: activations and weights are stored as DyBit codes, partial sums stay FP).
+(Sec. III-B: activations and weights are stored as DyBit codes, partial sums stay FP).  Where a
+layer's output goes to the next encoder unchanged (or through a max-pool of non-negative values,
+which keeps the maximum), its max|y| is taken in the convolution's epilogue
+(dybit_conv2d_absmax + dybit_scale_from_absmax) instead of by a pass over the fp32 tensor.
 Residual additions and pooling run on the fp32 tensors with torch ops; they are glue, not
 part of the library.
 
@@ -30,8 +33,9 @@ def _pad_channels(cin: int, bits_a: int, bits_w: int) -> int:
 
 
 class DybitNetwork:
-    def __init__(self, layers, weights, bitwidths, device="cuda"):
+    def __init__(self, layers, weights, bitwidths, device="cuda", epilogue_absmax=True):
         self.layers = layers
+        self.epilogue_absmax = epilogue_absmax   # False: every scale from a pass over the fp32 tensor
         self.bitwidths = bitwidths
         self.device = device
         self.params = {}
@@ -60,6 +64,10 @@ class DybitNetwork:
         tensors needed to check that layer in isolation (input, scale, codes, raw output)."""
         acts = {"input": x}
         nonneg = {"input": False}
+        known_max = {}                       # tensor name -> device scalar holding max|tensor|
+        n_fused = sum(1 for l in self.layers if l["op"] in ("conv", "fc") and not l.get("add"))
+        max_words = torch.zeros(max(n_fused, 1), dtype=torch.float32, device=x.device)
+        next_word = 0
         out = x
         for l in self.layers:
             name, op = l["name"], l["op"]
@@ -68,6 +76,8 @@ class DybitNetwork:
                 y = torch.nn.functional.max_pool2d(src.permute(0, 3, 1, 2), l["k"], l["stride"], l["pad"])
                 out = y.permute(0, 2, 3, 1).contiguous()
                 nonneg[name] = nonneg[l["src"]]
+                if nonneg[name] and l["src"] in known_max and l["k"] >= l["stride"]:
+                    known_max[name] = known_max[l["src"]]     # every element is in some window
             elif op == "avgpool":
                 out = src.mean(dim=(1, 2), keepdim=True)
                 nonneg[name] = nonneg[l["src"]]
@@ -78,14 +88,23 @@ class DybitNetwork:
                 if p["cpad"] != C:
                     src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
                 flat = src.reshape(-1)
-                sa = B.dybit_absmax_scale(flat, *a_fmt)
+                if l["src"] in known_max:                       # zero padding of channels keeps the maximum
+                    sa = B.dybit_scale_from_absmax(known_max[l["src"]], *a_fmt)
+                else:
+                    sa = B.dybit_absmax_scale(flat, *a_fmt)
                 qa = B.dybit_quantize(flat, sa, *a_fmt)
                 fused_relu = bool(l.get("relu")) and not l.get("add")
                 k = p["k"]
                 stride, pad = (l["stride"], l["pad"]) if op == "conv" else (1, 0)
-                y = B.dybit_conv2d(Bn, H, W, p["cpad"], p["cout"], k, k, stride, pad,
-                                   qa, a_fmt, sa, p["w_codes"], p["w_fmt"], p["w_scale"],
-                                   p["bias"], fused_relu)
+                conv_args = (Bn, H, W, p["cpad"], p["cout"], k, k, stride, pad,
+                             qa, a_fmt, sa, p["w_codes"], p["w_fmt"], p["w_scale"])
+                if l.get("add") or not self.epilogue_absmax:
+                    y = B.dybit_conv2d(*conv_args, p["bias"], fused_relu)
+                else:                                           # y is this layer's final output
+                    word = max_words[next_word:next_word + 1]
+                    next_word += 1
+                    y = B.dybit_conv2d_absmax(*conv_args, word, p["bias"], fused_relu)
+                    known_max[name] = word
                 if record is not None:
                     record(name, {"x": src, "a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "y": y,
                                   "relu": fused_relu, "stride": stride, "pad": pad, "k": k, **p})

@@ -279,3 +279,57 @@ def test_general_kernel_on_tiled_shapes(force_kernel, a_fmt, w_fmt):
     got = run_gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011)
     want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011)
     assert_within(got, want, den)
+
+
+# ---- running maximum of the outputs taken in the epilogue ---------------------------
+@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "general"], indirect=True)
+@pytest.mark.parametrize("relu", [False, True])
+def test_gemm_absmax_matches_a_pass_over_the_output(force_kernel, relu):
+    """max|C| from the epilogue is the maximum of the values actually written (ragged tiles, bias,
+    ReLU), bit for bit, and the scale derived from it equals dybit_absmax_scale of C."""
+    rng = np.random.default_rng(17)
+    a_fmt, w_fmt = (8, True), (4, True)
+    M, N, K = 300, 261, 192
+    qa = random_codes(rng, (M, K), a_fmt)
+    qw = random_codes(rng, (N, K), w_fmt)
+    bias = rng.normal(0, 3, N).astype(np.float32)
+    mx = torch.zeros(1, dtype=torch.float32, device="cuda")
+    c = B.dybit_gemm_absmax(M, N, K, pack_rows_dev(qa, 8), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
+                            scalar(0.011), mx, dev(bias), relu)
+    torch.cuda.synchronize()
+    want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, relu)
+    assert_within(c.cpu().numpy(), want, den)
+    assert mx.item() == c.abs().max().item()
+    for fmt in ((4, False), (8, True)):
+        s_fused = B.dybit_scale_from_absmax(mx, *fmt)
+        s_pass = B.dybit_absmax_scale(c.reshape(-1), *fmt)
+        assert s_fused.item() == s_pass.item()
+    # a larger value already in the word stays; a smaller one is replaced
+    big = torch.full((1,), 1.0e9, dtype=torch.float32, device="cuda")
+    B.dybit_gemm_absmax(M, N, K, pack_rows_dev(qa, 8), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
+                        scalar(0.011), big, dev(bias), relu)
+    assert big.item() == 1.0e9
+
+
+@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "general"], indirect=True)
+def test_conv2d_absmax(force_kernel):
+    rng = np.random.default_rng(23)
+    x_fmt, w_fmt = (4, False), (4, True)
+    qx = random_codes(rng, (2, 9, 10, 64), x_fmt)
+    qw = random_codes(rng, (70, 3, 3, 64), w_fmt)
+    bias = rng.normal(0, 1, 70).astype(np.float32)
+    mx = torch.zeros(1, dtype=torch.float32, device="cuda")
+    y = B.dybit_conv2d_absmax(2, 9, 10, 64, 70, 3, 3, 1, 1, pack_rows_dev(qx.reshape(-1, 64), 4), x_fmt, scalar(0.3),
+                              pack_rows_dev(qw.reshape(-1, 64), 4), w_fmt, scalar(0.02), mx, dev(bias), True)
+    torch.cuda.synchronize()
+    want, den = R.conv2d(qx, x_fmt, 0.3, qw, w_fmt, 0.02, 1, 1, bias, True)
+    assert_within(y.cpu().numpy(), want, den)
+    assert mx.item() == y.abs().max().item()
+
+
+def test_scale_from_absmax_of_zero_is_one():
+    z = torch.zeros(1, dtype=torch.float32, device="cuda")
+    assert B.dybit_scale_from_absmax(z, 4, True).item() == 1.0
+    v = torch.full((1,), 6.0, dtype=torch.float32, device="cuda")
+    assert B.dybit_scale_from_absmax(v, 4, True).item() == 1.5       # 2^(m-1) = 4
+    assert B.dybit_scale_from_absmax(v, 8, False).item() == 6.0 / 128
