@@ -304,6 +304,26 @@ def main():
                                     "frac_of_measured_copy": round(q["4bit"]["GBps"] / q["torch_copy_reference"]["GBps"], 4)}
         del x, y
 
+    # ---------------- the 4-bit W / 4-bit A convolution (config 2), kernel alone ------------
+    if args.workload == "cfg5" and not args.no_quantize:
+        c2 = synth.config2()
+        f_x, f_w = (4, False), (4, True)
+        Bn, H, Wd, Cin = c2["X"].shape
+        Cout, kh, kw, _ = c2["Wt"].shape
+        X2 = torch.from_numpy(c2["X"]).cuda().reshape(-1)
+        W2 = torch.from_numpy(c2["Wt"]).cuda().reshape(-1)
+        sx2, sw2 = B.dybit_absmax_scale(X2, *f_x), B.dybit_absmax_scale(W2, *f_w)
+        qx2, qw2 = B.dybit_quantize(X2, sx2, *f_x), B.dybit_quantize(W2, sw2, *f_w)
+        Y2 = torch.empty((Bn, H, Wd, Cout), dtype=torch.float32, device="cuda")
+        conv2 = (Bn, H, Wd, Cin, Cout, kh, kw, c2["stride"], c2["pad"])
+        c2_ms, _ = time_events(lambda: B.dybit_conv2d(*conv2, qx2, f_x, sx2, qw2, f_w, sw2, out=Y2), 30, 5, torch)
+        fl2 = 2.0 * Bn * H * Wd * Cout * kh * kw * Cin
+        out["conv_4bit_w_a"] = {"workload": "cfg2 conv 3x3 256->256 on 14x14, batch 64, W 4-bit signed, A 4-bit unsigned",
+                                "kernel": "dybit::mid::gemm_mid_kernel (128x128 tiles, two k-groups)",
+                                "kernel_ms": round(c2_ms, 4), "TFLOPs": round(fl2 / (c2_ms * 1e-3) / 1e12, 1),
+                                "frac_of_fp16_mfma_peak": round(fl2 / (c2_ms * 1e-3) / 1e12 / PEAK_FP16_MFMA_TFLOPS, 4)}
+        del X2, W2, Y2
+
     # ---------------- CPU baseline: the plain C oracle on a bounded sample -----------------
     if not args.no_cpu_baseline:
         from oracle import c_ref, dybit_ref as R

@@ -114,26 +114,30 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
     // Tiles at or past ktiles (the prefetch of the last steps, and the padding step when the
     // number of K steps is odd) are fetched from an out-of-range offset: they read zeros.
     const int64_t ktiles = g.K / TK;
+    // K steps are loaded in order, so for a convolution the filter row, filter column and first
+    // channel of the next step are counted up instead of being divided out of k every time.
+    int a_fr = 0, a_fs = 0, a_c0 = 0;
     auto load_A = [&](int64_t kt, u32x4 (*raw)[NA]) {
         const int64_t k0 = kt * TK;
-        int tap_off = 0, fr = 0, fs = 0;
-        if (CONV) {
-            const int tap = (int)(k0 / g.Cin), c0 = (int)(k0 - (int64_t)tap * g.Cin);    // uniform
-            fr = tap / g.kw;
-            fs = tap - fr * g.kw;
-            tap_off = (fr * g.Wd + fs) * pix_bytes + c0 * CA::BITS / 8;
-        }
+        const int tap_off = CONV ? (a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * CA::BITS / 8 : 0;
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
             u32 off;
             if (CONV) {
-                const bool in = okA[i] && (unsigned)(hi0[i] + fr) < (unsigned)g.H && (unsigned)(wi0[i] + fs) < (unsigned)g.Wd;
+                const bool in = okA[i] && (unsigned)(hi0[i] + a_fr) < (unsigned)g.H && (unsigned)(wi0[i] + a_fs) < (unsigned)g.Wd;
                 off = (in && kt < ktiles) ? offA[i] + (u32)tap_off : kOob;            // padding reads code 0
             } else {
                 off = kt < ktiles ? offA[i] + (u32)(k0 * CA::BITS / 8) : kOob;
             }
 #pragma unroll
             for (int p = 0; p < NA; ++p) raw[i][p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
+        }
+        if (CONV) {
+            a_c0 += TK;
+            while (a_c0 >= g.Cin) {
+                a_c0 -= g.Cin;
+                if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
+            }
         }
     };
     auto load_W = [&](int64_t kt, u32x4 (*raw)[NW]) {

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
     constexpr int NW = CW::BITS / 4;
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave & 3, kgp = wave >> 2;                        // row strip and k-group of the wave
     const int kq = lane >> 5;                                        // which 32 k of the k-group's 64 the lane owns
 
@@ -108,19 +108,30 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
     const u32 wrW = (u32)wrow * ROW_BYTES + (u32)wq * 64;
     const u32 rdW = (u32)(lane & 31) * ROW_BYTES + (u32)kgp * 128 + (u32)kq * 64;   // block kk adds 16 B, column block j adds 32 rows
 
-    auto load_A = [&](int64_t kt, u32x4 *raw) {
-        const int64_t k0 = kt * TK + kgp * 64;                                          // uniform per wave
+    // K steps are loaded in order, so the position of the next one is counted up instead of being
+    // divided out of k every time: first k of the wave's k-group, and for a convolution its filter
+    // row, filter column and first channel (all uniform over the wave, hence the readfirstlane above).
+    int64_t a_k0 = kgp * 64;
+    int a_fr = 0, a_fs = 0, a_c0 = 0;
+    auto settle_tap = [&]() {
+        while (a_c0 >= g.Cin) {
+            a_c0 -= g.Cin;
+            if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
+        }
+    };
+    if (CONV) { a_c0 = kgp * 64; settle_tap(); }
+    auto load_A = [&](u32x4 *raw) {
         u32 off;
         if (CONV) {
-            const int tap = (int)(k0 / g.Cin), c0 = (int)(k0 - (int64_t)tap * g.Cin);
-            const int fr = tap / g.kw, fs = tap - fr * g.kw;
-            const bool in = okA && k0 < g.K && (unsigned)(hi0 + fr) < (unsigned)g.H && (unsigned)(wi0 + fs) < (unsigned)g.Wd;
-            off = in ? offA + (u32)((fr * g.Wd + fs) * pix_bytes + c0 * CA::BITS / 8) : kOob;   // padding reads code 0
+            const bool in = okA && a_k0 < g.K && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
+            off = in ? offA + (u32)((a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * CA::BITS / 8) : kOob;   // padding reads code 0
         } else {
-            off = k0 < g.K ? offA + (u32)(k0 * CA::BITS / 8) : kOob;
+            off = a_k0 < g.K ? offA + (u32)(a_k0 * CA::BITS / 8) : kOob;
         }
 #pragma unroll
         for (int p = 0; p < NA; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
+        a_k0 += TK;
+        if (CONV) { a_c0 += TK; settle_tap(); }
     };
     auto load_W = [&](int64_t kt, u32x4 *raw) {
         const int64_t k0 = kt * TK + wq * 32;
@@ -152,9 +163,9 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
     f16x8 fw[4], fa;
 
     // ---- prologue: W tile 0 decoded into stage 0, A/W tile 1 in flight, first fragments in registers
-    load_A(0, rawA[0]);
+    load_A(rawA[0]);
     load_W(0, rawW[0]);
-    load_A(1, rawA[1]);
+    load_A(rawA[1]);
     load_W(1, rawW[1]);
 #pragma unroll
     for (int q = 0; q < 4; ++q) stage_W(rawW[0], q, lds);
@@ -187,7 +198,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
             if (kk == 0) { stage_W(rawW[s ^ 1], 0, nxt); stage_W(rawW[s ^ 1], 1, nxt); }
             if (kk == 1) stage_W(rawW[s ^ 1], 2, nxt);
             if (kk == 2) stage_W(rawW[s ^ 1], 3, nxt);
-            if (kk == 2) load_A(kt + 2, rawA[s]);                   // tile kt's codes are fully decoded by now
+            if (kk == 2) load_A(rawA[s]);                           // K step kt + 2; tile kt's codes are fully decoded by now
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
