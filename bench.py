@@ -29,6 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP16_MFMA_TFLOPS = 2500.0   # MI355X dense fp16/bf16 matrix peak
+PEAK_FP8_MFMA_TFLOPS = 5000.0    # MI355X dense fp8 matrix peak (pairs of 4-bit formats run on it)
 PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E peak
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (units of 2 KiB and 1 KiB on
@@ -103,7 +104,7 @@ def bench_network(args):
         "metric": "DyBit GEMM effective TOPS (+ quantize GB/s), % of roofline",
         "value": round(flops / (ms * 1e-3) / 1e12, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16 MFMA inputs (exact), f32 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f16 or e4m3 MFMA inputs by layer (exact), f32 accumulate", "data": "synthetic",
         "config": {"workload": name, "gemms": len(shapes), "GMAC": round(flops / 2e9, 1),
                    "step": "per layer absmax + quantize + conv (bias, ReLU); pooling / residual adds in torch"},
         "roofline": None,
@@ -237,16 +238,18 @@ def main():
     value = flops / (ms_per_step * 1e-3) / 1e12
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
 
+    use_f8 = a_fmt[0] == 4 and w_fmt[0] == 4       # pairs of 4-bit formats run on the fp8 matrix path
+    peak = PEAK_FP8_MFMA_TFLOPS if use_f8 else PEAK_FP16_MFMA_TFLOPS
     out = {
         "metric": "DyBit GEMM effective TOPS (+ quantize GB/s), % of roofline",
         "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16 MFMA inputs (exact), f32 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": ("e4m3" if use_f8 else "f16") + " MFMA inputs (exact), f32 accumulate", "data": "synthetic",
         "config": {"workload": name, "M": M, "N": N, "K": K, "a_fmt": list(a_fmt), "w_fmt": list(w_fmt),
                    "step": "absmax + quantize activations + gemm; weights pre-quantized"},
-        "roofline": {"bound": "mfma", "kernel": {"cfg5": "dybit::fast::gemm_fast_kernel (256x256 tiles)", "cfg2": "dybit::mid::gemm_mid_kernel (128x128 tiles, two k-groups)", "cfg1": "dybit::mid::gemm_mid_kernel (128x128 tiles)"}[args.workload], "achieved": round(gemm_tflops, 2),
-                     "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gemm_tflops / PEAK_FP16_MFMA_TFLOPS, 4),
+        "roofline": {"bound": "mfma", "kernel": {"cfg5": "dybit::fast::gemm_fast_kernel (256x256 tiles, fp16 MFMA)", "cfg2": "dybit::f8::gemm_f8_kernel (128x128 tiles, two k-groups, e4m3 MFMA)", "cfg1": "dybit::f8::gemm_f8_kernel (128x128 tiles, e4m3 MFMA)"}[args.workload], "achieved": round(gemm_tflops, 2),
+                     "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(gemm_tflops / peak, 4),
                      "kernel_ms": round(gemm_ms, 4), "traffic": MEASURED_TRAFFIC[args.workload]},
     }
 
@@ -257,11 +260,18 @@ def main():
         n = min(need, q.numel() * 8 // fmt[0])
         v = B.dybit_dequantize(q[: n * fmt[0] // 8], n, s, *fmt) / s
         return v.repeat((need + n - 1) // n)[:need]
-    ops16 = torch.cat([sample(qa, a_fmt, sa, 512 * 8), sample(qw, w_fmt, sw, 8 * 512 * 8)]).to(torch.float16).contiguous()
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
-    wgs, iters = 256 * 2, 2000
-    fl = B.dybit_diag_mfma_f16(ops16, wgs, iters, sink)
-    mf_ms, _ = time_events(lambda: B.dybit_diag_mfma_f16(ops16, wgs, iters, sink), 5, 2, torch)
+    per_lane = 32 if use_f8 else 8                 # operand elements per lane of one instruction
+    ops = torch.cat([sample(qa, a_fmt, sa, 512 * per_lane), sample(qw, w_fmt, sw, 8 * 512 * per_lane)])
+    if use_f8:
+        ops = ops.to(torch.float8_e4m3fn).view(torch.uint8).contiguous()
+        diag, iters = B.dybit_diag_mfma_f8, 1000
+    else:
+        ops = ops.to(torch.float16).contiguous()
+        diag, iters = B.dybit_diag_mfma_f16, 2000
+    wgs = 256 * 2
+    fl = diag(ops, wgs, iters, sink)
+    mf_ms, _ = time_events(lambda: diag(ops, wgs, iters, sink), 5, 2, torch)
     out["roofline"]["mfma_only_measured_TFLOPs"] = round(fl / (mf_ms * 1e-3) / 1e12, 1)
     out["roofline"]["frac_of_mfma_only_measured"] = round(gemm_tflops / (fl / (mf_ms * 1e-3) / 1e12), 4)
 
@@ -304,6 +314,30 @@ def main():
                                     "frac_of_measured_copy": round(q["4bit"]["GBps"] / q["torch_copy_reference"]["GBps"], 4)}
         del x, y
 
+    # ---------------- the same product with 4-bit activations (4-bit W / 4-bit A) -----------
+    # Two 4-bit operands are exact in e4m3 and run on the fp8 matrix path: its peak is the roofline.
+    if args.workload == "cfg5" and not args.no_quantize:
+        f4 = (4, True)
+        sa4 = B.dybit_absmax_scale(A, *f4)
+        qa4 = B.dybit_quantize(A, sa4, *f4)
+        C4 = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        g4_ms, _ = time_events(lambda: B.dybit_gemm(M, N, K, qa4, f4, sa4, qw, w_fmt, sw, out=C4), args.steps, args.warmup, torch)
+        tf4 = flops / (g4_ms * 1e-3) / 1e12
+        # the fp8 matrix cores alone on e4m3 bytes of these values (torch has the dtype; the library only times it)
+        def sample8(q, s, need):
+            v = B.dybit_dequantize(q[: need // 2], need, s, *f4) / s
+            return v.to(torch.float8_e4m3fn).view(torch.uint8)
+        ops8 = torch.cat([sample8(qa4, sa4, 512 * 32), sample8(qw, sw, 8 * 512 * 32)]).contiguous()
+        fl8 = B.dybit_diag_mfma_f8(ops8, 512, 1000, sink)
+        m8_ms, _ = time_events(lambda: B.dybit_diag_mfma_f8(ops8, 512, 1000, sink), 5, 2, torch)
+        out["roofline_4bit_w_a"] = {"bound": "mfma", "kernel": "dybit::f8::gemm_f8_kernel (256x256 tiles, e4m3 MFMA)",
+                                    "workload": "the same 8192^3 product with the activations quantized to 4-bit signed",
+                                    "achieved": round(tf4, 2), "peak": PEAK_FP8_MFMA_TFLOPS, "unit": "TFLOP/s",
+                                    "frac": round(tf4 / PEAK_FP8_MFMA_TFLOPS, 4), "kernel_ms": round(g4_ms, 4), "traffic": None,
+                                    "mfma_only_measured_TFLOPs": round(fl8 / (m8_ms * 1e-3) / 1e12, 1),
+                                    "frac_of_mfma_only_measured": round(tf4 / (fl8 / (m8_ms * 1e-3) / 1e12), 4)}
+        del C4, qa4
+
     # ---------------- the 4-bit W / 4-bit A convolution (config 2), kernel alone ------------
     if args.workload == "cfg5" and not args.no_quantize:
         c2 = synth.config2()
@@ -319,9 +353,9 @@ def main():
         c2_ms, _ = time_events(lambda: B.dybit_conv2d(*conv2, qx2, f_x, sx2, qw2, f_w, sw2, out=Y2), 30, 5, torch)
         fl2 = 2.0 * Bn * H * Wd * Cout * kh * kw * Cin
         out["conv_4bit_w_a"] = {"workload": "cfg2 conv 3x3 256->256 on 14x14, batch 64, W 4-bit signed, A 4-bit unsigned",
-                                "kernel": "dybit::mid::gemm_mid_kernel (128x128 tiles, two k-groups)",
+                                "kernel": "dybit::f8::gemm_f8_kernel (128x128 tiles, two k-groups, e4m3 MFMA)",
                                 "kernel_ms": round(c2_ms, 4), "TFLOPs": round(fl2 / (c2_ms * 1e-3) / 1e12, 1),
-                                "frac_of_fp16_mfma_peak": round(fl2 / (c2_ms * 1e-3) / 1e12 / PEAK_FP16_MFMA_TFLOPS, 4)}
+                                "frac_of_fp8_mfma_peak": round(fl2 / (c2_ms * 1e-3) / 1e12 / PEAK_FP8_MFMA_TFLOPS, 4)}
         del X2, W2, Y2
 
     # ---------------- CPU baseline: the plain C oracle on a bounded sample -----------------

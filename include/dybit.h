@@ -152,6 +152,11 @@ dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream);
 dybit_status dybit_diag_mfma_f16(const void *operands, int32_t workgroups, int32_t iters,
                                  float *sink, double *flops_out, dybit_stream stream);
 
+/* The same for the fp8 (e4m3) MFMA instruction that pairs of 4-bit formats run on.
+ * operands [device]: 9 * 512 * 32 bytes (147,456 bytes) of e4m3 values, 16-byte aligned. */
+dybit_status dybit_diag_mfma_f8(const void *operands, int32_t workgroups, int32_t iters,
+                                float *sink, double *flops_out, dybit_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -54,6 +54,7 @@ def lib() -> C.CDLL:
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
         L.dybit_diag_mfma_f16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
+        L.dybit_diag_mfma_f8.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
         _lib = L
     return _lib
 
@@ -208,4 +209,12 @@ def dybit_diag_mfma_f16(operands: torch.Tensor, workgroups: int, iters: int, sin
     flops = C.c_double(0.0)
     _check(lib().dybit_diag_mfma_f16(_ptr(operands), workgroups, iters, _ptr(sink), C.byref(flops), _stream(stream)),
            "dybit_diag_mfma_f16")
+    return float(flops.value)
+
+
+def dybit_diag_mfma_f8(operands: torch.Tensor, workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """The same for the fp8 (e4m3) instruction; `operands` holds e4m3 bytes."""
+    flops = C.c_double(0.0)
+    _check(lib().dybit_diag_mfma_f8(_ptr(operands), workgroups, iters, _ptr(sink), C.byref(flops), _stream(stream)),
+           "dybit_diag_mfma_f8")
     return float(flops.value)

@@ -18,6 +18,7 @@ SOURCES = [
     ("gemm_fast.hip", "gemm_fast_w8", ["-DDYBIT_FAST_W=2"]),
     ("gemm_mid.hip", "gemm_mid_w4", ["-DDYBIT_MID_W=0"]),
     ("gemm_mid.hip", "gemm_mid_w8", ["-DDYBIT_MID_W=2"]),
+    ("gemm_f8.hip", "gemm_f8", []),
     ("diag.hip", "diag", []),
 ]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",

@@ -27,6 +27,10 @@ bool launch_gemm_fast_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t s
 bool launch_gemm_mid_w0(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 
+// fp8 matrix path for pairs of 4-bit formats with signed weights (gemm_f8.hip): the 256 x 256 tile
+// when `large`, else the 128 x 128 tile.
+bool launch_gemm_f8(const GemmArgs &g, bool conv, bool large, hipStream_t st);
+
 // Picks a tiled kernel for the problem (gemm_dispatch.cpp).  Returns false when the problem does
 // not meet their preconditions; the caller then uses the general kernel.
 bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hipStream_t st);

@@ -6,7 +6,8 @@
 // least decode work per MFMA and is used when its tiles can fill the 256 compute units and N is
 // wide enough for them; the 128 x 128 kernel takes the rest.  The environment variable
 // DYBIT_GEMM_KERNEL = large | mid | general overrides the choice whenever the named kernel's
-// preconditions hold (tests use it to reach a given kernel with small shapes).
+// preconditions hold (tests use it to reach a given kernel with small shapes); DYBIT_GEMM_MFMA=f16
+// keeps pairs of 4-bit operands on the fp16 kernels instead of the fp8 ones.
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -36,6 +37,10 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
         const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
         large = g.N > 128 && tiles256 >= 128;
     }
+    // two 4-bit operands: every value is exact in e4m3, so the fp8 matrix path (twice the fp16 rate,
+    // byte decoders) takes them unless DYBIT_GEMM_MFMA=f16 asks for the fp16 kernels
+    const char *mfma = getenv("DYBIT_GEMM_MFMA");
+    if (a_bits == 4 && w_bits == 4 && !(mfma && !strcmp(mfma, "f16"))) return launch_gemm_f8(g, conv, large, st);
     if (large) return w_bits == 4 ? launch_gemm_fast_w0(g, a_bits, conv, st) : launch_gemm_fast_w2(g, a_bits, conv, st);
     return w_bits == 4 ? launch_gemm_mid_w0(g, a_bits, conv, st) : launch_gemm_mid_w2(g, a_bits, conv, st);
 }

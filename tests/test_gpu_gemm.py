@@ -174,14 +174,42 @@ def test_config5a_shape_sampled_outputs():
     assert_within(got, want, den)
 
 
+def test_8192_cubed_4bit_w_a_sampled_outputs():
+    """The same 8192^3 product with 4-bit activations, as bench.py times it (fp8 matrix path,
+    256 x 256 tiles); the oracle evaluates a sample of rows and columns exactly."""
+    size = 8192
+    cfg = synth.config5a(size=size)
+    a_fmt, w_fmt = (4, True), (4, True)
+    sa, qa = oracle_codes(cfg["A"], a_fmt)
+    sw, qw = oracle_codes(cfg["W"], w_fmt)
+    c = B.dybit_gemm(size, size, size, pack_rows_dev(qa, 4), a_fmt, scalar(sa),
+                     pack_rows_dev(qw, 4), w_fmt, scalar(sw))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([[0, 255, 256, size - 1], rng.integers(0, size, 60)]))
+    cols = np.unique(np.concatenate([[0, 255, 256, size - 1], rng.integers(0, size, 508)]))
+    want, den = R.gemm(qa[rows], a_fmt, sa, qw[cols], w_fmt, sw)
+    got = c[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert_within(got, want, den)
+
+
 # ---- tiled MFMA kernels (256 x 256 and 128 x 128 tiles, in-register decode) --------
 TILED_PAIRS = [(a, w) for w in ((4, True), (8, True)) for a in ((4, True), (4, False), (8, True), (8, False))]
-KERNELS = ["large", "mid1", "mid2"]      # mid1 / mid2: the 128 x 128 kernel with one / two k-groups
+# mid1 / mid2: the 128 x 128 kernel with one / two k-groups.  Two 4-bit operands run on the fp8 matrix
+# path by default; the "-f16" entries keep them on the fp16 kernels (and are skipped for other pairs,
+# which are on the fp16 kernels anyway).
+KERNELS = ["large", "mid1", "mid2", "large-f16", "mid1-f16", "mid2-f16"]
 
 
 @pytest.fixture
 def force_kernel(monkeypatch, request):
     name = request.param
+    if name.endswith("-f16"):
+        fmts = [request.getfixturevalue(k) for k in ("a_fmt", "w_fmt", "x_fmt") if k in request.fixturenames]
+        if fmts and not all(f[0] == 4 for f in fmts):
+            pytest.skip("only pairs of 4-bit formats have an fp8 path to switch off")
+        monkeypatch.setenv("DYBIT_GEMM_MFMA", "f16")
+        name = name[:-4]
     if name.startswith("mid") and name != "mid":
         monkeypatch.setenv("DYBIT_MID_KGROUPS", name[3:])
         name = "mid"
@@ -257,7 +285,7 @@ def test_tiled_kernels_conv(force_kernel, x_fmt, w_fmt, geom):
     assert_within(got, want, den)
 
 
-@pytest.mark.parametrize("force_kernel", ["mid1", "mid2"], indirect=True)
+@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid1-f16", "mid2-f16"], indirect=True)
 def test_mid_kernel_wide_channels_conv(force_kernel):
     """Cin = 192: a 128-wide K step straddles two filter taps (each k-group follows its own tap)."""
     rng = np.random.default_rng(11)
@@ -284,17 +312,18 @@ def test_general_kernel_on_tiled_shapes(force_kernel, a_fmt, w_fmt):
 # ---- running maximum of the outputs taken in the epilogue ---------------------------
 @pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "general"], indirect=True)
 @pytest.mark.parametrize("relu", [False, True])
-def test_gemm_absmax_matches_a_pass_over_the_output(force_kernel, relu):
+@pytest.mark.parametrize("a_fmt", [(8, True), (4, False)])
+def test_gemm_absmax_matches_a_pass_over_the_output(force_kernel, relu, a_fmt):
     """max|C| from the epilogue is the maximum of the values actually written (ragged tiles, bias,
     ReLU), bit for bit, and the scale derived from it equals dybit_absmax_scale of C."""
     rng = np.random.default_rng(17)
-    a_fmt, w_fmt = (8, True), (4, True)
+    w_fmt = (4, True)
     M, N, K = 300, 261, 192
     qa = random_codes(rng, (M, K), a_fmt)
     qw = random_codes(rng, (N, K), w_fmt)
     bias = rng.normal(0, 3, N).astype(np.float32)
     mx = torch.zeros(1, dtype=torch.float32, device="cuda")
-    c = B.dybit_gemm_absmax(M, N, K, pack_rows_dev(qa, 8), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
+    c = B.dybit_gemm_absmax(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
                             scalar(0.011), mx, dev(bias), relu)
     torch.cuda.synchronize()
     want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, relu)
@@ -306,7 +335,7 @@ def test_gemm_absmax_matches_a_pass_over_the_output(force_kernel, relu):
         assert s_fused.item() == s_pass.item()
     # a larger value already in the word stays; a smaller one is replaced
     big = torch.full((1,), 1.0e9, dtype=torch.float32, device="cuda")
-    B.dybit_gemm_absmax(M, N, K, pack_rows_dev(qa, 8), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
+    B.dybit_gemm_absmax(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
                         scalar(0.011), big, dev(bias), relu)
     assert big.item() == 1.0e9
 
