@@ -26,6 +26,7 @@
 
 #include "dybit_codec.h"
 #include "gemm_args.h"
+#include "tile_epilogue.h"
 
 namespace dybit {
 namespace f8 {
@@ -273,27 +274,8 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
             for (int v = 0; v < 16; ++v) acc[j][v] += red[((wr * CB + j) * 16 + v) * 64 + lane];
     }
 
-    // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU).  Accumulator v of a lane is row
-    // 8 (v / 4) + 4 (lane / 32) + v % 4 and column lane % 32 of its 32 x 32 block.
-    const float alpha = (*g.a_scale) * (*g.w_scale);
-    float mx = 0.0f;
-#pragma unroll
-    for (int j = 0; j < CB; ++j) {
-        const int64_t n = n0 + j * 32 + (lane & 31);
-        const bool n_ok = n < g.N;
-        const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t mr = m0 + wr * 32 + 8 * (v >> 2) + 4 * kq + (v & 3);
-            float c = acc[j][v] * alpha + b;
-            if (g.relu) c = fmaxf(c, 0.0f);
-            if (n_ok && mr < g.M) {
-                __builtin_nontemporal_store(c, g.C + mr * g.ldc + n);
-                mx = fmaxf(mx, fabsf(c));
-            }
-        }
-    }
-    if (g.absmax_bits) fold_absmax(g.absmax_bits, mx);
+    // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU), running maximum
+    epilogue_strip<CB>(g, acc, m0 + wr * 32, n0);
 }
 
 template <int FA, int FW, int NWM, int KG>

@@ -28,6 +28,7 @@
 
 #include "dybit_codec.h"
 #include "gemm_args.h"
+#include "tile_epilogue.h"
 
 #ifndef DYBIT_FAST_W
 #error "compile with -DDYBIT_FAST_W=<weight format id> (0: 4-bit signed, 2: 8-bit signed)"
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
     constexpr int NW = CW::BITS / 4;                               // 128-bit loads per k-half
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kg = lane >> 5;                                        // k-group of the lane
 
     // ---- tile assignment: consecutive workgroup ids go to different XCDs (8 of them, 32 compute
@@ -237,30 +238,9 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
         step(kt + 1, std::integral_constant<int, 1>{});
     }
 
-    // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU).  Accumulator v of a lane is row
-    // 8 (v / 4) + 4 (lane / 32) + v % 4 and column lane % 32 of its 32 x 32 block.
-    const float alpha = (*g.a_scale) * (*g.w_scale);
-    float mx = 0.0f;
+    // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU), running maximum
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int64_t n = n0 + j * 32 + (lane & 31);
-        const bool n_ok = n < g.N;
-        const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
-#pragma unroll
-        for (int i = 0; i < RB; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t mr = m0 + (wave * RB + i) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                float c = acc[i][j][v] * alpha + b;
-                if (g.relu) c = fmaxf(c, 0.0f);
-                if (n_ok && mr < g.M) {
-                    __builtin_nontemporal_store(c, g.C + mr * g.ldc + n);
-                    mx = fmaxf(mx, fabsf(c));
-                }
-            }
-        }
-    }
-    if (g.absmax_bits) fold_absmax(g.absmax_bits, mx);
+    for (int i = 0; i < RB; ++i) epilogue_strip<8>(g, acc[i], m0 + (wave * RB + i) * 32, n0);
 }
 
 constexpr int kRowBlocks = 1;   // row blocks per wave of the instantiated kernels

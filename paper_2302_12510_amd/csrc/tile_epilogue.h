@@ -1,0 +1,72 @@
+// Epilogue shared by the tiled matrix-product kernels: C = acc * (sA sW) (+ bias) (ReLU), optional
+// running maximum of |C|, for the 32-row strip of accumulator blocks one wave holds.
+//
+// Accumulator v of a lane is row 8 (v / 4) + 4 (lane / 32) + v % 4 and column lane % 32 of its
+// 32 x 32 block.  The strip is stored through a buffer descriptor that starts at the strip's first
+// row and ends after its last valid row, with 32-bit byte offsets: a row past M falls outside the
+// descriptor and a column past N gets an offset of 2^31, so the hardware drops those stores and the
+// loop needs neither 64-bit address arithmetic nor per-element branches.
+#ifndef DYBIT_TILE_EPILOGUE_H
+#define DYBIT_TILE_EPILOGUE_H
+
+#include "dybit_codec.h"
+#include "gemm_args.h"
+
+namespace dybit {
+
+template <int CB>
+__device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB],
+                                               const int64_t m_strip, const int64_t n0)
+{
+    const int lane = threadIdx.x & 63, kq = lane >> 5;
+    const float alpha = (*g.a_scale) * (*g.w_scale);
+    const int64_t rows_left = g.M - m_strip;                       // uniform over the wave
+    const int rows = rows_left >= 32 ? 32 : rows_left > 0 ? (int)rows_left : 0;
+    float mx = 0.0f;
+    if (g.ldc < (1 << 23)) {
+        const uint32_t ldc4 = (uint32_t)g.ldc * 4u;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            g.C + m_strip * g.ldc, 0, (int)((uint32_t)rows * ldc4), 0x00020000);
+        const bool track = g.absmax_bits != nullptr;
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const int64_t n = n0 + j * 32 + (lane & 31);
+            const bool n_ok = n < g.N;
+            const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
+            uint32_t off = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float c = acc[j][v] * alpha + b;
+                if (g.relu) c = fmaxf(c, 0.0f);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c), rsrc, off, 0, 2);
+                if (track) {
+                    // a row past M holds bias only (its codes read as zeros): keep it out of the maximum
+                    const int r = 8 * (v >> 2) + 4 * kq + (v & 3);
+                    mx = fmaxf(mx, (n_ok && r < rows) ? fabsf(c) : 0.0f);
+                }
+                off += (v & 3) == 3 ? 5u * ldc4 : ldc4;             // rows 0-3, 8-11, 16-19, 24-27 (+ 4 kq)
+            }
+        }
+    } else {                                                        // leading dimension too large for 32-bit offsets
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const int64_t n = n0 + j * 32 + (lane & 31);
+            const bool n_ok = n < g.N;
+            const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = 8 * (v >> 2) + 4 * kq + (v & 3);
+                float c = acc[j][v] * alpha + b;
+                if (g.relu) c = fmaxf(c, 0.0f);
+                if (n_ok && r < rows) {
+                    __builtin_nontemporal_store(c, g.C + (m_strip + r) * g.ldc + n);
+                    mx = fmaxf(mx, fabsf(c));
+                }
+            }
+        }
+    }
+    if (g.absmax_bits) fold_absmax(g.absmax_bits, mx);
+}
+
+}  // namespace dybit
+#endif
