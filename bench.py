@@ -34,7 +34,8 @@ PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E peak
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (units of 2 KiB and 1 KiB on
 # this device, calibrated on a 1 GiB copy); the summaries are under profiles/.
-MEASURED_TRAFFIC = {"cfg5": 262302 * 2048 + 262144 * 1024, "cfg2": None, "cfg1": None}
+MEASURED_TRAFFIC = {"cfg5": 262322 * 2048 + 262203 * 1024, "cfg2": 2098 * 2048 + 12544 * 1024, "cfg1": None}
+MEASURED_TRAFFIC_GEMM_4BIT = 196734 * 2048 + 262348 * 1024
 MEASURED_TRAFFIC_QUANTIZE4 = 524376 * 2048 + 131072 * 1024
 
 
@@ -333,7 +334,7 @@ def main():
         out["roofline_4bit_w_a"] = {"bound": "mfma", "kernel": "dybit::f8::gemm_f8_kernel (256x256 tiles, e4m3 MFMA)",
                                     "workload": "the same 8192^3 product with the activations quantized to 4-bit signed",
                                     "achieved": round(tf4, 2), "peak": PEAK_FP8_MFMA_TFLOPS, "unit": "TFLOP/s",
-                                    "frac": round(tf4 / PEAK_FP8_MFMA_TFLOPS, 4), "kernel_ms": round(g4_ms, 4), "traffic": None,
+                                    "frac": round(tf4 / PEAK_FP8_MFMA_TFLOPS, 4), "kernel_ms": round(g4_ms, 4), "traffic": MEASURED_TRAFFIC_GEMM_4BIT,
                                     "mfma_only_measured_TFLOPs": round(fl8 / (m8_ms * 1e-3) / 1e12, 1),
                                     "frac_of_mfma_only_measured": round(tf4 / (fl8 / (m8_ms * 1e-3) / 1e12), 4)}
         del C4, qa4
