@@ -148,6 +148,10 @@ def table(args):
         frac = "%.1f %% of %.0f TFLOP/s" % (100 * rf["frac"], rf["peak"]) if rf else "-"
         orc = "%.4f TOPS (%d), %s" % (cb["value"], cb["cores"], cb["sample"]) if cb else "-"
         print("| %s | %.4f ms | %.3f TOPS | %s | %s | %s |" % (r["config"]["workload"], r["ms_per_step"], r["value"], kern, frac, orc))
+        if "roofline_4bit_w_a" in r:
+            f = r["roofline_4bit_w_a"]
+            print("| 8192^3 GEMM at 4-bit W / 4-bit A (same tensors, activations quantized to 4-bit signed) | %.4f ms (kernel) | %.1f TOPS | %s | %.1f %% of %.0f TFLOP/s | - |"
+                  % (f["kernel_ms"], f["achieved"], f["kernel"], 100 * f["frac"], f["peak"]))
         if "quantize" in r:
             q = r["quantize"]
             print("| cfg5b quantize 2^28 fp32, 4-bit / 8-bit | %.4f / %.4f ms | %.0f / %.0f GB/s | quantize_kernel | %.1f %% / %.1f %% of 8000 GB/s (copy: %.0f GB/s) | - |"
@@ -375,7 +379,7 @@ def main():
             sflops = 2.0 * rows * N * K
         else:
             Bn, H, Wd, Cin, Cout, kh, kw, stride, pad = conv
-            nb = min(Bn, 16)
+            nb = Bn
             x_codes = R.unpack(qa_h[: nb * H * Wd * Cin * a_fmt[0] // 8], nb * H * Wd * Cin, a_fmt[0]).reshape(nb, H, Wd, Cin)
             w_codes = R.unpack(qw_h, Cout * kh * kw * Cin, w_fmt[0]).reshape(Cout, kh, kw, Cin)
             t0 = time.perf_counter()
