@@ -11,8 +11,13 @@ of a 2^28-element Laplace tensor at 4 and 8 bits, which is reported separately.
 
 Prints ONE JSON line.  `value` is the effective throughput of the whole step,
 2*M*N*K / step time, in TOPS.  `roofline` describes the GEMM kernel alone (HIP events
-around its launches inside the timed region), `quantize` the HBM-bound quantize pass,
-`cpu_baseline` the plain C oracle timed on the host cores over a bounded sample.
+around its launches inside the timed region), `quantize` / `roofline_quantize` the HBM-bound
+quantize pass, `cpu_baseline` the plain C oracle timed on the host cores over a bounded sample.
+Two more objects come from extra kernels timed after the step: `roofline_4bit_w_a` (the same
+8192^3 product with the activations quantized to 4 bits, which runs on the fp8 matrix path)
+and `conv_4bit_w_a` (the 3x3 convolution of configuration 2).
+
+`--workload cfg1|cfg2|cfg3|cfg4` time the other configurations; `--table` runs all of them.
 """
 from __future__ import annotations
 
