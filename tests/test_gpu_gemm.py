@@ -97,6 +97,24 @@ def test_ldc_and_untouched_padding():
     assert np.all(got[:, 20:] == -777.0)
 
 
+@pytest.mark.parametrize("a_fmt", [(4, False), (8, True)])
+def test_ldc_and_untouched_padding_tiled_kernels(a_fmt):
+    """The tiled kernels' epilogue (buffer stores) with a leading dimension larger than N and
+    ragged last rows / columns: nothing outside the M x N block is written."""
+    w_fmt = (4, True)
+    rng = np.random.default_rng(10)
+    M, N, K, ldc = 300, 70, 128, 96
+    qa = random_codes(rng, (M, K), a_fmt); qw = random_codes(rng, (N, K), w_fmt)
+    out = torch.full((M + 40, ldc), -777.0, dtype=torch.float32, device="cuda")
+    B.dybit_gemm(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(1.0), pack_rows_dev(qw, 4), w_fmt, scalar(1.0),
+                 out=out, ldc=ldc)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want, den = R.gemm(qa, a_fmt, 1.0, qw, w_fmt, 1.0)
+    assert_within(got[:M, :N], want, den)
+    assert np.all(got[:M, N:] == -777.0) and np.all(got[M:] == -777.0)
+
+
 def test_k_zero_writes_bias():
     bias = np.arange(7, dtype=np.float32) - 3
     c = B.dybit_gemm(5, 7, 0, None, (4, True), scalar(1.0), None, (4, True), scalar(1.0), dev(bias), True)
