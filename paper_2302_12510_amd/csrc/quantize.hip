@@ -243,9 +243,12 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
     }
 }
 
-// 6-bit: 16 consecutive elements per lane -> 96 bits = three words.
-template <bool SIGNED>
-__global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__restrict__ x, size_t n16,
+// 6-bit: like the kernel above, each lane takes a coalesced float4 and produces four codes (24 bits);
+// four neighbouring lanes' 96 bits are three words.  Lane k of a group of four (k < 3) fetches its
+// right neighbour's 24 bits and stores word k = (own >> 8k) | (neighbour << (24 - 8k)), so loads and
+// stores are both fully coalesced.  n4 must be a multiple of 4 (whole groups of 16 elements).
+template <bool SIGNED, int UNROLL>
+__global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__restrict__ x, size_t n4,
                                                              const float *__restrict__ scale,
                                                              uint8_t *__restrict__ out)
 {
@@ -256,36 +259,37 @@ __global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__rest
     }
     const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
     uint32_t *o = reinterpret_cast<uint32_t *>(out);
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (size_t)gridDim.x * kThreads) {
-        float e[16];
+    const int k = threadIdx.x & 3;
+    const size_t per_block = (size_t)kThreads * UNROLL;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
+        f32x4 v[UNROLL];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const f32x4 v = __builtin_nontemporal_load(x4 + 4 * i + u);
-            e[4 * u] = v.x; e[4 * u + 1] = v.y; e[4 * u + 2] = v.z; e[4 * u + 3] = v.w;
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t i = base + (size_t)u * kThreads + threadIdx.x;
+            v[u] = (i < n4) ? __builtin_nontemporal_load(x4 + i) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        uint32_t c[16];
-        bool any_redo = si.all_exact;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            bool redo;
-            c[k] = quantize_fast<6, SIGNED>(e[k], si.rinv, redo);
-            if (SIGNED && (c[k] & 31u) == 0u) c[k] = 0u;
-            any_redo |= redo;
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t i = base + (size_t)u * kThreads + threadIdx.x;
+            const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            uint32_t c[4];
+            bool any_redo = si.all_exact;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bool redo;
+                c[j] = quantize_fast<6, SIGNED>(e[j], si.rinv, redo);
+                if (SIGNED && (c[j] & 31u) == 0u) c[j] = 0u;
+                any_redo |= redo;
+            }
+            if (any_redo) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c[j] = quantize_exact<6, SIGNED>(e[j], si.s);
+            }
+            const uint32_t own = c[0] | (c[1] << 6) | (c[2] << 12) | (c[3] << 18);
+            const uint32_t right = __shfl_down(own, 1, 64);              // every lane takes part; lane 3 of a group ignores it
+            const uint32_t w = (own >> (8 * k)) | (right << (24 - 8 * k));
+            if (k < 3 && i < n4) __builtin_nontemporal_store(w, o + (i >> 2) * 3 + k);
         }
-        if (any_redo) {
-#pragma unroll
-            for (int k = 0; k < 16; ++k) c[k] = quantize_exact<6, SIGNED>(e[k], si.s);
-        }
-        uint64_t lo = 0, hi = 0;   // lo: codes 0..9 (60 bits) + low 4 bits of code 10; hi: rest
-#pragma unroll
-        for (int k = 0; k < 10; ++k) lo |= (uint64_t)c[k] << (6 * k);
-        lo |= (uint64_t)(c[10] & 15u) << 60;
-        hi = c[10] >> 4;
-#pragma unroll
-        for (int k = 11; k < 16; ++k) hi |= (uint64_t)c[k] << (6 * (k - 11) + 2);
-        o[3 * i] = (uint32_t)lo;
-        o[3 * i + 1] = (uint32_t)(lo >> 32);
-        o[3 * i + 2] = (uint32_t)hi;
     }
 }
 
@@ -367,8 +371,9 @@ static void launch_quantize(const float *x, size_t n, const float *scale, uint8_
     constexpr int UNROLL = DYBIT_QUANT_UNROLL;
     if (BITS == 6) {
         const size_t n16 = n / 16;
-        if (n16) hipLaunchKernelGGL((quantize6_kernel<SIGNED>), dim3(grid_for(n16, kThreads, 256 * 128)), dim3(kThreads), 0, st,
-                                    x, n16, scale, out);
+        if (n16) hipLaunchKernelGGL((quantize6_kernel<SIGNED, UNROLL>),
+                                    dim3(grid_for(4 * n16, kThreads * UNROLL, 256 * DYBIT_QUANT_BLOCKS_PER_CU)), dim3(kThreads), 0, st,
+                                    x, 4 * n16, scale, out);
         const size_t first = n16 * 16;
         if (first < n) {
             const size_t groups = (n - first + 3) / 4;
