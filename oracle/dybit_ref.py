@@ -284,13 +284,17 @@ def _decode_scaled_int(codes: np.ndarray, bits: int, signed: bool) -> np.ndarray
     return cb[np.asarray(codes, dtype=np.int64)]
 
 
-def gemm(a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale, bias=None, relu=False):
-    """C[m,n] = sA*sW * sum_k value(A[m,k]) * value(W[n,k]) (+ bias[n]) (ReLU).
+def gemm(a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale, bias=None, relu=False, residual=None):
+    """C[m,n] = sA*sW * sum_k value(A[m,k]) * value(W[n,k]) (+ bias[n]) (+ residual[m,n]) (ReLU).
+
+    `residual` is the identity shortcut of the ResNet workloads of Sec. IV: an fp32 tensor of
+    the output's shape added to the floating-point intermediate result before the ReLU (and
+    before anything is written back).
 
     a_codes: [M][K] unpacked codes, w_codes: [N][K]; *_fmt = (bits, signed).
     The sum is taken over exact integers (values times 2^(m-1)) in float64;
     every partial sum stays below 2^53, so the order of summation cannot matter.
-    Returns (C float64, D float64) with D[m,n] = sA*sW*sum_k|a*w| (+|bias|), the
+    Returns (C float64, D float64) with D[m,n] = sA*sW*sum_k|a*w| (+|bias|) (+|residual|), the
     tolerance denominator.
     """
     ia = _decode_scaled_int(a_codes, *a_fmt)
@@ -308,6 +312,10 @@ def gemm(a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale, bias=None, relu=False
         b = np.asarray(bias, dtype=np.float32).astype(np.float64)
         c = c + b[None, :]
         d = d + np.abs(b)[None, :]
+    if residual is not None:
+        r = np.asarray(residual, dtype=np.float32).astype(np.float64).reshape(c.shape)
+        c = c + r
+        d = d + np.abs(r)
     if relu:
         c = np.maximum(c, 0.0)
     return c, d
@@ -360,8 +368,9 @@ def im2col(x_codes: np.ndarray, kh: int, kw: int, stride: int, pad: int) -> np.n
 
 
 def conv2d(x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, stride, pad,
-           bias=None, relu=False):
-    """x_codes [B][H][W][Cin], w_codes [Cout][kh][kw][Cin] (unpacked codes).
+           bias=None, relu=False, residual=None):
+    """x_codes [B][H][W][Cin], w_codes [Cout][kh][kw][Cin] (unpacked codes); residual, if given,
+    has the output's shape [B][Ho][Wo][Cout].
     Returns (Y float64 [B][Ho][Wo][Cout], D same shape)."""
     x_codes = np.asarray(x_codes, dtype=np.uint8)
     w_codes = np.asarray(w_codes, dtype=np.uint8)
@@ -371,7 +380,8 @@ def conv2d(x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, stride, pad,
     Ho = conv_out_size(H, kh, stride, pad)
     Wo = conv_out_size(W, kw, stride, pad)
     cols = im2col(x_codes, kh, kw, stride, pad)
-    c, d = gemm(cols, x_fmt, x_scale, w_codes.reshape(Cout, -1), w_fmt, w_scale, bias, relu)
+    res = None if residual is None else np.asarray(residual, dtype=np.float32).reshape(B * Ho * Wo, Cout)
+    c, d = gemm(cols, x_fmt, x_scale, w_codes.reshape(Cout, -1), w_fmt, w_scale, bias, relu, res)
     return c.reshape(B, Ho, Wo, Cout), d.reshape(B, Ho, Wo, Cout)
 
 

@@ -99,6 +99,19 @@ def test_conv2d_vs_torch_float64(stride, pad, k):
     assert np.allclose(y, want, rtol=1e-13, atol=1e-13)
     yc, dc = c_ref.conv2d(x, x_fmt, sx, w, w_fmt, sw, stride, pad, bias, relu=True)
     assert np.array_equal(yc, y) and np.array_equal(dc, d)
+    # identity shortcut (the ResNet workloads): added before the ReLU; a sign error, an addition
+    # after the ReLU or a transposed layout all change the result
+    res = rng.normal(0, 1, want.shape).astype(np.float32)
+    yr, dr = R.conv2d(x, x_fmt, sx, w, w_fmt, sw, stride, pad, bias, relu=True, residual=res)
+    lin = torch.nn.functional.conv2d(vx, vw, torch.from_numpy(bias.astype(np.float64)),
+                                     stride=stride, padding=pad).permute(0, 2, 3, 1).numpy()
+    want_r = np.maximum(lin + res.astype(np.float64), 0.0)
+    assert np.allclose(yr, want_r, rtol=1e-13, atol=1e-13)
+    assert not np.allclose(yr, np.maximum(lin, 0.0) + res, atol=1e-6)       # not "ReLU, then add"
+    y0, d0 = R.conv2d(x, x_fmt, sx, w, w_fmt, sw, stride, pad, bias, relu=False)
+    assert np.array_equal(dr, d0 + np.abs(res.astype(np.float64)))          # tolerance denominator grows by |residual|
+    yz, _ = R.conv2d(x, x_fmt, sx, w, w_fmt, sw, stride, pad, bias, relu=True, residual=np.zeros_like(res))
+    assert np.array_equal(yz, y)
 
 
 def test_c_gemm_matches_numpy_on_config1_shape():
