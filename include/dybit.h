@@ -114,25 +114,32 @@ dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t 
                           const float *bias, int32_t relu,
                           float *Y, dybit_stream stream);
 
-/* Write-back support (Sec. III-B: results leave the array as DyBit codes, so with tensor-level scales
- * the encoder of the next layer needs max|result| first).  These variants do what dybit_gemm /
- * dybit_conv2d do and also fold the maximum of |value| over the values they write (after bias and
- * ReLU, NaNs ignored) into a running maximum: *absmax = max(*absmax, max|C|).  That spares the pass
- * over C that dybit_absmax_scale would need; finish with dybit_scale_from_absmax.
- * c_absmax / y_absmax [device, in/out]: 1 float, non-negative on entry (0 before the first
- * contributing call), updated with atomic maxima on its bit pattern.  NULL is DYBIT_ERR_NULL.
+/* Extended epilogue.  These variants do what dybit_gemm / dybit_conv2d do, with two optional additions:
+ *
+ *   residual  the identity shortcut of the residual networks the method is evaluated on (Sec. IV,
+ *             ResNet-18 / ResNet-50): C = acc * sA sW + bias + residual, then the ReLU.  An fp32
+ *             tensor laid out exactly like the output (GEMM: M rows of ldc floats; convolution:
+ *             [B][Ho][Wo][Cout]); it must not overlap the output.  NULL: no shortcut.
+ *   absmax    write-back support (Sec. III-B: results leave the array as DyBit codes, so with
+ *             tensor-level scales the encoder of the next layer needs max|result| first): the maximum
+ *             of |value| over the values written (after bias, shortcut and ReLU, NaNs ignored) is
+ *             folded into a running maximum, *absmax = max(*absmax, max|C|).  That spares the pass
+ *             over C that dybit_absmax_scale would need; finish with dybit_scale_from_absmax.
+ *             1 float [device, in/out], non-negative on entry (0 before the first contributing call),
+ *             updated with atomic maxima on its bit pattern.  NULL: not tracked.
+ *
  * All other arguments: as in dybit_gemm / dybit_conv2d. */
-dybit_status dybit_gemm_absmax(int64_t M, int64_t N, int64_t K,
-                               const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
-                               const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
-                               const float *bias, int32_t relu,
-                               float *C, int64_t ldc, float *c_absmax, dybit_stream stream);
-dybit_status dybit_conv2d_absmax(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
-                                 int32_t kh, int32_t kw, int32_t stride, int32_t pad,
-                                 const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
-                                 const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
-                                 const float *bias, int32_t relu,
-                                 float *Y, float *y_absmax, dybit_stream stream);
+dybit_status dybit_gemm_ex(int64_t M, int64_t N, int64_t K,
+                           const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                           const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                           const float *bias, const float *residual, int32_t relu,
+                           float *C, int64_t ldc, float *c_absmax, dybit_stream stream);
+dybit_status dybit_conv2d_ex(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                             int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                             const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                             const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                             const float *bias, const float *residual, int32_t relu,
+                             float *Y, float *y_absmax, dybit_stream stream);
 
 /* *scale_out = *absmax / 2^(m-1), or 1.0 when *absmax == 0: the last step of dybit_absmax_scale,
  * for a maximum obtained otherwise.  absmax, scale_out [device]: 1 float each (may be the same word). */

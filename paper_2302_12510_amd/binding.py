@@ -49,8 +49,8 @@ def lib() -> C.CDLL:
         L.dybit_dequantize.argtypes = [vp, sz, Fmt, vp, vp, vp]
         L.dybit_gemm.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, i64, vp]
         L.dybit_conv2d.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp]
-        L.dybit_gemm_absmax.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, i64, vp, vp]
-        L.dybit_conv2d_absmax.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp, vp]
+        L.dybit_gemm_ex.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, i64, vp, vp]
+        L.dybit_conv2d_ex.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, vp]
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
         L.dybit_diag_mfma_f16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
@@ -162,31 +162,34 @@ def dybit_conv2d(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: int, 
     return out
 
 
-def dybit_gemm_absmax(M: int, N: int, K: int, a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale, c_absmax,
-                      bias=None, relu: bool = False, out: torch.Tensor | None = None, ldc: int | None = None, stream=None):
-    """dybit_gemm that also folds max|C| into the device scalar c_absmax (float32, >= 0 on entry)."""
+def dybit_gemm_ex(M: int, N: int, K: int, a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale,
+                  bias=None, residual=None, relu: bool = False, absmax=None,
+                  out: torch.Tensor | None = None, ldc: int | None = None, stream=None):
+    """dybit_gemm with the optional shortcut tensor `residual` (laid out like the output) and the
+    optional running maximum `absmax` (device float32 scalar, >= 0 on entry)."""
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=a_scale.device)
     if ldc is None:
         ldc = N
-    _check(lib().dybit_gemm_absmax(M, N, K, _ptr(a_codes), fmt(*a_fmt), _ptr(a_scale),
-                                   _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), int(bool(relu)),
-                                   _ptr(out), ldc, _ptr(c_absmax), _stream(stream)), "dybit_gemm_absmax")
+    _check(lib().dybit_gemm_ex(M, N, K, _ptr(a_codes), fmt(*a_fmt), _ptr(a_scale),
+                               _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), _ptr(residual), int(bool(relu)),
+                               _ptr(out), ldc, _ptr(absmax), _stream(stream)), "dybit_gemm_ex")
     return out
 
 
-def dybit_conv2d_absmax(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: int, stride: int, pad: int,
-                        x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, y_absmax, bias=None, relu: bool = False,
-                        out: torch.Tensor | None = None, stream=None):
-    """dybit_conv2d that also folds max|Y| into the device scalar y_absmax (float32, >= 0 on entry)."""
+def dybit_conv2d_ex(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: int, stride: int, pad: int,
+                    x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, bias=None, residual=None, relu: bool = False,
+                    absmax=None, out: torch.Tensor | None = None, stream=None):
+    """dybit_conv2d with the optional shortcut tensor `residual` ([B][Ho][Wo][Cout]) and the optional
+    running maximum `absmax` (device float32 scalar, >= 0 on entry)."""
     Ho = (H + 2 * pad - kh) // stride + 1
     Wo = (W + 2 * pad - kw) // stride + 1
     if out is None:
         out = torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device=x_scale.device)
-    _check(lib().dybit_conv2d_absmax(B, H, W, Cin, Cout, kh, kw, stride, pad,
-                                     _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
-                                     _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), int(bool(relu)),
-                                     _ptr(out), _ptr(y_absmax), _stream(stream)), "dybit_conv2d_absmax")
+    _check(lib().dybit_conv2d_ex(B, H, W, Cin, Cout, kh, kw, stride, pad,
+                                 _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
+                                 _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), _ptr(residual), int(bool(relu)),
+                                 _ptr(out), _ptr(absmax), _stream(stream)), "dybit_conv2d_ex")
     return out
 
 

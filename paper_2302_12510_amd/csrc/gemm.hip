@@ -13,6 +13,7 @@
 #include "dybit_device.h"
 #include "dybit_host.h"
 #include "gemm_args.h"
+#include "tile_epilogue.h"
 
 namespace dybit {
 
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
     __shared__ uint32_t lutA[lut_entries<BA>()];
     __shared__ uint32_t lutW[lut_entries<BW>()];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t tiles_n = (g.N + BN - 1) / BN;
     const int64_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
@@ -320,28 +321,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
         __syncthreads();
     }
 
-    // epilogue: scale, bias, ReLU.  Accumulator v of a lane is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
-    const float alpha = (*g.a_scale) * (*g.w_scale);
-    float mx = 0.0f;
+    // epilogue (shared with the tiled kernels): each wave stores its two 32-row strips of 64 columns
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
-        if (n >= g.N) continue;
-        const float b = g.bias ? g.bias[n] : 0.0f;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (m >= g.M) continue;
-                float c = acc[i][j][v] * alpha + b;
-                if (g.relu) c = fmaxf(c, 0.0f);
-                g.C[m * g.ldc + n] = c;
-                mx = fmaxf(mx, fabsf(c));
-            }
-        }
-    }
-    if (g.absmax_bits) fold_absmax(g.absmax_bits, mx);   // uniform branch: every lane of the wave takes part
+    for (int i = 0; i < 2; ++i) epilogue_strip<2>(g, acc[i], m0 + wm * 64 + i * 32, n0 + wn * 64);
 }
 
 template <int BA, int BW>
@@ -378,7 +360,7 @@ static dybit_status gemm_impl(int64_t M, int64_t N, int64_t K,
                               const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
                               const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
                               const float *bias, int32_t relu,
-                              float *C, int64_t ldc, float *c_absmax, dybit_stream stream)
+                              float *C, int64_t ldc, const float *residual, float *c_absmax, dybit_stream stream)
 {
     dybit_status st = check_fmt(a_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
@@ -393,6 +375,7 @@ static dybit_status gemm_impl(int64_t M, int64_t N, int64_t K,
     g.a_signed = a_fmt.is_signed; g.w_signed = w_fmt.is_signed;
     g.a_scale = a_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
     g.C = C; g.ldc = ldc;
+    g.residual = residual;
     g.absmax_bits = reinterpret_cast<uint32_t *>(c_absmax);
     g.a_bytes = M * (K * a_fmt.bits / 8);
     g.w_bytes = N * (K * w_fmt.bits / 8);
@@ -408,17 +391,16 @@ extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
                                    const float *bias, int32_t relu,
                                    float *C, int64_t ldc, dybit_stream stream)
 {
-    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, bias, relu, C, ldc, nullptr, stream);
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, bias, relu, C, ldc, nullptr, nullptr, stream);
 }
 
-extern "C" dybit_status dybit_gemm_absmax(int64_t M, int64_t N, int64_t K,
-                                          const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
-                                          const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
-                                          const float *bias, int32_t relu,
-                                          float *C, int64_t ldc, float *c_absmax, dybit_stream stream)
+extern "C" dybit_status dybit_gemm_ex(int64_t M, int64_t N, int64_t K,
+                                      const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                                      const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                                      const float *bias, const float *residual, int32_t relu,
+                                      float *C, int64_t ldc, float *c_absmax, dybit_stream stream)
 {
-    if (!c_absmax) return DYBIT_ERR_NULL;
-    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, bias, relu, C, ldc, c_absmax, stream);
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, bias, relu, C, ldc, residual, c_absmax, stream);
 }
 
 static dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
@@ -426,7 +408,7 @@ static dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, in
                                 const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
                                 const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
                                 const float *bias, int32_t relu,
-                                float *Y, float *y_absmax, dybit_stream stream)
+                                float *Y, const float *residual, float *y_absmax, dybit_stream stream)
 {
     dybit_status st = check_fmt(x_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
@@ -446,6 +428,7 @@ static dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, in
     g.a_signed = x_fmt.is_signed; g.w_signed = w_fmt.is_signed;
     g.a_scale = x_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
     g.C = Y; g.ldc = Cout;
+    g.residual = residual;
     g.absmax_bits = reinterpret_cast<uint32_t *>(y_absmax);
     g.H = (int)H; g.Wd = (int)W; g.Cin = (int)Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.stride = stride; g.pad = pad;
@@ -465,17 +448,16 @@ extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Ci
                                      float *Y, dybit_stream stream)
 {
     return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale,
-                       bias, relu, Y, nullptr, stream);
+                       bias, relu, Y, nullptr, nullptr, stream);
 }
 
-extern "C" dybit_status dybit_conv2d_absmax(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
-                                            int32_t kh, int32_t kw, int32_t stride, int32_t pad,
-                                            const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
-                                            const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
-                                            const float *bias, int32_t relu,
-                                            float *Y, float *y_absmax, dybit_stream stream)
+extern "C" dybit_status dybit_conv2d_ex(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                        int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                        const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                        const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                        const float *bias, const float *residual, int32_t relu,
+                                        float *Y, float *y_absmax, dybit_stream stream)
 {
-    if (!y_absmax) return DYBIT_ERR_NULL;
     return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale,
-                       bias, relu, Y, y_absmax, stream);
+                       bias, relu, Y, residual, y_absmax, stream);
 }

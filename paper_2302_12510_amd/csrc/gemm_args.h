@@ -10,6 +10,7 @@ struct GemmArgs {
     const uint8_t *A, *W;            // packed codes, K-contiguous rows (conv: NHWC image / [Cout][kh][kw][Cin])
     int a_signed, w_signed;
     const float *a_scale, *w_scale, *bias;
+    const float *residual;           // optional: fp32 tensor laid out like C (same ldc), added before the ReLU
     int relu;
     uint32_t *absmax_bits;           // optional: running max |C| of the written values, as float bits (atomic max)
     float *C;

@@ -1,5 +1,5 @@
-// Epilogue shared by the tiled matrix-product kernels: C = acc * (sA sW) (+ bias) (ReLU), optional
-// running maximum of |C|, for the 32-row strip of accumulator blocks one wave holds.
+// Epilogue shared by the tiled matrix-product kernels: C = acc * (sA sW) (+ bias) (+ residual) (ReLU),
+// optional running maximum of |C|, for the 32-row strip of accumulator blocks one wave holds.
 //
 // Accumulator v of a lane is row 8 (v / 4) + 4 (lane / 32) + v % 4 and column lane % 32 of its
 // 32 x 32 block.  The strip is stored through a buffer descriptor that starts at the strip's first
@@ -14,6 +14,51 @@
 
 namespace dybit {
 
+template <int CB, bool HAS_RES>
+__device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB], const int64_t m_strip,
+                                             const int64_t n0, const int rows, const float alpha)
+{
+    const int lane = threadIdx.x & 63, kq = lane >> 5;
+    const uint32_t ldc4 = (uint32_t)g.ldc * 4u;
+    const int records = (int)((uint32_t)rows * ldc4);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(g.C + m_strip * g.ldc, 0, records, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(HAS_RES ? g.residual + m_strip * g.ldc : g.C), 0, HAS_RES ? records : 0, 0x00020000);
+    const bool track = g.absmax_bits != nullptr;
+    float mx = 0.0f;
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+        const int64_t n = n0 + j * 32 + (lane & 31);
+        const bool n_ok = n < g.N;
+        const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
+        const uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
+        float res[16];
+        if (HAS_RES) {                                                  // out-of-range elements read 0
+            uint32_t off = off0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                res[v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, off, 0, 0));
+                off += (v & 3) == 3 ? 5u * ldc4 : ldc4;
+            }
+        }
+        uint32_t off = off0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float c = acc[j][v] * alpha + b;
+            if (HAS_RES) c += res[v];
+            if (g.relu) c = fmaxf(c, 0.0f);
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c), rsrc, off, 0, 2);
+            if (track) {
+                // a row past M holds bias only (its codes read as zeros): keep it out of the maximum
+                const int r = 8 * (v >> 2) + 4 * kq + (v & 3);
+                mx = fmaxf(mx, (n_ok && r < rows) ? fabsf(c) : 0.0f);
+            }
+            off += (v & 3) == 3 ? 5u * ldc4 : ldc4;                     // rows 0-3, 8-11, 16-19, 24-27 (+ 4 kq)
+        }
+    }
+    return mx;
+}
+
 template <int CB>
 __device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB],
                                                const int64_t m_strip, const int64_t n0)
@@ -24,29 +69,8 @@ __device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f3
     const int rows = rows_left >= 32 ? 32 : rows_left > 0 ? (int)rows_left : 0;
     float mx = 0.0f;
     if (g.ldc < (1 << 23)) {
-        const uint32_t ldc4 = (uint32_t)g.ldc * 4u;
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            g.C + m_strip * g.ldc, 0, (int)((uint32_t)rows * ldc4), 0x00020000);
-        const bool track = g.absmax_bits != nullptr;
-#pragma unroll
-        for (int j = 0; j < CB; ++j) {
-            const int64_t n = n0 + j * 32 + (lane & 31);
-            const bool n_ok = n < g.N;
-            const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
-            uint32_t off = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float c = acc[j][v] * alpha + b;
-                if (g.relu) c = fmaxf(c, 0.0f);
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c), rsrc, off, 0, 2);
-                if (track) {
-                    // a row past M holds bias only (its codes read as zeros): keep it out of the maximum
-                    const int r = 8 * (v >> 2) + 4 * kq + (v & 3);
-                    mx = fmaxf(mx, (n_ok && r < rows) ? fabsf(c) : 0.0f);
-                }
-                off += (v & 3) == 3 ? 5u * ldc4 : ldc4;             // rows 0-3, 8-11, 16-19, 24-27 (+ 4 kq)
-            }
-        }
+        mx = g.residual ? store_strip<CB, true>(g, acc, m_strip, n0, rows, alpha)
+                        : store_strip<CB, false>(g, acc, m_strip, n0, rows, alpha);
     } else {                                                        // leading dimension too large for 32-bit offsets
 #pragma unroll
         for (int j = 0; j < CB; ++j) {
@@ -56,9 +80,10 @@ __device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f3
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int r = 8 * (v >> 2) + 4 * kq + (v & 3);
-                float c = acc[j][v] * alpha + b;
-                if (g.relu) c = fmaxf(c, 0.0f);
                 if (n_ok && r < rows) {
+                    float c = acc[j][v] * alpha + b;
+                    if (g.residual) c += g.residual[(m_strip + r) * g.ldc + n];
+                    if (g.relu) c = fmaxf(c, 0.0f);
                     __builtin_nontemporal_store(c, g.C + (m_strip + r) * g.ldc + n);
                     mx = fmaxf(mx, fabsf(c));
                 }

@@ -7,9 +7,9 @@ This is the paper's dataflow with the write-back quantization done as a separate
 (Sec. III-B: activations and weights are stored as DyBit codes, partial sums stay FP).  Where a
 layer's output goes to the next encoder unchanged (or through a max-pool of non-negative values,
 which keeps the maximum), its max|y| is taken in the convolution's epilogue
-(dybit_conv2d_absmax + dybit_scale_from_absmax) instead of by a pass over the fp32 tensor.
-Residual additions and pooling run on the fp32 tensors with torch ops; they are glue, not
-part of the library.
+(dybit_conv2d_ex + dybit_scale_from_absmax) instead of by a pass over the fp32 tensor; the
+identity shortcut of a residual block is added in the same epilogue, before the ReLU.
+Pooling runs on the fp32 tensors with torch ops; it is glue, not part of the library.
 
 Formats: weights are signed; an activation tensor is unsigned when it is the output of a
 ReLU or of a pooling of such outputs, signed otherwise (the network input).  Layer-wise
@@ -65,7 +65,7 @@ class DybitNetwork:
         acts = {"input": x}
         nonneg = {"input": False}
         known_max = {}                       # tensor name -> device scalar holding max|tensor|
-        n_fused = sum(1 for l in self.layers if l["op"] in ("conv", "fc") and not l.get("add"))
+        n_fused = sum(1 for l in self.layers if l["op"] in ("conv", "fc"))
         max_words = torch.zeros(max(n_fused, 1), dtype=torch.float32, device=x.device)
         next_word = 0
         out = x
@@ -93,26 +93,23 @@ class DybitNetwork:
                 else:
                     sa = B.dybit_absmax_scale(flat, *a_fmt)
                 qa = B.dybit_quantize(flat, sa, *a_fmt)
-                fused_relu = bool(l.get("relu")) and not l.get("add")
+                relu = bool(l.get("relu"))
                 k = p["k"]
                 stride, pad = (l["stride"], l["pad"]) if op == "conv" else (1, 0)
                 conv_args = (Bn, H, W, p["cpad"], p["cout"], k, k, stride, pad,
                              qa, a_fmt, sa, p["w_codes"], p["w_fmt"], p["w_scale"])
-                if l.get("add") or not self.epilogue_absmax:
-                    y = B.dybit_conv2d(*conv_args, p["bias"], fused_relu)
-                else:                                           # y is this layer's final output
+                shortcut = acts[l["add"]] if l.get("add") else None
+                if self.epilogue_absmax:
                     word = max_words[next_word:next_word + 1]
                     next_word += 1
-                    y = B.dybit_conv2d_absmax(*conv_args, word, p["bias"], fused_relu)
+                    y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu, word)
                     known_max[name] = word
+                else:
+                    y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu)
                 if record is not None:
-                    record(name, {"x": src, "a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "y": y,
-                                  "relu": fused_relu, "stride": stride, "pad": pad, "k": k, **p})
+                    record(name, {"x": src, "a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "y": y, "shortcut": shortcut,
+                                  "relu": relu, "stride": stride, "pad": pad, "k": k, **p})
                 out = y
-                if l.get("add"):
-                    out = out + acts[l["add"]]
-                    if l.get("relu"):
-                        out = torch.relu_(out)
                 nonneg[name] = bool(l.get("relu"))
             acts[name] = out
         return out.reshape(out.shape[0], -1)

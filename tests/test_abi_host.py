@@ -99,11 +99,12 @@ def test_argument_errors_without_gpu():
     assert cv(Cin=3) == B.ERR_ALIGNMENT                          # 12 bits per pixel
     assert cv(x=null) == B.ERR_NULL
     assert cv(Bn=0, x=null, y=null) == B.OK
-    # the variants that also take the running maximum: same checks, plus the extra pointer
-    assert L.dybit_gemm_absmax(8, 8, 16, p, f4, p, p, f4, p, null, 0, p, 8, null, None) == B.ERR_NULL
-    assert L.dybit_gemm_absmax(8, 8, 15, p, f4, p, p, f4, p, null, 0, p, 8, p, None) == B.ERR_ALIGNMENT
-    assert L.dybit_conv2d_absmax(1, 8, 8, 16, 8, 3, 3, 1, 1, p, f4, p, p, f4, p, null, 0, p, null, None) == B.ERR_NULL
-    assert L.dybit_conv2d_absmax(1, 8, 8, 16, 8, 3, 3, 0, 1, p, f4, p, p, f4, p, null, 0, p, p, None) == B.ERR_INVALID_ARG
+    # the extended variants: the same checks; shortcut and running maximum are optional
+    assert L.dybit_gemm_ex(8, 8, 16, p, f4, p, p, f4, p, null, null, 0, null, 8, null, None) == B.ERR_NULL
+    assert L.dybit_gemm_ex(8, 8, 15, p, f4, p, p, f4, p, null, p, 0, p, 8, p, None) == B.ERR_ALIGNMENT
+    assert L.dybit_gemm_ex(0, 8, 16, null, f4, p, null, f4, p, null, null, 0, null, 8, null, None) == B.OK
+    assert L.dybit_conv2d_ex(1, 8, 8, 16, 8, 3, 3, 1, 1, null, f4, p, p, f4, p, null, null, 0, p, null, None) == B.ERR_NULL
+    assert L.dybit_conv2d_ex(1, 8, 8, 16, 8, 3, 3, 0, 1, p, f4, p, p, f4, p, null, p, 0, p, p, None) == B.ERR_INVALID_ARG
     assert L.dybit_scale_from_absmax(null, f4, p, None) == B.ERR_NULL
     assert L.dybit_scale_from_absmax(p, bad, p, None) == B.ERR_UNSUPPORTED_BITS
     assert L.dybit_get_last_async_error(None, None) == B.ERR_NULL

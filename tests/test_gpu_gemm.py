@@ -341,8 +341,8 @@ def test_gemm_absmax_matches_a_pass_over_the_output(force_kernel, relu, a_fmt):
     qw = random_codes(rng, (N, K), w_fmt)
     bias = rng.normal(0, 3, N).astype(np.float32)
     mx = torch.zeros(1, dtype=torch.float32, device="cuda")
-    c = B.dybit_gemm_absmax(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
-                            scalar(0.011), mx, dev(bias), relu)
+    c = B.dybit_gemm_ex(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
+                        scalar(0.011), dev(bias), None, relu, mx)
     torch.cuda.synchronize()
     want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, relu)
     assert_within(c.cpu().numpy(), want, den)
@@ -353,25 +353,51 @@ def test_gemm_absmax_matches_a_pass_over_the_output(force_kernel, relu, a_fmt):
         assert s_fused.item() == s_pass.item()
     # a larger value already in the word stays; a smaller one is replaced
     big = torch.full((1,), 1.0e9, dtype=torch.float32, device="cuda")
-    B.dybit_gemm_absmax(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
-                        scalar(0.011), big, dev(bias), relu)
+    B.dybit_gemm_ex(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
+                    scalar(0.011), dev(bias), None, relu, big)
     assert big.item() == 1.0e9
 
 
-@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "general"], indirect=True)
-def test_conv2d_absmax(force_kernel):
+@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid1-f16", "general"], indirect=True)
+@pytest.mark.parametrize("with_shortcut", [False, True])
+def test_conv2d_ex_shortcut_and_absmax(force_kernel, with_shortcut):
+    """Shortcut added before the ReLU, running maximum over the values written, ragged tiles."""
     rng = np.random.default_rng(23)
     x_fmt, w_fmt = (4, False), (4, True)
     qx = random_codes(rng, (2, 9, 10, 64), x_fmt)
     qw = random_codes(rng, (70, 3, 3, 64), w_fmt)
     bias = rng.normal(0, 1, 70).astype(np.float32)
+    res = rng.normal(0, 20, (2, 9, 10, 70)).astype(np.float32) if with_shortcut else None
     mx = torch.zeros(1, dtype=torch.float32, device="cuda")
-    y = B.dybit_conv2d_absmax(2, 9, 10, 64, 70, 3, 3, 1, 1, pack_rows_dev(qx.reshape(-1, 64), 4), x_fmt, scalar(0.3),
-                              pack_rows_dev(qw.reshape(-1, 64), 4), w_fmt, scalar(0.02), mx, dev(bias), True)
+    y = B.dybit_conv2d_ex(2, 9, 10, 64, 70, 3, 3, 1, 1, pack_rows_dev(qx.reshape(-1, 64), 4), x_fmt, scalar(0.3),
+                          pack_rows_dev(qw.reshape(-1, 64), 4), w_fmt, scalar(0.02), dev(bias),
+                          None if res is None else dev(res), True, mx)
     torch.cuda.synchronize()
-    want, den = R.conv2d(qx, x_fmt, 0.3, qw, w_fmt, 0.02, 1, 1, bias, True)
+    want, den = R.conv2d(qx, x_fmt, 0.3, qw, w_fmt, 0.02, 1, 1, bias, True, res)
     assert_within(y.cpu().numpy(), want, den)
     assert mx.item() == y.abs().max().item()
+
+
+@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "general"], indirect=True)
+@pytest.mark.parametrize("a_fmt", [(8, True), (4, True)])
+def test_gemm_ex_shortcut(force_kernel, a_fmt):
+    """C = A W^T + bias + shortcut (no ReLU, so a wrong sign or a shortcut applied after the ReLU shows),
+    with a leading dimension larger than N shared by output and shortcut."""
+    rng = np.random.default_rng(29)
+    w_fmt = (4, True)
+    M, N, K, ldc = 290, 200, 128, 208
+    qa = random_codes(rng, (M, K), a_fmt)
+    qw = random_codes(rng, (N, K), w_fmt)
+    bias = rng.normal(0, 3, N).astype(np.float32)
+    res = rng.normal(0, 50, (M, ldc)).astype(np.float32)
+    out = torch.full((M, ldc), -777.0, dtype=torch.float32, device="cuda")
+    B.dybit_gemm_ex(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt,
+                    scalar(0.011), dev(bias), dev(res), False, None, out=out, ldc=ldc)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, False, res[:, :N])
+    assert_within(got[:, :N], want, den)
+    assert np.all(got[:, N:] == -777.0)
 
 
 def test_scale_from_absmax_of_zero_is_one():

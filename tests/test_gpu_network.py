@@ -44,8 +44,9 @@ def check_layer(name, rec, weights, rng, n_rows=None, n_codes=None):
     qx = codes.reshape(Bn, H, W, C)
     y = rec["y"].cpu().numpy()
     stride, pad = rec["stride"], rec["pad"]
+    shortcut = None if rec["shortcut"] is None else rec["shortcut"].cpu().numpy()    # added in the epilogue, before the ReLU
     if n_rows is None:
-        want, den = R.conv2d(qx, a_fmt, s, qw, w_fmt, sw, stride, pad, bias, rec["relu"])
+        want, den = R.conv2d(qx, a_fmt, s, qw, w_fmt, sw, stride, pad, bias, rec["relu"], shortcut)
         got = y
     else:
         Ho, Wo = y.shape[1], y.shape[2]
@@ -58,7 +59,8 @@ def check_layer(name, rec, weights, rng, n_rows=None, n_codes=None):
                 hi, wi = ho * stride - pad + r, wo * stride - pad + q
                 ok = (hi >= 0) & (hi < H) & (wi >= 0) & (wi < W)
                 patches[ok, r, q, :] = qx[b[ok], hi[ok], wi[ok], :]
-        want, den = R.gemm(patches.reshape(rows.size, -1), a_fmt, s, qw.reshape(cout, -1), w_fmt, sw, bias, rec["relu"])
+        res = None if shortcut is None else shortcut.reshape(-1, cout)[rows]
+        want, den = R.gemm(patches.reshape(rows.size, -1), a_fmt, s, qw.reshape(cout, -1), w_fmt, sw, bias, rec["relu"], res)
         got = y.reshape(-1, cout)[rows]
     err = np.abs(got.astype(np.float64) - want)
     assert np.all(err <= 1e-5 * den), (name, float((err / np.maximum(den, 1e-300)).max()))
