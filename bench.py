@@ -77,7 +77,7 @@ def time_events(fn, steps, warmup, torch):
 
 def bench_network(args):
     """Configs 3 and 4: a step is one forward pass of the chained network (per conv / linear layer
-    absmax -> quantize -> dybit_conv2d with bias and ReLU; pooling and residual adds in torch)."""
+    scale -> quantize -> dybit_conv2d_ex with bias, shortcut and ReLU fused; pooling in torch)."""
     import torch
     from paper_2302_12510_amd import binding as B
     from paper_2302_12510_amd import synth
@@ -112,7 +112,7 @@ def bench_network(args):
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 or e4m3 MFMA inputs by layer (exact), f32 accumulate", "data": "synthetic",
         "config": {"workload": name, "gemms": len(shapes), "GMAC": round(flops / 2e9, 1),
-                   "step": "per layer absmax + quantize + conv (bias, ReLU); pooling / residual adds in torch"},
+                   "step": "per layer scale + quantize + conv (bias, shortcut, ReLU and max|result| in the epilogue); pooling in torch"},
         "roofline": None,
     }
     if not args.no_cpu_baseline:
