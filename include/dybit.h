@@ -141,13 +141,47 @@ dybit_status dybit_conv2d_ex(int64_t B, int64_t H, int64_t W, int64_t Cin, int64
                              const float *bias, const float *residual, int32_t relu,
                              float *Y, float *y_absmax, dybit_stream stream);
 
+/* Fused write-back (Sec. III-B: the floating-point intermediate results are quantized to DyBit before
+ * they are written back).  These variants do what the _ex variants do and, in the same epilogue, encode
+ * every result with the format c_fmt and the given scale -- exactly the code dybit_quantize would produce
+ * from the fp32 value the call computes -- and store the codes packed like an activation operand of the
+ * next layer: M rows of N codes (convolution: [B][Ho][Wo][Cout], packed along Cout).
+ *
+ *   c_fmt     4-, 6- or 8-bit, signed or unsigned (DYBIT_ERR_UNSUPPORTED_BITS for 2-bit); N * bits must
+ *             be a multiple of 32, i.e. rows are whole 32-bit words (DYBIT_ERR_ALIGNMENT otherwise).
+ *   c_scale   [device] 1 float, known before the call (a calibrated or previous-iteration scale: the
+ *             maximum of this call's results is only known when it ends).  Results beyond
+ *             scale * 2^(m-1) saturate to the all-ones magnitude, as in dybit_quantize.  A scale that
+ *             is not positive and finite, or lies outside [2^-100, 2^100], writes no codes and sets the
+ *             asynchronous error flag (DYBIT_ERR_BAD_SCALE, see dybit_get_last_async_error).
+ *   C_codes   [device] M * N * bits / 8 bytes, 4-byte aligned, written by the call; must not overlap
+ *             any other argument.  NULL: no codes, the call is the _ex variant.
+ *   C / Y     the fp32 output becomes optional: NULL skips it (DYBIT_ERR_NULL when both outputs are
+ *             NULL).  ldc still gives the layout of `residual`; ldc and N must be below 2^23.
+ *
+ * All other arguments: as in dybit_gemm_ex / dybit_conv2d_ex; the running maximum, when asked for, is
+ * that of the fp32 values, before encoding. */
+dybit_status dybit_gemm_wb(int64_t M, int64_t N, int64_t K,
+                           const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                           const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                           const float *bias, const float *residual, int32_t relu,
+                           float *C, int64_t ldc, float *c_absmax,
+                           dybit_fmt c_fmt, const float *c_scale, uint8_t *C_codes, dybit_stream stream);
+dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                             int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                             const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                             const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                             const float *bias, const float *residual, int32_t relu,
+                             float *Y, float *y_absmax,
+                             dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream);
+
 /* *scale_out = *absmax / 2^(m-1), or 1.0 when *absmax == 0: the last step of dybit_absmax_scale,
  * for a maximum obtained otherwise.  absmax, scale_out [device]: 1 float each (may be the same word). */
 dybit_status dybit_scale_from_absmax(const float *absmax, dybit_fmt f, float *scale_out, dybit_stream stream);
 
 /* Waits for `stream`, then reports and clears the asynchronous error flag of the current
  * device: *flag_out [host] is DYBIT_OK or DYBIT_ERR_BAD_SCALE (a dybit_quantize kernel since the
- * last call found an unusable scale and wrote nothing). */
+ * last call, or a write-back epilogue, found an unusable scale and wrote no codes). */
 dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream);
 
 /* Measurement aid, not part of the method: runs only fp16 MFMA instructions (the instruction

@@ -51,6 +51,8 @@ def lib() -> C.CDLL:
         L.dybit_conv2d.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp]
         L.dybit_gemm_ex.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, i64, vp, vp]
         L.dybit_conv2d_ex.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, vp]
+        L.dybit_gemm_wb.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, i64, vp, Fmt, vp, vp, vp]
+        L.dybit_conv2d_wb.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, Fmt, vp, vp, vp]
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
         L.dybit_diag_mfma_f16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
@@ -191,6 +193,45 @@ def dybit_conv2d_ex(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: in
                                  _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), _ptr(residual), int(bool(relu)),
                                  _ptr(out), _ptr(absmax), _stream(stream)), "dybit_conv2d_ex")
     return out
+
+
+def dybit_gemm_wb(M: int, N: int, K: int, a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale, c_fmt, c_scale,
+                  bias=None, residual=None, relu: bool = False, absmax=None, fp32: bool = True,
+                  out: torch.Tensor | None = None, ldc: int | None = None,
+                  codes_out: torch.Tensor | None = None, stream=None):
+    """dybit_gemm_ex with the results also (fp32=True) or only (fp32=False) written back as packed
+    DyBit codes of format c_fmt under the given device scale.  Returns (C or None, codes [M][N*bits/8])."""
+    if ldc is None:
+        ldc = N
+    if fp32 and out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=a_scale.device)
+    if codes_out is None:
+        codes_out = torch.empty((M, N * c_fmt[0] // 8), dtype=torch.uint8, device=a_scale.device)
+    _check(lib().dybit_gemm_wb(M, N, K, _ptr(a_codes), fmt(*a_fmt), _ptr(a_scale),
+                               _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), _ptr(residual), int(bool(relu)),
+                               _ptr(out if fp32 else None), ldc, _ptr(absmax),
+                               fmt(*c_fmt), _ptr(c_scale), _ptr(codes_out), _stream(stream)), "dybit_gemm_wb")
+    return (out if fp32 else None), codes_out
+
+
+def dybit_conv2d_wb(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: int, stride: int, pad: int,
+                    x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, y_fmt, y_scale,
+                    bias=None, residual=None, relu: bool = False, absmax=None, fp32: bool = True,
+                    out: torch.Tensor | None = None, codes_out: torch.Tensor | None = None, stream=None):
+    """dybit_conv2d_ex with the results also (fp32=True) or only (fp32=False) written back as packed
+    DyBit codes.  Returns (Y or None, codes [B][Ho][Wo][Cout*bits/8])."""
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    if fp32 and out is None:
+        out = torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device=x_scale.device)
+    if codes_out is None:
+        codes_out = torch.empty((B, Ho, Wo, Cout * y_fmt[0] // 8), dtype=torch.uint8, device=x_scale.device)
+    _check(lib().dybit_conv2d_wb(B, H, W, Cin, Cout, kh, kw, stride, pad,
+                                 _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
+                                 _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), _ptr(residual), int(bool(relu)),
+                                 _ptr(out if fp32 else None), _ptr(absmax),
+                                 fmt(*y_fmt), _ptr(y_scale), _ptr(codes_out), _stream(stream)), "dybit_conv2d_wb")
+    return (out if fp32 else None), codes_out
 
 
 def dybit_scale_from_absmax(absmax: torch.Tensor, bits: int, signed: bool, out: torch.Tensor | None = None, stream=None):

@@ -19,6 +19,13 @@ SOURCES = [
     ("gemm_mid.hip", "gemm_mid_w4", ["-DDYBIT_MID_W=0"]),
     ("gemm_mid.hip", "gemm_mid_w8", ["-DDYBIT_MID_W=2"]),
     ("gemm_f8.hip", "gemm_f8", []),
+    # write-back builds of the same kernels (epilogue also encodes the results as DyBit codes)
+    ("gemm.hip", "gemm_wb", ["-DDYBIT_WB=1"]),
+    ("gemm_fast.hip", "gemm_fast_w4_wb", ["-DDYBIT_FAST_W=0", "-DDYBIT_WB=1"]),
+    ("gemm_fast.hip", "gemm_fast_w8_wb", ["-DDYBIT_FAST_W=2", "-DDYBIT_WB=1"]),
+    ("gemm_mid.hip", "gemm_mid_w4_wb", ["-DDYBIT_MID_W=0", "-DDYBIT_WB=1"]),
+    ("gemm_mid.hip", "gemm_mid_w8_wb", ["-DDYBIT_MID_W=2", "-DDYBIT_WB=1"]),
+    ("gemm_f8.hip", "gemm_f8_wb", ["-DDYBIT_WB=1"]),
     ("diag.hip", "diag", []),
 ]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
@@ -46,7 +53,7 @@ def _compile(item) -> str:
 
 
 def build(verbose: bool = True) -> str:
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 8)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     p = subprocess.run(cmd, capture_output=True, text=True)

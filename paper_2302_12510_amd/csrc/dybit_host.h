@@ -13,6 +13,9 @@ inline dybit_status check_fmt(dybit_fmt f)
     return DYBIT_OK;
 }
 
+// Device address of the asynchronous error flag of the current device, or NULL (quantize.hip).
+int *async_error_word();
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline dybit_status launch_status()

@@ -214,7 +214,7 @@ __device__ __forceinline__ Unit<BITS> load_unit_W(const GemmArgs &g, const uint8
     return load_unit_elems<BITS>(row, k0, g.K);
 }
 
-template <int BA, int BW, bool CONV, bool VEC>
+template <int BA, int BW, bool CONV, bool VEC, bool WB>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) _Float16 As[BM * LDK];
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
 
     // epilogue (shared with the tiled kernels): each wave stores its two 32-row strips of 64 columns
 #pragma unroll
-    for (int i = 0; i < 2; ++i) epilogue_strip<2>(g, acc[i], m0 + wm * 64 + i * 32, n0 + wn * 64);
+    for (int i = 0; i < 2; ++i) epilogue_strip<2, WB>(g, acc[i], m0 + wm * 64 + i * 32, n0 + wn * 64);
 }
 
 template <int BA, int BW>
@@ -332,15 +332,15 @@ static void launch_gemm(const GemmArgs &g, bool conv, bool vec, hipStream_t st)
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     const dim3 grid((unsigned)tiles), block(GEMM_THREADS);
     if (conv) {
-        if (vec) hipLaunchKernelGGL((gemm_kernel<BA, BW, true, true>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((gemm_kernel<BA, BW, true, false>), grid, block, 0, st, g);
+        if (vec) hipLaunchKernelGGL((gemm_kernel<BA, BW, true, true, kWriteBack>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((gemm_kernel<BA, BW, true, false, kWriteBack>), grid, block, 0, st, g);
     } else {
-        if (vec) hipLaunchKernelGGL((gemm_kernel<BA, BW, false, true>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((gemm_kernel<BA, BW, false, false>), grid, block, 0, st, g);
+        if (vec) hipLaunchKernelGGL((gemm_kernel<BA, BW, false, true, kWriteBack>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((gemm_kernel<BA, BW, false, false, kWriteBack>), grid, block, 0, st, g);
     }
 }
 
-static void dispatch_gemm(const GemmArgs &g, int ba, int bw, bool conv, bool vec, hipStream_t st)
+void DYBIT_WB_NAME(launch_gemm_general)(const GemmArgs &g, int ba, int bw, bool conv, bool vec, hipStream_t st)
 {
 #define DYBIT_G(A_, W_) case (A_) * 16 + (W_): launch_gemm<A_, W_>(g, conv, vec, st); break
     switch (ba * 16 + bw) {
@@ -354,36 +354,116 @@ static void dispatch_gemm(const GemmArgs &g, int ba, int bw, bool conv, bool vec
 
 }  // namespace dybit
 
+#if !DYBIT_WB   // the C entry points live in the plain build of this file
 using namespace dybit;
 
-static dybit_status gemm_impl(int64_t M, int64_t N, int64_t K,
-                              const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
-                              const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
-                              const float *bias, int32_t relu,
-                              float *C, int64_t ldc, const float *residual, float *c_absmax, dybit_stream stream)
+namespace {
+
+// What happens to the accumulators on the way out: every entry point fills one of these.
+struct Epilogue {
+    const float *bias = nullptr, *residual = nullptr;
+    int32_t relu = 0;
+    float *absmax = nullptr;
+    bool has_codes = false;          // write-back as DyBit codes requested
+    dybit_fmt q_fmt{0, 0};
+    const float *q_scale = nullptr;
+    uint8_t *q_out = nullptr;
+};
+
+// Checks the epilogue against the output shape and fills the matching fields of g.
+// fp32 output `C` may be NULL only when codes are written.
+dybit_status set_epilogue(GemmArgs &g, const Epilogue &e, float *C, int64_t ldc)
+{
+    g.bias = e.bias; g.relu = e.relu; g.residual = e.residual;
+    g.absmax_bits = reinterpret_cast<uint32_t *>(e.absmax);
+    g.C = C; g.ldc = ldc;
+    if (!e.has_codes) return C ? DYBIT_OK : DYBIT_ERR_NULL;
+    if (!e.q_out && !C) return DYBIT_ERR_NULL;
+    if (!e.q_out) return DYBIT_OK;                                       // fp32 only after all
+    if (!e.q_scale) return DYBIT_ERR_NULL;
+    g.q_out = e.q_out; g.q_scale = e.q_scale;
+    g.q_bits = e.q_fmt.bits; g.q_signed = e.q_fmt.is_signed;
+    g.q_row_bytes = g.N * e.q_fmt.bits / 8;
+    g.async_error = async_error_word();
+    return g.async_error ? DYBIT_OK : DYBIT_ERR_HIP;
+}
+
+// Argument checks of the write-back that need no device: format, whole words per row, sizes.
+dybit_status check_codes_out(const Epilogue &e, int64_t N, int64_t ldc)
+{
+    if (!e.has_codes) return DYBIT_OK;
+    const dybit_status st = check_fmt(e.q_fmt);
+    if (st != DYBIT_OK) return st;
+    if (e.q_fmt.bits == 2) return DYBIT_ERR_UNSUPPORTED_BITS;            // the epilogue packs 4-, 6- and 8-bit codes
+    if ((N * e.q_fmt.bits) % 32) return DYBIT_ERR_ALIGNMENT;
+    if (ldc >= (1 << 23) || N >= (1 << 23)) return DYBIT_ERR_INVALID_ARG;
+    if (e.q_out && (reinterpret_cast<uintptr_t>(e.q_out) & 3u)) return DYBIT_ERR_ALIGNMENT;
+    return DYBIT_OK;
+}
+
+dybit_status gemm_impl(int64_t M, int64_t N, int64_t K,
+                       const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                       const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                       const Epilogue &e, float *C, int64_t ldc, dybit_stream stream)
 {
     dybit_status st = check_fmt(a_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
     if (st != DYBIT_OK) return st;
-    if (M < 0 || N < 0 || K < 0 || ldc < N || (relu != 0 && relu != 1)) return DYBIT_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0 || ldc < N || (e.relu != 0 && e.relu != 1)) return DYBIT_ERR_INVALID_ARG;
     if ((K * a_fmt.bits) % 8 || (K * w_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
+    if ((st = check_codes_out(e, N, ldc)) != DYBIT_OK) return st;
     if (M == 0 || N == 0) return DYBIT_OK;
-    if (!a_scale || !w_scale || !C || (K && (!A_codes || !W_codes))) return DYBIT_ERR_NULL;
+    if (!a_scale || !w_scale || (K && (!A_codes || !W_codes))) return DYBIT_ERR_NULL;
     GemmArgs g{};
     g.M = M; g.N = N; g.K = K;
     g.A = A_codes; g.W = W_codes;
     g.a_signed = a_fmt.is_signed; g.w_signed = w_fmt.is_signed;
-    g.a_scale = a_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
-    g.C = C; g.ldc = ldc;
-    g.residual = residual;
-    g.absmax_bits = reinterpret_cast<uint32_t *>(c_absmax);
+    g.a_scale = a_scale; g.w_scale = w_scale;
+    if ((st = set_epilogue(g, e, C, ldc)) != DYBIT_OK) return st;
     g.a_bytes = M * (K * a_fmt.bits / 8);
     g.w_bytes = N * (K * w_fmt.bits / 8);
     if (launch_gemm_tiled(g, a_fmt.bits, w_fmt.bits, false, (hipStream_t)stream)) return launch_status();
     const bool vec = (K % UNIT == 0) && aligned16(A_codes) && aligned16(W_codes);
-    dispatch_gemm(g, a_fmt.bits, w_fmt.bits, false, vec, (hipStream_t)stream);
+    (g.q_out ? launch_gemm_general_wb : launch_gemm_general)(g, a_fmt.bits, w_fmt.bits, false, vec, (hipStream_t)stream);
     return launch_status();
 }
+
+dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                         int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                         const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                         const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                         const Epilogue &e, float *Y, dybit_stream stream)
+{
+    dybit_status st = check_fmt(x_fmt);
+    if (st == DYBIT_OK) st = check_fmt(w_fmt);
+    if (st != DYBIT_OK) return st;
+    if (B < 0 || H < 1 || W < 1 || Cin < 1 || Cout < 0 || kh < 1 || kw < 1 || stride < 1 || pad < 0 ||
+        (e.relu != 0 && e.relu != 1) || H > (1 << 24) || W > (1 << 24) || Cin > (1 << 24))
+        return DYBIT_ERR_INVALID_ARG;
+    if (H + 2 * (int64_t)pad < kh || W + 2 * (int64_t)pad < kw) return DYBIT_ERR_INVALID_ARG;
+    if ((int64_t)kh * kw > (1 << 24) || (int64_t)kh * kw * Cin > 0x7fffffff) return DYBIT_ERR_INVALID_ARG;   // K fits an int
+    if ((Cin * x_fmt.bits) % 8 || (Cin * w_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
+    if ((st = check_codes_out(e, Cout, Cout)) != DYBIT_OK) return st;
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    if (B == 0 || Cout == 0) return DYBIT_OK;
+    if (!x_scale || !w_scale || !X_codes || !Wt_codes) return DYBIT_ERR_NULL;
+    GemmArgs g{};
+    g.M = B * Ho * Wo; g.N = Cout; g.K = (int64_t)kh * kw * Cin;
+    g.A = X_codes; g.W = Wt_codes;
+    g.a_signed = x_fmt.is_signed; g.w_signed = w_fmt.is_signed;
+    g.a_scale = x_scale; g.w_scale = w_scale;
+    if ((st = set_epilogue(g, e, Y, Cout)) != DYBIT_OK) return st;
+    g.H = (int)H; g.Wd = (int)W; g.Cin = (int)Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
+    g.kh = kh; g.kw = kw; g.stride = stride; g.pad = pad;
+    g.a_bytes = B * H * W * (Cin * x_fmt.bits / 8);
+    g.w_bytes = Cout * (g.K * w_fmt.bits / 8);
+    if (launch_gemm_tiled(g, x_fmt.bits, w_fmt.bits, true, (hipStream_t)stream)) return launch_status();
+    const bool vec = (Cin % UNIT == 0) && aligned16(X_codes) && aligned16(Wt_codes);
+    (g.q_out ? launch_gemm_general_wb : launch_gemm_general)(g, x_fmt.bits, w_fmt.bits, true, vec, (hipStream_t)stream);
+    return launch_status();
+}
+
+}  // namespace
 
 extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
                                    const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
@@ -391,7 +471,9 @@ extern "C" dybit_status dybit_gemm(int64_t M, int64_t N, int64_t K,
                                    const float *bias, int32_t relu,
                                    float *C, int64_t ldc, dybit_stream stream)
 {
-    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, bias, relu, C, ldc, nullptr, nullptr, stream);
+    Epilogue e;
+    e.bias = bias; e.relu = relu;
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, e, C, ldc, stream);
 }
 
 extern "C" dybit_status dybit_gemm_ex(int64_t M, int64_t N, int64_t K,
@@ -400,44 +482,22 @@ extern "C" dybit_status dybit_gemm_ex(int64_t M, int64_t N, int64_t K,
                                       const float *bias, const float *residual, int32_t relu,
                                       float *C, int64_t ldc, float *c_absmax, dybit_stream stream)
 {
-    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, bias, relu, C, ldc, residual, c_absmax, stream);
+    Epilogue e;
+    e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = c_absmax;
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, e, C, ldc, stream);
 }
 
-static dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
-                                int32_t kh, int32_t kw, int32_t stride, int32_t pad,
-                                const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
-                                const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
-                                const float *bias, int32_t relu,
-                                float *Y, const float *residual, float *y_absmax, dybit_stream stream)
+extern "C" dybit_status dybit_gemm_wb(int64_t M, int64_t N, int64_t K,
+                                      const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                                      const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                                      const float *bias, const float *residual, int32_t relu,
+                                      float *C, int64_t ldc, float *c_absmax,
+                                      dybit_fmt c_fmt, const float *c_scale, uint8_t *C_codes, dybit_stream stream)
 {
-    dybit_status st = check_fmt(x_fmt);
-    if (st == DYBIT_OK) st = check_fmt(w_fmt);
-    if (st != DYBIT_OK) return st;
-    if (B < 0 || H < 1 || W < 1 || Cin < 1 || Cout < 0 || kh < 1 || kw < 1 || stride < 1 || pad < 0 ||
-        (relu != 0 && relu != 1) || H > (1 << 24) || W > (1 << 24) || Cin > (1 << 24))
-        return DYBIT_ERR_INVALID_ARG;
-    if (H + 2 * (int64_t)pad < kh || W + 2 * (int64_t)pad < kw) return DYBIT_ERR_INVALID_ARG;
-    if ((int64_t)kh * kw > (1 << 24) || (int64_t)kh * kw * Cin > 0x7fffffff) return DYBIT_ERR_INVALID_ARG;   // K fits an int
-    if ((Cin * x_fmt.bits) % 8 || (Cin * w_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
-    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
-    if (B == 0 || Cout == 0) return DYBIT_OK;
-    if (!x_scale || !w_scale || !Y || !X_codes || !Wt_codes) return DYBIT_ERR_NULL;
-    GemmArgs g{};
-    g.M = B * Ho * Wo; g.N = Cout; g.K = (int64_t)kh * kw * Cin;
-    g.A = X_codes; g.W = Wt_codes;
-    g.a_signed = x_fmt.is_signed; g.w_signed = w_fmt.is_signed;
-    g.a_scale = x_scale; g.w_scale = w_scale; g.bias = bias; g.relu = relu;
-    g.C = Y; g.ldc = Cout;
-    g.residual = residual;
-    g.absmax_bits = reinterpret_cast<uint32_t *>(y_absmax);
-    g.H = (int)H; g.Wd = (int)W; g.Cin = (int)Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
-    g.kh = kh; g.kw = kw; g.stride = stride; g.pad = pad;
-    g.a_bytes = B * H * W * (Cin * x_fmt.bits / 8);
-    g.w_bytes = Cout * (g.K * w_fmt.bits / 8);
-    if (launch_gemm_tiled(g, x_fmt.bits, w_fmt.bits, true, (hipStream_t)stream)) return launch_status();
-    const bool vec = (Cin % UNIT == 0) && aligned16(X_codes) && aligned16(Wt_codes);
-    dispatch_gemm(g, x_fmt.bits, w_fmt.bits, true, vec, (hipStream_t)stream);
-    return launch_status();
+    Epilogue e;
+    e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = c_absmax;
+    e.has_codes = true; e.q_fmt = c_fmt; e.q_scale = c_scale; e.q_out = C_codes;
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, e, C, ldc, stream);
 }
 
 extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
@@ -447,8 +507,9 @@ extern "C" dybit_status dybit_conv2d(int64_t B, int64_t H, int64_t W, int64_t Ci
                                      const float *bias, int32_t relu,
                                      float *Y, dybit_stream stream)
 {
-    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale,
-                       bias, relu, Y, nullptr, nullptr, stream);
+    Epilogue e;
+    e.bias = bias; e.relu = relu;
+    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, e, Y, stream);
 }
 
 extern "C" dybit_status dybit_conv2d_ex(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
@@ -458,6 +519,22 @@ extern "C" dybit_status dybit_conv2d_ex(int64_t B, int64_t H, int64_t W, int64_t
                                         const float *bias, const float *residual, int32_t relu,
                                         float *Y, float *y_absmax, dybit_stream stream)
 {
-    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale,
-                       bias, relu, Y, residual, y_absmax, stream);
+    Epilogue e;
+    e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = y_absmax;
+    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, e, Y, stream);
 }
+
+extern "C" dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                        int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                        const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                        const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                        const float *bias, const float *residual, int32_t relu,
+                                        float *Y, float *y_absmax,
+                                        dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream)
+{
+    Epilogue e;
+    e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = y_absmax;
+    e.has_codes = true; e.q_fmt = y_fmt; e.q_scale = y_scale; e.q_out = Y_codes;
+    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, e, Y, stream);
+}
+#endif   // !DYBIT_WB

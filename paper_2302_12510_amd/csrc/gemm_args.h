@@ -3,7 +3,18 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifndef DYBIT_WB
+#define DYBIT_WB 0
+#endif
+#if DYBIT_WB
+#define DYBIT_WB_NAME(name) name##_wb
+#else
+#define DYBIT_WB_NAME(name) name
+#endif
+
 namespace dybit {
+
+constexpr bool kWriteBack = DYBIT_WB != 0;
 
 struct GemmArgs {
     int64_t M, N, K;                 // conv: M = B*Ho*Wo, N = Cout, K = kh*kw*Cin
@@ -13,8 +24,14 @@ struct GemmArgs {
     const float *residual;           // optional: fp32 tensor laid out like C (same ldc), added before the ReLU
     int relu;
     uint32_t *absmax_bits;           // optional: running max |C| of the written values, as float bits (atomic max)
-    float *C;
+    float *C;                        // may be NULL when q_out is given
     int64_t ldc;
+    // optional write-back of the result as DyBit codes: M rows of q_row_bytes bytes (N codes, whole 32-bit words)
+    uint8_t *q_out;
+    const float *q_scale;
+    int q_bits, q_signed;
+    int64_t q_row_bytes;
+    int *async_error;                // device word that receives DYBIT_ERR_BAD_SCALE when *q_scale is unusable
     // convolution geometry (conv only)
     int H, Wd, Cin, Ho, Wo, kh, kw, stride, pad;
     int64_t a_bytes, w_bytes;        // sizes of the two code buffers
@@ -23,14 +40,26 @@ struct GemmArgs {
 // Tiled MFMA kernels for 4- and 8-bit operands with signed weights: the large-tile kernel
 // (gemm_fast.hip, 256 x 256) and the mid-size-tile kernel (gemm_mid.hip, 128 x 128), one
 // translation unit per weight format.  a_bits is 4 or 8; signedness comes from g.
+// Every kernel source is compiled twice: plain, and with DYBIT_WB=1 as the write-back build whose
+// epilogue also encodes the results (g.q_out must then be set); those entry points end in _wb.
 bool launch_gemm_fast_w0(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);   // W 4-bit signed
 bool launch_gemm_fast_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);   // W 8-bit signed
 bool launch_gemm_mid_w0(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_fast_w0_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_fast_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_mid_w0_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_mid_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 
 // fp8 matrix path for pairs of 4-bit formats with signed weights (gemm_f8.hip): the 256 x 256 tile
 // when `large`, else the 128 x 128 tile.
 bool launch_gemm_f8(const GemmArgs &g, bool conv, bool large, hipStream_t st);
+bool launch_gemm_f8_wb(const GemmArgs &g, bool conv, bool large, hipStream_t st);
+
+// General kernel (gemm.hip): any format pair and shape.  vec: operands are 16-byte aligned and K
+// (convolution: Cin) is a multiple of 16.
+void launch_gemm_general(const GemmArgs &g, int a_bits, int w_bits, bool conv, bool vec, hipStream_t st);
+void launch_gemm_general_wb(const GemmArgs &g, int a_bits, int w_bits, bool conv, bool vec, hipStream_t st);
 
 // Picks a tiled kernel for the problem (gemm_dispatch.cpp).  Returns false when the problem does
 // not meet their preconditions; the caller then uses the general kernel.

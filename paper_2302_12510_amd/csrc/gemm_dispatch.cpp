@@ -40,9 +40,14 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
     // two 4-bit operands: every value is exact in e4m3, so the fp8 matrix path (twice the fp16 rate,
     // byte decoders) takes them unless DYBIT_GEMM_MFMA=f16 asks for the fp16 kernels
     const char *mfma = getenv("DYBIT_GEMM_MFMA");
-    if (a_bits == 4 && w_bits == 4 && !(mfma && !strcmp(mfma, "f16"))) return launch_gemm_f8(g, conv, large, st);
-    if (large) return w_bits == 4 ? launch_gemm_fast_w0(g, a_bits, conv, st) : launch_gemm_fast_w2(g, a_bits, conv, st);
-    return w_bits == 4 ? launch_gemm_mid_w0(g, a_bits, conv, st) : launch_gemm_mid_w2(g, a_bits, conv, st);
+    const bool wb = g.q_out != nullptr;                             // write-back builds of the same kernels
+    if (a_bits == 4 && w_bits == 4 && !(mfma && !strcmp(mfma, "f16"))) return (wb ? launch_gemm_f8_wb : launch_gemm_f8)(g, conv, large, st);
+    if (large) {
+        if (w_bits == 4) return (wb ? launch_gemm_fast_w0_wb : launch_gemm_fast_w0)(g, a_bits, conv, st);
+        return (wb ? launch_gemm_fast_w2_wb : launch_gemm_fast_w2)(g, a_bits, conv, st);
+    }
+    if (w_bits == 4) return (wb ? launch_gemm_mid_w0_wb : launch_gemm_mid_w0)(g, a_bits, conv, st);
+    return (wb ? launch_gemm_mid_w2_wb : launch_gemm_mid_w2)(g, a_bits, conv, st);
 }
 
 }  // namespace dybit

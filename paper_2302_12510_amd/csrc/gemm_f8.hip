@@ -88,7 +88,7 @@ template <int NWM, int KG> struct Geom {
     static constexpr int THREADS = 64 * NWM * KG;
 };
 
-template <int FMT_A, int FMT_W, bool CONV, int NWM, int KG>
+template <int FMT_A, int FMT_W, bool CONV, int NWM, int KG, bool WB>
 __global__ __launch_bounds__(64 * NWM * KG, (NWM == 4 && KG == 1) ? 3 : 2)
 void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
@@ -275,7 +275,7 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
     }
 
     // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU), running maximum
-    epilogue_strip<CB>(g, acc, m0 + wr * 32, n0);
+    epilogue_strip<CB, WB>(g, acc, m0 + wr * 32, n0);
 }
 
 template <int FA, int FW, int NWM, int KG>
@@ -285,11 +285,11 @@ static void launch_cfg(const GemmArgs &g, bool conv, hipStream_t st)
     const int tiles_m = (int)((g.M + G::T - 1) / G::T), tiles_n = (int)((g.N + G::T - 1) / G::T);
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8)), block(G::THREADS);
     if (conv) {
-        auto k = gemm_f8_kernel<FA, FW, true, NWM, KG>;
+        auto k = gemm_f8_kernel<FA, FW, true, NWM, KG, kWriteBack>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
         hipLaunchKernelGGL(k, grid, block, G::LDS_BYTES, st, g, tiles_m, tiles_n);
     } else {
-        auto k = gemm_f8_kernel<FA, FW, false, NWM, KG>;
+        auto k = gemm_f8_kernel<FA, FW, false, NWM, KG, kWriteBack>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
         hipLaunchKernelGGL(k, grid, block, G::LDS_BYTES, st, g, tiles_m, tiles_n);
     }
@@ -308,7 +308,7 @@ static void launch(const GemmArgs &g, bool conv, bool large, hipStream_t st)
 
 }  // namespace f8
 
-bool launch_gemm_f8(const GemmArgs &g, bool conv, bool large, hipStream_t st)
+bool DYBIT_WB_NAME(launch_gemm_f8)(const GemmArgs &g, bool conv, bool large, hipStream_t st)
 {
     if (g.a_signed) f8::launch<fast::F4S>(g, conv, large, st);
     else f8::launch<fast::F4U>(g, conv, large, st);

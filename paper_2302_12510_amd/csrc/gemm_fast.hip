@@ -46,7 +46,7 @@ constexpr int LDS_BYTES = 2 * STAGE_BYTES;
 // ---------------------------------------------------------------------------
 // Kernel.  RB = 32-row blocks of A per wave: 1 -> eight waves (two per SIMD), 2 -> four waves.
 // ---------------------------------------------------------------------------
-template <int FMT_A, int FMT_W, bool CONV, int RB>
+template <int FMT_A, int FMT_W, bool CONV, int RB, bool WB>
 __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using CA = Codec<FMT_A>;
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
 
     // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU), running maximum
 #pragma unroll
-    for (int i = 0; i < RB; ++i) epilogue_strip<8>(g, acc[i], m0 + (wave * RB + i) * 32, n0);
+    for (int i = 0; i < RB; ++i) epilogue_strip<8, WB>(g, acc[i], m0 + (wave * RB + i) * 32, n0);
 }
 
 constexpr int kRowBlocks = 1;   // row blocks per wave of the instantiated kernels
@@ -251,11 +251,11 @@ static void launch(const GemmArgs &g, bool conv, hipStream_t st)
     const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8)), block(512 / kRowBlocks);
     if (conv) {
-        auto k = gemm_fast_kernel<FA, FW, true, kRowBlocks>;
+        auto k = gemm_fast_kernel<FA, FW, true, kRowBlocks, kWriteBack>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         hipLaunchKernelGGL(k, grid, block, LDS_BYTES, st, g, tiles_m, tiles_n);
     } else {
-        auto k = gemm_fast_kernel<FA, FW, false, kRowBlocks>;
+        auto k = gemm_fast_kernel<FA, FW, false, kRowBlocks, kWriteBack>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         hipLaunchKernelGGL(k, grid, block, LDS_BYTES, st, g, tiles_m, tiles_n);
     }
@@ -264,7 +264,7 @@ static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 }  // namespace fast
 
 // One translation unit per weight format (compile time); the entry point's name carries it.
-#define DYBIT_FAST_NAME2(w) launch_gemm_fast_w##w
+#define DYBIT_FAST_NAME2(w) DYBIT_WB_NAME(launch_gemm_fast_w##w)
 #define DYBIT_FAST_NAME(w) DYBIT_FAST_NAME2(w)
 bool DYBIT_FAST_NAME(DYBIT_FAST_W)(const GemmArgs &g, int a_bits, bool conv, hipStream_t st)
 {

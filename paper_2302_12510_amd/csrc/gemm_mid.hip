@@ -49,7 +49,7 @@ template <int KG> struct Geom {
 };
 static_assert(Geom<2>::LDS_BYTES >= 4 * 4 * 16 * 64 * 4, "reduction buffer must fit in the stages");
 
-template <int FMT_A, int FMT_W, bool CONV, int KG>
+template <int FMT_A, int FMT_W, bool CONV, int KG, bool WB>
 __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using CA = Codec<FMT_A>;
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
     }
 
     // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU), running maximum
-    epilogue_strip<4>(g, acc, m0 + wr * 32, n0);
+    epilogue_strip<4, WB>(g, acc, m0 + wr * 32, n0);
 }
 
 template <int FA, int FW, int KG>
@@ -243,11 +243,11 @@ static void launch_kg(const GemmArgs &g, bool conv, hipStream_t st, int tiles_m,
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8), 1, 1), block(256 * KG);
     constexpr int lds_bytes = Geom<KG>::LDS_BYTES;
     if (conv) {
-        auto k = gemm_mid_kernel<FA, FW, true, KG>;
+        auto k = gemm_mid_kernel<FA, FW, true, KG, kWriteBack>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         hipLaunchKernelGGL(k, grid, block, lds_bytes, st, g, tiles_m, tiles_n);
     } else {
-        auto k = gemm_mid_kernel<FA, FW, false, KG>;
+        auto k = gemm_mid_kernel<FA, FW, false, KG, kWriteBack>;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         hipLaunchKernelGGL(k, grid, block, lds_bytes, st, g, tiles_m, tiles_n);
     }
@@ -268,7 +268,7 @@ static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 }  // namespace mid
 
 // One translation unit per weight format (compile time); the entry point's name carries it.
-#define DYBIT_MID_NAME2(w) launch_gemm_mid_w##w
+#define DYBIT_MID_NAME2(w) DYBIT_WB_NAME(launch_gemm_mid_w##w)
 #define DYBIT_MID_NAME(w) DYBIT_MID_NAME2(w)
 bool DYBIT_MID_NAME(DYBIT_MID_W)(const GemmArgs &g, int a_bits, bool conv, hipStream_t st)
 {

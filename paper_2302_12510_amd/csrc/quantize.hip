@@ -457,6 +457,15 @@ extern "C" dybit_status dybit_dequantize(const uint8_t *codes, size_t n, dybit_f
     return launch_status();
 }
 
+namespace dybit {
+// Device address of the asynchronous error flag on the current device (each device has its own copy).
+int *async_error_word()
+{
+    void *ptr = nullptr;
+    return hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_async_error)) == hipSuccess ? static_cast<int *>(ptr) : nullptr;
+}
+}  // namespace dybit
+
 extern "C" dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream)
 {
     if (!flag_out) return DYBIT_ERR_NULL;

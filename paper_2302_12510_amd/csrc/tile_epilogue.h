@@ -1,37 +1,63 @@
 // Epilogue shared by the tiled matrix-product kernels: C = acc * (sA sW) (+ bias) (+ residual) (ReLU),
-// optional running maximum of |C|, for the 32-row strip of accumulator blocks one wave holds.
+// optional running maximum of |C|, optional write-back of C as DyBit codes (Sec. III-B), for the
+// 32-row strip of accumulator blocks one wave holds.
 //
 // Accumulator v of a lane is row 8 (v / 4) + 4 (lane / 32) + v % 4 and column lane % 32 of its
 // 32 x 32 block.  The strip is stored through a buffer descriptor that starts at the strip's first
 // row and ends after its last valid row, with 32-bit byte offsets: a row past M falls outside the
 // descriptor and a column past N gets an offset of 2^31, so the hardware drops those stores and the
-// loop needs neither 64-bit address arithmetic nor per-element branches.
+// loop needs neither 64-bit address arithmetic nor per-element branches.  The packed codes go out
+// the same way through a descriptor of their own; a NULL fp32 output becomes an empty descriptor.
 #ifndef DYBIT_TILE_EPILOGUE_H
 #define DYBIT_TILE_EPILOGUE_H
 
+#include "../../include/dybit.h"
 #include "dybit_codec.h"
 #include "gemm_args.h"
+#include "requant.h"
 
 namespace dybit {
 
-template <int CB, bool HAS_RES>
+template <int CB, bool HAS_RES, bool QOUT>
 __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB], const int64_t m_strip,
                                              const int64_t n0, const int rows, const float alpha)
 {
     const int lane = threadIdx.x & 63, kq = lane >> 5;
     const uint32_t ldc4 = (uint32_t)g.ldc * 4u;
     const int records = (int)((uint32_t)rows * ldc4);
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(g.C + m_strip * g.ldc, 0, records, 0x00020000);
+    float *const c_base = g.C ? g.C + m_strip * g.ldc : const_cast<float *>(g.a_scale);   // no fp32 output: empty descriptor
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(c_base, 0, g.C ? records : 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(HAS_RES ? g.residual + m_strip * g.ldc : g.C), 0, HAS_RES ? records : 0, 0x00020000);
     const bool track = g.absmax_bits != nullptr;
     float mx = 0.0f;
+    // write-back as codes: rows of q_row_bytes bytes
+    const uint32_t qrow = QOUT ? (uint32_t)g.q_row_bytes : 0u;
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        QOUT ? (void *)(g.q_out + m_strip * g.q_row_bytes) : (void *)g.a_scale, 0, QOUT ? (int)((uint32_t)rows * qrow) : 0, 0x00020000);
+    Requant rqp;
+    if (QOUT) {
+        rqp = make_requant(g.q_scale, g.q_bits, g.q_signed);
+        if (!rqp.ok) {                                              // unusable scale: no codes, flag the call
+            if (m_strip == 0 && n0 == 0 && lane == 0) *g.async_error = DYBIT_ERR_BAD_SCALE;
+        }
+    }
 #pragma unroll
     for (int j = 0; j < CB; ++j) {
         const int64_t n = n0 + j * 32 + (lane & 31);
         const bool n_ok = n < g.N;
         const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
-        const uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
+        uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
+        // The variants of this function are the two sides of one branch and walk the same offsets.
+        // Without this barrier the compiler computes all 128 of them once above the branch, where
+        // they do not fit the register file beside the accumulators and are spilled.
+        asm volatile("" : "+v"(off0));
+        PackSlot slot{};
+        uint32_t qoff = 0;
+        if (QOUT) {
+            slot = pack_slot(g.q_bits, lane, (uint32_t)n);
+            qoff = ((n_ok && slot.stores && rqp.ok) ? slot.byte_off : 0x80000000u) + (uint32_t)(4 * kq) * qrow;
+        }
         float res[16];
         if (HAS_RES) {                                                  // out-of-range elements read 0
             uint32_t off = off0;
@@ -54,12 +80,19 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
                 mx = fmaxf(mx, (n_ok && r < rows) ? fabsf(c) : 0.0f);
             }
             off += (v & 3) == 3 ? 5u * ldc4 : ldc4;                     // rows 0-3, 8-11, 16-19, 24-27 (+ 4 kq)
+            if (QOUT) {
+                const uint32_t w = pack_word(requant_code(c, rqp), g.q_bits, lane, slot);
+                __builtin_amdgcn_raw_buffer_store_b32(w, rq, qoff, 0, 2);
+                qoff += (v & 3) == 3 ? 5u * qrow : qrow;
+            }
         }
     }
     return mx;
 }
 
-template <int CB>
+// WB: the kernel is the write-back build (codes are written, see requant.h); kernels are compiled
+// in both forms so that the plain form carries none of the encoder's registers or branches.
+template <int CB, bool WB>
 __device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB],
                                                const int64_t m_strip, const int64_t n0)
 {
@@ -68,9 +101,12 @@ __device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f3
     const int64_t rows_left = g.M - m_strip;                       // uniform over the wave
     const int rows = rows_left >= 32 ? 32 : rows_left > 0 ? (int)rows_left : 0;
     float mx = 0.0f;
-    if (g.ldc < (1 << 23)) {
-        mx = g.residual ? store_strip<CB, true>(g, acc, m_strip, n0, rows, alpha)
-                        : store_strip<CB, false>(g, acc, m_strip, n0, rows, alpha);
+    if (WB) {                                                       // the host has checked ldc and the row size
+        mx = g.residual ? store_strip<CB, true, true>(g, acc, m_strip, n0, rows, alpha)
+                        : store_strip<CB, false, true>(g, acc, m_strip, n0, rows, alpha);
+    } else if (g.ldc < (1 << 23)) {
+        mx = g.residual ? store_strip<CB, true, false>(g, acc, m_strip, n0, rows, alpha)
+                        : store_strip<CB, false, false>(g, acc, m_strip, n0, rows, alpha);
     } else {                                                        // leading dimension too large for 32-bit offsets
 #pragma unroll
         for (int j = 0; j < CB; ++j) {

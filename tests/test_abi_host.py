@@ -105,6 +105,21 @@ def test_argument_errors_without_gpu():
     assert L.dybit_gemm_ex(0, 8, 16, null, f4, p, null, f4, p, null, null, 0, null, 8, null, None) == B.OK
     assert L.dybit_conv2d_ex(1, 8, 8, 16, 8, 3, 3, 1, 1, null, f4, p, p, f4, p, null, null, 0, p, null, None) == B.ERR_NULL
     assert L.dybit_conv2d_ex(1, 8, 8, 16, 8, 3, 3, 0, 1, p, f4, p, p, f4, p, null, p, 0, p, p, None) == B.ERR_INVALID_ARG
+    # the write-back variants: output format, whole words per row, at least one output
+    f6, f2 = B.fmt(6, False), B.fmt(2, True)
+    wb = lambda N=8, c=p, cf=f4, cs=p, cc=p: \
+        L.dybit_gemm_wb(8, N, 16, p, f4, p, p, f4, p, null, null, 0, c, N, null, cf, cs, cc, None)
+    assert wb(cf=f2) == B.ERR_UNSUPPORTED_BITS                   # the epilogue packs 4-, 6- and 8-bit codes
+    assert wb(cf=bad) == B.ERR_UNSUPPORTED_BITS
+    assert wb(cf=f6) == B.ERR_ALIGNMENT                          # 8 codes of 6 bits: a row is not whole words
+    assert wb(N=4) == B.ERR_ALIGNMENT                            # 16 bits per row
+    assert wb(cc=C.c_void_p(p.value + 1)) == B.ERR_ALIGNMENT
+    assert wb(c=null, cc=null) == B.ERR_NULL
+    assert wb(cs=null) == B.ERR_NULL
+    assert L.dybit_conv2d_wb(1, 8, 8, 16, 8, 3, 3, 1, 1, p, f4, p, p, f4, p, null, null, 0, null, null,
+                             f4, p, null, None) == B.ERR_NULL
+    assert L.dybit_conv2d_wb(1, 8, 8, 16, 12, 3, 3, 1, 1, p, f4, p, p, f4, p, null, null, 0, p, null,
+                             f4, p, p, None) == B.ERR_ALIGNMENT
     assert L.dybit_scale_from_absmax(null, f4, p, None) == B.ERR_NULL
     assert L.dybit_scale_from_absmax(p, bad, p, None) == B.ERR_UNSUPPORTED_BITS
     assert L.dybit_get_last_async_error(None, None) == B.ERR_NULL
