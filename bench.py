@@ -106,6 +106,17 @@ def bench_network(args):
     assert B.dybit_get_last_async_error() == B.OK
     shapes = net.gemm_shapes(batch, 224)
     flops = sum(2.0 * m * n * k for _, m, n, k in shapes)
+    # the same network with calibrated (static) scales and the write-back fused into the epilogues
+    net.calibrate(x)
+    for _ in range(args.warmup):
+        net.forward(x, static=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        net.forward(x, static=True)
+    torch.cuda.synchronize()
+    ms_static = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert B.dybit_get_last_async_error() == B.OK
     out = {
         "metric": "DyBit GEMM effective TOPS (+ quantize GB/s), % of roofline",
         "value": round(flops / (ms * 1e-3) / 1e12, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
@@ -114,6 +125,12 @@ def bench_network(args):
         "config": {"workload": name, "gemms": len(shapes), "GMAC": round(flops / 2e9, 1),
                    "step": "per layer scale + quantize + conv (bias, shortcut, ReLU and max|result| in the epilogue); pooling in torch"},
         "roofline": None,
+        "fused_write_back": {"ms_per_step": round(ms_static, 4), "TOPS": round(flops / (ms_static * 1e-3) / 1e12, 3),
+                             "step": "scales fixed by a calibration pass; every convolution whose consumers agree on a "
+                                     "format writes DyBit codes from its epilogue (dybit_conv2d_wb), fp32 only where a "
+                                     "shortcut, a pooling or the output needs it",
+                             "layers_writing_codes": sum(1 for p in net.plan.values() if p["fmt"]),
+                             "layers_writing_codes_only": sum(1 for p in net.plan.values() if not p["fp32"])},
     }
     if not args.no_cpu_baseline:
         # the oracle's convolution on a few images of one mid-network layer; the forward pass

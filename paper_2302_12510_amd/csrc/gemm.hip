@@ -322,8 +322,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
     }
 
     // epilogue (shared with the tiled kernels): each wave stores its two 32-row strips of 64 columns
-#pragma unroll
-    for (int i = 0; i < 2; ++i) epilogue_strip<2, WB>(g, acc[i], m0 + wm * 64 + i * 32, n0 + wn * 64);
+    epilogue_strip<2, WB>(g, acc[0], m0 + wm * 64, n0 + wn * 64);
+    epilogue_strip<2, WB>(g, acc[1], m0 + wm * 64 + 32, n0 + wn * 64);
 }
 
 template <int BA, int BW>

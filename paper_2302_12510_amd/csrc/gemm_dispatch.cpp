@@ -3,8 +3,9 @@
 // Both need 4- or 8-bit operands, signed weights, K (convolution: Cin) a multiple of 64 so that
 // a 64-wide k group is one run of whole 128-bit loads inside one filter tap, 16-byte aligned
 // code buffers, and buffers below 2 GiB (32-bit buffer offsets).  The 256 x 256 kernel does the
-// least decode work per MFMA and is used when its tiles can fill the 256 compute units and N is
-// wide enough for them; the 128 x 128 kernel takes the rest.  The environment variable
+// least decode work per MFMA and is used when its tiles can fill the 256 compute units, N is
+// wide enough for them and K is long enough for the main loop to outweigh the epilogue; the
+// 128 x 128 kernel takes the rest.  The environment variable
 // DYBIT_GEMM_KERNEL = large | mid | general overrides the choice whenever the named kernel's
 // preconditions hold (tests use it to reach a given kernel with small shapes); DYBIT_GEMM_MFMA=f16
 // keeps pairs of 4-bit operands on the fp16 kernels instead of the fp8 ones.
@@ -33,9 +34,14 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
         large = false;
     } else {
         // Too few 256 x 256 tiles cannot fill 256 compute units, and a narrow N wastes most of a
-        // 256-wide tile.
+        // 256-wide tile.  With a short K the epilogue (the stores of C, the loads of the shortcut)
+        // dominates, and the 128 x 128 kernel with three workgroups per compute unit keeps more
+        // of those memory operations in flight: measured over M x N from 6272 x 2048 to
+        // 401408 x 256, it is 1.1 to 1.7 times faster up to K = 512, level at K = 1024 (fp16
+        // kernels) or K = 2048 (fp8 kernels), and 10 to 30 % slower beyond.
         const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-        large = g.N > 128 && tiles256 >= 128;
+        const bool both4 = a_bits == 4 && w_bits == 4;
+        large = g.N > 128 && tiles256 >= 128 && g.K >= (both4 ? 2048 : 1024);
     }
     // two 4-bit operands: every value is exact in e4m3, so the fp8 matrix path (twice the fp16 rate,
     // byte decoders) takes them unless DYBIT_GEMM_MFMA=f16 asks for the fp16 kernels

@@ -19,18 +19,22 @@
 
 namespace dybit {
 
+// G: fractional bits kept by the magic-number rounding.  The error of c is below 2^(m-22), so
+// G = 12 serves every format (m <= 8); a format with fewer magnitude bits could afford more.
 struct Requant {
-    static constexpr int G = 12;                                                       // 2^(m-23) << 2^-(G+1) for m <= 8
+    static constexpr int G = 12;
     static constexpr uint32_t kMagic = ((uint32_t)(127 + 23 - G) << 23) | 0x400000u;   // 1.5 * 2^(23-G)
     static constexpr uint32_t kRound = kMagic + (1u << (G - 1));
+    static constexpr uint32_t kFracMask = (1u << G) - 1u, kFracHalf = 1u << (G - 1);
     float rinv;         // fl(1 / s)
     float p, s2;        // power of two that brings s into [1, 2), and s * p
     float vmax;         // 2^(m-1): the largest magnitude
     float neg_grid;     // -2^(m-1): -(codes per unit) on the fraction grid below 1
     float inv_grid;     // 2^-(m-1)
     float two_m;        // 2^m
+    float floor_x;      // lower clamp of the input: -inf (signed: |x| follows) or 0 (unsigned)
     uint32_t recip_k;   // (254 + m - 1) << 23: constant of the bit-pattern subtraction
-    uint32_t top;       // 2^m - 1, the all-ones magnitude
+    uint32_t m;         // magnitude bits
     uint32_t half;      // 2^(m-1): first code of the part above 1
     uint32_t sign_mask, sign_shift;
     bool is_signed;
@@ -47,12 +51,13 @@ __device__ __forceinline__ Requant make_requant(const float *scale, int bits, in
     r.p = __uint_as_float((254u - e) << 23);
     r.s2 = s * r.p;
     const int m = is_signed ? bits - 1 : bits;
+    r.m = (uint32_t)m;
     r.vmax = (float)(1u << (m - 1));
     r.neg_grid = -r.vmax;
     r.inv_grid = __uint_as_float((uint32_t)(127 - (m - 1)) << 23);
     r.two_m = (float)(1u << m);
+    r.floor_x = is_signed ? -__builtin_inff() : 0.0f;
     r.recip_k = (uint32_t)(254 + m - 1) << 23;
-    r.top = (1u << m) - 1u;
     r.half = 1u << (m - 1);
     r.is_signed = is_signed != 0;
     r.sign_mask = is_signed ? (1u << m) : 0u;
@@ -60,30 +65,63 @@ __device__ __forceinline__ Requant make_requant(const float *scale, int bits, in
     return r;
 }
 
-// Exact decision at the midpoint between magnitude codes `code - 1` and `code`.  ax = |x| (signed
-// formats) or max(x, 0); NaN -> 0.
-__device__ __forceinline__ uint32_t requant_settle(float x, float ax, uint32_t code, const Requant &r)
+// Fast path, first half: the bit pattern of (-c or 2^m - c) + magic for the value x.  The G low
+// bits are the rounded fraction of c; requant_needs_settling() says whether they read one half.
+// A NaN comes out as some finite pattern; the caller tests for NaN separately.
+__device__ __forceinline__ uint32_t requant_rounded(float x, const Requant &r)
 {
-    if (x != x) return 0u;
-    const uint32_t lo = code - 1u;                                  // code >= 1 whenever the G bits read one half
+    const float q = fminf(fabsf(fmaxf(x, r.floor_x)) * r.rinv, r.vmax);        // |x| or max(x, 0), over s, saturated
+    const float lin = q * r.neg_grid;                                          // -c
+    const float rec = __uint_as_float(r.recip_k - __float_as_uint(q));         // 2^m - c
+    return __float_as_uint((q < 1.0f ? lin : rec) + __uint_as_float(Requant::kMagic));
+}
+
+__device__ __forceinline__ bool requant_needs_settling(uint32_t zb)
+{
+    return (zb & Requant::kFracMask) == Requant::kFracHalf;
+}
+
+// The same test in a form that accumulates with an unsigned minimum: zero exactly when the G low
+// bits of zb read one half (the field moves to the top of the word and the addition flips its top bit).
+__device__ __forceinline__ uint32_t requant_settle_key(uint32_t zb)
+{
+    return (zb << (32 - Requant::G)) + 0x80000000u;
+}
+
+// Fast path, second half: the magnitude code, c rounded half up (the low m bits of the difference:
+// the 2^m of the upper form drops out).
+__device__ __forceinline__ uint32_t requant_magnitude(uint32_t zb, const Requant &r)
+{
+    return __builtin_amdgcn_ubfe(Requant::kRound - zb, Requant::G, r.m);
+}
+
+// Exact decision at the midpoint between magnitude codes `code - 1` and `code`, for a value whose
+// rounded fraction read one half (so code >= 1).  NaN -> 0.
+__device__ __forceinline__ uint32_t requant_settle(float x, uint32_t code, const Requant &r)
+{
+    const float ax = fabsf(fmaxf(x, r.floor_x));
+    const uint32_t lo = code - 1u;
     const float h = (float)lo + 0.5f;
     const float mid = lo < r.half ? h * r.inv_grid : __uint_as_float(r.recip_k - __float_as_uint(r.two_m - h));
     const float d = fmaf(-r.s2, mid, ax * r.p);                     // sign(|x| - s * mid), exact
-    return (d > 0.0f || (d == 0.0f && (lo & 1u))) ? code : lo;
+    const uint32_t settled = (d > 0.0f || (d == 0.0f && (lo & 1u))) ? code : lo;
+    return x != x ? 0u : settled;
 }
 
+// Sign bit for a signed format (sign_mask is 0 for an unsigned one); a zero magnitude never carries it.
+__device__ __forceinline__ uint32_t requant_with_sign(uint32_t mag, float x, const Requant &r)
+{
+    const uint32_t sign = (__float_as_uint(x) >> r.sign_shift) & r.sign_mask;
+    return mag ? (mag | sign) : 0u;
+}
+
+// One value, all steps (the epilogue below runs the steps in phases over 16 values instead).
 __device__ __forceinline__ uint32_t requant_code(float x, const Requant &r)
 {
-    const float ax = r.is_signed ? fabsf(x) : fmaxf(x, 0.0f);
-    const float q = fminf(ax * r.rinv, r.vmax);
-    const float lin = q * r.neg_grid;                                          // -c
-    const float rec = __uint_as_float(r.recip_k - __float_as_uint(q));         // 2^m - c
-    const float y = q < 1.0f ? lin : rec;
-    const uint32_t zb = __float_as_uint(y + __uint_as_float(Requant::kMagic));
-    uint32_t code = ((Requant::kRound - zb) >> Requant::G) & r.top;
-    if (((zb & ((1u << Requant::G) - 1u)) == (1u << (Requant::G - 1))) | (x != x)) code = requant_settle(x, ax, code, r);
-    const uint32_t sign = (__float_as_uint(x) >> r.sign_shift) & r.sign_mask;
-    return code ? (code | sign) : 0u;                                          // a zero magnitude never carries the sign
+    const uint32_t zb = requant_rounded(x, r);
+    uint32_t mag = requant_magnitude(zb, r);
+    if (requant_needs_settling(zb) | (x != x)) mag = requant_settle(x, mag, r);
+    return requant_with_sign(mag, x, r);
 }
 
 // ---- packing across lanes -----------------------------------------------------------------------
@@ -107,12 +145,13 @@ struct PackSlot {
     bool stores;
 };
 
-__device__ __forceinline__ PackSlot pack_slot(int bits, int lane, uint32_t col)
+template <int BITS>
+__device__ __forceinline__ PackSlot pack_slot(int lane, uint32_t col)
 {
     PackSlot p;
-    if (bits == 8) {
+    if (BITS == 8) {
         p.shift = (lane & 3) * 8;  p.byte_off = col;            p.stores = (lane & 3) == 0;
-    } else if (bits == 4) {
+    } else if (BITS == 4) {
         p.shift = (lane & 7) * 4;  p.byte_off = col >> 1;       p.stores = (lane & 7) == 0;
     } else {                                                    // 6-bit: 16 codes = three words
         const uint32_t k = (lane >> 2) & 3;                     // which group of four inside the 16
@@ -121,12 +160,13 @@ __device__ __forceinline__ PackSlot pack_slot(int bits, int lane, uint32_t col)
     return p;
 }
 
-__device__ __forceinline__ uint32_t pack_word(uint32_t code, int bits, int lane, const PackSlot &p)
+template <int BITS>
+__device__ __forceinline__ uint32_t pack_word(uint32_t code, int lane, const PackSlot &p)
 {
     uint32_t w = or_quad(code << p.shift);
-    if (bits == 4) {
+    if (BITS == 4) {
         w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xf, 0xf, true);   // row_half_mirror: the other four of eight
-    } else if (bits == 6) {
+    } else if (BITS == 6) {
         // four lanes hold 24 bits; word k of the three takes the rest from the next group of four
         const uint32_t k = (lane >> 2) & 3;
         const uint32_t next = (uint32_t)__shfl_down((int)w, 4, 16);

@@ -6,8 +6,7 @@
 // 32 x 32 block.  The strip is stored through a buffer descriptor that starts at the strip's first
 // row and ends after its last valid row, with 32-bit byte offsets: a row past M falls outside the
 // descriptor and a column past N gets an offset of 2^31, so the hardware drops those stores and the
-// loop needs neither 64-bit address arithmetic nor per-element branches.  The packed codes go out
-// the same way through a descriptor of their own; a NULL fp32 output becomes an empty descriptor.
+// loop needs neither 64-bit address arithmetic nor per-element branches.
 #ifndef DYBIT_TILE_EPILOGUE_H
 #define DYBIT_TILE_EPILOGUE_H
 
@@ -18,46 +17,30 @@
 
 namespace dybit {
 
-template <int CB, bool HAS_RES, bool QOUT>
+template <int CB, bool HAS_RES>
 __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB], const int64_t m_strip,
                                              const int64_t n0, const int rows, const float alpha)
 {
     const int lane = threadIdx.x & 63, kq = lane >> 5;
+    // The variants of this function are the sides of one branch and derive the same columns, bias
+    // values and store offsets from the lane number.  Without this barrier the compiler computes
+    // all of them once above the branch (128 offsets per lane), where they do not fit the register
+    // file beside the accumulators and are spilled.
+    int col = lane & 31;
+    asm volatile("" : "+v"(col));
     const uint32_t ldc4 = (uint32_t)g.ldc * 4u;
     const int records = (int)((uint32_t)rows * ldc4);
-    float *const c_base = g.C ? g.C + m_strip * g.ldc : const_cast<float *>(g.a_scale);   // no fp32 output: empty descriptor
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(c_base, 0, g.C ? records : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(g.C + m_strip * g.ldc, 0, records, 0x00020000);
     const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(HAS_RES ? g.residual + m_strip * g.ldc : g.C), 0, HAS_RES ? records : 0, 0x00020000);
     const bool track = g.absmax_bits != nullptr;
     float mx = 0.0f;
-    // write-back as codes: rows of q_row_bytes bytes
-    const uint32_t qrow = QOUT ? (uint32_t)g.q_row_bytes : 0u;
-    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
-        QOUT ? (void *)(g.q_out + m_strip * g.q_row_bytes) : (void *)g.a_scale, 0, QOUT ? (int)((uint32_t)rows * qrow) : 0, 0x00020000);
-    Requant rqp;
-    if (QOUT) {
-        rqp = make_requant(g.q_scale, g.q_bits, g.q_signed);
-        if (!rqp.ok) {                                              // unusable scale: no codes, flag the call
-            if (m_strip == 0 && n0 == 0 && lane == 0) *g.async_error = DYBIT_ERR_BAD_SCALE;
-        }
-    }
 #pragma unroll
     for (int j = 0; j < CB; ++j) {
-        const int64_t n = n0 + j * 32 + (lane & 31);
+        const int64_t n = n0 + j * 32 + col;
         const bool n_ok = n < g.N;
         const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
-        uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
-        // The variants of this function are the two sides of one branch and walk the same offsets.
-        // Without this barrier the compiler computes all 128 of them once above the branch, where
-        // they do not fit the register file beside the accumulators and are spilled.
-        asm volatile("" : "+v"(off0));
-        PackSlot slot{};
-        uint32_t qoff = 0;
-        if (QOUT) {
-            slot = pack_slot(g.q_bits, lane, (uint32_t)n);
-            qoff = ((n_ok && slot.stores && rqp.ok) ? slot.byte_off : 0x80000000u) + (uint32_t)(4 * kq) * qrow;
-        }
+        const uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
         float res[16];
         if (HAS_RES) {                                                  // out-of-range elements read 0
             uint32_t off = off0;
@@ -80,10 +63,94 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
                 mx = fmaxf(mx, (n_ok && r < rows) ? fabsf(c) : 0.0f);
             }
             off += (v & 3) == 3 ? 5u * ldc4 : ldc4;                     // rows 0-3, 8-11, 16-19, 24-27 (+ 4 kq)
-            if (QOUT) {
-                const uint32_t w = pack_word(requant_code(c, rqp), g.q_bits, lane, slot);
-                __builtin_amdgcn_raw_buffer_store_b32(w, rq, qoff, 0, 2);
-                qoff += (v & 3) == 3 ? 5u * qrow : qrow;
+        }
+    }
+    return mx;
+}
+
+// The same strip with the write-back encoder (requant.h): per 32 x 32 block, three phases over the
+// lane's values (eight at a time) so that the instruction streams of the values interleave and the only branch is
+// one per block -- (1) result, optional fp32 store, rounded real-valued code; (2) only if some
+// lane's value sits within 2^-G of a decision point (or is NaN): the exact decision for those;
+// (3) sign, packing across lanes, store of the packed words through a descriptor of their own.
+// A NULL fp32 output becomes an empty descriptor whose stores the hardware drops.
+template <int CB, bool HAS_RES, int BITS>
+__device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f32x16 (&acc)[CB], const int64_t m_strip,
+                                                const int64_t n0, const int rows, const float alpha)
+{
+    const int lane = threadIdx.x & 63, kq = lane >> 5;
+    int col = lane & 31;
+    asm volatile("" : "+v"(col));                                      // see store_strip
+    const uint32_t ldc4 = (uint32_t)g.ldc * 4u;
+    const int records = (int)((uint32_t)rows * ldc4);
+    float *const c_base = g.C ? g.C + m_strip * g.ldc : const_cast<float *>(g.a_scale);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(c_base, 0, g.C ? records : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(HAS_RES ? g.residual + m_strip * g.ldc : g.a_scale), 0, HAS_RES ? records : 0, 0x00020000);
+    const uint32_t qrow = (uint32_t)g.q_row_bytes;
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(g.q_out + m_strip * g.q_row_bytes, 0,
+                                                                        (int)((uint32_t)rows * qrow), 0x00020000);
+    const Requant rqp = make_requant(g.q_scale, BITS, g.q_signed);
+    if (!rqp.ok && m_strip == 0 && n0 == 0 && lane == 0) *g.async_error = DYBIT_ERR_BAD_SCALE;   // no codes, flag the call
+    constexpr int GV = 8;
+    const bool track = g.absmax_bits != nullptr;
+    const float relu_floor = g.relu ? 0.0f : -__builtin_inff();        // ReLU as a maximum: no select per value
+    float mx = 0.0f;
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+        const int64_t n = n0 + j * 32 + col;
+        const bool n_ok = n < g.N;
+        const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
+        const uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
+        const PackSlot slot = pack_slot<BITS>(lane, (uint32_t)n);
+        uint32_t qoff = ((n_ok && slot.stores && rqp.ok) ? slot.byte_off : 0x80000000u) + (uint32_t)(4 * kq) * qrow;
+        uint32_t off = off0, roff = off0;
+#pragma unroll
+        for (int h = 0; h < 16; h += GV) {                                   // GV values at a time: fewer live registers
+            float res[GV];
+            if (HAS_RES) {
+#pragma unroll
+                for (int u = 0; u < GV; ++u) {
+                    res[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, roff, 0, 0));
+                    roff += ((h + u) & 3) == 3 ? 5u * ldc4 : ldc4;
+                }
+            }
+            float c[GV];
+            uint32_t zb[GV];
+            uint32_t settle_key = 0xffffffffu;                               // minimum over the values: 0 = some value needs phase 2
+#pragma unroll
+            for (int u = 0; u < GV; ++u) {                                   // phase 1
+                const int v = h + u;
+                c[u] = acc[j][v] * alpha + b;
+                if (HAS_RES) c[u] += res[u];
+                c[u] = fmaxf(c[u], relu_floor);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c[u]), rsrc, off, 0, 2);
+                off += (v & 3) == 3 ? 5u * ldc4 : ldc4;
+                if (track) {
+                    const int r = 8 * (v >> 2) + 4 * kq + (v & 3);
+                    mx = fmaxf(mx, (n_ok && r < rows) ? fabsf(c[u]) : 0.0f);
+                }
+                zb[u] = requant_rounded(c[u], rqp);
+                settle_key = min(settle_key, (c[u] != c[u]) ? 0u : requant_settle_key(zb[u]));
+            }
+            uint32_t code[GV];
+#pragma unroll
+            for (int u = 0; u < GV; ++u) code[u] = requant_magnitude(zb[u], rqp);
+            if (__builtin_amdgcn_ballot_w64(settle_key == 0u)) {             // phase 2 (uniform branch)
+#pragma unroll
+                for (int u = 0; u < GV; ++u) {
+                    const uint32_t fixed = requant_settle(c[u], code[u], rqp);
+                    code[u] = (requant_needs_settling(zb[u]) | (c[u] != c[u])) ? fixed : code[u];
+                }
+            }
+            if (rqp.is_signed) {                                             // uniform
+#pragma unroll
+                for (int u = 0; u < GV; ++u) code[u] = requant_with_sign(code[u], c[u], rqp);
+            }
+#pragma unroll
+            for (int u = 0; u < GV; ++u) {                                   // phase 3
+                __builtin_amdgcn_raw_buffer_store_b32(pack_word<BITS>(code[u], lane, slot), rq, qoff, 0, 2);
+                qoff += ((h + u) & 3) == 3 ? 5u * qrow : qrow;
             }
         }
     }
@@ -101,12 +168,19 @@ __device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f3
     const int64_t rows_left = g.M - m_strip;                       // uniform over the wave
     const int rows = rows_left >= 32 ? 32 : rows_left > 0 ? (int)rows_left : 0;
     float mx = 0.0f;
-    if (WB) {                                                       // the host has checked ldc and the row size
-        mx = g.residual ? store_strip<CB, true, true>(g, acc, m_strip, n0, rows, alpha)
-                        : store_strip<CB, false, true>(g, acc, m_strip, n0, rows, alpha);
+    if (WB) {                                                       // the host has checked ldc, N and the format
+        if (g.residual) {
+            mx = g.q_bits == 4 ? store_strip_wb<CB, true, 4>(g, acc, m_strip, n0, rows, alpha)
+               : g.q_bits == 8 ? store_strip_wb<CB, true, 8>(g, acc, m_strip, n0, rows, alpha)
+                               : store_strip_wb<CB, true, 6>(g, acc, m_strip, n0, rows, alpha);
+        } else {
+            mx = g.q_bits == 4 ? store_strip_wb<CB, false, 4>(g, acc, m_strip, n0, rows, alpha)
+               : g.q_bits == 8 ? store_strip_wb<CB, false, 8>(g, acc, m_strip, n0, rows, alpha)
+                               : store_strip_wb<CB, false, 6>(g, acc, m_strip, n0, rows, alpha);
+        }
     } else if (g.ldc < (1 << 23)) {
-        mx = g.residual ? store_strip<CB, true, false>(g, acc, m_strip, n0, rows, alpha)
-                        : store_strip<CB, false, false>(g, acc, m_strip, n0, rows, alpha);
+        mx = g.residual ? store_strip<CB, true>(g, acc, m_strip, n0, rows, alpha)
+                        : store_strip<CB, false>(g, acc, m_strip, n0, rows, alpha);
     } else {                                                        // leading dimension too large for 32-bit offsets
 #pragma unroll
         for (int j = 0; j < CB; ++j) {

@@ -11,6 +11,13 @@ which keeps the maximum), its max|y| is taken in the convolution's epilogue
 identity shortcut of a residual block is added in the same epilogue, before the ReLU.
 Pooling runs on the fp32 tensors with torch ops; it is glue, not part of the library.
 
+With `forward(x, static=True)` after a `calibrate(x)` the chain follows the paper's dataflow to
+the letter: the scales of all activation tensors are fixed (those of the calibration input), every
+convolution whose consumers agree on a format encodes its results in its own epilogue
+(dybit_conv2d_wb) and the next layer reads those codes; the fp32 tensor is only written where a
+shortcut, a pooling or the network output needs it, and no pass over an fp32 tensor remains except
+behind the pooling layers.
+
 Formats: weights are signed; an activation tensor is unsigned when it is the output of a
 ReLU or of a pooling of such outputs, signed otherwise (the network input).  Layer-wise
 bitwidths come from a table {layer name: (bits_W, bits_A)}, as the search of Sec. III-C
@@ -59,9 +66,49 @@ class DybitNetwork:
                 "cin": cin, "cpad": cpad, "cout": cout, "k": kh, "a_bits": ba,
             }
 
-    def forward(self, x: torch.Tensor, record=None) -> torch.Tensor:
+        self._plan_write_back()
+        self.static_scale = None                 # layer name -> device scale of its input, set by calibrate()
+
+    def _plan_write_back(self):
+        """Per conv layer: the format its consumers want its output in (if they agree and the packed
+        rows are whole words) and whether anyone needs the fp32 tensor."""
+        nonneg = {"input": False}
+        produced_by = {}
+        for l in self.layers:
+            if l["op"] in ("conv", "fc"):
+                nonneg[l["name"]] = bool(l.get("relu"))
+                produced_by[l["name"]] = l
+            else:
+                nonneg[l["name"]] = nonneg[l["src"]]
+        self.a_fmt = {l["name"]: (self.params[l["name"]]["a_bits"], not nonneg[l["src"]])
+                      for l in self.layers if l["op"] in ("conv", "fc")}
+        self.plan = {}
+        last = self.layers[-1]["name"]
+        for name, l in produced_by.items():
+            cout = self.params[name]["cout"]
+            users = [u for u in self.layers if u["src"] == name]
+            convs = [u for u in users if u["op"] in ("conv", "fc")]
+            fmts = {self.a_fmt[u["name"]] for u in convs}
+            fused = (len(fmts) == 1 and l["op"] == "conv"
+                     and all(self.params[u["name"]]["cpad"] == cout for u in convs)
+                     and (cout * next(iter(fmts))[0]) % 32 == 0)
+            need_fp32 = (name == last or not fused or any(u["op"] not in ("conv", "fc") for u in users)
+                         or any(u.get("add") == name for u in self.layers))
+            self.plan[name] = {"fmt": next(iter(fmts)) if fused else None,
+                               "scale_of": convs[0]["name"] if fused else None, "fp32": need_fp32}
+
+    def calibrate(self, x: torch.Tensor) -> None:
+        """Fixes the scale of every activation tensor to the one a dynamic forward pass over x uses."""
+        scales = {}
+        self.forward(x, record=lambda name, rec: scales.__setitem__(name, rec["a_scale"].clone()))
+        self.static_scale = scales
+
+    def forward(self, x: torch.Tensor, record=None, static: bool = False) -> torch.Tensor:
         """x: NHWC float32 on the device.  `record(name, dict)` receives, per conv/fc layer, the
-        tensors needed to check that layer in isolation (input, scale, codes, raw output)."""
+        tensors needed to check that layer in isolation (input, scale, codes, raw output).
+        static=True: calibrated scales and fused write-back (see the module text)."""
+        if static:
+            return self._forward_static(x, record)
         acts = {"input": x}
         nonneg = {"input": False}
         known_max = {}                       # tensor name -> device scalar holding max|tensor|
@@ -111,6 +158,61 @@ class DybitNetwork:
                                   "relu": relu, "stride": stride, "pad": pad, "k": k, **p})
                 out = y
                 nonneg[name] = bool(l.get("relu"))
+            acts[name] = out
+        return out.reshape(out.shape[0], -1)
+
+    def _forward_static(self, x: torch.Tensor, record=None) -> torch.Tensor:
+        if self.static_scale is None:
+            raise RuntimeError("calibrate() first: the static chain needs a scale per activation tensor")
+        acts = {"input": x}                  # fp32 tensors (None where only codes were written)
+        codes = {}                           # tensor name -> (format, scale, packed codes)
+        shapes = {"input": tuple(x.shape)}
+        out = x
+        for l in self.layers:
+            name, op = l["name"], l["op"]
+            src = acts[l["src"]]
+            if op == "maxpool":
+                y = torch.nn.functional.max_pool2d(src.permute(0, 3, 1, 2), l["k"], l["stride"], l["pad"])
+                out = y.permute(0, 2, 3, 1).contiguous()
+            elif op == "avgpool":
+                out = src.mean(dim=(1, 2), keepdim=True)
+            else:
+                p = self.params[name]
+                a_fmt = self.a_fmt[name]
+                sa = self.static_scale[name]
+                Bn, H, W, C = shapes[l["src"]]
+                if l["src"] in codes and codes[l["src"]][0] == a_fmt:
+                    qa = codes[l["src"]][2]                         # written by the producer's epilogue
+                else:
+                    if p["cpad"] != C:
+                        src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
+                    qa = B.dybit_quantize(src.reshape(-1), sa, *a_fmt)
+                relu = bool(l.get("relu"))
+                k = p["k"]
+                stride, pad = (l["stride"], l["pad"]) if op == "conv" else (1, 0)
+                conv_args = (Bn, H, W, p["cpad"], p["cout"], k, k, stride, pad,
+                             qa, a_fmt, sa, p["w_codes"], p["w_fmt"], p["w_scale"])
+                shortcut = acts[l["add"]] if l.get("add") else None
+                plan = self.plan[name]
+                y_codes = None
+                if plan["fmt"] is not None:
+                    y_scale = self.static_scale[plan["scale_of"]]
+                    y, y_codes = B.dybit_conv2d_wb(*conv_args, plan["fmt"], y_scale, p["bias"], shortcut, relu,
+                                                   fp32=plan["fp32"])
+                    codes[name] = (plan["fmt"], y_scale, y_codes)
+                else:
+                    y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu)
+                if record is not None:
+                    record(name, {"a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "in_shape": (Bn, H, W, p["cpad"]),
+                                  "y": y, "y_codes": y_codes, "y_fmt": plan["fmt"],
+                                  "y_scale": None if y_codes is None else y_scale, "shortcut": shortcut,
+                                  "relu": relu, "stride": stride, "pad": pad, "k": k, **p})
+                out = y
+                Ho = (H + 2 * pad - k) // stride + 1
+                Wo = (W + 2 * pad - k) // stride + 1
+                shapes[name] = (Bn, Ho, Wo, p["cout"])
+            if op in ("maxpool", "avgpool"):
+                shapes[name] = tuple(out.shape)
             acts[name] = out
         return out.reshape(out.shape[0], -1)
 

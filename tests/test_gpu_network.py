@@ -43,27 +43,76 @@ def check_layer(name, rec, weights, rng, n_rows=None, n_codes=None):
     # (i) convolution output
     qx = codes.reshape(Bn, H, W, C)
     y = rec["y"].cpu().numpy()
+    rows, want, den = conv_reference(rec, qx, qw, bias, s, sw, rng, n_rows)
+    got = y.reshape(-1, cout)[rows]
+    err = np.abs(got.astype(np.float64) - want)
+    assert np.all(err <= 1e-5 * den), (name, float((err / np.maximum(den, 1e-300)).max()))
+
+
+def conv_reference(rec, qx, qw, bias, s, sw, rng, n_rows):
+    """Oracle result of the layer on the given codes: (row indices, exact result, tolerance
+    denominator), for all output rows (n_rows None) or a random sample plus the first and last."""
+    a_fmt, w_fmt = rec["a_fmt"], rec["w_fmt"]
+    Bn, H, W, C = qx.shape
+    cout, k = qw.shape[0], qw.shape[1]
     stride, pad = rec["stride"], rec["pad"]
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
     shortcut = None if rec["shortcut"] is None else rec["shortcut"].cpu().numpy()    # added in the epilogue, before the ReLU
     if n_rows is None:
         want, den = R.conv2d(qx, a_fmt, s, qw, w_fmt, sw, stride, pad, bias, rec["relu"], shortcut)
-        got = y
-    else:
-        Ho, Wo = y.shape[1], y.shape[2]
-        rows = np.unique(np.concatenate([[0, Bn * Ho * Wo - 1], rng.integers(0, Bn * Ho * Wo, n_rows)]))
-        b, rem = np.divmod(rows, Ho * Wo)
-        ho, wo = np.divmod(rem, Wo)
-        patches = np.zeros((rows.size, k, k, C), dtype=np.uint8)           # code 0 outside the image
-        for r in range(k):
-            for q in range(k):
-                hi, wi = ho * stride - pad + r, wo * stride - pad + q
-                ok = (hi >= 0) & (hi < H) & (wi >= 0) & (wi < W)
-                patches[ok, r, q, :] = qx[b[ok], hi[ok], wi[ok], :]
-        res = None if shortcut is None else shortcut.reshape(-1, cout)[rows]
-        want, den = R.gemm(patches.reshape(rows.size, -1), a_fmt, s, qw.reshape(cout, -1), w_fmt, sw, bias, rec["relu"], res)
-        got = y.reshape(-1, cout)[rows]
-    err = np.abs(got.astype(np.float64) - want)
-    assert np.all(err <= 1e-5 * den), (name, float((err / np.maximum(den, 1e-300)).max()))
+        return np.arange(Bn * Ho * Wo), want.reshape(-1, cout), den.reshape(-1, cout)
+    rows = np.unique(np.concatenate([[0, Bn * Ho * Wo - 1], rng.integers(0, Bn * Ho * Wo, n_rows)]))
+    b, rem = np.divmod(rows, Ho * Wo)
+    ho, wo = np.divmod(rem, Wo)
+    patches = np.zeros((rows.size, k, k, C), dtype=np.uint8)           # code 0 outside the image
+    for r in range(k):
+        for q in range(k):
+            hi, wi = ho * stride - pad + r, wo * stride - pad + q
+            ok = (hi >= 0) & (hi < H) & (wi >= 0) & (wi < W)
+            patches[ok, r, q, :] = qx[b[ok], hi[ok], wi[ok], :]
+    res = None if shortcut is None else shortcut.reshape(-1, cout)[rows]
+    want, den = R.gemm(patches.reshape(rows.size, -1), a_fmt, s, qw.reshape(cout, -1), w_fmt, sw, bias, rec["relu"], res)
+    return rows, want, den
+
+
+def check_layer_static(name, rec, weights, rng, n_rows=None):
+    """Fused write-back chain: the layer's input codes are whatever the producer wrote.  Checked here:
+    the fp32 output (where written) within tolerance of the oracle on those codes; the codes written
+    back bit-exact the oracle's quantization of that fp32 output; where only codes are written, each
+    must be a code the oracle's quantizer yields for some value within the tolerance of the exact
+    result (the quantizer is monotone, so that is an interval of the codebook)."""
+    a_fmt, w_fmt = rec["a_fmt"], rec["w_fmt"]
+    Bn, H, W, C = rec["in_shape"]
+    s, sw = np.float32(rec["a_scale"].item()), np.float32(rec["w_scale"].item())
+    qx = R.unpack(rec["a_codes"].cpu().numpy().reshape(-1), Bn * H * W * C, a_fmt[0]).reshape(Bn, H, W, C)
+    w, bias = weights[name]
+    cout, k, _, cin = w.shape
+    wp = np.zeros((cout, k, k, C), dtype=np.float32)
+    wp[..., :cin] = w
+    qw = R.quantize(wp, sw, *w_fmt)
+    rows, want, den = conv_reference(rec, qx, qw, bias, s, sw, rng, n_rows)
+    y32 = None
+    if rec["y"] is not None:
+        y32 = rec["y"].cpu().numpy().reshape(-1, cout)[rows]
+        err = np.abs(y32.astype(np.float64) - want)
+        assert np.all(err <= 1e-5 * den), (name, float((err / np.maximum(den, 1e-300)).max()))
+    if rec["y_codes"] is None:
+        return
+    y_fmt, ys = rec["y_fmt"], np.float32(rec["y_scale"].item())
+    row_bytes = cout * y_fmt[0] // 8
+    packed = rec["y_codes"].cpu().numpy().reshape(-1, row_bytes)[rows]
+    got = R.unpack_rows(packed, cout, y_fmt[0])
+    if y32 is not None:
+        assert np.array_equal(got, R.quantize(y32, ys, *y_fmt)), name
+        return
+    book = R.codebook(*y_fmt)
+    tol = 1e-5 * den
+    lo = book[R.quantize(np.nextafter((want - tol).astype(np.float32), np.float32(-np.inf)), ys, *y_fmt)]
+    hi = book[R.quantize(np.nextafter((want + tol).astype(np.float32), np.float32(np.inf)), ys, *y_fmt)]
+    v = book[got]
+    assert np.all((v >= lo) & (v <= hi)), (name, int(((v < lo) | (v > hi)).sum()))
+    exact = R.quantize(want.astype(np.float32), ys, *y_fmt)
+    assert (got != exact).mean() < 1e-2, name                      # flips only next to a decision point
 
 
 def run_chain(layers, bits, batch, hw, n_rows, n_codes):
@@ -84,6 +133,55 @@ def run_chain(layers, bits, batch, hw, n_rows, n_codes):
     assert logits.shape == (batch, 1000) and bool(torch.isfinite(logits).all())
     assert len(seen) == len([l for l in layers if l["op"] in ("conv", "fc")])
     return logits
+
+
+def run_chain_static(layers, bits, batch, hw, n_rows):
+    weights = synth.network_weights(layers, seed=0)
+    net = DybitNetwork(layers, weights, bits)
+    x = torch.from_numpy(synth.network_input(batch, hw, seed=0)).cuda()
+    net.calibrate(x)
+    rng = np.random.default_rng(1)
+    seen, fused, codes_only = [], 0, 0
+
+    def record(name, rec):
+        nonlocal fused, codes_only
+        torch.cuda.synchronize()
+        check_layer_static(name, rec, weights, rng, n_rows)
+        seen.append(name)
+        fused += rec["y_codes"] is not None
+        codes_only += rec["y"] is None
+
+    logits = net.forward(x, record, static=True)
+    torch.cuda.synchronize()
+    assert B.dybit_get_last_async_error() == B.OK
+    assert logits.shape == (batch, 1000) and bool(torch.isfinite(logits).all())
+    assert len(seen) == len([l for l in layers if l["op"] in ("conv", "fc")])
+    # on the calibration input the static chain encodes the same fp32 values with the same scales as the
+    # dynamic chain, in the epilogue instead of in a pass of its own: the logits are the same bits
+    assert torch.equal(logits, net.forward(x))
+    return fused, codes_only
+
+
+def test_resnet18_fused_write_back_small_every_output():
+    layers = synth.resnet18_layers()
+    fused, codes_only = run_chain_static(layers, synth.bitwidths_fixed(layers), batch=2, hw=64, n_rows=None)
+    assert fused == 15 and codes_only == 11      # all but the first conv, the three downsample convs, the last conv and fc
+
+
+def test_resnet50_mixed_fused_write_back_small_every_output():
+    layers = synth.resnet50_layers()
+    fused, codes_only = run_chain_static(layers, synth.bitwidths_mixed(layers, seed=0), batch=2, hw=64, n_rows=None)
+    assert fused == 45 and codes_only == 33
+
+
+def test_resnet18_config3_fused_write_back_full_size_sampled():
+    layers = synth.resnet18_layers()
+    run_chain_static(layers, synth.bitwidths_fixed(layers), batch=64, hw=224, n_rows=96)
+
+
+def test_resnet50_config4_fused_write_back_full_size_sampled():
+    layers = synth.resnet50_layers()
+    run_chain_static(layers, synth.bitwidths_mixed(layers, seed=0), batch=128, hw=224, n_rows=64)
 
 
 def test_resnet18_small_every_output():
