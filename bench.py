@@ -170,6 +170,10 @@ def table(args):
         frac = "%.1f %% of %.0f TFLOP/s" % (100 * rf["frac"], rf["peak"]) if rf else "-"
         orc = "%.4f TOPS (%d), %s" % (cb["value"], cb["cores"], cb["sample"]) if cb else "-"
         print("| %s | %.4f ms | %.3f TOPS | %s | %s | %s |" % (r["config"]["workload"], r["ms_per_step"], r["value"], kern, frac, orc))
+        if "fused_write_back" in r:
+            f = r["fused_write_back"]
+            print("| the same network, calibrated scales, write-back fused into the epilogues (%d of %d layers write codes, %d of them codes only) | %.4f ms | %.3f TOPS | - | - | - |"
+                  % (f["layers_writing_codes"], r["config"]["gemms"], f["layers_writing_codes_only"], f["ms_per_step"], f["TOPS"]))
         if "roofline_4bit_w_a" in r:
             f = r["roofline_4bit_w_a"]
             print("| 8192^3 GEMM at 4-bit W / 4-bit A (same tensors, activations quantized to 4-bit signed) | %.4f ms (kernel) | %.1f TOPS | %s | %.1f %% of %.0f TFLOP/s | - |"
