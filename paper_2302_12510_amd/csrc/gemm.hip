@@ -157,11 +157,56 @@ __device__ __forceinline__ Unit<BITS> load_unit_elems(const uint8_t *row, int64_
 // Row descriptor of the activation operand: a plain matrix row, or an output pixel of a convolution.
 struct RowA {
     const uint8_t *base;   // GEMM: start of the row; CONV: start of image b
+    uint32_t img_off;      // CONV: byte offset of image b inside the activation tensor
     int hi0, wi0;          // CONV: top-left input coordinate of the receptive field
     bool valid;
 };
 
-template <int BITS, bool CONV, bool VEC>
+// How the kernel reaches its operands.
+//   ELEMS  code by code: any K, any Cin, any alignment
+//   VEC    a 16-code unit is one aligned vector load (GEMM: K, convolution: Cin a multiple of 16)
+//   RUNS   convolution with few channels (Cin divides 16, kw * Cin a multiple of 16): a unit is
+//          16 / Cin neighbouring taps of one filter row, which are contiguous in the image; weights
+//          as in VEC (K is then a multiple of 16)
+enum : int { ELEMS = 0, VEC = 1, RUNS = 2 };
+
+// RUNS: 16 codes = `taps` pixels starting at filter row fr, tap ur * taps.  The run starts at any
+// byte, so it is fetched as aligned words through a buffer descriptor (words before the tensor or
+// past its end read 0) and shifted into place; taps left or right of the image are masked to code
+// 0, a filter row above or below it reads nothing.
+template <int BITS>
+__device__ __forceinline__ Unit<BITS> load_unit_A_run(const GemmArgs &g, const __amdgpu_buffer_rsrc_t rsrc, const RowA &r,
+                                                      int fr, int ur, int64_t k0)
+{
+    constexpr int NWORD = BITS / 2;
+    Unit<BITS> u;
+    const int taps = UNIT / g.Cin, tap_bits = g.Cin * BITS;
+    const int hi = r.hi0 + fr, wi = r.wi0 + ur * taps;
+    const bool row_ok = r.valid && k0 < g.K && (unsigned)hi < (unsigned)g.H;
+    const int byte_off = (int)r.img_off + (hi * g.Wd + wi) * (tap_bits / 8);   // negative left of the first pixel
+    const int shift = byte_off & 3;
+    const int base = byte_off - shift;
+    uint32_t raw[NWORD + 1];
+#pragma unroll
+    for (int j = 0; j <= NWORD; ++j) {
+        // a word before the tensor gets the out-of-range offset explicitly: the hardware adds offsets
+        // without wrapping at 32 bits, so a negative offset plus 4 j would not come back into range
+        const int o = base + 4 * j;
+        raw[j] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, (row_ok && o >= 0) ? (uint32_t)o : 0x80000000u, 0, 0);
+    }
+    int t_lo = max(0, -wi), t_hi = min(taps, g.Wd - wi);
+    t_hi = max(t_hi, t_lo);
+    const int bit_lo = t_lo * tap_bits, bit_hi = t_hi * tap_bits;
+#pragma unroll
+    for (int i = 0; i < NWORD; ++i) {
+        const int lo = min(max(bit_lo - 32 * i, 0), 32), up = min(max(bit_hi - 32 * i, 0), 32);
+        const uint32_t keep = (uint32_t)((1ull << up) - 1ull) & ~(uint32_t)((1ull << lo) - 1ull);
+        u.w[i] = __builtin_amdgcn_alignbyte(raw[i + 1], raw[i], (uint32_t)shift) & keep;
+    }
+    return u;
+}
+
+template <int BITS, bool CONV, int MODE>
 __device__ __forceinline__ Unit<BITS> load_unit_A(const GemmArgs &g, const RowA &r, int64_t k0)
 {
     Unit<BITS> u;
@@ -169,11 +214,11 @@ __device__ __forceinline__ Unit<BITS> load_unit_A(const GemmArgs &g, const RowA 
     for (int i = 0; i < BITS / 2; ++i) u.w[i] = 0;
     if (!r.valid || k0 >= g.K) return u;
     if (!CONV) {
-        if (VEC) return load_unit_vec<BITS>(r.base + k0 * BITS / 8);
+        if (MODE == VEC) return load_unit_vec<BITS>(r.base + k0 * BITS / 8);
         return load_unit_elems<BITS>(r.base, k0, g.K);
     }
     const int64_t pix_bytes = (int64_t)g.Cin * BITS / 8;
-    if (VEC) {   // the whole unit lies inside one filter tap
+    if (MODE == VEC) {   // the whole unit lies inside one filter tap
         const int tap = (int)(k0 / g.Cin), c0 = (int)(k0 - (int64_t)tap * g.Cin);
         const int fr = tap / g.kw, fs = tap - fr * g.kw;
         const int hi = r.hi0 + fr, wi = r.wi0 + fs;
@@ -203,18 +248,18 @@ __device__ __forceinline__ Unit<BITS> load_unit_A(const GemmArgs &g, const RowA 
     return u;
 }
 
-template <int BITS, bool VEC>
+template <int BITS, bool VECW>
 __device__ __forceinline__ Unit<BITS> load_unit_W(const GemmArgs &g, const uint8_t *row, bool valid, int64_t k0)
 {
     Unit<BITS> u;
 #pragma unroll
     for (int i = 0; i < BITS / 2; ++i) u.w[i] = 0;
     if (!valid || k0 >= g.K) return u;
-    if (VEC) return load_unit_vec<BITS>(row + k0 * BITS / 8);
+    if (VECW) return load_unit_vec<BITS>(row + k0 * BITS / 8);
     return load_unit_elems<BITS>(row, k0, g.K);
 }
 
-template <int BA, int BW, bool CONV, bool VEC, bool WB>
+template <int BA, int BW, bool CONV, int MODE, bool WB>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) _Float16 As[BM * LDK];
@@ -251,11 +296,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
             const int rem = (int)(mm - b * g.Ho * g.Wo);
             const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
             ra[i].base = g.A + b * g.H * g.Wd * ((int64_t)g.Cin * BA / 8);
+            ra[i].img_off = (uint32_t)(b * g.H * g.Wd * ((int64_t)g.Cin * BA / 8));     // RUNS: the tensor is below 2 GiB
             ra[i].hi0 = ho * g.stride - g.pad;
             ra[i].wi0 = wo * g.stride - g.pad;
         } else {
             ra[i].base = g.A + (ra[i].valid ? m : 0) * a_row_bytes;
             ra[i].hi0 = ra[i].wi0 = 0;
+            ra[i].img_off = 0;
         }
         vw[i] = n < g.N;
         rw[i] = g.W + (vw[i] ? n : 0) * w_row_bytes;
@@ -269,14 +316,35 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+    // RUNS: filter row and unit inside it of each staged unit, counted up from K step to K step
+    // (a K step is BK / UNIT = 4 units further); the descriptor spans whole words of the tensor.
+    const int units_per_row = MODE == RUNS ? g.kw * g.Cin / UNIT : 1;
+    int run_fr[UPT], run_ur[UPT];
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(g.A), 0, MODE == RUNS ? (int)((g.a_bytes + 3) & ~(int64_t)3) : 0, 0x00020000);
+    auto next_run = [&](int i, int step) {
+        run_ur[i] += step;
+        while (run_ur[i] >= units_per_row) { run_ur[i] -= units_per_row; ++run_fr[i]; }
+    };
+    auto fetch_A = [&](int i, int64_t k0) -> Unit<BA> {
+        if (MODE == RUNS) {
+            const Unit<BA> u = load_unit_A_run<BA>(g, rsrcA, ra[i], run_fr[i], run_ur[i], k0);
+            next_run(i, BK / UNIT);
+            return u;
+        }
+        return load_unit_A<BA, CONV, MODE>(g, ra[i], k0);
+    };
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) { run_fr[i] = 0; run_ur[i] = 0; next_run(i, ukq[i]); }
+
     Unit<BA> ua[UPT];
     Unit<BW> uw[UPT];
     const int64_t ktiles = (g.K + BK - 1) / BK;
     if (ktiles > 0) {
 #pragma unroll
         for (int i = 0; i < UPT; ++i) {
-            ua[i] = load_unit_A<BA, CONV, VEC>(g, ra[i], (int64_t)ukq[i] * UNIT);
-            uw[i] = load_unit_W<BW, VEC>(g, rw[i], vw[i], (int64_t)ukq[i] * UNIT);
+            ua[i] = fetch_A(i, (int64_t)ukq[i] * UNIT);
+            uw[i] = load_unit_W<BW, MODE != ELEMS>(g, rw[i], vw[i], (int64_t)ukq[i] * UNIT);
         }
     }
     __syncthreads();   // tables ready
@@ -299,8 +367,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
             const int64_t kb = (kt + 1) * BK;
 #pragma unroll
             for (int i = 0; i < UPT; ++i) {
-                ua[i] = load_unit_A<BA, CONV, VEC>(g, ra[i], kb + ukq[i] * UNIT);
-                uw[i] = load_unit_W<BW, VEC>(g, rw[i], vw[i], kb + ukq[i] * UNIT);
+                ua[i] = fetch_A(i, kb + ukq[i] * UNIT);
+                uw[i] = load_unit_W<BW, MODE != ELEMS>(g, rw[i], vw[i], kb + ukq[i] * UNIT);
             }
         }
 #pragma unroll
@@ -327,22 +395,23 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
 }
 
 template <int BA, int BW>
-static void launch_gemm(const GemmArgs &g, bool conv, bool vec, hipStream_t st)
+static void launch_gemm(const GemmArgs &g, bool conv, int mode, hipStream_t st)
 {
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     const dim3 grid((unsigned)tiles), block(GEMM_THREADS);
     if (conv) {
-        if (vec) hipLaunchKernelGGL((gemm_kernel<BA, BW, true, true, kWriteBack>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((gemm_kernel<BA, BW, true, false, kWriteBack>), grid, block, 0, st, g);
+        if (mode == RUNS) hipLaunchKernelGGL((gemm_kernel<BA, BW, true, RUNS, kWriteBack>), grid, block, 0, st, g);
+        else if (mode == VEC) hipLaunchKernelGGL((gemm_kernel<BA, BW, true, VEC, kWriteBack>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((gemm_kernel<BA, BW, true, ELEMS, kWriteBack>), grid, block, 0, st, g);
     } else {
-        if (vec) hipLaunchKernelGGL((gemm_kernel<BA, BW, false, true, kWriteBack>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((gemm_kernel<BA, BW, false, false, kWriteBack>), grid, block, 0, st, g);
+        if (mode == VEC) hipLaunchKernelGGL((gemm_kernel<BA, BW, false, VEC, kWriteBack>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((gemm_kernel<BA, BW, false, ELEMS, kWriteBack>), grid, block, 0, st, g);
     }
 }
 
-void DYBIT_WB_NAME(launch_gemm_general)(const GemmArgs &g, int ba, int bw, bool conv, bool vec, hipStream_t st)
+void DYBIT_WB_NAME(launch_gemm_general)(const GemmArgs &g, int ba, int bw, bool conv, int mode, hipStream_t st)
 {
-#define DYBIT_G(A_, W_) case (A_) * 16 + (W_): launch_gemm<A_, W_>(g, conv, vec, st); break
+#define DYBIT_G(A_, W_) case (A_) * 16 + (W_): launch_gemm<A_, W_>(g, conv, mode, st); break
     switch (ba * 16 + bw) {
         DYBIT_G(2, 2); DYBIT_G(2, 4); DYBIT_G(2, 6); DYBIT_G(2, 8);
         DYBIT_G(4, 2); DYBIT_G(4, 4); DYBIT_G(4, 6); DYBIT_G(4, 8);
@@ -423,8 +492,8 @@ dybit_status gemm_impl(int64_t M, int64_t N, int64_t K,
     g.a_bytes = M * (K * a_fmt.bits / 8);
     g.w_bytes = N * (K * w_fmt.bits / 8);
     if (launch_gemm_tiled(g, a_fmt.bits, w_fmt.bits, false, (hipStream_t)stream)) return launch_status();
-    const bool vec = (K % UNIT == 0) && aligned16(A_codes) && aligned16(W_codes);
-    (g.q_out ? launch_gemm_general_wb : launch_gemm_general)(g, a_fmt.bits, w_fmt.bits, false, vec, (hipStream_t)stream);
+    const int mode = (K % UNIT == 0) && aligned16(A_codes) && aligned16(W_codes) ? 1 : 0;   // VEC : ELEMS
+    (g.q_out ? launch_gemm_general_wb : launch_gemm_general)(g, a_fmt.bits, w_fmt.bits, false, mode, (hipStream_t)stream);
     return launch_status();
 }
 
@@ -458,8 +527,13 @@ dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t C
     g.a_bytes = B * H * W * (Cin * x_fmt.bits / 8);
     g.w_bytes = Cout * (g.K * w_fmt.bits / 8);
     if (launch_gemm_tiled(g, x_fmt.bits, w_fmt.bits, true, (hipStream_t)stream)) return launch_status();
-    const bool vec = (Cin % UNIT == 0) && aligned16(X_codes) && aligned16(Wt_codes);
-    (g.q_out ? launch_gemm_general_wb : launch_gemm_general)(g, x_fmt.bits, w_fmt.bits, true, vec, (hipStream_t)stream);
+    // operand access of the general kernel: whole 16-channel vectors, runs of neighbouring taps
+    // when there are few channels (the first layer of an image network), else code by code
+    const bool aligned = aligned16(X_codes) && aligned16(Wt_codes);
+    int mode = 0;
+    if (aligned && Cin % UNIT == 0) mode = 1;
+    else if (aligned && UNIT % Cin == 0 && ((int64_t)kw * Cin) % UNIT == 0 && g.a_bytes < 0x7fffffff) mode = 2;
+    (g.q_out ? launch_gemm_general_wb : launch_gemm_general)(g, x_fmt.bits, w_fmt.bits, true, mode, (hipStream_t)stream);
     return launch_status();
 }
 

@@ -56,10 +56,11 @@ bool launch_gemm_mid_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t
 bool launch_gemm_f8(const GemmArgs &g, bool conv, bool large, hipStream_t st);
 bool launch_gemm_f8_wb(const GemmArgs &g, bool conv, bool large, hipStream_t st);
 
-// General kernel (gemm.hip): any format pair and shape.  vec: operands are 16-byte aligned and K
-// (convolution: Cin) is a multiple of 16.
-void launch_gemm_general(const GemmArgs &g, int a_bits, int w_bits, bool conv, bool vec, hipStream_t st);
-void launch_gemm_general_wb(const GemmArgs &g, int a_bits, int w_bits, bool conv, bool vec, hipStream_t st);
+// General kernel (gemm.hip): any format pair and shape.  mode: 0 operands fetched code by code;
+// 1 operands are 16-byte aligned and K (convolution: Cin) is a multiple of 16; 2 (convolution
+// only) aligned operands, Cin divides 16 and kw * Cin is a multiple of 16, tensor below 2 GiB.
+void launch_gemm_general(const GemmArgs &g, int a_bits, int w_bits, bool conv, int mode, hipStream_t st);
+void launch_gemm_general_wb(const GemmArgs &g, int a_bits, int w_bits, bool conv, int mode, hipStream_t st);
 
 // Picks a tiled kernel for the problem (gemm_dispatch.cpp).  Returns false when the problem does
 // not meet their preconditions; the caller then uses the general kernel.

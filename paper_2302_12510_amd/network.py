@@ -39,6 +39,23 @@ def _pad_channels(cin: int, bits_a: int, bits_w: int) -> int:
     return c
 
 
+def _pad_few_channels(cin: int, kw: int, bits_a: int, bits_w: int):
+    """Layout of a convolution with few input channels (an image network's first layer) that lets the
+    library fetch runs of neighbouring taps: channels padded to a divisor of 16 and the filter rows
+    padded with zero taps until kw * channels is a multiple of 16.  Zero weights change no result; the
+    caller uses this layout only for inputs where the wider filter leaves the output width unchanged.
+    Returns (channels, kw) or None when the layer does not qualify."""
+    if cin >= 16:
+        return None
+    for c in (1, 2, 4, 8):
+        if c >= cin and (c * bits_a) % 8 == 0 and (c * bits_w) % 8 == 0:
+            k2 = kw
+            while (k2 * c) % 16:
+                k2 += 1
+            return (c, k2)
+    return None
+
+
 class DybitNetwork:
     def __init__(self, layers, weights, bitwidths, device="cuda", epilogue_absmax=True):
         self.layers = layers
@@ -52,19 +69,21 @@ class DybitNetwork:
             w, b = weights[l["name"]]
             bw, ba = bitwidths[l["name"]]
             cout, kh, kw, cin = w.shape
-            cpad = _pad_channels(cin, ba, bw)
-            if cpad != cin:
-                wp = np.zeros((cout, kh, kw, cpad), dtype=np.float32)
-                wp[..., :cin] = w
-                w = wp
-            wd = torch.from_numpy(np.ascontiguousarray(w)).to(device).reshape(-1)
             w_fmt = (bw, True)
-            sw = B.dybit_absmax_scale(wd, *w_fmt)
-            qw = B.dybit_quantize(wd, sw, *w_fmt)
-            self.params[l["name"]] = {
-                "w_fmt": w_fmt, "w_scale": sw, "w_codes": qw, "bias": torch.from_numpy(b).to(device),
-                "cin": cin, "cpad": cpad, "cout": cout, "k": kh, "a_bits": ba,
-            }
+
+            def layout(cpad, kwp):
+                wp = np.zeros((cout, kh, kwp, cpad), dtype=np.float32)
+                wp[:, :, :kw, :cin] = w
+                wd = torch.from_numpy(wp).to(device).reshape(-1)
+                sw = B.dybit_absmax_scale(wd, *w_fmt)          # zero padding changes neither the scale nor a code
+                return {"w_fmt": w_fmt, "w_scale": sw, "w_codes": B.dybit_quantize(wd, sw, *w_fmt),
+                        "bias": torch.from_numpy(b).to(device), "cin": cin, "cpad": cpad, "cout": cout,
+                        "k": kh, "kw": kwp, "kw_real": kw, "a_bits": ba}
+
+            self.params[l["name"]] = layout(_pad_channels(cin, ba, bw), kw)
+            few = _pad_few_channels(cin, kw, ba, bw) if l["op"] == "conv" else None
+            if few is not None and few != (self.params[l["name"]]["cpad"], kw):
+                self.params[l["name"]]["few"] = layout(*few)   # used when the wider filter keeps the output size
 
         self._plan_write_back()
         self.static_scale = None                 # layer name -> device scale of its input, set by calibrate()
@@ -96,6 +115,17 @@ class DybitNetwork:
                          or any(u.get("add") == name for u in self.layers))
             self.plan[name] = {"fmt": next(iter(fmts)) if fused else None,
                                "scale_of": convs[0]["name"] if fused else None, "fp32": need_fp32}
+
+    def _layer_params(self, l, width: int):
+        """Parameters of a conv/fc layer for an input of the given width: the few-channel layout
+        (wider, zero-padded filter rows) if the layer has one and it yields the same output width."""
+        p = self.params[l["name"]]
+        few = p.get("few")
+        if few is not None:
+            span = width + 2 * l["pad"]
+            if (span - few["kw"]) // l["stride"] == (span - p["kw"]) // l["stride"]:
+                return few
+        return p
 
     def calibrate(self, x: torch.Tensor) -> None:
         """Fixes the scale of every activation tensor to the one a dynamic forward pass over x uses."""
@@ -129,9 +159,9 @@ class DybitNetwork:
                 out = src.mean(dim=(1, 2), keepdim=True)
                 nonneg[name] = nonneg[l["src"]]
             else:
-                p = self.params[name]
-                a_fmt = (p["a_bits"], not nonneg[l["src"]])
                 Bn, H, W, C = src.shape
+                p = self._layer_params(l, W) if op == "conv" else self.params[name]
+                a_fmt = (p["a_bits"], not nonneg[l["src"]])
                 if p["cpad"] != C:
                     src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
                 flat = src.reshape(-1)
@@ -143,7 +173,7 @@ class DybitNetwork:
                 relu = bool(l.get("relu"))
                 k = p["k"]
                 stride, pad = (l["stride"], l["pad"]) if op == "conv" else (1, 0)
-                conv_args = (Bn, H, W, p["cpad"], p["cout"], k, k, stride, pad,
+                conv_args = (Bn, H, W, p["cpad"], p["cout"], k, p["kw"], stride, pad,
                              qa, a_fmt, sa, p["w_codes"], p["w_fmt"], p["w_scale"])
                 shortcut = acts[l["add"]] if l.get("add") else None
                 if self.epilogue_absmax:
@@ -177,10 +207,10 @@ class DybitNetwork:
             elif op == "avgpool":
                 out = src.mean(dim=(1, 2), keepdim=True)
             else:
-                p = self.params[name]
                 a_fmt = self.a_fmt[name]
                 sa = self.static_scale[name]
                 Bn, H, W, C = shapes[l["src"]]
+                p = self._layer_params(l, W) if op == "conv" else self.params[name]
                 if l["src"] in codes and codes[l["src"]][0] == a_fmt:
                     qa = codes[l["src"]][2]                         # written by the producer's epilogue
                 else:
@@ -190,7 +220,7 @@ class DybitNetwork:
                 relu = bool(l.get("relu"))
                 k = p["k"]
                 stride, pad = (l["stride"], l["pad"]) if op == "conv" else (1, 0)
-                conv_args = (Bn, H, W, p["cpad"], p["cout"], k, k, stride, pad,
+                conv_args = (Bn, H, W, p["cpad"], p["cout"], k, p["kw"], stride, pad,
                              qa, a_fmt, sa, p["w_codes"], p["w_fmt"], p["w_scale"])
                 shortcut = acts[l["add"]] if l.get("add") else None
                 plan = self.plan[name]

@@ -33,9 +33,9 @@ def check_layer(name, rec, weights, rng, n_rows=None, n_codes=None):
         assert np.array_equal(codes[idx], R.quantize(flat[idx], s, *a_fmt)), name
     # weights: quantized once by the library, checked against the oracle on the same padded tensor
     w, bias = weights[name]
-    cout, k, _, cin = w.shape
-    wp = np.zeros((cout, k, k, C), dtype=np.float32)
-    wp[..., :cin] = w
+    cout, k, kw, cin = w.shape
+    wp = np.zeros((cout, k, rec["kw"], C), dtype=np.float32)      # the driver may pad channels and filter rows with zeros
+    wp[:, :, :kw, :cin] = w
     sw = np.float32(rec["w_scale"].item())
     assert sw == R.absmax_scale(wp, *w_fmt), name
     qw = R.quantize(wp, sw, *w_fmt)
@@ -54,9 +54,9 @@ def conv_reference(rec, qx, qw, bias, s, sw, rng, n_rows):
     denominator), for all output rows (n_rows None) or a random sample plus the first and last."""
     a_fmt, w_fmt = rec["a_fmt"], rec["w_fmt"]
     Bn, H, W, C = qx.shape
-    cout, k = qw.shape[0], qw.shape[1]
+    cout, k, kw = qw.shape[0], qw.shape[1], qw.shape[2]
     stride, pad = rec["stride"], rec["pad"]
-    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - kw) // stride + 1
     shortcut = None if rec["shortcut"] is None else rec["shortcut"].cpu().numpy()    # added in the epilogue, before the ReLU
     if n_rows is None:
         want, den = R.conv2d(qx, a_fmt, s, qw, w_fmt, sw, stride, pad, bias, rec["relu"], shortcut)
@@ -64,9 +64,9 @@ def conv_reference(rec, qx, qw, bias, s, sw, rng, n_rows):
     rows = np.unique(np.concatenate([[0, Bn * Ho * Wo - 1], rng.integers(0, Bn * Ho * Wo, n_rows)]))
     b, rem = np.divmod(rows, Ho * Wo)
     ho, wo = np.divmod(rem, Wo)
-    patches = np.zeros((rows.size, k, k, C), dtype=np.uint8)           # code 0 outside the image
+    patches = np.zeros((rows.size, k, kw, C), dtype=np.uint8)          # code 0 outside the image
     for r in range(k):
-        for q in range(k):
+        for q in range(kw):
             hi, wi = ho * stride - pad + r, wo * stride - pad + q
             ok = (hi >= 0) & (hi < H) & (wi >= 0) & (wi < W)
             patches[ok, r, q, :] = qx[b[ok], hi[ok], wi[ok], :]
@@ -86,9 +86,9 @@ def check_layer_static(name, rec, weights, rng, n_rows=None):
     s, sw = np.float32(rec["a_scale"].item()), np.float32(rec["w_scale"].item())
     qx = R.unpack(rec["a_codes"].cpu().numpy().reshape(-1), Bn * H * W * C, a_fmt[0]).reshape(Bn, H, W, C)
     w, bias = weights[name]
-    cout, k, _, cin = w.shape
-    wp = np.zeros((cout, k, k, C), dtype=np.float32)
-    wp[..., :cin] = w
+    cout, k, kw, cin = w.shape
+    wp = np.zeros((cout, k, rec["kw"], C), dtype=np.float32)
+    wp[:, :, :kw, :cin] = w
     qw = R.quantize(wp, sw, *w_fmt)
     rows, want, den = conv_reference(rec, qx, qw, bias, s, sw, rng, n_rows)
     y32 = None
