@@ -18,6 +18,7 @@ SOURCES = [
     ("gemm_fast.hip", "gemm_fast_w8", ["-DDYBIT_FAST_W=2"]),
     ("gemm_mid.hip", "gemm_mid_w4", ["-DDYBIT_MID_W=0"]),
     ("gemm_mid.hip", "gemm_mid_w8", ["-DDYBIT_MID_W=2"]),
+    ("gemm_mid.hip", "gemm_mid_w6", ["-DDYBIT_MID_W=4"]),
     ("gemm_f8.hip", "gemm_f8", []),
     # write-back builds of the same kernels (epilogue also encodes the results as DyBit codes)
     ("gemm.hip", "gemm_wb", ["-DDYBIT_WB=1"]),
@@ -25,6 +26,7 @@ SOURCES = [
     ("gemm_fast.hip", "gemm_fast_w8_wb", ["-DDYBIT_FAST_W=2", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w4_wb", ["-DDYBIT_MID_W=0", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w8_wb", ["-DDYBIT_MID_W=2", "-DDYBIT_WB=1"]),
+    ("gemm_mid.hip", "gemm_mid_w6_wb", ["-DDYBIT_MID_W=4", "-DDYBIT_WB=1"]),
     ("gemm_f8.hip", "gemm_f8_wb", ["-DDYBIT_WB=1"]),
     ("diag.hip", "diag", []),
 ]

@@ -1,7 +1,7 @@
 // Decoders from packed DyBit codes to fp16 pairs, entirely in the vector ALU (no table look-ups
 // in memory).  Shared by the tiled matrix-product kernels.
 //
-// Every DyBit value of the 4- and 8-bit formats is exact in fp16.  Both decoders emit each group
+// Every DyBit value of the 4-, 6- and 8-bit formats is exact in fp16.  All decoders emit each group
 // of eight consecutive k values in the order (k0,k2,k1,k3,k4,k6,k5,k7): that is the order their
 // packed arithmetic produces for free, and a contraction does not care about the order of k as
 // long as both operands agree.
@@ -23,7 +23,7 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kOob = 0x80000000u;            // a buffer offset past every supported size: such loads return 0
 
-enum { F4S = 0, F4U = 1, F8S = 2, F8U = 3 };
+enum { F4S = 0, F4U = 1, F8S = 2, F8U = 3, F6S = 4, F6U = 5 };
 
 // ---------------------------------------------------------------------------
 // Codecs: packed codes -> fp16 pairs, entirely in the vector ALU.
@@ -46,10 +46,17 @@ __device__ __forceinline__ u32 recip_decode_pair(u32 h, u32 k2)
     return __builtin_bit_cast(u32, v);
 }
 
+// Four 6-bit codes in the low 24 bits of t -> one code per byte (bits above 24 are ignored).
+__device__ __forceinline__ u32 unpack_six(u32 t)
+{
+    return (t & 0x3fu) | ((t << 2) & 0x3f00u) | ((t << 4) & 0x3f0000u) | ((t << 6) & 0x3f000000u);
+}
+
 template <int FMT> struct Codec;
 
-// Codec<F>::word decodes one 32-bit word; Codec<F>::eight decodes the q-th group of eight codes of
-// a thread's 32 codes (held in BITS / 4 registers of 128 bits) into four registers of two halves.
+// Codec<F>::word decodes one 32-bit word; decode_eight decodes the q-th group of eight codes of
+// a thread's 32 codes (held in registers of 128 bits: one for 4-bit codes, two for 8-bit codes,
+// the first 24 bytes of two for 6-bit codes) into four registers of two halves.
 template <int FMT>
 __device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
 {
@@ -57,6 +64,15 @@ __device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
     if constexpr (C::BITS == 8) {
         const u32x4 r = raw[q >> 1];
         C::two_words((q & 1) ? r.z : r.x, (q & 1) ? r.w : r.y, d);
+    } else if constexpr (C::BITS == 6) {
+        // eight codes are 48 bits: two groups of four codes (24 bits) taken out of the 192-bit run
+        const u32x4 r0 = raw[0], r1 = raw[1];
+        u32 ta, tb;
+        if (q == 0)      { ta = r0.x;                                     tb = __builtin_amdgcn_alignbit(r0.y, r0.x, 24); }
+        else if (q == 1) { ta = __builtin_amdgcn_alignbit(r0.z, r0.y, 16); tb = r0.z >> 8; }
+        else if (q == 2) { ta = r0.w;                                     tb = __builtin_amdgcn_alignbit(r1.x, r0.w, 24); }
+        else             { ta = __builtin_amdgcn_alignbit(r1.y, r1.x, 16); tb = r1.y >> 8; }
+        C::two_words(unpack_six(ta), unpack_six(tb), d);
     } else {
         const u32x4 r = raw[0];
         C::word(q == 0 ? r.x : q == 1 ? r.y : q == 2 ? r.z : r.w, d);
@@ -130,6 +146,40 @@ template <> struct Codec<F8U> {
         h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
         h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
         recip_decode_4pairs(h, 0x94009400u, d);
+    }
+};
+
+// 6-bit formats: the codes are first spread to one per byte (unpack_six), then the arithmetic
+// decoder runs with m = 5 (signed: sign in bit 5 of each byte) or m = 6 magnitude bits.
+template <> struct Codec<F6S> {
+    static constexpr int BITS = 6;
+    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
+    {
+        const u32 m0 = ~w0 & 0x1f1f1f1fu, m1 = ~w1 & 0x1f1f1f1fu;         // 31 - c in every byte
+        u32 h[4], v[4];
+        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
+        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
+        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
+        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
+        recip_decode_4pairs(h, 0x88008800u, v);
+        d[0] = (v[0] & 0x7fff7fffu) | ((w0 << 10) & 0x80008000u);         // sign: bit 5 of bytes 0, 2
+        d[1] = (v[1] & 0x7fff7fffu) | ((w0 << 2) & 0x80008000u);          //       bit 5 of bytes 1, 3
+        d[2] = (v[2] & 0x7fff7fffu) | ((w1 << 10) & 0x80008000u);
+        d[3] = (v[3] & 0x7fff7fffu) | ((w1 << 2) & 0x80008000u);
+    }
+};
+
+template <> struct Codec<F6U> {
+    static constexpr int BITS = 6;
+    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
+    {
+        const u32 m0 = ~w0 & 0x3f3f3f3fu, m1 = ~w1 & 0x3f3f3f3fu;         // 63 - c in every byte
+        u32 h[4];
+        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
+        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
+        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
+        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
+        recip_decode_4pairs(h, 0x8C008C00u, d);
     }
 };
 

@@ -49,14 +49,32 @@ template <int KG> struct Geom {
 };
 static_assert(Geom<2>::LDS_BYTES >= 4 * 4 * 16 * 64 * 4, "reduction buffer must fit in the stages");
 
+// A run of 32 codes into registers: one or two 128-bit loads, or (6-bit: 24 bytes, a multiple of 8 from
+// the row start) three 64-bit loads.  An out-of-range offset reads zeros.
+template <int BITS>
+__device__ __forceinline__ void load_run(const __amdgpu_buffer_rsrc_t rsrc, u32 off, u32x4 *raw)
+{
+    if constexpr (BITS == 6) {
+        const auto a = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0);
+        const auto b = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off + 8, 0, 0);
+        const auto c = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off + 16, 0, 0);
+        raw[0] = u32x4{a[0], a[1], b[0], b[1]};
+        raw[1] = u32x4{c[0], c[1], 0u, 0u};
+    } else {
+#pragma unroll
+        for (int p = 0; p < BITS / 4; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + p * 16, 0, 0);
+    }
+}
+
 template <int FMT_A, int FMT_W, bool CONV, int KG, bool WB>
 __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
     constexpr int TK = Geom<KG>::TK, ROW_BYTES = Geom<KG>::ROW_BYTES, STAGE_BYTES = Geom<KG>::STAGE_BYTES;
-    constexpr int NA = CA::BITS / 4;                               // 128-bit loads per lane and K step
-    constexpr int NW = CW::BITS / 4;
+    constexpr int NA = (CA::BITS + 3) / 4;                         // 128-bit registers per lane and K step (6-bit: 24 of 32 bytes used)
+    constexpr int NW = (CW::BITS + 3) / 4;
+    constexpr int RUN_A = 4 * CA::BITS, RUN_W = 4 * CW::BITS;       // bytes of a run of 32 codes
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -97,15 +115,15 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
             const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
             hi0 = ho * g.stride - g.pad;
             wi0 = wo * g.stride - g.pad;
-            offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * 16 * NA);
+            offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);
         } else {
-            offA = okA ? (u32)(m * a_row_bytes + kq * 16 * NA) : kOob;
+            offA = okA ? (u32)(m * a_row_bytes + kq * RUN_A) : kOob;
         }
     }
     // ---- W staging: a row of the K step is TK / 32 = 2 KG runs of 32 codes, one thread each
     const int wrow = tid / (2 * KG), wq = tid % (2 * KG);
     const int64_t nrow = n0 + wrow;
-    const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + wq * 16 * NW) : kOob;
+    const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + wq * RUN_W) : kOob;
     const u32 wrW = (u32)wrow * ROW_BYTES + (u32)wq * 64;
     const u32 rdW = (u32)(lane & 31) * ROW_BYTES + (u32)kgp * 128 + (u32)kq * 64;   // block kk adds 16 B, column block j adds 32 rows
 
@@ -129,16 +147,14 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
         } else {
             off = a_k0 < g.K ? offA + (u32)(a_k0 * CA::BITS / 8) : kOob;
         }
-#pragma unroll
-        for (int p = 0; p < NA; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
+        load_run<CA::BITS>(rsrcA, off, raw);
         a_k0 += TK;
         if (CONV) { a_c0 += TK; settle_tap(); }
     };
     auto load_W = [&](int64_t kt, u32x4 *raw) {
         const int64_t k0 = kt * TK + wq * 32;
         const u32 off = k0 < g.K ? offW + (u32)(kt * TK * CW::BITS / 8) : kOob;
-#pragma unroll
-        for (int p = 0; p < NW; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + p * 16, 0, 0);
+        load_run<CW::BITS>(rsrcW, off, raw);
     };
     auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
         u32 d[4];
@@ -160,6 +176,8 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
 
+    // decode instructions to place behind each MFMA: the 6-bit decoders are about 1.5 times as long
+    constexpr int VALU_PER_MFMA = 12 + (CA::BITS == 6 ? 6 : 0) + (CW::BITS == 6 ? 6 : 0);
     u32x4 rawA[2][NA], rawW[2][NW];
     f16x8 fw[4], fa;
 
@@ -204,7 +222,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
             for (int r = 0; r < 4; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                 // DS read
-                __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);                // VALU
+                __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);     // VALU
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -273,10 +291,12 @@ static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 bool DYBIT_MID_NAME(DYBIT_MID_W)(const GemmArgs &g, int a_bits, bool conv, hipStream_t st)
 {
     using namespace fast;
-    const int fa = (a_bits == 8 ? F8S : F4S) + (g.a_signed ? 0 : 1);
+    const int fa = (a_bits == 8 ? F8S : a_bits == 6 ? F6S : F4S) + (g.a_signed ? 0 : 1);
     switch (fa) {
         case F4S: mid::launch<F4S, DYBIT_MID_W>(g, conv, st); return true;
         case F4U: mid::launch<F4U, DYBIT_MID_W>(g, conv, st); return true;
+        case F6S: mid::launch<F6S, DYBIT_MID_W>(g, conv, st); return true;
+        case F6U: mid::launch<F6U, DYBIT_MID_W>(g, conv, st); return true;
         case F8S: mid::launch<F8S, DYBIT_MID_W>(g, conv, st); return true;
         case F8U: mid::launch<F8U, DYBIT_MID_W>(g, conv, st); return true;
         default: return false;
