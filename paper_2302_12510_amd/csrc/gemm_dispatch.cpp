@@ -21,7 +21,10 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
 {
     if ((a_bits != 4 && a_bits != 6 && a_bits != 8) || (w_bits != 4 && w_bits != 6 && w_bits != 8) || !g.w_signed) return false;
     if (g.M < 1 || g.N < 1 || g.K < 64 || g.K % 64) return false;
-    if (conv && g.Cin % 64) return false;
+    // a convolution needs whole 64-code k groups inside a filter tap, or (few channels) filter rows of
+    // exactly 32 codes, which the 128 x 128 kernel fetches row by row
+    const bool rows = conv && g.Cin < 64 && (int64_t)g.kw * g.Cin == 32;
+    if (conv && g.Cin % 64 && !rows) return false;
     if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W)) & 15) return false;
     if (g.a_bytes >= 0x7fffffff || g.w_bytes >= 0x7fffffff) return false;
 
@@ -44,12 +47,12 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
         large = g.N > 128 && tiles256 >= 128 && g.K >= (both4 ? 2048 : 1024);
     }
     const bool six = a_bits == 6 || w_bits == 6;                    // 6-bit operands: the 128 x 128 kernel only
-    if (six) large = false;
+    if (six || rows) large = false;
     // two 4-bit operands: every value is exact in e4m3, so the fp8 matrix path (twice the fp16 rate,
     // byte decoders) takes them unless DYBIT_GEMM_MFMA=f16 asks for the fp16 kernels
     const char *mfma = getenv("DYBIT_GEMM_MFMA");
     const bool wb = g.q_out != nullptr;                             // write-back builds of the same kernels
-    if (a_bits == 4 && w_bits == 4 && !(mfma && !strcmp(mfma, "f16"))) return (wb ? launch_gemm_f8_wb : launch_gemm_f8)(g, conv, large, st);
+    if (a_bits == 4 && w_bits == 4 && !rows && !(mfma && !strcmp(mfma, "f16"))) return (wb ? launch_gemm_f8_wb : launch_gemm_f8)(g, conv, large, st);
     if (large) {
         if (w_bits == 4) return (wb ? launch_gemm_fast_w0_wb : launch_gemm_fast_w0)(g, a_bits, conv, st);
         return (wb ? launch_gemm_fast_w2_wb : launch_gemm_fast_w2)(g, a_bits, conv, st);

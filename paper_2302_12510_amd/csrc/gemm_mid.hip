@@ -66,13 +66,23 @@ __device__ __forceinline__ void load_run(const __amdgpu_buffer_rsrc_t rsrc, u32 
     }
 }
 
-template <int FMT_A, int FMT_W, bool CONV, int KG, bool WB>
+// CONV: 0 matrix product; 1 convolution whose 64-code k groups lie inside one filter tap (Cin a multiple
+// of 64); 2 (ROWS) convolution with few channels where one filter row is exactly one 32-code run
+// (kw * Cin = 32, e.g. 8 taps of 4 channels: the first layer of an image network with its weights
+// padded by zero taps): a lane's run is filter row 2 * step + kq of its output pixel, contiguous in
+// the image from any byte on.  It is fetched as aligned words (one more than the run holds; a word
+// before or past the tensor reads 0) and, when it is decoded, shifted into place and the taps left or
+// right of the image are masked to code 0.
+constexpr int ROWS = 2;
+
+template <int FMT_A, int FMT_W, int CONV, int KG, bool WB>
 __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
     constexpr int TK = Geom<KG>::TK, ROW_BYTES = Geom<KG>::ROW_BYTES, STAGE_BYTES = Geom<KG>::STAGE_BYTES;
-    constexpr int NA = (CA::BITS + 3) / 4;                         // 128-bit registers per lane and K step (6-bit: 24 of 32 bytes used)
+    constexpr int WORDS_A = CA::BITS;                               // 32-bit words in a run of 32 codes
+    constexpr int NA = CONV == ROWS ? (WORDS_A + 1 + 3) / 4 : (CA::BITS + 3) / 4;   // 128-bit registers per lane and K step
     constexpr int NW = (CW::BITS + 3) / 4;
     constexpr int RUN_A = 4 * CA::BITS, RUN_W = 4 * CW::BITS;       // bytes of a run of 32 codes
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -94,8 +104,11 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
     }
     const int64_t m0 = (int64_t)tile_m * TM, n0 = (int64_t)tile_n * TN;
 
+    // ROWS reads aligned words: the descriptor then ends on a word boundary, so that the last bytes of
+    // the tensor are not dropped with their (at most three bytes longer) word
+    const int64_t a_span = CONV == ROWS ? ((g.a_bytes + 3) & ~(int64_t)3) : g.a_bytes;
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.A), 0, (int)(g.a_bytes > 0x7fffffff ? 0x7fffffff : g.a_bytes), 0x00020000);
+        const_cast<uint8_t *>(g.A), 0, (int)(a_span > 0x7fffffff ? 0x7fffffff : a_span), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
 
@@ -105,6 +118,9 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
     u32 offA;
     int hi0 = 0, wi0 = 0;
     bool okA;
+    // ROWS: byte shift of the lane's runs inside their aligned words, and the bits of the run that
+    // belong to taps inside the image (both the same for every filter row of the pixel)
+    u32 row_shift = 0, row_keep[CONV == ROWS ? WORDS_A : 1];
     {
         const int64_t m = m0 + wr * 32 + (lane & 31);
         okA = m < g.M;
@@ -115,7 +131,21 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
             const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
             hi0 = ho * g.stride - g.pad;
             wi0 = wo * g.stride - g.pad;
-            offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);
+            if (CONV == ROWS) {
+                // first byte of filter row 0 of the pixel (negative left of the first pixel of the tensor)
+                const int first = (int)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes);
+                row_shift = (u32)first & 3u;                     // Wd * pix_bytes may be odd: see load_A
+                offA = (u32)first;
+                const int taps = 32 / g.Cin, tap_bits = g.Cin * CA::BITS;
+                const int t_lo = max(0, -wi0), t_hi = max(min(taps, g.Wd - wi0), t_lo);
+#pragma unroll
+                for (int i = 0; i < WORDS_A; ++i) {
+                    const int lo = min(max(t_lo * tap_bits - 32 * i, 0), 32), up = min(max(t_hi * tap_bits - 32 * i, 0), 32);
+                    row_keep[i] = (u32)((1ull << up) - 1ull) & ~(u32)((1ull << lo) - 1ull);
+                }
+            } else {
+                offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);
+            }
         } else {
             offA = okA ? (u32)(m * a_row_bytes + kq * RUN_A) : kOob;
         }
@@ -138,8 +168,30 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
             if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
         }
     };
-    if (CONV) { a_c0 = kgp * 64; settle_tap(); }
+    if (CONV == 1) { a_c0 = kgp * 64; settle_tap(); }
     auto load_A = [&](u32x4 *raw) {
+        if constexpr (CONV == ROWS) {
+            // filter row of this lane's run, its first byte, and the aligned words that hold it; the
+            // byte shift travels with the words (last register) because rows may start at any byte
+            const int fr = (int)(a_k0 >> 5) + kq;
+            const int hi = hi0 + fr;
+            const bool in = okA && a_k0 < g.K && (unsigned)hi < (unsigned)g.H;
+            const int byte_off = (int)offA + fr * g.Wd * pix_bytes;
+            const int shift = byte_off & 3, base = byte_off - shift;
+            u32 w[NA * 4];
+#pragma unroll
+            for (int j = 0; j < NA * 4; ++j) w[j] = 0;
+#pragma unroll
+            for (int j = 0; j <= WORDS_A; ++j) {
+                const int o = base + 4 * j;                      // no wrap-around in the hardware's offset addition:
+                w[j] = __builtin_amdgcn_raw_buffer_load_b32(rsrcA, (in && o >= 0) ? (u32)o : kOob, 0, 0);   // say "outside" explicitly
+            }
+            w[NA * 4 - 1] = (u32)shift;
+#pragma unroll
+            for (int p = 0; p < NA; ++p) raw[p] = u32x4{w[4 * p], w[4 * p + 1], w[4 * p + 2], w[4 * p + 3]};
+            a_k0 += TK;
+            return;
+        }
         u32 off;
         if (CONV) {
             const bool in = okA && a_k0 < g.K && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
@@ -149,7 +201,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
         }
         load_run<CA::BITS>(rsrcA, off, raw);
         a_k0 += TK;
-        if (CONV) { a_c0 += TK; settle_tap(); }
+        if (CONV == 1) { a_c0 += TK; settle_tap(); }
     };
     auto load_W = [&](int64_t kt, u32x4 *raw) {
         const int64_t k0 = kt * TK + wq * 32;
@@ -158,7 +210,18 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
     };
     auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
         u32 d[4];
-        decode_eight<FMT_A>(raw, q, d);
+        if constexpr (CONV == ROWS) {
+            // shift the run into place and drop the taps outside the image (only the words group q
+            // needs survive dead-code elimination: q is a constant where this is inlined)
+            const u32 shift = raw[NA - 1].w;
+            u32x4 t[2] = {u32x4{0u, 0u, 0u, 0u}, u32x4{0u, 0u, 0u, 0u}};
+#pragma unroll
+            for (int i = 0; i < WORDS_A; ++i)
+                t[i >> 2][i & 3] = __builtin_amdgcn_alignbyte(raw[(i + 1) >> 2][(i + 1) & 3], raw[i >> 2][i & 3], shift) & row_keep[i];
+            decode_eight<FMT_A>(t, q, d);
+        } else {
+            decode_eight<FMT_A>(raw, q, d);
+        }
         return __builtin_bit_cast(f16x8, u32x4{d[0], d[1], d[2], d[3]});
     };
     auto stage_W = [&](const u32x4 *raw, int q, char *tile) {
@@ -255,20 +318,21 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 3 : 2) void gemm_mid_kernel(con
     epilogue_strip<4, WB>(g, acc, m0 + wr * 32, n0);
 }
 
-template <int FA, int FW, int KG>
-static void launch_kg(const GemmArgs &g, bool conv, hipStream_t st, int tiles_m, int tiles_n)
+template <int FA, int FW, int CONV, int KG>
+static void launch_one(const GemmArgs &g, hipStream_t st, int tiles_m, int tiles_n)
 {
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8), 1, 1), block(256 * KG);
     constexpr int lds_bytes = Geom<KG>::LDS_BYTES;
-    if (conv) {
-        auto k = gemm_mid_kernel<FA, FW, true, KG, kWriteBack>;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        hipLaunchKernelGGL(k, grid, block, lds_bytes, st, g, tiles_m, tiles_n);
-    } else {
-        auto k = gemm_mid_kernel<FA, FW, false, KG, kWriteBack>;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        hipLaunchKernelGGL(k, grid, block, lds_bytes, st, g, tiles_m, tiles_n);
-    }
+    auto k = gemm_mid_kernel<FA, FW, CONV, KG, kWriteBack>;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    hipLaunchKernelGGL(k, grid, block, lds_bytes, st, g, tiles_m, tiles_n);
+}
+
+template <int FA, int FW, int KG>
+static void launch_kg(const GemmArgs &g, bool conv, hipStream_t st, int tiles_m, int tiles_n)
+{
+    if (conv) launch_one<FA, FW, 1, KG>(g, st, tiles_m, tiles_n);
+    else launch_one<FA, FW, 0, KG>(g, st, tiles_m, tiles_n);
 }
 
 // More tiles than compute units: small workgroups, three per compute unit.  Otherwise one
@@ -277,6 +341,7 @@ template <int FA, int FW>
 static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 {
     const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
+    if (conv && g.Cin < 64) return launch_one<FA, FW, ROWS, 1>(g, st, tiles_m, tiles_n);   // kw * Cin = 32 (checked by the dispatcher)
     const char *force = getenv("DYBIT_MID_KGROUPS");
     const bool one = force ? atoi(force) == 1 : (int64_t)tiles_m * tiles_n > 256;
     if (one) launch_kg<FA, FW, 1>(g, conv, st, tiles_m, tiles_n);

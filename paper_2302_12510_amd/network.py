@@ -39,12 +39,14 @@ def _pad_channels(cin: int, bits_a: int, bits_w: int) -> int:
     return c
 
 
-def _pad_few_channels(cin: int, kw: int, bits_a: int, bits_w: int):
+def _pad_few_channels(cin: int, kh: int, kw: int, bits_a: int, bits_w: int):
     """Layout of a convolution with few input channels (an image network's first layer) that lets the
-    library fetch runs of neighbouring taps: channels padded to a divisor of 16 and the filter rows
-    padded with zero taps until kw * channels is a multiple of 16.  Zero weights change no result; the
-    caller uses this layout only for inputs where the wider filter leaves the output width unchanged.
-    Returns (channels, kw) or None when the layer does not qualify."""
+    library fetch whole runs of neighbouring taps: channels padded to a divisor of 16 and the filter
+    rows padded with zero taps until kw * channels is a multiple of 16; when a filter row is then
+    exactly 32 codes, the filter also gets an even number of rows, which puts the layer on the tiled
+    kernels.  Zero weights change no result; the caller uses this layout only for inputs where the
+    larger filter leaves the output size unchanged.
+    Returns (channels, kh, kw) or None when the layer does not qualify."""
     if cin >= 16:
         return None
     for c in (1, 2, 4, 8):
@@ -52,7 +54,7 @@ def _pad_few_channels(cin: int, kw: int, bits_a: int, bits_w: int):
             k2 = kw
             while (k2 * c) % 16:
                 k2 += 1
-            return (c, k2)
+            return (c, kh + (kh % 2 if k2 * c == 32 else 0), k2)
     return None
 
 
@@ -71,19 +73,19 @@ class DybitNetwork:
             cout, kh, kw, cin = w.shape
             w_fmt = (bw, True)
 
-            def layout(cpad, kwp):
-                wp = np.zeros((cout, kh, kwp, cpad), dtype=np.float32)
-                wp[:, :, :kw, :cin] = w
+            def layout(cpad, khp, kwp):
+                wp = np.zeros((cout, khp, kwp, cpad), dtype=np.float32)
+                wp[:, :kh, :kw, :cin] = w
                 wd = torch.from_numpy(wp).to(device).reshape(-1)
                 sw = B.dybit_absmax_scale(wd, *w_fmt)          # zero padding changes neither the scale nor a code
                 return {"w_fmt": w_fmt, "w_scale": sw, "w_codes": B.dybit_quantize(wd, sw, *w_fmt),
                         "bias": torch.from_numpy(b).to(device), "cin": cin, "cpad": cpad, "cout": cout,
-                        "k": kh, "kw": kwp, "kw_real": kw, "a_bits": ba}
+                        "k": khp, "kw": kwp, "a_bits": ba}
 
-            self.params[l["name"]] = layout(_pad_channels(cin, ba, bw), kw)
-            few = _pad_few_channels(cin, kw, ba, bw) if l["op"] == "conv" else None
-            if few is not None and few != (self.params[l["name"]]["cpad"], kw):
-                self.params[l["name"]]["few"] = layout(*few)   # used when the wider filter keeps the output size
+            self.params[l["name"]] = layout(_pad_channels(cin, ba, bw), kh, kw)
+            few = _pad_few_channels(cin, kh, kw, ba, bw) if l["op"] == "conv" else None
+            if few is not None and few != (self.params[l["name"]]["cpad"], kh, kw):
+                self.params[l["name"]]["few"] = layout(*few)   # used when the larger filter keeps the output size
 
         self._plan_write_back()
         self.static_scale = None                 # layer name -> device scale of its input, set by calibrate()
@@ -116,14 +118,15 @@ class DybitNetwork:
             self.plan[name] = {"fmt": next(iter(fmts)) if fused else None,
                                "scale_of": convs[0]["name"] if fused else None, "fp32": need_fp32}
 
-    def _layer_params(self, l, width: int):
-        """Parameters of a conv/fc layer for an input of the given width: the few-channel layout
-        (wider, zero-padded filter rows) if the layer has one and it yields the same output width."""
+    def _layer_params(self, l, height: int, width: int):
+        """Parameters of a conv layer for an input of the given size: the few-channel layout (filter
+        padded with zero taps) if the layer has one and it yields the same output size."""
         p = self.params[l["name"]]
         few = p.get("few")
         if few is not None:
-            span = width + 2 * l["pad"]
-            if (span - few["kw"]) // l["stride"] == (span - p["kw"]) // l["stride"]:
+            same = all((n + 2 * l["pad"] - few[k]) // l["stride"] == (n + 2 * l["pad"] - p[k]) // l["stride"]
+                       for n, k in ((height, "k"), (width, "kw")))
+            if same:
                 return few
         return p
 
@@ -160,7 +163,7 @@ class DybitNetwork:
                 nonneg[name] = nonneg[l["src"]]
             else:
                 Bn, H, W, C = src.shape
-                p = self._layer_params(l, W) if op == "conv" else self.params[name]
+                p = self._layer_params(l, H, W) if op == "conv" else self.params[name]
                 a_fmt = (p["a_bits"], not nonneg[l["src"]])
                 if p["cpad"] != C:
                     src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
@@ -210,7 +213,7 @@ class DybitNetwork:
                 a_fmt = self.a_fmt[name]
                 sa = self.static_scale[name]
                 Bn, H, W, C = shapes[l["src"]]
-                p = self._layer_params(l, W) if op == "conv" else self.params[name]
+                p = self._layer_params(l, H, W) if op == "conv" else self.params[name]
                 if l["src"] in codes and codes[l["src"]][0] == a_fmt:
                     qa = codes[l["src"]][2]                         # written by the producer's epilogue
                 else:
@@ -239,7 +242,7 @@ class DybitNetwork:
                                   "relu": relu, "stride": stride, "pad": pad, "k": k, **p})
                 out = y
                 Ho = (H + 2 * pad - k) // stride + 1
-                Wo = (W + 2 * pad - k) // stride + 1
+                Wo = (W + 2 * pad - p["kw"]) // stride + 1
                 shapes[name] = (Bn, Ho, Wo, p["cout"])
             if op in ("maxpool", "avgpool"):
                 shapes[name] = tuple(out.shape)

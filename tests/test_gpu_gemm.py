@@ -169,17 +169,20 @@ def test_conv_small(x_fmt, w_fmt, Cin, geom):
                                                  ((8, True), (4, True), 2, 8), ((4, False), (8, True), 2, 16),
                                                  ((8, False), (8, True), 1, 16), ((6, False), (6, True), 8, 4)])
 @pytest.mark.parametrize("kh,stride,pad,shape", [(7, 2, 3, (3, 23, 21)), (3, 1, 1, (2, 9, 17)), (1, 1, 0, (1, 5, 19)),
-                                                 (2, 3, 4, (2, 12, 16)), (5, 2, 8, (1, 7, 16))])
+                                                 (2, 3, 4, (2, 12, 16)), (5, 2, 8, (1, 7, 16)),
+                                                 (8, 2, 3, (3, 23, 21)), (4, 1, 2, (2, 9, 27)), (6, 2, 5, (1, 30, 17))])
 def test_conv_few_channels(x_fmt, w_fmt, Cin, kw, kh, stride, pad, shape):
     """Few input channels with kw * Cin a multiple of 16 (the first layer of an image network with its
-    filter rows padded by zero taps): the general kernel fetches runs of neighbouring taps.  Rectangular
+    filter rows padded by zero taps): the general kernel fetches runs of neighbouring taps, and where a
+    filter row is exactly 32 codes and the filter has an even number of rows the 128 x 128 kernel fetches
+    whole filter rows.  Rectangular
     filters, taps left / right / above / below the image, runs that start at any byte (6-bit: three bytes
     per pixel), tensors whose size is not a multiple of four bytes, padding wider than the filter."""
     Bn, H, W = shape
     if W + 2 * pad < kw or H + 2 * pad < kh:
         pytest.skip("filter larger than the padded image")
     rng = np.random.default_rng(Cin * 100 + kw * 10 + kh)
-    Cout = 19
+    Cout = 19 if kh % 2 else 150                                  # two column tiles for the tiled kernel
     qx = random_codes(rng, (Bn, H, W, Cin), x_fmt)
     qw = random_codes(rng, (Cout, kh, kw, Cin), w_fmt)
     bias = rng.normal(0, 1, Cout).astype(np.float32)

@@ -34,8 +34,8 @@ def check_layer(name, rec, weights, rng, n_rows=None, n_codes=None):
     # weights: quantized once by the library, checked against the oracle on the same padded tensor
     w, bias = weights[name]
     cout, k, kw, cin = w.shape
-    wp = np.zeros((cout, k, rec["kw"], C), dtype=np.float32)      # the driver may pad channels and filter rows with zeros
-    wp[:, :, :kw, :cin] = w
+    wp = np.zeros((cout, rec["k"], rec["kw"], C), dtype=np.float32)   # the driver may pad channels and the filter with zeros
+    wp[:, :k, :kw, :cin] = w
     sw = np.float32(rec["w_scale"].item())
     assert sw == R.absmax_scale(wp, *w_fmt), name
     qw = R.quantize(wp, sw, *w_fmt)
@@ -87,8 +87,8 @@ def check_layer_static(name, rec, weights, rng, n_rows=None):
     qx = R.unpack(rec["a_codes"].cpu().numpy().reshape(-1), Bn * H * W * C, a_fmt[0]).reshape(Bn, H, W, C)
     w, bias = weights[name]
     cout, k, kw, cin = w.shape
-    wp = np.zeros((cout, k, rec["kw"], C), dtype=np.float32)
-    wp[:, :, :kw, :cin] = w
+    wp = np.zeros((cout, rec["k"], rec["kw"], C), dtype=np.float32)
+    wp[:, :k, :kw, :cin] = w
     qw = R.quantize(wp, sw, *w_fmt)
     rows, want, den = conv_reference(rec, qx, qw, bias, s, sw, rng, n_rows)
     y32 = None
