@@ -21,7 +21,10 @@ SOURCES = [
     ("gemm_mid.hip", "gemm_mid_w6", ["-DDYBIT_MID_W=4"]),
     ("gemm_f8.hip", "gemm_f8", []),
     # write-back builds of the same kernels (epilogue also encodes the results as DyBit codes)
-    ("gemm.hip", "gemm_wb", ["-DDYBIT_WB=1"]),
+    ("gemm.hip", "gemm_wb_a2", ["-DDYBIT_WB=1", "-DDYBIT_GEN_A=2"]),
+    ("gemm.hip", "gemm_wb_a4", ["-DDYBIT_WB=1", "-DDYBIT_GEN_A=4"]),
+    ("gemm.hip", "gemm_wb_a6", ["-DDYBIT_WB=1", "-DDYBIT_GEN_A=6"]),
+    ("gemm.hip", "gemm_wb_a8", ["-DDYBIT_WB=1", "-DDYBIT_GEN_A=8"]),
     ("gemm_fast.hip", "gemm_fast_w4_wb", ["-DDYBIT_FAST_W=0", "-DDYBIT_WB=1"]),
     ("gemm_fast.hip", "gemm_fast_w8_wb", ["-DDYBIT_FAST_W=2", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w4_wb", ["-DDYBIT_MID_W=0", "-DDYBIT_WB=1"]),
@@ -54,9 +57,22 @@ def _compile(item) -> str:
     return obj
 
 
+# Longest compilations first, so that the pool's last jobs are short ones.
+_ORDER = ("gemm", "gemm_wb", "gemm_mid", "gemm_f8", "gemm_fast", "quantize")
+
+
+def _rank(item) -> int:
+    stem = item[1]
+    for i, prefix in enumerate(_ORDER):
+        if stem == prefix or (i >= 1 and stem.startswith(prefix)):
+            return i
+    return len(_ORDER)
+
+
 def build(verbose: bool = True) -> str:
-    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 8)) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+    jobs = sorted(SOURCES, key=_rank)
+    with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 8)) as ex:
+        objs = list(ex.map(_compile, jobs))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     p = subprocess.run(cmd, capture_output=True, text=True)
     if p.returncode:

@@ -409,6 +409,13 @@ static void launch_gemm(const GemmArgs &g, bool conv, int mode, hipStream_t st)
     }
 }
 
+// The write-back build of this file is compiled once per activation width (DYBIT_GEN_A = 2, 4, 6, 8:
+// a quarter of the kernels each, so that the translation units compile side by side); the plain
+// build holds all sixteen pairs.
+#ifndef DYBIT_GEN_A
+#define DYBIT_GEN_A 0
+#endif
+#if DYBIT_GEN_A == 0
 void DYBIT_WB_NAME(launch_gemm_general)(const GemmArgs &g, int ba, int bw, bool conv, int mode, hipStream_t st)
 {
 #define DYBIT_G(A_, W_) case (A_) * 16 + (W_): launch_gemm<A_, W_>(g, conv, mode, st); break
@@ -420,10 +427,23 @@ void DYBIT_WB_NAME(launch_gemm_general)(const GemmArgs &g, int ba, int bw, bool 
     }
 #undef DYBIT_G
 }
+#else
+#define DYBIT_GEN_NAME2(a) DYBIT_WB_NAME(launch_gemm_general_a##a)
+#define DYBIT_GEN_NAME(a) DYBIT_GEN_NAME2(a)
+void DYBIT_GEN_NAME(DYBIT_GEN_A)(const GemmArgs &g, int bw, bool conv, int mode, hipStream_t st)
+{
+    switch (bw) {
+        case 2: launch_gemm<DYBIT_GEN_A, 2>(g, conv, mode, st); break;
+        case 4: launch_gemm<DYBIT_GEN_A, 4>(g, conv, mode, st); break;
+        case 6: launch_gemm<DYBIT_GEN_A, 6>(g, conv, mode, st); break;
+        case 8: launch_gemm<DYBIT_GEN_A, 8>(g, conv, mode, st); break;
+    }
+}
+#endif
 
 }  // namespace dybit
 
-#if !DYBIT_WB   // the C entry points live in the plain build of this file
+#if !DYBIT_WB && DYBIT_GEN_A == 0   // the C entry points live in the plain build of this file
 using namespace dybit;
 
 namespace {
@@ -611,4 +631,4 @@ extern "C" dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t
     e.has_codes = true; e.q_fmt = y_fmt; e.q_scale = y_scale; e.q_out = Y_codes;
     return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, e, Y, stream);
 }
-#endif   // !DYBIT_WB
+#endif   // plain build

@@ -63,6 +63,11 @@ bool launch_gemm_f8_wb(const GemmArgs &g, bool conv, bool large, hipStream_t st)
 // only) aligned operands, Cin divides 16 and kw * Cin is a multiple of 16, tensor below 2 GiB.
 void launch_gemm_general(const GemmArgs &g, int a_bits, int w_bits, bool conv, int mode, hipStream_t st);
 void launch_gemm_general_wb(const GemmArgs &g, int a_bits, int w_bits, bool conv, int mode, hipStream_t st);
+// the write-back build's kernels, one translation unit per activation width (gemm_dispatch.cpp joins them)
+void launch_gemm_general_a2_wb(const GemmArgs &g, int w_bits, bool conv, int mode, hipStream_t st);
+void launch_gemm_general_a4_wb(const GemmArgs &g, int w_bits, bool conv, int mode, hipStream_t st);
+void launch_gemm_general_a6_wb(const GemmArgs &g, int w_bits, bool conv, int mode, hipStream_t st);
+void launch_gemm_general_a8_wb(const GemmArgs &g, int w_bits, bool conv, int mode, hipStream_t st);
 
 // Picks a tiled kernel for the problem (gemm_dispatch.cpp).  Returns false when the problem does
 // not meet their preconditions; the caller then uses the general kernel.

@@ -17,6 +17,16 @@
 
 namespace dybit {
 
+void launch_gemm_general_wb(const GemmArgs &g, int a_bits, int w_bits, bool conv, int mode, hipStream_t st)
+{
+    switch (a_bits) {
+        case 2: launch_gemm_general_a2_wb(g, w_bits, conv, mode, st); break;
+        case 4: launch_gemm_general_a4_wb(g, w_bits, conv, mode, st); break;
+        case 6: launch_gemm_general_a6_wb(g, w_bits, conv, mode, st); break;
+        case 8: launch_gemm_general_a8_wb(g, w_bits, conv, mode, st); break;
+    }
+}
+
 bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hipStream_t st)
 {
     if ((a_bits != 4 && a_bits != 6 && a_bits != 8) || (w_bits != 4 && w_bits != 6 && w_bits != 8) || !g.w_signed) return false;
