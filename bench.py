@@ -39,8 +39,8 @@ PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E peak
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (units of 2 KiB and 1 KiB on
 # this device, calibrated on a 1 GiB copy); the summaries are under profiles/.
-MEASURED_TRAFFIC = {"cfg5": 262322 * 2048 + 262203 * 1024, "cfg2": 2098 * 2048 + 12544 * 1024, "cfg1": None}
-MEASURED_TRAFFIC_GEMM_4BIT = 196734 * 2048 + 262348 * 1024
+MEASURED_TRAFFIC = {"cfg5": 262303 * 2048 + 262222 * 1024, "cfg2": 2119 * 2048 + 12544 * 1024, "cfg1": None}
+MEASURED_TRAFFIC_GEMM_4BIT = 196756 * 2048 + 262305 * 1024
 MEASURED_TRAFFIC_QUANTIZE4 = 524376 * 2048 + 131072 * 1024
 
 
@@ -73,6 +73,29 @@ def time_events(fn, steps, warmup, torch):
     torch.cuda.synchronize()
     ts = sorted(s.elapsed_time(e) for s, e in ev)
     return float(np.mean(ts)), float(ts[len(ts) // 2])
+
+
+def network_roofline(work, ms):
+    """Network-level bound of the dynamic chain: per layer the larger of its matrix time at the peak
+    of the MFMA type its operands run on (e4m3 for two 4-bit operands, else fp16) and its HBM time for
+    the algorithmic bytes (packed operands once, fp32 output once, fp32 shortcut once), plus the HBM
+    time of the quantize pass over the layer's input (4 + bits/8 bytes per activation); summed over
+    the layers and divided by the measured time of a forward pass."""
+    t_mfma = t_hbm = t_bound = 0.0
+    for w in work:
+        flops = 2.0 * w["M"] * w["N"] * w["K"]
+        peak = PEAK_FP8_MFMA_TFLOPS if (w["bits_w"] == 4 and w["bits_a"] == 4) else PEAK_FP16_MFMA_TFLOPS
+        byts = w["inputs"] * w["bits_a"] / 8 + w["N"] * w["K"] * w["bits_w"] / 8 + 4.0 * w["M"] * w["N"] * (2 if w["shortcut"] else 1)
+        quant = w["inputs"] * (4 + w["bits_a"] / 8)
+        tm, th = flops / (peak * 1e12), byts / (PEAK_HBM_GBPS * 1e9)
+        t_mfma += tm
+        t_hbm += th + quant / (PEAK_HBM_GBPS * 1e9)
+        t_bound += max(tm, th) + quant / (PEAK_HBM_GBPS * 1e9)
+    flops = sum(2.0 * w["M"] * w["N"] * w["K"] for w in work)
+    return {"bound": "hbm+mfma", "rule": "per layer max(mfma time, hbm time) + hbm time of its quantize pass, summed",
+            "achieved": round(flops / (ms * 1e-3) / 1e12, 3), "peak": round(flops / t_bound / 1e12, 3), "unit": "TOPS",
+            "frac": round(t_bound * 1e3 / ms, 4), "bound_ms": round(t_bound * 1e3, 4),
+            "mfma_ms_at_peak": round(t_mfma * 1e3, 4), "hbm_ms_at_peak": round(t_hbm * 1e3, 4), "traffic": None}
 
 
 def bench_network(args):
@@ -124,7 +147,7 @@ def bench_network(args):
         "vs_baseline": None, "dtype": "f16 or e4m3 MFMA inputs by layer (exact), f32 accumulate", "data": "synthetic",
         "config": {"workload": name, "gemms": len(shapes), "GMAC": round(flops / 2e9, 1),
                    "step": "per layer scale + quantize + conv (bias, shortcut, ReLU and max|result| in the epilogue); pooling in torch"},
-        "roofline": None,
+        "roofline": network_roofline(net.layer_work(batch, 224), ms),
         "fused_write_back": {"ms_per_step": round(ms_static, 4), "TOPS": round(flops / (ms_static * 1e-3) / 1e12, 3),
                              "step": "scales fixed by a calibration pass; every convolution whose consumers agree on a "
                                      "format writes DyBit codes from its epilogue (dybit_conv2d_wb), fp32 only where a "
@@ -166,8 +189,15 @@ def table(args):
     print("|---|---|---|---|---|---|")
     for wl, r in rows:
         rf, cb = r.get("roofline"), r.get("cpu_baseline")
-        kern = "%s: %.4f ms, %.1f TFLOP/s" % (rf["kernel"], rf["kernel_ms"], rf["achieved"]) if rf else "-"
-        frac = "%.1f %% of %.0f TFLOP/s" % (100 * rf["frac"], rf["peak"]) if rf else "-"
+        if rf and "kernel" in rf:
+            kern = "%s: %.4f ms, %.1f TFLOP/s" % (rf["kernel"], rf["kernel_ms"], rf["achieved"])
+            frac = "%.1f %% of %.0f TFLOP/s" % (100 * rf["frac"], rf["peak"])
+        elif rf:                                                    # chained networks: per-layer bound, summed
+            kern = "-"
+            frac = "%.1f %% of the per-layer max(MFMA, HBM) bound (%.3f ms: MFMA %.3f ms, HBM %.3f ms at peak)" % (
+                100 * rf["frac"], rf["bound_ms"], rf["mfma_ms_at_peak"], rf["hbm_ms_at_peak"])
+        else:
+            kern = frac = "-"
         orc = "%.4f TOPS (%d), %s" % (cb["value"], cb["cores"], cb["sample"]) if cb else "-"
         print("| %s | %.4f ms | %.3f TOPS | %s | %s | %s |" % (r["config"]["workload"], r["ms_per_step"], r["value"], kern, frac, orc))
         if "fused_write_back" in r:

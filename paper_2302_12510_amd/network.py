@@ -249,6 +249,32 @@ class DybitNetwork:
             acts[name] = out
         return out.reshape(out.shape[0], -1)
 
+    def layer_work(self, batch: int, hw: int):
+        """Per conv/fc layer, for an input of batch x hw x hw: the GEMM shape (K on the real channel
+        count), the number of input activations, the operand widths and whether a shortcut is added --
+        what a per-layer roofline needs."""
+        sizes = {"input": hw}
+        out = []
+        for l in self.layers:
+            s = sizes[l["src"]]
+            if l["op"] == "maxpool":
+                sizes[l["name"]] = (s + 2 * l["pad"] - l["k"]) // l["stride"] + 1
+            elif l["op"] == "avgpool":
+                sizes[l["name"]] = 1
+            else:
+                bw, ba = self.bitwidths[l["name"]]
+                if l["op"] == "fc":
+                    sizes[l["name"]] = 1
+                    m, n, k, n_in = batch, l["cout"], l["cin"], batch * l["cin"]
+                else:
+                    o = (s + 2 * l["pad"] - l["k"]) // l["stride"] + 1
+                    sizes[l["name"]] = o
+                    m, n, k = batch * o * o, l["cout"], l["k"] * l["k"] * l["cin"]
+                    n_in = batch * s * s * l["cin"]
+                out.append({"name": l["name"], "M": m, "N": n, "K": k, "inputs": n_in, "bits_w": bw, "bits_a": ba,
+                            "shortcut": bool(l.get("add"))})
+        return out
+
     def gemm_shapes(self, batch: int, hw: int):
         """(name, M, N, K) of every conv/fc layer for an input of batch x hw x hw (K counted on
         the real channel count, not the padded one)."""
