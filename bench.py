@@ -47,9 +47,10 @@ MEASURED_TRAFFIC_QUANTIZE4 = 524376 * 2048 + 131072 * 1024
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1", "cfg3", "cfg4"],
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=30,
+                    help="untimed steps; the device needs a few tens of milliseconds of load to settle its clocks")
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1", "cfg3", "cfg4", "modes"],
                     help="cfg5 (default): 8192^3 GEMM + 2^28 quantize; cfg1 / cfg2: the small GEMM and the "
                          "convolution; cfg3 / cfg4: one forward pass of the ResNet-18 / ResNet-50 chains")
     ap.add_argument("--table", action="store_true",
@@ -96,6 +97,39 @@ def network_roofline(work, ms):
             "achieved": round(flops / (ms * 1e-3) / 1e12, 3), "peak": round(flops / t_bound / 1e12, 3), "unit": "TOPS",
             "frac": round(t_bound * 1e3 / ms, 4), "bound_ms": round(t_bound * 1e3, 4),
             "mfma_ms_at_peak": round(t_mfma * 1e3, 4), "hbm_ms_at_peak": round(t_hbm * 1e3, 4), "traffic": None}
+
+
+def bench_modes(args):
+    """The (W, A) bitwidth mode matrix {8, 4, 2} x {8, 4, 2} the mixed-precision search chooses from
+    (Sec. III-C), plus the 6-bit column and row: kernel time of the cfg5 GEMM shape for every pair, on the
+    tensors of config 5 (weights signed, activations signed).  One JSON line with a TFLOP/s table."""
+    import torch
+    from paper_2302_12510_amd import binding as B
+    from paper_2302_12510_amd import synth
+
+    torch.cuda.set_device(0)
+    B.lib()
+    size = args.size
+    cfg = synth.config5a(size=size)
+    A = torch.from_numpy(cfg["A"]).cuda().reshape(-1)
+    Wf = torch.from_numpy(cfg["W"]).cuda().reshape(-1)
+    C = torch.empty((size, size), dtype=torch.float32, device="cuda")
+    flops = 2.0 * size ** 3
+    table = {}
+    for bw in (8, 6, 4, 2):
+        sw = B.dybit_absmax_scale(Wf, bw, True)
+        qw = B.dybit_quantize(Wf, sw, bw, True)
+        for ba in (8, 6, 4, 2):
+            sa = B.dybit_absmax_scale(A, ba, True)
+            qa = B.dybit_quantize(A, sa, ba, True)
+            ms, _ = time_events(lambda: B.dybit_gemm(size, size, size, qa, (ba, True), sa, qw, (bw, True), sw, out=C),
+                                args.steps, args.warmup, torch)
+            table["W%d/A%d" % (bw, ba)] = {"kernel_ms": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1)}
+    assert B.dybit_get_last_async_error() == B.OK
+    print(json.dumps({"metric": "DyBit GEMM kernel TFLOP/s per (W, A) bitwidth mode", "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                      "config": {"workload": "mode matrix: GEMM M=N=K=%d on the config 5 tensors, W and A signed" % size},
+                      "modes": table}))
 
 
 def bench_network(args):
@@ -225,6 +259,8 @@ def main():
         return table(args)
     if args.workload in ("cfg3", "cfg4"):
         return bench_network(args)
+    if args.workload == "modes":
+        return bench_modes(args)
     import torch
     from paper_2302_12510_amd import binding as B
     from paper_2302_12510_amd import synth

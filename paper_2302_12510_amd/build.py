@@ -19,6 +19,7 @@ SOURCES = [
     ("gemm_mid.hip", "gemm_mid_w4", ["-DDYBIT_MID_W=0"]),
     ("gemm_mid.hip", "gemm_mid_w8", ["-DDYBIT_MID_W=2"]),
     ("gemm_mid.hip", "gemm_mid_w6", ["-DDYBIT_MID_W=4"]),
+    ("gemm_mid.hip", "gemm_mid_w2", ["-DDYBIT_MID_W=6"]),
     ("gemm_f8.hip", "gemm_f8", []),
     # write-back builds of the same kernels (epilogue also encodes the results as DyBit codes)
     ("gemm.hip", "gemm_wb_a2", ["-DDYBIT_WB=1", "-DDYBIT_GEN_A=2"]),
@@ -30,6 +31,7 @@ SOURCES = [
     ("gemm_mid.hip", "gemm_mid_w4_wb", ["-DDYBIT_MID_W=0", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w8_wb", ["-DDYBIT_MID_W=2", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w6_wb", ["-DDYBIT_MID_W=4", "-DDYBIT_WB=1"]),
+    ("gemm_mid.hip", "gemm_mid_w2_wb", ["-DDYBIT_MID_W=6", "-DDYBIT_WB=1"]),
     ("gemm_f8.hip", "gemm_f8_wb", ["-DDYBIT_WB=1"]),
     ("diag.hip", "diag", []),
 ]

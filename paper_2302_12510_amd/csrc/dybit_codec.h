@@ -1,7 +1,7 @@
 // Decoders from packed DyBit codes to fp16 pairs, entirely in the vector ALU (no table look-ups
 // in memory).  Shared by the tiled matrix-product kernels.
 //
-// Every DyBit value of the 4-, 6- and 8-bit formats is exact in fp16.  All decoders emit each group
+// Every DyBit value of the 2-, 4-, 6- and 8-bit formats is exact in fp16.  All decoders emit each group
 // of eight consecutive k values in the order (k0,k2,k1,k3,k4,k6,k5,k7): that is the order their
 // packed arithmetic produces for free, and a contraction does not care about the order of k as
 // long as both operands agree.
@@ -23,7 +23,7 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kOob = 0x80000000u;            // a buffer offset past every supported size: such loads return 0
 
-enum { F4S = 0, F4U = 1, F8S = 2, F8U = 3, F6S = 4, F6U = 5 };
+enum { F4S = 0, F4U = 1, F8S = 2, F8U = 3, F6S = 4, F6U = 5, F2S = 6, F2U = 7 };
 
 // ---------------------------------------------------------------------------
 // Codecs: packed codes -> fp16 pairs, entirely in the vector ALU.
@@ -56,7 +56,8 @@ template <int FMT> struct Codec;
 
 // Codec<F>::word decodes one 32-bit word; decode_eight decodes the q-th group of eight codes of
 // a thread's 32 codes (held in registers of 128 bits: one for 4-bit codes, two for 8-bit codes,
-// the first 24 bytes of two for 6-bit codes) into four registers of two halves.
+// the first 24 bytes of two for 6-bit codes, the first 8 bytes of one for 2-bit codes) into four
+// registers of two halves.
 template <int FMT>
 __device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
 {
@@ -64,6 +65,10 @@ __device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
     if constexpr (C::BITS == 8) {
         const u32x4 r = raw[q >> 1];
         C::two_words((q & 1) ? r.z : r.x, (q & 1) ? r.w : r.y, d);
+    } else if constexpr (C::BITS == 2) {
+        const u32x4 r = raw[0];
+        const u32 w = (q & 2) ? r.y : r.x;
+        C::half_word((q & 1) ? (w >> 16) : w, d);
     } else if constexpr (C::BITS == 6) {
         // eight codes are 48 bits: two groups of four codes (24 bits) taken out of the 192-bit run
         const u32x4 r0 = raw[0], r1 = raw[1];
@@ -182,6 +187,28 @@ template <> struct Codec<F6U> {
         recip_decode_4pairs(h, 0x8C008C00u, d);
     }
 };
+
+// 2-bit formats: four values, so the high byte of the half comes from a 4-entry byte table
+// (v_perm_b32) indexed by the code itself, sign included; the low byte is zero.
+// half_word: 8 codes (k0..k7) in the low 16 bits of w -> (k0,k2), (k1,k3), (k4,k6), (k5,k7).
+template <u32 TABLE> struct Codec2 {
+    static constexpr int BITS = 2;
+    static __device__ __forceinline__ u32 spread_even(u32 w)       // fields 0, 2, 4, 6 -> one per byte
+    {
+        return (w & 0x3u) | ((w << 4) & 0x300u) | ((w << 8) & 0x30000u) | ((w << 12) & 0x3000000u);
+    }
+    static __device__ __forceinline__ void half_word(u32 w, u32 *d)
+    {
+        const u32 e = __builtin_amdgcn_perm(0u, TABLE, spread_even(w));         // high bytes of k0 k2 k4 k6
+        const u32 o = __builtin_amdgcn_perm(0u, TABLE, spread_even(w >> 2));    // k1 k3 k5 k7
+        d[0] = __builtin_amdgcn_perm(0u, e, 0x010c000cu);
+        d[1] = __builtin_amdgcn_perm(0u, o, 0x010c000cu);
+        d[2] = __builtin_amdgcn_perm(0u, e, 0x030c020cu);
+        d[3] = __builtin_amdgcn_perm(0u, o, 0x030c020cu);
+    }
+};
+template <> struct Codec<F2S> : Codec2<0xBC003C00u> {};   // codes 00, 01, 10, 11 -> 0, +1, (-0 =) 0, -1
+template <> struct Codec<F2U> : Codec2<0x403C3800u> {};   //                        0, 0.5, 1, 2
 
 // 4-bit formats: every value has at most 3 significant bits, so its half has a zero low byte
 // and the high byte comes from an 8-entry byte table held in two registers (v_perm_b32).

@@ -46,12 +46,14 @@ bool launch_gemm_fast_w0(const GemmArgs &g, int a_bits, bool conv, hipStream_t s
 bool launch_gemm_fast_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);   // W 8-bit signed
 bool launch_gemm_mid_w0(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
-bool launch_gemm_mid_w4(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);    // W 6-bit signed; a_bits 4, 6 or 8 for all three
+bool launch_gemm_mid_w4(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);    // W 6-bit signed
+bool launch_gemm_mid_w6(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);    // W 2-bit signed; a_bits 2, 4, 6 or 8 for all four
 bool launch_gemm_fast_w0_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_fast_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w0_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w4_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_mid_w6_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 
 // fp8 matrix path for pairs of 4-bit formats with signed weights (gemm_f8.hip): the 256 x 256 tile
 // when `large`, else the 128 x 128 tile.

@@ -1,6 +1,6 @@
 // Chooses between the tiled MFMA kernels of the DyBit matrix product.
 //
-// All need 4-, 6- or 8-bit operands (6-bit: the 128 x 128 fp16 kernel only), signed weights, K (convolution: Cin) a multiple of 64 so that
+// All need signed weights (2- and 6-bit operands: the 128 x 128 fp16 kernel only), K (convolution: Cin) a multiple of 64 so that
 // a 64-wide k group is one run of whole 128-bit loads inside one filter tap, 16-byte aligned
 // code buffers, and buffers below 2 GiB (32-bit buffer offsets).  The 256 x 256 kernel does the
 // least decode work per MFMA and is used when its tiles can fill the 256 compute units, N is
@@ -29,7 +29,7 @@ void launch_gemm_general_wb(const GemmArgs &g, int a_bits, int w_bits, bool conv
 
 bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hipStream_t st)
 {
-    if ((a_bits != 4 && a_bits != 6 && a_bits != 8) || (w_bits != 4 && w_bits != 6 && w_bits != 8) || !g.w_signed) return false;
+    if (!g.w_signed) return false;                                  // every width 2, 4, 6, 8 has a decoder; weights are signed
     if (g.M < 1 || g.N < 1 || g.K < 64 || g.K % 64) return false;
     // a convolution needs whole 64-code k groups inside a filter tap, or (few channels) filter rows of
     // exactly 32 codes, which the 128 x 128 kernel fetches row by row
@@ -56,8 +56,8 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
         const bool both4 = a_bits == 4 && w_bits == 4;
         large = g.N > 128 && tiles256 >= 128 && g.K >= (both4 ? 2048 : 1024);
     }
-    const bool six = a_bits == 6 || w_bits == 6;                    // 6-bit operands: the 128 x 128 kernel only
-    if (six || rows) large = false;
+    const bool mid_only = (a_bits != 4 && a_bits != 8) || (w_bits != 4 && w_bits != 8);   // 2- and 6-bit operands: the 128 x 128 kernel only
+    if (mid_only || rows) large = false;
     // two 4-bit operands: every value is exact in e4m3, so the fp8 matrix path (twice the fp16 rate,
     // byte decoders) takes them unless DYBIT_GEMM_MFMA=f16 asks for the fp16 kernels
     const char *mfma = getenv("DYBIT_GEMM_MFMA");
@@ -69,6 +69,7 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
     }
     if (w_bits == 4) return (wb ? launch_gemm_mid_w0_wb : launch_gemm_mid_w0)(g, a_bits, conv, st);
     if (w_bits == 6) return (wb ? launch_gemm_mid_w4_wb : launch_gemm_mid_w4)(g, a_bits, conv, st);
+    if (w_bits == 2) return (wb ? launch_gemm_mid_w6_wb : launch_gemm_mid_w6)(g, a_bits, conv, st);
     return (wb ? launch_gemm_mid_w2_wb : launch_gemm_mid_w2)(g, a_bits, conv, st);
 }
 

@@ -50,11 +50,14 @@ template <int KG> struct Geom {
 static_assert(Geom<2>::LDS_BYTES >= 4 * 4 * 16 * 64 * 4, "reduction buffer must fit in the stages");
 
 // A run of 32 codes into registers: one or two 128-bit loads, or (6-bit: 24 bytes, a multiple of 8 from
-// the row start) three 64-bit loads.  An out-of-range offset reads zeros.
+// the row start) three 64-bit loads, or (2-bit: 8 bytes) one.  An out-of-range offset reads zeros.
 template <int BITS>
 __device__ __forceinline__ void load_run(const __amdgpu_buffer_rsrc_t rsrc, u32 off, u32x4 *raw)
 {
-    if constexpr (BITS == 6) {
+    if constexpr (BITS == 2) {
+        const auto a = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0);
+        raw[0] = u32x4{a[0], a[1], 0u, 0u};
+    } else if constexpr (BITS == 6) {
         const auto a = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0);
         const auto b = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off + 8, 0, 0);
         const auto c = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off + 16, 0, 0);
@@ -356,8 +359,10 @@ static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 bool DYBIT_MID_NAME(DYBIT_MID_W)(const GemmArgs &g, int a_bits, bool conv, hipStream_t st)
 {
     using namespace fast;
-    const int fa = (a_bits == 8 ? F8S : a_bits == 6 ? F6S : F4S) + (g.a_signed ? 0 : 1);
+    const int fa = (a_bits == 8 ? F8S : a_bits == 6 ? F6S : a_bits == 2 ? F2S : F4S) + (g.a_signed ? 0 : 1);
     switch (fa) {
+        case F2S: mid::launch<F2S, DYBIT_MID_W>(g, conv, st); return true;
+        case F2U: mid::launch<F2U, DYBIT_MID_W>(g, conv, st); return true;
         case F4S: mid::launch<F4S, DYBIT_MID_W>(g, conv, st); return true;
         case F4U: mid::launch<F4U, DYBIT_MID_W>(g, conv, st); return true;
         case F6S: mid::launch<F6S, DYBIT_MID_W>(g, conv, st); return true;
