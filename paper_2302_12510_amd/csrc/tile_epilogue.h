@@ -35,20 +35,38 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
         const_cast<float *>(HAS_RES ? g.residual + m_strip * g.ldc : g.C), 0, HAS_RES ? records : 0, 0x00020000);
     const bool track = g.absmax_bits != nullptr;
     float mx = 0.0f;
+    // The shortcut values of block j + 1 are requested before block j is stored (kernels with at most
+    // four blocks per wave: the others have no registers to spare).  Memory operations retire in order,
+    // so waiting for those loads does not wait for the stores issued after them; without the prefetch
+    // every block's loads queue behind the previous block's stores and the two latencies add up.
+    constexpr bool PREFETCH = HAS_RES && CB <= 4;
+    auto first_offset = [&](int j, bool &n_ok, int64_t &n) {
+        n = n0 + j * 32 + col;
+        n_ok = n < g.N;
+        return (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
+    };
+    auto load_shortcut = [&](uint32_t off, float (&r)[16]) {           // out-of-range elements read 0
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            r[v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, off, 0, 0));
+            off += (v & 3) == 3 ? 5u * ldc4 : ldc4;
+        }
+    };
+    float res2[2][16];
+    if (PREFETCH) {
+        bool ok0; int64_t nn0;
+        load_shortcut(first_offset(0, ok0, nn0), res2[0]);
+    }
 #pragma unroll
     for (int j = 0; j < CB; ++j) {
-        const int64_t n = n0 + j * 32 + col;
-        const bool n_ok = n < g.N;
+        bool n_ok; int64_t n;
+        const uint32_t off0 = first_offset(j, n_ok, n);
         const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
-        const uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
-        float res[16];
-        if (HAS_RES) {                                                  // out-of-range elements read 0
-            uint32_t off = off0;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                res[v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, off, 0, 0));
-                off += (v & 3) == 3 ? 5u * ldc4 : ldc4;
-            }
+        float (&res)[16] = res2[PREFETCH ? (j & 1) : 0];
+        if (HAS_RES && !PREFETCH) load_shortcut(off0, res);
+        if (PREFETCH && j + 1 < CB) {
+            bool ok1; int64_t nn1;
+            load_shortcut(first_offset(j + 1, ok1, nn1), res2[(j + 1) & 1]);
         }
         uint32_t off = off0;
 #pragma unroll
@@ -96,6 +114,16 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
     const bool track = g.absmax_bits != nullptr;
     const float relu_floor = g.relu ? 0.0f : -__builtin_inff();        // ReLU as a maximum: no select per value
     float mx = 0.0f;
+    constexpr bool PREFETCH = HAS_RES && CB <= 4;
+    float res2[2][GV];
+    uint32_t roff = 0;                                                  // walks the shortcut's rows like `off` walks C's
+    auto load_shortcut = [&](int first_v, float (&r)[GV]) {
+#pragma unroll
+        for (int u = 0; u < GV; ++u) {
+            r[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, roff, 0, 0));
+            roff += ((first_v + u) & 3) == 3 ? 5u * ldc4 : ldc4;
+        }
+    };
 #pragma unroll
     for (int j = 0; j < CB; ++j) {
         const int64_t n = n0 + j * 32 + col;
@@ -104,15 +132,22 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
         const uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
         const PackSlot slot = pack_slot<BITS>(lane, (uint32_t)n);
         uint32_t qoff = ((n_ok && slot.stores && rqp.ok) ? slot.byte_off : 0x80000000u) + (uint32_t)(4 * kq) * qrow;
-        uint32_t off = off0, roff = off0;
+        uint32_t off = off0;
+        if (HAS_RES && (j == 0 || !PREFETCH)) { roff = off0; if (PREFETCH) load_shortcut(0, res2[0]); }
 #pragma unroll
         for (int h = 0; h < 16; h += GV) {                                   // GV values at a time: fewer live registers
-            float res[GV];
-            if (HAS_RES) {
-#pragma unroll
-                for (int u = 0; u < GV; ++u) {
-                    res[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, roff, 0, 0));
-                    roff += ((h + u) & 3) == 3 ? 5u * ldc4 : ldc4;
+            // the shortcut values of the next group are requested before this group is stored (see
+            // store_strip) where the kernel has registers for them; else they are loaded here
+            const int grp = (j * 16 + h) / GV;
+            float (&res)[GV] = res2[PREFETCH ? (grp & 1) : 0];
+            if (HAS_RES && !PREFETCH) load_shortcut(h, res);
+            if (PREFETCH) {
+                if (h + GV < 16) {
+                    load_shortcut(h + GV, res2[(grp + 1) & 1]);
+                } else if (j + 1 < CB) {
+                    const int64_t n1 = n0 + (j + 1) * 32 + col;
+                    roff = (n1 < g.N ? (uint32_t)n1 * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
+                    load_shortcut(0, res2[(grp + 1) & 1]);
                 }
             }
             float c[GV];
