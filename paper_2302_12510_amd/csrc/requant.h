@@ -126,10 +126,13 @@ __device__ __forceinline__ uint32_t requant_code(float x, const Requant &r)
 
 // ---- packing across lanes -----------------------------------------------------------------------
 // In the matrix-core result layout the 32 lanes of a half-wave hold 32 consecutive columns of one
-// row, so the codes of neighbouring lanes are neighbours in the packed row.  Each lane shifts its
-// code to its position inside a 32-bit word and the lanes that share the word OR their parts
-// together with data-parallel lane permutes (no LDS, no memory); the first lane of the group
-// stores the word.  All 64 lanes must be active.
+// row, so the codes of neighbouring lanes are neighbours in the packed row.  8-bit codes need no
+// packing: every lane stores its byte (32 consecutive bytes per row and instruction, the same
+// footprint as eight lanes storing words).  4-bit codes: a lane pair ORs its two nibbles together
+// with one data-parallel lane permute and the even lane stores the byte.  6-bit codes: each lane
+// shifts its code to its position inside a 32-bit word, the four lanes that share 24 bits OR their
+// parts together (two permutes), and 16 lanes' 96 bits leave as three words.  No LDS, no memory;
+// all 64 lanes must be active.
 __device__ __forceinline__ uint32_t or_quad(uint32_t w)
 {
     w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
@@ -140,8 +143,8 @@ __device__ __forceinline__ uint32_t or_quad(uint32_t w)
 // Where a lane's word goes inside the packed row and whether the lane is the one that stores it.
 // col = column of the lane's value (a multiple of 32 plus lane % 32).
 struct PackSlot {
-    uint32_t shift;      // position of the lane's code inside the group's word(s)
-    uint32_t byte_off;   // byte offset of the lane's word inside the packed row
+    uint32_t shift;      // position of the lane's code inside the group's byte or word(s)
+    uint32_t byte_off;   // byte offset of the lane's byte (4-, 8-bit) or word (6-bit) inside the packed row
     bool stores;
 };
 
@@ -150,9 +153,9 @@ __device__ __forceinline__ PackSlot pack_slot(int lane, uint32_t col)
 {
     PackSlot p;
     if (BITS == 8) {
-        p.shift = (lane & 3) * 8;  p.byte_off = col;            p.stores = (lane & 3) == 0;
+        p.shift = 0;               p.byte_off = col;            p.stores = true;
     } else if (BITS == 4) {
-        p.shift = (lane & 7) * 4;  p.byte_off = col >> 1;       p.stores = (lane & 7) == 0;
+        p.shift = (lane & 1) * 4;  p.byte_off = col >> 1;       p.stores = (lane & 1) == 0;
     } else {                                                    // 6-bit: 16 codes = three words
         const uint32_t k = (lane >> 2) & 3;                     // which group of four inside the 16
         p.shift = (lane & 3) * 6;  p.byte_off = (col >> 4) * 12 + 4 * k;   p.stores = (lane & 3) == 0 && k < 3;
@@ -163,10 +166,13 @@ __device__ __forceinline__ PackSlot pack_slot(int lane, uint32_t col)
 template <int BITS>
 __device__ __forceinline__ uint32_t pack_word(uint32_t code, int lane, const PackSlot &p)
 {
-    uint32_t w = or_quad(code << p.shift);
+    if (BITS == 8) return code;
     if (BITS == 4) {
-        w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xf, 0xf, true);   // row_half_mirror: the other four of eight
-    } else if (BITS == 6) {
+        const uint32_t w = code << p.shift;
+        return w | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]: the neighbour's nibble
+    }
+    uint32_t w = or_quad(code << p.shift);
+    if (BITS == 6) {
         // four lanes hold 24 bits; word k of the three takes the rest from the next group of four
         const uint32_t k = (lane >> 2) & 3;
         const uint32_t next = (uint32_t)__shfl_down((int)w, 4, 16);

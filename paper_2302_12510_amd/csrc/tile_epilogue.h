@@ -184,7 +184,9 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
             }
 #pragma unroll
             for (int u = 0; u < GV; ++u) {                                   // phase 3
-                __builtin_amdgcn_raw_buffer_store_b32(pack_word<BITS>(code[u], lane, slot), rq, qoff, 0, 2);
+                const uint32_t packed = pack_word<BITS>(code[u], lane, slot);
+                if constexpr (BITS == 6) __builtin_amdgcn_raw_buffer_store_b32(packed, rq, qoff, 0, 2);
+                else __builtin_amdgcn_raw_buffer_store_b8((unsigned char)packed, rq, qoff, 0, 2);
                 qoff += ((h + u) & 3) == 3 ? 5u * qrow : qrow;
             }
         }
