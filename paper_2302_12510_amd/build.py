@@ -21,6 +21,10 @@ SOURCES = [
     ("gemm_mid.hip", "gemm_mid_w6", ["-DDYBIT_MID_W=4"]),
     ("gemm_mid.hip", "gemm_mid_w2", ["-DDYBIT_MID_W=6"]),
     ("gemm_f8.hip", "gemm_f8", []),
+    ("gemm_ws.hip", "gemm_ws_w4", ["-DDYBIT_WS_W=0"]),
+    ("gemm_ws.hip", "gemm_ws_w8", ["-DDYBIT_WS_W=2"]),
+    ("gemm_ws.hip", "gemm_ws_w6", ["-DDYBIT_WS_W=4"]),
+    ("gemm_ws.hip", "gemm_ws_w2", ["-DDYBIT_WS_W=6"]),
     # write-back builds of the same kernels (epilogue also encodes the results as DyBit codes)
     ("gemm.hip", "gemm_wb_a2", ["-DDYBIT_WB=1", "-DDYBIT_GEN_A=2"]),
     ("gemm.hip", "gemm_wb_a4", ["-DDYBIT_WB=1", "-DDYBIT_GEN_A=4"]),
@@ -33,6 +37,10 @@ SOURCES = [
     ("gemm_mid.hip", "gemm_mid_w6_wb", ["-DDYBIT_MID_W=4", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w2_wb", ["-DDYBIT_MID_W=6", "-DDYBIT_WB=1"]),
     ("gemm_f8.hip", "gemm_f8_wb", ["-DDYBIT_WB=1"]),
+    ("gemm_ws.hip", "gemm_ws_w4_wb", ["-DDYBIT_WS_W=0", "-DDYBIT_WB=1"]),
+    ("gemm_ws.hip", "gemm_ws_w8_wb", ["-DDYBIT_WS_W=2", "-DDYBIT_WB=1"]),
+    ("gemm_ws.hip", "gemm_ws_w6_wb", ["-DDYBIT_WS_W=4", "-DDYBIT_WB=1"]),
+    ("gemm_ws.hip", "gemm_ws_w2_wb", ["-DDYBIT_WS_W=6", "-DDYBIT_WB=1"]),
     ("diag.hip", "diag", []),
 ]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
@@ -60,7 +68,7 @@ def _compile(item) -> str:
 
 
 # Longest compilations first, so that the pool's last jobs are short ones.
-_ORDER = ("gemm", "gemm_wb", "gemm_mid", "gemm_f8", "gemm_fast", "quantize")
+_ORDER = ("gemm", "gemm_wb", "gemm_mid", "gemm_ws", "gemm_f8", "gemm_fast", "quantize")
 
 
 def _rank(item) -> int:

@@ -55,6 +55,18 @@ bool launch_gemm_mid_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t
 bool launch_gemm_mid_w4_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w6_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 
+// Weight-stationary kernel (gemm_ws.hip) for layers whose decoded weight matrix fits the LDS of a
+// compute unit (N <= 128, N rounded up to 64 or 128 rows of 2 K + 16 bytes within 160 KiB); one
+// translation unit per weight format as above.  Returns false when the weights do not fit.
+bool launch_gemm_ws_w0(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_ws_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_ws_w4(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_ws_w6(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_ws_w0_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_ws_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_ws_w4_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_ws_w6_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+
 // fp8 matrix path for pairs of 4-bit formats with signed weights (gemm_f8.hip): the 256 x 256 tile
 // when `large`, else the 128 x 128 tile.
 bool launch_gemm_f8(const GemmArgs &g, bool conv, bool large, hipStream_t st);

@@ -41,6 +41,23 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
     bool large;
     const char *force = getenv("DYBIT_GEMM_KERNEL");
     if (force && !strcmp(force, "general")) return false;
+
+    // Weight-stationary kernel: the whole decoded weight matrix in LDS, for many rows against few
+    // weights (it declines when the weights do not fit).  DYBIT_GEMM_KERNEL=ws forces it where it fits.
+    const bool ws_forced = force && !strcmp(force, "ws");
+    const char *ws_env = getenv("DYBIT_GEMM_WS");                  // DYBIT_GEMM_WS=0 keeps it out of the automatic choice
+    const bool ws_off = ws_env && !strcmp(ws_env, "0");
+    if (!rows && (ws_forced || (!force && !ws_off && g.N <= 128 && g.M >= 16384))) {
+        const bool wb_ = g.q_out != nullptr;
+        bool done = false;
+        switch (w_bits) {
+            case 4: done = (wb_ ? launch_gemm_ws_w0_wb : launch_gemm_ws_w0)(g, a_bits, conv, st); break;
+            case 8: done = (wb_ ? launch_gemm_ws_w2_wb : launch_gemm_ws_w2)(g, a_bits, conv, st); break;
+            case 6: done = (wb_ ? launch_gemm_ws_w4_wb : launch_gemm_ws_w4)(g, a_bits, conv, st); break;
+            case 2: done = (wb_ ? launch_gemm_ws_w6_wb : launch_gemm_ws_w6)(g, a_bits, conv, st); break;
+        }
+        if (done) return true;
+    }
     if (force && !strcmp(force, "large")) {
         large = true;
     } else if (force && !strcmp(force, "mid")) {

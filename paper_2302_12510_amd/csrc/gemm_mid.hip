@@ -49,26 +49,6 @@ template <int KG> struct Geom {
 };
 static_assert(Geom<2>::LDS_BYTES >= 4 * 4 * 16 * 64 * 4, "reduction buffer must fit in the stages");
 
-// A run of 32 codes into registers: one or two 128-bit loads, or (6-bit: 24 bytes, a multiple of 8 from
-// the row start) three 64-bit loads, or (2-bit: 8 bytes) one.  An out-of-range offset reads zeros.
-template <int BITS>
-__device__ __forceinline__ void load_run(const __amdgpu_buffer_rsrc_t rsrc, u32 off, u32x4 *raw)
-{
-    if constexpr (BITS == 2) {
-        const auto a = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0);
-        raw[0] = u32x4{a[0], a[1], 0u, 0u};
-    } else if constexpr (BITS == 6) {
-        const auto a = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0);
-        const auto b = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off + 8, 0, 0);
-        const auto c = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off + 16, 0, 0);
-        raw[0] = u32x4{a[0], a[1], b[0], b[1]};
-        raw[1] = u32x4{c[0], c[1], 0u, 0u};
-    } else {
-#pragma unroll
-        for (int p = 0; p < BITS / 4; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + p * 16, 0, 0);
-    }
-}
-
 // CONV: 0 matrix product; 1 convolution whose 64-code k groups lie inside one filter tap (Cin a multiple
 // of 64); 2 (ROWS) convolution with few channels where one filter row is exactly one 32-code run
 // (kw * Cin = 32, e.g. 8 taps of 4 channels: the first layer of an image network with its weights

@@ -1,0 +1,237 @@
+// Weight-stationary DyBit matrix product for gfx950, for layers whose whole weight matrix fits the
+// LDS of a compute unit once decoded (N rows of K halves plus padding <= 160 KiB; N <= 128): the 1 x 1
+// and the early 3 x 3 convolutions of a network, where M (output pixels) is huge and N * K is small.
+//
+// The tiled kernels decode the weight tile of every K step again in every workgroup, and with a
+// small K that work, the barriers around it and the half-empty 128-column tile of an N = 64 layer
+// outweigh the matrix instructions.  Here a workgroup of eight waves decodes all of W into LDS once
+// and then walks over 256-row slabs of A for as long as there are any (a persistent grid of at most
+// two workgroups per compute unit).  After the initial barrier the waves never synchronise again:
+// wave w owns rows 32 w .. 32 w + 31 of the slab and all N columns (N / 32 accumulator blocks), its
+// lanes fetch and decode their own 32 codes of A per K step (two K steps ahead, as in the tiled
+// kernels) and read W fragments from the resident tile.  Per K step a wave issues 4 * N / 32 MFMAs
+// and decodes 32 codes per lane; nothing is decoded for columns that do not exist.
+//
+// Operand decoders, k order, out-of-range conventions and the epilogue are those of the tiled
+// kernels (dybit_codec.h, tile_epilogue.h).  K must be a multiple of 64 (convolution: Cin).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include <type_traits>
+
+#include "dybit_codec.h"
+#include "gemm_args.h"
+#include "tile_epilogue.h"
+
+#ifndef DYBIT_WS_W
+#error "compile with -DDYBIT_WS_W=<weight format id> (0: 4-bit, 2: 8-bit, 4: 6-bit, 6: 2-bit; signed)"
+#endif
+
+namespace dybit {
+namespace ws {
+
+using namespace fast;
+
+constexpr int THREADS = 512, SLAB = 256;                           // eight waves, 32 rows each
+
+// CB: 32-column blocks per wave (N <= 32 CB).  With two blocks a wave needs few registers and two
+// workgroups share a compute unit (four waves per SIMD) when their weight tiles both fit its LDS.
+template <int FMT_A, int FMT_W, bool CONV, int CB, bool WB>
+__global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+{
+    using CA = Codec<FMT_A>;
+    using CW = Codec<FMT_W>;
+    constexpr int NA = (CA::BITS + 3) / 4, NW = (CW::BITS + 3) / 4;
+    constexpr int RUN_A = 4 * CA::BITS, RUN_W = 4 * CW::BITS;       // bytes of a run of 32 codes
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kq = lane >> 5;
+    const int ktiles = (int)(g.K / 64);
+
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(g.A), 0, (int)(g.a_bytes > 0x7fffffff ? 0x7fffffff : g.a_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
+
+    // ---- W: every run of 32 codes is decoded once and stays.  Row n of the tile is K halves plus 16
+    // bytes of padding (fragment reads of 32 consecutive rows then fall into different banks); rows
+    // N .. 32 CB - 1 hold zeros (their runs are fetched from the out-of-range offset).
+    {
+        const int runs_per_row = ktiles * 2, w_row_bytes = (int)(g.K * CW::BITS / 8);
+        const int total = CB * 32 * runs_per_row;
+        for (int r = tid; r < total; r += THREADS) {
+            const int row = r / runs_per_row, run = r - row * runs_per_row;
+            u32x4 raw[NW];
+            load_run<CW::BITS>(rsrcW, row < g.N ? (u32)(row * w_row_bytes + run * RUN_W) : kOob, raw);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                u32 d[4];
+                decode_eight<FMT_W>(raw, q, d);
+                *reinterpret_cast<u32x4 *>(lds + row * row_bytes + run * 64 + q * 16) = u32x4{d[0], d[1], d[2], d[3]};
+            }
+        }
+    }
+    __syncthreads();
+
+    const int a_row_bytes = (int)(g.K * CA::BITS / 8);
+    const int pix_bytes = CONV ? g.Cin * CA::BITS / 8 : 0;
+    const u32 rdW = (u32)(lane & 31) * (u32)row_bytes + (u32)kq * 64;   // K step adds 128 B, block kk 16 B, column block j 32 rows
+
+    float run_max = 0.0f;                                            // max |C| over every strip this lane stores
+    for (int slab = blockIdx.x; slab < slabs; slab += gridDim.x) {
+        const int64_t m_strip = (int64_t)slab * SLAB + wave * 32;
+        if (m_strip >= g.M) continue;                                // uniform per wave; no barriers below
+        // ---- A: the lane's own row, the 32 codes kq of every K step
+        u32 offA;
+        int hi0 = 0, wi0 = 0;
+        bool okA;
+        {
+            const int64_t m = m_strip + (lane & 31);
+            okA = m < g.M;
+            if (CONV) {
+                const int64_t mm = okA ? m : 0;
+                const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
+                const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
+                const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+                hi0 = ho * g.stride - g.pad;
+                wi0 = wo * g.stride - g.pad;
+                offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);
+            } else {
+                offA = okA ? (u32)(m * a_row_bytes + kq * RUN_A) : kOob;
+            }
+        }
+        // position of the next K step to load: first k, and for a convolution its filter row, filter
+        // column and first channel (uniform over the wave), counted up from step to step
+        int a_k0 = 0, a_fr = 0, a_fs = 0, a_c0 = 0;
+        auto load_A = [&](u32x4 *raw) {
+            u32 off;
+            if (CONV) {
+                const bool in = okA && a_k0 < g.K && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
+                off = in ? offA + (u32)((a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * CA::BITS / 8) : kOob;   // padding reads code 0
+            } else {
+                off = a_k0 < g.K ? offA + (u32)(a_k0 * CA::BITS / 8) : kOob;
+            }
+            load_run<CA::BITS>(rsrcA, off, raw);
+            a_k0 += 64;
+            if (CONV) {
+                a_c0 += 64;
+                if (a_c0 >= g.Cin) {
+                    a_c0 = 0;
+                    if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
+                }
+            }
+        };
+        auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
+            u32 d[4];
+            decode_eight<FMT_A>(raw, q, d);
+            return __builtin_bit_cast(f16x8, u32x4{d[0], d[1], d[2], d[3]});
+        };
+
+        f32x16 acc[CB];
+#pragma unroll
+        for (int j = 0; j < CB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+
+        u32x4 rawA[2][NA];
+        load_A(rawA[0]);
+        load_A(rawA[1]);
+        f16x8 fa = decode_A(rawA[0], 0);
+
+        // One K step: four k blocks of CB MFMAs; the A fragment of the next block is decoded while
+        // this block's MFMAs run, the codes of K step kt + 2 are requested once step kt's are decoded.
+        auto step = [&](int kt, auto stage_tag) {
+            constexpr int s = decltype(stage_tag)::value;
+            const char *wk = lds + rdW + kt * 128;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const f16x8 fa_cur = fa;
+                f16x8 fw[CB];
+#pragma unroll
+                for (int j = 0; j < CB; ++j) fw[j] = *reinterpret_cast<const f16x8 *>(wk + kk * 16 + j * 32 * row_bytes);
+                fa = kk < 3 ? decode_A(rawA[s], kk + 1) : decode_A(rawA[s ^ 1], 0);
+#pragma unroll
+                for (int j = 0; j < CB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa_cur, fw[j], acc[j], 0, 0, 0);
+                if (kk == 3) load_A(rawA[s]);
+            }
+        };
+        for (int kt = 0; kt < ktiles; kt += 2) {
+            step(kt, std::integral_constant<int, 0>{});
+            if (kt + 1 < ktiles) step(kt + 1, std::integral_constant<int, 1>{});
+        }
+        run_max = fmaxf(run_max, epilogue_strip<CB, WB, false>(g, acc, m_strip, 0));
+    }
+
+    // ---- running maximum: one merge per workgroup.  The persistent waves finish their strips in step,
+    // so a merge per strip would send thousands of waves to the same word at the same moment.
+    if (g.absmax_bits) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) run_max = fmaxf(run_max, __shfl_xor(run_max, off, 64));
+        __syncthreads();                                            // every wave is done with the weight tile
+        float *red = reinterpret_cast<float *>(lds);
+        if (lane == 0) red[wave] = run_max;
+        __syncthreads();
+        if (tid == 0) {
+            float m = red[0];
+#pragma unroll
+            for (int w = 1; w < THREADS / 64; ++w) m = fmaxf(m, red[w]);
+            const uint32_t bits = __float_as_uint(m);
+            if (bits > __hip_atomic_load(g.absmax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(g.absmax_bits, bits);
+        }
+    }
+}
+
+template <int FA, int FW, bool CONV, int CB>
+static void launch_cb(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
+{
+    const int slabs = (int)((g.M + SLAB - 1) / SLAB);
+    const int per_cu = (lds_bytes <= 80 * 1024 && CB == 2) ? 2 : 1;  // workgroups that fit a compute unit (LDS, registers)
+    const int grid = slabs < 256 * per_cu ? slabs : 256 * per_cu;
+    auto k = gemm_ws_kernel<FA, FW, CONV, CB, kWriteBack>;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(THREADS), lds_bytes, st, g, slabs, row_bytes);
+}
+
+template <int FA, int FW>
+static bool launch(const GemmArgs &g, bool conv, hipStream_t st)
+{
+    // Up to 128 columns: with more, a wave's accumulators leave no registers for the epilogue and the
+    // 128 x 128 kernel is as fast or faster (measured).
+    const int cb = g.N <= 64 ? 2 : 4;
+    const int row_bytes = (int)g.K * 2 + 16;
+    const int lds_bytes = cb * 32 * row_bytes;
+    if (g.N > 128 || lds_bytes > 160 * 1024) return false;
+#define DYBIT_WS_CB(C_) \
+    if (conv) launch_cb<FA, FW, true, C_>(g, st, row_bytes, lds_bytes); else launch_cb<FA, FW, false, C_>(g, st, row_bytes, lds_bytes)
+    if (cb == 2) { DYBIT_WS_CB(2); }
+    else { DYBIT_WS_CB(4); }
+#undef DYBIT_WS_CB
+    return true;
+}
+
+}  // namespace ws
+
+// One translation unit per weight format (compile time); the entry point's name carries it.
+// Returns false when the weight matrix does not fit the LDS of a compute unit.
+#define DYBIT_WS_NAME2(w) DYBIT_WB_NAME(launch_gemm_ws_w##w)
+#define DYBIT_WS_NAME(w) DYBIT_WS_NAME2(w)
+bool DYBIT_WS_NAME(DYBIT_WS_W)(const GemmArgs &g, int a_bits, bool conv, hipStream_t st)
+{
+    using namespace fast;
+    const int fa = (a_bits == 8 ? F8S : a_bits == 6 ? F6S : a_bits == 2 ? F2S : F4S) + (g.a_signed ? 0 : 1);
+    switch (fa) {
+        case F2S: return ws::launch<F2S, DYBIT_WS_W>(g, conv, st);
+        case F2U: return ws::launch<F2U, DYBIT_WS_W>(g, conv, st);
+        case F4S: return ws::launch<F4S, DYBIT_WS_W>(g, conv, st);
+        case F4U: return ws::launch<F4U, DYBIT_WS_W>(g, conv, st);
+        case F6S: return ws::launch<F6S, DYBIT_WS_W>(g, conv, st);
+        case F6U: return ws::launch<F6U, DYBIT_WS_W>(g, conv, st);
+        case F8S: return ws::launch<F8S, DYBIT_WS_W>(g, conv, st);
+        case F8U: return ws::launch<F8U, DYBIT_WS_W>(g, conv, st);
+        default: return false;
+    }
+}
+
+}  // namespace dybit

@@ -196,8 +196,11 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
 
 // WB: the kernel is the write-back build (codes are written, see requant.h); kernels are compiled
 // in both forms so that the plain form carries none of the encoder's registers or branches.
-template <int CB, bool WB>
-__device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB],
+// FOLD: merge the strip's maximum into the running maximum here (one read, at most one atomic per
+// wave); a kernel whose waves store many strips passes false, keeps the returned per-lane maximum
+// and merges once at its end.
+template <int CB, bool WB, bool FOLD = true>
+__device__ __forceinline__ float epilogue_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB],
                                                const int64_t m_strip, const int64_t n0)
 {
     const int lane = threadIdx.x & 63, kq = lane >> 5;
@@ -237,7 +240,8 @@ __device__ __forceinline__ void epilogue_strip(const GemmArgs &g, const fast::f3
             }
         }
     }
-    if (g.absmax_bits) fold_absmax(g.absmax_bits, mx);
+    if (FOLD && g.absmax_bits) fold_absmax(g.absmax_bits, mx);
+    return mx;
 }
 
 }  // namespace dybit

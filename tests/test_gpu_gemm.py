@@ -352,6 +352,45 @@ def test_mid_kernel_wide_channels_conv(force_kernel):
     assert_within(got, want, den)
 
 
+WS_PAIRS = [((4, False), (4, True)), ((8, True), (4, True)), ((8, False), (8, True)), ((6, False), (6, True)),
+            ((6, True), (4, True)), ((4, True), (8, True)), ((2, False), (2, True)), ((8, True), (6, True)),
+            ((2, True), (8, True)), ((4, False), (2, True))]
+
+
+@pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
+@pytest.mark.parametrize("a_fmt,w_fmt", WS_PAIRS)
+@pytest.mark.parametrize("shape", [(1000, 64, 64), (300, 70, 192), (2049, 128, 576), (257, 100, 128), (5, 128, 256),
+                                   (70000, 33, 64)])
+def test_weight_stationary_kernel(force_kernel, a_fmt, w_fmt, shape):
+    """The whole weight matrix decoded into LDS once, a persistent grid walking over the rows: N not a
+    multiple of 32, ragged M, one to nine K steps, more slabs than workgroups (70000 rows), both
+    column-block counts (N <= 64, <= 128); bias + ReLU and a leading dimension larger than N."""
+    M, N, K = shape
+    rng = np.random.default_rng(M + 7 * N + K)
+    qa = random_codes(rng, (M, K), a_fmt)
+    qw = random_codes(rng, (N, K), w_fmt)
+    bias = rng.normal(0, 3, N).astype(np.float32)
+    got = run_gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, True, ldc=N + 8)
+    want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, True)
+    assert_within(got[:, :N], want, den)
+    assert np.all(got[:, N:] == -777.0)
+
+
+@pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
+@pytest.mark.parametrize("x_fmt,w_fmt", WS_PAIRS[:6])
+@pytest.mark.parametrize("geom", [(3, 1, 1), (1, 1, 0), (3, 2, 1), (1, 2, 0)])
+def test_weight_stationary_kernel_conv(force_kernel, x_fmt, w_fmt, geom):
+    k, stride, pad = geom
+    rng = np.random.default_rng(k * 11 + stride)
+    Bn, H, W, Cin, Cout = 3, 13, 11, 64, 96
+    qx = random_codes(rng, (Bn, H, W, Cin), x_fmt)
+    qw = random_codes(rng, (Cout, k, k, Cin), w_fmt)
+    bias = rng.normal(0, 1, Cout).astype(np.float32)
+    got = run_conv(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, False)
+    want, den = R.conv2d(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, False)
+    assert_within(got, want, den)
+
+
 @pytest.mark.parametrize("force_kernel", ["general"], indirect=True)
 @pytest.mark.parametrize("a_fmt,w_fmt", [((4, False), (4, True)), ((8, True), (4, True)), ((8, False), (8, True))])
 def test_general_kernel_on_tiled_shapes(force_kernel, a_fmt, w_fmt):

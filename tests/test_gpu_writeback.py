@@ -101,6 +101,29 @@ def test_conv2d_wb(force_kernel, y_fmt):
     check_codes(codes, y32.reshape(-1, Cout), y_scale, y_fmt)
 
 
+@pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
+@pytest.mark.parametrize("c_fmt", OUT_FMTS)
+def test_gemm_wb_weight_stationary(force_kernel, c_fmt):
+    rng = np.random.default_rng(47 + c_fmt[0])
+    a_fmt, w_fmt = (8, False), (4, True)
+    M, N, K = 777, 96, 128
+    qa = random_codes(rng, (M, K), a_fmt)
+    qw = random_codes(rng, (N, K), w_fmt)
+    bias = rng.normal(0, 3, N).astype(np.float32)
+    res = rng.normal(0, 30, (M, N)).astype(np.float32)
+    relu = not c_fmt[1]
+    want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, relu, res)
+    c_scale = np.float32(0.8 * np.abs(want).max() / R.vmax(*c_fmt))
+    mx = torch.zeros(1, dtype=torch.float32, device="cuda")
+    c, codes = B.dybit_gemm_wb(M, N, K, pack_rows_dev(qa, 8), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt, scalar(0.011),
+                               c_fmt, scalar(c_scale), dev(bias), dev(res), relu, mx)
+    torch.cuda.synchronize()
+    c32 = c.cpu().numpy()
+    assert_within(c32, want, den)
+    check_codes(codes, c32, c_scale, c_fmt)
+    assert mx.item() == np.abs(c32).max()
+
+
 def test_wb_codes_feed_the_next_product():
     """The packed codes are laid out as the activation operand of a following dybit_gemm."""
     rng = np.random.default_rng(41)
