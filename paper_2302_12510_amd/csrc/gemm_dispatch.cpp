@@ -47,7 +47,7 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
     const bool ws_forced = force && !strcmp(force, "ws");
     const char *ws_env = getenv("DYBIT_GEMM_WS");                  // DYBIT_GEMM_WS=0 keeps it out of the automatic choice
     const bool ws_off = ws_env && !strcmp(ws_env, "0");
-    if (!rows && (ws_forced || (!force && !ws_off && g.N <= 128 && g.M >= 16384))) {
+    if (ws_forced || (!force && !ws_off && g.N <= 128 && g.M >= 16384)) {
         const bool wb_ = g.q_out != nullptr;
         bool done = false;
         switch (w_bits) {

@@ -35,14 +35,21 @@ using namespace fast;
 
 constexpr int THREADS = 512, SLAB = 256;                           // eight waves, 32 rows each
 
+// CONV: 0 matrix product; 1 convolution whose 64-code k groups lie inside one filter tap (Cin a
+// multiple of 64); 2 (ROWS) convolution with few channels where one filter row is exactly one 32-code
+// run (kw * Cin = 32): the run of lane-half kq in K step t is filter row 2 t + kq of the lane's output
+// pixel, fetched as aligned words and shifted / masked when it is decoded (as in the 128 x 128 kernel).
 // CB: 32-column blocks per wave (N <= 32 CB).  With two blocks a wave needs few registers and two
 // workgroups share a compute unit (four waves per SIMD) when their weight tiles both fit its LDS.
-template <int FMT_A, int FMT_W, bool CONV, int CB, bool WB>
+constexpr int ROWS = 2;
+
+template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
 __global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
-    constexpr int NA = (CA::BITS + 3) / 4, NW = (CW::BITS + 3) / 4;
+    constexpr int WORDS_A = CA::BITS;                               // 32-bit words in a run of 32 codes
+    constexpr int NA = CONV == ROWS ? (WORDS_A + 1 + 3) / 4 : (CA::BITS + 3) / 4, NW = (CW::BITS + 3) / 4;
     constexpr int RUN_A = 4 * CA::BITS, RUN_W = 4 * CW::BITS;       // bytes of a run of 32 codes
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -50,8 +57,10 @@ __global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const
     const int kq = lane >> 5;
     const int ktiles = (int)(g.K / 64);
 
+    // ROWS reads aligned words: the descriptor then ends on a word boundary
+    const int64_t a_span = CONV == ROWS ? ((g.a_bytes + 3) & ~(int64_t)3) : g.a_bytes;
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.A), 0, (int)(g.a_bytes > 0x7fffffff ? 0x7fffffff : g.a_bytes), 0x00020000);
+        const_cast<uint8_t *>(g.A), 0, (int)(a_span > 0x7fffffff ? 0x7fffffff : a_span), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
 
@@ -87,6 +96,7 @@ __global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const
         u32 offA;
         int hi0 = 0, wi0 = 0;
         bool okA;
+        u32 row_keep[CONV == ROWS ? WORDS_A : 1];                    // ROWS: bits of a run that belong to taps inside the image
         {
             const int64_t m = m_strip + (lane & 31);
             okA = m < g.M;
@@ -97,7 +107,18 @@ __global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const
                 const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
                 hi0 = ho * g.stride - g.pad;
                 wi0 = wo * g.stride - g.pad;
-                offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);
+                if (CONV == ROWS) {
+                    offA = (u32)(int)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes);   // first byte of filter row 0 (may be negative)
+                    const int taps = 32 / g.Cin, tap_bits = g.Cin * CA::BITS;
+                    const int t_lo = max(0, -wi0), t_hi = max(min(taps, g.Wd - wi0), t_lo);
+#pragma unroll
+                    for (int i = 0; i < WORDS_A; ++i) {
+                        const int lo = min(max(t_lo * tap_bits - 32 * i, 0), 32), up = min(max(t_hi * tap_bits - 32 * i, 0), 32);
+                        row_keep[i] = (u32)((1ull << up) - 1ull) & ~(u32)((1ull << lo) - 1ull);
+                    }
+                } else {
+                    offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);
+                }
             } else {
                 offA = okA ? (u32)(m * a_row_bytes + kq * RUN_A) : kOob;
             }
@@ -106,6 +127,26 @@ __global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const
         // column and first channel (uniform over the wave), counted up from step to step
         int a_k0 = 0, a_fr = 0, a_fs = 0, a_c0 = 0;
         auto load_A = [&](u32x4 *raw) {
+            if constexpr (CONV == ROWS) {
+                const int fr = (a_k0 >> 5) + kq;
+                const int hi = hi0 + fr;
+                const bool in = okA && a_k0 < g.K && (unsigned)hi < (unsigned)g.H;
+                const int byte_off = (int)offA + fr * g.Wd * pix_bytes;
+                const int shift = byte_off & 3, base = byte_off - shift;
+                u32 w[NA * 4];
+#pragma unroll
+                for (int j = 0; j < NA * 4; ++j) w[j] = 0;
+#pragma unroll
+                for (int j = 0; j <= WORDS_A; ++j) {
+                    const int o = base + 4 * j;                  // a word before the tensor is "outside" explicitly
+                    w[j] = __builtin_amdgcn_raw_buffer_load_b32(rsrcA, (in && o >= 0) ? (u32)o : kOob, 0, 0);
+                }
+                w[NA * 4 - 1] = (u32)shift;                      // travels with the words to the decoder
+#pragma unroll
+                for (int p = 0; p < NA; ++p) raw[p] = u32x4{w[4 * p], w[4 * p + 1], w[4 * p + 2], w[4 * p + 3]};
+                a_k0 += 64;
+                return;
+            }
             u32 off;
             if (CONV) {
                 const bool in = okA && a_k0 < g.K && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
@@ -115,7 +156,7 @@ __global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const
             }
             load_run<CA::BITS>(rsrcA, off, raw);
             a_k0 += 64;
-            if (CONV) {
+            if (CONV == 1) {
                 a_c0 += 64;
                 if (a_c0 >= g.Cin) {
                     a_c0 = 0;
@@ -125,7 +166,16 @@ __global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const
         };
         auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
             u32 d[4];
-            decode_eight<FMT_A>(raw, q, d);
+            if constexpr (CONV == ROWS) {
+                const u32 shift = raw[NA - 1].w;
+                u32x4 t[2] = {u32x4{0u, 0u, 0u, 0u}, u32x4{0u, 0u, 0u, 0u}};
+#pragma unroll
+                for (int i = 0; i < WORDS_A; ++i)
+                    t[i >> 2][i & 3] = __builtin_amdgcn_alignbyte(raw[(i + 1) >> 2][(i + 1) & 3], raw[i >> 2][i & 3], shift) & row_keep[i];
+                decode_eight<FMT_A>(t, q, d);
+            } else {
+                decode_eight<FMT_A>(raw, q, d);
+            }
             return __builtin_bit_cast(f16x8, u32x4{d[0], d[1], d[2], d[3]});
         };
 
@@ -183,7 +233,7 @@ __global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const
     }
 }
 
-template <int FA, int FW, bool CONV, int CB>
+template <int FA, int FW, int CONV, int CB>
 static void launch_cb(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
 {
     const int slabs = (int)((g.M + SLAB - 1) / SLAB);
@@ -203,8 +253,11 @@ static bool launch(const GemmArgs &g, bool conv, hipStream_t st)
     const int row_bytes = (int)g.K * 2 + 16;
     const int lds_bytes = cb * 32 * row_bytes;
     if (g.N > 128 || lds_bytes > 160 * 1024) return false;
+    const bool rows = conv && g.Cin < 64;                            // kw * Cin = 32 (checked by the dispatcher)
 #define DYBIT_WS_CB(C_) \
-    if (conv) launch_cb<FA, FW, true, C_>(g, st, row_bytes, lds_bytes); else launch_cb<FA, FW, false, C_>(g, st, row_bytes, lds_bytes)
+    if (rows) launch_cb<FA, FW, ROWS, C_>(g, st, row_bytes, lds_bytes); \
+    else if (conv) launch_cb<FA, FW, 1, C_>(g, st, row_bytes, lds_bytes); \
+    else launch_cb<FA, FW, 0, C_>(g, st, row_bytes, lds_bytes)
     if (cb == 2) { DYBIT_WS_CB(2); }
     else { DYBIT_WS_CB(4); }
 #undef DYBIT_WS_CB

@@ -391,6 +391,24 @@ def test_weight_stationary_kernel_conv(force_kernel, x_fmt, w_fmt, geom):
     assert_within(got, want, den)
 
 
+@pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
+@pytest.mark.parametrize("x_fmt,w_fmt,Cin,kw", [((8, True), (8, True), 4, 8), ((6, True), (4, True), 4, 8), ((4, False), (6, True), 8, 4),
+                                                 ((2, True), (8, True), 4, 8), ((8, False), (4, True), 2, 16)])
+@pytest.mark.parametrize("kh,stride,pad,shape", [(8, 2, 3, (3, 23, 21)), (2, 3, 4, (2, 12, 16)), (4, 1, 2, (2, 9, 27)), (6, 2, 5, (1, 30, 17))])
+def test_weight_stationary_kernel_few_channels(force_kernel, x_fmt, w_fmt, Cin, kw, kh, stride, pad, shape):
+    """Filter rows of exactly 32 codes fetched row by row (see test_conv_few_channels), weights resident."""
+    Bn, H, W = shape
+    rng = np.random.default_rng(Cin * 100 + kw * 10 + kh + 1)
+    Cout = 100
+    qx = random_codes(rng, (Bn, H, W, Cin), x_fmt)
+    qw = random_codes(rng, (Cout, kh, kw, Cin), w_fmt)
+    bias = rng.normal(0, 1, Cout).astype(np.float32)
+    got = run_conv(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, False)
+    want, den = R.conv2d(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, False)
+    assert got.shape == want.shape
+    assert_within(got, want, den)
+
+
 @pytest.mark.parametrize("force_kernel", ["general"], indirect=True)
 @pytest.mark.parametrize("a_fmt,w_fmt", [((4, False), (4, True)), ((8, True), (4, True)), ((8, False), (8, True))])
 def test_general_kernel_on_tiled_shapes(force_kernel, a_fmt, w_fmt):
