@@ -80,6 +80,14 @@ dybit_status dybit_absmax_scale(const float *x, size_t n, dybit_fmt f, float *sc
 dybit_status dybit_quantize(const float *x, size_t n, dybit_fmt f, const float *scale,
                             uint8_t *codes_out, dybit_stream stream);
 
+/* dybit_scale_from_absmax and dybit_quantize in one launch, for a tensor whose maximum is already known
+ * (a running maximum from the epilogue that produced it): scale = *absmax / 2^(m-1) (1.0 for a maximum of
+ * 0), *scale_out = scale for the kernels that follow, codes as dybit_quantize with that scale.
+ * absmax [device]: 1 float, >= 0.  scale_out [device]: 1 float, a different word (DYBIT_ERR_INVALID_ARG
+ * otherwise).  When n is small enough to leave a remainder kernel, both launches write the same scale. */
+dybit_status dybit_quantize_absmax(const float *x, size_t n, dybit_fmt f, const float *absmax, float *scale_out,
+                                   uint8_t *codes_out, dybit_stream stream);
+
 /* Decoder (Sec. III-B): y_out[j] = (*scale) * value(code j), one float multiply.
  * codes [device]: packed, 16-byte aligned.  y_out [device]: n floats, 16-byte aligned. */
 dybit_status dybit_dequantize(const uint8_t *codes, size_t n, dybit_fmt f, const float *scale,

@@ -47,6 +47,7 @@ def lib() -> C.CDLL:
         L.dybit_absmax_scale.argtypes = [vp, sz, Fmt, vp, vp]
         L.dybit_quantize.argtypes = [vp, sz, Fmt, vp, vp, vp]
         L.dybit_dequantize.argtypes = [vp, sz, Fmt, vp, vp, vp]
+        L.dybit_quantize_absmax.argtypes = [vp, sz, Fmt, vp, vp, vp, vp]
         L.dybit_gemm.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, i64, vp]
         L.dybit_conv2d.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp]
         L.dybit_gemm_ex.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, i64, vp, vp]
@@ -124,6 +125,20 @@ def dybit_quantize(x: torch.Tensor, scale: torch.Tensor, bits: int, signed: bool
     _check(lib().dybit_quantize(_ptr(x), n, fmt(bits, signed), _ptr(scale), _ptr(out), _stream(stream)),
            "dybit_quantize")
     return out
+
+
+def dybit_quantize_absmax(x: torch.Tensor, absmax: torch.Tensor, bits: int, signed: bool,
+                          out: torch.Tensor | None = None, scale_out: torch.Tensor | None = None, stream=None):
+    """Scale from a known max|x| (device scalar) and packed codes in one launch; returns (scale, codes)."""
+    assert x.dtype == torch.float32 and absmax.dtype == torch.float32
+    n = x.numel()
+    if out is None:
+        out = torch.empty(dybit_packed_bytes(bits, signed, n), dtype=torch.uint8, device=x.device)
+    if scale_out is None:
+        scale_out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(lib().dybit_quantize_absmax(_ptr(x), n, fmt(bits, signed), _ptr(absmax), _ptr(scale_out), _ptr(out),
+                                       _stream(stream)), "dybit_quantize_absmax")
+    return scale_out, out
 
 
 def dybit_dequantize(codes: torch.Tensor, n: int, scale: torch.Tensor, bits: int, signed: bool,

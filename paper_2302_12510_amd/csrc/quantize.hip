@@ -185,10 +185,17 @@ struct ScaleInfo {
     bool ok, all_exact;
 };
 
-__device__ __forceinline__ ScaleInfo load_scale(const float *scale)
+// inv_vmax > 0: *scale holds max|x| instead of the scale; the scale is max|x| * inv_vmax (1.0 for a
+// maximum of 0), exactly what dybit_scale_from_absmax computes, and the first thread of the grid
+// writes it to *scale_out for the kernels that follow.
+__device__ __forceinline__ ScaleInfo load_scale(const float *scale, float inv_vmax = 0.0f, float *scale_out = nullptr)
 {
     ScaleInfo si;
     si.s = *scale;
+    if (inv_vmax > 0.0f) {
+        si.s = (si.s == 0.0f) ? 1.0f : si.s * inv_vmax;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = si.s;
+    }
     const uint32_t e = (__float_as_uint(si.s) >> 23) & 0xffu;
     si.ok = (si.s > 0.0f) && e != 0u && e != 255u;                      // finite, normal, positive
     si.all_exact = e < 27u || e > 227u;                                 // outside [2^-100, 2^100]
@@ -201,11 +208,11 @@ __device__ __forceinline__ ScaleInfo load_scale(const float *scale)
 template <int BITS, bool SIGNED, int UNROLL>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restrict__ x, size_t n4,
                                                             const float *__restrict__ scale,
-                                                            uint8_t *__restrict__ out)
+                                                            uint8_t *__restrict__ out, float inv_vmax, float *scale_out)
 {
     using word_t = typename std::conditional<BITS == 8, uint32_t,
                    typename std::conditional<BITS == 4, uint16_t, uint8_t>::type>::type;
-    const ScaleInfo si = load_scale(scale);
+    const ScaleInfo si = load_scale(scale, inv_vmax, scale_out);
     if (!si.ok) {
         if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
         return;
@@ -250,9 +257,9 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
 template <bool SIGNED, int UNROLL>
 __global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__restrict__ x, size_t n4,
                                                              const float *__restrict__ scale,
-                                                             uint8_t *__restrict__ out)
+                                                             uint8_t *__restrict__ out, float inv_vmax, float *scale_out)
 {
-    const ScaleInfo si = load_scale(scale);
+    const ScaleInfo si = load_scale(scale, inv_vmax, scale_out);
     if (!si.ok) {
         if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
         return;
@@ -296,9 +303,9 @@ __global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__rest
 // Remainder: one thread per group of 4 elements starting at element `first`; exact path, byte stores.
 template <int BITS, bool SIGNED>
 __global__ void quantize_tail_kernel(const float *__restrict__ x, size_t first, size_t n,
-                                     const float *__restrict__ scale, uint8_t *__restrict__ out)
+                                     const float *__restrict__ scale, uint8_t *__restrict__ out, float inv_vmax, float *scale_out)
 {
-    const ScaleInfo si = load_scale(scale);
+    const ScaleInfo si = load_scale(scale, inv_vmax, scale_out);
     if (!si.ok) {
         if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
         return;
@@ -366,25 +373,27 @@ static int grid_for(size_t work_items, int per_block, int max_blocks)
 }
 
 template <int BITS, bool SIGNED>
-static void launch_quantize(const float *x, size_t n, const float *scale, uint8_t *out, hipStream_t st)
+static void launch_quantize(const float *x, size_t n, const float *scale, uint8_t *out, hipStream_t st,
+                            float inv_vmax = 0.0f, float *scale_out = nullptr)
 {
     constexpr int UNROLL = DYBIT_QUANT_UNROLL;
     if (BITS == 6) {
         const size_t n16 = n / 16;
         if (n16) hipLaunchKernelGGL((quantize6_kernel<SIGNED, UNROLL>),
                                     dim3(grid_for(4 * n16, kThreads * UNROLL, 256 * DYBIT_QUANT_BLOCKS_PER_CU)), dim3(kThreads), 0, st,
-                                    x, 4 * n16, scale, out);
+                                    x, 4 * n16, scale, out, inv_vmax, scale_out);
         const size_t first = n16 * 16;
         if (first < n) {
             const size_t groups = (n - first + 3) / 4;
-            hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3((unsigned)groups), dim3(1), 0, st, x, first, n, scale, out);
+            hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3((unsigned)groups), dim3(1), 0, st, x, first, n, scale, out,
+                               inv_vmax, scale_out);
         }
     } else {
         const size_t n4 = n / 4;
         if (n4) hipLaunchKernelGGL((quantize_kernel<BITS == 6 ? 8 : BITS, SIGNED, UNROLL>),
-                                   dim3(grid_for(n4, kThreads * UNROLL, 256 * DYBIT_QUANT_BLOCKS_PER_CU)), dim3(kThreads), 0, st, x, n4, scale, out);
+                                   dim3(grid_for(n4, kThreads * UNROLL, 256 * DYBIT_QUANT_BLOCKS_PER_CU)), dim3(kThreads), 0, st, x, n4, scale, out, inv_vmax, scale_out);
         if (n4 * 4 < n)
-            hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3(1), dim3(1), 0, st, x, n4 * 4, n, scale, out);
+            hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3(1), dim3(1), 0, st, x, n4 * 4, n, scale, out, inv_vmax, scale_out);
     }
 }
 
@@ -428,6 +437,31 @@ extern "C" dybit_status dybit_quantize(const float *x, size_t n, dybit_fmt f, co
     if (n == 0) return DYBIT_OK;
     hipStream_t hs = (hipStream_t)stream;
 #define DYBIT_Q(B, S) launch_quantize<B, S>(x, n, scale, codes_out, hs)
+    switch (f.bits * 2 + f.is_signed) {
+        case 4: DYBIT_Q(2, false); break;   case 5: DYBIT_Q(2, true); break;
+        case 8: DYBIT_Q(4, false); break;   case 9: DYBIT_Q(4, true); break;
+        case 12: DYBIT_Q(6, false); break;  case 13: DYBIT_Q(6, true); break;
+        case 16: DYBIT_Q(8, false); break;  case 17: DYBIT_Q(8, true); break;
+    }
+#undef DYBIT_Q
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_quantize_absmax(const float *x, size_t n, dybit_fmt f, const float *absmax, float *scale_out,
+                                              uint8_t *codes_out, dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (!absmax || !scale_out || ((!x || !codes_out) && n)) return DYBIT_ERR_NULL;
+    if (absmax == scale_out) return DYBIT_ERR_INVALID_ARG;              // every block reads the maximum; one thread writes the scale
+    if (!aligned16(x) || !aligned16(codes_out)) return DYBIT_ERR_ALIGNMENT;
+    hipStream_t hs = (hipStream_t)stream;
+    const float inv_vmax = 1.0f / (float)(1u << (mag_bits(f.bits, f.is_signed) - 1));
+    if (n == 0) {                                                       // nothing to encode: the scale is still produced
+        hipLaunchKernelGGL(absmax_to_scale_kernel, dim3(1), dim3(1), 0, hs, absmax, scale_out, inv_vmax);
+        return launch_status();
+    }
+#define DYBIT_Q(B, S) launch_quantize<B, S>(x, n, absmax, codes_out, hs, inv_vmax, scale_out)
     switch (f.bits * 2 + f.is_signed) {
         case 4: DYBIT_Q(2, false); break;   case 5: DYBIT_Q(2, true); break;
         case 8: DYBIT_Q(4, false); break;   case 9: DYBIT_Q(4, true); break;

@@ -169,10 +169,10 @@ class DybitNetwork:
                     src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
                 flat = src.reshape(-1)
                 if l["src"] in known_max:                       # zero padding of channels keeps the maximum
-                    sa = B.dybit_scale_from_absmax(known_max[l["src"]], *a_fmt)
+                    sa, qa = B.dybit_quantize_absmax(flat, known_max[l["src"]], *a_fmt)
                 else:
                     sa = B.dybit_absmax_scale(flat, *a_fmt)
-                qa = B.dybit_quantize(flat, sa, *a_fmt)
+                    qa = B.dybit_quantize(flat, sa, *a_fmt)
                 relu = bool(l.get("relu"))
                 k = p["k"]
                 stride, pad = (l["stride"], l["pad"]) if op == "conv" else (1, 0)

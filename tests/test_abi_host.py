@@ -120,6 +120,11 @@ def test_argument_errors_without_gpu():
                              f4, p, null, None) == B.ERR_NULL
     assert L.dybit_conv2d_wb(1, 8, 8, 16, 12, 3, 3, 1, 1, p, f4, p, p, f4, p, null, null, 0, p, null,
                              f4, p, p, None) == B.ERR_ALIGNMENT
+    p2 = C.c_void_p(0x2000)
+    assert L.dybit_quantize_absmax(p, 64, f4, null, p2, p, None) == B.ERR_NULL
+    assert L.dybit_quantize_absmax(p, 64, f4, p, p, p, None) == B.ERR_INVALID_ARG     # maximum and scale in one word
+    assert L.dybit_quantize_absmax(p, 64, bad, p, p2, p, None) == B.ERR_UNSUPPORTED_BITS
+    assert L.dybit_quantize_absmax(C.c_void_p(0x1004), 64, f4, p, p2, p, None) == B.ERR_ALIGNMENT
     assert L.dybit_scale_from_absmax(null, f4, p, None) == B.ERR_NULL
     assert L.dybit_scale_from_absmax(p, bad, p, None) == B.ERR_UNSUPPORTED_BITS
     assert L.dybit_get_last_async_error(None, None) == B.ERR_NULL

@@ -132,3 +132,23 @@ def test_quantize_is_deterministic_and_leaves_guard_bytes():
     B.dybit_quantize(x, s, *fmt, out=buf[:nb])
     assert torch.equal(a, buf)
     assert int((buf[nb:] != 0x5A).sum().item()) == 0
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+@pytest.mark.parametrize("n", [1, 5, 16, 4099, (1 << 18) + 21])
+def test_quantize_with_a_known_maximum(fmt, n):
+    """dybit_quantize_absmax = dybit_scale_from_absmax + dybit_quantize in one launch: scale and codes
+    are those of the oracle for the tensor's own maximum; an all-zero tensor gets scale 1."""
+    rng = np.random.default_rng(n + fmt[0])
+    x = rng.laplace(0, 0.02, n).astype(np.float32)
+    if not fmt[1]:
+        x = np.abs(x)
+    for arr in (x, np.zeros(n, np.float32)):
+        xd = torch.from_numpy(arr).cuda()
+        mx = torch.tensor([float(np.abs(arr).max())], dtype=torch.float32, device="cuda")
+        scale, codes = B.dybit_quantize_absmax(xd, mx, *fmt)
+        torch.cuda.synchronize()
+        s = R.absmax_scale(arr, *fmt)
+        assert scale.item() == s
+        assert np.array_equal(codes.cpu().numpy(), R.pack(R.quantize(arr, s, *fmt), fmt[0]))
+    assert B.dybit_get_last_async_error() == B.OK
