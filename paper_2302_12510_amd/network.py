@@ -145,6 +145,7 @@ class DybitNetwork:
         acts = {"input": x}
         nonneg = {"input": False}
         known_max = {}                       # tensor name -> device scalar holding max|tensor|
+        encoded = {}                         # (tensor name, format, padded channels) -> (scale, codes)
         n_fused = sum(1 for l in self.layers if l["op"] in ("conv", "fc"))
         max_words = torch.zeros(max(n_fused, 1), dtype=torch.float32, device=x.device)
         next_word = 0
@@ -168,11 +169,15 @@ class DybitNetwork:
                 if p["cpad"] != C:
                     src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
                 flat = src.reshape(-1)
-                if l["src"] in known_max:                       # zero padding of channels keeps the maximum
-                    sa, qa = B.dybit_quantize_absmax(flat, known_max[l["src"]], *a_fmt)
+                key = (l["src"], a_fmt, p["cpad"])                  # two consumers of one tensor in one format share its codes
+                if key in encoded:
+                    sa, qa = encoded[key]
+                elif l["src"] in known_max:                     # zero padding of channels keeps the maximum
+                    sa, qa = encoded[key] = B.dybit_quantize_absmax(flat, known_max[l["src"]], *a_fmt)
                 else:
                     sa = B.dybit_absmax_scale(flat, *a_fmt)
                     qa = B.dybit_quantize(flat, sa, *a_fmt)
+                    encoded[key] = (sa, qa)
                 relu = bool(l.get("relu"))
                 k = p["k"]
                 stride, pad = (l["stride"], l["pad"]) if op == "conv" else (1, 0)
