@@ -44,7 +44,7 @@ constexpr int THREADS = 512, SLAB = 256;                           // eight wave
 constexpr int ROWS = 2;
 
 template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
-__global__ __launch_bounds__(THREADS, CB == 2 ? 4 : 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+__global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
@@ -237,7 +237,7 @@ template <int FA, int FW, int CONV, int CB>
 static void launch_cb(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
 {
     const int slabs = (int)((g.M + SLAB - 1) / SLAB);
-    const int per_cu = (lds_bytes <= 80 * 1024 && CB == 2) ? 2 : 1;  // workgroups that fit a compute unit (LDS, registers)
+    const int per_cu = (lds_bytes <= 80 * 1024 && CB == 2 && !kWriteBack) ? 2 : 1;  // workgroups that fit a compute unit (LDS, registers; the write-back epilogue needs the registers of a second one)
     const int grid = slabs < 256 * per_cu ? slabs : 256 * per_cu;
     auto k = gemm_ws_kernel<FA, FW, CONV, CB, kWriteBack>;
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
