@@ -394,3 +394,13 @@ def rmse(x: np.ndarray, xq: np.ndarray) -> float:
     xq = np.asarray(xq, dtype=np.float64).ravel()
     sigma = x.std()
     return float(np.sqrt(np.mean(((x - xq) / sigma) ** 2)))
+
+
+def quantization_rmse(x: np.ndarray, scale, bits: int, signed: bool) -> float:
+    """Eq. 2 for one tensor in one DyBit format: x_hat = s * value(code of x) with the product taken
+    in float64 (the quantized value itself, Sec. III-A, not its float32 rounding), sigma the standard
+    deviation of x (one value for the whole tensor, population form)."""
+    x = np.asarray(x, dtype=np.float32).ravel()
+    codes = quantize(x, scale, bits, signed)
+    x_hat = np.float64(np.float32(scale)) * codebook(bits, signed)[np.asarray(codes, dtype=np.int64)]
+    return rmse(x, x_hat)
