@@ -50,9 +50,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed steps; the device needs a few tens of milliseconds of load to settle its clocks")
-    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1", "cfg3", "cfg4", "modes"],
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1", "cfg3", "cfg4", "modes", "search"],
                     help="cfg5 (default): 8192^3 GEMM + 2^28 quantize; cfg1 / cfg2: the small GEMM and the "
                          "convolution; cfg3 / cfg4: one forward pass of the ResNet-18 / ResNet-50 chains")
+    ap.add_argument("--network", default="resnet18", choices=["resnet18", "resnet50"], help="network of --workload search")
     ap.add_argument("--table", action="store_true",
                     help="run every configuration in a child process each and print a markdown table")
     ap.add_argument("--size", type=int, default=8192, help="M=N=K of the cfg5 GEMM")
@@ -130,6 +131,68 @@ def bench_modes(args):
                       "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
                       "config": {"workload": "mode matrix: GEMM M=N=K=%d on the config 5 tensors, W and A signed" % size},
                       "modes": table}))
+
+
+def bench_search(args):
+    """The layer-wise bitwidth search (Sec. III-C, Alg. 1) on measured latencies: every conv / linear layer
+    of the network is timed on the device in the nine (W, A) modes of {8, 4, 2}^2, the tensor errors (Eq. 2)
+    come from dybit_rmse, dybit_search picks the widths for a few constraints of both strategies, and the
+    network is run with the widths found.  One JSON line."""
+    import torch
+    from paper_2302_12510_amd import binding as B
+    from paper_2302_12510_amd import search, synth
+    from paper_2302_12510_amd.network import DybitNetwork
+
+    torch.cuda.set_device(0)
+    B.lib()
+    layers, batch = (synth.resnet18_layers(), 64) if args.network == "resnet18" else (synth.resnet50_layers(), 128)
+    weights = synth.network_weights(layers, seed=0)
+    x = torch.from_numpy(synth.network_input(batch, 224, seed=0)).cuda()
+    t0 = time.perf_counter()
+    tables = search.measure_tables(layers, weights, x, steps=max(3, args.steps // 5), warmup=3)
+    t_tables = time.perf_counter() - t0
+
+    def run(widths):
+        net = DybitNetwork(layers, weights, widths)
+        for _ in range(args.warmup):
+            net.forward(x)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            net.forward(x)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / args.steps
+
+    names = tables["names"]
+    base_ms = run({n: (8, 8) for n in names})
+    lat = tables["lat"]
+    results = []
+    for strategy, constraint in (("speedup", 1.05), ("speedup", 1.1), ("speedup", 1.15), ("rmse", 1.5), ("rmse", 2.0), ("rmse", 4.0)):
+        t0 = time.perf_counter()
+        widths, ratio, met = search.search_bitwidths(tables, strategy, constraint, 4)
+        t_search = time.perf_counter() - t0
+        idx = {8: 0, 4: 1, 2: 2}
+        predicted = sum(lat[i, idx[widths[n][0]], idx[widths[n][1]]] for i, n in enumerate(names))
+        error = sum(tables["rmse_w"][i, idx[widths[n][0]]] + tables["rmse_a"][i, idx[widths[n][1]]] for i, n in enumerate(names))
+        ms = run(widths)
+        results.append({"strategy": strategy, "constraint": constraint, "k": 4, "met": met, "ratio": round(ratio, 4),
+                        "search_ms": round(t_search * 1e3, 3),
+                        "sum_of_layer_latencies_ms": round(float(predicted), 4), "sum_of_layer_rmse": round(float(error), 4),
+                        "forward_ms": round(ms, 4), "measured_speedup_over_8_8": round(base_ms / ms, 4),
+                        "widths_W_A": {n: list(widths[n]) for n in names}})
+    assert B.dybit_get_last_async_error() == B.OK
+    print(json.dumps({
+        "metric": "layer-wise bitwidth search on measured latencies", "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "data": "synthetic (random weights: the error columns are those of these tensors, not of a trained model)",
+        "config": {"workload": "search: %s, batch %d, 224x224, widths from {8,4,2}, k = 4" % (args.network, batch),
+                   "layers": len(names)},
+        "tables_seconds": round(t_tables, 1),
+        "forward_ms_8_8": round(base_ms, 4),
+        "sum_of_layer_latencies_ms_8_8": round(float(lat[:, 0, 0].sum()), 4),
+        "sum_of_layer_latencies_ms_2_2": round(float(lat[:, 2, 2].sum()), 4),
+        "sum_of_layer_rmse_8_8": round(float(tables["rmse_w"][:, 0].sum() + tables["rmse_a"][:, 0].sum()), 4),
+        "layer_latency_ms": {n: [[round(float(v), 4) for v in row] for row in lat[i]] for i, n in enumerate(names)},
+        "results": results}))
 
 
 def bench_network(args):
@@ -261,6 +324,8 @@ def main():
         return bench_network(args)
     if args.workload == "modes":
         return bench_modes(args)
+    if args.workload == "search":
+        return bench_search(args)
     import torch
     from paper_2302_12510_amd import binding as B
     from paper_2302_12510_amd import synth
@@ -400,6 +465,9 @@ def main():
             del codes
         ams, _ = time_events(lambda: B.dybit_absmax_scale(x, 8, True, out=sa), 10, 2, torch)
         q["absmax"] = {"ms": round(ams, 4), "GBps": round(4.0 * n / (ams * 1e-3) / 1e9, 1)}
+        err = torch.empty(4, dtype=torch.float64, device="cuda")
+        rms, _ = time_events(lambda: B.dybit_rmse(x, s, 8, True, out=err), 10, 2, torch)
+        q["rmse_8bit"] = {"ms": round(rms, 4), "GBps": round(4.0 * n / (rms * 1e-3) / 1e9, 1), "value": round(err[0].item(), 6)}
         y = torch.empty_like(x)
         cms, _ = time_events(lambda: y.copy_(x), 10, 2, torch)
         q["torch_copy_reference"] = {"ms": round(cms, 4), "GBps": round(8.0 * n / (cms * 1e-3) / 1e9, 1)}

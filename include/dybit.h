@@ -187,6 +187,46 @@ dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t Cin, int64
  * for a maximum obtained otherwise.  absmax, scale_out [device]: 1 float each (may be the same word). */
 dybit_status dybit_scale_from_absmax(const float *absmax, dybit_fmt f, float *scale_out, dybit_stream stream);
 
+/* Quantization error of one tensor in one format (Sec. III-C, Eq. 2):
+ *     RMSE = sqrt( mean( ((x - x_hat) / sigma)^2 ) ),   x_hat = s * value(code nearest to x / s),
+ * sigma the standard deviation of x (population form, one value for the tensor).  One pass over x.
+ * x [device]: n floats, 16-byte aligned, n >= 1 (DYBIT_ERR_INVALID_ARG for 0).  scale [device]: 1 float;
+ * a scale that is not positive and finite, or outside [2^-100, 2^100], gives NaN results and sets the
+ * asynchronous error flag (DYBIT_ERR_BAD_SCALE).  out [device]: 4 doubles, 8-byte aligned:
+ *     out[0] = RMSE, out[1] = sum (x - x_hat)^2, out[2] = sum x, out[3] = sum x^2
+ * (the three sums are what devices holding parts of one tensor would add up before the last step).
+ * The differences are formed in float (one rounding each), the sums in double; the order of the
+ * additions across workgroups is not fixed, so the last bits can differ from call to call.  A NaN
+ * or infinity in x gives non-finite results; a constant tensor (sigma = 0) gives inf or NaN. */
+dybit_status dybit_rmse(const float *x, size_t n, dybit_fmt f, const float *scale, double *out, dybit_stream stream);
+
+/* Layer-wise bitwidth search (Sec. III-C, Eq. 3, Eq. 4, Alg. 1).  Host only; all pointers [host].
+ * Widths are chosen from {8, 4, 2} ("levels" 0, 1, 2).
+ *   lat      n_layers * 3 * 3 doubles, lat[(l*3 + w_level)*3 + a_level] > 0: latency of layer l in that mode
+ *            (measured on the device, where the paper asks a simulator of its accelerator).
+ *   rmse_w   n_layers * 3 doubles >= 0: error (Eq. 2) of layer l's weight tensor at each level.
+ *   rmse_a   the same for the layer's input activation tensor.  A layer's error is the sum of the two.
+ *   strategy DYBIT_SEARCH_SPEEDUP: least error subject to  total latency at (8,8) / total latency >= constraint
+ *            (Eq. 3); DYBIT_SEARCH_RMSE: least latency subject to  total error / total error at (8,8) <=
+ *            constraint (Eq. 4).
+ *   k        how many layers one round considers (>= 1).
+ * Each round takes the layers that can still be lowered, ranks them by the constrained quantity under the
+ * current assignment (speedup: slowest first; error: least error first), keeps the first k, re-ranks
+ * those by the other quantity (least error first / slowest first; ties to the lower index throughout),
+ * and lowers first the weights, then the activations of the listed layers by one level each, checking
+ * the ratio after every single step.  Speedup strategy: stops as soon as the ratio reaches the
+ * constraint, or when every layer is at 2/2 bits (*met_out = 0).  Error strategy: the constraint is a
+ * budget; the first step that exceeds it is taken back and ends the search.
+ *   w_bits_out, a_bits_out   n_layers ints each: 8, 4 or 2.  ratio_out, met_out [may be NULL]: the final
+ *            ratio and whether it satisfies the constraint.
+ * DYBIT_ERR_INVALID_ARG: n_layers < 1, k < 1, unknown strategy, NaN constraint, a latency that is not
+ * positive and finite, an error that is negative or not finite, or a zero (8,8) total. */
+#define DYBIT_SEARCH_SPEEDUP 0
+#define DYBIT_SEARCH_RMSE 1
+dybit_status dybit_search(int32_t n_layers, const double *lat, const double *rmse_w, const double *rmse_a,
+                          int32_t strategy, double constraint, int32_t k,
+                          int32_t *w_bits_out, int32_t *a_bits_out, double *ratio_out, int32_t *met_out);
+
 /* Waits for `stream`, then reports and clears the asynchronous error flag of the current
  * device: *flag_out [host] is DYBIT_OK or DYBIT_ERR_BAD_SCALE (a dybit_quantize kernel since the
  * last call, or a write-back epilogue, found an unusable scale and wrote no codes). */

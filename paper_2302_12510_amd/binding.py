@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
         L.dybit_gemm_wb.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, i64, vp, Fmt, vp, vp, vp]
         L.dybit_conv2d_wb.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, Fmt, vp, vp, vp]
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
+        L.dybit_rmse.argtypes = [vp, sz, Fmt, vp, vp, vp]
+        L.dybit_search.argtypes = [i32, vp, vp, vp, i32, C.c_double, i32, vp, vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
         L.dybit_diag_mfma_f16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
         L.dybit_diag_mfma_f8.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
@@ -105,7 +107,39 @@ def dybit_packed_bytes(bits: int, signed: bool, n: int) -> int:
     return int(lib().dybit_packed_bytes(fmt(bits, signed), n))
 
 
+SEARCH_SPEEDUP, SEARCH_RMSE = 0, 1
+
+
+def dybit_search(lat, rmse_w, rmse_a, strategy: int, constraint: float, k: int):
+    """lat: [layers][3][3], rmse_w / rmse_a: [layers][3] (levels 8, 4, 2 bits).
+    Returns (w_bits, a_bits, ratio, met)."""
+    import numpy as np
+    lat = np.ascontiguousarray(lat, dtype=np.float64)
+    rmse_w = np.ascontiguousarray(rmse_w, dtype=np.float64)
+    rmse_a = np.ascontiguousarray(rmse_a, dtype=np.float64)
+    n = lat.shape[0] if lat.ndim == 3 else 0
+    if lat.shape != (n, 3, 3) or rmse_w.shape != (n, 3) or rmse_a.shape != (n, 3):
+        raise ValueError("expected tables of shape [layers][3][3] and [layers][3]")
+    w = np.zeros(max(n, 1), dtype=np.int32)
+    a = np.zeros(max(n, 1), dtype=np.int32)
+    ratio, met = C.c_double(0.0), C.c_int32(0)
+    vp = lambda arr: arr.ctypes.data_as(C.c_void_p)
+    _check(lib().dybit_search(n, vp(lat), vp(rmse_w), vp(rmse_a), int(strategy), float(constraint), int(k),
+                              vp(w), vp(a), C.byref(ratio), C.byref(met)), "dybit_search")
+    return w[:n].tolist(), a[:n].tolist(), ratio.value, bool(met.value)
+
+
 # ---- device -----------------------------------------------------------------
+def dybit_rmse(x: torch.Tensor, scale: torch.Tensor, bits: int, signed: bool, out: torch.Tensor | None = None, stream=None):
+    """Device tensor of 4 doubles: RMSE (Eq. 2), sum (x - x_hat)^2, sum x, sum x^2."""
+    assert x.dtype == torch.float32 and scale.dtype == torch.float32
+    if out is None:
+        out = torch.empty(4, dtype=torch.float64, device=x.device)
+    assert out.dtype == torch.float64 and out.numel() >= 4
+    _check(lib().dybit_rmse(_ptr(x), x.numel(), fmt(bits, signed), _ptr(scale), _ptr(out), _stream(stream)), "dybit_rmse")
+    return out
+
+
 def dybit_absmax_scale(x: torch.Tensor, bits: int, signed: bool, out: torch.Tensor | None = None, stream=None):
     assert x.dtype == torch.float32
     if out is None:

@@ -12,6 +12,8 @@ LIB = os.path.join(HERE, "libdybit.so")
 SOURCES = [
     ("host.cpp", "host", []),
     ("quantize.hip", "quantize", []),
+    ("metric.hip", "metric", []),
+    ("search.cpp", "search", []),
     ("gemm.hip", "gemm", []),
     ("gemm_dispatch.cpp", "gemm_dispatch", []),
     ("gemm_fast.hip", "gemm_fast_w4", ["-DDYBIT_FAST_W=0"]),

@@ -128,3 +128,71 @@ def test_argument_errors_without_gpu():
     assert L.dybit_scale_from_absmax(null, f4, p, None) == B.ERR_NULL
     assert L.dybit_scale_from_absmax(p, bad, p, None) == B.ERR_UNSUPPORTED_BITS
     assert L.dybit_get_last_async_error(None, None) == B.ERR_NULL
+
+
+def test_rmse_argument_errors_without_gpu():
+    L = B.lib()
+    f4, bad = B.fmt(4, True), B.fmt(3, False)
+    p, null = C.c_void_p(0x1000), C.c_void_p(0)
+    assert L.dybit_rmse(p, 64, bad, p, p, None) == B.ERR_UNSUPPORTED_BITS
+    assert L.dybit_rmse(null, 64, f4, p, p, None) == B.ERR_NULL
+    assert L.dybit_rmse(p, 64, f4, null, p, None) == B.ERR_NULL
+    assert L.dybit_rmse(p, 64, f4, p, null, None) == B.ERR_NULL
+    assert L.dybit_rmse(p, 0, f4, p, p, None) == B.ERR_INVALID_ARG
+    assert L.dybit_rmse(C.c_void_p(0x1004), 64, f4, p, p, None) == B.ERR_ALIGNMENT
+    assert L.dybit_rmse(p, 64, f4, p, C.c_void_p(0x1004), None) == B.ERR_ALIGNMENT
+
+
+# ---- the search is host code: checked in full against the oracle here ---------------------------------
+from oracle import search_ref as S  # noqa: E402
+from test_oracle_search import LAT, ERR, random_tables  # noqa: E402
+
+STRATEGY = {"speedup": B.SEARCH_SPEEDUP, "rmse": B.SEARCH_RMSE}
+
+
+def test_search_hand_traces():
+    """The runs traced by hand in the oracle's tests (Alg. 1)."""
+    assert B.dybit_search(LAT, ERR, ERR, B.SEARCH_SPEEDUP, 2.0, 2)[:2] == ([4, 4, 8], [8, 4, 8])
+    assert B.dybit_search(LAT, ERR, ERR, B.SEARCH_SPEEDUP, 3.0, 2)[:2] == ([4, 4, 4], [4, 4, 8])
+    assert B.dybit_search(LAT, ERR, ERR, B.SEARCH_RMSE, 5.0, 2)[:2] == ([4, 4, 8], [4, 4, 8])
+    assert B.dybit_search(LAT, ERR, ERR, B.SEARCH_RMSE, 2.5, 1)[:2] == ([8, 4, 8], [8, 4, 8])
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_search_matches_oracle(seed):
+    """Same tables, same sums in the same order: widths, ratio and verdict are identical, not close."""
+    rng = np.random.default_rng(500 + seed)
+    n = int(rng.integers(1, 40))
+    lat, ew, ea = random_tables(rng, n)
+    if seed % 3 == 0:                                   # ties: equal layers must come out in index order
+        lat[n // 2:] = [lat[0]] * (n - n // 2)
+        ew[n // 2:] = [ew[0]] * (n - n // 2)
+    for strategy in ("speedup", "rmse"):
+        for constraint in (0.7, 1.0, 1.2, 2.0, 3.5, 8.0, 1e6):
+            for k in (1, 2, 5, n, n + 3):
+                want = S.search(lat, ew, ea, strategy, constraint, k)
+                got = B.dybit_search(lat, ew, ea, STRATEGY[strategy], constraint, k)
+                assert got == tuple(want), (strategy, constraint, k)
+
+
+def test_search_argument_errors():
+    L = B.lib()
+    n = 3
+    lat = np.ones((n, 3, 3))
+    e = np.ones((n, 3))
+    w = np.zeros(n, dtype=np.int32)
+    vp = lambda a: a.ctypes.data_as(C.c_void_p)
+    call = lambda n_=n, lat_=lat, ew=e, ea=e, strat=0, c=2.0, k=1, wo=w, ao=w: L.dybit_search(
+        n_, vp(lat_) if lat_ is not None else None, vp(ew) if ew is not None else None, vp(ea) if ea is not None else None,
+        strat, c, k, vp(wo) if wo is not None else None, vp(ao) if ao is not None else None, None, None)
+    assert call() == B.OK
+    assert call(lat_=None) == B.ERR_NULL and call(ew=None) == B.ERR_NULL and call(wo=None) == B.ERR_NULL
+    assert call(n_=0) == B.ERR_INVALID_ARG and call(k=0) == B.ERR_INVALID_ARG and call(strat=2) == B.ERR_INVALID_ARG
+    assert call(c=float("nan")) == B.ERR_INVALID_ARG
+    bad = lat.copy(); bad[1, 2, 0] = 0.0
+    assert call(lat_=bad) == B.ERR_INVALID_ARG
+    bad = lat.copy(); bad[0, 0, 0] = float("inf")
+    assert call(lat_=bad) == B.ERR_INVALID_ARG
+    neg = e.copy(); neg[2, 1] = -1e-9
+    assert call(ea=neg) == B.ERR_INVALID_ARG
+    assert call(ew=np.zeros((n, 3)), ea=np.zeros((n, 3)), strat=1) == B.ERR_INVALID_ARG     # zero error at (8, 8)
