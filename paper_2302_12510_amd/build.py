@@ -22,7 +22,8 @@ SOURCES = [
     ("gemm_mid.hip", "gemm_mid_w8", ["-DDYBIT_MID_W=2"]),
     ("gemm_mid.hip", "gemm_mid_w6", ["-DDYBIT_MID_W=4"]),
     ("gemm_mid.hip", "gemm_mid_w2", ["-DDYBIT_MID_W=6"]),
-    ("gemm_f8.hip", "gemm_f8", []),
+    ("gemm_f8.hip", "gemm_f8_w4", ["-DDYBIT_F8_W=0"]),
+    ("gemm_f8.hip", "gemm_f8_w2", ["-DDYBIT_F8_W=6"]),
     ("gemm_ws.hip", "gemm_ws_w4", ["-DDYBIT_WS_W=0"]),
     ("gemm_ws.hip", "gemm_ws_w8", ["-DDYBIT_WS_W=2"]),
     ("gemm_ws.hip", "gemm_ws_w6", ["-DDYBIT_WS_W=4"]),
@@ -38,7 +39,8 @@ SOURCES = [
     ("gemm_mid.hip", "gemm_mid_w8_wb", ["-DDYBIT_MID_W=2", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w6_wb", ["-DDYBIT_MID_W=4", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w2_wb", ["-DDYBIT_MID_W=6", "-DDYBIT_WB=1"]),
-    ("gemm_f8.hip", "gemm_f8_wb", ["-DDYBIT_WB=1"]),
+    ("gemm_f8.hip", "gemm_f8_w4_wb", ["-DDYBIT_F8_W=0", "-DDYBIT_WB=1"]),
+    ("gemm_f8.hip", "gemm_f8_w2_wb", ["-DDYBIT_F8_W=6", "-DDYBIT_WB=1"]),
     ("gemm_ws.hip", "gemm_ws_w4_wb", ["-DDYBIT_WS_W=0", "-DDYBIT_WB=1"]),
     ("gemm_ws.hip", "gemm_ws_w8_wb", ["-DDYBIT_WS_W=2", "-DDYBIT_WB=1"]),
     ("gemm_ws.hip", "gemm_ws_w6_wb", ["-DDYBIT_WS_W=4", "-DDYBIT_WB=1"]),

@@ -69,8 +69,10 @@ bool launch_gemm_ws_w6_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t 
 
 // fp8 matrix path for pairs of 4-bit formats with signed weights (gemm_f8.hip): the 256 x 256 tile
 // when `large`, else the 128 x 128 tile.
-bool launch_gemm_f8(const GemmArgs &g, bool conv, bool large, hipStream_t st);
-bool launch_gemm_f8_wb(const GemmArgs &g, bool conv, bool large, hipStream_t st);
+bool launch_gemm_f8_w0(const GemmArgs &g, int a_bits, bool conv, bool large, hipStream_t st);      // W 4-bit signed
+bool launch_gemm_f8_w6(const GemmArgs &g, int a_bits, bool conv, bool large, hipStream_t st);      // W 2-bit signed
+bool launch_gemm_f8_w0_wb(const GemmArgs &g, int a_bits, bool conv, bool large, hipStream_t st);
+bool launch_gemm_f8_w6_wb(const GemmArgs &g, int a_bits, bool conv, bool large, hipStream_t st);
 
 // General kernel (gemm.hip): any format pair and shape.  mode: 0 operands fetched code by code;
 // 1 operands are 16-byte aligned and K (convolution: Cin) is a multiple of 16; 2 (convolution

@@ -39,6 +39,7 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
     if (g.a_bytes >= 0x7fffffff || g.w_bytes >= 0x7fffffff) return false;
 
     bool large;
+    const bool low_pair = (a_bits == 4 || a_bits == 2) && (w_bits == 4 || w_bits == 2);
     const char *force = getenv("DYBIT_GEMM_KERNEL");
     if (force && !strcmp(force, "general")) return false;
 
@@ -70,16 +71,18 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
         // 401408 x 256, it is 1.1 to 1.7 times faster up to K = 512, level at K = 1024 (fp16
         // kernels) or K = 2048 (fp8 kernels), and 10 to 30 % slower beyond.
         const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-        const bool both4 = a_bits == 4 && w_bits == 4;
-        large = g.N > 128 && tiles256 >= 128 && g.K >= (both4 ? 2048 : 1024);
+        large = g.N > 128 && tiles256 >= 128 && g.K >= (low_pair ? 2048 : 1024);
     }
-    const bool mid_only = (a_bits != 4 && a_bits != 8) || (w_bits != 4 && w_bits != 8);   // 2- and 6-bit operands: the 128 x 128 kernel only
-    if (mid_only || rows) large = false;
-    // two 4-bit operands: every value is exact in e4m3, so the fp8 matrix path (twice the fp16 rate,
-    // byte decoders) takes them unless DYBIT_GEMM_MFMA=f16 asks for the fp16 kernels
+    // two operands of 4 or 2 bits: every value is exact in e4m3, so the fp8 matrix path (twice the
+    // fp16 rate, byte decoders) takes them unless DYBIT_GEMM_MFMA=f16 asks for the fp16 kernels
     const char *mfma = getenv("DYBIT_GEMM_MFMA");
     const bool wb = g.q_out != nullptr;                             // write-back builds of the same kernels
-    if (a_bits == 4 && w_bits == 4 && !rows && !(mfma && !strcmp(mfma, "f16"))) return (wb ? launch_gemm_f8_wb : launch_gemm_f8)(g, conv, large, st);
+    if (low_pair && !rows && !(mfma && !strcmp(mfma, "f16"))) {
+        if (w_bits == 4) return (wb ? launch_gemm_f8_w0_wb : launch_gemm_f8_w0)(g, a_bits, conv, large, st);
+        return (wb ? launch_gemm_f8_w6_wb : launch_gemm_f8_w6)(g, a_bits, conv, large, st);
+    }
+    const bool mid_only = (a_bits != 4 && a_bits != 8) || (w_bits != 4 && w_bits != 8);   // fp16 kernels, 2- and 6-bit operands: the 128 x 128 kernel only
+    if (mid_only || rows) large = false;
     if (large) {
         if (w_bits == 4) return (wb ? launch_gemm_fast_w0_wb : launch_gemm_fast_w0)(g, a_bits, conv, st);
         return (wb ? launch_gemm_fast_w2_wb : launch_gemm_fast_w2)(g, a_bits, conv, st);

@@ -1,13 +1,15 @@
-// DyBit matrix product for pairs of 4-bit formats on the fp8 matrix path of gfx950
+// DyBit matrix product for pairs of 4-bit and 2-bit formats on the fp8 matrix path of gfx950
 // (`v_mfma_f32_32x32x64_f8f6f4` with both operands e4m3): every value of the 4-bit formats has at
-// most 3 significant bits and lies in [1/8, 8], so it is exact in e4m3; one instruction contracts
-// 64 k in the time the fp16 instruction needs for 32, and the decoders emit bytes, not halves.
+// most 3 significant bits and lies in [1/8, 8], and the 2-bit formats hold 0, 1/2, 1, 2 or 0, +-1, so
+// all are exact in e4m3; one instruction contracts 64 k in the time the fp16 instruction needs for
+// 32, and the decoders emit bytes, not halves.
 //
 // Same organisation as the fp16 kernels (gemm_fast.hip, gemm_mid.hip): square tile of 32 NWM rows
 // and columns; NWM x KG waves; wave (wr, g) owns rows 32 wr .. + 31, all columns (CB = NWM
 // accumulator blocks) and, of every K step of 128 KG, the k-group k = 128 g .. 128 g + 127, which
 // is two MFMA blocks of 64.  Lane (row, kq = lane / 32) of the A operand supplies k = 32 kq .. + 31
-// of a block: 32 codes = one 128-bit load, decoded in registers straight into the 32-byte fragment.
+// of a block: 32 codes = one 128-bit (2-bit codes: 64-bit) load, decoded in registers straight into
+// the 32-byte fragment.
 // W is decoded once per workgroup (each thread 64 codes of one row) into a double-buffered LDS tile
 // of bytes (rows padded by 16 B) and read back as 32-byte fragments through a ring of two fragment
 // registers that is refilled right behind the MFMAs.  KG = 2 k-groups add their accumulators
@@ -15,9 +17,10 @@
 //   NWM = 8, KG = 1   256 x 256 tile, 8 waves (two per SIMD)               many large tiles
 //   NWM = 4, KG = 1   128 x 128 tile, 4 waves, three workgroups per CU     more tiles than CUs
 //   NWM = 4, KG = 2   128 x 128 tile, 8 waves                              at most one tile per CU
-// The order of the 32 k inside a lane's fragment is whatever the decoder produces (per 32-bit
-// word: the four even codes, then the four odd ones); both operands use the same decoder layout,
-// and the instruction pairs byte i of an A lane with byte i of the B lane of the same k-quarter.
+// The order of the 32 k inside a lane's fragment is the one the 4-bit decoders produce (per eight
+// consecutive codes: the four even ones, then the four odd ones); the 2-bit decoders emit the same
+// order, and the instruction pairs byte i of an A lane with byte i of the B lane of the same
+// k-quarter.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -34,6 +37,7 @@ namespace f8 {
 using namespace fast;
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef u32 u32x2 __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------
 // Decoders: 8 packed 4-bit codes (one word) -> 8 e4m3 bytes in two registers (even codes, odd codes).
@@ -66,15 +70,43 @@ template <> struct Codec8<F4U> {
     }
 };
 
-// 32 codes (four words) -> one 32-byte fragment
+// 2-bit formats: 16 packed codes (one word) -> 16 e4m3 bytes in four registers, in the order of the
+// 4-bit decoders: (k0 k2 k4 k6) (k1 k3 k5 k7) (k8 k10 k12 k14) (k9 k11 k13 k15).  Field j of every
+// byte of the word (shift by 2j, mask) gives the codes k = j, j + 4, j + 8, j + 12 as table indices;
+// the 4-entry byte table (sign included) is one register, and a second permute puts the bytes of
+// fields 0 / 2 (and 1 / 3) side by side.
+template <u32 TABLE> struct Codec8Two {
+    static __device__ __forceinline__ void word16(u32 w, u32 *d)
+    {
+        const u32 v0 = __builtin_amdgcn_perm(0u, TABLE, w & 0x03030303u);           // k0 k4 k8 k12
+        const u32 v1 = __builtin_amdgcn_perm(0u, TABLE, (w >> 2) & 0x03030303u);    // k1 k5 k9 k13
+        const u32 v2 = __builtin_amdgcn_perm(0u, TABLE, (w >> 4) & 0x03030303u);    // k2 k6 k10 k14
+        const u32 v3 = __builtin_amdgcn_perm(0u, TABLE, (w >> 6) & 0x03030303u);    // k3 k7 k11 k15
+        d[0] = __builtin_amdgcn_perm(v2, v0, 0x05010400u);                          // k0 k2 k4 k6
+        d[1] = __builtin_amdgcn_perm(v3, v1, 0x05010400u);
+        d[2] = __builtin_amdgcn_perm(v2, v0, 0x07030602u);                          // k8 k10 k12 k14
+        d[3] = __builtin_amdgcn_perm(v3, v1, 0x07030602u);
+    }
+};
+template <> struct Codec8<F2S> : Codec8Two<0xB8003800u> {};   // e4m3 of 0, +1, 0 (the unused pattern sign = 1, magnitude = 0), -1
+template <> struct Codec8<F2U> : Codec8Two<0x40383000u> {};   // e4m3 of 0, 0.5, 1, 2
+
+template <int FMT> constexpr int bits_of() { return (FMT == F2S || FMT == F2U) ? 2 : 4; }
+
+// 32 codes -> one 32-byte fragment.  4-bit: the four words of r; 2-bit: words `first`, `first + 1`.
 template <int FMT>
-__device__ __forceinline__ i32x8 decode_fragment(const u32x4 r)
+__device__ __forceinline__ i32x8 decode_fragment(const u32x4 r, int first = 0)
 {
     u32 d[8];
-    Codec8<FMT>::word(r.x, d);
-    Codec8<FMT>::word(r.y, d + 2);
-    Codec8<FMT>::word(r.z, d + 4);
-    Codec8<FMT>::word(r.w, d + 6);
+    if constexpr (bits_of<FMT>() == 2) {
+        Codec8<FMT>::word16(first ? r.z : r.x, d);
+        Codec8<FMT>::word16(first ? r.w : r.y, d + 4);
+    } else {
+        Codec8<FMT>::word(r.x, d);
+        Codec8<FMT>::word(r.y, d + 2);
+        Codec8<FMT>::word(r.z, d + 4);
+        Codec8<FMT>::word(r.w, d + 6);
+    }
     return i32x8{(int)d[0], (int)d[1], (int)d[2], (int)d[3], (int)d[4], (int)d[5], (int)d[6], (int)d[7]};
 }
 
@@ -97,6 +129,8 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
     constexpr int CB = NWM;                                        // 32-column blocks per wave
     constexpr int NQ = 2 * CB;                                     // MFMAs per wave and K step
     constexpr int R = 2;                                           // W fragment registers (ring); more would spill
+    constexpr int BA = bits_of<FMT_A>(), BW = bits_of<FMT_W>();    // code widths
+    constexpr int A_LOAD = 4 * BA;                                 // bytes of a lane's 32 codes of A
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -123,8 +157,8 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
         const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
 
     // ---- A: the lane's own row; per 64-wide block its 32 codes (16 bytes) at k-quarter kq
-    const int a_row_bytes = (int)(g.K / 2), w_row_bytes = (int)(g.K / 2);
-    const int pix_bytes = CONV ? g.Cin / 2 : 0;
+    const int a_row_bytes = (int)(g.K * BA / 8), w_row_bytes = (int)(g.K * BW / 8);
+    const int pix_bytes = CONV ? g.Cin * BA / 8 : 0;
     u32 offA;
     int hi0 = 0, wi0 = 0;
     bool okA;
@@ -138,15 +172,15 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
             const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
             hi0 = ho * g.stride - g.pad;
             wi0 = wo * g.stride - g.pad;
-            offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * 16);
+            offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * A_LOAD);
         } else {
-            offA = okA ? (u32)(m * a_row_bytes + kq * 16) : kOob;
+            offA = okA ? (u32)(m * a_row_bytes + kq * A_LOAD) : kOob;
         }
     }
     // ---- W staging: a row of the K step is 2 KG runs of 64 codes, one thread each
     const int wrow = tid / (2 * KG), wp = tid % (2 * KG);
     const int64_t nrow = n0 + wrow;
-    const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + wp * 32) : kOob;
+    const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + wp * (8 * BW)) : kOob;
     const u32 wrW = (u32)wrow * ROW_BYTES + (u32)wp * 64;
     const u32 rdW = (u32)(lane & 31) * ROW_BYTES + (u32)kgp * 128 + (u32)kq * 32;   // block b adds 64 B, column block j adds 32 rows
 
@@ -165,11 +199,16 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
         u32 off;
         if (CONV) {
             const bool in = okA && a_k0 < g.K && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
-            off = in ? offA + (u32)((a_fr * g.Wd + a_fs) * pix_bytes + a_c0 / 2) : kOob;   // padding reads code 0
+            off = in ? offA + (u32)((a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * BA / 8) : kOob;   // padding reads code 0
         } else {
-            off = a_k0 < g.K ? offA + (u32)(a_k0 / 2) : kOob;
+            off = a_k0 < g.K ? offA + (u32)(a_k0 * BA / 8) : kOob;
         }
-        raw = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off, 0, 0);
+        if constexpr (BA == 2) {
+            const u32x2 two = __builtin_amdgcn_raw_buffer_load_b64(rsrcA, off, 0, 0);
+            raw = u32x4{two.x, two.y, 0u, 0u};
+        } else {
+            raw = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off, 0, 0);
+        }
         a_k0 += advance;
         if (CONV) { a_c0 += advance; settle_tap(); }
     };
@@ -179,12 +218,12 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
     };
     auto load_W = [&](int64_t kt, u32x4 *raw) {
         const int64_t k0 = kt * TK + wp * 64;
-        const u32 off = k0 < g.K ? offW + (u32)(kt * (TK / 2)) : kOob;     // K is a multiple of 64
-        raw[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off, 0, 0);
-        raw[1] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + 16, 0, 0);
+        const u32 off = k0 < g.K ? offW + (u32)(kt * (TK * BW / 8)) : kOob;     // K is a multiple of 64
+        raw[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off, 0, 0);       // 4-bit: 32 codes; 2-bit: all 64
+        if constexpr (BW == 4) raw[1] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + 16, 0, 0);
     };
-    auto stage_W = [&](const u32x4 &raw, int h, char *tile) {              // 32 codes -> 32 bytes
-        const i32x8 f = decode_fragment<FMT_W>(raw);
+    auto stage_W = [&](const u32x4 *raw, int h, char *tile) {              // half h of the thread's 64 codes -> 32 bytes
+        const i32x8 f = BW == 4 ? decode_fragment<FMT_W>(raw[h]) : decode_fragment<FMT_W>(raw[0], h);
         *reinterpret_cast<u32x4 *>(tile + wrW + h * 32) = u32x4{(u32)f[0], (u32)f[1], (u32)f[2], (u32)f[3]};
         *reinterpret_cast<u32x4 *>(tile + wrW + h * 32 + 16) = u32x4{(u32)f[4], (u32)f[5], (u32)f[6], (u32)f[7]};
     };
@@ -208,8 +247,8 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
     load_W(0, rawW[0]);
     load_A(rawA[1]);
     load_W(1, rawW[1]);
-    stage_W(rawW[0][0], 0, lds);
-    stage_W(rawW[0][1], 1, lds);
+    stage_W(rawW[0], 0, lds);
+    stage_W(rawW[0], 1, lds);
     fa = decode_fragment<FMT_A>(rawA[0][0]);
     __syncthreads();
 #pragma unroll
@@ -236,8 +275,8 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
                 acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa_cur, fw[q % R], acc[j], 0, 0, 0, 0, 0, 0);
                 const int qn = q + R;
                 fw[q % R] = qn < NQ ? read_W(cur, qn / CB, qn % CB) : read_W(nxt, (qn - NQ) / CB, (qn - NQ) % CB);
-                if (q == 0) stage_W(rawW[s ^ 1][0], 0, nxt);
-                if (q == (NQ - R) / 2) stage_W(rawW[s ^ 1][1], 1, nxt);
+                if (q == 0) stage_W(rawW[s ^ 1], 0, nxt);
+                if (q == (NQ - R) / 2) stage_W(rawW[s ^ 1], 1, nxt);
             }
             fa = b == 0 ? decode_fragment<FMT_A>(rawA[s][1]) : decode_fragment<FMT_A>(rawA[s ^ 1][0]);
             if (b == 1) load_A(rawA[s]);                            // K step kt + 2; step kt's codes are decoded by now
@@ -295,23 +334,41 @@ static void launch_cfg(const GemmArgs &g, bool conv, hipStream_t st)
     }
 }
 
-template <int FA>
+template <int FA, int FW>
 static void launch(const GemmArgs &g, bool conv, bool large, hipStream_t st)
 {
-    if (large) return launch_cfg<FA, F4S, 8, 1>(g, conv, st);
+    if (large) return launch_cfg<FA, FW, 8, 1>(g, conv, st);
     const int64_t tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
     const char *force = getenv("DYBIT_MID_KGROUPS");
     const bool one = force ? atoi(force) == 1 : tiles > 256;
-    if (one) launch_cfg<FA, F4S, 4, 1>(g, conv, st);
-    else launch_cfg<FA, F4S, 4, 2>(g, conv, st);
+    if (one) launch_cfg<FA, FW, 4, 1>(g, conv, st);
+    else launch_cfg<FA, FW, 4, 2>(g, conv, st);
 }
 
 }  // namespace f8
 
-bool DYBIT_WB_NAME(launch_gemm_f8)(const GemmArgs &g, bool conv, bool large, hipStream_t st)
+// One translation unit per weight format (DYBIT_F8_W: 0 = 4-bit signed, 6 = 2-bit signed); the
+// activation format is chosen here.
+#ifndef DYBIT_F8_W
+#error "compile with -DDYBIT_F8_W=0 or 6"
+#endif
+#define DYBIT_F8_CAT_(a, b) a##b
+#define DYBIT_F8_CAT(a, b) DYBIT_F8_CAT_(a, b)
+#define DYBIT_F8_WB(name) DYBIT_WB_NAME(name)                       // expands `name` before the suffix is pasted on
+#define DYBIT_F8_LAUNCH DYBIT_F8_WB(DYBIT_F8_CAT(launch_gemm_f8_w, DYBIT_F8_W))
+
+bool DYBIT_F8_LAUNCH(const GemmArgs &g, int a_bits, bool conv, bool large, hipStream_t st)
 {
-    if (g.a_signed) f8::launch<fast::F4S>(g, conv, large, st);
-    else f8::launch<fast::F4U>(g, conv, large, st);
+    constexpr int FW = DYBIT_F8_W;
+    if (a_bits == 4) {
+        if (g.a_signed) f8::launch<fast::F4S, FW>(g, conv, large, st);
+        else f8::launch<fast::F4U, FW>(g, conv, large, st);
+    } else if (a_bits == 2) {
+        if (g.a_signed) f8::launch<fast::F2S, FW>(g, conv, large, st);
+        else f8::launch<fast::F2U, FW>(g, conv, large, st);
+    } else {
+        return false;
+    }
     return true;
 }
 

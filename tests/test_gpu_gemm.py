@@ -247,10 +247,11 @@ TILED_PAIRS += [(a, (6, True)) for a in ((4, False), (6, True), (6, False), (8, 
 TILED_PAIRS += [((6, True), (4, True)), ((6, False), (4, True)), ((6, True), (8, True)), ((6, False), (8, True))]
 # ... and the 2-bit formats of the {8, 4, 2} x {8, 4, 2} mode matrix
 TILED_PAIRS += [((2, True), (2, True)), ((2, False), (2, True)), ((8, True), (2, True)), ((4, False), (2, True)),
-                ((2, False), (4, True)), ((2, True), (8, True)), ((2, False), (6, True))]
-# mid1 / mid2: the 128 x 128 kernel with one / two k-groups.  Two 4-bit operands run on the fp8 matrix
-# path by default; the "-f16" entries keep them on the fp16 kernels (and are skipped for other pairs,
-# which are on the fp16 kernels anyway).
+                ((2, False), (4, True)), ((2, True), (8, True)), ((2, False), (6, True)), ((4, True), (2, True)),
+                ((2, True), (4, True))]
+# mid1 / mid2: the 128 x 128 kernel with one / two k-groups.  Two operands of 4 or 2 bits run on the fp8
+# matrix path by default (256 x 256 tiles included); the "-f16" entries keep them on the fp16 kernels
+# (and are skipped for other pairs, which are on the fp16 kernels anyway).
 KERNELS = ["large", "mid1", "mid2", "large-f16", "mid1-f16", "mid2-f16"]
 
 
@@ -258,11 +259,12 @@ KERNELS = ["large", "mid1", "mid2", "large-f16", "mid1-f16", "mid2-f16"]
 def force_kernel(monkeypatch, request):
     name = request.param
     fmts = [request.getfixturevalue(k) for k in ("a_fmt", "w_fmt", "x_fmt") if k in request.fixturenames]
-    if name.startswith("large") and any(f[0] in (2, 6) for f in fmts):
-        pytest.skip("2- and 6-bit operands run on the 128 x 128 kernel only")
+    low_pair = bool(fmts) and all(f[0] in (2, 4) for f in fmts)
+    if name.startswith("large") and any(f[0] in (2, 6) for f in fmts) and (not low_pair or name.endswith("-f16")):
+        pytest.skip("on the fp16 kernels 2- and 6-bit operands run on the 128 x 128 kernel only")
     if name.endswith("-f16"):
-        if fmts and not all(f[0] == 4 for f in fmts):
-            pytest.skip("only pairs of 4-bit formats have an fp8 path to switch off")
+        if fmts and not low_pair:
+            pytest.skip("only pairs of 4- and 2-bit formats have an fp8 path to switch off")
         monkeypatch.setenv("DYBIT_GEMM_MFMA", "f16")
         name = name[:-4]
     if name.startswith("mid") and name != "mid":

@@ -28,7 +28,7 @@ def check_codes(codes_dev, c32: np.ndarray, c_scale, c_fmt):
 
 @pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "general"], indirect=True)
 @pytest.mark.parametrize("c_fmt", OUT_FMTS)
-@pytest.mark.parametrize("a_fmt", [(8, True), (4, False)])
+@pytest.mark.parametrize("a_fmt", [(8, True), (4, False), (2, False)])
 def test_gemm_wb(force_kernel, c_fmt, a_fmt):
     """Ragged M, several column tiles, bias + shortcut, values from far below the smallest step up to
     saturation; both outputs, then codes only."""
