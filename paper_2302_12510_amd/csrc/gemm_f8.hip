@@ -17,6 +17,7 @@
 //   NWM = 8, KG = 1   256 x 256 tile, 8 waves (two per SIMD)               many large tiles
 //   NWM = 4, KG = 1   128 x 128 tile, 4 waves, three workgroups per CU     more tiles than CUs
 //   NWM = 4, KG = 2   128 x 128 tile, 8 waves                              at most one tile per CU
+//   NWM = 2, KG = 2   64 x 64 tile, 4 waves, four workgroups per CU        128 x 128 tiles for under half the CUs
 // The order of the 32 k inside a lane's fragment is the one the 4-bit decoders produce (per eight
 // consecutive codes: the four even ones, then the four odd ones); the 2-bit decoders emit the same
 // order, and the instruction pairs byte i of an A lane with byte i of the B lane of the same
@@ -121,7 +122,7 @@ template <int NWM, int KG> struct Geom {
 };
 
 template <int FMT_A, int FMT_W, bool CONV, int NWM, int KG, bool WB>
-__global__ __launch_bounds__(64 * NWM * KG, (NWM == 4 && KG == 1 && !WB) ? 3 : 2)
+__global__ __launch_bounds__(64 * NWM * KG, NWM == 2 ? 4 : (NWM == 4 && KG == 1 && !WB) ? 3 : 2)
 void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using G = Geom<NWM, KG>;
@@ -339,6 +340,11 @@ static void launch(const GemmArgs &g, bool conv, bool large, hipStream_t st)
 {
     if (large) return launch_cfg<FA, FW, 8, 1>(g, conv, st);
     const int64_t tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
+    // Few tiles: a quarter-size tile puts four times as many workgroups on the device (each decodes
+    // its A rows for half as many columns, which costs less than idle compute units).
+    // DYBIT_MID_TILE=64 / 128 overrides the choice.
+    const char *tile = getenv("DYBIT_MID_TILE");
+    if (tile ? atoi(tile) == 64 : tiles <= 128) return launch_cfg<FA, FW, 2, 2>(g, conv, st);
     const char *force = getenv("DYBIT_MID_KGROUPS");
     const bool one = force ? atoi(force) == 1 : tiles > 256;
     if (one) launch_cfg<FA, FW, 4, 1>(g, conv, st);

@@ -252,7 +252,8 @@ TILED_PAIRS += [((2, True), (2, True)), ((2, False), (2, True)), ((8, True), (2,
 # mid1 / mid2: the 128 x 128 kernel with one / two k-groups.  Two operands of 4 or 2 bits run on the fp8
 # matrix path by default (256 x 256 tiles included); the "-f16" entries keep them on the fp16 kernels
 # (and are skipped for other pairs, which are on the fp16 kernels anyway).
-KERNELS = ["large", "mid1", "mid2", "large-f16", "mid1-f16", "mid2-f16"]
+# mid64: the 64 x 64 tile of the fp8-path kernel (chosen by itself when 128 x 128 tiles are few).
+KERNELS = ["large", "mid1", "mid2", "mid64", "large-f16", "mid1-f16", "mid2-f16"]
 
 
 @pytest.fixture
@@ -267,8 +268,14 @@ def force_kernel(monkeypatch, request):
             pytest.skip("only pairs of 4- and 2-bit formats have an fp8 path to switch off")
         monkeypatch.setenv("DYBIT_GEMM_MFMA", "f16")
         name = name[:-4]
-    if name.startswith("mid") and name != "mid":
+    if name == "mid64":
+        if fmts and not low_pair:
+            pytest.skip("the 64 x 64 tile exists on the fp8 path only")
+        monkeypatch.setenv("DYBIT_MID_TILE", "64")
+        name = "mid"
+    elif name.startswith("mid") and name != "mid":
         monkeypatch.setenv("DYBIT_MID_KGROUPS", name[3:])
+        monkeypatch.setenv("DYBIT_MID_TILE", "128")
         name = "mid"
     monkeypatch.setenv("DYBIT_GEMM_KERNEL", name)
     return request.param
@@ -342,7 +349,7 @@ def test_tiled_kernels_conv(force_kernel, x_fmt, w_fmt, geom):
     assert_within(got, want, den)
 
 
-@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid1-f16", "mid2-f16"], indirect=True)
+@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid64", "mid1-f16", "mid2-f16"], indirect=True)
 def test_mid_kernel_wide_channels_conv(force_kernel):
     """Cin = 192: a 128-wide K step straddles two filter taps (each k-group follows its own tap)."""
     rng = np.random.default_rng(11)
@@ -424,7 +431,7 @@ def test_general_kernel_on_tiled_shapes(force_kernel, a_fmt, w_fmt):
 
 
 # ---- running maximum of the outputs taken in the epilogue ---------------------------
-@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "general"], indirect=True)
+@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "mid64", "general"], indirect=True)
 @pytest.mark.parametrize("relu", [False, True])
 @pytest.mark.parametrize("a_fmt", [(8, True), (4, False)])
 def test_gemm_absmax_matches_a_pass_over_the_output(force_kernel, relu, a_fmt):
@@ -454,7 +461,7 @@ def test_gemm_absmax_matches_a_pass_over_the_output(force_kernel, relu, a_fmt):
     assert big.item() == 1.0e9
 
 
-@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid1-f16", "general"], indirect=True)
+@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid64", "mid1-f16", "general"], indirect=True)
 @pytest.mark.parametrize("with_shortcut", [False, True])
 def test_conv2d_ex_shortcut_and_absmax(force_kernel, with_shortcut):
     """Shortcut added before the ReLU, running maximum over the values written, ragged tiles."""
@@ -474,7 +481,7 @@ def test_conv2d_ex_shortcut_and_absmax(force_kernel, with_shortcut):
     assert mx.item() == y.abs().max().item()
 
 
-@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "general"], indirect=True)
+@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "mid64", "general"], indirect=True)
 @pytest.mark.parametrize("a_fmt", [(8, True), (4, True)])
 def test_gemm_ex_shortcut(force_kernel, a_fmt):
     """C = A W^T + bias + shortcut (no ReLU, so a wrong sign or a shortcut applied after the ReLU shows),

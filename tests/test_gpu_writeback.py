@@ -26,7 +26,7 @@ def check_codes(codes_dev, c32: np.ndarray, c_scale, c_fmt):
     assert not bad.any(), f"{bad.sum()} of {bad.size} packed bytes differ; first at {np.argwhere(bad)[0]}"
 
 
-@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "general"], indirect=True)
+@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "mid64", "general"], indirect=True)
 @pytest.mark.parametrize("c_fmt", OUT_FMTS)
 @pytest.mark.parametrize("a_fmt", [(8, True), (4, False), (2, False)])
 def test_gemm_wb(force_kernel, c_fmt, a_fmt):
@@ -79,7 +79,7 @@ def test_gemm_wb_exact_ties_and_every_value(force_kernel, c_fmt):
         check_codes(codes, c32, c_scale, c_fmt)
 
 
-@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid1-f16", "general"], indirect=True)
+@pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid64", "mid1-f16", "general"], indirect=True)
 @pytest.mark.parametrize("y_fmt", [(4, False), (6, False), (8, True)])
 def test_conv2d_wb(force_kernel, y_fmt):
     rng = np.random.default_rng(37)
