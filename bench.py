@@ -465,6 +465,10 @@ def main():
             del codes
         ams, _ = time_events(lambda: B.dybit_absmax_scale(x, 8, True, out=sa), 10, 2, torch)
         q["absmax"] = {"ms": round(ams, 4), "GBps": round(4.0 * n / (ams * 1e-3) / 1e9, 1)}
+        y = torch.empty(n, dtype=torch.float32, device="cuda")
+        fms, _ = time_events(lambda: B.dybit_fake_quant(x, s, 8, True, out=y), 10, 2, torch)
+        q["fake_quant_8bit"] = {"ms": round(fms, 4), "GBps": round(8.0 * n / (fms * 1e-3) / 1e9, 1)}
+        del y
         err = torch.empty(4, dtype=torch.float64, device="cuda")
         rms, _ = time_events(lambda: B.dybit_rmse(x, s, 8, True, out=err), 10, 2, torch)
         q["rmse_8bit"] = {"ms": round(rms, 4), "GBps": round(4.0 * n / (rms * 1e-3) / 1e9, 1), "value": round(err[0].item(), 6)}

@@ -187,6 +187,15 @@ dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t Cin, int64
  * for a maximum obtained otherwise.  absmax, scale_out [device]: 1 float each (may be the same word). */
 dybit_status dybit_scale_from_absmax(const float *absmax, dybit_fmt f, float *scale_out, dybit_stream stream);
 
+/* Quantize and decode again in one pass, y = s * value(code nearest to x / s): the forward of the
+ * quantization-aware training step that follows the search (Sec. III-C); bit for bit the result of
+ * dybit_dequantize on dybit_quantize's codes, without the codes reaching memory.  (The straight-through
+ * gradient of that step is the identity inside the representable range and is left to the caller.)
+ * x, y_out [device]: n floats each, 16-byte aligned (may be the same buffer).  scale [device]: as for
+ * dybit_quantize; an unusable scale writes nothing and sets the asynchronous error flag. */
+dybit_status dybit_fake_quant(const float *x, size_t n, dybit_fmt f, const float *scale, float *y_out,
+                              dybit_stream stream);
+
 /* Quantization error of one tensor in one format (Sec. III-C, Eq. 2):
  *     RMSE = sqrt( mean( ((x - x_hat) / sigma)^2 ) ),   x_hat = s * value(code nearest to x / s),
  * sigma the standard deviation of x (population form, one value for the tensor).  One pass over x.

@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
         L.dybit_conv2d_wb.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, Fmt, vp, vp, vp]
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
         L.dybit_rmse.argtypes = [vp, sz, Fmt, vp, vp, vp]
+        L.dybit_fake_quant.argtypes = [vp, sz, Fmt, vp, vp, vp]
         L.dybit_search.argtypes = [i32, vp, vp, vp, i32, C.c_double, i32, vp, vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
         L.dybit_diag_mfma_f16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
@@ -173,6 +174,17 @@ def dybit_quantize_absmax(x: torch.Tensor, absmax: torch.Tensor, bits: int, sign
     _check(lib().dybit_quantize_absmax(_ptr(x), n, fmt(bits, signed), _ptr(absmax), _ptr(scale_out), _ptr(out),
                                        _stream(stream)), "dybit_quantize_absmax")
     return scale_out, out
+
+
+def dybit_fake_quant(x: torch.Tensor, scale: torch.Tensor, bits: int, signed: bool, out: torch.Tensor | None = None, stream=None):
+    """y = scale * value(code of x): quantize and decode in one pass."""
+    assert x.dtype == torch.float32 and scale.dtype == torch.float32
+    if out is None:
+        out = torch.empty_like(x)
+    assert out.dtype == torch.float32 and out.numel() == x.numel()
+    _check(lib().dybit_fake_quant(_ptr(x), x.numel(), fmt(bits, signed), _ptr(scale), _ptr(out), _stream(stream)),
+           "dybit_fake_quant")
+    return out
 
 
 def dybit_dequantize(codes: torch.Tensor, n: int, scale: torch.Tensor, bits: int, signed: bool,

@@ -300,6 +300,62 @@ __global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__rest
     }
 }
 
+// quantize followed by dequantize without the codes ever reaching memory (the forward of the
+// quantization-aware training step, Sec. III-C): y = s * value(code of x), bit for bit what
+// dybit_dequantize returns for dybit_quantize's codes.  8 bytes per element.
+template <int BITS, bool SIGNED>
+__device__ __forceinline__ float code_to_value(uint32_t code, float s)
+{
+    return s * code_value(code, BITS, SIGNED);                           // the expression of the dequantize table
+}
+
+template <int BITS, bool SIGNED, int UNROLL>
+__global__ __launch_bounds__(kThreads) void fake_quant_kernel(const float *__restrict__ x, size_t n,
+                                                              const float *__restrict__ scale, float *__restrict__ y)
+{
+    const ScaleInfo si = load_scale(scale);
+    if (!si.ok) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        return;
+    }
+    const size_t n4 = n >> 2;
+    const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
+    f32x4 *y4 = reinterpret_cast<f32x4 *>(y);
+    const size_t per_block = (size_t)kThreads * UNROLL;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
+        f32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t i = base + (size_t)u * kThreads + threadIdx.x;
+            v[u] = (i < n4) ? __builtin_nontemporal_load(x4 + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t i = base + (size_t)u * kThreads + threadIdx.x;
+            const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            uint32_t c[4];
+            bool any_redo = si.all_exact;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                bool redo;
+                c[k] = quantize_fast<BITS, SIGNED>(e[k], si.rinv, redo);
+                any_redo |= redo;
+            }
+            if (any_redo) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) c[k] = quantize_exact<BITS, SIGNED>(e[k], si.s);
+            }
+            const f32x4 out = {code_to_value<BITS, SIGNED>(c[0], si.s), code_to_value<BITS, SIGNED>(c[1], si.s),
+                               code_to_value<BITS, SIGNED>(c[2], si.s), code_to_value<BITS, SIGNED>(c[3], si.s)};
+            if (i < n4) __builtin_nontemporal_store(out, y4 + i);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {                      // remainder: exact path
+        const size_t j = (n4 << 2) + threadIdx.x;
+        y[j] = code_to_value<BITS, SIGNED>(quantize_exact<BITS, SIGNED>(x[j], si.s), si.s);
+    }
+}
+
 // Remainder: one thread per group of 4 elements starting at element `first`; exact path, byte stores.
 template <int BITS, bool SIGNED>
 __global__ void quantize_tail_kernel(const float *__restrict__ x, size_t first, size_t n,
@@ -469,6 +525,27 @@ extern "C" dybit_status dybit_quantize_absmax(const float *x, size_t n, dybit_fm
         case 16: DYBIT_Q(8, false); break;  case 17: DYBIT_Q(8, true); break;
     }
 #undef DYBIT_Q
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_fake_quant(const float *x, size_t n, dybit_fmt f, const float *scale, float *y_out,
+                                         dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (!scale || ((!x || !y_out) && n)) return DYBIT_ERR_NULL;
+    if (!aligned16(x) || !aligned16(y_out)) return DYBIT_ERR_ALIGNMENT;
+    if (n == 0) return DYBIT_OK;
+    hipStream_t hs = (hipStream_t)stream;
+    const int grid = grid_for(n / 4 + 1, kThreads * 4, 256 * DYBIT_QUANT_BLOCKS_PER_CU);
+#define DYBIT_FQ(B, S) hipLaunchKernelGGL((fake_quant_kernel<B, S, 4>), dim3(grid), dim3(kThreads), 0, hs, x, n, scale, y_out)
+    switch (f.bits * 2 + f.is_signed) {
+        case 4: DYBIT_FQ(2, false); break;   case 5: DYBIT_FQ(2, true); break;
+        case 8: DYBIT_FQ(4, false); break;   case 9: DYBIT_FQ(4, true); break;
+        case 12: DYBIT_FQ(6, false); break;  case 13: DYBIT_FQ(6, true); break;
+        case 16: DYBIT_FQ(8, false); break;  case 17: DYBIT_FQ(8, true); break;
+    }
+#undef DYBIT_FQ
     return launch_status();
 }
 

@@ -141,6 +141,11 @@ def test_rmse_argument_errors_without_gpu():
     assert L.dybit_rmse(p, 0, f4, p, p, None) == B.ERR_INVALID_ARG
     assert L.dybit_rmse(C.c_void_p(0x1004), 64, f4, p, p, None) == B.ERR_ALIGNMENT
     assert L.dybit_rmse(p, 64, f4, p, C.c_void_p(0x1004), None) == B.ERR_ALIGNMENT
+    assert L.dybit_fake_quant(p, 64, bad, p, p, None) == B.ERR_UNSUPPORTED_BITS
+    assert L.dybit_fake_quant(null, 64, f4, p, p, None) == B.ERR_NULL
+    assert L.dybit_fake_quant(p, 64, f4, null, p, None) == B.ERR_NULL
+    assert L.dybit_fake_quant(p, 64, f4, p, C.c_void_p(0x1008), None) == B.ERR_ALIGNMENT
+    assert L.dybit_fake_quant(null, 0, f4, p, null, None) == B.OK
 
 
 # ---- the search is host code: checked in full against the oracle here ---------------------------------

@@ -152,3 +152,32 @@ def test_quantize_with_a_known_maximum(fmt, n):
         assert scale.item() == s
         assert np.array_equal(codes.cpu().numpy(), R.pack(R.quantize(arr, s, *fmt), fmt[0]))
     assert B.dybit_get_last_async_error() == B.OK
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 4099, (1 << 20) + 7])
+def test_fake_quant_equals_quantize_then_dequantize(fmt, n):
+    """dybit_fake_quant against the oracle's dequantize(quantize(x)), bit for bit, with special values,
+    saturation and (signed formats) negative values that round to zero."""
+    rng = np.random.default_rng(n + fmt[0])
+    x = rng.laplace(0, 0.02, n).astype(np.float32)
+    x[:: max(n // 7, 1)] *= np.float32(30.0)
+    if n > 4:
+        x[1], x[2], x[3], x[4] = np.nan, np.inf, -np.inf, -1e-9
+    s = np.float32(0.6) * R.absmax_scale(np.nan_to_num(x, nan=0.0, posinf=0.0, neginf=0.0), *fmt)
+    want = R.dequantize(R.quantize(x, s, *fmt), s, *fmt)
+    got = B.dybit_fake_quant(dev(x), scalar(s), *fmt)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_fake_quant_in_place_and_bad_scale():
+    x = dev(np.linspace(-3, 3, 1001, dtype=np.float32))
+    want = B.dybit_fake_quant(x, scalar(0.25), 4, True).clone()
+    B.dybit_fake_quant(x, scalar(0.25), 4, True, out=x)
+    assert torch.equal(x, want)
+    assert B.dybit_get_last_async_error() == B.OK
+    y = torch.full((1001,), 7.0, device="cuda")
+    B.dybit_fake_quant(x, scalar(0.0), 4, True, out=y)
+    assert B.dybit_get_last_async_error() == B.ERR_BAD_SCALE
+    assert bool((y == 7.0).all())
