@@ -291,7 +291,9 @@ def gemm(a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale, bias=None, relu=False
     the output's shape added to the floating-point intermediate result before the ReLU (and
     before anything is written back).
 
-    a_codes: [M][K] unpacked codes, w_codes: [N][K]; *_fmt = (bits, signed).
+    a_codes: [M][K] unpacked codes, w_codes: [N][K]; *_fmt = (bits, signed).  w_scale is one
+    number (tensor-level precision, Sec. I) or N numbers, one per row of W (per-output-channel
+    weight scales: column n of C then carries sW[n]).
     The sum is taken over exact integers (values times 2^(m-1)) in float64;
     every partial sum stays below 2^53, so the order of summation cannot matter.
     Returns (C float64, D float64) with D[m,n] = sA*sW*sum_k|a*w| (+|bias|) (+|residual|), the
@@ -301,8 +303,10 @@ def gemm(a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale, bias=None, relu=False
     iw = _decode_scaled_int(w_codes, *w_fmt)
     ma = magnitude_bits(*a_fmt)
     mw = magnitude_bits(*w_fmt)
-    unit = float(np.float64(np.float32(a_scale)) * np.float64(np.float32(w_scale))) \
-        * 2.0 ** (-(ma - 1) - (mw - 1))
+    sw = np.asarray(w_scale, dtype=np.float32).astype(np.float64)
+    if sw.ndim not in (0, 1) or (sw.ndim == 1 and sw.size != iw.shape[0]):
+        raise ValueError("w_scale is a scalar or one value per row of W")
+    unit = np.float64(np.float32(a_scale)) * sw * 2.0 ** (-(ma - 1) - (mw - 1))     # scalar or [N]
     acc = ia @ iw.T
     den = np.abs(ia) @ np.abs(iw).T
     assert den.max(initial=0.0) < 2.0 ** 53
@@ -404,3 +408,15 @@ def quantization_rmse(x: np.ndarray, scale, bits: int, signed: bool) -> float:
     codes = quantize(x, scale, bits, signed)
     x_hat = np.float64(np.float32(scale)) * codebook(bits, signed)[np.asarray(codes, dtype=np.int64)]
     return rmse(x, x_hat)
+
+
+def quantize_rows(x2d: np.ndarray, bits: int, signed: bool):
+    """Per-row (per-output-channel) max-abs scales and codes of a weight matrix [rows][cols]:
+    absmax_scale and quantize applied to every row on its own.  Returns (scales float32 [rows],
+    codes [rows][cols])."""
+    x2d = np.asarray(x2d, dtype=np.float32)
+    scales = np.array([absmax_scale(row, bits, signed) for row in x2d], dtype=np.float32)
+    codes = np.stack([quantize(row, scales[i], bits, signed) for i, row in enumerate(x2d)]) if len(x2d) else \
+        np.zeros(x2d.shape, dtype=np.uint8)
+    return scales, codes
+

@@ -128,3 +128,41 @@ def test_c_gemm_matches_numpy_on_config1_shape():
     # the quantized product tracks the float product (sanity of the whole chain)
     ref = cfg["A"].astype(np.float64) @ cfg["W"].astype(np.float64).T
     assert np.corrcoef(ref.ravel(), c.ravel())[0, 1] > 0.95
+
+
+def test_per_channel_weight_scales_are_the_scalar_case_column_by_column():
+    """A vector w_scale: column n of the result is the (pinned) scalar-scale product with sW[n]."""
+    rng = np.random.default_rng(21)
+    a_fmt, w_fmt = (8, True), (4, True)
+    qa = rng.integers(0, 256, (7, 24)).astype(np.uint8)
+    qw = rng.integers(0, 16, (5, 24)).astype(np.uint8)
+    sw = rng.uniform(0.01, 2.0, 5).astype(np.float32)
+    bias = rng.normal(0, 1, 5).astype(np.float32)
+    res = rng.normal(0, 1, (7, 5)).astype(np.float32)
+    c, d = R.gemm(qa, a_fmt, 0.3, qw, w_fmt, sw, bias, True, res)
+    for n in range(5):
+        cn, dn = R.gemm(qa, a_fmt, 0.3, qw[n:n + 1], w_fmt, sw[n], bias[n:n + 1], True, res[:, n:n + 1])
+        assert np.array_equal(c[:, n:n + 1], cn) and np.array_equal(d[:, n:n + 1], dn)
+    with pytest.raises(ValueError):
+        R.gemm(qa, a_fmt, 0.3, qw, w_fmt, sw[:3])
+    # convolution: the same through im2col
+    qx = rng.integers(0, 16, (1, 5, 6, 4)).astype(np.uint8)
+    qf = rng.integers(0, 16, (3, 3, 3, 4)).astype(np.uint8)
+    y, _ = R.conv2d(qx, (4, False), 0.5, qf, (4, True), sw[:3], 1, 1)
+    for n in range(3):
+        yn, _ = R.conv2d(qx, (4, False), 0.5, qf[n:n + 1], (4, True), sw[n], 1, 1)
+        assert np.array_equal(y[..., n:n + 1], yn)
+
+
+def test_quantize_rows_is_row_by_row():
+    rng = np.random.default_rng(22)
+    w = rng.laplace(0, 0.02, (6, 40)).astype(np.float32) * rng.uniform(0.1, 10, (6, 1)).astype(np.float32)
+    w[3] = 0.0
+    s, q = R.quantize_rows(w, 4, True)
+    assert s.dtype == np.float32 and s.shape == (6,) and q.shape == (6, 40)
+    for i in range(6):
+        assert s[i] == R.absmax_scale(w[i], 4, True)
+        assert np.array_equal(q[i], R.quantize(w[i], s[i], 4, True))
+    assert s[3] == 1.0 and not q[3].any()
+    # every row uses the whole code range: its largest magnitude is the all-ones code
+    assert all((q[i] & 7).max() == 7 for i in (0, 1, 2, 4, 5))
