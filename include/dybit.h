@@ -183,6 +183,34 @@ dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t Cin, int64
                              float *Y, float *y_absmax,
                              dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream);
 
+/* Per-output-channel weight scales (an option on top of the tensor-level scale of Sec. I: one scale per
+ * row of W / per filter, the usual remedy for networks whose channels differ widely in range, such as the
+ * depthwise-separable ones of Sec. IV).
+ *
+ * dybit_quantize_rows: max-abs scale and codes of every row of x on its own.
+ *   x [device]: rows * cols floats, row-major.  cols * bits must be a multiple of 8 (DYBIT_ERR_ALIGNMENT).
+ *   scales_out [device]: rows floats, scales_out[r] = max|x[r][:]| / 2^(m-1) (1.0 for an all-zero row).
+ *   codes_out [device]: rows * cols * bits / 8 bytes, rows back to back.  A row whose maximum is infinite
+ *   or subnormal gets no codes and sets the asynchronous error flag.
+ * dybit_gemm_pc / dybit_conv2d_pc: dybit_gemm_wb / dybit_conv2d_wb with w_scales [device] holding N (Cout)
+ *   floats: C[m][n] = sA * w_scales[n] * sum_k a[m][k] w[n][k] (+ bias[n]) (+ residual) (ReLU).  C_codes /
+ *   Y_codes may be NULL (then c_fmt and c_scale are ignored and the fp32 output is required). */
+dybit_status dybit_quantize_rows(const float *x, int64_t rows, int64_t cols, dybit_fmt f, float *scales_out,
+                                 uint8_t *codes_out, dybit_stream stream);
+dybit_status dybit_gemm_pc(int64_t M, int64_t N, int64_t K,
+                           const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                           const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scales,
+                           const float *bias, const float *residual, int32_t relu,
+                           float *C, int64_t ldc, float *c_absmax,
+                           dybit_fmt c_fmt, const float *c_scale, uint8_t *C_codes, dybit_stream stream);
+dybit_status dybit_conv2d_pc(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                             int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                             const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                             const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scales,
+                             const float *bias, const float *residual, int32_t relu,
+                             float *Y, float *y_absmax,
+                             dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream);
+
 /* *scale_out = *absmax / 2^(m-1), or 1.0 when *absmax == 0: the last step of dybit_absmax_scale,
  * for a maximum obtained otherwise.  absmax, scale_out [device]: 1 float each (may be the same word). */
 dybit_status dybit_scale_from_absmax(const float *absmax, dybit_fmt f, float *scale_out, dybit_stream stream);

@@ -55,6 +55,9 @@ def lib() -> C.CDLL:
         L.dybit_gemm_wb.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, i64, vp, Fmt, vp, vp, vp]
         L.dybit_conv2d_wb.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, Fmt, vp, vp, vp]
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
+        L.dybit_quantize_rows.argtypes = [vp, i64, i64, Fmt, vp, vp, vp]
+        L.dybit_gemm_pc.argtypes = L.dybit_gemm_wb.argtypes
+        L.dybit_conv2d_pc.argtypes = L.dybit_conv2d_wb.argtypes
         L.dybit_rmse.argtypes = [vp, sz, Fmt, vp, vp, vp]
         L.dybit_fake_quant.argtypes = [vp, sz, Fmt, vp, vp, vp]
         L.dybit_search.argtypes = [i32, vp, vp, vp, i32, C.c_double, i32, vp, vp, C.POINTER(C.c_double), C.POINTER(i32)]
@@ -293,6 +296,57 @@ def dybit_conv2d_wb(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: in
                                  _ptr(out if fp32 else None), _ptr(absmax),
                                  fmt(*y_fmt), _ptr(y_scale), _ptr(codes_out), _stream(stream)), "dybit_conv2d_wb")
     return (out if fp32 else None), codes_out
+
+
+def dybit_quantize_rows(x: torch.Tensor, bits: int, signed: bool, stream=None):
+    """x: [rows][cols] float32.  Returns (scales [rows], codes [rows][cols*bits/8]): every row encoded under
+    its own max-abs scale."""
+    assert x.dtype == torch.float32 and x.dim() == 2
+    rows, cols = x.shape
+    scales = torch.empty(rows, dtype=torch.float32, device=x.device)
+    codes = torch.empty((rows, cols * bits // 8), dtype=torch.uint8, device=x.device)
+    _check(lib().dybit_quantize_rows(_ptr(x), rows, cols, fmt(bits, signed), _ptr(scales), _ptr(codes), _stream(stream)),
+           "dybit_quantize_rows")
+    return scales, codes
+
+
+def dybit_gemm_pc(M: int, N: int, K: int, a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scales,
+                  bias=None, residual=None, relu: bool = False, absmax=None, c_fmt=None, c_scale=None,
+                  fp32: bool = True, out: torch.Tensor | None = None, ldc: int | None = None, stream=None):
+    """The matrix product with one weight scale per output column (w_scales: N floats).  With c_fmt and
+    c_scale the results are also (or, fp32=False, only) written back as codes.  Returns (C or None, codes or None)."""
+    if ldc is None:
+        ldc = N
+    if fp32 and out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=a_scale.device)
+    codes = None
+    if c_fmt is not None:
+        codes = torch.empty((M, N * c_fmt[0] // 8), dtype=torch.uint8, device=a_scale.device)
+    _check(lib().dybit_gemm_pc(M, N, K, _ptr(a_codes), fmt(*a_fmt), _ptr(a_scale),
+                               _ptr(w_codes), fmt(*w_fmt), _ptr(w_scales), _ptr(bias), _ptr(residual), int(bool(relu)),
+                               _ptr(out if fp32 else None), ldc, _ptr(absmax),
+                               fmt(*(c_fmt or (8, False))), _ptr(c_scale), _ptr(codes), _stream(stream)), "dybit_gemm_pc")
+    return (out if fp32 else None), codes
+
+
+def dybit_conv2d_pc(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: int, stride: int, pad: int,
+                    x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scales,
+                    bias=None, residual=None, relu: bool = False, absmax=None, y_fmt=None, y_scale=None,
+                    fp32: bool = True, out: torch.Tensor | None = None, stream=None):
+    """The convolution with one weight scale per output channel (w_scales: Cout floats); see dybit_gemm_pc."""
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    if fp32 and out is None:
+        out = torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device=x_scale.device)
+    codes = None
+    if y_fmt is not None:
+        codes = torch.empty((B, Ho, Wo, Cout * y_fmt[0] // 8), dtype=torch.uint8, device=x_scale.device)
+    _check(lib().dybit_conv2d_pc(B, H, W, Cin, Cout, kh, kw, stride, pad,
+                                 _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
+                                 _ptr(w_codes), fmt(*w_fmt), _ptr(w_scales), _ptr(bias), _ptr(residual), int(bool(relu)),
+                                 _ptr(out if fp32 else None), _ptr(absmax),
+                                 fmt(*(y_fmt or (8, False))), _ptr(y_scale), _ptr(codes), _stream(stream)), "dybit_conv2d_pc")
+    return (out if fp32 else None), codes
 
 
 def dybit_scale_from_absmax(absmax: torch.Tensor, bits: int, signed: bool, out: torch.Tensor | None = None, stream=None):

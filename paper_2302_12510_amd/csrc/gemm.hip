@@ -457,6 +457,7 @@ struct Epilogue {
     dybit_fmt q_fmt{0, 0};
     const float *q_scale = nullptr;
     uint8_t *q_out = nullptr;
+    bool w_per_channel = false;      // w_scale holds one value per output column
 };
 
 // Checks the epilogue against the output shape and fills the matching fields of g.
@@ -464,6 +465,7 @@ struct Epilogue {
 dybit_status set_epilogue(GemmArgs &g, const Epilogue &e, float *C, int64_t ldc)
 {
     g.bias = e.bias; g.relu = e.relu; g.residual = e.residual;
+    g.w_per_channel = e.w_per_channel ? 1 : 0;
     g.absmax_bits = reinterpret_cast<uint32_t *>(e.absmax);
     g.C = C; g.ldc = ldc;
     if (!e.has_codes) return C ? DYBIT_OK : DYBIT_ERR_NULL;
@@ -630,5 +632,32 @@ extern "C" dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t
     e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = y_absmax;
     e.has_codes = true; e.q_fmt = y_fmt; e.q_scale = y_scale; e.q_out = Y_codes;
     return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, e, Y, stream);
+}
+
+extern "C" dybit_status dybit_gemm_pc(int64_t M, int64_t N, int64_t K,
+                                      const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                                      const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scales,
+                                      const float *bias, const float *residual, int32_t relu,
+                                      float *C, int64_t ldc, float *c_absmax,
+                                      dybit_fmt c_fmt, const float *c_scale, uint8_t *C_codes, dybit_stream stream)
+{
+    Epilogue e;
+    e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = c_absmax; e.w_per_channel = true;
+    e.has_codes = C_codes != nullptr; e.q_fmt = c_fmt; e.q_scale = c_scale; e.q_out = C_codes;
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scales, e, C, ldc, stream);
+}
+
+extern "C" dybit_status dybit_conv2d_pc(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                        int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                        const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                        const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scales,
+                                        const float *bias, const float *residual, int32_t relu,
+                                        float *Y, float *y_absmax,
+                                        dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream)
+{
+    Epilogue e;
+    e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = y_absmax; e.w_per_channel = true;
+    e.has_codes = Y_codes != nullptr; e.q_fmt = y_fmt; e.q_scale = y_scale; e.q_out = Y_codes;
+    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scales, e, Y, stream);
 }
 #endif   // plain build

@@ -21,6 +21,7 @@ struct GemmArgs {
     const uint8_t *A, *W;            // packed codes, K-contiguous rows (conv: NHWC image / [Cout][kh][kw][Cin])
     int a_signed, w_signed;
     const float *a_scale, *w_scale, *bias;
+    int w_per_channel;               // 0: *w_scale is the scale of the whole tensor; 1: w_scale[n] per output column n
     const float *residual;           // optional: fp32 tensor laid out like C (same ldc), added before the ReLU
     int relu;
     uint32_t *absmax_bits;           // optional: running max |C| of the written values, as float bits (atomic max)

@@ -376,6 +376,41 @@ __global__ void quantize_tail_kernel(const float *__restrict__ x, size_t first, 
     for (int b = 0; b < nbytes; ++b) out[byte0 + b] = (uint8_t)(w >> (8 * b));
 }
 
+// Row-wise (per-output-channel) max-abs scale and codes of a weight matrix: one workgroup per row,
+// first the row's maximum, then the exact encoder on every element.  Weight tensors are small and
+// are encoded once, so this kernel is written for clarity: a thread produces whole bytes (8-bit: one
+// code, 4-bit: two, 2-bit: four, 6-bit: four codes in three bytes).
+template <int BITS, bool SIGNED>
+__global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const float *__restrict__ x, int64_t cols, float inv_vmax,
+                                                                 float *__restrict__ scales, uint8_t *__restrict__ out)
+{
+    constexpr int EPG = BITS == 8 ? 1 : BITS == 4 ? 2 : 4;             // elements per group of whole bytes
+    constexpr int BPG = BITS == 6 ? 3 : 1;
+    const float *row = x + (int64_t)blockIdx.x * cols;
+    uint8_t *orow = out + (int64_t)blockIdx.x * (cols * BITS / 8);
+    float mx = 0.0f;
+    for (int64_t i = threadIdx.x; i < cols; i += kThreads) mx = fmaxf(mx, fabsf(row[i]));
+    __shared__ float wave_max[kThreads / 64];
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+    const float s = (mx == 0.0f) ? 1.0f : mx * inv_vmax;               // as dybit_absmax_scale
+    if (threadIdx.x == 0) scales[blockIdx.x] = s;
+    const uint32_t e = (__float_as_uint(s) >> 23) & 0xffu;
+    if (!(s > 0.0f) || e == 0u || e == 255u) {                         // an infinite or subnormal maximum: no codes
+        if (threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        return;
+    }
+    for (int64_t gi = threadIdx.x; gi < cols / EPG; gi += kThreads) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int k = 0; k < EPG; ++k) w |= quantize_exact<BITS, SIGNED>(row[gi * EPG + k], s) << (k * BITS);
+#pragma unroll
+        for (int b = 0; b < BPG; ++b) orow[gi * BPG + b] = (uint8_t)(w >> (8 * b));
+    }
+}
+
 // ---------------------------------------------------------------------------
 // dequantize
 // ---------------------------------------------------------------------------
@@ -525,6 +560,28 @@ extern "C" dybit_status dybit_quantize_absmax(const float *x, size_t n, dybit_fm
         case 16: DYBIT_Q(8, false); break;  case 17: DYBIT_Q(8, true); break;
     }
 #undef DYBIT_Q
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_quantize_rows(const float *x, int64_t rows, int64_t cols, dybit_fmt f, float *scales_out,
+                                            uint8_t *codes_out, dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (rows < 0 || cols < 0 || rows > 0x7fffffff) return DYBIT_ERR_INVALID_ARG;
+    if ((cols * f.bits) % 8) return DYBIT_ERR_ALIGNMENT;
+    if (rows == 0) return DYBIT_OK;
+    if (!scales_out || ((!x || !codes_out) && cols)) return DYBIT_ERR_NULL;
+    const float inv_vmax = 1.0f / (float)(1u << (mag_bits(f.bits, f.is_signed) - 1));
+#define DYBIT_QR(B, S) hipLaunchKernelGGL((quantize_rows_kernel<B, S>), dim3((unsigned)rows), dim3(kThreads), 0, (hipStream_t)stream, \
+                                          x, cols, inv_vmax, scales_out, codes_out)
+    switch (f.bits * 2 + f.is_signed) {
+        case 4: DYBIT_QR(2, false); break;   case 5: DYBIT_QR(2, true); break;
+        case 8: DYBIT_QR(4, false); break;   case 9: DYBIT_QR(4, true); break;
+        case 12: DYBIT_QR(6, false); break;  case 13: DYBIT_QR(6, true); break;
+        case 16: DYBIT_QR(8, false); break;  case 17: DYBIT_QR(8, true); break;
+    }
+#undef DYBIT_QR
     return launch_status();
 }
 

@@ -1,4 +1,5 @@
 // Epilogue shared by the tiled matrix-product kernels: C = acc * (sA sW) (+ bias) (+ residual) (ReLU),
+// sW the scale of the weight tensor or of the output column's weight row (g.w_per_channel),
 // optional running maximum of |C|, optional write-back of C as DyBit codes (Sec. III-B), for the
 // 32-row strip of accumulator blocks one wave holds.
 //
@@ -62,6 +63,7 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
         bool n_ok; int64_t n;
         const uint32_t off0 = first_offset(j, n_ok, n);
         const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
+        const float al = g.w_per_channel ? alpha * g.w_scale[n_ok ? n : 0] : alpha;
         float (&res)[16] = res2[PREFETCH ? (j & 1) : 0];
         if (HAS_RES && !PREFETCH) load_shortcut(off0, res);
         if (PREFETCH && j + 1 < CB) {
@@ -71,7 +73,7 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
         uint32_t off = off0;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            float c = acc[j][v] * alpha + b;
+            float c = acc[j][v] * al + b;
             if (HAS_RES) c += res[v];
             if (g.relu) c = fmaxf(c, 0.0f);
             __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c), rsrc, off, 0, 2);
@@ -129,6 +131,7 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
         const int64_t n = n0 + j * 32 + col;
         const bool n_ok = n < g.N;
         const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
+        const float al = g.w_per_channel ? alpha * g.w_scale[n_ok ? n : 0] : alpha;
         const uint32_t off0 = (n_ok ? (uint32_t)n * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
         const PackSlot slot = pack_slot<BITS>(lane, (uint32_t)n);
         uint32_t qoff = ((n_ok && slot.stores && rqp.ok) ? slot.byte_off : 0x80000000u) + (uint32_t)(4 * kq) * qrow;
@@ -156,7 +159,7 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
 #pragma unroll
             for (int u = 0; u < GV; ++u) {                                   // phase 1
                 const int v = h + u;
-                c[u] = acc[j][v] * alpha + b;
+                c[u] = acc[j][v] * al + b;
                 if (HAS_RES) c[u] += res[u];
                 c[u] = fmaxf(c[u], relu_floor);
                 __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c[u]), rsrc, off, 0, 2);
@@ -204,7 +207,7 @@ __device__ __forceinline__ float epilogue_strip(const GemmArgs &g, const fast::f
                                                const int64_t m_strip, const int64_t n0)
 {
     const int lane = threadIdx.x & 63, kq = lane >> 5;
-    const float alpha = (*g.a_scale) * (*g.w_scale);
+    const float alpha = g.w_per_channel ? *g.a_scale : (*g.a_scale) * (*g.w_scale);   // per channel: sW[n] joins per column
     const int64_t rows_left = g.M - m_strip;                       // uniform over the wave
     const int rows = rows_left >= 32 ? 32 : rows_left > 0 ? (int)rows_left : 0;
     float mx = 0.0f;
@@ -227,11 +230,12 @@ __device__ __forceinline__ float epilogue_strip(const GemmArgs &g, const fast::f
             const int64_t n = n0 + j * 32 + (lane & 31);
             const bool n_ok = n < g.N;
             const float b = (g.bias && n_ok) ? g.bias[n] : 0.0f;
+            const float al = g.w_per_channel ? alpha * g.w_scale[n_ok ? n : 0] : alpha;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int r = 8 * (v >> 2) + 4 * kq + (v & 3);
                 if (n_ok && r < rows) {
-                    float c = acc[j][v] * alpha + b;
+                    float c = acc[j][v] * al + b;
                     if (g.residual) c += g.residual[(m_strip + r) * g.ldc + n];
                     if (g.relu) c = fmaxf(c, 0.0f);
                     __builtin_nontemporal_store(c, g.C + (m_strip + r) * g.ldc + n);

@@ -18,6 +18,10 @@ convolution whose consumers agree on a format encodes its results in its own epi
 shortcut, a pooling or the network output needs it, and no pass over an fp32 tensor remains except
 behind the pooling layers.
 
+`per_channel=True` gives every output channel of every layer its own weight scale (row-wise max-abs,
+dybit_quantize_rows; the convolutions then run through dybit_conv2d_pc); activations keep one scale
+per tensor.
+
 Formats: weights are signed; an activation tensor is unsigned when it is the output of a
 ReLU or of a pooling of such outputs, signed otherwise (the network input).  Layer-wise
 bitwidths come from a table {layer name: (bits_W, bits_A)}, as the search of Sec. III-C
@@ -59,8 +63,9 @@ def _pad_few_channels(cin: int, kh: int, kw: int, bits_a: int, bits_w: int):
 
 
 class DybitNetwork:
-    def __init__(self, layers, weights, bitwidths, device="cuda", epilogue_absmax=True):
+    def __init__(self, layers, weights, bitwidths, device="cuda", epilogue_absmax=True, per_channel=False):
         self.layers = layers
+        self.per_channel = per_channel           # True: one weight scale per output channel (dybit_quantize_rows, dybit_conv2d_pc)
         self.epilogue_absmax = epilogue_absmax   # False: every scale from a pass over the fp32 tensor
         self.bitwidths = bitwidths
         self.device = device
@@ -77,8 +82,12 @@ class DybitNetwork:
                 wp = np.zeros((cout, khp, kwp, cpad), dtype=np.float32)
                 wp[:, :kh, :kw, :cin] = w
                 wd = torch.from_numpy(wp).to(device).reshape(-1)
-                sw = B.dybit_absmax_scale(wd, *w_fmt)          # zero padding changes neither the scale nor a code
-                return {"w_fmt": w_fmt, "w_scale": sw, "w_codes": B.dybit_quantize(wd, sw, *w_fmt),
+                if per_channel:
+                    sw, wq = B.dybit_quantize_rows(wd.reshape(cout, -1), *w_fmt)
+                else:
+                    sw = B.dybit_absmax_scale(wd, *w_fmt)      # zero padding changes neither the scale nor a code
+                    wq = B.dybit_quantize(wd, sw, *w_fmt)
+                return {"w_fmt": w_fmt, "w_scale": sw, "w_codes": wq,
                         "bias": torch.from_numpy(b).to(device), "cin": cin, "cpad": cpad, "cout": cout,
                         "k": khp, "kw": kwp, "a_bits": ba}
 
@@ -184,13 +193,15 @@ class DybitNetwork:
                 conv_args = (Bn, H, W, p["cpad"], p["cout"], k, p["kw"], stride, pad,
                              qa, a_fmt, sa, p["w_codes"], p["w_fmt"], p["w_scale"])
                 shortcut = acts[l["add"]] if l.get("add") else None
+                word = None
                 if self.epilogue_absmax:
                     word = max_words[next_word:next_word + 1]
                     next_word += 1
-                    y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu, word)
                     known_max[name] = word
+                if self.per_channel:
+                    y, _ = B.dybit_conv2d_pc(*conv_args, p["bias"], shortcut, relu, word)
                 else:
-                    y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu)
+                    y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu, word)
                 if record is not None:
                     record(name, {"x": src, "a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "y": y, "shortcut": shortcut,
                                   "relu": relu, "stride": stride, "pad": pad, "k": k, **p})
@@ -235,9 +246,15 @@ class DybitNetwork:
                 y_codes = None
                 if plan["fmt"] is not None:
                     y_scale = self.static_scale[plan["scale_of"]]
-                    y, y_codes = B.dybit_conv2d_wb(*conv_args, plan["fmt"], y_scale, p["bias"], shortcut, relu,
-                                                   fp32=plan["fp32"])
+                    if self.per_channel:
+                        y, y_codes = B.dybit_conv2d_pc(*conv_args, p["bias"], shortcut, relu, None, plan["fmt"], y_scale,
+                                                       fp32=plan["fp32"])
+                    else:
+                        y, y_codes = B.dybit_conv2d_wb(*conv_args, plan["fmt"], y_scale, p["bias"], shortcut, relu,
+                                                       fp32=plan["fp32"])
                     codes[name] = (plan["fmt"], y_scale, y_codes)
+                elif self.per_channel:
+                    y, _ = B.dybit_conv2d_pc(*conv_args, p["bias"], shortcut, relu)
                 else:
                     y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu)
                 if record is not None:

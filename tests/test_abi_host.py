@@ -201,3 +201,24 @@ def test_search_argument_errors():
     neg = e.copy(); neg[2, 1] = -1e-9
     assert call(ea=neg) == B.ERR_INVALID_ARG
     assert call(ew=np.zeros((n, 3)), ea=np.zeros((n, 3)), strat=1) == B.ERR_INVALID_ARG     # zero error at (8, 8)
+
+
+def test_per_channel_argument_errors_without_gpu():
+    L = B.lib()
+    f4, f6, bad = B.fmt(4, True), B.fmt(6, True), B.fmt(5, True)
+    p, null = C.c_void_p(0x1000), C.c_void_p(0)
+    assert L.dybit_quantize_rows(p, 4, 16, bad, p, p, None) == B.ERR_UNSUPPORTED_BITS
+    assert L.dybit_quantize_rows(p, -1, 16, f4, p, p, None) == B.ERR_INVALID_ARG
+    assert L.dybit_quantize_rows(p, 4, 3, f4, p, p, None) == B.ERR_ALIGNMENT          # a row of 12 bits
+    assert L.dybit_quantize_rows(p, 4, 6, f6, p, p, None) == B.ERR_ALIGNMENT          # a row of 36 bits
+    assert L.dybit_quantize_rows(p, 4, 16, f4, null, p, None) == B.ERR_NULL
+    assert L.dybit_quantize_rows(null, 4, 16, f4, p, p, None) == B.ERR_NULL
+    assert L.dybit_quantize_rows(null, 0, 16, f4, null, null, None) == B.OK
+    pc = lambda w=p, c=p, cc=null, cf=f4: L.dybit_gemm_pc(8, 8, 16, p, f4, p, p, f4, w, null, null, 0, c, 8, null, cf, p, cc, None)
+    assert pc(w=null) == B.ERR_NULL
+    assert pc(c=null) == B.ERR_NULL                                                    # no codes asked for: fp32 output required
+    assert pc(cc=p, cf=B.fmt(2, True)) == B.ERR_UNSUPPORTED_BITS
+    assert pc(cc=p, cf=f6) == B.ERR_ALIGNMENT
+    assert L.dybit_conv2d_pc(1, 8, 8, 16, 8, 3, 3, 1, 1, p, f4, p, p, f4, null, null, null, 0, p, null,
+                             f4, p, null, None) == B.ERR_NULL
+
