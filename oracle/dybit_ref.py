@@ -389,6 +389,43 @@ def conv2d(x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, stride, pad,
     return c.reshape(B, Ho, Wo, Cout), d.reshape(B, Ho, Wo, Cout)
 
 
+def dwconv2d(x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, stride, pad, bias=None, relu=False):
+    """Depthwise convolution (the layer type of the depthwise-separable network of Sec. IV): every
+    channel is filtered on its own,
+        Y[b,ho,wo,c] = sA*sW * sum_{r,s} value(X[b, ho*stride-pad+r, wo*stride-pad+s, c]) * value(Wt[r,s,c])
+                       (+ bias[c]) (ReLU),
+    taps outside the image contributing 0.  x_codes [B][H][W][C], w_codes [kh][kw][C] (unpacked
+    codes, channel innermost like the image).  Exact integer sums as in gemm.
+    Returns (Y float64 [B][Ho][Wo][C], D same shape: the tolerance denominator)."""
+    x_codes = np.asarray(x_codes, dtype=np.uint8)
+    w_codes = np.asarray(w_codes, dtype=np.uint8)
+    B, H, W, C = x_codes.shape
+    kh, kw, C2 = w_codes.shape
+    assert C == C2
+    Ho = conv_out_size(H, kh, stride, pad)
+    Wo = conv_out_size(W, kw, stride, pad)
+    ix = np.zeros((B, H + 2 * pad, W + 2 * pad, C), dtype=np.float64)
+    ix[:, pad:pad + H, pad:pad + W, :] = _decode_scaled_int(x_codes, *x_fmt)
+    iw = _decode_scaled_int(w_codes, *w_fmt)
+    acc = np.zeros((B, Ho, Wo, C), dtype=np.float64)
+    den = np.zeros((B, Ho, Wo, C), dtype=np.float64)
+    for r in range(kh):
+        for q in range(kw):
+            win = ix[:, r:r + stride * Ho:stride, q:q + stride * Wo:stride, :]
+            acc += win * iw[r, q, :]
+            den += np.abs(win) * np.abs(iw[r, q, :])
+    unit = float(np.float64(np.float32(x_scale)) * np.float64(np.float32(w_scale))) \
+        * 2.0 ** (-(magnitude_bits(*x_fmt) - 1) - (magnitude_bits(*w_fmt) - 1))
+    y, d = acc * unit, den * unit
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float32).astype(np.float64)
+        y = y + b
+        d = d + np.abs(b)
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y, d
+
+
 # --------------------------------------------------------------------------
 # Quantization error metric (Eq. 2)
 # --------------------------------------------------------------------------

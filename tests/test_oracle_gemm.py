@@ -166,3 +166,33 @@ def test_quantize_rows_is_row_by_row():
     assert s[3] == 1.0 and not q[3].any()
     # every row uses the whole code range: its largest magnitude is the all-ones code
     assert all((q[i] & 7).max() == 7 for i in (0, 1, 2, 4, 5))
+
+
+@pytest.mark.parametrize("stride,pad,kh,kw", [(1, 1, 3, 3), (2, 1, 3, 3), (1, 0, 1, 1), (2, 2, 5, 3), (1, 2, 3, 5)])
+def test_dwconv2d_pins(stride, pad, kh, kw):
+    """Depthwise convolution against (a) torch's grouped conv2d in float64 over the decoded tensors and
+    (b) the dense oracle convolution with a filter that is zero wherever the two channels differ."""
+    rng = np.random.default_rng(31 + kh)
+    x_fmt, w_fmt = (4, False), (8, True)
+    B, H, W, C = 2, 9, 7, 6
+    x = _codes(rng, (B, H, W, C), x_fmt)
+    w = _codes(rng, (kh, kw, C), w_fmt)
+    bias = rng.normal(0, 1, C).astype(np.float32)
+    sx, sw = np.float32(0.25), np.float32(0.5)
+    y, d = R.dwconv2d(x, x_fmt, sx, w, w_fmt, sw, stride, pad, bias, relu=True)
+    vx = torch.from_numpy(R.codebook(*x_fmt)[x] * float(sx)).permute(0, 3, 1, 2)
+    vw = torch.from_numpy(R.codebook(*w_fmt)[w] * float(sw)).permute(2, 0, 1).unsqueeze(1)      # [C][1][kh][kw]
+    want = torch.nn.functional.conv2d(vx, vw, torch.from_numpy(bias.astype(np.float64)), stride=stride,
+                                      padding=pad, groups=C).clamp_min(0).permute(0, 2, 3, 1).numpy()
+    assert y.shape == want.shape
+    assert np.allclose(y, want, rtol=1e-13, atol=1e-13)
+    dense = np.zeros((C, kh, kw, C), dtype=np.uint8)
+    for c in range(C):
+        dense[c, :, :, c] = w[:, :, c]
+    y2, d2 = R.conv2d(x, x_fmt, sx, dense, w_fmt, sw, stride, pad, bias, relu=True)
+    assert np.array_equal(y, y2) and np.array_equal(d, d2)
+    # one non-zero input and one non-zero tap: the product lands at the pixel the geometry says, in its own channel
+    x1 = np.zeros((1, 6, 6, 3), np.uint8); w1 = np.zeros((3, 3, 3), np.uint8)
+    x1[0, 2, 3, 1] = 8; w1[0, 2, 1] = 8                           # value 1 in both 4-bit unsigned formats
+    y1, _ = R.dwconv2d(x1, (4, False), 1.0, w1, (4, False), 1.0, 1, 1)
+    assert np.count_nonzero(y1) == 1 and y1[0, 3, 2, 1] == 1.0    # ho = hi + pad - r = 2 + 1 - 0, wo = 3 + 1 - 2
