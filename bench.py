@@ -50,7 +50,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed steps; the device needs a few tens of milliseconds of load to settle its clocks")
-    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1", "cfg3", "cfg4", "modes", "search"],
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg1", "cfg3", "cfg4", "modes", "search", "dwconv"],
                     help="cfg5 (default): 8192^3 GEMM + 2^28 quantize; cfg1 / cfg2: the small GEMM and the "
                          "convolution; cfg3 / cfg4: one forward pass of the ResNet-18 / ResNet-50 chains")
     ap.add_argument("--network", default="resnet18", choices=["resnet18", "resnet50"], help="network of --workload search")
@@ -131,6 +131,43 @@ def bench_modes(args):
                       "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
                       "config": {"workload": "mode matrix: GEMM M=N=K=%d on the config 5 tensors, W and A signed" % size},
                       "modes": table}))
+
+
+def bench_dwconv(args):
+    """Depthwise 3 x 3 convolutions of the depthwise-separable network of Sec. IV (MobileNetV2 shapes, batch
+    64): absmax-scaled 4-bit unsigned activations, 4-bit signed filters.  HBM-bound: bytes = codes read +
+    fp32 results written.  One JSON line."""
+    import torch
+    from paper_2302_12510_amd import binding as B
+    from paper_2302_12510_amd import synth
+
+    torch.cuda.set_device(0)
+    B.lib()
+    rows = []
+    for (hw, c, stride) in ((112, 96, 2), (56, 144, 1), (28, 192, 1), (14, 576, 1), (7, 960, 1)):
+        x = torch.from_numpy(synth.half_normal((64, hw, hw, c), 1.0, seed=1)).cuda().reshape(-1)
+        w = torch.from_numpy(synth.kaiming_normal((3, 3, c), 9, seed=2)).cuda().reshape(-1)
+        sx = B.dybit_absmax_scale(x, 4, False)
+        qx = B.dybit_quantize(x, sx, 4, False)
+        sw = B.dybit_absmax_scale(w, 4, True)
+        qw = B.dybit_quantize(w, sw, 4, True)
+        ho = (hw + 2 - 3) // stride + 1
+        y = torch.empty((64, ho, ho, c), dtype=torch.float32, device="cuda")
+        ms, _ = time_events(lambda: B.dybit_dwconv2d(64, hw, hw, c, 3, 3, stride, 1, qx, (4, False), sx, qw, (4, True), sw,
+                                                     None, True, None, out=y), args.steps, args.warmup, torch)
+        byts = qx.numel() + qw.numel() + 4 * y.numel()
+        rows.append({"shape": "64x%dx%dx%d stride %d" % (hw, hw, c, stride), "kernel_ms": round(ms, 4),
+                     "GBps": round(byts / (ms * 1e-3) / 1e9, 1), "frac_of_8TBps": round(byts / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                     "GMACps": round(9.0 * y.numel() / (ms * 1e-3) / 1e9, 1)})
+        del x, y, qx
+    assert B.dybit_get_last_async_error() == B.OK
+    best = max(rows, key=lambda r: r["GBps"])
+    print(json.dumps({"metric": "DyBit depthwise convolution GB/s", "value": best["GBps"], "unit": "GB/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": "depthwise 3x3 convolutions, MobileNetV2 shapes, batch 64, W 4-bit signed, A 4-bit unsigned"},
+                      "roofline": {"bound": "hbm", "kernel": "dybit dwconv_kernel", "achieved": best["GBps"], "peak": PEAK_HBM_GBPS,
+                                   "unit": "GB/s", "frac": best["frac_of_8TBps"], "traffic": None, "shape": best["shape"]},
+                      "layers": rows}))
 
 
 def bench_search(args):
@@ -326,6 +363,8 @@ def main():
         return bench_modes(args)
     if args.workload == "search":
         return bench_search(args)
+    if args.workload == "dwconv":
+        return bench_dwconv(args)
     import torch
     from paper_2302_12510_amd import binding as B
     from paper_2302_12510_amd import synth

@@ -211,6 +211,22 @@ dybit_status dybit_conv2d_pc(int64_t B, int64_t H, int64_t W, int64_t Cin, int64
                              float *Y, float *y_absmax,
                              dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream);
 
+/* Depthwise convolution (the layer type of the depthwise-separable network of Sec. IV): every channel is
+ * filtered on its own,
+ *     Y[b][ho][wo][c] = sX*sW * sum_{r,s} x[b][ho*stride-pad+r][wo*stride-pad+s][c] * w[r][s][c] (+ bias[c]) (ReLU),
+ * taps outside the image contributing 0.
+ * X_codes [device]: [B][H][W][C] codes;  Wt_codes [device]: [kh][kw][C] codes (channel innermost, like the
+ * image); formats of 2, 4 or 8 bits (DYBIT_ERR_UNSUPPORTED_BITS for 6), C * bits a multiple of 32 for both
+ * (DYBIT_ERR_ALIGNMENT), buffers 16-byte aligned.  x_scale, w_scale [device]: 1 float each.
+ * bias [device, may be NULL]: C floats.  Y [device]: [B][Ho][Wo][C] floats.  y_absmax [device, may be NULL]:
+ * running maximum as in dybit_gemm_ex.  Filters and strides whose input patch for 8 x 8 outputs exceeds
+ * 64 KiB of floats for 32 channels (e.g. 9 x 9 at stride 4) are refused with DYBIT_ERR_INVALID_ARG. */
+dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t C,
+                            int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                            const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                            const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                            const float *bias, int32_t relu, float *Y, float *y_absmax, dybit_stream stream);
+
 /* *scale_out = *absmax / 2^(m-1), or 1.0 when *absmax == 0: the last step of dybit_absmax_scale,
  * for a maximum obtained otherwise.  absmax, scale_out [device]: 1 float each (may be the same word). */
 dybit_status dybit_scale_from_absmax(const float *absmax, dybit_fmt f, float *scale_out, dybit_stream stream);

@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
         L.dybit_conv2d_wb.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, Fmt, vp, vp, vp]
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
         L.dybit_quantize_rows.argtypes = [vp, i64, i64, Fmt, vp, vp, vp]
+        L.dybit_dwconv2d.argtypes = [i64] * 4 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp, vp]
         L.dybit_gemm_pc.argtypes = L.dybit_gemm_wb.argtypes
         L.dybit_conv2d_pc.argtypes = L.dybit_conv2d_wb.argtypes
         L.dybit_rmse.argtypes = [vp, sz, Fmt, vp, vp, vp]
@@ -296,6 +297,20 @@ def dybit_conv2d_wb(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: in
                                  _ptr(out if fp32 else None), _ptr(absmax),
                                  fmt(*y_fmt), _ptr(y_scale), _ptr(codes_out), _stream(stream)), "dybit_conv2d_wb")
     return (out if fp32 else None), codes_out
+
+
+def dybit_dwconv2d(B: int, H: int, W: int, C: int, kh: int, kw: int, stride: int, pad: int,
+                   x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, bias=None, relu: bool = False, absmax=None,
+                   out: torch.Tensor | None = None, stream=None):
+    """Depthwise convolution: x_codes [B][H][W][C], w_codes [kh][kw][C]; returns Y [B][Ho][Wo][C] float32."""
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = torch.empty((B, Ho, Wo, C), dtype=torch.float32, device=x_scale.device)
+    _check(lib().dybit_dwconv2d(B, H, W, C, kh, kw, stride, pad, _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
+                                _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), int(bool(relu)),
+                                _ptr(out), _ptr(absmax), _stream(stream)), "dybit_dwconv2d")
+    return out
 
 
 def dybit_quantize_rows(x: torch.Tensor, bits: int, signed: bool, stream=None):

@@ -13,6 +13,7 @@ SOURCES = [
     ("host.cpp", "host", []),
     ("quantize.hip", "quantize", []),
     ("metric.hip", "metric", []),
+    ("dwconv.hip", "dwconv", []),
     ("search.cpp", "search", []),
     ("gemm.hip", "gemm", []),
     ("gemm_dispatch.cpp", "gemm_dispatch", []),

@@ -1,0 +1,209 @@
+// Depthwise convolution on DyBit codes for gfx950 (the layer type of the depthwise-separable
+// network of Sec. IV): Y[b,ho,wo,c] = sA sW sum_{r,s} x[b,hi,wi,c] w[r,s,c] (+ bias[c]) (ReLU).
+//
+// Nine multiply-adds per output and no contraction over channels: this is not matrix-core work.
+// It is bound by the fp32 output (4 bytes per result against <= 1 byte of codes read), so the
+// kernel is organised to keep the vector-ALU work per output low enough for the HBM rate:
+// a workgroup owns an 8 x 8 (3 x 3 filter at stride 1: 8 x 16) patch of output pixels and 32 channels; it decodes the input patch
+// (with its halo) and the filter taps of those channels ONCE into LDS as floats, then every thread
+// accumulates four neighbouring channels of a pixel with 128-bit LDS reads -- each input code is
+// decoded once per patch (a look-up in a small LDS table of the format's values) instead of once
+// per tap.  The 3 x 3 filters at stride 1 and 2 have kernels of their own with the taps unrolled
+// and held in registers; every other geometry runs the same code with run-time loops.  Image, filter and output are channel-innermost,
+// so global loads (whole 32-bit words of codes) and stores (float4) are contiguous per pixel.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dybit_device.h"
+#include "dybit_host.h"
+#include "gemm_args.h"
+
+namespace dybit {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int TH = 8, CG = 32;                     // rows of the output patch and channel group of a workgroup
+// columns of the output patch: 16 for the 3 x 3 filter at stride 1 (the halo and the fixed work of a
+// workgroup are shared by more outputs), 8 otherwise (a wider input patch would not leave room for
+// several workgroups per compute unit)
+constexpr int patch_width(int kh, int kw, int stride) { return (kh == 3 && kw == 3 && stride == 1) ? 16 : 8; }
+constexpr int kMaxLdsBytes = 64 * 1024;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct DwArgs {
+    const uint32_t *X, *Wt;                        // packed codes, read as whole words
+    const float *x_scale, *w_scale, *bias;
+    float *Y;
+    uint32_t *absmax_bits;
+    int B, H, W, C, Ho, Wo, kh, kw, stride, pad, relu;
+    int a_bits, a_signed, w_bits, w_signed;
+    int in_h, in_w;                                // extent of the input patch, halo included
+    int tiles_h, tiles_w, groups;
+};
+
+// K: filter size when it is square and known at compile time (3), else 0; S: stride (1, 2) or 0.
+// BA, BW: code widths of image and filter (2, 4 or 8).
+template <int BA, int BW, int K, int S>
+__global__ __launch_bounds__(kThreads) void dwconv_kernel(const DwArgs a)
+{
+    constexpr int TW = patch_width(K, K, S);
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int kh = K ? K : a.kh, kw = K ? K : a.kw, stride = S ? S : a.stride;
+    const int in_h = (TH - 1) * stride + kh, in_w = (TW - 1) * stride + kw;
+    float *tile = lds;                                           // [in_h * in_w][CG]
+    float *taps = tile + (size_t)in_h * in_w * CG;               // [kh * kw][CG]
+    float *lut_a = taps + (size_t)kh * kw * CG;                  // value of every code of the two formats
+    float *lut_w = lut_a + (1 << BA);
+    const int tid = threadIdx.x;
+    int id = blockIdx.x;
+    const int cg = id % a.groups; id /= a.groups;
+    const int tw = id % a.tiles_w; id /= a.tiles_w;
+    const int th = id % a.tiles_h;
+    const int b = id / a.tiles_h;
+    const int ho0 = th * TH, wo0 = tw * TW, c_first = cg * CG;
+
+    if (tid < (1 << BA)) lut_a[tid] = code_value(tid, BA, a.a_signed);
+    if (tid < (1 << BW)) lut_w[tid] = code_value(tid, BW, a.w_signed);
+    __syncthreads();
+
+    // ---- stage the input patch: one item = one word of codes of one pixel
+    {
+        constexpr int WPP = CG * BA / 32, CPW = 32 / BA;                  // words per pixel and group, codes per word
+        const int64_t row_words = (int64_t)a.C * BA / 32;                 // words per pixel in the image
+        const int items = in_h * in_w * WPP;
+        for (int it = tid; it < items; it += kThreads) {
+            const int pix = it / WPP, wd = it % WPP;
+            const int iy = pix / in_w, ix = pix - iy * in_w;
+            const int hi = ho0 * stride - a.pad + iy, wi = wo0 * stride - a.pad + ix;
+            const bool in = (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W && c_first + wd * CPW < a.C;
+            const uint32_t word = in ? a.X[(((int64_t)b * a.H + hi) * a.W + wi) * row_words + c_first * BA / 32 + wd] : 0u;
+            float *dst = tile + (size_t)pix * CG + wd * CPW;              // code 0 is 0.0: padding and channels past C
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) dst[j] = lut_a[(word >> (j * BA)) & ((1u << BA) - 1u)];
+        }
+    }
+    // ---- stage the filter taps of the group's channels
+    {
+        constexpr int WPP = CG * BW / 32, CPW = 32 / BW;
+        const int64_t row_words = (int64_t)a.C * BW / 32;
+        const int items = kh * kw * WPP;
+        for (int it = tid; it < items; it += kThreads) {
+            const int tap = it / WPP, wd = it % WPP;
+            const bool in = c_first + wd * CPW < a.C;
+            const uint32_t word = in ? a.Wt[(int64_t)tap * row_words + c_first * BW / 32 + wd] : 0u;
+            float *dst = taps + (size_t)tap * CG + wd * CPW;
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) dst[j] = lut_w[(word >> (j * BW)) & ((1u << BW) - 1u)];
+        }
+    }
+    __syncthreads();
+
+    // ---- accumulate: one item = four neighbouring channels of one output pixel; a thread's two items
+    // share the channels, so with a 3 x 3 filter its taps stay in registers
+    const float alpha = (*a.x_scale) * (*a.w_scale);
+    const int quad = tid & (CG / 4 - 1);
+    float4 wreg[K ? K * K : 1];
+    if (K) {
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) wreg[t] = *reinterpret_cast<const float4 *>(taps + (size_t)t * CG + quad * 4);
+    }
+    float mx = 0.0f;
+#pragma unroll
+    for (int it = tid; it < TH * TW * (CG / 4); it += kThreads) {
+        const int pix = it / (CG / 4);
+        const int py = pix / TW, px = pix % TW;
+        const int ho = ho0 + py, wo = wo0 + px, c = c_first + quad * 4;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        auto tap = [&](const float4 x, const float4 w) {
+            acc.x = fmaf(x.x, w.x, acc.x);
+            acc.y = fmaf(x.y, w.y, acc.y);
+            acc.z = fmaf(x.z, w.z, acc.z);
+            acc.w = fmaf(x.w, w.w, acc.w);
+        };
+        const float *origin = tile + ((size_t)(py * stride) * in_w + px * stride) * CG + quad * 4;
+        if (K) {
+#pragma unroll
+            for (int r = 0; r < K; ++r)
+#pragma unroll
+                for (int q = 0; q < K; ++q)
+                    tap(*reinterpret_cast<const float4 *>(origin + ((size_t)r * in_w + q) * CG), wreg[r * K + q]);
+        } else {
+            for (int r = 0; r < kh; ++r)
+                for (int q = 0; q < kw; ++q)
+                    tap(*reinterpret_cast<const float4 *>(origin + ((size_t)r * in_w + q) * CG),
+                        *reinterpret_cast<const float4 *>(taps + (size_t)(r * kw + q) * CG + quad * 4));
+        }
+        if (ho < a.Ho && wo < a.Wo && c < a.C) {                  // C is a multiple of 4: a quad is inside or outside
+            float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (a.bias) bv = *reinterpret_cast<const float4 *>(a.bias + c);
+            float4 y = make_float4(acc.x * alpha + bv.x, acc.y * alpha + bv.y, acc.z * alpha + bv.z, acc.w * alpha + bv.w);
+            if (a.relu) y = make_float4(fmaxf(y.x, 0.f), fmaxf(y.y, 0.f), fmaxf(y.z, 0.f), fmaxf(y.w, 0.f));
+            __builtin_nontemporal_store(f32x4{y.x, y.y, y.z, y.w},
+                                        reinterpret_cast<f32x4 *>(a.Y + (((int64_t)b * a.Ho + ho) * a.Wo + wo) * a.C + c));
+            mx = fmaxf(mx, fmaxf(fmaxf(fabsf(y.x), fabsf(y.y)), fmaxf(fabsf(y.z), fabsf(y.w))));
+        }
+    }
+    if (a.absmax_bits) fold_absmax(a.absmax_bits, mx);           // every lane of every wave arrives here
+}
+
+template <int BA, int BW>
+void launch_dw(const DwArgs &a, size_t lds_bytes, hipStream_t st, unsigned blocks)
+{
+    auto go = [&](auto kernel) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), lds_bytes, st, a);
+    };
+    if (a.kh == 3 && a.kw == 3 && a.stride == 1) go(dwconv_kernel<BA, BW, 3, 1>);
+    else if (a.kh == 3 && a.kw == 3 && a.stride == 2) go(dwconv_kernel<BA, BW, 3, 2>);
+    else go(dwconv_kernel<BA, BW, 0, 0>);
+}
+
+}  // namespace
+}  // namespace dybit
+
+using namespace dybit;
+
+extern "C" dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t C,
+                                       int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                       const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                       const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                       const float *bias, int32_t relu, float *Y, float *y_absmax, dybit_stream stream)
+{
+    dybit_status st = check_fmt(x_fmt);
+    if (st == DYBIT_OK) st = check_fmt(w_fmt);
+    if (st != DYBIT_OK) return st;
+    if (x_fmt.bits == 6 || w_fmt.bits == 6) return DYBIT_ERR_UNSUPPORTED_BITS;      // whole codes per 32-bit word only
+    if (B < 0 || H < 1 || W < 1 || C < 0 || kh < 1 || kw < 1 || stride < 1 || pad < 0 || (relu != 0 && relu != 1) ||
+        H > (1 << 24) || W > (1 << 24) || C > (1 << 24) || kh > 64 || kw > 64 || stride > 64)
+        return DYBIT_ERR_INVALID_ARG;
+    if (H + 2 * (int64_t)pad < kh || W + 2 * (int64_t)pad < kw) return DYBIT_ERR_INVALID_ARG;
+    if ((C * x_fmt.bits) % 32 || (C * w_fmt.bits) % 32) return DYBIT_ERR_ALIGNMENT;   // a pixel's codes are whole words
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    const int TW = patch_width(kh, kw, stride);
+    const int in_h = (TH - 1) * stride + kh, in_w = (TW - 1) * stride + kw;
+    const int64_t lds_bytes = ((int64_t)in_h * in_w + (int64_t)kh * kw) * CG * 4 + 4 * ((1 << x_fmt.bits) + (1 << w_fmt.bits));
+    if (lds_bytes > kMaxLdsBytes) return DYBIT_ERR_INVALID_ARG;                    // filter / stride too large for one patch
+    if (B == 0 || C == 0) return DYBIT_OK;
+    if (!x_scale || !w_scale || !X_codes || !Wt_codes || !Y) return DYBIT_ERR_NULL;
+    if (!aligned16(X_codes) || !aligned16(Wt_codes) || !aligned16(Y) || (bias && !aligned16(bias))) return DYBIT_ERR_ALIGNMENT;
+    DwArgs a{};
+    a.X = reinterpret_cast<const uint32_t *>(X_codes); a.Wt = reinterpret_cast<const uint32_t *>(Wt_codes);
+    a.x_scale = x_scale; a.w_scale = w_scale; a.bias = bias; a.Y = Y;
+    a.absmax_bits = reinterpret_cast<uint32_t *>(y_absmax);
+    a.B = (int)B; a.H = (int)H; a.W = (int)W; a.C = (int)C; a.Ho = (int)Ho; a.Wo = (int)Wo;
+    a.kh = kh; a.kw = kw; a.stride = stride; a.pad = pad; a.relu = relu;
+    a.a_bits = x_fmt.bits; a.a_signed = x_fmt.is_signed; a.w_bits = w_fmt.bits; a.w_signed = w_fmt.is_signed;
+    a.in_h = in_h; a.in_w = in_w;
+    a.tiles_h = (int)((Ho + TH - 1) / TH); a.tiles_w = (int)((Wo + TW - 1) / TW); a.groups = (int)((C + CG - 1) / CG);
+    const int64_t blocks = B * a.tiles_h * a.tiles_w * a.groups;
+    if (blocks > 0x7fffffff || B > 0x7fffffff) return DYBIT_ERR_INVALID_ARG;
+    hipStream_t hs = (hipStream_t)stream;
+#define DYBIT_DW(BA, BW) launch_dw<BA, BW>(a, (size_t)lds_bytes, hs, (unsigned)blocks)
+    switch (x_fmt.bits * 16 + w_fmt.bits) {
+        case 0x22: DYBIT_DW(2, 2); break;  case 0x24: DYBIT_DW(2, 4); break;  case 0x28: DYBIT_DW(2, 8); break;
+        case 0x42: DYBIT_DW(4, 2); break;  case 0x44: DYBIT_DW(4, 4); break;  case 0x48: DYBIT_DW(4, 8); break;
+        case 0x82: DYBIT_DW(8, 2); break;  case 0x84: DYBIT_DW(8, 4); break;  case 0x88: DYBIT_DW(8, 8); break;
+    }
+#undef DYBIT_DW
+    return launch_status();
+}

@@ -222,3 +222,18 @@ def test_per_channel_argument_errors_without_gpu():
     assert L.dybit_conv2d_pc(1, 8, 8, 16, 8, 3, 3, 1, 1, p, f4, p, p, f4, null, null, null, 0, p, null,
                              f4, p, null, None) == B.ERR_NULL
 
+
+def test_dwconv_argument_errors_without_gpu():
+    L = B.lib()
+    f4, f6 = B.fmt(4, True), B.fmt(6, True)
+    p, null = C.c_void_p(0x1000), C.c_void_p(0)
+    dw = lambda Cn=32, xf=f4, wf=f4, k=3, st=1, x=p, y=p, bias=null: L.dybit_dwconv2d(
+        1, 8, 8, Cn, k, k, st, 1, x, xf, p, p, wf, p, bias, 0, y, null, None)
+    assert dw(xf=f6) == B.ERR_UNSUPPORTED_BITS and dw(wf=f6) == B.ERR_UNSUPPORTED_BITS
+    assert dw(Cn=4) == B.ERR_ALIGNMENT
+    assert dw(k=9, st=4) == B.ERR_INVALID_ARG
+    assert dw(st=0) == B.ERR_INVALID_ARG
+    assert dw(x=null) == B.ERR_NULL and dw(y=null) == B.ERR_NULL
+    assert dw(bias=C.c_void_p(0x1004)) == B.ERR_ALIGNMENT
+    assert dw(Cn=0) == B.OK
+
