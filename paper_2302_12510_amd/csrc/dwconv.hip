@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "dybit_device.h"
 #include "dybit_host.h"
 #include "gemm_args.h"
@@ -66,81 +68,119 @@ __global__ __launch_bounds__(kThreads) void dwconv_kernel(const DwArgs a)
     if (tid < (1 << BW)) lut_w[tid] = code_value(tid, BW, a.w_signed);
     __syncthreads();
 
-    // ---- stage the input patch: one item = one word of codes of one pixel
+    // Writes the values of the CPW codes of one word to consecutive floats, four at a time.
+    auto expand = [&](uint32_t word, const float *lut, auto bits_tag, float *dst) {
+        constexpr int BITS = decltype(bits_tag)::value, CPW = 32 / BITS;
+#pragma unroll
+        for (int j = 0; j < CPW; j += 4) {
+            f32x4 v;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = lut[(word >> ((j + u) * BITS)) & ((1u << BITS) - 1u)];
+            *reinterpret_cast<f32x4 *>(dst + j) = v;
+        }
+    };
+    // ---- stage the input patch: one item = one word of codes of one pixel (offsets inside one image fit 32 bits)
     {
         constexpr int WPP = CG * BA / 32, CPW = 32 / BA;                  // words per pixel and group, codes per word
-        const int64_t row_words = (int64_t)a.C * BA / 32;                 // words per pixel in the image
+        const int row_words = a.C * BA / 32;                              // words per pixel in the image
+        const uint32_t *image = a.X + (int64_t)b * a.H * a.W * row_words + c_first * BA / 32;
         const int items = in_h * in_w * WPP;
+        const int hi0 = ho0 * stride - a.pad, wi0 = wo0 * stride - a.pad;
         for (int it = tid; it < items; it += kThreads) {
             const int pix = it / WPP, wd = it % WPP;
             const int iy = pix / in_w, ix = pix - iy * in_w;
-            const int hi = ho0 * stride - a.pad + iy, wi = wo0 * stride - a.pad + ix;
+            const int hi = hi0 + iy, wi = wi0 + ix;
             const bool in = (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W && c_first + wd * CPW < a.C;
-            const uint32_t word = in ? a.X[(((int64_t)b * a.H + hi) * a.W + wi) * row_words + c_first * BA / 32 + wd] : 0u;
-            float *dst = tile + (size_t)pix * CG + wd * CPW;              // code 0 is 0.0: padding and channels past C
-#pragma unroll
-            for (int j = 0; j < CPW; ++j) dst[j] = lut_a[(word >> (j * BA)) & ((1u << BA) - 1u)];
+            const uint32_t word = in ? image[(hi * a.W + wi) * row_words + wd] : 0u;
+            expand(word, lut_a, std::integral_constant<int, BA>{}, tile + pix * CG + wd * CPW);   // code 0 is 0.0: padding, channels past C
         }
     }
     // ---- stage the filter taps of the group's channels
     {
         constexpr int WPP = CG * BW / 32, CPW = 32 / BW;
-        const int64_t row_words = (int64_t)a.C * BW / 32;
+        const int row_words = a.C * BW / 32;
         const int items = kh * kw * WPP;
         for (int it = tid; it < items; it += kThreads) {
             const int tap = it / WPP, wd = it % WPP;
             const bool in = c_first + wd * CPW < a.C;
-            const uint32_t word = in ? a.Wt[(int64_t)tap * row_words + c_first * BW / 32 + wd] : 0u;
-            float *dst = taps + (size_t)tap * CG + wd * CPW;
-#pragma unroll
-            for (int j = 0; j < CPW; ++j) dst[j] = lut_w[(word >> (j * BW)) & ((1u << BW) - 1u)];
+            const uint32_t word = in ? a.Wt[tap * row_words + c_first * BW / 32 + wd] : 0u;
+            expand(word, lut_w, std::integral_constant<int, BW>{}, taps + tap * CG + wd * CPW);
         }
     }
     __syncthreads();
 
-    // ---- accumulate: one item = four neighbouring channels of one output pixel; a thread's two items
-    // share the channels, so with a 3 x 3 filter its taps stay in registers
+    // ---- accumulate
     const float alpha = (*a.x_scale) * (*a.w_scale);
-    const int quad = tid & (CG / 4 - 1);
-    float4 wreg[K ? K * K : 1];
-    if (K) {
-#pragma unroll
-        for (int t = 0; t < K * K; ++t) wreg[t] = *reinterpret_cast<const float4 *>(taps + (size_t)t * CG + quad * 4);
-    }
     float mx = 0.0f;
+    auto finish = [&](const f32x4 acc, const f32x4 bv, float *dst) {
+        f32x4 y;
 #pragma unroll
-    for (int it = tid; it < TH * TW * (CG / 4); it += kThreads) {
-        const int pix = it / (CG / 4);
-        const int py = pix / TW, px = pix % TW;
-        const int ho = ho0 + py, wo = wo0 + px, c = c_first + quad * 4;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        auto tap = [&](const float4 x, const float4 w) {
-            acc.x = fmaf(x.x, w.x, acc.x);
-            acc.y = fmaf(x.y, w.y, acc.y);
-            acc.z = fmaf(x.z, w.z, acc.z);
-            acc.w = fmaf(x.w, w.w, acc.w);
-        };
-        const float *origin = tile + ((size_t)(py * stride) * in_w + px * stride) * CG + quad * 4;
-        if (K) {
+        for (int u = 0; u < 4; ++u) {
+            y[u] = acc[u] * alpha + bv[u];
+            if (a.relu) y[u] = fmaxf(y[u], 0.0f);
+            mx = fmaxf(mx, fabsf(y[u]));
+        }
+        __builtin_nontemporal_store(y, reinterpret_cast<f32x4 *>(dst));
+    };
+    if constexpr (K != 0) {
+        // 3 x 3: a thread owns four neighbouring channels of one output column and R consecutive output
+        // rows; the taps stay in registers and the window of input rows slides down, so that an input
+        // row is read from LDS once per thread, not once per output row.
+        constexpr int COLS = TW * (CG / 4), R = TH / (kThreads / COLS);
+        const int col = tid % COLS, quad = col & (CG / 4 - 1), px = col / (CG / 4), py0 = (tid / COLS) * R;
+        const int c = c_first + quad * 4, wo = wo0 + px;
+        f32x4 wreg[K * K], win[K][K];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) wreg[t] = *reinterpret_cast<const f32x4 *>(taps + t * CG + quad * 4);
+        const bool col_ok = wo < a.Wo && c < a.C;                 // C is a multiple of 4: a quad is inside or outside
+        f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+        if (a.bias && col_ok) bv = *reinterpret_cast<const f32x4 *>(a.bias + c);
+        float *dst = a.Y + (((int64_t)b * a.Ho + ho0 + py0) * a.Wo + wo) * a.C + c;
+        const float *origin = tile + ((py0 * S) * in_w + px * S) * CG + quad * 4;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+#pragma unroll
+            for (int r = 0; r < K; ++r) {
+                if (i > 0 && r + S < K) {                         // this input row was the previous output's row r + S
+#pragma unroll
+                    for (int q = 0; q < K; ++q) win[r][q] = win[r + S][q];
+                } else {
+#pragma unroll
+                    for (int q = 0; q < K; ++q)
+                        win[r][q] = *reinterpret_cast<const f32x4 *>(origin + ((i * S + r) * in_w + q) * CG);
+                }
+            }
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int r = 0; r < K; ++r)
 #pragma unroll
                 for (int q = 0; q < K; ++q)
-                    tap(*reinterpret_cast<const float4 *>(origin + ((size_t)r * in_w + q) * CG), wreg[r * K + q]);
-        } else {
-            for (int r = 0; r < kh; ++r)
-                for (int q = 0; q < kw; ++q)
-                    tap(*reinterpret_cast<const float4 *>(origin + ((size_t)r * in_w + q) * CG),
-                        *reinterpret_cast<const float4 *>(taps + (size_t)(r * kw + q) * CG + quad * 4));
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) acc[u] = fmaf(win[r][q][u], wreg[r * K + q][u], acc[u]);
+            if (col_ok && ho0 + py0 + i < a.Ho) finish(acc, bv, dst);
+            dst += (int64_t)a.Wo * a.C;
         }
-        if (ho < a.Ho && wo < a.Wo && c < a.C) {                  // C is a multiple of 4: a quad is inside or outside
-            float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (a.bias) bv = *reinterpret_cast<const float4 *>(a.bias + c);
-            float4 y = make_float4(acc.x * alpha + bv.x, acc.y * alpha + bv.y, acc.z * alpha + bv.z, acc.w * alpha + bv.w);
-            if (a.relu) y = make_float4(fmaxf(y.x, 0.f), fmaxf(y.y, 0.f), fmaxf(y.z, 0.f), fmaxf(y.w, 0.f));
-            __builtin_nontemporal_store(f32x4{y.x, y.y, y.z, y.w},
-                                        reinterpret_cast<f32x4 *>(a.Y + (((int64_t)b * a.Ho + ho) * a.Wo + wo) * a.C + c));
-            mx = fmaxf(mx, fmaxf(fmaxf(fabsf(y.x), fabsf(y.y)), fmaxf(fabsf(y.z), fabsf(y.w))));
+    } else {
+        // any other geometry: one item = four neighbouring channels of one output pixel, run-time loops
+        const int quad = tid & (CG / 4 - 1);
+        for (int it = tid; it < TH * TW * (CG / 4); it += kThreads) {
+            const int pix = it / (CG / 4);
+            const int py = pix / TW, px = pix % TW;
+            const int ho = ho0 + py, wo = wo0 + px, c = c_first + quad * 4;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            const float *origin = tile + ((py * stride) * in_w + px * stride) * CG + quad * 4;
+            for (int r = 0; r < kh; ++r)
+                for (int q = 0; q < kw; ++q) {
+                    const f32x4 x = *reinterpret_cast<const f32x4 *>(origin + (r * in_w + q) * CG);
+                    const f32x4 w = *reinterpret_cast<const f32x4 *>(taps + (r * kw + q) * CG + quad * 4);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) acc[u] = fmaf(x[u], w[u], acc[u]);
+                }
+            if (ho < a.Ho && wo < a.Wo && c < a.C) {
+                f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+                if (a.bias) bv = *reinterpret_cast<const f32x4 *>(a.bias + c);
+                finish(acc, bv, a.Y + (((int64_t)b * a.Ho + ho) * a.Wo + wo) * a.C + c);
+            }
         }
     }
     if (a.absmax_bits) fold_absmax(a.absmax_bits, mx);           // every lane of every wave arrives here
@@ -183,6 +223,8 @@ extern "C" dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t 
     const int in_h = (TH - 1) * stride + kh, in_w = (TW - 1) * stride + kw;
     const int64_t lds_bytes = ((int64_t)in_h * in_w + (int64_t)kh * kw) * CG * 4 + 4 * ((1 << x_fmt.bits) + (1 << w_fmt.bits));
     if (lds_bytes > kMaxLdsBytes) return DYBIT_ERR_INVALID_ARG;                    // filter / stride too large for one patch
+    if (H * W * (C * x_fmt.bits / 32) > 0x7fffffff || (int64_t)kh * kw * (C * w_fmt.bits / 32) > 0x7fffffff)
+        return DYBIT_ERR_INVALID_ARG;                                              // offsets inside one image are 32-bit
     if (B == 0 || C == 0) return DYBIT_OK;
     if (!x_scale || !w_scale || !X_codes || !Wt_codes || !Y) return DYBIT_ERR_NULL;
     if (!aligned16(X_codes) || !aligned16(Wt_codes) || !aligned16(Y) || (bias && !aligned16(bias))) return DYBIT_ERR_ALIGNMENT;
