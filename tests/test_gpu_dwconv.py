@@ -45,6 +45,24 @@ def test_dwconv_matches_oracle(x_fmt, w_fmt, geom, C):
     assert mx.item() == np.abs(got).max()
 
 
+@pytest.mark.parametrize("shape", [(1, 1, 1, 32), (3, 2, 3, 8), (1, 8, 16, 32), (2, 9, 17, 40), (5, 1, 40, 16)])
+@pytest.mark.parametrize("geom", [(3, 3, 1, 1), (3, 3, 2, 1), (1, 1, 1, 0), (3, 1, 1, 1)])
+def test_dwconv_tiny_and_patch_sized_images(shape, geom):
+    """Images smaller than a patch, exactly one patch, one pixel more than a patch, a single row."""
+    kh, kw, stride, pad = geom
+    Bn, H, W, C = shape
+    if H + 2 * pad < kh or W + 2 * pad < kw:
+        pytest.skip("filter larger than the padded image")
+    rng = np.random.default_rng(H * 100 + W + kh)
+    x_fmt, w_fmt = (8, False), (4, True)
+    qx = random_codes(rng, shape, x_fmt)
+    qw = random_codes(rng, (kh, kw, C), w_fmt)
+    want, den = R.dwconv2d(qx, x_fmt, 0.7, qw, w_fmt, 0.02, stride, pad)
+    got = run(qx, x_fmt, 0.7, qw, w_fmt, 0.02, stride, pad)
+    assert got.shape == want.shape
+    assert_within(got, want, den)
+
+
 def test_dwconv_single_products_land_where_the_geometry_says():
     """One non-zero code in the image and one in the filter, for every tap and several pixels: exact."""
     for (hi, wi, c) in [(0, 0, 0), (5, 9, 17), (8, 15, 31), (8, 0, 40)]:
