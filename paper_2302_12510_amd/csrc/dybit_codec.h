@@ -236,11 +236,13 @@ template <> struct Codec<F4U> {
     {
         // high bytes of 0 .. .875 in steps of .125, then 1, 1.25, 1.5, 1.75, 2, 3, 4, 8 (Table I)
         const u32 alo = 0x36343000u, ahi = 0x3B3A3938u, blo = 0x3F3E3D3Cu, bhi = 0x48444240u;
+        // two 8-entry byte tables indexed by the low three bits; a third permute takes byte i from the
+        // upper table's result where bit 3 of code i is set (selector i + 4), else from the lower one's
         const u32 se = w & 0x07070707u, so = (w >> 4) & 0x07070707u;
-        const u32 me = w & 0x08080808u, mo = w & 0x80808080u;
-        const u32 maske = (me << 5) - (me >> 3), masko = (mo << 1) - (mo >> 7);    // 0xff where bit 3 set
-        const u32 e = (__builtin_amdgcn_perm(bhi, blo, se) & maske) | (__builtin_amdgcn_perm(ahi, alo, se) & ~maske);
-        const u32 o = (__builtin_amdgcn_perm(bhi, blo, so) & masko) | (__builtin_amdgcn_perm(ahi, alo, so) & ~masko);
+        const u32 pick_e = ((w >> 1) & 0x04040404u) | 0x03020100u;
+        const u32 pick_o = ((w >> 5) & 0x04040404u) | 0x03020100u;
+        const u32 e = __builtin_amdgcn_perm(__builtin_amdgcn_perm(bhi, blo, se), __builtin_amdgcn_perm(ahi, alo, se), pick_e);
+        const u32 o = __builtin_amdgcn_perm(__builtin_amdgcn_perm(bhi, blo, so), __builtin_amdgcn_perm(ahi, alo, so), pick_o);
         d[0] = __builtin_amdgcn_perm(0u, e, 0x010c000cu);
         d[1] = __builtin_amdgcn_perm(0u, o, 0x010c000cu);
         d[2] = __builtin_amdgcn_perm(0u, e, 0x030c020cu);
