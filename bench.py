@@ -252,27 +252,32 @@ def bench_network(args):
         name = "cfg4 ResNet-50 forward, batch 128, 224x224; per-layer (W, A) bits drawn from {4,6,8}, seed 0"
     net = DybitNetwork(layers, synth.network_weights(layers, seed=0), bits)
     x = torch.from_numpy(synth.network_input(batch, 224, seed=0)).cuda()
-    for _ in range(args.warmup):
-        net.forward(x)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        net.forward(x)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # a step = one forward pass; the same pass is also recorded into a HIP graph (every launch of the
+    # pass, no host work per launch) and replayed: the faster of the two is the reported step
+    ms_eager = timed(lambda: net.forward(x))
+    graph, _ = net.capture(x)
+    ms_graph = timed(graph.replay)
+    ms = min(ms_eager, ms_graph)
     assert B.dybit_get_last_async_error() == B.OK
     shapes = net.gemm_shapes(batch, 224)
     flops = sum(2.0 * m * n * k for _, m, n, k in shapes)
     # the same network with calibrated (static) scales and the write-back fused into the epilogues
     net.calibrate(x)
-    for _ in range(args.warmup):
-        net.forward(x, static=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        net.forward(x, static=True)
-    torch.cuda.synchronize()
-    ms_static = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_static_eager = timed(lambda: net.forward(x, static=True))
+    graph_static, _ = net.capture(x, static=True)
+    ms_static_graph = timed(graph_static.replay)
+    ms_static = min(ms_static_eager, ms_static_graph)
     assert B.dybit_get_last_async_error() == B.OK
     out = {
         "metric": "DyBit GEMM effective TOPS (+ quantize GB/s), % of roofline",
@@ -280,9 +285,12 @@ def bench_network(args):
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 or e4m3 MFMA inputs by layer (exact), f32 accumulate", "data": "synthetic",
         "config": {"workload": name, "gemms": len(shapes), "GMAC": round(flops / 2e9, 1),
-                   "step": "per layer scale + quantize + conv (bias, shortcut, ReLU and max|result| in the epilogue); pooling in torch"},
+                   "step": "per layer scale + quantize + conv (bias, shortcut, ReLU and max|result| in the epilogue); pooling in torch; "
+                           + ("launched from a HIP graph of the pass" if ms_graph <= ms_eager else "launched call by call")},
+        "launch": {"eager_ms_per_step": round(ms_eager, 4), "hip_graph_replay_ms_per_step": round(ms_graph, 4)},
         "roofline": network_roofline(net.layer_work(batch, 224), ms),
         "fused_write_back": {"ms_per_step": round(ms_static, 4), "TOPS": round(flops / (ms_static * 1e-3) / 1e12, 3),
+                             "eager_ms_per_step": round(ms_static_eager, 4), "hip_graph_replay_ms_per_step": round(ms_static_graph, 4),
                              "step": "scales fixed by a calibration pass; every convolution whose consumers agree on a "
                                      "format writes DyBit codes from its epilogue (dybit_conv2d_wb), fp32 only where a "
                                      "shortcut, a pooling or the output needs it",

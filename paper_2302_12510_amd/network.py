@@ -210,6 +210,22 @@ class DybitNetwork:
             acts[name] = out
         return out.reshape(out.shape[0], -1)
 
+    def capture(self, x: torch.Tensor, static: bool = False):
+        """Records one forward pass over the (fixed) input buffer x into a HIP graph.  Returns
+        (graph, logits): `graph.replay()` reruns every launch of the pass without host work per launch
+        and rewrites `logits` in place; new inputs are copied into x before a replay.  The pass contains
+        kernels only (the library clears its words with small kernels, never with memset nodes)."""
+        side = torch.cuda.Stream()                       # default priority
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                    # warm-up outside the capture: allocator, lazy initialisation
+            for _ in range(2):
+                self.forward(x, static=static)
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            logits = self.forward(x, static=static)
+        return graph, logits
+
     def _forward_static(self, x: torch.Tensor, record=None) -> torch.Tensor:
         if self.static_scale is None:
             raise RuntimeError("calibrate() first: the static chain needs a scale per activation tensor")

@@ -218,3 +218,29 @@ def test_gemm_shape_table_matches_the_workload_description():
     layers = synth.resnet50_layers()
     s50 = DybitNetwork.gemm_shapes(type("S", (), {"layers": layers})(), 128, 224)
     assert len(s50) == 54 and sum(m * nn * k for _, m, nn, k in s50) == pytest.approx(523.4e9, rel=2e-2)
+
+
+@pytest.mark.parametrize("static", [False, True])
+def test_graph_replay_equals_the_eager_pass(static):
+    """A forward pass captured into a HIP graph: every replay, with eager work and synchronisations in
+    between and with a new input copied into the captured buffer, gives the eager pass's logits bit for bit."""
+    layers = synth.resnet18_layers()
+    weights = synth.network_weights(layers, seed=2)
+    net = DybitNetwork(layers, weights, synth.bitwidths_fixed(layers))
+    inputs = [torch.from_numpy(synth.network_input(2, 64, seed=s)).cuda() for s in (5, 6, 7)]
+    if static:
+        net.calibrate(inputs[0])
+    eager = [net.forward(v, static=static).clone() for v in inputs]
+    torch.cuda.synchronize()
+    x = inputs[0].clone()
+    graph, logits = net.capture(x, static=static)
+    for rep in range(2):
+        for v, want in zip(inputs, eager):
+            x.copy_(v)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(logits, want), (rep, static)
+            again = net.forward(v, static=static)                 # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(again, want)
+    assert B.dybit_get_last_async_error() == B.OK
