@@ -101,23 +101,28 @@ __global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_ker
             const int64_t m = m_strip + (lane & 31);
             okA = m < g.M;
             if (CONV) {
-                const int64_t mm = okA ? m : 0;
-                const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
-                const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
-                const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+                // M fits 31 bits (checked at launch): 32-bit divisions, a fraction of the cost of 64-bit ones,
+                // and this set-up runs once per slab, which for a short K is as much work as the K loop
+                const u32 mm = okA ? (u32)m : 0u;
+                const u32 plane = (u32)g.Ho * (u32)g.Wo;
+                const int b = (int)(mm / plane);
+                const int rem = (int)(mm - (u32)b * plane);
+                const int ho = (int)((u32)rem / (u32)g.Wo), wo = rem - ho * g.Wo;
                 hi0 = ho * g.stride - g.pad;
                 wi0 = wo * g.stride - g.pad;
                 if (CONV == ROWS) {
-                    offA = (u32)(int)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes);   // first byte of filter row 0 (may be negative)
-                    const int taps = 32 / g.Cin, tap_bits = g.Cin * CA::BITS;
+                    offA = (u32)(((b * g.H + hi0) * g.Wd + wi0) * pix_bytes);   // first byte of filter row 0 (may be negative); the image is under 2 GiB
+                    const int taps = g.kw, tap_bits = g.Cin * CA::BITS;                       // kw * Cin = 32
                     const int t_lo = max(0, -wi0), t_hi = max(min(taps, g.Wd - wi0), t_lo);
 #pragma unroll
                     for (int i = 0; i < WORDS_A; ++i) {
+                        // bits [lo, up) of word i, 0 <= lo <= up <= 32
                         const int lo = min(max(t_lo * tap_bits - 32 * i, 0), 32), up = min(max(t_hi * tap_bits - 32 * i, 0), 32);
-                        row_keep[i] = (u32)((1ull << up) - 1ull) & ~(u32)((1ull << lo) - 1ull);
+                        const u32 below_up = up >= 32 ? ~0u : (1u << up) - 1u, below_lo = lo >= 32 ? ~0u : (1u << lo) - 1u;
+                        row_keep[i] = below_up & ~below_lo;
                     }
                 } else {
-                    offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);
+                    offA = (u32)(((b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);   // the image is under 2 GiB
                 }
             } else {
                 offA = okA ? (u32)(m * a_row_bytes + kq * RUN_A) : kOob;
@@ -252,7 +257,7 @@ static bool launch(const GemmArgs &g, bool conv, hipStream_t st)
     const int cb = g.N <= 64 ? 2 : 4;
     const int row_bytes = (int)g.K * 2 + 16;
     const int lds_bytes = cb * 32 * row_bytes;
-    if (g.N > 128 || lds_bytes > 160 * 1024) return false;
+    if (g.N > 128 || lds_bytes > 160 * 1024 || g.M > 0x7fffffff) return false;
     const bool rows = conv && g.Cin < 64;                            // kw * Cin = 32 (checked by the dispatcher)
 #define DYBIT_WS_CB(C_) \
     if (rows) launch_cb<FA, FW, ROWS, C_>(g, st, row_bytes, lds_bytes); \
