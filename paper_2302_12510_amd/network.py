@@ -10,6 +10,8 @@ which keeps the maximum), its max|y| is taken in the convolution's epilogue
 (dybit_conv2d_ex + dybit_scale_from_absmax) instead of by a pass over the fp32 tensor; the
 identity shortcut of a residual block is added in the same epilogue, before the ReLU.
 Pooling runs on the fp32 tensors with torch ops; it is glue, not part of the library.
+A layer with op "dwconv" (depthwise convolution, the building block of the depthwise-separable
+network of Sec. IV; filter [kh][kw][C]) runs through dybit_dwconv2d in the dynamic chain.
 
 With `forward(x, static=True)` after a `calibrate(x)` the chain follows the paper's dataflow to
 the letter: the scales of all activation tensors are fixed (those of the calibration input), every
@@ -71,6 +73,15 @@ class DybitNetwork:
         self.device = device
         self.params = {}
         for l in layers:
+            if l["op"] == "dwconv":                  # depthwise: filter [kh][kw][C], one scale for the tensor
+                w, b = weights[l["name"]]
+                bw, ba = bitwidths[l["name"]]
+                wd = torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).to(device).reshape(-1)
+                sw = B.dybit_absmax_scale(wd, bw, True)
+                self.params[l["name"]] = {"w_fmt": (bw, True), "w_scale": sw, "w_codes": B.dybit_quantize(wd, sw, bw, True),
+                                          "bias": torch.from_numpy(b).to(device), "a_bits": ba, "k": w.shape[0], "kw": w.shape[1],
+                                          "cin": w.shape[2], "cpad": w.shape[2], "cout": w.shape[2]}
+                continue
             if l["op"] not in ("conv", "fc"):
                 continue
             w, b = weights[l["name"]]
@@ -108,6 +119,8 @@ class DybitNetwork:
             if l["op"] in ("conv", "fc"):
                 nonneg[l["name"]] = bool(l.get("relu"))
                 produced_by[l["name"]] = l
+            elif l["op"] == "dwconv":
+                nonneg[l["name"]] = bool(l.get("relu"))
             else:
                 nonneg[l["name"]] = nonneg[l["src"]]
         self.a_fmt = {l["name"]: (self.params[l["name"]]["a_bits"], not nonneg[l["src"]])
@@ -155,7 +168,7 @@ class DybitNetwork:
         nonneg = {"input": False}
         known_max = {}                       # tensor name -> device scalar holding max|tensor|
         encoded = {}                         # (tensor name, format, padded channels) -> (scale, codes)
-        n_fused = sum(1 for l in self.layers if l["op"] in ("conv", "fc"))
+        n_fused = sum(1 for l in self.layers if l["op"] in ("conv", "fc", "dwconv"))
         max_words = torch.zeros(max(n_fused, 1), dtype=torch.float32, device=x.device)
         next_word = 0
         out = x
@@ -171,6 +184,32 @@ class DybitNetwork:
             elif op == "avgpool":
                 out = src.mean(dim=(1, 2), keepdim=True)
                 nonneg[name] = nonneg[l["src"]]
+            elif op == "dwconv":
+                Bn, H, W, C = src.shape
+                p = self.params[name]
+                a_fmt = (p["a_bits"], not nonneg[l["src"]])
+                flat = src.reshape(-1)
+                key = (l["src"], a_fmt, C)
+                if key in encoded:
+                    sa, qa = encoded[key]
+                elif l["src"] in known_max:
+                    sa, qa = encoded[key] = B.dybit_quantize_absmax(flat, known_max[l["src"]], *a_fmt)
+                else:
+                    sa = B.dybit_absmax_scale(flat, *a_fmt)
+                    qa = B.dybit_quantize(flat, sa, *a_fmt)
+                    encoded[key] = (sa, qa)
+                relu = bool(l.get("relu"))
+                word = None
+                if self.epilogue_absmax:
+                    word = max_words[next_word:next_word + 1]
+                    next_word += 1
+                    known_max[name] = word
+                out = B.dybit_dwconv2d(Bn, H, W, C, p["k"], p["kw"], l["stride"], l["pad"], qa, a_fmt, sa,
+                                       p["w_codes"], p["w_fmt"], p["w_scale"], p["bias"], relu, word)
+                if record is not None:
+                    record(name, {"x": src, "a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "y": out, "shortcut": None,
+                                  "relu": relu, "stride": l["stride"], "pad": l["pad"], **p})
+                nonneg[name] = relu
             else:
                 Bn, H, W, C = src.shape
                 p = self._layer_params(l, H, W) if op == "conv" else self.params[name]
@@ -236,6 +275,8 @@ class DybitNetwork:
         for l in self.layers:
             name, op = l["name"], l["op"]
             src = acts[l["src"]]
+            if op == "dwconv":
+                raise NotImplementedError("the fused write-back chain has no depthwise layers; use the dynamic chain")
             if op == "maxpool":
                 y = torch.nn.functional.max_pool2d(src.permute(0, 3, 1, 2), l["k"], l["stride"], l["pad"])
                 out = y.permute(0, 2, 3, 1).contiguous()

@@ -107,3 +107,54 @@ def test_dwconv_empty_and_refused_arguments():
     with pytest.raises(B.DybitError) as e:
         B.dybit_dwconv2d(1, 64, 64, 32, 9, 9, 4, 1, x, (8, False), scalar(1), w, (8, True), scalar(1))   # patch too large
     assert e.value.status == B.ERR_INVALID_ARG
+
+
+def test_depthwise_separable_block_in_the_chain():
+    """An inverted-residual block of the depthwise-separable network of Sec. IV in the dynamic chain
+    (1 x 1 expansion, depthwise 3 x 3, 1 x 1 projection with the block input added), twice, the second
+    time at stride 2 without the shortcut: every layer is checked on the GPU's own input -- max-abs scale
+    and codes bit-exact, output within tolerance of the oracle's convolution / depthwise convolution."""
+    from paper_2302_12510_amd import synth
+    from paper_2302_12510_amd.network import DybitNetwork
+    layers = [
+        {"name": "stem", "op": "conv", "src": "input", "cin": 3, "cout": 32, "k": 3, "stride": 1, "pad": 1, "relu": True},
+        {"name": "b1e", "op": "conv", "src": "stem", "cin": 32, "cout": 96, "k": 1, "stride": 1, "pad": 0, "relu": True},
+        {"name": "b1d", "op": "dwconv", "src": "b1e", "stride": 1, "pad": 1, "relu": True},
+        {"name": "b1p", "op": "conv", "src": "b1d", "cin": 96, "cout": 32, "k": 1, "stride": 1, "pad": 0, "relu": False, "add": "stem"},
+        {"name": "b2e", "op": "conv", "src": "b1p", "cin": 32, "cout": 96, "k": 1, "stride": 1, "pad": 0, "relu": True},
+        {"name": "b2d", "op": "dwconv", "src": "b2e", "stride": 2, "pad": 1, "relu": True},
+        {"name": "b2p", "op": "conv", "src": "b2d", "cin": 96, "cout": 64, "k": 1, "stride": 1, "pad": 0, "relu": False},
+    ]
+    conv_layers = [l for l in layers if l["op"] == "conv"]
+    weights = synth.network_weights(conv_layers, seed=8)
+    for i, name in enumerate(("b1d", "b2d")):
+        weights[name] = (synth.kaiming_normal((3, 3, 96), 9, seed=8, stream=50 + i), synth.normal((96,), 0.01, seed=8, stream=60 + i))
+    bits = {"stem": (8, 8), "b1e": (4, 8), "b1d": (4, 4), "b1p": (8, 4), "b2e": (4, 8), "b2d": (8, 8), "b2p": (4, 4)}
+    net = DybitNetwork(layers, weights, bits)
+    x = dev(synth.network_input(2, 20, seed=8))
+    recs = {}
+    out = net.forward(x, record=lambda n, r: recs.__setitem__(n, r))
+    torch.cuda.synchronize()
+    assert out.shape == (2, 10 * 10 * 64) and torch.isfinite(out).all()
+    for l in layers:
+        name, rec = l["name"], recs[l["name"]]
+        xs = rec["x"].cpu().numpy()
+        s = np.float32(rec["a_scale"].item())
+        assert s == R.absmax_scale(xs, *rec["a_fmt"]), name
+        qx = R.unpack(rec["a_codes"].cpu().numpy(), xs.size, rec["a_fmt"][0]).reshape(xs.shape)
+        assert np.array_equal(qx.reshape(-1), R.quantize(xs.reshape(-1), s, *rec["a_fmt"])), name
+        w, bias = weights[name]
+        sw = np.float32(rec["w_scale"].item())
+        if l["op"] == "dwconv":
+            assert sw == R.absmax_scale(w, *rec["w_fmt"])
+            qw = R.quantize(w.reshape(-1), sw, *rec["w_fmt"]).reshape(w.shape)
+            want, den = R.dwconv2d(qx, rec["a_fmt"], s, qw, rec["w_fmt"], sw, l["stride"], l["pad"], bias, rec["relu"])
+        else:
+            cout, k, kw, cin = w.shape
+            wp = np.zeros((cout, rec["k"], rec["kw"], xs.shape[-1]), dtype=np.float32)
+            wp[:, :k, :kw, :cin] = w
+            qw = R.quantize(wp.reshape(-1), sw, *rec["w_fmt"]).reshape(wp.shape)
+            shortcut = None if rec["shortcut"] is None else rec["shortcut"].cpu().numpy()
+            want, den = R.conv2d(qx, rec["a_fmt"], s, qw, rec["w_fmt"], sw, rec["stride"], rec["pad"], bias, rec["relu"], shortcut)
+        assert_within(rec["y"].cpu().numpy(), want, den)
+    assert B.dybit_get_last_async_error() == B.OK
