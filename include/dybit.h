@@ -285,6 +285,42 @@ dybit_status dybit_search(int32_t n_layers, const double *lat, const double *rms
  * last call, or a write-back epilogue, found an unusable scale and wrote no codes). */
 dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream);
 
+/* Which kernel a matrix-product call ran on (Sec. III-B's array has one datapath; this library picks
+ * among several kernels by shape and formats).  Host only, no device work.
+ *
+ * dybit_last_gemm_kernel: the kernel that the calling host thread's most recent dybit_gemm* /
+ * dybit_conv2d* call launched (DYBIT_KERNEL_NONE before the first, or when the call returned early:
+ * an error, M == 0 or N == 0).
+ *
+ * dybit_set_option: overrides the automatic choice for the whole process, for tests and A/B
+ * measurements.  name / value [host, NUL-terminated]:
+ *   "gemm_kernel"  "auto" | "general" | "mid" | "large" | "ws"  -- takes the named kernel family whenever
+ *                  the problem meets its preconditions (otherwise the automatic choice continues, which
+ *                  dybit_last_gemm_kernel shows)
+ *   "gemm_mfma"    "auto" | "f16"   -- "f16" keeps pairs of 4- and 2-bit operands off the e4m3 kernels
+ *   "mid_tile"     "auto" | "64" | "128"   -- tile of the e4m3 kernel when it is not the 256 x 256 one
+ *   "mid_kgroups"  "auto" | "1" | "2"      -- k-groups per workgroup of the 128 x 128 kernels
+ *   "gemm_ws"      "auto" | "off"   -- "off" leaves the weight-stationary kernel out of the automatic choice
+ * Initial values come from the environment, read once when the library is first used (DYBIT_GEMM_KERNEL,
+ * DYBIT_GEMM_MFMA, DYBIT_MID_TILE, DYBIT_MID_KGROUPS, DYBIT_GEMM_WS=0).  DYBIT_ERR_NULL for a NULL
+ * argument, DYBIT_ERR_INVALID_ARG for an unknown name or value.  Not synchronised with calls running on
+ * other host threads: set options before starting them. */
+typedef enum {
+    DYBIT_KERNEL_NONE = 0,
+    DYBIT_KERNEL_GENERAL = 1,        /* any formats and shapes, LDS look-up tables, 128 x 128 tile      */
+    DYBIT_KERNEL_F16_256 = 2,        /* fp16 MFMA, 256 x 256 tile                                       */
+    DYBIT_KERNEL_F16_128_KG1 = 3,    /* fp16 MFMA, 128 x 128 tile, one k-group                          */
+    DYBIT_KERNEL_F16_128_KG2 = 4,    /* fp16 MFMA, 128 x 128 tile, two k-groups                         */
+    DYBIT_KERNEL_F16_128_ROWS = 5,   /* fp16 MFMA, 128 x 128 tile, few-channel convolution by filter rows */
+    DYBIT_KERNEL_F16_WS = 6,         /* fp16 MFMA, weight-stationary                                    */
+    DYBIT_KERNEL_F8_256 = 7,         /* e4m3 MFMA, 256 x 256 tile                                       */
+    DYBIT_KERNEL_F8_128_KG1 = 8,     /* e4m3 MFMA, 128 x 128 tile, one k-group                          */
+    DYBIT_KERNEL_F8_128_KG2 = 9,     /* e4m3 MFMA, 128 x 128 tile, two k-groups                         */
+    DYBIT_KERNEL_F8_64 = 10          /* e4m3 MFMA, 64 x 64 tile, two k-groups                           */
+} dybit_kernel_id;
+int32_t dybit_last_gemm_kernel(void);
+dybit_status dybit_set_option(const char *name, const char *value);
+
 /* Measurement aid, not part of the method: runs only fp16 MFMA instructions (the instruction
  * dybit_gemm uses) on operand values taken from `operands` and reports how many flops the launch
  * performs, so that a caller can time it and obtain the matrix-core rate this device sustains.

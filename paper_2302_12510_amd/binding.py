@@ -63,6 +63,9 @@ def lib() -> C.CDLL:
         L.dybit_fake_quant.argtypes = [vp, sz, Fmt, vp, vp, vp]
         L.dybit_search.argtypes = [i32, vp, vp, vp, i32, C.c_double, i32, vp, vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
+        L.dybit_last_gemm_kernel.argtypes = []
+        L.dybit_last_gemm_kernel.restype = i32
+        L.dybit_set_option.argtypes = [C.c_char_p, C.c_char_p]
         L.dybit_diag_mfma_f16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
         L.dybit_diag_mfma_f8.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
         _lib = L
@@ -99,6 +102,19 @@ def _ptr(t) -> int | None:
 
 
 # ---- host-only --------------------------------------------------------------
+KERNEL_NAMES = ("none", "general", "f16_256", "f16_128_kg1", "f16_128_kg2", "f16_128_rows", "f16_ws",
+                "f8_256", "f8_128_kg1", "f8_128_kg2", "f8_64")
+
+
+def dybit_last_gemm_kernel() -> str:
+    """Name (KERNEL_NAMES) of the kernel this thread's last matrix-product call launched."""
+    return KERNEL_NAMES[lib().dybit_last_gemm_kernel()]
+
+
+def dybit_set_option(name: str, value: str = "auto") -> None:
+    _check(lib().dybit_set_option(name.encode(), value.encode()), "dybit_set_option")
+
+
 def dybit_codebook(bits: int, signed: bool):
     """numpy float32 array of the 2^bits code values."""
     import numpy as np

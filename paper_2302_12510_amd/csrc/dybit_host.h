@@ -18,9 +18,13 @@ int *async_error_word();
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// A HIP error that a launch function met before its launch (gemm_dispatch.cpp keeps it per host thread).
+hipError_t take_hip_error();
+
 inline dybit_status launch_status()
 {
-    return hipGetLastError() == hipSuccess ? DYBIT_OK : DYBIT_ERR_HIP;
+    const hipError_t before = take_hip_error(), at_launch = hipGetLastError();
+    return (before == hipSuccess && at_launch == hipSuccess) ? DYBIT_OK : DYBIT_ERR_HIP;
 }
 
 }  // namespace dybit

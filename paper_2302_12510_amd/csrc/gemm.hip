@@ -321,7 +321,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
     const int units_per_row = MODE == RUNS ? g.kw * g.Cin / UNIT : 1;
     int run_fr[UPT], run_ur[UPT];
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.A), 0, MODE == RUNS ? (int)((g.a_bytes + 3) & ~(int64_t)3) : 0, 0x00020000);
+        const_cast<uint8_t *>(g.A), 0, MODE == RUNS ? (int)g.a_bytes : 0, 0x00020000);   // RUNS: whole words (checked by the entry point)
     auto next_run = [&](int i, int step) {
         run_ur[i] += step;
         while (run_ur[i] >= units_per_row) { run_ur[i] -= units_per_row; ++run_fr[i]; }
@@ -399,6 +399,7 @@ static void launch_gemm(const GemmArgs &g, bool conv, int mode, hipStream_t st)
 {
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     const dim3 grid((unsigned)tiles), block(GEMM_THREADS);
+    note_kernel(DYBIT_KERNEL_GENERAL);
     if (conv) {
         if (mode == RUNS) hipLaunchKernelGGL((gemm_kernel<BA, BW, true, RUNS, kWriteBack>), grid, block, 0, st, g);
         else if (mode == VEC) hipLaunchKernelGGL((gemm_kernel<BA, BW, true, VEC, kWriteBack>), grid, block, 0, st, g);
@@ -497,6 +498,7 @@ dybit_status gemm_impl(int64_t M, int64_t N, int64_t K,
                        const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
                        const Epilogue &e, float *C, int64_t ldc, dybit_stream stream)
 {
+    clear_call_record();
     dybit_status st = check_fmt(a_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
     if (st != DYBIT_OK) return st;
@@ -525,6 +527,7 @@ dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t C
                          const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
                          const Epilogue &e, float *Y, dybit_stream stream)
 {
+    clear_call_record();
     dybit_status st = check_fmt(x_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
     if (st != DYBIT_OK) return st;
@@ -554,7 +557,7 @@ dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t C
     const bool aligned = aligned16(X_codes) && aligned16(Wt_codes);
     int mode = 0;
     if (aligned && Cin % UNIT == 0) mode = 1;
-    else if (aligned && UNIT % Cin == 0 && ((int64_t)kw * Cin) % UNIT == 0 && g.a_bytes < 0x7fffffff) mode = 2;
+    else if (aligned && UNIT % Cin == 0 && ((int64_t)kw * Cin) % UNIT == 0 && g.a_bytes < 0x7fffffff && g.a_bytes % 4 == 0) mode = 2;
     (g.q_out ? launch_gemm_general_wb : launch_gemm_general)(g, x_fmt.bits, w_fmt.bits, true, mode, (hipStream_t)stream);
     return launch_status();
 }

@@ -38,6 +38,25 @@ struct GemmArgs {
     int64_t a_bytes, w_bytes;        // sizes of the two code buffers
 };
 
+// Overrides of the automatic kernel choice (0 = automatic everywhere).  They start from the
+// environment, read once when the library is first used (DYBIT_GEMM_KERNEL, DYBIT_GEMM_MFMA,
+// DYBIT_MID_TILE, DYBIT_MID_KGROUPS, DYBIT_GEMM_WS), and change only through dybit_set_option.
+struct DispatchOptions {
+    int kernel;        // 0 automatic, else DYBIT_FORCE_*
+    int mfma_f16;      // 1: pairs of 4- and 2-bit operands stay on the fp16 kernels
+    int mid_tile;      // 0 automatic, 64 or 128: tile of the fp8-path kernel when it is not the 256 x 256 one
+    int mid_kgroups;   // 0 automatic, 1 or 2: k-groups of the 128 x 128 kernels
+    int ws_off;        // 1: the weight-stationary kernel is left out of the automatic choice
+};
+enum { DYBIT_FORCE_GENERAL = 1, DYBIT_FORCE_MID = 2, DYBIT_FORCE_LARGE = 3, DYBIT_FORCE_WS = 4 };
+DispatchOptions dispatch_options();
+// Record of the kernel a launch function started, per host thread (dybit_last_gemm_kernel reads it),
+// and of a HIP error met on the way (hipFuncSetAttribute, ...), which the entry point then reports.
+void note_kernel(int id);
+void note_hip(hipError_t e);
+void clear_call_record();          // an entry point calls this first
+hipError_t take_hip_error();       // ... and this last: the first error noted since, or hipSuccess
+
 // Tiled MFMA kernels for 4- and 8-bit operands with signed weights: the large-tile kernel
 // (gemm_fast.hip, 256 x 256) and the mid-size-tile kernel (gemm_mid.hip, 128 x 128), one
 // translation unit per weight format.  a_bits is 4 or 8; signedness comes from g.

@@ -5,17 +5,96 @@
 // code buffers, and buffers below 2 GiB (32-bit buffer offsets).  The 256 x 256 kernel does the
 // least decode work per MFMA and is used when its tiles can fill the 256 compute units, N is
 // wide enough for them and K is long enough for the main loop to outweigh the epilogue; the
-// 128 x 128 kernel takes the rest.  The environment variable
-// DYBIT_GEMM_KERNEL = large | mid | general overrides the choice whenever the named kernel's
-// preconditions hold (tests use it to reach a given kernel with small shapes); DYBIT_GEMM_MFMA=f16
-// keeps pairs of 4-bit operands on the fp16 kernels instead of the fp8 ones.
+// 128 x 128 kernel takes the rest.  dybit_set_option (initial values: the environment, read once)
+// overrides the choice whenever the named kernel's preconditions hold; every launch records the kernel
+// it started, which dybit_last_gemm_kernel reports, so a test can tell which kernel it exercised.
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+
+#include "../../include/dybit.h"
 #include "gemm_args.h"
 
 namespace dybit {
+
+namespace {
+
+std::atomic<int> opt_kernel{0}, opt_mfma_f16{0}, opt_mid_tile{0}, opt_mid_kgroups{0}, opt_ws_off{0};
+thread_local int last_kernel = DYBIT_KERNEL_NONE;
+thread_local hipError_t pending_hip_error = hipSuccess;
+
+// name / value -> option; false for an unknown pair.  "auto" resets an option.
+bool apply_option(const char *name, const char *value)
+{
+    const bool is_auto = !strcmp(value, "auto");
+    if (!strcmp(name, "gemm_kernel")) {
+        const int v = is_auto ? 0 : !strcmp(value, "general") ? DYBIT_FORCE_GENERAL : !strcmp(value, "mid") ? DYBIT_FORCE_MID
+                    : !strcmp(value, "large") ? DYBIT_FORCE_LARGE : !strcmp(value, "ws") ? DYBIT_FORCE_WS : -1;
+        if (v < 0) return false;
+        opt_kernel = v;
+    } else if (!strcmp(name, "gemm_mfma")) {
+        if (!is_auto && strcmp(value, "f16")) return false;
+        opt_mfma_f16 = is_auto ? 0 : 1;
+    } else if (!strcmp(name, "mid_tile")) {
+        const int v = is_auto ? 0 : !strcmp(value, "64") ? 64 : !strcmp(value, "128") ? 128 : -1;
+        if (v < 0) return false;
+        opt_mid_tile = v;
+    } else if (!strcmp(name, "mid_kgroups")) {
+        const int v = is_auto ? 0 : !strcmp(value, "1") ? 1 : !strcmp(value, "2") ? 2 : -1;
+        if (v < 0) return false;
+        opt_mid_kgroups = v;
+    } else if (!strcmp(name, "gemm_ws")) {
+        if (!is_auto && strcmp(value, "off")) return false;
+        opt_ws_off = is_auto ? 0 : 1;
+    } else {
+        return false;
+    }
+    return true;
+}
+
+// The environment gives the initial values, once; values it cannot hold are ignored.
+void options_from_environment()
+{
+    static const bool done = [] {
+        static const char *const vars[][2] = {{"DYBIT_GEMM_KERNEL", "gemm_kernel"}, {"DYBIT_GEMM_MFMA", "gemm_mfma"},
+                                              {"DYBIT_MID_TILE", "mid_tile"}, {"DYBIT_MID_KGROUPS", "mid_kgroups"}};
+        for (const auto &v : vars) {
+            const char *e = getenv(v[0]);
+            if (e && *e) apply_option(v[1], e);
+        }
+        const char *ws = getenv("DYBIT_GEMM_WS");
+        if (ws && !strcmp(ws, "0")) apply_option("gemm_ws", "off");
+        return true;
+    }();
+    (void)done;
+}
+
+}  // namespace
+
+DispatchOptions dispatch_options()
+{
+    options_from_environment();
+    return DispatchOptions{opt_kernel.load(), opt_mfma_f16.load(), opt_mid_tile.load(), opt_mid_kgroups.load(), opt_ws_off.load()};
+}
+
+void note_kernel(int id) { last_kernel = id; }
+void note_hip(hipError_t e)
+{
+    if (e != hipSuccess && pending_hip_error == hipSuccess) pending_hip_error = e;
+}
+void clear_call_record()
+{
+    last_kernel = DYBIT_KERNEL_NONE;
+    pending_hip_error = hipSuccess;
+}
+hipError_t take_hip_error()
+{
+    const hipError_t e = pending_hip_error;
+    pending_hip_error = hipSuccess;
+    return e;
+}
 
 void launch_gemm_general_wb(const GemmArgs &g, int a_bits, int w_bits, bool conv, int mode, hipStream_t st)
 {
@@ -33,22 +112,20 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
     if (g.M < 1 || g.N < 1 || g.K < 64 || g.K % 64) return false;
     // a convolution needs whole 64-code k groups inside a filter tap, or (few channels) filter rows of
     // exactly 32 codes, which the 128 x 128 kernel fetches row by row
-    const bool rows = conv && g.Cin < 64 && (int64_t)g.kw * g.Cin == 32;
+    const bool rows = conv && g.Cin < 64 && (int64_t)g.kw * g.Cin == 32 && g.a_bytes % 4 == 0;   // fetched as aligned words: none may reach past the tensor
     if (conv && g.Cin % 64 && !rows) return false;
     if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W)) & 15) return false;
     if (g.a_bytes >= 0x7fffffff || g.w_bytes >= 0x7fffffff) return false;
 
     bool large;
     const bool low_pair = (a_bits == 4 || a_bits == 2) && (w_bits == 4 || w_bits == 2);
-    const char *force = getenv("DYBIT_GEMM_KERNEL");
-    if (force && !strcmp(force, "general")) return false;
+    const DispatchOptions opt = dispatch_options();
+    const int force = opt.kernel;
+    if (force == DYBIT_FORCE_GENERAL) return false;
 
     // Weight-stationary kernel: the whole decoded weight matrix in LDS, for many rows against few
-    // weights (it declines when the weights do not fit).  DYBIT_GEMM_KERNEL=ws forces it where it fits.
-    const bool ws_forced = force && !strcmp(force, "ws");
-    const char *ws_env = getenv("DYBIT_GEMM_WS");                  // DYBIT_GEMM_WS=0 keeps it out of the automatic choice
-    const bool ws_off = ws_env && !strcmp(ws_env, "0");
-    if (ws_forced || (!force && !ws_off && g.N <= 128 && g.M >= 16384)) {
+    // weights (it declines when the weights do not fit).
+    if (force == DYBIT_FORCE_WS || (!force && !opt.ws_off && g.N <= 128 && g.M >= 16384)) {
         const bool wb_ = g.q_out != nullptr;
         bool done = false;
         switch (w_bits) {
@@ -59,9 +136,9 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
         }
         if (done) return true;
     }
-    if (force && !strcmp(force, "large")) {
+    if (force == DYBIT_FORCE_LARGE) {
         large = true;
-    } else if (force && !strcmp(force, "mid")) {
+    } else if (force == DYBIT_FORCE_MID) {
         large = false;
     } else {
         // Too few 256 x 256 tiles cannot fill 256 compute units, and a narrow N wastes most of a
@@ -74,10 +151,9 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
         large = g.N > 128 && tiles256 >= 128 && g.K >= (low_pair ? 2048 : 1024);
     }
     // two operands of 4 or 2 bits: every value is exact in e4m3, so the fp8 matrix path (twice the
-    // fp16 rate, byte decoders) takes them unless DYBIT_GEMM_MFMA=f16 asks for the fp16 kernels
-    const char *mfma = getenv("DYBIT_GEMM_MFMA");
+    // fp16 rate, byte decoders) takes them unless the "gemm_mfma" option asks for the fp16 kernels
     const bool wb = g.q_out != nullptr;                             // write-back builds of the same kernels
-    if (low_pair && !rows && !(mfma && !strcmp(mfma, "f16"))) {
+    if (low_pair && !rows && !opt.mfma_f16) {
         if (w_bits == 4) return (wb ? launch_gemm_f8_w0_wb : launch_gemm_f8_w0)(g, a_bits, conv, large, st);
         return (wb ? launch_gemm_f8_w6_wb : launch_gemm_f8_w6)(g, a_bits, conv, large, st);
     }
@@ -94,3 +170,12 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
 }
 
 }  // namespace dybit
+
+extern "C" int32_t dybit_last_gemm_kernel(void) { return dybit::last_kernel; }
+
+extern "C" dybit_status dybit_set_option(const char *name, const char *value)
+{
+    if (!name || !value) return DYBIT_ERR_NULL;
+    dybit::options_from_environment();                              // so that a later first use does not overwrite this
+    return dybit::apply_option(name, value) ? DYBIT_OK : DYBIT_ERR_INVALID_ARG;
+}

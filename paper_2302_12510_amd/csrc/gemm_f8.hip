@@ -344,13 +344,14 @@ static void launch_cfg(const GemmArgs &g, bool conv, hipStream_t st)
     using G = Geom<NWM, KG>;
     const int tiles_m = (int)((g.M + G::T - 1) / G::T), tiles_n = (int)((g.N + G::T - 1) / G::T);
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8)), block(G::THREADS);
+    note_kernel(NWM == 8 ? DYBIT_KERNEL_F8_256 : NWM == 2 ? DYBIT_KERNEL_F8_64 : KG == 1 ? DYBIT_KERNEL_F8_128_KG1 : DYBIT_KERNEL_F8_128_KG2);
     if (conv) {
         auto k = gemm_f8_kernel<FA, FW, true, NWM, KG, kWriteBack>;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+        note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
         hipLaunchKernelGGL(k, grid, block, G::LDS_BYTES, st, g, tiles_m, tiles_n);
     } else {
         auto k = gemm_f8_kernel<FA, FW, false, NWM, KG, kWriteBack>;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+        note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
         hipLaunchKernelGGL(k, grid, block, G::LDS_BYTES, st, g, tiles_m, tiles_n);
     }
 }
@@ -362,11 +363,10 @@ static void launch(const GemmArgs &g, bool conv, bool large, hipStream_t st)
     const int64_t tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
     // Few tiles: a quarter-size tile puts four times as many workgroups on the device (each decodes
     // its A rows for half as many columns, which costs less than idle compute units).
-    // DYBIT_MID_TILE=64 / 128 overrides the choice.
-    const char *tile = getenv("DYBIT_MID_TILE");
-    if (tile ? atoi(tile) == 64 : tiles <= 128) return launch_cfg<FA, FW, 2, 2>(g, conv, st);
-    const char *force = getenv("DYBIT_MID_KGROUPS");
-    const bool one = force ? atoi(force) == 1 : tiles > 256;
+    // The "mid_tile" and "mid_kgroups" options override the choice.
+    const DispatchOptions opt = dispatch_options();
+    if (opt.mid_tile ? opt.mid_tile == 64 : tiles <= 128) return launch_cfg<FA, FW, 2, 2>(g, conv, st);
+    const bool one = opt.mid_kgroups ? opt.mid_kgroups == 1 : tiles > 256;
     if (one) launch_cfg<FA, FW, 4, 1>(g, conv, st);
     else launch_cfg<FA, FW, 4, 2>(g, conv, st);
 }

@@ -250,13 +250,14 @@ static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 {
     const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8)), block(512 / kRowBlocks);
+    note_kernel(DYBIT_KERNEL_F16_256);
     if (conv) {
         auto k = gemm_fast_kernel<FA, FW, true, kRowBlocks, kWriteBack>;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
         hipLaunchKernelGGL(k, grid, block, LDS_BYTES, st, g, tiles_m, tiles_n);
     } else {
         auto k = gemm_fast_kernel<FA, FW, false, kRowBlocks, kWriteBack>;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
         hipLaunchKernelGGL(k, grid, block, LDS_BYTES, st, g, tiles_m, tiles_n);
     }
 }

@@ -87,9 +87,9 @@ __global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_k
     }
     const int64_t m0 = (int64_t)tile_m * TM, n0 = (int64_t)tile_n * TN;
 
-    // ROWS reads aligned words: the descriptor then ends on a word boundary, so that the last bytes of
-    // the tensor are not dropped with their (at most three bytes longer) word
-    const int64_t a_span = CONV == ROWS ? ((g.a_bytes + 3) & ~(int64_t)3) : g.a_bytes;
+    // ROWS reads aligned words; the dispatcher takes it only for tensors of a whole number of words, so
+    // the descriptor ends exactly with the tensor and no word reaches past it
+    const int64_t a_span = g.a_bytes;
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(g.A), 0, (int)(a_span > 0x7fffffff ? 0x7fffffff : a_span), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
@@ -307,7 +307,8 @@ static void launch_one(const GemmArgs &g, hipStream_t st, int tiles_m, int tiles
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8), 1, 1), block(256 * KG);
     constexpr int lds_bytes = Geom<KG>::LDS_BYTES;
     auto k = gemm_mid_kernel<FA, FW, CONV, KG, kWriteBack>;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    note_kernel(CONV == ROWS ? DYBIT_KERNEL_F16_128_ROWS : KG == 1 ? DYBIT_KERNEL_F16_128_KG1 : DYBIT_KERNEL_F16_128_KG2);
+    note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     hipLaunchKernelGGL(k, grid, block, lds_bytes, st, g, tiles_m, tiles_n);
 }
 
@@ -319,14 +320,14 @@ static void launch_kg(const GemmArgs &g, bool conv, hipStream_t st, int tiles_m,
 }
 
 // More tiles than compute units: small workgroups, three per compute unit.  Otherwise one
-// eight-wave workgroup per compute unit.  DYBIT_MID_KGROUPS = 1 | 2 overrides (tests).
+// eight-wave workgroup per compute unit.  The "mid_kgroups" option overrides (tests).
 template <int FA, int FW>
 static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 {
     const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
     if (conv && g.Cin < 64) return launch_one<FA, FW, ROWS, 1>(g, st, tiles_m, tiles_n);   // kw * Cin = 32 (checked by the dispatcher)
-    const char *force = getenv("DYBIT_MID_KGROUPS");
-    const bool one = force ? atoi(force) == 1 : (int64_t)tiles_m * tiles_n > 256;
+    const int force = dispatch_options().mid_kgroups;
+    const bool one = force ? force == 1 : (int64_t)tiles_m * tiles_n > 256;
     if (one) launch_kg<FA, FW, 1>(g, conv, st, tiles_m, tiles_n);
     else launch_kg<FA, FW, 2>(g, conv, st, tiles_m, tiles_n);
 }

@@ -57,8 +57,8 @@ __global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_ker
     const int kq = lane >> 5;
     const int ktiles = (int)(g.K / 64);
 
-    // ROWS reads aligned words: the descriptor then ends on a word boundary
-    const int64_t a_span = CONV == ROWS ? ((g.a_bytes + 3) & ~(int64_t)3) : g.a_bytes;
+    // ROWS reads aligned words; the dispatcher takes it only for tensors of a whole number of words
+    const int64_t a_span = g.a_bytes;
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(g.A), 0, (int)(a_span > 0x7fffffff ? 0x7fffffff : a_span), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
@@ -245,7 +245,8 @@ static void launch_cb(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_
     const int per_cu = (lds_bytes <= 80 * 1024 && CB == 2 && !kWriteBack) ? 2 : 1;  // workgroups that fit a compute unit (LDS, registers; the write-back epilogue needs the registers of a second one)
     const int grid = slabs < 256 * per_cu ? slabs : 256 * per_cu;
     auto k = gemm_ws_kernel<FA, FW, CONV, CB, kWriteBack>;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    note_kernel(DYBIT_KERNEL_F16_WS);
+    note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(THREADS), lds_bytes, st, g, slabs, row_bytes);
 }
 

@@ -114,7 +114,9 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
     if (!rqp.ok && m_strip == 0 && n0 == 0 && lane == 0) *g.async_error = DYBIT_ERR_BAD_SCALE;   // no codes, flag the call
     constexpr int GV = 8;
     const bool track = g.absmax_bits != nullptr;
-    const float relu_floor = g.relu ? 0.0f : -__builtin_inff();        // ReLU as a maximum: no select per value
+    // ReLU as a maximum with a uniform floor (no select per value).  Without ReLU the floor is NaN:
+    // the maximum of a number and NaN is the number, and a NaN result stays NaN (and becomes code 0)
+    const float relu_floor = g.relu ? 0.0f : __builtin_nanf("");
     float mx = 0.0f;
     constexpr bool PREFETCH = HAS_RES && CB <= 4;
     float res2[2][GV];

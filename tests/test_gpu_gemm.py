@@ -27,6 +27,7 @@ def run_gemm(qa, a_fmt, sa, qw, w_fmt, sw, bias=None, relu=False, ldc=None):
     c = B.dybit_gemm(M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(sa),
                      pack_rows_dev(qw, w_fmt[0]), w_fmt, scalar(sw),
                      None if bias is None else dev(bias), relu, out=out, ldc=ldc)
+    assert_forced_kernel_ran()
     torch.cuda.synchronize()
     return c.cpu().numpy()
 
@@ -256,29 +257,66 @@ TILED_PAIRS += [((2, True), (2, True)), ((2, False), (2, True)), ((8, True), (2,
 KERNELS = ["large", "mid1", "mid2", "mid64", "large-f16", "mid1-f16", "mid2-f16"]
 
 
+# kernels (binding.KERNEL_NAMES) that a forced family may legitimately run on, by matrix path
+_FAMILY = {"large": ({"f16_256"}, {"f8_256"}), "mid1": ({"f16_128_kg1", "f16_128_rows"}, {"f8_128_kg1"}),
+           "mid2": ({"f16_128_kg2", "f16_128_rows"}, {"f8_128_kg2"}), "mid": ({"f16_128_kg1", "f16_128_kg2", "f16_128_rows"}, set()),
+           "mid64": (set(), {"f8_64"}), "ws": ({"f16_ws"}, set()), "general": ({"general"}, {"general"})}
+_expected_kernels = None
+
+
+def assert_forced_kernel_ran():
+    """The kernel the last matrix-product call launched is one the forced family allows."""
+    if _expected_kernels is not None:
+        ran = B.dybit_last_gemm_kernel()
+        assert ran in _expected_kernels, f"forced {sorted(_expected_kernels)} but the call ran on {ran}"
+
+
 @pytest.fixture
-def force_kernel(monkeypatch, request):
+def force_kernel(request):
+    """Forces a kernel family through dybit_set_option for one test and checks, after every run_gemm and at
+    the end of the test, that the call really ran on it (dybit_last_gemm_kernel)."""
+    global _expected_kernels
     name = request.param
     fmts = [request.getfixturevalue(k) for k in ("a_fmt", "w_fmt", "x_fmt") if k in request.fixturenames]
     low_pair = bool(fmts) and all(f[0] in (2, 4) for f in fmts)
     if name.startswith("large") and any(f[0] in (2, 6) for f in fmts) and (not low_pair or name.endswith("-f16")):
         pytest.skip("on the fp16 kernels 2- and 6-bit operands run on the 128 x 128 kernel only")
-    if name.endswith("-f16"):
+    options = {}
+    f16_only = name.endswith("-f16")
+    if f16_only:
         if fmts and not low_pair:
             pytest.skip("only pairs of 4- and 2-bit formats have an fp8 path to switch off")
-        monkeypatch.setenv("DYBIT_GEMM_MFMA", "f16")
+        options["gemm_mfma"] = "f16"
         name = name[:-4]
+    family = name
     if name == "mid64":
         if fmts and not low_pair:
             pytest.skip("the 64 x 64 tile exists on the fp8 path only")
-        monkeypatch.setenv("DYBIT_MID_TILE", "64")
+        options["mid_tile"] = "64"
         name = "mid"
     elif name.startswith("mid") and name != "mid":
-        monkeypatch.setenv("DYBIT_MID_KGROUPS", name[3:])
-        monkeypatch.setenv("DYBIT_MID_TILE", "128")
+        options["mid_kgroups"] = name[3:]
+        options["mid_tile"] = "128"
         name = "mid"
-    monkeypatch.setenv("DYBIT_GEMM_KERNEL", name)
-    return request.param
+    options["gemm_kernel"] = name
+    f16_set, f8_set = _FAMILY[family]
+    if family in ("ws", "general"):                         # one kernel for every pair
+        _expected_kernels = f16_set | f8_set
+    elif f16_only or (fmts and not low_pair):
+        _expected_kernels = set(f16_set)
+    elif fmts:
+        _expected_kernels = set(f8_set)
+    else:                                                   # the test picks its own formats
+        _expected_kernels = f16_set | f8_set
+    for k, v in options.items():
+        B.dybit_set_option(k, v)
+    try:
+        yield request.param
+        assert_forced_kernel_ran()
+    finally:
+        _expected_kernels = None
+        for k in options:
+            B.dybit_set_option(k, "auto")
 
 
 @pytest.mark.parametrize("force_kernel", KERNELS, indirect=True)
@@ -477,7 +515,7 @@ def test_conv2d_ex_shortcut_and_absmax(force_kernel, with_shortcut):
                           None if res is None else dev(res), True, mx)
     torch.cuda.synchronize()
     want, den = R.conv2d(qx, x_fmt, 0.3, qw, w_fmt, 0.02, 1, 1, bias, True, res)
-    assert_within(y.cpu().numpy(), want, den)
+    assert_within(y.cpu().numpy(), want, den, shortcut=with_shortcut)
     assert mx.item() == y.abs().max().item()
 
 
@@ -499,7 +537,7 @@ def test_gemm_ex_shortcut(force_kernel, a_fmt):
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, False, res[:, :N])
-    assert_within(got[:, :N], want, den)
+    assert_within(got[:, :N], want, den, shortcut=True)
     assert np.all(got[:, N:] == -777.0)
 
 

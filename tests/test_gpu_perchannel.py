@@ -64,7 +64,7 @@ def test_gemm_per_channel(force_kernel, a_fmt, with_codes):
                                dev(bias), dev(res), True, mx, c_fmt, scalar(c_scale) if with_codes else None)
     torch.cuda.synchronize()
     c32 = c.cpu().numpy()
-    assert_within(c32, want, den)
+    assert_within(c32, want, den, shortcut=True)
     assert mx.item() == np.abs(c32).max()
     if with_codes:
         check_codes(codes, c32, c_scale, c_fmt)
@@ -137,7 +137,7 @@ def test_network_with_per_channel_weight_scales():
         shortcut = None if rec["shortcut"] is None else rec["shortcut"].cpu().numpy()
         want, den = R.conv2d(qx, rec["a_fmt"], rec["a_scale"].item(), qw.reshape(wp.shape), rec["w_fmt"], sw,
                              rec["stride"], rec["pad"], bias, rec["relu"], shortcut)
-        assert_within(rec["y"].cpu().numpy(), want, den)
+        assert_within(rec["y"].cpu().numpy(), want, den, shortcut=shortcut is not None)
     net.calibrate(x)
     fused = net.forward(x, static=True)
     assert torch.equal(fused, out)

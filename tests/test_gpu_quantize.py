@@ -181,3 +181,34 @@ def test_fake_quant_in_place_and_bad_scale():
     B.dybit_fake_quant(x, scalar(0.0), 4, True, out=y)
     assert B.dybit_get_last_async_error() == B.ERR_BAD_SCALE
     assert bool((y == 7.0).all())
+
+
+def test_config5b_full_size():
+    """The standalone quantize workload at its stated size (2^28 Laplace floats), i.e. the launch the
+    benchmark times: four loads in flight per lane and more than one trip round the grid-stride loop.
+    Scale bit-equal, packed codes byte for byte against the C oracle (plain loops, OpenMP) at 4 bits
+    signed, 8 bits signed and 6 bits signed, and the decoder on the 8-bit codes at that size."""
+    from oracle import c_ref
+    n = 1 << 28
+    x = synth.config5b(n=n)
+    xd = torch.from_numpy(x).cuda()
+    for fmt in ((4, True), (8, True), (6, True)):
+        sd = B.dybit_absmax_scale(xd, *fmt)
+        s = c_ref.absmax_scale(x, *fmt)
+        assert sd.item() == s, fmt
+        codes = B.dybit_quantize(xd, sd, *fmt)
+        torch.cuda.synchronize()
+        q = c_ref.quantize(x, s, *fmt)
+        want = c_ref.pack(q, fmt[0])
+        got = codes.cpu().numpy()
+        assert got.shape == want.shape
+        if not np.array_equal(got, want):
+            bad = np.nonzero(got != want)[0]
+            raise AssertionError(f"fmt {fmt}: {bad.size} packed bytes differ, first at byte {bad[0]}")
+        if fmt == (8, True):
+            y = B.dybit_dequantize(codes, n, sd, *fmt)
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy().view(np.uint32), c_ref.dequantize(q, s, *fmt).view(np.uint32))
+            del y
+        del codes, q, want, got
+    assert B.dybit_get_last_async_error() == B.OK
