@@ -1,7 +1,10 @@
 // Decoders from packed DyBit codes to fp16 pairs, entirely in the vector ALU (no table look-ups
 // in memory).  Shared by the tiled matrix-product kernels.
 //
-// Every DyBit value of the 2-, 4-, 6- and 8-bit formats is exact in fp16.  All decoders emit each group
+// Every DyBit value of the 2-, 4-, 6- and 8-bit formats is exact in fp16, and so is its 2^-14-fold
+// (as a subnormal half below 2^-14), which is what the arithmetic decoders of the 6- and 8-bit
+// formats produce: Codec<F>::ACC_EXP is the power of two the epilogue multiplies back in.
+// All decoders emit each group
 // of eight consecutive k values in the order (k0,k2,k1,k3,k4,k6,k5,k7): that is the order their
 // packed arithmetic produces for free, and a contraction does not care about the order of k as
 // long as both operands agree.
@@ -28,22 +31,27 @@ enum { F4S = 0, F4U = 1, F8S = 2, F8U = 3, F6S = 4, F6U = 5, F2S = 6, F2U = 7 };
 // ---------------------------------------------------------------------------
 // Codecs: packed codes -> fp16 pairs, entirely in the vector ALU.
 // ---------------------------------------------------------------------------
-// Arithmetic decoder for m magnitude bits (used for the 8-bit formats).  With n = 2^m - c:
-//   R = bitcast(K - bits(half(n)))      K = (15 + 15 + m-1) << 10
-// equals the DyBit value for codes with a leading one (see magnitude_value in dybit_device.h),
-// and for codes below that (n >= 2^(m-1)) it equals 1/2 + c/2^m, so the fraction c/2^(m-1) is
-// 2R - 1.  Because 2R - 1 >= R exactly when R >= 1, the value is min(R, 2R - 1) for every code.
-// half(n) comes from the usual trick: the bits 0x6400 | (2^m - 1 - c) are the half 1024 + 2^m-1-c,
-// and subtracting 1023 leaves n.  Both R and 2R-1 are non-negative, so the minimum is taken
-// on the bit patterns (no NaN canonicalisation needed).
-__device__ __forceinline__ u32 recip_decode_pair(u32 h, u32 k2)
+// Arithmetic decoder for m magnitude bits (used for the 6- and 8-bit formats).  With n = 2^m - c
+// (1 <= n <= 2^m) held as a half,
+//   R = bitcast(K - bits(half(n)))      K = (15 + m) << 10
+// is the DyBit value of the code times 2^-14, for every code:
+//   * a code with i leading ones, a zero and the k-bit fraction x (k = m-i-1) has n = 2^(k+1) - x, so
+//     half(n) has exponent k (k+1 when x == 0) and mantissa 1 - x/2^k; the subtraction turns that into
+//     exponent field i and mantissa x/2^k, i.e. 2^(i-1) (1 + x/2^k) 2^-14 (Eq. 1), and its borrow
+//     handles x == 0 and the all-ones code (n = 1 -> 2^(m-1) 2^-14);
+//   * a code whose first bit is 0 (n > 2^(m-1)) has half(n) in the top binade, the difference has
+//     exponent field 0 and mantissa bits c << (11-m): the subnormal half c 2^(1-m) 2^-14, which is
+//     the pure fraction of those codes on the same scale (the matrix cores take subnormal halves as
+//     they are); c == 0 gives 0.
+// The factor 2^14 per arithmetic operand is applied to the accumulators in the epilogue (ACC_EXP);
+// it is a power of two, so nothing is rounded differently.
+// half(n) comes from the usual trick: the bits 0x6400 | c are the half 1024 + c, and subtracting that
+// from 1024 + 2^m leaves n exactly.
+__device__ __forceinline__ u32 recip_decode_pair(u32 h, _Float16 base, u32 k2)
 {
-    const f16x2 nf = __builtin_bit_cast(f16x2, h) + (f16x2){(_Float16)-1023.0f, (_Float16)-1023.0f};
+    const f16x2 nf = (f16x2){base, base} - __builtin_bit_cast(f16x2, h);
     const u16x2 rb = __builtin_bit_cast(u16x2, k2) - __builtin_bit_cast(u16x2, nf);
-    const f16x2 R = __builtin_bit_cast(f16x2, rb);
-    const f16x2 L = R * (f16x2){(_Float16)2.0f, (_Float16)2.0f} + (f16x2){(_Float16)-1.0f, (_Float16)-1.0f};
-    const u16x2 v = __builtin_elementwise_min(rb, __builtin_bit_cast(u16x2, L));
-    return __builtin_bit_cast(u32, v);
+    return __builtin_bit_cast(u32, rb);
 }
 
 // Four 6-bit codes in the low 24 bits of t -> one code per byte (bits above 24 are ignored).
@@ -87,104 +95,95 @@ __device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
 // Four independent copies of the arithmetic decoder, written stage by stage so that no
 // instruction consumes the result of the one just before it (a packed-fp16 result needs a
 // wait state before it can be read).
-__device__ __forceinline__ void recip_decode_4pairs(const u32 *h, u32 k2, u32 *v)
+__device__ __forceinline__ void recip_decode_4pairs(const u32 *h, _Float16 base, u32 k2, u32 *v)
 {
-    const f16x2 m1023 = {(_Float16)-1023.0f, (_Float16)-1023.0f}, two = {(_Float16)2.0f, (_Float16)2.0f},
-                mone = {(_Float16)-1.0f, (_Float16)-1.0f};
-    f16x2 nf[4], L[4];
-    u16x2 rb[4];
+    const f16x2 b2 = {base, base};
+    f16x2 nf[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) nf[i] = __builtin_bit_cast(f16x2, h[i]) + m1023;
+    for (int i = 0; i < 4; ++i) nf[i] = b2 - __builtin_bit_cast(f16x2, h[i]);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) rb[i] = __builtin_bit_cast(u16x2, k2) - __builtin_bit_cast(u16x2, nf[i]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) L[i] = __builtin_bit_cast(f16x2, rb[i]) * two + mone;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = __builtin_bit_cast(u32, __builtin_elementwise_min(rb[i], __builtin_bit_cast(u16x2, L[i])));
+    for (int i = 0; i < 4; ++i) v[i] = __builtin_bit_cast(u32, __builtin_bit_cast(u16x2, k2) - __builtin_bit_cast(u16x2, nf[i]));
 }
 
 template <> struct Codec<F8S> {
-    static constexpr int BITS = 8;
+    static constexpr int BITS = 8, ACC_EXP = 14;
     // 4 codes (k0..k3) -> (k0,k2), (k1,k3)
     static __device__ __forceinline__ void word(u32 w, u32 *d)
     {
-        const u32 wm = ~w & 0x7f7f7f7fu;                                   // 127 - c in every byte
+        const u32 wm = w & 0x7f7f7f7fu;                                    // c in every byte
         const u32 h0 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04020400u);
         const u32 h1 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04030401u);
-        const u32 v0 = recip_decode_pair(h0, 0x90009000u), v1 = recip_decode_pair(h1, 0x90009000u);
-        d[0] = (v0 & 0x7fff7fffu) | ((w << 8) & 0x80008000u);             // sign bit of bytes 0, 2
-        d[1] = (v1 & 0x7fff7fffu) | (w & 0x80008000u);                    // sign bit of bytes 1, 3
+        const u32 v0 = recip_decode_pair(h0, (_Float16)1152.0f, 0x58005800u), v1 = recip_decode_pair(h1, (_Float16)1152.0f, 0x58005800u);
+        d[0] = v0 | ((w << 8) & 0x80008000u);                             // sign bit of bytes 0, 2
+        d[1] = v1 | (w & 0x80008000u);                                    // sign bit of bytes 1, 3
     }
     // 8 codes (two words) -> four registers, the four pairs decoded side by side
     static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
     {
-        const u32 m0 = ~w0 & 0x7f7f7f7fu, m1 = ~w1 & 0x7f7f7f7fu;
+        const u32 m0 = w0 & 0x7f7f7f7fu, m1 = w1 & 0x7f7f7f7fu;
         u32 h[4], v[4];
         h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
         h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
         h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
         h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
-        recip_decode_4pairs(h, 0x90009000u, v);
-        d[0] = (v[0] & 0x7fff7fffu) | ((w0 << 8) & 0x80008000u);
-        d[1] = (v[1] & 0x7fff7fffu) | (w0 & 0x80008000u);
-        d[2] = (v[2] & 0x7fff7fffu) | ((w1 << 8) & 0x80008000u);
-        d[3] = (v[3] & 0x7fff7fffu) | (w1 & 0x80008000u);
+        recip_decode_4pairs(h, (_Float16)1152.0f, 0x58005800u, v);
+        d[0] = v[0] | ((w0 << 8) & 0x80008000u);
+        d[1] = v[1] | (w0 & 0x80008000u);
+        d[2] = v[2] | ((w1 << 8) & 0x80008000u);
+        d[3] = v[3] | (w1 & 0x80008000u);
     }
 };
 
 template <> struct Codec<F8U> {
-    static constexpr int BITS = 8;
+    static constexpr int BITS = 8, ACC_EXP = 14;
     static __device__ __forceinline__ void word(u32 w, u32 *d)
     {
-        const u32 wm = ~w;                                                 // 255 - c in every byte
-        const u32 h0 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04020400u);
-        const u32 h1 = __builtin_amdgcn_perm(0x64646464u, wm, 0x04030401u);
-        d[0] = recip_decode_pair(h0, 0x94009400u);
-        d[1] = recip_decode_pair(h1, 0x94009400u);
+        const u32 h0 = __builtin_amdgcn_perm(0x64646464u, w, 0x04020400u);
+        const u32 h1 = __builtin_amdgcn_perm(0x64646464u, w, 0x04030401u);
+        d[0] = recip_decode_pair(h0, (_Float16)1280.0f, 0x5C005C00u);
+        d[1] = recip_decode_pair(h1, (_Float16)1280.0f, 0x5C005C00u);
     }
     static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
     {
-        const u32 m0 = ~w0, m1 = ~w1;
         u32 h[4];
-        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
-        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
-        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
-        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
-        recip_decode_4pairs(h, 0x94009400u, d);
+        h[0] = __builtin_amdgcn_perm(0x64646464u, w0, 0x04020400u);
+        h[1] = __builtin_amdgcn_perm(0x64646464u, w0, 0x04030401u);
+        h[2] = __builtin_amdgcn_perm(0x64646464u, w1, 0x04020400u);
+        h[3] = __builtin_amdgcn_perm(0x64646464u, w1, 0x04030401u);
+        recip_decode_4pairs(h, (_Float16)1280.0f, 0x5C005C00u, d);
     }
 };
 
 // 6-bit formats: the codes are first spread to one per byte (unpack_six), then the arithmetic
 // decoder runs with m = 5 (signed: sign in bit 5 of each byte) or m = 6 magnitude bits.
 template <> struct Codec<F6S> {
-    static constexpr int BITS = 6;
+    static constexpr int BITS = 6, ACC_EXP = 14;
     static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
     {
-        const u32 m0 = ~w0 & 0x1f1f1f1fu, m1 = ~w1 & 0x1f1f1f1fu;         // 31 - c in every byte
+        const u32 m0 = w0 & 0x1f1f1f1fu, m1 = w1 & 0x1f1f1f1fu;           // c in every byte
         u32 h[4], v[4];
         h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
         h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
         h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
         h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
-        recip_decode_4pairs(h, 0x88008800u, v);
-        d[0] = (v[0] & 0x7fff7fffu) | ((w0 << 10) & 0x80008000u);         // sign: bit 5 of bytes 0, 2
-        d[1] = (v[1] & 0x7fff7fffu) | ((w0 << 2) & 0x80008000u);          //       bit 5 of bytes 1, 3
-        d[2] = (v[2] & 0x7fff7fffu) | ((w1 << 10) & 0x80008000u);
-        d[3] = (v[3] & 0x7fff7fffu) | ((w1 << 2) & 0x80008000u);
+        recip_decode_4pairs(h, (_Float16)1056.0f, 0x50005000u, v);
+        d[0] = v[0] | ((w0 << 10) & 0x80008000u);                         // sign: bit 5 of bytes 0, 2
+        d[1] = v[1] | ((w0 << 2) & 0x80008000u);                          //       bit 5 of bytes 1, 3
+        d[2] = v[2] | ((w1 << 10) & 0x80008000u);
+        d[3] = v[3] | ((w1 << 2) & 0x80008000u);
     }
 };
 
 template <> struct Codec<F6U> {
-    static constexpr int BITS = 6;
-    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)
+    static constexpr int BITS = 6, ACC_EXP = 14;
+    static __device__ __forceinline__ void two_words(u32 w0, u32 w1, u32 *d)                  // bytes hold 6 bits each
     {
-        const u32 m0 = ~w0 & 0x3f3f3f3fu, m1 = ~w1 & 0x3f3f3f3fu;         // 63 - c in every byte
         u32 h[4];
-        h[0] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04020400u);
-        h[1] = __builtin_amdgcn_perm(0x64646464u, m0, 0x04030401u);
-        h[2] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04020400u);
-        h[3] = __builtin_amdgcn_perm(0x64646464u, m1, 0x04030401u);
-        recip_decode_4pairs(h, 0x8C008C00u, d);
+        h[0] = __builtin_amdgcn_perm(0x64646464u, w0, 0x04020400u);
+        h[1] = __builtin_amdgcn_perm(0x64646464u, w0, 0x04030401u);
+        h[2] = __builtin_amdgcn_perm(0x64646464u, w1, 0x04020400u);
+        h[3] = __builtin_amdgcn_perm(0x64646464u, w1, 0x04030401u);
+        recip_decode_4pairs(h, (_Float16)1088.0f, 0x54005400u, d);
     }
 };
 
@@ -192,7 +191,7 @@ template <> struct Codec<F6U> {
 // (v_perm_b32) indexed by the code itself, sign included; the low byte is zero.
 // half_word: 8 codes (k0..k7) in the low 16 bits of w -> (k0,k2), (k1,k3), (k4,k6), (k5,k7).
 template <u32 TABLE> struct Codec2 {
-    static constexpr int BITS = 2;
+    static constexpr int BITS = 2, ACC_EXP = 0;
     static __device__ __forceinline__ u32 spread_even(u32 w)       // fields 0, 2, 4, 6 -> one per byte
     {
         return (w & 0x3u) | ((w << 4) & 0x300u) | ((w << 8) & 0x30000u) | ((w << 12) & 0x3000000u);
@@ -213,7 +212,7 @@ template <> struct Codec<F2U> : Codec2<0x403C3800u> {};   //                    
 // 4-bit formats: every value has at most 3 significant bits, so its half has a zero low byte
 // and the high byte comes from an 8-entry byte table held in two registers (v_perm_b32).
 template <> struct Codec<F4S> {
-    static constexpr int BITS = 4;
+    static constexpr int BITS = 4, ACC_EXP = 0;
     // 8 codes (k0..k7) -> (k0,k2), (k1,k3), (k4,k6), (k5,k7)
     static __device__ __forceinline__ void word(u32 w, u32 *d)
     {
@@ -231,7 +230,7 @@ template <> struct Codec<F4S> {
 };
 
 template <> struct Codec<F4U> {
-    static constexpr int BITS = 4;
+    static constexpr int BITS = 4, ACC_EXP = 0;
     static __device__ __forceinline__ void word(u32 w, u32 *d)
     {
         // high bytes of 0 .. .875 in steps of .125, then 1, 1.25, 1.5, 1.75, 2, 3, 4, 8 (Table I)

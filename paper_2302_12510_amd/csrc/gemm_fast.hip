@@ -1,23 +1,24 @@
-// Large-tile DyBit matrix product for gfx950: 256 x 256 tile of C per workgroup, K step 64,
-// eight waves (two per SIMD); wave w owns rows 32 w .. 32 w + 31 of the tile and all 256
-// columns, i.e. 8 accumulator blocks of 32 x 32 in 128 AGPRs.
+// Large-tile DyBit matrix product for gfx950: 256 x 256 tile of C per workgroup, eight waves (two
+// per SIMD); wave w owns rows 32 w .. 32 w + 31 of the tile and all 256 columns, i.e. 8 accumulator
+// blocks of 32 x 32 in 128 AGPRs.  K step TK = 128 (K, for a convolution Cin, a multiple of 128) or 64.
 //
 // Why this shape.  Measured on this chip, a wave issues about one instruction per five cycles
 // and every MFMA occupies the vector-ALU issue port for about twelve of its 32 cycles, so the
 // decode arithmetic (the bulk of the instructions) must be spread over two waves per SIMD and
 // nothing else may compete for issue slots.  LDS stores are the slow LDS operation (about 36
 // cycles per 128-bit store per wave), LDS loads are not.  Hence:
-//   * the activation operand A never touches LDS: every lane fetches the 32 codes of its own
-//     row that its MFMA fragments need (128-bit buffer loads, two K steps ahead), decodes them
-//     in registers and feeds the MFMA directly.  With one 32-row block per wave no A code is
-//     decoded twice.
-//   * the weight operand W is decoded once per workgroup (each thread 32 codes per K step),
+//   * the activation operand A never touches LDS: every lane fetches the TK / 2 codes of its own
+//     row that its MFMA fragments need (consecutive 128-bit buffer loads, two K steps ahead), decodes
+//     them in registers and feeds the MFMA directly.  With one 32-row block per wave no A code is
+//     decoded twice.  With TK = 128 the two lanes of a row together fetch 128 bytes of 8-bit codes,
+//     one whole cache line per row and step, and there is one workgroup barrier per 128 k.
+//   * the weight operand W is decoded once per workgroup (each thread TK / 2 codes per K step),
 //     stored to a double-buffered LDS tile with one 128-bit store per 8 codes and read back by
 //     all eight waves as MFMA fragments (`ds_read_b128`, rows padded by 16 B: no bank conflicts,
-//     immediate offsets only).
+//     immediate offsets only) through a ring of four registers.
 //   * decode is arithmetic / byte-permute work in the vector ALU, no table look-ups.
-// A lane of k-group g (lane / 32) owns k = 32 g .. 32 g + 31 of every K step; MFMA block kk of
-// a step contracts k = 32 g + 8 kk .. + 7.  The order of k inside an MFMA does not matter as
+// A lane of k-group g (lane / 32) owns k = g TK/2 .. g TK/2 + TK/2 - 1 of every K step; MFMA block kk
+// of a step contracts k = g TK/2 + 8 kk .. + 7.  The order of k inside an MFMA does not matter as
 // long as both operands agree, so both codecs emit each group of eight k values in the order
 // (k0,k2,k1,k3,k4,k6,k5,k7): that is the order their packed arithmetic produces for free.
 #include <hip/hip_runtime.h>
@@ -33,28 +34,34 @@
 #ifndef DYBIT_FAST_W
 #error "compile with -DDYBIT_FAST_W=<weight format id> (0: 4-bit signed, 2: 8-bit signed)"
 #endif
+#ifndef DYBIT_FAST_VALU_PER_MFMA
+#define DYBIT_FAST_VALU_PER_MFMA 4     // vector-ALU instructions the scheduler places behind each MFMA
+#endif
 
 namespace dybit {
 namespace fast {
 
-
-constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int ROW_BYTES = TK * 2 + 16;            // one LDS row of W: 64 halves = 8 chunks of 16 B, plus 16 B of padding
-constexpr int STAGE_BYTES = TN * ROW_BYTES;       // 36 KiB per stage
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+constexpr int TM = 256, TN = 256;
+template <int TK> struct Geom {
+    static constexpr int KK = TK / 16;                         // MFMA k blocks per K step
+    static constexpr int ROW_BYTES = TK * 2 + 16;              // one LDS row of W: TK halves plus 16 B of padding
+    static constexpr int STAGE_BYTES = TN * ROW_BYTES;         // 36 KiB (TK = 64) or 68 KiB (TK = 128) per stage
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+};
 
 // ---------------------------------------------------------------------------
-// Kernel.  RB = 32-row blocks of A per wave: 1 -> eight waves (two per SIMD), 2 -> four waves.
+// Kernel
 // ---------------------------------------------------------------------------
-template <int FMT_A, int FMT_W, bool CONV, int RB, bool WB>
-__global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
+template <int FMT_A, int FMT_W, bool CONV, int TK, bool WB>
+__global__ __launch_bounds__(512) void gemm_fast_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
-    constexpr int NTHREADS = 512 / RB;
-    constexpr int NA = CA::BITS / 4;                               // 128-bit loads per lane, row block and K step
-    constexpr int WPT = RB;                                        // W k-halves (32 codes) per thread and K step
-    constexpr int NW = CW::BITS / 4;                               // 128-bit loads per k-half
+    using G = Geom<TK>;
+    constexpr int KK = G::KK, ROW_BYTES = G::ROW_BYTES, STAGE_BYTES = G::STAGE_BYTES;
+    constexpr int RUN_A = CA::BITS / 4, RUN_W = CW::BITS / 4;      // 128-bit registers per run of 32 codes
+    constexpr int NA = RUN_A * (TK / 64);                          // 128-bit loads per lane and K step (consecutive bytes)
+    constexpr int NW = RUN_W * (TK / 64);                          // ... per thread for W
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -81,36 +88,30 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
     const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
 
-    // ---- A: the lane's own rows (one per row block), its k-group's half of the K step
+    // ---- A: the lane's own row, its k-group's half of the K step
     const int a_row_bytes = (int)(g.K * CA::BITS / 8), w_row_bytes = (int)(g.K * CW::BITS / 8);
     const int pix_bytes = CONV ? g.Cin * CA::BITS / 8 : 0;
-    u32 offA[RB];
-    int hi0[RB], wi0[RB];
-    bool okA[RB];
-#pragma unroll
-    for (int i = 0; i < RB; ++i) {
-        const int64_t m = m0 + (wave * RB + i) * 32 + (lane & 31);
-        okA[i] = m < g.M;
-        hi0[i] = wi0[i] = 0;
-        if (CONV) {
-            const int64_t mm = okA[i] ? m : 0;
-            const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
-            const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
-            const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
-            hi0[i] = ho * g.stride - g.pad;
-            wi0[i] = wo * g.stride - g.pad;
-            offA[i] = (u32)((((int64_t)b * g.H + hi0[i]) * g.Wd + wi0[i]) * pix_bytes + kg * 16 * NA);
-        } else {
-            offA[i] = okA[i] ? (u32)(m * a_row_bytes + kg * 16 * NA) : kOob;   // rows past M stay out of range as k advances
-        }
+    u32 offA;
+    int hi0 = 0, wi0 = 0;
+    const int64_t m_lane = m0 + wave * 32 + (lane & 31);
+    const bool okA = m_lane < g.M;
+    if (CONV) {
+        const int64_t mm = okA ? m_lane : 0;
+        const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
+        const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
+        const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+        hi0 = ho * g.stride - g.pad;
+        wi0 = wo * g.stride - g.pad;
+        offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kg * 16 * NA);
+    } else {
+        offA = okA ? (u32)(m_lane * a_row_bytes + kg * 16 * NA) : kOob;   // rows past M stay out of range as k advances
     }
-    // ---- W staging.  Eight waves: thread t decodes row t / 2, k-half t % 2.  Four waves: row t, both k-halves.
-    const int wrow = RB == 1 ? (tid >> 1) : tid;
-    const int wh0 = RB == 1 ? (tid & 1) : 0;
+    // ---- W staging: thread t decodes row t / 2, k-half t % 2
+    const int wrow = tid >> 1, wh0 = tid & 1;
     const int64_t nrow = n0 + wrow;
     const u32 offW = nrow < g.N ? (u32)(nrow * w_row_bytes + wh0 * 16 * NW) : kOob;
-    const u32 wrW = (u32)wrow * ROW_BYTES + (u32)wh0 * 64;                       // chunk 4 h + q
-    const u32 rdW = (u32)(lane & 31) * ROW_BYTES + (u32)kg * 64;                 // chunk 4 g + kk, block j adds 32 rows
+    const u32 wrW = (u32)wrow * ROW_BYTES + (u32)wh0 * TK;                       // chunk KK h + q
+    const u32 rdW = (u32)(lane & 31) * ROW_BYTES + (u32)kg * TK;                 // chunk KK g + kk, block j adds 32 rows
 
     // Tiles at or past ktiles (the prefetch of the last steps, and the padding step when the
     // number of K steps is odd) are fetched from an out-of-range offset: they read zeros.
@@ -118,63 +119,51 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
     // K steps are loaded in order, so for a convolution the filter row, filter column and first
     // channel of the next step are counted up instead of being divided out of k every time.
     int a_fr = 0, a_fs = 0, a_c0 = 0;
-    auto load_A = [&](int64_t kt, u32x4 (*raw)[NA]) {
-        const int64_t k0 = kt * TK;
-        const int tap_off = CONV ? (a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * CA::BITS / 8 : 0;
-#pragma unroll
-        for (int i = 0; i < RB; ++i) {
-            u32 off;
-            if (CONV) {
-                const bool in = okA[i] && (unsigned)(hi0[i] + a_fr) < (unsigned)g.H && (unsigned)(wi0[i] + a_fs) < (unsigned)g.Wd;
-                off = (in && kt < ktiles) ? offA[i] + (u32)tap_off : kOob;            // padding reads code 0
-            } else {
-                off = kt < ktiles ? offA[i] + (u32)(k0 * CA::BITS / 8) : kOob;
-            }
-#pragma unroll
-            for (int p = 0; p < NA; ++p) raw[i][p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
-        }
+    auto load_A = [&](int64_t kt, u32x4 *raw) {
+        u32 off;
         if (CONV) {
+            const int tap_off = (a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * CA::BITS / 8;
+            const bool in = okA && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
+            off = (in && kt < ktiles) ? offA + (u32)tap_off : kOob;            // padding reads code 0
             a_c0 += TK;
             while (a_c0 >= g.Cin) {
                 a_c0 -= g.Cin;
                 if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
             }
+        } else {
+            off = kt < ktiles ? offA + (u32)(kt * TK * CA::BITS / 8) : kOob;
         }
+#pragma unroll
+        for (int p = 0; p < NA; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off + p * 16, 0, 0);
     };
-    auto load_W = [&](int64_t kt, u32x4 (*raw)[NW]) {
+    auto load_W = [&](int64_t kt, u32x4 *raw) {
         const u32 off = kt < ktiles ? offW + (u32)(kt * TK * CW::BITS / 8) : kOob;
 #pragma unroll
-        for (int h = 0; h < WPT; ++h)
-#pragma unroll
-            for (int p = 0; p < NW; ++p) raw[h][p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + (h * NW + p) * 16, 0, 0);
+        for (int p = 0; p < NW; ++p) raw[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off + p * 16, 0, 0);
     };
+    // q: group of eight codes among the TK / 2 of the lane (run q / 4, group q % 4 of that run)
     auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
         u32 d[4];
-        decode_eight<FMT_A>(raw, q, d);
+        decode_eight<FMT_A>(raw + (q >> 2) * RUN_A, q & 3, d);
         return __builtin_bit_cast(f16x8, u32x4{d[0], d[1], d[2], d[3]});
     };
-    auto stage_W = [&](u32x4 (*raw)[NW], int q, char *tile) {
-#pragma unroll
-        for (int h = 0; h < WPT; ++h) {
-            u32 d[4];
-            decode_eight<FMT_W>(raw[h], q, d);
-            *reinterpret_cast<u32x4 *>(tile + wrW + h * 64 + q * 16) = u32x4{d[0], d[1], d[2], d[3]};
-        }
+    auto stage_W = [&](const u32x4 *raw, int q, char *tile) {
+        u32 d[4];
+        decode_eight<FMT_W>(raw + (q >> 2) * RUN_W, q & 3, d);
+        *reinterpret_cast<u32x4 *>(tile + wrW + q * 16) = u32x4{d[0], d[1], d[2], d[3]};
     };
     auto read_W = [&](const char *tile, int kk, int j) -> f16x8 {
         return *reinterpret_cast<const f16x8 *>(tile + rdW + kk * 16 + j * 32 * ROW_BYTES);
     };
 
-    f32x16 acc[RB][8];
+    f32x16 acc[8];
 #pragma unroll
-    for (int i = 0; i < RB; ++i)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
 
-    u32x4 rawA[2][RB][NA], rawW[2][WPT][NW];
-    f16x8 fw[8], fa[RB];
+    u32x4 rawA[2][NA], rawW[2][NW];
+    f16x8 fw[4], fa;
 
     // ---- prologue: W tile 0 decoded into stage 0, A/W tile 1 in flight, first fragments in registers
     load_A(0, rawA[0]);
@@ -182,19 +171,19 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
     load_A(1, rawA[1]);
     load_W(1, rawW[1]);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) stage_W(rawW[0], q, lds);
-#pragma unroll
-    for (int i = 0; i < RB; ++i) fa[i] = decode_A(rawA[0][i], 0);
+    for (int q = 0; q < KK; ++q) stage_W(rawW[0], q, lds);
+    fa = decode_A(rawA[0], 0);
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 8; ++j) fw[j] = read_W(lds, 0, j);
+    for (int j = 0; j < 4; ++j) fw[j] = read_W(lds, 0, j);
 
-    // One K step over LDS stage s: four k blocks of 8 RB MFMAs.  As soon as the MFMAs that use a
-    // W fragment have issued, its register is refilled with the fragment of the next k block.
-    // The next W tile is decoded into the other stage during blocks 0..2; the workgroup barrier
-    // sits before block 3 and the first fragments of the next tile are requested right after it,
-    // so their LDS latency hides behind the MFMAs of block 3.  The A fragments of block kk + 1
-    // are decoded during block kk; the A codes of tile kt + 2 are fetched once tile kt's have
+    // One K step over LDS stage s: KK k blocks of 8 MFMAs.  The W fragments go through a ring of four
+    // registers: as soon as the MFMA that uses one has issued, it is refilled with the fragment four
+    // MFMAs ahead (column blocks 4..7 of this k block, then blocks 0..3 of the next).
+    // The next W tile is decoded into the other stage during blocks 0..KK-2; the workgroup barrier
+    // sits before the last block and the first fragments of the next tile are requested right after
+    // it, so their LDS latency hides behind the MFMAs of that block.  The A fragment of block kk + 1
+    // is decoded during block kk; the A codes of tile kt + 2 are fetched once tile kt's have
     // been consumed.  Every step is the same straight-line code (no tail variants: the
     // accumulators stay in place), so the last steps decode and prefetch tiles of zeros.
     auto step = [&](int64_t kt, auto stage_tag) {
@@ -203,31 +192,26 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
         char *nxt = lds + (s ^ 1) * STAGE_BYTES;
         load_W(kt + 2, rawW[s]);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk == 3) __syncthreads();
-            f16x8 fa_cur[RB];
-#pragma unroll
-            for (int i = 0; i < RB; ++i) fa_cur[i] = fa[i];
+        for (int kk = 0; kk < KK; ++kk) {
+            if (kk == KK - 1) __syncthreads();
+            const f16x8 fa_cur = fa;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-#pragma unroll
-                for (int i = 0; i < RB; ++i)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa_cur[i], fw[j], acc[i][j], 0, 0, 0);
-                fw[j] = kk < 3 ? read_W(cur, kk + 1, j) : read_W(nxt, 0, j);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa_cur, fw[j & 3], acc[j], 0, 0, 0);
+                if (j < 4) fw[j & 3] = read_W(cur, kk, j + 4);
+                else fw[j & 3] = kk < KK - 1 ? read_W(cur, kk + 1, j - 4) : read_W(nxt, 0, j - 4);
             }
-#pragma unroll
-            for (int i = 0; i < RB; ++i) fa[i] = kk < 3 ? decode_A(rawA[s][i], kk + 1) : decode_A(rawA[s ^ 1][i], 0);
+            fa = kk < KK - 1 ? decode_A(rawA[s], kk + 1) : decode_A(rawA[s ^ 1], 0);
             if (kk == 0) { stage_W(rawW[s ^ 1], 0, nxt); stage_W(rawW[s ^ 1], 1, nxt); }
-            if (kk == 1) stage_W(rawW[s ^ 1], 2, nxt);
-            if (kk == 2) stage_W(rawW[s ^ 1], 3, nxt);
-            if (kk == 2) load_A(kt + 2, rawA[s]);                   // tile kt's codes are fully decoded by now
-            // Issue order inside the block: RB MFMAs, the fragment refill behind them, a share of
+            else if (kk < KK - 1) stage_W(rawW[s ^ 1], kk + 1, nxt);
+            if (kk == KK - 2) load_A(kt + 2, rawA[s]);              // tile kt's codes are fully decoded by now
+            // Issue order inside the block: an MFMA, the fragment refill behind it, a share of
             // the decode arithmetic.
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x008, RB, 0);                // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                 // DS read
-                __builtin_amdgcn_sched_group_barrier(0x002, 6 * RB, 0);            // VALU
+                __builtin_amdgcn_sched_group_barrier(0x002, DYBIT_FAST_VALU_PER_MFMA, 0);   // VALU
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -239,26 +223,31 @@ __global__ __launch_bounds__(512 / RB) void gemm_fast_kernel(const GemmArgs g, c
     }
 
     // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU), running maximum
-#pragma unroll
-    for (int i = 0; i < RB; ++i) epilogue_strip<8, WB>(g, acc[i], m0 + (wave * RB + i) * 32, n0);
+    epilogue_strip<8, WB, true, CA::ACC_EXP + CW::ACC_EXP>(g, acc, m0 + wave * 32, n0);
 }
 
-constexpr int kRowBlocks = 1;   // row blocks per wave of the instantiated kernels
+template <int FA, int FW, bool CONV, int TK>
+static void launch_tk(const GemmArgs &g, hipStream_t st)
+{
+    const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
+    const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8)), block(512);
+    auto k = gemm_fast_kernel<FA, FW, CONV, TK, kWriteBack>;
+    note_kernel(DYBIT_KERNEL_F16_256);
+    note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, Geom<TK>::LDS_BYTES));
+    hipLaunchKernelGGL(k, grid, block, Geom<TK>::LDS_BYTES, st, g, tiles_m, tiles_n);
+}
 
+// K steps of 128 where a step never straddles a row end or a filter tap, else of 64.
 template <int FA, int FW>
 static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 {
-    const int tiles_m = (int)((g.M + TM - 1) / TM), tiles_n = (int)((g.N + TN - 1) / TN);
-    const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8)), block(512 / kRowBlocks);
-    note_kernel(DYBIT_KERNEL_F16_256);
+    const bool wide = (conv ? g.Cin : g.K) % 128 == 0;
     if (conv) {
-        auto k = gemm_fast_kernel<FA, FW, true, kRowBlocks, kWriteBack>;
-        note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-        hipLaunchKernelGGL(k, grid, block, LDS_BYTES, st, g, tiles_m, tiles_n);
+        if (wide) launch_tk<FA, FW, true, 128>(g, st);
+        else launch_tk<FA, FW, true, 64>(g, st);
     } else {
-        auto k = gemm_fast_kernel<FA, FW, false, kRowBlocks, kWriteBack>;
-        note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-        hipLaunchKernelGGL(k, grid, block, LDS_BYTES, st, g, tiles_m, tiles_n);
+        if (wide) launch_tk<FA, FW, false, 128>(g, st);
+        else launch_tk<FA, FW, false, 64>(g, st);
     }
 }
 

@@ -298,7 +298,7 @@ __global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_k
     }
 
     // ---- epilogue: C = acc * (sA sW) (+ bias) (ReLU), running maximum
-    epilogue_strip<4, WB>(g, acc, m0 + wr * 32, n0);
+    epilogue_strip<4, WB, true, CA::ACC_EXP + CW::ACC_EXP>(g, acc, m0 + wr * 32, n0);
 }
 
 template <int FA, int FW, int CONV, int KG>

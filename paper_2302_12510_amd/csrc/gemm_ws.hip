@@ -216,7 +216,7 @@ __global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_ker
             step(kt, std::integral_constant<int, 0>{});
             if (kt + 1 < ktiles) step(kt + 1, std::integral_constant<int, 1>{});
         }
-        run_max = fmaxf(run_max, epilogue_strip<CB, WB, false>(g, acc, m_strip, 0));
+        run_max = fmaxf(run_max, epilogue_strip<CB, WB, false, CA::ACC_EXP + CW::ACC_EXP>(g, acc, m_strip, 0));
     }
 
     // ---- running maximum: one merge per workgroup.  The persistent waves finish their strips in step,

@@ -70,16 +70,22 @@ __global__ __launch_bounds__(kThreads) void rmse_kernel(const float *__restrict_
     const size_t n4 = n >> 2;
     const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
     Sums a{0.0, 0.0, 0.0};
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-    for (; i + (kInFlight - 1) * stride < n4; i += kInFlight * stride) {
+    // a workgroup reads contiguous chunks of kInFlight x kThreads 128-bit words (loads a whole grid
+    // apart, a large power of two, would keep hitting the same memory channels)
+    constexpr size_t per_block = (size_t)kThreads * kInFlight;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
+        const size_t i = base + threadIdx.x;
         f32x4 v[kInFlight];
+        if (base + per_block <= n4) {                                  // uniform: a whole chunk
 #pragma unroll
-        for (int u = 0; u < kInFlight; ++u) v[u] = __builtin_nontemporal_load(x4 + i + u * stride);
+            for (int u = 0; u < kInFlight; ++u) v[u] = __builtin_nontemporal_load(x4 + i + u * kThreads);
 #pragma unroll
-        for (int u = 0; u < kInFlight; ++u) add4<M, SIGNED>(a, v[u], rinv, s);
+            for (int u = 0; u < kInFlight; ++u) add4<M, SIGNED>(a, v[u], rinv, s);
+        } else {
+            for (int u = 0; u < kInFlight; ++u)
+                if (i + u * kThreads < n4) add4<M, SIGNED>(a, x4[i + u * kThreads], rinv, s);
+        }
     }
-    for (; i < n4; i += stride) add4<M, SIGNED>(a, x4[i], rinv, s);
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
         const float xe = x[(n4 << 2) + threadIdx.x];
         const float d = quant_error<M, SIGNED>(xe, rinv, s);
@@ -122,7 +128,7 @@ template <int M, bool SIGNED>
 void launch_rmse(const float *x, size_t n, const float *scale, double *out, int *flag, hipStream_t st)
 {
     size_t blocks = (n / 4 + (size_t)kThreads * kInFlight) / ((size_t)kThreads * kInFlight);
-    if (blocks > 256 * 8) blocks = 256 * 8;
+    if (blocks > 256 * 4) blocks = 256 * 4;
     hipLaunchKernelGGL((rmse_kernel<M, SIGNED>), dim3((unsigned)blocks), dim3(kThreads), 0, st, x, n, scale, out, flag);
 }
 

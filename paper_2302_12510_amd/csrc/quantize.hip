@@ -38,27 +38,30 @@ __global__ void absmax_init_kernel(float *scale_out) { *scale_out = 0.0f; }
 __global__ __launch_bounds__(kThreads) void absmax_kernel(const float *__restrict__ x, size_t n,
                                                           float *scale_out)
 {
+    // A workgroup reads contiguous chunks of 4 x kThreads 128-bit words (16 KiB), four loads in flight per
+    // lane.  (A lane whose four loads are a whole grid apart -- a large power of two -- keeps hitting
+    // the same memory channels: that form measured 5.4 TB/s against 7.0 TB/s for this one.)
     const size_t n4 = n >> 2;
     const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
     float mx = 0.0f;
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-    for (; i + 3 * stride < n4; i += 4 * stride) {
-        const f32x4 a = __builtin_nontemporal_load(x4 + i);
-        const f32x4 b = __builtin_nontemporal_load(x4 + i + stride);
-        const f32x4 c = __builtin_nontemporal_load(x4 + i + 2 * stride);
-        const f32x4 d = __builtin_nontemporal_load(x4 + i + 3 * stride);
-        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
-        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
-        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
-        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
-    }
-    for (; i < n4; i += stride) {
-        const f32x4 a = x4[i];
-        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+    constexpr size_t per_block = (size_t)kThreads * 4;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
+        const size_t i = base + threadIdx.x;
+        f32x4 v[4];
+        if (base + per_block <= n4) {                                  // uniform: a whole chunk
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(x4 + i + u * kThreads);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = (i + u * kThreads < n4) ? x4[i + u * kThreads] : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v[u].x), fabsf(v[u].y)), fmaxf(fabsf(v[u].z), fabsf(v[u].w))));
     }
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) mx = fmaxf(mx, fabsf(x[(n4 << 2) + threadIdx.x]));
-    // one atomic per workgroup: atomics on a single address serialise in L2 (about 10 ns each)
+    // At most one atomic per workgroup, and only when it would raise the word: atomics on a single address
+    // serialise in L2 (about 10 ns each).  A stale read can only cause a needless atomic.
     __shared__ float wave_max[kThreads / 64];
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = mx;
@@ -66,7 +69,9 @@ __global__ __launch_bounds__(kThreads) void absmax_kernel(const float *__restric
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) mx = fmaxf(mx, wave_max[w]);
-        if (mx > 0.0f) atomicMax(reinterpret_cast<unsigned int *>(scale_out), __float_as_uint(mx));
+        unsigned int *word = reinterpret_cast<unsigned int *>(scale_out);
+        const unsigned int bits = __float_as_uint(mx);
+        if (bits > __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(word, bits);
     }
 }
 
@@ -88,21 +93,26 @@ __global__ void absmax_finish_kernel(float *scale_out, float inv_vmax)
 // The result must be the code nearest to x in exact arithmetic, but x / s cannot be formed
 // exactly in float.  Two paths:
 //
-//  fast  q = |x| * fl(1/s) is within 2^-23 (relative) of the true quotient t.  The "real-valued
-//        code" c(t) -- t * 2^(m-1) below 1, 2^m - n(t) above, where n(t) is t's bit pattern
-//        subtracted from a constant (the inverse of magnitude_value) -- is piecewise linear,
-//        continuous, and the decision points are exactly its half-integers.  It is rounded to
+//  fast  q = min(|x| * fl(1/s), vmax) is within 2^-23 (relative) of the true quotient t.  The
+//        "real-valued code" c(t) -- t * 2^(m-1) below 1, then the inverse of magnitude_value -- is
+//        piecewise linear, continuous, and the decision points are exactly its half-integers.
+//        One expression yields n = 2^m - c(q) over the whole range: with q' = q * 2^-126,
+//        n = bitcast(((127 + m) << 23) - bits(q')).  For q >= 1 that is the decoder's identity read
+//        backwards; for q < 1, q' is a subnormal float whose bits are q * 2^23, linear in q, and the
+//        difference lands in the top binade [2^(m-1), 2^m] at 2^m - q 2^(m-1).  n is rounded to
 //        G fractional bits with one magic-number addition; unless those bits read exactly
 //        one half, q and t are on the same side of every decision point and the code is the
-//        integer part rounded half up.
-//  exact when the G bits read one half (probability 2^-G), for NaN, and for scales so
+//        integer part rounded half up.  Error budget: |c(q) - c(t)| <= 1.5 * 2^(m-24) < 2^-(G+1).
+//        A NaN becomes q = 0 (v_med3_f32 returns the minimum of its other operands for a NaN).
+//  exact when the G bits read one half (probability 2^-G), and for scales so
 //        extreme that 1/s or the product could leave the normal range: the side of the
 //        decision point is the sign of fma(-s, mid, |x|), which is exact; zero is a tie and
 //        goes to the even code.
 template <int M>
 struct QConst {
-    static constexpr int G = 12;                                       // 2^(M-23) error << 2^-(G+1)
+    static constexpr int G = 13;                                       // 1.5 * 2^(M-24) < 2^-(G+1) for M <= 8; 2^M + magic stays in magic's binade
     static constexpr uint32_t kRecip = (uint32_t)(254 + M - 1) << 23;  // see magnitude_value
+    static constexpr uint32_t kRecipSub = (uint32_t)(127 + M) << 23;   // the same constant for an argument scaled by 2^-126
     static constexpr uint32_t kMagic = ((uint32_t)(127 + 23 - G) << 23) | 0x400000u;  // 1.5 * 2^(23-G)
     static constexpr uint32_t kRound = kMagic + (1u << (G - 1));
     static constexpr uint32_t kTop = (1u << M) - 1;
@@ -155,29 +165,64 @@ __device__ __forceinline__ uint32_t quantize_exact(float x, float s)
     return (SIGNED && neg && j) ? (j | (1u << M)) : j;
 }
 
-// Fast path for one element; sets `redo` when the exact path must decide.
+// Fast path for one element: kRound minus the rounded n, i.e. the magnitude code in bits G .. G+M-1
+// (rounded half up) above G fraction bits that are all zero exactly when the exact path must decide.
+template <int BITS, bool SIGNED>
+__device__ __forceinline__ uint32_t quantize_fast_raw(float x, float rinv)
+{
+    constexpr int M = SIGNED ? BITS - 1 : BITS;
+    using K = QConst<M>;
+    const float vmax = (float)(1u << (M - 1));
+    const float t = x * rinv;
+    const float q = SIGNED ? __builtin_amdgcn_fmed3f(fabsf(t), 0.0f, vmax) : __builtin_amdgcn_fmed3f(t, 0.0f, vmax);   // NaN -> 0
+    const float qs = q * __uint_as_float(1u << 23);                      // q * 2^-126
+    const float nf = __uint_as_float(K::kRecipSub - __float_as_uint(qs));   // 2^m - c
+    return K::kRound - __float_as_uint(nf + __uint_as_float(K::kMagic));
+}
+
+// One element: the code (sign included, possibly a negative zero); sets `redo` when the exact path must decide.
 template <int BITS, bool SIGNED>
 __device__ __forceinline__ uint32_t quantize_fast(float x, float rinv, bool &redo)
 {
     constexpr int M = SIGNED ? BITS - 1 : BITS;
     using K = QConst<M>;
-    const float vmax = (float)(1u << (M - 1));
-    const float q = SIGNED ? fminf(fabsf(x) * rinv, vmax) : fminf(fmaxf(x * rinv, 0.0f), vmax);
-    const float lin = q * -(float)(1u << (M - 1));                       // -c
-    const float rec = __uint_as_float(K::kRecip - __float_as_uint(q));   // 2^m - c
-    const float y = (q < 1.0f) ? lin : rec;
-    const uint32_t zb = __float_as_uint(y + __uint_as_float(K::kMagic));
-    redo = ((zb & ((1u << K::G) - 1)) == (1u << (K::G - 1))) | (x != x);
-    uint32_t code = ((K::kRound - zb) >> K::G) & K::kTop;
+    const uint32_t r = quantize_fast_raw<BITS, SIGNED>(x, rinv);
+    redo = (r << (32 - K::G)) == 0u;
+    uint32_t code = (r >> K::G) & K::kTop;
     if (SIGNED) code |= (__float_as_uint(x) >> (31 - M)) & (1u << M);
     return code;
 }
 
-// Clears the sign bit of every field whose magnitude is zero (fields of BITS bits in a word).
+// Four elements: their codes packed into fields of BITS bits (negative zeros cleared); sets `redo`
+// when the exact path must decide one of them.
+template <int BITS>
+__device__ __forceinline__ uint32_t clear_negative_zero(uint32_t w);
+template <int BITS, bool SIGNED>
+__device__ __forceinline__ uint32_t quantize_fast4(const float (&e)[4], float rinv, bool &redo)
+{
+    constexpr int M = SIGNED ? BITS - 1 : BITS;
+    using K = QConst<M>;
+    uint32_t r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r[k] = quantize_fast_raw<BITS, SIGNED>(e[k], rinv);
+    // the smallest of the four fraction fields (moved to the top of the word) is zero when one of them is
+    redo = min(min(r[0] << (32 - K::G), r[1] << (32 - K::G)), min(r[2] << (32 - K::G), r[3] << (32 - K::G))) == 0u;
+    uint32_t w = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w |= ((r[k] >> K::G) & K::kTop) << (k * BITS);
+    if (SIGNED) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w |= (__float_as_uint(e[k]) >> (31 - M - k * BITS)) & (1u << (M + k * BITS));
+        w = clear_negative_zero<BITS>(w);
+    }
+    return w;
+}
+
+// Clears the sign bit of every field whose magnitude is zero (four fields of BITS bits in a word).
 template <int BITS>
 __device__ __forceinline__ uint32_t clear_negative_zero(uint32_t w)
 {
-    constexpr uint32_t ones = BITS == 8 ? 0x01010101u : BITS == 4 ? 0x11111111u : BITS == 2 ? 0x55555555u : 0u;
+    constexpr uint32_t ones = 1u | (1u << BITS) | (1u << (2 * BITS)) | (1u << (3 * BITS));
     constexpr uint32_t sign = ones << (BITS - 1);
     constexpr uint32_t magm = sign - ones;
     const uint32_t t = w & magm;
@@ -207,7 +252,8 @@ __device__ __forceinline__ ScaleInfo load_scale(const float *scale, float inv_vm
     return si;
 }
 
-// 4 consecutive elements per lane per load (coalesced float4), UNROLL loads in flight.
+// 4 consecutive elements per lane per load (coalesced float4), UNROLL loads in flight; a workgroup works
+// on contiguous chunks of UNROLL x kThreads loads.  Whole chunks run without bounds checks.
 // Output per load: 4*BITS bits, stored as one 8/16/32-bit word.  BITS in {2, 4, 8}.
 template <int BITS, bool SIGNED, int UNROLL>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restrict__ x, size_t n4,
@@ -223,33 +269,35 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
     }
     const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
     word_t *o = reinterpret_cast<word_t *>(out);
-    const size_t per_block = (size_t)kThreads * UNROLL;
-    for (size_t base = (size_t)blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
-        f32x4 v[UNROLL];
+    auto encode = [&](const f32x4 v) -> uint32_t {
+        const float e[4] = {v.x, v.y, v.z, v.w};
+        bool redo;
+        uint32_t w = quantize_fast4<BITS, SIGNED>(e, si.rinv, redo);
+        if (redo | si.all_exact) {
+            w = 0;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const size_t i = base + (size_t)u * kThreads + threadIdx.x;
-            v[u] = (i < n4) ? __builtin_nontemporal_load(x4 + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < 4; ++k) w |= quantize_exact<BITS, SIGNED>(e[k], si.s) << (k * BITS);
         }
+        return w;
+    };
+    constexpr size_t per_block = (size_t)kThreads * UNROLL;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
+        const size_t i = base + threadIdx.x;
+        f32x4 v[UNROLL];
+        if (base + per_block <= n4) {                                  // uniform: a whole chunk
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const size_t i = base + (size_t)u * kThreads + threadIdx.x;
-            const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-            uint32_t w = 0;
-            bool any_redo = si.all_exact;
+            for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(x4 + i + u * kThreads);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                bool redo;
-                w |= quantize_fast<BITS, SIGNED>(e[k], si.rinv, redo) << (k * BITS);
-                any_redo |= redo;
+            for (int u = 0; u < UNROLL; ++u) __builtin_nontemporal_store((word_t)encode(v[u]), o + i + u * kThreads);
+        } else {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                v[u] = (i + u * kThreads < n4) ? __builtin_nontemporal_load(x4 + i + u * kThreads) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t w = encode(v[u]);
+                if (i + u * kThreads < n4) __builtin_nontemporal_store((word_t)w, o + i + u * kThreads);
             }
-            if (SIGNED) w = clear_negative_zero<BITS>(w);
-            if (any_redo) {
-                w = 0;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) w |= quantize_exact<BITS, SIGNED>(e[k], si.s) << (k * BITS);
-            }
-            if (i < n4) __builtin_nontemporal_store((word_t)w, o + i);
         }
     }
 }
@@ -283,20 +331,13 @@ __global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__rest
         for (int u = 0; u < UNROLL; ++u) {
             const size_t i = base + (size_t)u * kThreads + threadIdx.x;
             const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-            uint32_t c[4];
-            bool any_redo = si.all_exact;
+            bool redo;
+            uint32_t own = quantize_fast4<6, SIGNED>(e, si.rinv, redo);   // four 6-bit fields
+            if (redo | si.all_exact) {
+                own = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                bool redo;
-                c[j] = quantize_fast<6, SIGNED>(e[j], si.rinv, redo);
-                if (SIGNED && (c[j] & 31u) == 0u) c[j] = 0u;
-                any_redo |= redo;
+                for (int j = 0; j < 4; ++j) own |= quantize_exact<6, SIGNED>(e[j], si.s) << (6 * j);
             }
-            if (any_redo) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) c[j] = quantize_exact<6, SIGNED>(e[j], si.s);
-            }
-            const uint32_t own = c[0] | (c[1] << 6) | (c[2] << 12) | (c[3] << 18);
             const uint32_t right = __shfl_down(own, 1, 64);              // every lane takes part; lane 3 of a group ignores it
             const uint32_t w = (own >> (8 * k)) | (right << (24 - 8 * k));
             if (k < 3 && i < n4) __builtin_nontemporal_store(w, o + (i >> 2) * 3 + k);
@@ -512,7 +553,7 @@ extern "C" dybit_status dybit_absmax_scale(const float *x, size_t n, dybit_fmt f
     if (!aligned16(x)) return DYBIT_ERR_ALIGNMENT;
     hipStream_t hs = (hipStream_t)stream;
     hipLaunchKernelGGL(absmax_init_kernel, dim3(1), dim3(1), 0, hs, scale_out);
-    if (n) hipLaunchKernelGGL(absmax_kernel, dim3(grid_for(n / 4 + 1, kThreads * 8, 256 * 4)), dim3(kThreads), 0, hs, x, n, scale_out);
+    if (n) hipLaunchKernelGGL(absmax_kernel, dim3(grid_for(n / 4 + 1, kThreads * 4, 256 * 4)), dim3(kThreads), 0, hs, x, n, scale_out);
     const int m = mag_bits(f.bits, f.is_signed);
     hipLaunchKernelGGL(absmax_finish_kernel, dim3(1), dim3(1), 0, hs, scale_out, 1.0f / (float)(1u << (m - 1)));
     return launch_status();

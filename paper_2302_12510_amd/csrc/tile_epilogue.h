@@ -18,7 +18,16 @@
 
 namespace dybit {
 
-template <int CB, bool HAS_RES>
+// ACC_EXP: the accumulators hold the sum times 2^-ACC_EXP (operands decoded on a power-of-two scale,
+// dybit_codec.h); they are multiplied back first, which is exact, so the result is rounded as before.
+template <int ACC_EXP>
+__device__ __forceinline__ float acc_value(float a)
+{
+    if constexpr (ACC_EXP == 0) return a;
+    else return a * __uint_as_float((uint32_t)(127 + ACC_EXP) << 23);
+}
+
+template <int CB, bool HAS_RES, int ACC_EXP>
 __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB], const int64_t m_strip,
                                              const int64_t n0, const int rows, const float alpha)
 {
@@ -73,7 +82,7 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
         uint32_t off = off0;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            float c = acc[j][v] * al + b;
+            float c = acc_value<ACC_EXP>(acc[j][v]) * al + b;
             if (HAS_RES) c += res[v];
             if (g.relu) c = fmaxf(c, 0.0f);
             __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c), rsrc, off, 0, 2);
@@ -94,7 +103,7 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
 // lane's value sits within 2^-G of a decision point (or is NaN): the exact decision for those;
 // (3) sign, packing across lanes, store of the packed words through a descriptor of their own.
 // A NULL fp32 output becomes an empty descriptor whose stores the hardware drops.
-template <int CB, bool HAS_RES, int BITS>
+template <int CB, bool HAS_RES, int BITS, int ACC_EXP>
 __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f32x16 (&acc)[CB], const int64_t m_strip,
                                                 const int64_t n0, const int rows, const float alpha)
 {
@@ -161,7 +170,7 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
 #pragma unroll
             for (int u = 0; u < GV; ++u) {                                   // phase 1
                 const int v = h + u;
-                c[u] = acc[j][v] * al + b;
+                c[u] = acc_value<ACC_EXP>(acc[j][v]) * al + b;
                 if (HAS_RES) c[u] += res[u];
                 c[u] = fmaxf(c[u], relu_floor);
                 __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c[u]), rsrc, off, 0, 2);
@@ -204,7 +213,7 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
 // FOLD: merge the strip's maximum into the running maximum here (one read, at most one atomic per
 // wave); a kernel whose waves store many strips passes false, keeps the returned per-lane maximum
 // and merges once at its end.
-template <int CB, bool WB, bool FOLD = true>
+template <int CB, bool WB, bool FOLD = true, int ACC_EXP = 0>
 __device__ __forceinline__ float epilogue_strip(const GemmArgs &g, const fast::f32x16 (&acc)[CB],
                                                const int64_t m_strip, const int64_t n0)
 {
@@ -215,17 +224,17 @@ __device__ __forceinline__ float epilogue_strip(const GemmArgs &g, const fast::f
     float mx = 0.0f;
     if (WB) {                                                       // the host has checked ldc, N and the format
         if (g.residual) {
-            mx = g.q_bits == 4 ? store_strip_wb<CB, true, 4>(g, acc, m_strip, n0, rows, alpha)
-               : g.q_bits == 8 ? store_strip_wb<CB, true, 8>(g, acc, m_strip, n0, rows, alpha)
-                               : store_strip_wb<CB, true, 6>(g, acc, m_strip, n0, rows, alpha);
+            mx = g.q_bits == 4 ? store_strip_wb<CB, true, 4, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
+               : g.q_bits == 8 ? store_strip_wb<CB, true, 8, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
+                               : store_strip_wb<CB, true, 6, ACC_EXP>(g, acc, m_strip, n0, rows, alpha);
         } else {
-            mx = g.q_bits == 4 ? store_strip_wb<CB, false, 4>(g, acc, m_strip, n0, rows, alpha)
-               : g.q_bits == 8 ? store_strip_wb<CB, false, 8>(g, acc, m_strip, n0, rows, alpha)
-                               : store_strip_wb<CB, false, 6>(g, acc, m_strip, n0, rows, alpha);
+            mx = g.q_bits == 4 ? store_strip_wb<CB, false, 4, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
+               : g.q_bits == 8 ? store_strip_wb<CB, false, 8, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
+                               : store_strip_wb<CB, false, 6, ACC_EXP>(g, acc, m_strip, n0, rows, alpha);
         }
     } else if (g.ldc < (1 << 23)) {
-        mx = g.residual ? store_strip<CB, true>(g, acc, m_strip, n0, rows, alpha)
-                        : store_strip<CB, false>(g, acc, m_strip, n0, rows, alpha);
+        mx = g.residual ? store_strip<CB, true, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
+                        : store_strip<CB, false, ACC_EXP>(g, acc, m_strip, n0, rows, alpha);
     } else {                                                        // leading dimension too large for 32-bit offsets
 #pragma unroll
         for (int j = 0; j < CB; ++j) {
@@ -237,7 +246,7 @@ __device__ __forceinline__ float epilogue_strip(const GemmArgs &g, const fast::f
             for (int v = 0; v < 16; ++v) {
                 const int r = 8 * (v >> 2) + 4 * kq + (v & 3);
                 if (n_ok && r < rows) {
-                    float c = acc[j][v] * al + b;
+                    float c = acc_value<ACC_EXP>(acc[j][v]) * al + b;
                     if (g.residual) c += g.residual[(m_strip + r) * g.ldc + n];
                     if (g.relu) c = fmaxf(c, 0.0f);
                     __builtin_nontemporal_store(c, g.C + (m_strip + r) * g.ldc + n);

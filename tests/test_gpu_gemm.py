@@ -142,6 +142,7 @@ def run_conv(qx, x_fmt, sx, qw, w_fmt, sw, stride, pad, bias=None, relu=False):
                        pack_rows_dev(qx.reshape(-1, Cin), x_fmt[0]), x_fmt, scalar(sx),
                        pack_rows_dev(qw.reshape(-1, Cin), w_fmt[0]), w_fmt, scalar(sw),
                        None if bias is None else dev(bias), relu)
+    assert_forced_kernel_ran()
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
@@ -188,6 +189,9 @@ def test_conv_few_channels(x_fmt, w_fmt, Cin, kw, kh, stride, pad, shape):
     qw = random_codes(rng, (Cout, kh, kw, Cin), w_fmt)
     bias = rng.normal(0, 1, Cout).astype(np.float32)
     got = run_conv(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, False)
+    # which kernel took it: whole filter rows (aligned words: tensors of whole words only), else the general one
+    by_rows = kw * Cin == 32 and kh % 2 == 0 and (Bn * H * W * Cin * x_fmt[0] // 8) % 4 == 0
+    assert B.dybit_last_gemm_kernel() == ("f16_128_rows" if by_rows else "general")
     want, den = R.conv2d(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, False)
     assert got.shape == want.shape
     assert_within(got, want, den)
@@ -443,8 +447,13 @@ def test_weight_stationary_kernel_conv(force_kernel, x_fmt, w_fmt, geom):
                                                  ((2, True), (8, True), 4, 8), ((8, False), (4, True), 2, 16)])
 @pytest.mark.parametrize("kh,stride,pad,shape", [(8, 2, 3, (3, 23, 21)), (2, 3, 4, (2, 12, 16)), (4, 1, 2, (2, 9, 27)), (6, 2, 5, (1, 30, 17))])
 def test_weight_stationary_kernel_few_channels(force_kernel, x_fmt, w_fmt, Cin, kw, kh, stride, pad, shape):
-    """Filter rows of exactly 32 codes fetched row by row (see test_conv_few_channels), weights resident."""
+    """Filter rows of exactly 32 codes fetched row by row (see test_conv_few_channels), weights resident.
+    The rows are fetched as aligned 32-bit words, so the kernel is only taken for image tensors of a
+    whole number of words; the others must fall back to the general kernel (and still be right)."""
+    global _expected_kernels
     Bn, H, W = shape
+    if (Bn * H * W * Cin * x_fmt[0] // 8) % 4:
+        _expected_kernels = {"general"}
     rng = np.random.default_rng(Cin * 100 + kw * 10 + kh + 1)
     Cout = 100
     qx = random_codes(rng, (Bn, H, W, Cin), x_fmt)
