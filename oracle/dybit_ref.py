@@ -415,8 +415,10 @@ def dwconv2d(x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, stride, pad, bias
             win = ix[:, r:r + stride * Ho:stride, q:q + stride * Wo:stride, :]
             acc += win * iw[r, q, :]
             den += np.abs(win) * np.abs(iw[r, q, :])
-    unit = float(np.float64(np.float32(x_scale)) * np.float64(np.float32(w_scale))) \
-        * 2.0 ** (-(magnitude_bits(*x_fmt) - 1) - (magnitude_bits(*w_fmt) - 1))
+    sw = np.asarray(w_scale, dtype=np.float32).astype(np.float64)            # one number, or one per channel
+    if sw.ndim not in (0, 1) or (sw.ndim == 1 and sw.size != C):
+        raise ValueError("w_scale is a scalar or one value per channel")
+    unit = np.float64(np.float32(x_scale)) * sw * 2.0 ** (-(magnitude_bits(*x_fmt) - 1) - (magnitude_bits(*w_fmt) - 1))
     y, d = acc * unit, den * unit
     if bias is not None:
         b = np.asarray(bias, dtype=np.float32).astype(np.float64)
@@ -425,6 +427,34 @@ def dwconv2d(x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, stride, pad, bias
     if relu:
         y = np.maximum(y, 0.0)
     return y, d
+
+
+def group_conv2d(x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, stride, pad, groups,
+                 bias=None, relu=False, residual=None):
+    """Grouped convolution (the layer type between the dense and the depthwise convolution of the
+    networks of Sec. IV): input channels and output channels are split into `groups` equal parts and
+    part g of the output sees part g of the input only.  x_codes [B][H][W][Cin]; w_codes
+    [Cout][kh][kw][Cin / groups]; output channel n belongs to group n // (Cout / groups).  w_scale is
+    one number or one per output channel.  Written as the definition: one dense convolution per group
+    on its channel slices, the results side by side.  Returns (Y, D) like conv2d."""
+    x_codes = np.asarray(x_codes, dtype=np.uint8)
+    w_codes = np.asarray(w_codes, dtype=np.uint8)
+    B, H, W, Cin = x_codes.shape
+    Cout, kh, kw, Cg = w_codes.shape
+    if groups < 1 or Cin % groups or Cout % groups or Cg * groups != Cin:
+        raise ValueError("groups must divide Cin and Cout, and the filters hold Cin / groups channels")
+    Cog = Cout // groups
+    sw = np.asarray(w_scale, dtype=np.float32)
+    ys, ds = [], []
+    for g in range(groups):
+        n0, n1 = g * Cog, (g + 1) * Cog
+        y, d = conv2d(x_codes[..., g * Cg:(g + 1) * Cg], x_fmt, x_scale, w_codes[n0:n1], w_fmt,
+                      sw if sw.ndim == 0 else sw[n0:n1], stride, pad,
+                      None if bias is None else np.asarray(bias)[n0:n1], relu,
+                      None if residual is None else np.asarray(residual)[..., n0:n1])
+        ys.append(y)
+        ds.append(d)
+    return np.concatenate(ys, axis=-1), np.concatenate(ds, axis=-1)
 
 
 # --------------------------------------------------------------------------
@@ -457,4 +487,28 @@ def quantize_rows(x2d: np.ndarray, bits: int, signed: bool):
     codes = np.stack([quantize(row, scales[i], bits, signed) for i, row in enumerate(x2d)]) if len(x2d) else \
         np.zeros(x2d.shape, dtype=np.uint8)
     return scales, codes
+
+
+def quantize_cols(x2d: np.ndarray, bits: int, signed: bool):
+    """Per-column max-abs scales and codes of a matrix [rows][cols]: the per-channel scales of a
+    depthwise filter, whose layout [kh*kw][C] has the channel innermost.  absmax_scale and quantize
+    applied to every column on its own.  Returns (scales float32 [cols], codes [rows][cols])."""
+    x2d = np.asarray(x2d, dtype=np.float32)
+    scales, codes = quantize_rows(np.ascontiguousarray(x2d.T), bits, signed)
+    return scales, np.ascontiguousarray(codes.T)
+
+
+def fake_quant_grad(x: np.ndarray, grad: np.ndarray, scale, bits: int, signed: bool) -> np.ndarray:
+    """Backward of the quantize-then-decode operator of the fine-tuning step (Sec. III-C) under the
+    straight-through estimator: the rounding is treated as the identity and the saturation as the
+    clamp it is, so d x_hat / d x = 1 where x lies inside the representable range
+    [-s vmax, s vmax] (unsigned formats: [0, s vmax]), bounds included, and 0 outside (and for NaN).
+    Returns grad * mask as float32."""
+    x = np.asarray(x, dtype=np.float32)
+    g = np.asarray(grad, dtype=np.float32)
+    hi = np.float64(np.float32(scale)) * vmax(bits, signed)
+    lo = -hi if signed else 0.0
+    xd = x.astype(np.float64)
+    inside = (xd >= lo) & (xd <= hi)                                         # False for NaN
+    return np.where(inside, g, np.float32(0.0)).astype(np.float32)
 
