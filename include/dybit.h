@@ -227,18 +227,71 @@ dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t C,
                             const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
                             const float *bias, int32_t relu, float *Y, float *y_absmax, dybit_stream stream);
 
+/* dybit_dwconv2d with the options of the matrix-product calls (Sec. IV's depthwise-separable network inside
+ * the write-back dataflow of Sec. III-B):
+ *   w_per_channel  1: w_scale [device] holds C floats, one per channel (the scales dybit_quantize_cols
+ *                  returns for a [kh*kw][C] filter); 0: one float for the whole filter.
+ *   Y              [device, may be NULL when Y_codes is given]: the fp32 output.
+ *   y_fmt, y_scale, Y_codes  [may be NULL: no codes]: every result is also encoded with format y_fmt (4 or
+ *                  8 bits; DYBIT_ERR_UNSUPPORTED_BITS otherwise) under the known scale *y_scale [device], exactly
+ *                  as dybit_quantize would encode the fp32 value, and stored packed along C as [B][Ho][Wo][C]
+ *                  codes (C * bits a multiple of 32).  An unusable scale (see dybit_gemm_wb) writes no codes
+ *                  and sets the asynchronous error flag.
+ * Everything else as in dybit_dwconv2d. */
+dybit_status dybit_dwconv2d_wb(int64_t B, int64_t H, int64_t W, int64_t C,
+                               int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                               const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                               const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale, int32_t w_per_channel,
+                               const float *bias, int32_t relu, float *Y, float *y_absmax,
+                               dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream);
+
+/* Grouped convolution (the layer type between the dense and the depthwise convolution in the networks of
+ * Sec. IV): input and output channels are split into `groups` equal parts and part g of the output sees
+ * part g of the input only; output channel n belongs to group n / (Cout / groups).
+ * X_codes [device]: [B][H][W][Cin] codes.  Wt_codes [device]: [Cout][kh][kw][Cin / groups] codes.
+ * groups must divide Cin and Cout (DYBIT_ERR_INVALID_ARG); a group's channels must start on a byte of every
+ * pixel and filter, i.e. (Cin / groups) * bits a multiple of 8 for both formats (DYBIT_ERR_ALIGNMENT).
+ * w_scale [device]: 1 float, or Cout floats when w_per_channel is 1.  bias [device, may be NULL]: Cout floats.
+ * residual [device, may be NULL]: like Y.  Y [device]: [B][Ho][Wo][Cout] floats.  y_absmax: as in dybit_conv2d_ex.
+ * One launch per group on the group's channel slices (groups = Cin = Cout is a depthwise convolution with the
+ * filters laid out [C][kh][kw][1]; dybit_dwconv2d, with channel-innermost filters, is the fast form of that). */
+dybit_status dybit_group_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int32_t kh, int32_t kw, int32_t stride, int32_t pad, int32_t groups,
+                                const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale, int32_t w_per_channel,
+                                const float *bias, const float *residual, int32_t relu,
+                                float *Y, float *y_absmax, dybit_stream stream);
+
+/* Max-abs scale and codes of every column of x on its own: the per-channel scales of a depthwise filter,
+ * whose layout [kh*kw][C] has the channel innermost.
+ *   x [device]: rows * cols floats, row-major.  cols * bits must be a multiple of 8 (DYBIT_ERR_ALIGNMENT).
+ *   scales_out [device]: cols floats, scales_out[c] = max|x[:][c]| / 2^(m-1) (1.0 for an all-zero column).
+ *   codes_out [device]: rows * cols * bits / 8 bytes, laid out like x.  A column whose maximum is infinite
+ *   or subnormal gets code 0 throughout and sets the asynchronous error flag. */
+dybit_status dybit_quantize_cols(const float *x, int64_t rows, int64_t cols, dybit_fmt f, float *scales_out,
+                                 uint8_t *codes_out, dybit_stream stream);
+
 /* *scale_out = *absmax / 2^(m-1), or 1.0 when *absmax == 0: the last step of dybit_absmax_scale,
  * for a maximum obtained otherwise.  absmax, scale_out [device]: 1 float each (may be the same word). */
 dybit_status dybit_scale_from_absmax(const float *absmax, dybit_fmt f, float *scale_out, dybit_stream stream);
 
 /* Quantize and decode again in one pass, y = s * value(code nearest to x / s): the forward of the
  * quantization-aware training step that follows the search (Sec. III-C); bit for bit the result of
- * dybit_dequantize on dybit_quantize's codes, without the codes reaching memory.  (The straight-through
- * gradient of that step is the identity inside the representable range and is left to the caller.)
+ * dybit_dequantize on dybit_quantize's codes, without the codes reaching memory (its gradient:
+ * dybit_fake_quant_bwd).
  * x, y_out [device]: n floats each, 16-byte aligned (may be the same buffer).  scale [device]: as for
  * dybit_quantize; an unusable scale writes nothing and sets the asynchronous error flag. */
 dybit_status dybit_fake_quant(const float *x, size_t n, dybit_fmt f, const float *scale, float *y_out,
                               dybit_stream stream);
+
+/* Backward of dybit_fake_quant under the straight-through estimator (the fine-tuning step of Sec. III-C
+ * treats the rounding as the identity and the saturation as the clamp it is):
+ *     grad_in[j] = grad_out[j]  if x[j] lies in [-s vmax, s vmax] (unsigned formats: [0, s vmax]), bounds included,
+ *                = 0            otherwise, and for a NaN x[j].
+ * x, grad_out, grad_in [device]: n floats each, 16-byte aligned (grad_in may be grad_out).  scale [device]:
+ * the scale of the forward; not positive or not finite: nothing is written and the asynchronous error flag is set. */
+dybit_status dybit_fake_quant_bwd(const float *x, const float *grad_out, size_t n, dybit_fmt f, const float *scale,
+                                  float *grad_in, dybit_stream stream);
 
 /* Quantization error of one tensor in one format (Sec. III-C, Eq. 2):
  *     RMSE = sqrt( mean( ((x - x_hat) / sigma)^2 ) ),   x_hat = s * value(code nearest to x / s),

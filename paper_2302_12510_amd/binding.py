@@ -61,6 +61,10 @@ def lib() -> C.CDLL:
         L.dybit_conv2d_pc.argtypes = L.dybit_conv2d_wb.argtypes
         L.dybit_rmse.argtypes = [vp, sz, Fmt, vp, vp, vp]
         L.dybit_fake_quant.argtypes = [vp, sz, Fmt, vp, vp, vp]
+        L.dybit_fake_quant_bwd.argtypes = [vp, vp, sz, Fmt, vp, vp, vp]
+        L.dybit_quantize_cols.argtypes = [vp, i64, i64, Fmt, vp, vp, vp]
+        L.dybit_dwconv2d_wb.argtypes = [i64] * 4 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, i32, vp, i32, vp, vp, Fmt, vp, vp, vp]
+        L.dybit_group_conv2d.argtypes = [i64] * 5 + [i32] * 5 + [vp, Fmt, vp, vp, Fmt, vp, i32, vp, vp, i32, vp, vp, vp]
         L.dybit_search.argtypes = [i32, vp, vp, vp, i32, C.c_double, i32, vp, vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
         L.dybit_last_gemm_kernel.argtypes = []
@@ -207,6 +211,17 @@ def dybit_fake_quant(x: torch.Tensor, scale: torch.Tensor, bits: int, signed: bo
     return out
 
 
+def dybit_fake_quant_bwd(x: torch.Tensor, grad_out: torch.Tensor, scale: torch.Tensor, bits: int, signed: bool,
+                         out: torch.Tensor | None = None, stream=None):
+    """Straight-through gradient of dybit_fake_quant: grad_out where x lies inside the format's range, else 0."""
+    assert x.dtype == torch.float32 and grad_out.dtype == torch.float32 and grad_out.numel() == x.numel()
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().dybit_fake_quant_bwd(_ptr(x), _ptr(grad_out), x.numel(), fmt(bits, signed), _ptr(scale), _ptr(out),
+                                      _stream(stream)), "dybit_fake_quant_bwd")
+    return out
+
+
 def dybit_dequantize(codes: torch.Tensor, n: int, scale: torch.Tensor, bits: int, signed: bool,
                      out: torch.Tensor | None = None, stream=None):
     assert codes.dtype == torch.uint8
@@ -327,6 +342,52 @@ def dybit_dwconv2d(B: int, H: int, W: int, C: int, kh: int, kw: int, stride: int
                                 _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias), int(bool(relu)),
                                 _ptr(out), _ptr(absmax), _stream(stream)), "dybit_dwconv2d")
     return out
+
+
+def dybit_dwconv2d_wb(B: int, H: int, W: int, C: int, kh: int, kw: int, stride: int, pad: int,
+                      x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, bias=None, relu: bool = False, absmax=None,
+                      y_fmt=None, y_scale=None, per_channel: bool = False, fp32: bool = True,
+                      out: torch.Tensor | None = None, stream=None):
+    """dybit_dwconv2d with per-channel weight scales (per_channel: w_scale holds C floats) and, with y_fmt and
+    y_scale, the results also (fp32=False: only) written back as codes.  Returns (Y or None, codes or None)."""
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    if fp32 and out is None:
+        out = torch.empty((B, Ho, Wo, C), dtype=torch.float32, device=x_scale.device)
+    codes = None
+    if y_fmt is not None:
+        codes = torch.empty((B, Ho, Wo, C * y_fmt[0] // 8), dtype=torch.uint8, device=x_scale.device)
+    _check(lib().dybit_dwconv2d_wb(B, H, W, C, kh, kw, stride, pad, _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
+                                   _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), int(bool(per_channel)), _ptr(bias), int(bool(relu)),
+                                   _ptr(out) if fp32 else None, _ptr(absmax), fmt(*(y_fmt or (4, False))), _ptr(y_scale),
+                                   _ptr(codes), _stream(stream)), "dybit_dwconv2d_wb")
+    return (out if fp32 else None), codes
+
+
+def dybit_group_conv2d(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: int, stride: int, pad: int, groups: int,
+                       x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, bias=None, residual=None, relu: bool = False,
+                       absmax=None, per_channel: bool = False, out: torch.Tensor | None = None, stream=None):
+    """Grouped convolution: x_codes [B][H][W][Cin], w_codes [Cout][kh][kw][Cin/groups]; returns Y [B][Ho][Wo][Cout]."""
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device=x_scale.device)
+    _check(lib().dybit_group_conv2d(B, H, W, Cin, Cout, kh, kw, stride, pad, groups, _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
+                                    _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), int(bool(per_channel)), _ptr(bias), _ptr(residual),
+                                    int(bool(relu)), _ptr(out), _ptr(absmax), _stream(stream)), "dybit_group_conv2d")
+    return out
+
+
+def dybit_quantize_cols(x: torch.Tensor, bits: int, signed: bool, stream=None):
+    """x: [rows][cols] float32.  Returns (scales [cols], codes [rows][cols*bits/8]): every column encoded under
+    its own max-abs scale (a depthwise filter [kh*kw][C] with one scale per channel)."""
+    assert x.dtype == torch.float32 and x.dim() == 2
+    rows, cols = x.shape
+    scales = torch.empty(cols, dtype=torch.float32, device=x.device)
+    codes = torch.empty((rows, cols * bits // 8), dtype=torch.uint8, device=x.device)
+    _check(lib().dybit_quantize_cols(_ptr(x), rows, cols, fmt(bits, signed), _ptr(scales), _ptr(codes), _stream(stream)),
+           "dybit_quantize_cols")
+    return scales, codes
 
 
 def dybit_quantize_rows(x: torch.Tensor, bits: int, signed: bool, stream=None):

@@ -19,6 +19,7 @@
 #include "dybit_device.h"
 #include "dybit_host.h"
 #include "gemm_args.h"
+#include "requant.h"
 
 namespace dybit {
 namespace {
@@ -35,8 +36,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 struct DwArgs {
     const uint32_t *X, *Wt;                        // packed codes, read as whole words
     const float *x_scale, *w_scale, *bias;
-    float *Y;
+    float *Y;                                      // may be NULL when q_out is given
     uint32_t *absmax_bits;
+    int w_per_channel;                             // w_scale holds one value per channel
+    uint8_t *q_out;                                // optional write-back as DyBit codes, packed along C like the image
+    const float *q_scale;
+    int q_bits, q_signed;
+    int *async_error;
     int B, H, W, C, Ho, Wo, kh, kw, stride, pad, relu;
     int a_bits, a_signed, w_bits, w_signed;
     int in_h, in_w;                                // extent of the input patch, halo included
@@ -109,18 +115,40 @@ __global__ __launch_bounds__(kThreads) void dwconv_kernel(const DwArgs a)
     }
     __syncthreads();
 
-    // ---- accumulate
-    const float alpha = (*a.x_scale) * (*a.w_scale);
+    // ---- accumulate.  A thread's four channels are the same for all its outputs: their scales are read once.
+    const int c_thread = c_first + (tid & (CG / 4 - 1)) * 4;
+    f32x4 alpha;
+    {
+        const float sx = *a.x_scale;
+        const bool pc = a.w_per_channel && c_thread < a.C;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) alpha[u] = sx * (pc ? a.w_scale[c_thread + u] : a.w_scale[0]);
+    }
+    // optional write-back (Sec. III-B): the four results of a thread are four neighbouring codes of the
+    // packed output pixel, i.e. 16 bits (4-bit formats) or one word (8-bit formats)
+    Requant rq{};
+    const bool wb = a.q_out != nullptr;
+    if (wb) {
+        rq = make_requant(a.q_scale, a.q_bits, a.q_signed);
+        if (!rq.ok && blockIdx.x == 0 && tid == 0) *a.async_error = DYBIT_ERR_BAD_SCALE;   // no codes, flag the call
+    }
     float mx = 0.0f;
-    auto finish = [&](const f32x4 acc, const f32x4 bv, float *dst) {
+    auto finish = [&](const f32x4 acc, const f32x4 bv, int64_t elem) {          // elem: index of the thread's first output value
         f32x4 y;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            y[u] = acc[u] * alpha + bv[u];
+            y[u] = acc[u] * alpha[u] + bv[u];
             if (a.relu) y[u] = fmaxf(y[u], 0.0f);
             mx = fmaxf(mx, fabsf(y[u]));
         }
-        __builtin_nontemporal_store(y, reinterpret_cast<f32x4 *>(dst));
+        if (a.Y) __builtin_nontemporal_store(y, reinterpret_cast<f32x4 *>(a.Y + elem));
+        if (wb && rq.ok) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) w |= requant_code(y[u], rq) << (u * a.q_bits);
+            if (a.q_bits == 8) *reinterpret_cast<uint32_t *>(a.q_out + elem) = w;
+            else *reinterpret_cast<uint16_t *>(a.q_out + (elem >> 1)) = (uint16_t)w;
+        }
     };
     if constexpr (K != 0) {
         // 3 x 3: a thread owns four neighbouring channels of one output column and R consecutive output
@@ -135,7 +163,7 @@ __global__ __launch_bounds__(kThreads) void dwconv_kernel(const DwArgs a)
         const bool col_ok = wo < a.Wo && c < a.C;                 // C is a multiple of 4: a quad is inside or outside
         f32x4 bv = {0.f, 0.f, 0.f, 0.f};
         if (a.bias && col_ok) bv = *reinterpret_cast<const f32x4 *>(a.bias + c);
-        float *dst = a.Y + (((int64_t)b * a.Ho + ho0 + py0) * a.Wo + wo) * a.C + c;
+        int64_t elem = (((int64_t)b * a.Ho + ho0 + py0) * a.Wo + wo) * a.C + c;
         const float *origin = tile + ((py0 * S) * in_w + px * S) * CG + quad * 4;
 #pragma unroll
         for (int i = 0; i < R; ++i) {
@@ -157,8 +185,8 @@ __global__ __launch_bounds__(kThreads) void dwconv_kernel(const DwArgs a)
                 for (int q = 0; q < K; ++q)
 #pragma unroll
                     for (int u = 0; u < 4; ++u) acc[u] = fmaf(win[r][q][u], wreg[r * K + q][u], acc[u]);
-            if (col_ok && ho0 + py0 + i < a.Ho) finish(acc, bv, dst);
-            dst += (int64_t)a.Wo * a.C;
+            if (col_ok && ho0 + py0 + i < a.Ho) finish(acc, bv, elem);
+            elem += (int64_t)a.Wo * a.C;
         }
     } else {
         // any other geometry: one item = four neighbouring channels of one output pixel, run-time loops
@@ -179,7 +207,7 @@ __global__ __launch_bounds__(kThreads) void dwconv_kernel(const DwArgs a)
             if (ho < a.Ho && wo < a.Wo && c < a.C) {
                 f32x4 bv = {0.f, 0.f, 0.f, 0.f};
                 if (a.bias) bv = *reinterpret_cast<const f32x4 *>(a.bias + c);
-                finish(acc, bv, a.Y + (((int64_t)b * a.Ho + ho) * a.Wo + wo) * a.C + c);
+                finish(acc, bv, (((int64_t)b * a.Ho + ho) * a.Wo + wo) * a.C + c);
             }
         }
     }
@@ -190,7 +218,7 @@ template <int BA, int BW>
 void launch_dw(const DwArgs &a, size_t lds_bytes, hipStream_t st, unsigned blocks)
 {
     auto go = [&](auto kernel) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), lds_bytes, st, a);
     };
     if (a.kh == 3 && a.kw == 3 && a.stride == 1) go(dwconv_kernel<BA, BW, 3, 1>);
@@ -203,11 +231,12 @@ void launch_dw(const DwArgs &a, size_t lds_bytes, hipStream_t st, unsigned block
 
 using namespace dybit;
 
-extern "C" dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t C,
-                                       int32_t kh, int32_t kw, int32_t stride, int32_t pad,
-                                       const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
-                                       const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
-                                       const float *bias, int32_t relu, float *Y, float *y_absmax, dybit_stream stream)
+static dybit_status dwconv_impl(int64_t B, int64_t H, int64_t W, int64_t C,
+                                int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale, int32_t w_per_channel,
+                                const float *bias, int32_t relu, float *Y, float *y_absmax,
+                                dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream)
 {
     dybit_status st = check_fmt(x_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
@@ -218,6 +247,14 @@ extern "C" dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t 
         return DYBIT_ERR_INVALID_ARG;
     if (H + 2 * (int64_t)pad < kh || W + 2 * (int64_t)pad < kw) return DYBIT_ERR_INVALID_ARG;
     if ((C * x_fmt.bits) % 32 || (C * w_fmt.bits) % 32) return DYBIT_ERR_ALIGNMENT;   // a pixel's codes are whole words
+    if (w_per_channel != 0 && w_per_channel != 1) return DYBIT_ERR_INVALID_ARG;
+    if (Y_codes) {
+        if ((st = check_fmt(y_fmt)) != DYBIT_OK) return st;
+        if (y_fmt.bits != 4 && y_fmt.bits != 8) return DYBIT_ERR_UNSUPPORTED_BITS;     // four codes of a thread are 16 or 32 bits
+        if ((C * y_fmt.bits) % 32) return DYBIT_ERR_ALIGNMENT;
+        if (!y_scale) return DYBIT_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(Y_codes) & 3u) return DYBIT_ERR_ALIGNMENT;
+    }
     const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
     const int TW = patch_width(kh, kw, stride);
     const int in_h = (TH - 1) * stride + kh, in_w = (TW - 1) * stride + kw;
@@ -226,12 +263,19 @@ extern "C" dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t 
     if (H * W * (C * x_fmt.bits / 32) > 0x7fffffff || (int64_t)kh * kw * (C * w_fmt.bits / 32) > 0x7fffffff)
         return DYBIT_ERR_INVALID_ARG;                                              // offsets inside one image are 32-bit
     if (B == 0 || C == 0) return DYBIT_OK;
-    if (!x_scale || !w_scale || !X_codes || !Wt_codes || !Y) return DYBIT_ERR_NULL;
+    if (!x_scale || !w_scale || !X_codes || !Wt_codes || (!Y && !Y_codes)) return DYBIT_ERR_NULL;
     if (!aligned16(X_codes) || !aligned16(Wt_codes) || !aligned16(Y) || (bias && !aligned16(bias))) return DYBIT_ERR_ALIGNMENT;
+    clear_call_record();
     DwArgs a{};
     a.X = reinterpret_cast<const uint32_t *>(X_codes); a.Wt = reinterpret_cast<const uint32_t *>(Wt_codes);
     a.x_scale = x_scale; a.w_scale = w_scale; a.bias = bias; a.Y = Y;
     a.absmax_bits = reinterpret_cast<uint32_t *>(y_absmax);
+    a.w_per_channel = w_per_channel;
+    if (Y_codes) {
+        a.q_out = Y_codes; a.q_scale = y_scale; a.q_bits = y_fmt.bits; a.q_signed = y_fmt.is_signed;
+        a.async_error = async_error_word();
+        if (!a.async_error) return DYBIT_ERR_HIP;
+    }
     a.B = (int)B; a.H = (int)H; a.W = (int)W; a.C = (int)C; a.Ho = (int)Ho; a.Wo = (int)Wo;
     a.kh = kh; a.kw = kw; a.stride = stride; a.pad = pad; a.relu = relu;
     a.a_bits = x_fmt.bits; a.a_signed = x_fmt.is_signed; a.w_bits = w_fmt.bits; a.w_signed = w_fmt.is_signed;
@@ -248,4 +292,26 @@ extern "C" dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t 
     }
 #undef DYBIT_DW
     return launch_status();
+}
+
+extern "C" dybit_status dybit_dwconv2d(int64_t B, int64_t H, int64_t W, int64_t C,
+                                       int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                       const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                       const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                       const float *bias, int32_t relu, float *Y, float *y_absmax, dybit_stream stream)
+{
+    if (!Y && B && C) return DYBIT_ERR_NULL;
+    return dwconv_impl(B, H, W, C, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, 0, bias, relu,
+                       Y, y_absmax, dybit_fmt{0, 0}, nullptr, nullptr, stream);
+}
+
+extern "C" dybit_status dybit_dwconv2d_wb(int64_t B, int64_t H, int64_t W, int64_t C,
+                                          int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                          const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                          const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale, int32_t w_per_channel,
+                                          const float *bias, int32_t relu, float *Y, float *y_absmax,
+                                          dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream)
+{
+    return dwconv_impl(B, H, W, C, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, w_per_channel, bias, relu,
+                       Y, y_absmax, y_fmt, y_scale, Y_codes, stream);
 }

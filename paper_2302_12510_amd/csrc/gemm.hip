@@ -217,7 +217,7 @@ __device__ __forceinline__ Unit<BITS> load_unit_A(const GemmArgs &g, const RowA 
         if (MODE == VEC) return load_unit_vec<BITS>(r.base + k0 * BITS / 8);
         return load_unit_elems<BITS>(r.base, k0, g.K);
     }
-    const int64_t pix_bytes = (int64_t)g.Cin * BITS / 8;
+    const int64_t pix_bytes = g.pix_bytes;
     if (MODE == VEC) {   // the whole unit lies inside one filter tap
         const int tap = (int)(k0 / g.Cin), c0 = (int)(k0 - (int64_t)tap * g.Cin);
         const int fr = tap / g.kw, fs = tap - fr * g.kw;
@@ -295,8 +295,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs g)
             const int64_t b = mm / ((int64_t)g.Ho * g.Wo);
             const int rem = (int)(mm - b * g.Ho * g.Wo);
             const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
-            ra[i].base = g.A + b * g.H * g.Wd * ((int64_t)g.Cin * BA / 8);
-            ra[i].img_off = (uint32_t)(b * g.H * g.Wd * ((int64_t)g.Cin * BA / 8));     // RUNS: the tensor is below 2 GiB
+            ra[i].base = g.A + b * g.H * g.Wd * (int64_t)g.pix_bytes;
+            ra[i].img_off = (uint32_t)(b * g.H * g.Wd * (int64_t)g.pix_bytes);     // RUNS: the tensor is below 2 GiB (and pixels are dense)
             ra[i].hi0 = ho * g.stride - g.pad;
             ra[i].wi0 = wo * g.stride - g.pad;
         } else {
@@ -525,8 +525,12 @@ dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t C
                          int32_t kh, int32_t kw, int32_t stride, int32_t pad,
                          const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
                          const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
-                         const Epilogue &e, float *Y, dybit_stream stream)
+                         const Epilogue &e, float *Y, dybit_stream stream,
+                         int64_t ldy = 0, int64_t image_channels = 0, int64_t x_bytes_left = 0)
 {
+    // ldy / image_channels / x_bytes_left (grouped convolution): X_codes and Y point at one channel group of
+    // tensors with image_channels input and ldy output channels per pixel; x_bytes_left bytes of the image
+    // tensor remain from X_codes on.  0: dense tensors of Cin and Cout channels.
     clear_call_record();
     dybit_status st = check_fmt(x_fmt);
     if (st == DYBIT_OK) st = check_fmt(w_fmt);
@@ -537,7 +541,9 @@ dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t C
     if (H + 2 * (int64_t)pad < kh || W + 2 * (int64_t)pad < kw) return DYBIT_ERR_INVALID_ARG;
     if ((int64_t)kh * kw > (1 << 24) || (int64_t)kh * kw * Cin > 0x7fffffff) return DYBIT_ERR_INVALID_ARG;   // K fits an int
     if ((Cin * x_fmt.bits) % 8 || (Cin * w_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
-    if ((st = check_codes_out(e, Cout, Cout)) != DYBIT_OK) return st;
+    if (ldy == 0) ldy = Cout;
+    if (image_channels == 0) image_channels = Cin;
+    if ((st = check_codes_out(e, Cout, ldy)) != DYBIT_OK) return st;
     const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
     if (B == 0 || Cout == 0) return DYBIT_OK;
     if (!x_scale || !w_scale || !X_codes || !Wt_codes) return DYBIT_ERR_NULL;
@@ -546,10 +552,12 @@ dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t C
     g.A = X_codes; g.W = Wt_codes;
     g.a_signed = x_fmt.is_signed; g.w_signed = w_fmt.is_signed;
     g.a_scale = x_scale; g.w_scale = w_scale;
-    if ((st = set_epilogue(g, e, Y, Cout)) != DYBIT_OK) return st;
+    if ((st = set_epilogue(g, e, Y, ldy)) != DYBIT_OK) return st;
     g.H = (int)H; g.Wd = (int)W; g.Cin = (int)Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.kh = kh; g.kw = kw; g.stride = stride; g.pad = pad;
-    g.a_bytes = B * H * W * (Cin * x_fmt.bits / 8);
+    g.pix_bytes = (int)(image_channels * x_fmt.bits / 8);
+    const bool dense = image_channels == Cin;
+    g.a_bytes = dense ? B * H * W * (Cin * x_fmt.bits / 8) : x_bytes_left;
     g.w_bytes = Cout * (g.K * w_fmt.bits / 8);
     if (launch_gemm_tiled(g, x_fmt.bits, w_fmt.bits, true, (hipStream_t)stream)) return launch_status();
     // operand access of the general kernel: whole 16-channel vectors, runs of neighbouring taps
@@ -557,7 +565,7 @@ dybit_status conv2d_impl(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t C
     const bool aligned = aligned16(X_codes) && aligned16(Wt_codes);
     int mode = 0;
     if (aligned && Cin % UNIT == 0) mode = 1;
-    else if (aligned && UNIT % Cin == 0 && ((int64_t)kw * Cin) % UNIT == 0 && g.a_bytes < 0x7fffffff && g.a_bytes % 4 == 0) mode = 2;
+    else if (aligned && dense && UNIT % Cin == 0 && ((int64_t)kw * Cin) % UNIT == 0 && g.a_bytes < 0x7fffffff && g.a_bytes % 4 == 0) mode = 2;
     (g.q_out ? launch_gemm_general_wb : launch_gemm_general)(g, x_fmt.bits, w_fmt.bits, true, mode, (hipStream_t)stream);
     return launch_status();
 }
@@ -662,5 +670,37 @@ extern "C" dybit_status dybit_conv2d_pc(int64_t B, int64_t H, int64_t W, int64_t
     e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = y_absmax; e.w_per_channel = true;
     e.has_codes = Y_codes != nullptr; e.q_fmt = y_fmt; e.q_scale = y_scale; e.q_out = Y_codes;
     return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scales, e, Y, stream);
+}
+extern "C" dybit_status dybit_group_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                           int32_t kh, int32_t kw, int32_t stride, int32_t pad, int32_t groups,
+                                           const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                           const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale, int32_t w_per_channel,
+                                           const float *bias, const float *residual, int32_t relu,
+                                           float *Y, float *y_absmax, dybit_stream stream)
+{
+    dybit_status st = check_fmt(x_fmt);
+    if (st == DYBIT_OK) st = check_fmt(w_fmt);
+    if (st != DYBIT_OK) return st;
+    if (groups < 1 || Cin < 1 || Cout < 0 || Cin % groups || Cout % groups || (w_per_channel != 0 && w_per_channel != 1))
+        return DYBIT_ERR_INVALID_ARG;
+    const int64_t Cg = Cin / groups, Cog = Cout / groups;
+    // a group's channels start on a byte of every pixel and of every filter
+    if ((Cg * x_fmt.bits) % 8 || (Cg * w_fmt.bits) % 8 || (Cin * x_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
+    if (B < 0 || H < 1 || W < 1 || kh < 1 || kw < 1) return DYBIT_ERR_INVALID_ARG;
+    if (B == 0 || Cout == 0) return DYBIT_OK;
+    if (!X_codes || !Wt_codes || !Y || !w_scale) return DYBIT_ERR_NULL;
+    const int64_t x_bytes = B * H * W * (Cin * x_fmt.bits / 8);
+    const int64_t group_x = Cg * x_fmt.bits / 8, group_w = Cog * ((int64_t)kh * kw * Cg * w_fmt.bits / 8);
+    Epilogue e;
+    e.relu = relu; e.absmax = y_absmax; e.w_per_channel = w_per_channel != 0;
+    for (int64_t gi = 0; gi < groups; ++gi) {
+        e.bias = bias ? bias + gi * Cog : nullptr;
+        e.residual = residual ? residual + gi * Cog : nullptr;
+        st = conv2d_impl(B, H, W, Cg, Cog, kh, kw, stride, pad, X_codes + gi * group_x, x_fmt, x_scale,
+                         Wt_codes + gi * group_w, w_fmt, w_per_channel ? w_scale + gi * Cog : w_scale, e, Y + gi * Cog, stream,
+                         Cout, Cin, x_bytes - gi * group_x);
+        if (st != DYBIT_OK) return st;
+    }
+    return DYBIT_OK;
 }
 #endif   // plain build

@@ -35,6 +35,8 @@ struct GemmArgs {
     int *async_error;                // device word that receives DYBIT_ERR_BAD_SCALE when *q_scale is unusable
     // convolution geometry (conv only)
     int H, Wd, Cin, Ho, Wo, kh, kw, stride, pad;
+    int pix_bytes;                   // bytes from a pixel to the next one in the image: Cin * bits / 8, or more when A
+                                     // points at one channel group of a wider image (grouped convolution)
     int64_t a_bytes, w_bytes;        // sizes of the two code buffers
 };
 

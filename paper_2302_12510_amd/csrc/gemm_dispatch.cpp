@@ -112,7 +112,8 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
     if (g.M < 1 || g.N < 1 || g.K < 64 || g.K % 64) return false;
     // a convolution needs whole 64-code k groups inside a filter tap, or (few channels) filter rows of
     // exactly 32 codes, which the 128 x 128 kernel fetches row by row
-    const bool rows = conv && g.Cin < 64 && (int64_t)g.kw * g.Cin == 32 && g.a_bytes % 4 == 0;   // fetched as aligned words: none may reach past the tensor
+    const bool dense = conv && (int64_t)g.pix_bytes * 8 == (int64_t)g.Cin * a_bits;   // not one channel group of a wider image
+    const bool rows = dense && g.Cin < 64 && (int64_t)g.kw * g.Cin == 32 && g.a_bytes % 4 == 0;   // fetched as aligned words: none may reach past the tensor
     if (conv && g.Cin % 64 && !rows) return false;
     if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W)) & 15) return false;
     if (g.a_bytes >= 0x7fffffff || g.w_bytes >= 0x7fffffff) return false;

@@ -179,7 +179,7 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 
     // ---- A: the lane's own row; per 64-wide block its 32 codes (16 bytes) at k-quarter kq
     const int a_row_bytes = (int)(g.K * BA / 8), w_row_bytes = (int)(g.K * BW / 8);
-    const int pix_bytes = CONV ? g.Cin * BA / 8 : 0;
+    const int pix_bytes = CONV ? g.pix_bytes : 0;
     u32 offA;
     int hi0 = 0, wi0 = 0;
     bool okA;

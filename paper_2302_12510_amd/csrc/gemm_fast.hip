@@ -90,7 +90,7 @@ __global__ __launch_bounds__(512) void gemm_fast_kernel(const GemmArgs g, const 
 
     // ---- A: the lane's own row, its k-group's half of the K step
     const int a_row_bytes = (int)(g.K * CA::BITS / 8), w_row_bytes = (int)(g.K * CW::BITS / 8);
-    const int pix_bytes = CONV ? g.Cin * CA::BITS / 8 : 0;
+    const int pix_bytes = CONV ? g.pix_bytes : 0;
     u32 offA;
     int hi0 = 0, wi0 = 0;
     const int64_t m_lane = m0 + wave * 32 + (lane & 31);

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_k
 
     // ---- A: the lane's own row, the 32 codes kq of its k-group's 64
     const int a_row_bytes = (int)(g.K * CA::BITS / 8), w_row_bytes = (int)(g.K * CW::BITS / 8);
-    const int pix_bytes = CONV ? g.Cin * CA::BITS / 8 : 0;
+    const int pix_bytes = CONV ? g.pix_bytes : 0;
     u32 offA;
     int hi0 = 0, wi0 = 0;
     bool okA;

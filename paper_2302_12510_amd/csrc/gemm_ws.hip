@@ -85,7 +85,7 @@ __global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_ker
     __syncthreads();
 
     const int a_row_bytes = (int)(g.K * CA::BITS / 8);
-    const int pix_bytes = CONV ? g.Cin * CA::BITS / 8 : 0;
+    const int pix_bytes = CONV ? g.pix_bytes : 0;
     const u32 rdW = (u32)(lane & 31) * (u32)row_bytes + (u32)kq * 64;   // K step adds 128 B, block kk 16 B, column block j 32 rows
 
     float run_max = 0.0f;                                            // max |C| over every strip this lane stores

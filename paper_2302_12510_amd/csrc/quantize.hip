@@ -456,6 +456,93 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const float *__
     }
 }
 
+// Column-wise (per-channel, channel innermost) max-abs scales of a matrix [rows][cols]: a workgroup owns
+// 64 neighbouring columns, four row lanes each, so that the loads of a wave are contiguous.
+__global__ __launch_bounds__(kThreads) void col_scale_kernel(const float *__restrict__ x, int64_t rows, int64_t cols, float inv_vmax,
+                                                             float *__restrict__ scales)
+{
+    const int c_local = threadIdx.x & 63, r_lane = threadIdx.x >> 6;
+    const int64_t c = (int64_t)blockIdx.x * 64 + c_local;
+    float mx = 0.0f;
+    if (c < cols)
+        for (int64_t r = r_lane; r < rows; r += kThreads / 64) mx = fmaxf(mx, fabsf(x[r * cols + c]));
+    __shared__ float part[kThreads / 64][64];
+    part[r_lane][c_local] = mx;
+    __syncthreads();
+    if (r_lane == 0 && c < cols) {
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) mx = fmaxf(mx, part[w][c_local]);
+        scales[c] = (mx == 0.0f) ? 1.0f : mx * inv_vmax;              // as dybit_absmax_scale
+    }
+}
+
+// Codes of a matrix [rows][cols] under one scale per column: a thread produces whole bytes (see
+// quantize_rows_kernel), every element with the exact encoder under its own column's scale.
+template <int BITS, bool SIGNED>
+__global__ __launch_bounds__(kThreads) void quantize_cols_kernel(const float *__restrict__ x, int64_t cols, int64_t groups,
+                                                                 const float *__restrict__ scales, uint8_t *__restrict__ out)
+{
+    constexpr int EPG = BITS == 8 ? 1 : BITS == 4 ? 2 : 4;             // elements per group of whole bytes
+    constexpr int BPG = BITS == 6 ? 3 : 1;
+    const int64_t gi = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // cols is a multiple of EPG: a group stays inside a row
+    if (gi >= groups) return;
+    uint32_t w = 0;
+    bool bad = false;
+#pragma unroll
+    for (int k = 0; k < EPG; ++k) {
+        const int64_t i = gi * EPG + k;
+        const float s = scales[i % cols];
+        const uint32_t e = (__float_as_uint(s) >> 23) & 0xffu;
+        const bool ok = s > 0.0f && e != 0u && e != 255u;              // an infinite or subnormal maximum: code 0
+        bad |= !ok;
+        w |= (ok ? quantize_exact<BITS, SIGNED>(x[i], s) : 0u) << (k * BITS);
+    }
+#pragma unroll
+    for (int b = 0; b < BPG; ++b) out[gi * BPG + b] = (uint8_t)(w >> (8 * b));
+    if (bad) g_async_error = DYBIT_ERR_BAD_SCALE;
+}
+
+// Straight-through gradient of the quantize-then-decode operator: the incoming gradient where x lies
+// inside [lo, hi] (bounds included), zero elsewhere and for NaN.  12 bytes per element.
+__global__ __launch_bounds__(kThreads) void fake_quant_bwd_kernel(const float *__restrict__ x, const float *__restrict__ grad, size_t n,
+                                                                  const float *__restrict__ scale, float vmax, int is_signed,
+                                                                  float *__restrict__ out)
+{
+    const float s = *scale;
+    if (!(s > 0.0f) || ((__float_as_uint(s) >> 23) & 0xffu) == 255u) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        return;
+    }
+    // s * 2^(m-1) is exact; should it overflow, every finite x is inside and +Inf is not
+    const float hi = fminf(s * vmax, __uint_as_float(0x7f7fffffu)), lo = is_signed ? -hi : 0.0f;
+    const size_t n4 = n >> 2;
+    const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x), *g4 = reinterpret_cast<const f32x4 *>(grad);
+    f32x4 *o4 = reinterpret_cast<f32x4 *>(out);
+    auto mask = [&](f32x4 xv, f32x4 gv) {
+        f32x4 r;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r[k] = (xv[k] >= lo && xv[k] <= hi) ? gv[k] : 0.0f;
+        return r;
+    };
+    constexpr size_t per_block = (size_t)kThreads * 2;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < n4; base += (size_t)gridDim.x * per_block) {
+        const size_t i = base + threadIdx.x;
+        if (base + per_block <= n4) {                                  // uniform: a whole chunk, four loads in flight
+            const f32x4 a0 = __builtin_nontemporal_load(x4 + i), a1 = __builtin_nontemporal_load(x4 + i + kThreads);
+            const f32x4 b0 = __builtin_nontemporal_load(g4 + i), b1 = __builtin_nontemporal_load(g4 + i + kThreads);
+            __builtin_nontemporal_store(mask(a0, b0), o4 + i);
+            __builtin_nontemporal_store(mask(a1, b1), o4 + i + kThreads);
+        } else {
+            for (int u = 0; u < 2; ++u)
+                if (i + u * kThreads < n4) o4[i + u * kThreads] = mask(x4[i + u * kThreads], g4[i + u * kThreads]);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const size_t j = (n4 << 2) + threadIdx.x;
+        out[j] = (x[j] >= lo && x[j] <= hi) ? grad[j] : 0.0f;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // dequantize
 // ---------------------------------------------------------------------------
@@ -634,6 +721,48 @@ extern "C" dybit_status dybit_quantize_rows(const float *x, int64_t rows, int64_
         case 16: DYBIT_QR(8, false); break;  case 17: DYBIT_QR(8, true); break;
     }
 #undef DYBIT_QR
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_quantize_cols(const float *x, int64_t rows, int64_t cols, dybit_fmt f, float *scales_out,
+                                            uint8_t *codes_out, dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (rows < 0 || cols < 0 || rows > (1 << 30) || cols > (1 << 30)) return DYBIT_ERR_INVALID_ARG;
+    if ((cols * f.bits) % 8) return DYBIT_ERR_ALIGNMENT;
+    if (cols == 0) return DYBIT_OK;
+    if (!scales_out || ((!x || !codes_out) && rows)) return DYBIT_ERR_NULL;
+    hipStream_t hs = (hipStream_t)stream;
+    const float inv_vmax = 1.0f / (float)(1u << (mag_bits(f.bits, f.is_signed) - 1));
+    hipLaunchKernelGGL(col_scale_kernel, dim3((unsigned)((cols + 63) / 64)), dim3(kThreads), 0, hs, x, rows, cols, inv_vmax, scales_out);
+    const int64_t groups = rows * cols / (f.bits == 8 ? 1 : f.bits == 4 ? 2 : 4);
+    if (groups) {
+        const dim3 grid((unsigned)((groups + kThreads - 1) / kThreads));
+#define DYBIT_QC(B, S) hipLaunchKernelGGL((quantize_cols_kernel<B, S>), grid, dim3(kThreads), 0, hs, x, cols, groups, scales_out, codes_out)
+        switch (f.bits * 2 + f.is_signed) {
+            case 4: DYBIT_QC(2, false); break;   case 5: DYBIT_QC(2, true); break;
+            case 8: DYBIT_QC(4, false); break;   case 9: DYBIT_QC(4, true); break;
+            case 12: DYBIT_QC(6, false); break;  case 13: DYBIT_QC(6, true); break;
+            case 16: DYBIT_QC(8, false); break;  case 17: DYBIT_QC(8, true); break;
+        }
+#undef DYBIT_QC
+    }
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_fake_quant_bwd(const float *x, const float *grad_out, size_t n, dybit_fmt f, const float *scale,
+                                             float *grad_in, dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (!scale || ((!x || !grad_out || !grad_in) && n)) return DYBIT_ERR_NULL;
+    if (!aligned16(x) || !aligned16(grad_out) || !aligned16(grad_in)) return DYBIT_ERR_ALIGNMENT;
+    if (n == 0) return DYBIT_OK;
+    const float vmax = (float)(1u << (mag_bits(f.bits, f.is_signed) - 1));
+    const int grid = grid_for(n / 4 + 1, kThreads * 2, 256 * 64);
+    hipLaunchKernelGGL(fake_quant_bwd_kernel, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, x, grad_out, n, scale, vmax,
+                       f.is_signed, grad_in);
     return launch_status();
 }
 

@@ -11,7 +11,8 @@ which keeps the maximum), its max|y| is taken in the convolution's epilogue
 identity shortcut of a residual block is added in the same epilogue, before the ReLU.
 Pooling runs on the fp32 tensors with torch ops; it is glue, not part of the library.
 A layer with op "dwconv" (depthwise convolution, the building block of the depthwise-separable
-network of Sec. IV; filter [kh][kw][C]) runs through dybit_dwconv2d in the dynamic chain.
+network of Sec. IV; filter [kh][kw][C]) runs through dybit_dwconv2d_wb in both chains: it reads the
+codes its producer wrote and writes codes for its consumer like a dense convolution.
 
 With `forward(x, static=True)` after a `calibrate(x)` the chain follows the paper's dataflow to
 the letter: the scales of all activation tensors are fixed (those of the calibration input), every
@@ -21,8 +22,8 @@ shortcut, a pooling or the network output needs it, and no pass over an fp32 ten
 behind the pooling layers.
 
 `per_channel=True` gives every output channel of every layer its own weight scale (row-wise max-abs,
-dybit_quantize_rows; the convolutions then run through dybit_conv2d_pc); activations keep one scale
-per tensor.
+dybit_quantize_rows; the convolutions then run through dybit_conv2d_pc; depthwise filters: one scale per
+channel, dybit_quantize_cols); activations keep one scale per tensor.
 
 Formats: weights are signed; an activation tensor is unsigned when it is the output of a
 ReLU or of a pooling of such outputs, signed otherwise (the network input).  Layer-wise
@@ -73,12 +74,16 @@ class DybitNetwork:
         self.device = device
         self.params = {}
         for l in layers:
-            if l["op"] == "dwconv":                  # depthwise: filter [kh][kw][C], one scale for the tensor
+            if l["op"] == "dwconv":                  # depthwise: filter [kh][kw][C]
                 w, b = weights[l["name"]]
                 bw, ba = bitwidths[l["name"]]
                 wd = torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).to(device).reshape(-1)
-                sw = B.dybit_absmax_scale(wd, bw, True)
-                self.params[l["name"]] = {"w_fmt": (bw, True), "w_scale": sw, "w_codes": B.dybit_quantize(wd, sw, bw, True),
+                if per_channel:                      # one scale per channel: the columns of the [kh*kw][C] filter
+                    sw, wq = B.dybit_quantize_cols(wd.reshape(-1, w.shape[2]), bw, True)
+                else:
+                    sw = B.dybit_absmax_scale(wd, bw, True)
+                    wq = B.dybit_quantize(wd, sw, bw, True)
+                self.params[l["name"]] = {"w_fmt": (bw, True), "w_scale": sw, "w_codes": wq,
                                           "bias": torch.from_numpy(b).to(device), "a_bits": ba, "k": w.shape[0], "kw": w.shape[1],
                                           "cin": w.shape[2], "cpad": w.shape[2], "cout": w.shape[2]}
                 continue
@@ -115,27 +120,27 @@ class DybitNetwork:
         rows are whole words) and whether anyone needs the fp32 tensor."""
         nonneg = {"input": False}
         produced_by = {}
+        coded = ("conv", "fc", "dwconv")             # layers that read codes
         for l in self.layers:
-            if l["op"] in ("conv", "fc"):
+            if l["op"] in coded:
                 nonneg[l["name"]] = bool(l.get("relu"))
                 produced_by[l["name"]] = l
-            elif l["op"] == "dwconv":
-                nonneg[l["name"]] = bool(l.get("relu"))
             else:
                 nonneg[l["name"]] = nonneg[l["src"]]
         self.a_fmt = {l["name"]: (self.params[l["name"]]["a_bits"], not nonneg[l["src"]])
-                      for l in self.layers if l["op"] in ("conv", "fc")}
+                      for l in self.layers if l["op"] in coded}
         self.plan = {}
         last = self.layers[-1]["name"]
         for name, l in produced_by.items():
             cout = self.params[name]["cout"]
             users = [u for u in self.layers if u["src"] == name]
-            convs = [u for u in users if u["op"] in ("conv", "fc")]
+            convs = [u for u in users if u["op"] in coded]
             fmts = {self.a_fmt[u["name"]] for u in convs}
-            fused = (len(fmts) == 1 and l["op"] == "conv"
+            fused = (len(fmts) == 1 and l["op"] in ("conv", "dwconv")
                      and all(self.params[u["name"]]["cpad"] == cout for u in convs)
-                     and (cout * next(iter(fmts))[0]) % 32 == 0)
-            need_fp32 = (name == last or not fused or any(u["op"] not in ("conv", "fc") for u in users)
+                     and (cout * next(iter(fmts))[0]) % 32 == 0
+                     and (l["op"] == "conv" or next(iter(fmts))[0] in (4, 8)))     # the depthwise epilogue packs 4- and 8-bit codes
+            need_fp32 = (name == last or not fused or any(u["op"] not in coded for u in users)
                          or any(u.get("add") == name for u in self.layers))
             self.plan[name] = {"fmt": next(iter(fmts)) if fused else None,
                                "scale_of": convs[0]["name"] if fused else None, "fp32": need_fp32}
@@ -204,8 +209,9 @@ class DybitNetwork:
                     word = max_words[next_word:next_word + 1]
                     next_word += 1
                     known_max[name] = word
-                out = B.dybit_dwconv2d(Bn, H, W, C, p["k"], p["kw"], l["stride"], l["pad"], qa, a_fmt, sa,
-                                       p["w_codes"], p["w_fmt"], p["w_scale"], p["bias"], relu, word)
+                out, _ = B.dybit_dwconv2d_wb(Bn, H, W, C, p["k"], p["kw"], l["stride"], l["pad"], qa, a_fmt, sa,
+                                             p["w_codes"], p["w_fmt"], p["w_scale"], p["bias"], relu, word,
+                                             per_channel=self.per_channel)
                 if record is not None:
                     record(name, {"x": src, "a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "y": out, "shortcut": None,
                                   "relu": relu, "stride": l["stride"], "pad": l["pad"], **p})
@@ -276,7 +282,32 @@ class DybitNetwork:
             name, op = l["name"], l["op"]
             src = acts[l["src"]]
             if op == "dwconv":
-                raise NotImplementedError("the fused write-back chain has no depthwise layers; use the dynamic chain")
+                a_fmt = self.a_fmt[name]
+                sa = self.static_scale[name]
+                Bn, H, W, C = shapes[l["src"]]
+                p = self.params[name]
+                if l["src"] in codes and codes[l["src"]][0] == a_fmt:
+                    qa = codes[l["src"]][2]                         # written by the producer's epilogue
+                else:
+                    qa = B.dybit_quantize(src.reshape(-1), sa, *a_fmt)
+                relu = bool(l.get("relu"))
+                plan = self.plan[name]
+                y_scale = None if plan["fmt"] is None else self.static_scale[plan["scale_of"]]
+                y, y_codes = B.dybit_dwconv2d_wb(Bn, H, W, C, p["k"], p["kw"], l["stride"], l["pad"], qa, a_fmt, sa,
+                                                 p["w_codes"], p["w_fmt"], p["w_scale"], p["bias"], relu, None,
+                                                 plan["fmt"], y_scale, per_channel=self.per_channel,
+                                                 fp32=plan["fp32"] or plan["fmt"] is None)
+                if y_codes is not None:
+                    codes[name] = (plan["fmt"], y_scale, y_codes)
+                if record is not None:
+                    record(name, {"a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "in_shape": (Bn, H, W, C), "y": y,
+                                  "y_codes": y_codes, "y_fmt": plan["fmt"], "y_scale": y_scale, "shortcut": None,
+                                  "relu": relu, "stride": l["stride"], "pad": l["pad"], **p})
+                out = y
+                shapes[name] = (Bn, (H + 2 * l["pad"] - p["k"]) // l["stride"] + 1,
+                                (W + 2 * l["pad"] - p["kw"]) // l["stride"] + 1, C)
+                acts[name] = out
+                continue
             if op == "maxpool":
                 y = torch.nn.functional.max_pool2d(src.permute(0, 3, 1, 2), l["k"], l["stride"], l["pad"])
                 out = y.permute(0, 2, 3, 1).contiguous()

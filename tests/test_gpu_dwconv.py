@@ -158,3 +158,70 @@ def test_depthwise_separable_block_in_the_chain():
             want, den = R.conv2d(qx, rec["a_fmt"], s, qw, rec["w_fmt"], sw, rec["stride"], rec["pad"], bias, rec["relu"], shortcut)
         assert_within(rec["y"].cpu().numpy(), want, den, shortcut=rec.get("shortcut") is not None)
     assert B.dybit_get_last_async_error() == B.OK
+
+
+def _separable_net(per_channel):
+    from paper_2302_12510_amd import synth
+    from paper_2302_12510_amd.network import DybitNetwork
+    layers = [
+        {"name": "stem", "op": "conv", "src": "input", "cin": 3, "cout": 32, "k": 3, "stride": 1, "pad": 1, "relu": True},
+        {"name": "b1e", "op": "conv", "src": "stem", "cin": 32, "cout": 96, "k": 1, "stride": 1, "pad": 0, "relu": True},
+        {"name": "b1d", "op": "dwconv", "src": "b1e", "stride": 1, "pad": 1, "relu": True},
+        {"name": "b1p", "op": "conv", "src": "b1d", "cin": 96, "cout": 32, "k": 1, "stride": 1, "pad": 0, "relu": False, "add": "stem"},
+        {"name": "b2e", "op": "conv", "src": "b1p", "cin": 32, "cout": 96, "k": 1, "stride": 1, "pad": 0, "relu": True},
+        {"name": "b2d", "op": "dwconv", "src": "b2e", "stride": 2, "pad": 1, "relu": True},
+        {"name": "b2p", "op": "conv", "src": "b2d", "cin": 96, "cout": 64, "k": 1, "stride": 1, "pad": 0, "relu": False},
+    ]
+    weights = synth.network_weights([l for l in layers if l["op"] == "conv"], seed=8)
+    for i, name in enumerate(("b1d", "b2d")):
+        w = synth.kaiming_normal((3, 3, 96), 9, seed=8, stream=50 + i) * np.logspace(-1, 1, 96).astype(np.float32)   # channels of very different range
+        weights[name] = (w.astype(np.float32), synth.normal((96,), 0.01, seed=8, stream=60 + i))
+    bits = {"stem": (8, 8), "b1e": (4, 8), "b1d": (4, 4), "b1p": (8, 4), "b2e": (4, 8), "b2d": (8, 8), "b2p": (4, 8)}
+    return layers, weights, DybitNetwork(layers, weights, bits, per_channel=per_channel), dev(synth.network_input(2, 20, seed=8))
+
+
+@pytest.mark.parametrize("per_channel", [False, True])
+def test_depthwise_layers_in_the_fused_write_back_chain(per_channel):
+    """The same block with calibrated scales and the write-back fused into the epilogues: the depthwise
+    layers read the codes the 1 x 1 expansion wrote and write codes for the 1 x 1 projection.  Checked:
+    both depthwise layers really exchange codes only; every layer's fp32 output (where written) within
+    tolerance of the oracle on the layer's own input codes; written codes bit-exact the oracle's encoding
+    of that fp32 output; and on the calibration input the fused chain reproduces the dynamic chain's
+    result bit for bit (same values, same scales, same encoder)."""
+    layers, weights, net, x = _separable_net(per_channel)
+    dyn = net.forward(x).clone()
+    net.calibrate(x)
+    assert net.plan["b1e"]["fmt"] == (4, False) and not net.plan["b1e"]["fp32"]        # expansion -> depthwise: codes only
+    assert net.plan["b1d"]["fmt"] == (4, False) and not net.plan["b1d"]["fp32"]        # depthwise -> projection: codes only
+    assert net.plan["b2d"]["fmt"] == (8, False) and not net.plan["b2d"]["fp32"]
+    recs = {}
+    fused = net.forward(x, static=True, record=lambda n, r: recs.__setitem__(n, r))
+    torch.cuda.synchronize()
+    assert torch.equal(fused, dyn)
+    assert recs["b1d"]["y"] is None and recs["b1d"]["y_codes"] is not None
+    # the depthwise layers in isolation, on their own input codes, with both outputs requested
+    for name in ("b1d", "b2d"):
+        rec = recs[name]
+        Bn, H, W, C = rec["in_shape"]
+        l = next(l for l in layers if l["name"] == name)
+        y, codes = B.dybit_dwconv2d_wb(Bn, H, W, C, 3, 3, l["stride"], l["pad"], rec["a_codes"], rec["a_fmt"], rec["a_scale"],
+                                       rec["w_codes"], rec["w_fmt"], rec["w_scale"], rec["bias"], True, None,
+                                       rec["y_fmt"], rec["y_scale"], per_channel=per_channel)
+        torch.cuda.synchronize()
+        assert torch.equal(codes, rec["y_codes"])
+        qx = R.unpack(rec["a_codes"].cpu().numpy().reshape(-1), Bn * H * W * C, rec["a_fmt"][0]).reshape(Bn, H, W, C)
+        w, bias = weights[name]
+        if per_channel:
+            sw, qw = R.quantize_cols(w.reshape(-1, C), *rec["w_fmt"])
+            assert np.array_equal(rec["w_scale"].cpu().numpy(), sw)
+        else:
+            sw = R.absmax_scale(w, *rec["w_fmt"])
+            qw = R.quantize(w.reshape(-1), sw, *rec["w_fmt"])
+            assert rec["w_scale"].item() == sw
+        want, den = R.dwconv2d(qx, rec["a_fmt"], rec["a_scale"].item(), qw.reshape(3, 3, C), rec["w_fmt"], sw,
+                               l["stride"], l["pad"], bias, True)
+        y32 = y.cpu().numpy()
+        assert_within(y32, want, den)
+        ys = np.float32(rec["y_scale"].item())
+        assert np.array_equal(codes.cpu().numpy().reshape(-1), R.pack(R.quantize(y32.reshape(-1), ys, *rec["y_fmt"]), rec["y_fmt"][0]))
+    assert B.dybit_get_last_async_error() == B.OK
