@@ -19,6 +19,8 @@ SOURCES = [
     ("gemm_dispatch.cpp", "gemm_dispatch", []),
     ("gemm_fast.hip", "gemm_fast_w4", ["-DDYBIT_FAST_W=0"]),
     ("gemm_fast.hip", "gemm_fast_w8", ["-DDYBIT_FAST_W=2"]),
+    ("gemm_fast.hip", "gemm_fast_w6", ["-DDYBIT_FAST_W=4"]),
+    ("gemm_fast.hip", "gemm_fast_w2", ["-DDYBIT_FAST_W=6"]),
     ("gemm_mid.hip", "gemm_mid_w4", ["-DDYBIT_MID_W=0"]),
     ("gemm_mid.hip", "gemm_mid_w8", ["-DDYBIT_MID_W=2"]),
     ("gemm_mid.hip", "gemm_mid_w6", ["-DDYBIT_MID_W=4"]),
@@ -36,6 +38,8 @@ SOURCES = [
     ("gemm.hip", "gemm_wb_a8", ["-DDYBIT_WB=1", "-DDYBIT_GEN_A=8"]),
     ("gemm_fast.hip", "gemm_fast_w4_wb", ["-DDYBIT_FAST_W=0", "-DDYBIT_WB=1"]),
     ("gemm_fast.hip", "gemm_fast_w8_wb", ["-DDYBIT_FAST_W=2", "-DDYBIT_WB=1"]),
+    ("gemm_fast.hip", "gemm_fast_w6_wb", ["-DDYBIT_FAST_W=4", "-DDYBIT_WB=1"]),
+    ("gemm_fast.hip", "gemm_fast_w2_wb", ["-DDYBIT_FAST_W=6", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w4_wb", ["-DDYBIT_MID_W=0", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w8_wb", ["-DDYBIT_MID_W=2", "-DDYBIT_WB=1"]),
     ("gemm_mid.hip", "gemm_mid_w6_wb", ["-DDYBIT_MID_W=4", "-DDYBIT_WB=1"]),

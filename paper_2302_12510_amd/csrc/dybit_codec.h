@@ -65,7 +65,7 @@ template <int FMT> struct Codec;
 // Codec<F>::word decodes one 32-bit word; decode_eight decodes the q-th group of eight codes of
 // a thread's 32 codes (held in registers of 128 bits: one for 4-bit codes, two for 8-bit codes,
 // the first 24 bytes of two for 6-bit codes, the first 8 bytes of one for 2-bit codes) into four
-// registers of two halves.
+// registers of two halves.  2- and 6-bit codes: q may run to 7 over a run of 64 codes (one / three registers).
 template <int FMT>
 __device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
 {
@@ -73,18 +73,18 @@ __device__ __forceinline__ void decode_eight(const u32x4 *raw, int q, u32 *d)
     if constexpr (C::BITS == 8) {
         const u32x4 r = raw[q >> 1];
         C::two_words((q & 1) ? r.z : r.x, (q & 1) ? r.w : r.y, d);
-    } else if constexpr (C::BITS == 2) {
+    } else if constexpr (C::BITS == 2) {                               // q < 4: a run of 32 codes (8 bytes); q < 8: of 64 codes
         const u32x4 r = raw[0];
-        const u32 w = (q & 2) ? r.y : r.x;
+        const u32 w = q < 2 ? r.x : q < 4 ? r.y : q < 6 ? r.z : r.w;
         C::half_word((q & 1) ? (w >> 16) : w, d);
     } else if constexpr (C::BITS == 6) {
-        // eight codes are 48 bits: two groups of four codes (24 bits) taken out of the 192-bit run
-        const u32x4 r0 = raw[0], r1 = raw[1];
+        // eight codes are 48 bits: two groups of four codes (24 bits) taken out of the run's words (a run of
+        // 32 codes is six words, of 64 codes twelve; groups 2 p and 2 p + 1 share words 3 p .. 3 p + 2)
+        auto word = [&](int i) -> u32 { const u32x4 r = raw[i >> 2]; return (i & 3) == 0 ? r.x : (i & 3) == 1 ? r.y : (i & 3) == 2 ? r.z : r.w; };
+        const int i0 = 3 * (q >> 1);
         u32 ta, tb;
-        if (q == 0)      { ta = r0.x;                                     tb = __builtin_amdgcn_alignbit(r0.y, r0.x, 24); }
-        else if (q == 1) { ta = __builtin_amdgcn_alignbit(r0.z, r0.y, 16); tb = r0.z >> 8; }
-        else if (q == 2) { ta = r0.w;                                     tb = __builtin_amdgcn_alignbit(r1.x, r0.w, 24); }
-        else             { ta = __builtin_amdgcn_alignbit(r1.y, r1.x, 16); tb = r1.y >> 8; }
+        if ((q & 1) == 0) { ta = word(i0);                                              tb = __builtin_amdgcn_alignbit(word(i0 + 1), word(i0), 24); }
+        else              { ta = __builtin_amdgcn_alignbit(word(i0 + 2), word(i0 + 1), 16); tb = word(i0 + 2) >> 8; }
         C::two_words(unpack_six(ta), unpack_six(tb), d);
     } else {
         const u32x4 r = raw[0];

@@ -66,12 +66,17 @@ hipError_t take_hip_error();       // ... and this last: the first error noted s
 // epilogue also encodes the results (g.q_out must then be set); those entry points end in _wb.
 bool launch_gemm_fast_w0(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);   // W 4-bit signed
 bool launch_gemm_fast_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);   // W 8-bit signed
+bool launch_gemm_fast_w4(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);   // W 6-bit signed
+bool launch_gemm_fast_w6(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);   // W 2-bit signed; a_bits 2, 4, 6 or 8 for all four; false:
+                                                                                      // K (Cin) is not a multiple of 128 while an operand is 2- or 6-bit
 bool launch_gemm_mid_w0(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w2(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w4(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);    // W 6-bit signed
 bool launch_gemm_mid_w6(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);    // W 2-bit signed; a_bits 2, 4, 6 or 8 for all four
 bool launch_gemm_fast_w0_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_fast_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_fast_w4_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
+bool launch_gemm_fast_w6_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w0_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w2_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);
 bool launch_gemm_mid_w4_wb(const GemmArgs &g, int a_bits, bool conv, hipStream_t st);

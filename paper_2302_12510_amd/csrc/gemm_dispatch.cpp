@@ -1,6 +1,6 @@
 // Chooses between the tiled MFMA kernels of the DyBit matrix product.
 //
-// All need signed weights (2- and 6-bit operands: the 128 x 128 fp16 kernel only), K (convolution: Cin) a multiple of 64 so that
+// All need signed weights, K (convolution: Cin) a multiple of 64 (2- and 6-bit operands on the 256 x 256 kernel: of 128) so that
 // a 64-wide k group is one run of whole 128-bit loads inside one filter tap, 16-byte aligned
 // code buffers, and buffers below 2 GiB (32-bit buffer offsets).  The 256 x 256 kernel does the
 // least decode work per MFMA and is used when its tiles can fill the 256 compute units, N is
@@ -158,11 +158,14 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
         if (w_bits == 4) return (wb ? launch_gemm_f8_w0_wb : launch_gemm_f8_w0)(g, a_bits, conv, large, st);
         return (wb ? launch_gemm_f8_w6_wb : launch_gemm_f8_w6)(g, a_bits, conv, large, st);
     }
-    const bool mid_only = (a_bits != 4 && a_bits != 8) || (w_bits != 4 && w_bits != 8);   // fp16 kernels, 2- and 6-bit operands: the 128 x 128 kernel only
-    if (mid_only || rows) large = false;
-    if (large) {
-        if (w_bits == 4) return (wb ? launch_gemm_fast_w0_wb : launch_gemm_fast_w0)(g, a_bits, conv, st);
-        return (wb ? launch_gemm_fast_w2_wb : launch_gemm_fast_w2)(g, a_bits, conv, st);
+    if (rows) large = false;
+    if (large) {                                                   // declines a 2- or 6-bit operand unless K (Cin) is a multiple of 128
+        bool done;
+        if (w_bits == 4) done = (wb ? launch_gemm_fast_w0_wb : launch_gemm_fast_w0)(g, a_bits, conv, st);
+        else if (w_bits == 6) done = (wb ? launch_gemm_fast_w4_wb : launch_gemm_fast_w4)(g, a_bits, conv, st);
+        else if (w_bits == 2) done = (wb ? launch_gemm_fast_w6_wb : launch_gemm_fast_w6)(g, a_bits, conv, st);
+        else done = (wb ? launch_gemm_fast_w2_wb : launch_gemm_fast_w2)(g, a_bits, conv, st);
+        if (done) return true;
     }
     if (w_bits == 4) return (wb ? launch_gemm_mid_w0_wb : launch_gemm_mid_w0)(g, a_bits, conv, st);
     if (w_bits == 6) return (wb ? launch_gemm_mid_w4_wb : launch_gemm_mid_w4)(g, a_bits, conv, st);

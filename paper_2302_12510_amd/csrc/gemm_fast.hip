@@ -32,7 +32,7 @@
 #include "tile_epilogue.h"
 
 #ifndef DYBIT_FAST_W
-#error "compile with -DDYBIT_FAST_W=<weight format id> (0: 4-bit signed, 2: 8-bit signed)"
+#error "compile with -DDYBIT_FAST_W=<weight format id> (0: 4-bit signed, 2: 8-bit signed, 4: 6-bit signed, 6: 2-bit signed)"
 #endif
 #ifndef DYBIT_FAST_VALU_PER_MFMA
 #define DYBIT_FAST_VALU_PER_MFMA 4     // vector-ALU instructions the scheduler places behind each MFMA
@@ -59,9 +59,12 @@ __global__ __launch_bounds__(512) void gemm_fast_kernel(const GemmArgs g, const 
     using CW = Codec<FMT_W>;
     using G = Geom<TK>;
     constexpr int KK = G::KK, ROW_BYTES = G::ROW_BYTES, STAGE_BYTES = G::STAGE_BYTES;
-    constexpr int RUN_A = CA::BITS / 4, RUN_W = CW::BITS / 4;      // 128-bit registers per run of 32 codes
-    constexpr int NA = RUN_A * (TK / 64);                          // 128-bit loads per lane and K step (consecutive bytes)
-    constexpr int NW = RUN_W * (TK / 64);                          // ... per thread for W
+    // A lane's TK / 2 codes of a K step are consecutive bytes, fetched as whole 128-bit registers: 6-bit
+    // codes (24 bytes per 32 codes) and 2-bit codes (8 bytes) therefore need the 128-wide K step.
+    static_assert((TK / 2 * CA::BITS) % 128 == 0 && (TK / 2 * CW::BITS) % 128 == 0, "2- and 6-bit operands need TK = 128");
+    constexpr int RUN_A = CA::BITS / 4, RUN_W = CW::BITS / 4;      // 128-bit registers per run of 32 codes (4-, 8-bit codes)
+    constexpr int NA = TK / 2 * CA::BITS / 128;                    // 128-bit loads per lane and K step (consecutive bytes)
+    constexpr int NW = TK / 2 * CW::BITS / 128;                    // ... per thread for W
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -144,12 +147,14 @@ __global__ __launch_bounds__(512) void gemm_fast_kernel(const GemmArgs g, const 
     // q: group of eight codes among the TK / 2 of the lane (run q / 4, group q % 4 of that run)
     auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {
         u32 d[4];
-        decode_eight<FMT_A>(raw + (q >> 2) * RUN_A, q & 3, d);
+        if constexpr (CA::BITS == 6 || CA::BITS == 2) decode_eight<FMT_A>(raw, q, d);
+        else decode_eight<FMT_A>(raw + (q >> 2) * RUN_A, q & 3, d);
         return __builtin_bit_cast(f16x8, u32x4{d[0], d[1], d[2], d[3]});
     };
     auto stage_W = [&](const u32x4 *raw, int q, char *tile) {
         u32 d[4];
-        decode_eight<FMT_W>(raw + (q >> 2) * RUN_W, q & 3, d);
+        if constexpr (CW::BITS == 6 || CW::BITS == 2) decode_eight<FMT_W>(raw, q, d);
+        else decode_eight<FMT_W>(raw + (q >> 2) * RUN_W, q & 3, d);
         *reinterpret_cast<u32x4 *>(tile + wrW + q * 16) = u32x4{d[0], d[1], d[2], d[3]};
     };
     auto read_W = [&](const char *tile, int kk, int j) -> f16x8 {
@@ -237,18 +242,22 @@ static void launch_tk(const GemmArgs &g, hipStream_t st)
     hipLaunchKernelGGL(k, grid, block, Geom<TK>::LDS_BYTES, st, g, tiles_m, tiles_n);
 }
 
-// K steps of 128 where a step never straddles a row end or a filter tap, else of 64.
+// K steps of 128 where a step never straddles a row end or a filter tap, else of 64 (not with a 2- or 6-bit
+// operand, whose runs of 32 codes are not whole 128-bit registers: false, the caller takes another kernel).
 template <int FA, int FW>
-static void launch(const GemmArgs &g, bool conv, hipStream_t st)
+static bool launch(const GemmArgs &g, bool conv, hipStream_t st)
 {
+    constexpr bool six = Codec<FA>::BITS == 6 || Codec<FW>::BITS == 6 || Codec<FA>::BITS == 2 || Codec<FW>::BITS == 2;
     const bool wide = (conv ? g.Cin : g.K) % 128 == 0;
+    if (six && !wide) return false;
     if (conv) {
         if (wide) launch_tk<FA, FW, true, 128>(g, st);
-        else launch_tk<FA, FW, true, 64>(g, st);
+        else if constexpr (!six) launch_tk<FA, FW, true, 64>(g, st);
     } else {
         if (wide) launch_tk<FA, FW, false, 128>(g, st);
-        else launch_tk<FA, FW, false, 64>(g, st);
+        else if constexpr (!six) launch_tk<FA, FW, false, 64>(g, st);
     }
+    return true;
 }
 
 }  // namespace fast
@@ -259,12 +268,16 @@ static void launch(const GemmArgs &g, bool conv, hipStream_t st)
 bool DYBIT_FAST_NAME(DYBIT_FAST_W)(const GemmArgs &g, int a_bits, bool conv, hipStream_t st)
 {
     using namespace fast;
-    const int fa = (a_bits == 8 ? F8S : F4S) + (g.a_signed ? 0 : 1);
+    const int fa = (a_bits == 8 ? F8S : a_bits == 6 ? F6S : a_bits == 2 ? F2S : F4S) + (g.a_signed ? 0 : 1);
     switch (fa) {
-        case F4S: fast::launch<F4S, DYBIT_FAST_W>(g, conv, st); return true;
-        case F4U: fast::launch<F4U, DYBIT_FAST_W>(g, conv, st); return true;
-        case F8S: fast::launch<F8S, DYBIT_FAST_W>(g, conv, st); return true;
-        case F8U: fast::launch<F8U, DYBIT_FAST_W>(g, conv, st); return true;
+        case F2S: return fast::launch<F2S, DYBIT_FAST_W>(g, conv, st);
+        case F2U: return fast::launch<F2U, DYBIT_FAST_W>(g, conv, st);
+        case F4S: return fast::launch<F4S, DYBIT_FAST_W>(g, conv, st);
+        case F4U: return fast::launch<F4U, DYBIT_FAST_W>(g, conv, st);
+        case F6S: return fast::launch<F6S, DYBIT_FAST_W>(g, conv, st);
+        case F6U: return fast::launch<F6U, DYBIT_FAST_W>(g, conv, st);
+        case F8S: return fast::launch<F8S, DYBIT_FAST_W>(g, conv, st);
+        case F8U: return fast::launch<F8U, DYBIT_FAST_W>(g, conv, st);
         default: return false;
     }
 }

@@ -247,7 +247,7 @@ def test_8192_cubed_4bit_w_a_sampled_outputs():
 
 # ---- tiled MFMA kernels (256 x 256 and 128 x 128 tiles, in-register decode) --------
 TILED_PAIRS = [(a, w) for w in ((4, True), (8, True)) for a in ((4, True), (4, False), (8, True), (8, False))]
-# pairs with a 6-bit operand: on the 128 x 128 kernel only (skipped for the other entries of KERNELS)
+# pairs with a 6-bit operand (on the 256 x 256 fp16 kernel when K is a multiple of 128, else on the 128 x 128 one)
 TILED_PAIRS += [(a, (6, True)) for a in ((4, False), (6, True), (6, False), (8, True))]
 TILED_PAIRS += [((6, True), (4, True)), ((6, False), (4, True)), ((6, True), (8, True)), ((6, False), (8, True))]
 # ... and the 2-bit formats of the {8, 4, 2} x {8, 4, 2} mode matrix
@@ -283,8 +283,6 @@ def force_kernel(request):
     name = request.param
     fmts = [request.getfixturevalue(k) for k in ("a_fmt", "w_fmt", "x_fmt") if k in request.fixturenames]
     low_pair = bool(fmts) and all(f[0] in (2, 4) for f in fmts)
-    if name.startswith("large") and any(f[0] in (2, 6) for f in fmts) and (not low_pair or name.endswith("-f16")):
-        pytest.skip("on the fp16 kernels 2- and 6-bit operands run on the 128 x 128 kernel only")
     options = {}
     f16_only = name.endswith("-f16")
     if f16_only:
@@ -306,6 +304,10 @@ def force_kernel(request):
     f16_set, f8_set = _FAMILY[family]
     if family in ("ws", "general"):                         # one kernel for every pair
         _expected_kernels = f16_set | f8_set
+    elif family == "large" and any(f[0] in (2, 6) for f in fmts) and (f16_only or not low_pair):
+        # a 2- or 6-bit operand is on the 256 x 256 fp16 kernel only when K (Cin) is a multiple of 128; other shapes
+        # go on to the 128 x 128 kernel (test_large_kernel_six_bit_operands pins the first case)
+        _expected_kernels = f16_set | _FAMILY["mid"][0]
     elif f16_only or (fmts and not low_pair):
         _expected_kernels = set(f16_set)
     elif fmts:
@@ -389,6 +391,56 @@ def test_tiled_kernels_conv(force_kernel, x_fmt, w_fmt, geom):
     got = run_conv(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, True)
     want, den = R.conv2d(qx, x_fmt, 0.21, qw, w_fmt, 0.05, stride, pad, bias, True)
     assert_within(got, want, den)
+
+
+SIX_PAIRS = [((6, True), (6, True)), ((6, False), (6, True)), ((8, True), (6, True)), ((4, False), (6, True)),
+             ((6, True), (4, True)), ((6, False), (8, True)), ((2, True), (8, True)), ((2, False), (6, True)),
+             ((8, False), (2, True)), ((6, True), (2, True))]
+
+
+@pytest.mark.parametrize("a_fmt,w_fmt", SIX_PAIRS)
+def test_large_kernel_six_bit_operands(a_fmt, w_fmt):
+    """2- and 6-bit operands on the 256 x 256 fp16 kernel (K steps of 128: a lane's 64 codes are 16 / 48 bytes): ragged M and N,
+    an odd number of K steps, every (A code, W code) pair, one-hot rows, a convolution with 128 channels;
+    each call must really run on that kernel."""
+    B.dybit_set_option("gemm_kernel", "large")
+    try:
+        rng = np.random.default_rng(a_fmt[0] * 10 + w_fmt[0])
+        for (M, N, K) in ((300, 520, 384), (257, 255, 128), (2100, 300, 640)):
+            qa = random_codes(rng, (M, K), a_fmt)
+            qw = random_codes(rng, (N, K), w_fmt)
+            bias = rng.normal(0, 3, N).astype(np.float32)
+            got = run_gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, True)
+            assert B.dybit_last_gemm_kernel() == "f16_256"
+            want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, True)
+            assert_within(got, want, den)
+        na, nw = 1 << a_fmt[0], 1 << w_fmt[0]
+        K = 128 * ((na * nw + 127) // 128)
+        qa = np.zeros((260, K), np.uint8); qw = np.zeros((258, K), np.uint8)
+        for r in range(260):
+            qa[r] = np.roll(np.resize(np.repeat(np.arange(na), nw), K), r)
+        for r in range(258):
+            qw[r] = np.roll(np.resize(np.tile(np.arange(nw), na), K), 3 * r)
+        got = run_gemm(qa, a_fmt, 1.0, qw, w_fmt, 1.0)
+        assert B.dybit_last_gemm_kernel() == "f16_256"
+        want, den = R.gemm(qa, a_fmt, 1.0, qw, w_fmt, 1.0)
+        assert_within(got, want, den)
+        cba = R.codebook(*a_fmt)
+        one_w = int(np.where(R.codebook(*w_fmt) == 1.0)[0][0])
+        qa1 = np.zeros((na, 128), np.uint8); qw1 = np.zeros((128, 128), np.uint8)
+        qa1[np.arange(na), np.arange(na) % 128] = np.arange(na)
+        qw1[np.arange(128), np.arange(128)] = one_w
+        got = run_gemm(qa1, a_fmt, 1.0, qw1, w_fmt, 1.0)
+        want = np.zeros((na, 128)); want[np.arange(na), np.arange(na) % 128] = cba
+        assert np.array_equal(got.astype(np.float64), want)
+        qx = random_codes(rng, (2, 9, 10, 128), a_fmt)
+        qf = random_codes(rng, (140, 3, 3, 128), w_fmt)
+        got = run_conv(qx, a_fmt, 0.3, qf, w_fmt, 0.02, 1, 1)
+        assert B.dybit_last_gemm_kernel() == "f16_256"
+        want, den = R.conv2d(qx, a_fmt, 0.3, qf, w_fmt, 0.02, 1, 1)
+        assert_within(got, want, den)
+    finally:
+        B.dybit_set_option("gemm_kernel", "auto")
 
 
 @pytest.mark.parametrize("force_kernel", ["mid1", "mid2", "mid64", "mid1-f16", "mid2-f16"], indirect=True)
