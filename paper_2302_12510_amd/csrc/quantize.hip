@@ -176,8 +176,8 @@ __device__ __forceinline__ uint32_t quantize_fast_raw(float x, float rinv)
     const float t = x * rinv;
     const float q = SIGNED ? __builtin_amdgcn_fmed3f(fabsf(t), 0.0f, vmax) : __builtin_amdgcn_fmed3f(t, 0.0f, vmax);   // NaN -> 0
     const float qs = q * __uint_as_float(1u << 23);                      // q * 2^-126
-    const float nf = __uint_as_float(K::kRecipSub - __float_as_uint(qs));   // 2^m - c
-    return K::kRound - __float_as_uint(nf + __uint_as_float(K::kMagic));
+    const float nf = __uint_as_float(K::kRecipSub - __float_as_uint(qs));   // 2^m - c (-2^m should the median of -0, 0, vmax be -0)
+    return K::kRound - __float_as_uint(fabsf(nf) + __uint_as_float(K::kMagic));
 }
 
 // One element: the code (sign included, possibly a negative zero); sets `redo` when the exact path must decide.

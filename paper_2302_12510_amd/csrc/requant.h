@@ -3,14 +3,16 @@
 // even magnitude code -- the same function the stand-alone quantize pass computes, with the format
 // as run-time (wave-uniform) parameters so that one epilogue serves every output format.
 //
-// Fast path: q = |x| * fl(1/s) is within 2^-23 (relative) of the true quotient t.  The real-valued
-// code c(t) -- t * 2^(m-1) below 1, and 2^m minus the value whose bit pattern is a constant minus
-// t's above -- is piecewise linear and continuous, and the decision points between codes are its
-// half-integers.  c is rounded to G fractional bits by one magic-number addition; unless those
-// bits read exactly one half, q and t lie on the same side of every decision point.  When they do
-// read one half (one element in 2^G) the nearest decision point is the midpoint above code
-// floor(c), and the sign of fma(-s, midpoint, |x|), which is exact, settles the side; zero is a
-// tie and goes to the even code.
+// Fast path: q = min(|x| * fl(1/s), vmax) is within 2^-23 (relative) of the true quotient t.  The real-valued
+// code c(t) -- t * 2^(m-1) below 1, then the inverse of the decoder's bit-pattern identity -- is
+// piecewise linear and continuous, and the decision points between codes are its half-integers.  One
+// expression yields n = 2^m - c(q) over the whole range: with q' = q * 2^-126 (a subnormal float below 1,
+// whose bits are linear in q), n = bitcast(((127 + m) << 23) - bits(q')).  n is rounded to G fractional
+// bits by one magic-number addition; unless those bits read exactly one half, q and t lie on the same
+// side of every decision point.  When they do read one half (one element in 2^G) the nearest decision
+// point is the midpoint above code floor(c), and the sign of fma(-s, midpoint, |x|), which is exact,
+// settles the side; zero is a tie and goes to the even code.  A NaN becomes q = 0, hence code 0
+// (v_med3_f32 returns the minimum of its other operands for a NaN).
 #ifndef DYBIT_REQUANT_H
 #define DYBIT_REQUANT_H
 
@@ -19,21 +21,22 @@
 
 namespace dybit {
 
-// G: fractional bits kept by the magic-number rounding.  The error of c is below 2^(m-22), so
-// G = 12 serves every format (m <= 8); a format with fewer magnitude bits could afford more.
+// G: fractional bits kept by the magic-number rounding.  The error of c is below 1.5 * 2^(m-24), so
+// G = 13 serves every format (m <= 8), and 2^m + magic stays inside the magic number's binade.
 struct Requant {
-    static constexpr int G = 12;
+    static constexpr int G = 13;
     static constexpr uint32_t kMagic = ((uint32_t)(127 + 23 - G) << 23) | 0x400000u;   // 1.5 * 2^(23-G)
     static constexpr uint32_t kRound = kMagic + (1u << (G - 1));
     static constexpr uint32_t kFracMask = (1u << G) - 1u, kFracHalf = 1u << (G - 1);
     float rinv;         // fl(1 / s)
     float p, s2;        // power of two that brings s into [1, 2), and s * p
     float vmax;         // 2^(m-1): the largest magnitude
-    float neg_grid;     // -2^(m-1): -(codes per unit) on the fraction grid below 1
     float inv_grid;     // 2^-(m-1)
     float two_m;        // 2^m
-    float floor_x;      // lower clamp of the input: -inf (signed: |x| follows) or 0 (unsigned)
+    float floor_x;      // lower clamp of the input when a decision is settled: -inf (signed: |x| follows) or 0 (unsigned)
+    uint32_t abs_mask;  // clears the sign of x / s for a signed format, keeps it for an unsigned one (negative -> 0)
     uint32_t recip_k;   // (254 + m - 1) << 23: constant of the bit-pattern subtraction
+    uint32_t recip_sub; // (127 + m) << 23: the same for an argument scaled by 2^-126
     uint32_t m;         // magnitude bits
     uint32_t half;      // 2^(m-1): first code of the part above 1
     uint32_t sign_mask, sign_shift;
@@ -53,11 +56,12 @@ __device__ __forceinline__ Requant make_requant(const float *scale, int bits, in
     const int m = is_signed ? bits - 1 : bits;
     r.m = (uint32_t)m;
     r.vmax = (float)(1u << (m - 1));
-    r.neg_grid = -r.vmax;
     r.inv_grid = __uint_as_float((uint32_t)(127 - (m - 1)) << 23);
     r.two_m = (float)(1u << m);
     r.floor_x = is_signed ? -__builtin_inff() : 0.0f;
+    r.abs_mask = is_signed ? 0x7fffffffu : 0xffffffffu;
     r.recip_k = (uint32_t)(254 + m - 1) << 23;
+    r.recip_sub = (uint32_t)(127 + m) << 23;
     r.half = 1u << (m - 1);
     r.is_signed = is_signed != 0;
     r.sign_mask = is_signed ? (1u << m) : 0u;
@@ -65,15 +69,15 @@ __device__ __forceinline__ Requant make_requant(const float *scale, int bits, in
     return r;
 }
 
-// Fast path, first half: the bit pattern of (-c or 2^m - c) + magic for the value x.  The G low
-// bits are the rounded fraction of c; requant_needs_settling() says whether they read one half.
-// A NaN comes out as some finite pattern; the caller tests for NaN separately.
+// Fast path, first half: the bit pattern of (2^m - c) + magic for the value x.  The G low bits are the
+// rounded fraction of c; requant_needs_settling() says whether they read one half.  A NaN gives c = 0.
 __device__ __forceinline__ uint32_t requant_rounded(float x, const Requant &r)
 {
-    const float q = fminf(fabsf(fmaxf(x, r.floor_x)) * r.rinv, r.vmax);        // |x| or max(x, 0), over s, saturated
-    const float lin = q * r.neg_grid;                                          // -c
-    const float rec = __uint_as_float(r.recip_k - __float_as_uint(q));         // 2^m - c
-    return __float_as_uint((q < 1.0f ? lin : rec) + __uint_as_float(Requant::kMagic));
+    const float t = __uint_as_float(__float_as_uint(x * r.rinv) & r.abs_mask);  // |x| / s, or x / s (negative: clamped to 0 below)
+    const float q = __builtin_amdgcn_fmed3f(t, 0.0f, r.vmax);                   // saturated; NaN -> 0
+    const float qs = q * __uint_as_float(1u << 23);                             // q * 2^-126
+    const float n = __uint_as_float(r.recip_sub - __float_as_uint(qs));         // 2^m - c (-2^m should the median of -0, 0, vmax be -0)
+    return __float_as_uint(fabsf(n) + __uint_as_float(Requant::kMagic));
 }
 
 __device__ __forceinline__ bool requant_needs_settling(uint32_t zb)
@@ -96,7 +100,7 @@ __device__ __forceinline__ uint32_t requant_magnitude(uint32_t zb, const Requant
 }
 
 // Exact decision at the midpoint between magnitude codes `code - 1` and `code`, for a value whose
-// rounded fraction read one half (so code >= 1).  NaN -> 0.
+// rounded fraction read one half (so code >= 1; a NaN never gets here, its fraction reads zero).
 __device__ __forceinline__ uint32_t requant_settle(float x, uint32_t code, const Requant &r)
 {
     const float ax = fabsf(fmaxf(x, r.floor_x));
@@ -104,8 +108,7 @@ __device__ __forceinline__ uint32_t requant_settle(float x, uint32_t code, const
     const float h = (float)lo + 0.5f;
     const float mid = lo < r.half ? h * r.inv_grid : __uint_as_float(r.recip_k - __float_as_uint(r.two_m - h));
     const float d = fmaf(-r.s2, mid, ax * r.p);                     // sign(|x| - s * mid), exact
-    const uint32_t settled = (d > 0.0f || (d == 0.0f && (lo & 1u))) ? code : lo;
-    return x != x ? 0u : settled;
+    return (d > 0.0f || (d == 0.0f && (lo & 1u))) ? code : lo;
 }
 
 // Sign bit for a signed format (sign_mask is 0 for an unsigned one); a zero magnitude never carries it.
@@ -120,7 +123,7 @@ __device__ __forceinline__ uint32_t requant_code(float x, const Requant &r)
 {
     const uint32_t zb = requant_rounded(x, r);
     uint32_t mag = requant_magnitude(zb, r);
-    if (requant_needs_settling(zb) | (x != x)) mag = requant_settle(x, mag, r);
+    if (requant_needs_settling(zb)) mag = requant_settle(x, mag, r);
     return requant_with_sign(mag, x, r);
 }
 

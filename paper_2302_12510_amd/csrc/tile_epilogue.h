@@ -100,7 +100,7 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
 // The same strip with the write-back encoder (requant.h): per 32 x 32 block, three phases over the
 // lane's values (eight at a time) so that the instruction streams of the values interleave and the only branch is
 // one per block -- (1) result, optional fp32 store, rounded real-valued code; (2) only if some
-// lane's value sits within 2^-G of a decision point (or is NaN): the exact decision for those;
+// lane's value sits within 2^-G of a decision point: the exact decision for those;
 // (3) sign, packing across lanes, store of the packed words through a descriptor of their own.
 // A NULL fp32 output becomes an empty descriptor whose stores the hardware drops.
 template <int CB, bool HAS_RES, int BITS, int ACC_EXP>
@@ -180,7 +180,7 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
                     mx = fmaxf(mx, (n_ok && r < rows) ? fabsf(c[u]) : 0.0f);
                 }
                 zb[u] = requant_rounded(c[u], rqp);
-                settle_key = min(settle_key, (c[u] != c[u]) ? 0u : requant_settle_key(zb[u]));
+                settle_key = min(settle_key, requant_settle_key(zb[u]));
             }
             uint32_t code[GV];
 #pragma unroll
@@ -189,7 +189,7 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
 #pragma unroll
                 for (int u = 0; u < GV; ++u) {
                     const uint32_t fixed = requant_settle(c[u], code[u], rqp);
-                    code[u] = (requant_needs_settling(zb[u]) | (c[u] != c[u])) ? fixed : code[u];
+                    code[u] = requant_needs_settling(zb[u]) ? fixed : code[u];
                 }
             }
             if (rqp.is_signed) {                                             // uniform

@@ -19,7 +19,9 @@ the letter: the scales of all activation tensors are fixed (those of the calibra
 convolution whose consumers agree on a format encodes its results in its own epilogue
 (dybit_conv2d_wb) and the next layer reads those codes; the fp32 tensor is only written where a
 shortcut, a pooling or the network output needs it, and no pass over an fp32 tensor remains except
-behind the pooling layers.
+behind the pooling layers.  The scales need not come from an offline calibration: with
+`forward(x, static=True, track=True)` every epilogue also takes max|result| of the pass, and
+`advance_scales()` turns those maxima into the scales of the next pass (previous-iteration scales).
 
 `per_channel=True` gives every output channel of every layer its own weight scale (row-wise max-abs,
 dybit_quantize_rows; the convolutions then run through dybit_conv2d_pc; depthwise filters: one scale per
@@ -163,12 +165,15 @@ class DybitNetwork:
         self.forward(x, record=lambda name, rec: scales.__setitem__(name, rec["a_scale"].clone()))
         self.static_scale = scales
 
-    def forward(self, x: torch.Tensor, record=None, static: bool = False) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, record=None, static: bool = False, track: bool = False) -> torch.Tensor:
         """x: NHWC float32 on the device.  `record(name, dict)` receives, per conv/fc layer, the
         tensors needed to check that layer in isolation (input, scale, codes, raw output).
-        static=True: calibrated scales and fused write-back (see the module text)."""
+        static=True: the scales of the activation tensors are given (calibrate(), or the previous pass:
+        see advance_scales()) and the write-back is fused (see the module text).
+        track=True (static chain): every layer also folds max|result| of this pass into a word of its
+        own, from which advance_scales() derives the scales of the next pass."""
         if static:
-            return self._forward_static(x, record)
+            return self._forward_static(x, record, track)
         acts = {"input": x}
         nonneg = {"input": False}
         known_max = {}                       # tensor name -> device scalar holding max|tensor|
@@ -271,9 +276,38 @@ class DybitNetwork:
             logits = self.forward(x, static=static)
         return graph, logits
 
-    def _forward_static(self, x: torch.Tensor, record=None) -> torch.Tensor:
+    def advance_scales(self) -> None:
+        """Previous-iteration scales (Sec. III-B writes results back as codes, and with tensor-level scales
+        the encoder needs max|result| before the results exist): after a forward(static=True, track=True)
+        the scale of every activation tensor that a tracked layer produced becomes the max-abs scale of
+        the values that pass produced.  The next pass encodes under those scales (a tensor that grew beyond
+        its previous maximum saturates at the all-ones code).  Device work only: one small kernel per tensor."""
+        if getattr(self, "_tracked", None) is None:
+            raise RuntimeError("run forward(static=True, track=True) first")
+        origin = {}                                     # tensor name -> producing layer whose maximum it carries
+        nonneg = {"input": False}
+        for l in self.layers:
+            name, op = l["name"], l["op"]
+            if op in ("conv", "fc", "dwconv"):
+                origin[name] = name
+                nonneg[name] = bool(l.get("relu"))
+            else:
+                nonneg[name] = nonneg[l["src"]]
+                if op == "maxpool" and nonneg[name] and l["k"] >= l["stride"] and l["src"] in origin:
+                    origin[name] = origin[l["src"]]     # every element is in some window: the maximum survives
+        for l in self.layers:
+            if l["op"] in ("conv", "fc", "dwconv") and l["src"] in origin:
+                B.dybit_scale_from_absmax(self._tracked[origin[l["src"]]], *self.a_fmt[l["name"]], out=self.static_scale[l["name"]])
+
+    def _forward_static(self, x: torch.Tensor, record=None, track: bool = False) -> torch.Tensor:
         if self.static_scale is None:
             raise RuntimeError("calibrate() first: the static chain needs a scale per activation tensor")
+        words = None
+        if track:
+            names = [l["name"] for l in self.layers if l["op"] in ("conv", "fc", "dwconv")]
+            buf = torch.zeros(len(names), dtype=torch.float32, device=x.device)
+            words = {n: buf[i:i + 1] for i, n in enumerate(names)}
+        self._tracked = words
         acts = {"input": x}                  # fp32 tensors (None where only codes were written)
         codes = {}                           # tensor name -> (format, scale, packed codes)
         shapes = {"input": tuple(x.shape)}
@@ -294,7 +328,8 @@ class DybitNetwork:
                 plan = self.plan[name]
                 y_scale = None if plan["fmt"] is None else self.static_scale[plan["scale_of"]]
                 y, y_codes = B.dybit_dwconv2d_wb(Bn, H, W, C, p["k"], p["kw"], l["stride"], l["pad"], qa, a_fmt, sa,
-                                                 p["w_codes"], p["w_fmt"], p["w_scale"], p["bias"], relu, None,
+                                                 p["w_codes"], p["w_fmt"], p["w_scale"], p["bias"], relu,
+                                                 None if words is None else words[name],
                                                  plan["fmt"], y_scale, per_channel=self.per_channel,
                                                  fp32=plan["fp32"] or plan["fmt"] is None)
                 if y_codes is not None:
@@ -332,19 +367,20 @@ class DybitNetwork:
                 shortcut = acts[l["add"]] if l.get("add") else None
                 plan = self.plan[name]
                 y_codes = None
+                word = None if words is None else words[name]
                 if plan["fmt"] is not None:
                     y_scale = self.static_scale[plan["scale_of"]]
                     if self.per_channel:
-                        y, y_codes = B.dybit_conv2d_pc(*conv_args, p["bias"], shortcut, relu, None, plan["fmt"], y_scale,
+                        y, y_codes = B.dybit_conv2d_pc(*conv_args, p["bias"], shortcut, relu, word, plan["fmt"], y_scale,
                                                        fp32=plan["fp32"])
                     else:
-                        y, y_codes = B.dybit_conv2d_wb(*conv_args, plan["fmt"], y_scale, p["bias"], shortcut, relu,
+                        y, y_codes = B.dybit_conv2d_wb(*conv_args, plan["fmt"], y_scale, p["bias"], shortcut, relu, word,
                                                        fp32=plan["fp32"])
                     codes[name] = (plan["fmt"], y_scale, y_codes)
                 elif self.per_channel:
-                    y, _ = B.dybit_conv2d_pc(*conv_args, p["bias"], shortcut, relu)
+                    y, _ = B.dybit_conv2d_pc(*conv_args, p["bias"], shortcut, relu, word)
                 else:
-                    y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu)
+                    y = B.dybit_conv2d_ex(*conv_args, p["bias"], shortcut, relu, word)
                 if record is not None:
                     record(name, {"a_fmt": a_fmt, "a_scale": sa, "a_codes": qa, "in_shape": (Bn, H, W, p["cpad"]),
                                   "y": y, "y_codes": y_codes, "y_fmt": plan["fmt"],

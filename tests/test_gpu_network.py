@@ -246,3 +246,50 @@ def test_graph_replay_equals_the_eager_pass(static):
             torch.cuda.synchronize()
             assert torch.equal(again, want)
     assert B.dybit_get_last_async_error() == B.OK
+
+
+def test_previous_iteration_scales():
+    """The fused chain with scales taken from the pass before instead of an offline calibration
+    (forward(static=True, track=True) + advance_scales()).  Checked: every layer's tracked word is the
+    maximum of the fp32 tensor it wrote (where it wrote one); after advance_scales() every consumer's scale
+    is the oracle's max-abs scale of that maximum; on the calibration input nothing changes and the chain
+    still reproduces the dynamic chain bit for bit; on another input the pass after the update saturates
+    nothing that the pass before produced."""
+    layers = synth.resnet18_layers()
+    weights = synth.network_weights(layers, seed=3)
+    net = DybitNetwork(layers, weights, synth.bitwidths_fixed(layers))
+    x0 = torch.from_numpy(synth.network_input(2, 64, seed=11)).cuda()
+    x1 = torch.from_numpy(3.0 * synth.network_input(2, 64, seed=12)).cuda()        # a louder input: larger activations
+    net.calibrate(x0)
+    calibrated = {k: v.clone() for k, v in net.static_scale.items()}
+    dyn0 = net.forward(x0).clone()
+    net.forward(x0, static=True, track=True)
+    net.advance_scales()
+    torch.cuda.synchronize()
+    for k, v in calibrated.items():
+        assert torch.equal(net.static_scale[k], v), k                             # same tensors, same maxima
+    assert torch.equal(net.forward(x0, static=True), dyn0)
+    recs = {}
+    net.forward(x1, static=True, track=True, record=lambda n, r: recs.__setitem__(n, r))
+    torch.cuda.synchronize()
+    words = {n: w.item() for n, w in net._tracked.items()}
+    for name, rec in recs.items():
+        if rec["y"] is not None:
+            assert words[name] == rec["y"].abs().max().item(), name
+    net.advance_scales()
+    torch.cuda.synchronize()
+    src_of = {l["name"]: l["src"] for l in layers}
+    by_name = {l["name"]: l for l in layers}
+    grew = 0
+    for l in layers:
+        if l["op"] not in ("conv", "fc"):
+            continue
+        t = l["src"]
+        while t in by_name and by_name[t]["op"] == "maxpool":
+            t = src_of[t]
+        if t in words:
+            want = R.absmax_scale(np.array([words[t]], np.float32), *net.a_fmt[l["name"]])
+            assert net.static_scale[l["name"]].item() == want, l["name"]
+            grew += net.static_scale[l["name"]].item() > calibrated[l["name"]].item()
+    assert grew >= 10                                                             # the louder input raised the scales
+    assert B.dybit_get_last_async_error() == B.OK
