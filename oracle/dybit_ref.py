@@ -460,6 +460,25 @@ def group_conv2d(x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, stride, pad, 
 # --------------------------------------------------------------------------
 # Quantization error metric (Eq. 2)
 # --------------------------------------------------------------------------
+def maxpool2d_codes(x_codes: np.ndarray, bits: int, signed: bool, k: int, stride: int, pad: int) -> np.ndarray:
+    """Max pooling of a tensor of DyBit codes [B][H][W][C] (Sec. III-B: activations are stored as codes):
+    per window and channel the code whose value is largest, taps outside the image left out; the value zero
+    is reported as code 0.  Plain loops over windows."""
+    cb = codebook(bits, signed)
+    canon = {float(v): c for c, v in reversed(list(enumerate(cb)))}      # smallest code of every value
+    Bn, H, W, C = x_codes.shape
+    Ho, Wo = conv_out_size(H, k, stride, pad), conv_out_size(W, k, stride, pad)
+    vals = cb[np.asarray(x_codes, dtype=np.int64)]
+    out = np.zeros((Bn, Ho, Wo, C), dtype=np.uint8)
+    for ho in range(Ho):
+        for wo in range(Wo):
+            r0, s0 = ho * stride - pad, wo * stride - pad
+            win = vals[:, max(r0, 0):min(r0 + k, H), max(s0, 0):min(s0 + k, W), :]
+            best = win.reshape(Bn, -1, C).max(axis=1)
+            out[:, ho, wo, :] = np.vectorize(canon.__getitem__, otypes=[np.uint8])(best)
+    return out
+
+
 def rmse(x: np.ndarray, xq: np.ndarray) -> float:
     """sqrt(mean(((x - xq)/sigma)^2)), sigma = standard deviation of x (Eq. 2)."""
     x = np.asarray(x, dtype=np.float64).ravel()
