@@ -78,6 +78,24 @@ def time_events(fn, steps, warmup, torch):
     return float(np.mean(ts)), float(ts[len(ts) // 2])
 
 
+def time_batches(fn, launches, batches, warmup, torch):
+    """Average duration of a launch over back-to-back launches: one event pair around each batch (a
+    kernel shorter than the gap between two host calls is otherwise timed with that gap included)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(batches):
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(launches):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        ts.append(s.elapsed_time(e) / launches)
+    return float(np.mean(ts))
+
+
 def network_roofline(work, ms):
     """Network-level bound of the dynamic chain: per layer the larger of its matrix time at the peak
     of the MFMA type its operands run on (e4m3 for two 4-bit operands, else fp16) and its HBM time for
@@ -280,6 +298,16 @@ def bench_network(args):
     ms_static_graph = timed(graph_static.replay)
     ms_static = min(ms_static_eager, ms_static_graph)
     assert B.dybit_get_last_async_error() == B.OK
+    # ... and with the shortcuts and the max-pool on codes as well (no fp32 tensor between the stem and the average pool
+    # wherever the readers of a tensor agree on a format)
+    del graph, graph_static
+    net_c = DybitNetwork(layers, synth.network_weights(layers, seed=0), bits, code_shortcuts=True)
+    net_c.calibrate(x)
+    ms_codes_eager = timed(lambda: net_c.forward(x, static=True))
+    graph_codes, _ = net_c.capture(x, static=True)
+    ms_codes_graph = timed(graph_codes.replay)
+    ms_codes = min(ms_codes_eager, ms_codes_graph)
+    assert B.dybit_get_last_async_error() == B.OK
     out = {
         "metric": "DyBit GEMM effective TOPS at 4-bit W/A (+ quantize GB/s), % of roofline",
         "value": round(flops / (ms * 1e-3) / 1e12, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
@@ -297,6 +325,13 @@ def bench_network(args):
                                      "shortcut, a pooling or the output needs it",
                              "layers_writing_codes": sum(1 for p in net.plan.values() if p["fmt"]),
                              "layers_writing_codes_only": sum(1 for p in net.plan.values() if not p["fp32"])},
+        "codes_only_chain": {"ms_per_step": round(ms_codes, 4), "TOPS": round(flops / (ms_codes * 1e-3) / 1e12, 3),
+                             "eager_ms_per_step": round(ms_codes_eager, 4), "hip_graph_replay_ms_per_step": round(ms_codes_graph, 4),
+                             "step": "the fused chain with the shortcut of a residual block read as the DyBit codes its tensor is "
+                                     "stored as (dybit_conv2d_wb_rc) and the max-pool on codes (dybit_maxpool2d_codes)",
+                             "shortcuts_read_as_codes": sum(1 for p in net_c.plan.values() if p["shortcut_codes"]),
+                             "maxpools_on_codes": sum(1 for f in net_c.pool_fmt.values() if f),
+                             "layers_writing_codes_only": sum(1 for p in net_c.plan.values() if not p["fp32"])},
     }
     if not args.no_cpu_baseline:
         # the oracle's convolution on a few images of one mid-network layer; the forward pass
@@ -347,6 +382,10 @@ def table(args):
             f = r["fused_write_back"]
             print("| the same network, calibrated scales, write-back fused into the epilogues (%d of %d layers write codes, %d of them codes only) | %.4f ms | %.3f TOPS | - | - | - |"
                   % (f["layers_writing_codes"], r["config"]["gemms"], f["layers_writing_codes_only"], f["ms_per_step"], f["TOPS"]))
+        if "codes_only_chain" in r:
+            f = r["codes_only_chain"]
+            print("| the same fused chain with shortcuts and max-pool on codes (%d shortcuts, %d max-pools; %d layers codes only) | %.4f ms | %.3f TOPS | - | - | - |"
+                  % (f["shortcuts_read_as_codes"], f["maxpools_on_codes"], f["layers_writing_codes_only"], f["ms_per_step"], f["TOPS"]))
         if "roofline_4bit_w_a" in r:
             f = r["roofline_4bit_w_a"]
             print("| 8192^3 GEMM at 4-bit W / 4-bit A (same tensors, activations quantized to 4-bit signed) | %.4f ms (kernel) | %.1f TOPS | %s | %.1f %% of %.0f TFLOP/s | - |"
@@ -574,11 +613,12 @@ def main():
         qx2, qw2 = B.dybit_quantize(X2, sx2, *f_x), B.dybit_quantize(W2, sw2, *f_w)
         Y2 = torch.empty((Bn, H, Wd, Cout), dtype=torch.float32, device="cuda")
         conv2 = (Bn, H, Wd, Cin, Cout, kh, kw, c2["stride"], c2["pad"])
-        c2_ms, _ = time_events(lambda: B.dybit_conv2d(*conv2, qx2, f_x, sx2, qw2, f_w, sw2, out=Y2), 30, 5, torch)
+        c2_ms = time_batches(lambda: B.dybit_conv2d(*conv2, qx2, f_x, sx2, qw2, f_w, sw2, out=Y2), 25, 4, 5, torch)
         fl2 = 2.0 * Bn * H * Wd * Cout * kh * kw * Cin
         out["conv_4bit_w_a"] = {"workload": "cfg2 conv 3x3 256->256 on 14x14, batch 64, W 4-bit signed, A 4-bit unsigned",
                                 "kernel": "dybit::f8::gemm_f8_kernel (128x128 tiles, two k-groups, e4m3 MFMA)",
-                                "kernel_ms": round(c2_ms, 4), "TFLOPs": round(fl2 / (c2_ms * 1e-3) / 1e12, 1),
+                                "kernel_ms": round(c2_ms, 4), "timing": "HIP events around batches of 25 back-to-back launches",
+                                "TFLOPs": round(fl2 / (c2_ms * 1e-3) / 1e12, 1),
                                 "frac_of_fp8_mfma_peak": round(fl2 / (c2_ms * 1e-3) / 1e12 / PEAK_FP8_MFMA_TFLOPS, 4)}
         del X2, W2, Y2
 

@@ -183,6 +183,49 @@ dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t Cin, int64
                              float *Y, float *y_absmax,
                              dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream);
 
+/* The write-back variants with the shortcut tensor itself given as DyBit codes (Sec. III-B: between layers
+ * the activations exist in memory as codes only; a residual block then adds the codes its input was
+ * stored as): C = relu?(A W^T + bias + r_scale * value(R_codes)), encoded as in dybit_gemm_wb.
+ *
+ *   R_codes   [device] M rows of N codes, packed like C_codes ([B][Ho][Wo][Cout] for the convolution), rows
+ *             of N * bits / 8 bytes (N * bits a multiple of 8, DYBIT_ERR_ALIGNMENT otherwise); read only;
+ *             must not overlap C_codes.  NULL: DYBIT_ERR_NULL.
+ *   r_fmt     4-, 6- or 8-bit, signed or unsigned (DYBIT_ERR_UNSUPPORTED_BITS for 2-bit).
+ *   r_scale   [device] 1 float.  The value added is the fp32 number dybit_dequantize would write for the
+ *             code, fl(r_scale * value(code)), in the same fp32 addition as the fp32 shortcut of the _wb form.
+ *   C_codes   required here (DYBIT_ERR_NULL): the decoder of the shortcut lives in the write-back epilogue.
+ *
+ * All other arguments and errors: as in dybit_gemm_wb / dybit_conv2d_wb. */
+dybit_status dybit_gemm_wb_rc(int64_t M, int64_t N, int64_t K,
+                              const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                              const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                              const float *bias, const uint8_t *R_codes, dybit_fmt r_fmt, const float *r_scale,
+                              int32_t relu, float *C, int64_t ldc, float *c_absmax,
+                              dybit_fmt c_fmt, const float *c_scale, uint8_t *C_codes, dybit_stream stream);
+dybit_status dybit_conv2d_wb_rc(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                const float *bias, const uint8_t *R_codes, dybit_fmt r_fmt, const float *r_scale,
+                                int32_t relu, float *Y, float *y_absmax,
+                                dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream);
+
+/* Max pooling on packed DyBit codes (Sec. III-B: between layers the activations exist as codes).  The
+ * encoder is monotone, so the maximum by value of a window's codes is the code of the window's maximum: the
+ * output equals, bit for bit, dybit_quantize of the pooled fp32 tensor under the scale the input was
+ * encoded with (the scale itself is not needed and stays the caller's).
+ *
+ *   X_codes   [device] [B][H][W][C] codes packed along C, C * bits a multiple of 32 (DYBIT_ERR_ALIGNMENT),
+ *             4-byte aligned; read only.
+ *   fmt       2-, 4- or 8-bit, signed or unsigned (6-bit: DYBIT_ERR_UNSUPPORTED_BITS).
+ *   k, stride, pad   square window; taps outside the image are skipped; 2 * pad <= k and H + 2 pad >= k,
+ *             W + 2 pad >= k (DYBIT_ERR_INVALID_ARG otherwise).
+ *   Y_codes   [device] [B][Ho][Wo][C] packed the same way, Ho = (H + 2 pad - k) / stride + 1; written by the
+ *             call; value zero is always written as the all-zero code.  Must not overlap X_codes. */
+dybit_status dybit_maxpool2d_codes(int64_t B, int64_t H, int64_t W, int64_t C,
+                                   int32_t k, int32_t stride, int32_t pad,
+                                   const uint8_t *X_codes, dybit_fmt fmt, uint8_t *Y_codes, dybit_stream stream);
+
 /* Per-output-channel weight scales (an option on top of the tensor-level scale of Sec. I: one scale per
  * row of W / per filter, the usual remedy for networks whose channels differ widely in range, such as the
  * depthwise-separable ones of Sec. IV).

@@ -54,6 +54,9 @@ def lib() -> C.CDLL:
         L.dybit_conv2d_ex.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, vp]
         L.dybit_gemm_wb.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, i64, vp, Fmt, vp, vp, vp]
         L.dybit_conv2d_wb.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, i32, vp, vp, Fmt, vp, vp, vp]
+        L.dybit_gemm_wb_rc.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, Fmt, vp, i32, vp, i64, vp, Fmt, vp, vp, vp]
+        L.dybit_conv2d_wb_rc.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, Fmt, vp, i32, vp, vp, Fmt, vp, vp, vp]
+        L.dybit_maxpool2d_codes.argtypes = [i64] * 4 + [i32] * 3 + [vp, Fmt, vp, vp]
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
         L.dybit_quantize_rows.argtypes = [vp, i64, i64, Fmt, vp, vp, vp]
         L.dybit_dwconv2d.argtypes = [i64] * 4 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp, vp]
@@ -328,6 +331,56 @@ def dybit_conv2d_wb(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: in
                                  _ptr(out if fp32 else None), _ptr(absmax),
                                  fmt(*y_fmt), _ptr(y_scale), _ptr(codes_out), _stream(stream)), "dybit_conv2d_wb")
     return (out if fp32 else None), codes_out
+
+
+def dybit_gemm_wb_rc(M: int, N: int, K: int, a_codes, a_fmt, a_scale, w_codes, w_fmt, w_scale, c_fmt, c_scale,
+                     r_codes, r_fmt, r_scale, bias=None, relu: bool = False, absmax=None, fp32: bool = True,
+                     out: torch.Tensor | None = None, codes_out: torch.Tensor | None = None, stream=None):
+    """dybit_gemm_wb with the shortcut given as packed DyBit codes `r_codes` ([M][N*bits/8]) of format r_fmt
+    and scale r_scale.  Returns (C or None, codes)."""
+    if fp32 and out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=a_scale.device)
+    if codes_out is None:
+        codes_out = torch.empty((M, N * c_fmt[0] // 8), dtype=torch.uint8, device=a_scale.device)
+    _check(lib().dybit_gemm_wb_rc(M, N, K, _ptr(a_codes), fmt(*a_fmt), _ptr(a_scale),
+                                  _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias),
+                                  _ptr(r_codes), fmt(*r_fmt), _ptr(r_scale), int(bool(relu)),
+                                  _ptr(out if fp32 else None), N, _ptr(absmax),
+                                  fmt(*c_fmt), _ptr(c_scale), _ptr(codes_out), _stream(stream)), "dybit_gemm_wb_rc")
+    return (out if fp32 else None), codes_out
+
+
+def dybit_conv2d_wb_rc(B: int, H: int, W: int, Cin: int, Cout: int, kh: int, kw: int, stride: int, pad: int,
+                       x_codes, x_fmt, x_scale, w_codes, w_fmt, w_scale, y_fmt, y_scale,
+                       r_codes, r_fmt, r_scale, bias=None, relu: bool = False, absmax=None, fp32: bool = True,
+                       out: torch.Tensor | None = None, codes_out: torch.Tensor | None = None, stream=None):
+    """dybit_conv2d_wb with the shortcut given as packed DyBit codes `r_codes` ([B][Ho][Wo][Cout*bits/8]).
+    Returns (Y or None, codes)."""
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    if fp32 and out is None:
+        out = torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device=x_scale.device)
+    if codes_out is None:
+        codes_out = torch.empty((B, Ho, Wo, Cout * y_fmt[0] // 8), dtype=torch.uint8, device=x_scale.device)
+    _check(lib().dybit_conv2d_wb_rc(B, H, W, Cin, Cout, kh, kw, stride, pad,
+                                    _ptr(x_codes), fmt(*x_fmt), _ptr(x_scale),
+                                    _ptr(w_codes), fmt(*w_fmt), _ptr(w_scale), _ptr(bias),
+                                    _ptr(r_codes), fmt(*r_fmt), _ptr(r_scale), int(bool(relu)),
+                                    _ptr(out if fp32 else None), _ptr(absmax),
+                                    fmt(*y_fmt), _ptr(y_scale), _ptr(codes_out), _stream(stream)), "dybit_conv2d_wb_rc")
+    return (out if fp32 else None), codes_out
+
+
+def dybit_maxpool2d_codes(B: int, H: int, W: int, C: int, k: int, stride: int, pad: int, x_codes, x_fmt,
+                          out: torch.Tensor | None = None, stream=None):
+    """Max pooling of packed codes [B][H][W][C*bits/8] -> [B][Ho][Wo][C*bits/8] (same format, same scale)."""
+    Ho = (H + 2 * pad - k) // stride + 1
+    Wo = (W + 2 * pad - k) // stride + 1
+    if out is None:
+        out = torch.empty((B, Ho, Wo, C * x_fmt[0] // 8), dtype=torch.uint8, device=x_codes.device)
+    _check(lib().dybit_maxpool2d_codes(B, H, W, C, k, stride, pad, _ptr(x_codes), fmt(*x_fmt), _ptr(out), _stream(stream)),
+           "dybit_maxpool2d_codes")
+    return out
 
 
 def dybit_dwconv2d(B: int, H: int, W: int, C: int, kh: int, kw: int, stride: int, pad: int,

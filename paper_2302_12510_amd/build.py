@@ -14,6 +14,7 @@ SOURCES = [
     ("quantize.hip", "quantize", []),
     ("metric.hip", "metric", []),
     ("dwconv.hip", "dwconv", []),
+    ("pool.hip", "pool", []),
     ("search.cpp", "search", []),
     ("gemm.hip", "gemm", []),
     ("gemm_dispatch.cpp", "gemm_dispatch", []),

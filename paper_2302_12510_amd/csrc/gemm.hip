@@ -459,6 +459,9 @@ struct Epilogue {
     const float *q_scale = nullptr;
     uint8_t *q_out = nullptr;
     bool w_per_channel = false;      // w_scale holds one value per output column
+    const uint8_t *res_codes = nullptr;   // the shortcut as packed DyBit codes (needs the write-back form: q_out)
+    dybit_fmt res_fmt{0, 0};
+    const float *res_scale = nullptr;
 };
 
 // Checks the epilogue against the output shape and fills the matching fields of g.
@@ -477,6 +480,11 @@ dybit_status set_epilogue(GemmArgs &g, const Epilogue &e, float *C, int64_t ldc)
     g.q_bits = e.q_fmt.bits; g.q_signed = e.q_fmt.is_signed;
     g.q_row_bytes = g.N * e.q_fmt.bits / 8;
     g.async_error = async_error_word();
+    if (e.res_codes) {
+        g.res_codes = e.res_codes; g.res_scale = e.res_scale;
+        g.res_bits = e.res_fmt.bits; g.res_signed = e.res_fmt.is_signed;
+        g.res_row_bytes = g.N * e.res_fmt.bits / 8;
+    }
     return g.async_error ? DYBIT_OK : DYBIT_ERR_HIP;
 }
 
@@ -490,6 +498,14 @@ dybit_status check_codes_out(const Epilogue &e, int64_t N, int64_t ldc)
     if ((N * e.q_fmt.bits) % 32) return DYBIT_ERR_ALIGNMENT;
     if (ldc >= (1 << 23) || N >= (1 << 23)) return DYBIT_ERR_INVALID_ARG;
     if (e.q_out && (reinterpret_cast<uintptr_t>(e.q_out) & 3u)) return DYBIT_ERR_ALIGNMENT;
+    if (e.res_codes) {                                                   // shortcut as codes: only with codes out, whole bytes per row
+        const dybit_status sr = check_fmt(e.res_fmt);
+        if (sr != DYBIT_OK) return sr;
+        if (e.res_fmt.bits == 2) return DYBIT_ERR_UNSUPPORTED_BITS;
+        if (e.residual || !e.q_out) return DYBIT_ERR_INVALID_ARG;
+        if (!e.res_scale) return DYBIT_ERR_NULL;
+        if ((N * e.res_fmt.bits) % 8) return DYBIT_ERR_ALIGNMENT;
+    }
     return DYBIT_OK;
 }
 
@@ -642,6 +658,37 @@ extern "C" dybit_status dybit_conv2d_wb(int64_t B, int64_t H, int64_t W, int64_t
     Epilogue e;
     e.bias = bias; e.residual = residual; e.relu = relu; e.absmax = y_absmax;
     e.has_codes = true; e.q_fmt = y_fmt; e.q_scale = y_scale; e.q_out = Y_codes;
+    return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, e, Y, stream);
+}
+
+extern "C" dybit_status dybit_gemm_wb_rc(int64_t M, int64_t N, int64_t K,
+                                         const uint8_t *A_codes, dybit_fmt a_fmt, const float *a_scale,
+                                         const uint8_t *W_codes, dybit_fmt w_fmt, const float *w_scale,
+                                         const float *bias, const uint8_t *R_codes, dybit_fmt r_fmt, const float *r_scale,
+                                         int32_t relu, float *C, int64_t ldc, float *c_absmax,
+                                         dybit_fmt c_fmt, const float *c_scale, uint8_t *C_codes, dybit_stream stream)
+{
+    Epilogue e;
+    e.bias = bias; e.relu = relu; e.absmax = c_absmax;
+    e.res_codes = R_codes; e.res_fmt = r_fmt; e.res_scale = r_scale;
+    e.has_codes = true; e.q_fmt = c_fmt; e.q_scale = c_scale; e.q_out = C_codes;
+    if (!R_codes || !C_codes) return DYBIT_ERR_NULL;
+    return gemm_impl(M, N, K, A_codes, a_fmt, a_scale, W_codes, w_fmt, w_scale, e, C, ldc, stream);
+}
+
+extern "C" dybit_status dybit_conv2d_wb_rc(int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                           int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                           const uint8_t *X_codes, dybit_fmt x_fmt, const float *x_scale,
+                                           const uint8_t *Wt_codes, dybit_fmt w_fmt, const float *w_scale,
+                                           const float *bias, const uint8_t *R_codes, dybit_fmt r_fmt, const float *r_scale,
+                                           int32_t relu, float *Y, float *y_absmax,
+                                           dybit_fmt y_fmt, const float *y_scale, uint8_t *Y_codes, dybit_stream stream)
+{
+    Epilogue e;
+    e.bias = bias; e.relu = relu; e.absmax = y_absmax;
+    e.res_codes = R_codes; e.res_fmt = r_fmt; e.res_scale = r_scale;
+    e.has_codes = true; e.q_fmt = y_fmt; e.q_scale = y_scale; e.q_out = Y_codes;
+    if (!R_codes || !Y_codes) return DYBIT_ERR_NULL;
     return conv2d_impl(B, H, W, Cin, Cout, kh, kw, stride, pad, X_codes, x_fmt, x_scale, Wt_codes, w_fmt, w_scale, e, Y, stream);
 }
 

@@ -23,6 +23,12 @@ struct GemmArgs {
     const float *a_scale, *w_scale, *bias;
     int w_per_channel;               // 0: *w_scale is the scale of the whole tensor; 1: w_scale[n] per output column n
     const float *residual;           // optional: fp32 tensor laid out like C (same ldc), added before the ReLU
+    // the shortcut as DyBit codes instead (write-back build only; at most one of the two forms): M rows of
+    // res_row_bytes bytes holding N codes of res_bits bits (4, 6 or 8), value = *res_scale * value(code)
+    const uint8_t *res_codes;
+    const float *res_scale;
+    int res_bits, res_signed;
+    int64_t res_row_bytes;
     int relu;
     uint32_t *absmax_bits;           // optional: running max |C| of the written values, as float bits (atomic max)
     float *C;                        // may be NULL when q_out is given

@@ -44,7 +44,7 @@ constexpr int THREADS = 512, SLAB = 256;                           // eight wave
 constexpr int ROWS = 2;
 
 template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
-__global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+__global__ __launch_bounds__(THREADS, 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;

@@ -546,8 +546,20 @@ __global__ __launch_bounds__(kThreads) void fake_quant_bwd_kernel(const float *_
 // ---------------------------------------------------------------------------
 // dequantize
 // ---------------------------------------------------------------------------
-// Table of s * value(code) in LDS (one multiply per entry, as the definition says); each
-// lane expands 16 packed bytes per iteration.
+// Table of s * value(code) in LDS (one multiply per entry, as the definition says).  A lane expands one
+// group of four codes (BITS / 2 bytes) into one float4, so that every store instruction of a wave
+// covers 1 KiB of consecutive output; a workgroup works on contiguous chunks of UNROLL x kThreads groups
+// with UNROLL loads in flight, whole chunks without bounds checks.
+template <int BITS>
+__device__ __forceinline__ uint32_t load_code_group(const uint8_t *__restrict__ codes, size_t g)
+{
+    if (BITS == 8) return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(codes) + g);
+    if (BITS == 4) return __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(codes) + g);
+    if (BITS == 2) return __builtin_nontemporal_load(codes + g);
+    const uint8_t *p = codes + g * 3;
+    return p[0] | (p[1] << 8) | (p[2] << 16);
+}
+
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t *__restrict__ codes, size_t n,
                                                               int is_signed, const float *__restrict__ scale,
@@ -557,34 +569,39 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t *__r
     const float s = *scale;
     for (int c = threadIdx.x; c < (1 << BITS); c += kThreads) lut[c] = s * code_value(c, BITS, is_signed);
     __syncthreads();
-    constexpr int EPG = BITS == 6 ? 4 : 8 / BITS * 4;      // elements per group
-    constexpr int BPG = EPG * BITS / 8;                     // bytes per group: 6-bit 3, others 4
-    const size_t groups = n / EPG;
-    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups; g += (size_t)gridDim.x * kThreads) {
-        uint32_t w;
-        if (BITS == 6) {
-            const uint8_t *p = codes + g * 3;
-            w = p[0] | (p[1] << 8) | (p[2] << 16);
+    constexpr int UNROLL = 4;
+    constexpr uint32_t kMask = (1u << BITS) - 1;
+    const size_t groups = n / 4;
+    f32x4 *y4 = reinterpret_cast<f32x4 *>(y);
+    auto expand = [&](uint32_t w) {
+        return f32x4{lut[w & kMask], lut[(w >> BITS) & kMask], lut[(w >> (2 * BITS)) & kMask], lut[(w >> (3 * BITS)) & kMask]};
+    };
+    constexpr size_t per_block = (size_t)kThreads * UNROLL;
+    for (size_t base = (size_t)blockIdx.x * per_block; base < groups; base += (size_t)gridDim.x * per_block) {
+        const size_t i = base + threadIdx.x;
+        uint32_t w[UNROLL];
+        if (base + per_block <= groups) {                              // uniform: a whole chunk
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) w[u] = load_code_group<BITS>(codes, i + u * kThreads);
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) __builtin_nontemporal_store(expand(w[u]), y4 + i + u * kThreads);
         } else {
-            w = reinterpret_cast<const uint32_t *>(codes)[g];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) w[u] = (i + u * kThreads < groups) ? load_code_group<BITS>(codes, i + u * kThreads) : 0u;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                if (i + u * kThreads < groups) __builtin_nontemporal_store(expand(w[u]), y4 + i + u * kThreads);
         }
-        float v[EPG];
-#pragma unroll
-        for (int k = 0; k < EPG; ++k) v[k] = lut[(w >> (k * BITS)) & ((1u << BITS) - 1)];
-#pragma unroll
-        for (int k = 0; k < EPG; k += 4)
-            reinterpret_cast<float4 *>(y)[(g * EPG + k) >> 2] = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
     }
-    // remainder (< EPG elements), one thread
+    // remainder (< 4 elements), one thread
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        for (size_t j = groups * EPG; j < n; ++j) {
+        for (size_t j = groups * 4; j < n; ++j) {
             const size_t bit = j * BITS;
             uint32_t w = codes[bit >> 3];
             if ((bit & 7) + BITS > 8) w |= (uint32_t)codes[(bit >> 3) + 1] << 8;
-            y[j] = lut[(w >> (bit & 7)) & ((1u << BITS) - 1)];
+            y[j] = lut[(w >> (bit & 7)) & kMask];
         }
     }
-    (void)BPG;
 }
 
 static int grid_for(size_t work_items, int per_block, int max_blocks)
@@ -796,7 +813,7 @@ extern "C" dybit_status dybit_dequantize(const uint8_t *codes, size_t n, dybit_f
     if (!aligned16(codes) || !aligned16(y_out)) return DYBIT_ERR_ALIGNMENT;
     if (n == 0) return DYBIT_OK;
     hipStream_t hs = (hipStream_t)stream;
-    const int grid = grid_for(n / 8 + 1, kThreads, 256 * 128);
+    const int grid = grid_for(n / 4 + 1, kThreads * 4, 256 * 16);
     switch (f.bits) {
         case 2: hipLaunchKernelGGL((dequantize_kernel<2>), dim3(grid), dim3(kThreads), 0, hs, codes, n, f.is_signed, scale, y_out); break;
         case 4: hipLaunchKernelGGL((dequantize_kernel<4>), dim3(grid), dim3(kThreads), 0, hs, codes, n, f.is_signed, scale, y_out); break;

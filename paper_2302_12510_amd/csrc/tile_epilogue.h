@@ -1,5 +1,6 @@
 // Epilogue shared by the tiled matrix-product kernels: C = acc * (sA sW) (+ bias) (+ residual) (ReLU),
-// sW the scale of the weight tensor or of the output column's weight row (g.w_per_channel),
+// sW the scale of the weight tensor or of the output column's weight row (g.w_per_channel), the residual
+// (shortcut) an fp32 tensor or, in the write-back build, a tensor of DyBit codes with a scale of its own,
 // optional running maximum of |C|, optional write-back of C as DyBit codes (Sec. III-B), for the
 // 32-row strip of accumulator blocks one wave holds.
 //
@@ -97,13 +98,49 @@ __device__ __forceinline__ float store_strip(const GemmArgs &g, const fast::f32x
     return mx;
 }
 
+// Shortcut tensor given as DyBit codes (Sec. III-B: activations live in memory as codes): the value added
+// is fl(s_r * value(code)), the number dybit_dequantize writes.  RES_TABLE (4- and 6-bit codes): lane i of a
+// register holds that number for code i and a value is fetched with one cross-lane read.  RES_ARITH (8-bit
+// codes): the decoder identity of dybit_codec.h in fp32 -- with n = 2^m - magnitude,
+// value * 2^-126 = bitcast(((127 + m) << 23) - bits(float(n))) over the whole range (a subnormal below 1).
+enum { RES_NONE = 0, RES_F32 = 1, RES_TABLE = 2, RES_ARITH = 3 };
+
+struct ResCodes {
+    uint32_t m, mag_mask, two_m, recip_sub, sign_shift;   // magnitude bits, 2^m - 1, 2^m, (127 + m) << 23, 31 - m
+    float s;                                              // the shortcut tensor's scale
+    uint32_t code_mask;                                   // 2^bits - 1
+    uint32_t table;                                       // RES_TABLE: bits of fl(s * value(lane))
+};
+
+__device__ __forceinline__ float res_value(uint32_t code, const ResCodes &r)
+{
+    const float n = (float)(r.two_m - (code & r.mag_mask));
+    const float v = __uint_as_float(r.recip_sub - __float_as_uint(n)) * __uint_as_float(0x7E800000u);   // * 2^126: exact
+    return __uint_as_float(__float_as_uint(v * r.s) ^ ((code << r.sign_shift) & 0x80000000u));
+}
+
+__device__ __forceinline__ ResCodes make_res_codes(const GemmArgs &g, int lane)
+{
+    ResCodes r;
+    const int m = g.res_signed ? g.res_bits - 1 : g.res_bits;
+    r.m = (uint32_t)m;
+    r.mag_mask = (1u << m) - 1u;
+    r.two_m = 1u << m;
+    r.recip_sub = (uint32_t)(127 + m) << 23;
+    r.sign_shift = (uint32_t)(31 - m);                    // unsigned format: bit m of a code is never set
+    r.s = *g.res_scale;
+    r.code_mask = (1u << g.res_bits) - 1u;
+    r.table = __float_as_uint(res_value((uint32_t)lane & r.code_mask, r));
+    return r;
+}
+
 // The same strip with the write-back encoder (requant.h): per 32 x 32 block, three phases over the
 // lane's values (eight at a time) so that the instruction streams of the values interleave and the only branch is
 // one per block -- (1) result, optional fp32 store, rounded real-valued code; (2) only if some
 // lane's value sits within 2^-G of a decision point: the exact decision for those;
 // (3) sign, packing across lanes, store of the packed words through a descriptor of their own.
 // A NULL fp32 output becomes an empty descriptor whose stores the hardware drops.
-template <int CB, bool HAS_RES, int BITS, int ACC_EXP>
+template <int CB, int RES, int BITS, int ACC_EXP>
 __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f32x16 (&acc)[CB], const int64_t m_strip,
                                                 const int64_t n0, const int rows, const float alpha)
 {
@@ -114,8 +151,15 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
     const int records = (int)((uint32_t)rows * ldc4);
     float *const c_base = g.C ? g.C + m_strip * g.ldc : const_cast<float *>(g.a_scale);
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(c_base, 0, g.C ? records : 0, 0x00020000);
+    constexpr bool HAS_RES = RES != RES_NONE, RES_CODES = RES == RES_TABLE || RES == RES_ARITH;
+    const uint32_t rrow = RES_CODES ? (uint32_t)g.res_row_bytes : ldc4;       // bytes from a shortcut row to the next
     const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(HAS_RES ? g.residual + m_strip * g.ldc : g.a_scale), 0, HAS_RES ? records : 0, 0x00020000);
+        RES_CODES ? const_cast<uint8_t *>(g.res_codes + m_strip * g.res_row_bytes)
+                  : reinterpret_cast<uint8_t *>(const_cast<float *>(RES == RES_F32 ? g.residual + m_strip * g.ldc : g.a_scale)),
+        0, HAS_RES ? (int)((uint32_t)rows * rrow) : 0, 0x00020000);
+    ResCodes rc{};
+    if (RES_CODES) rc = make_res_codes(g, lane);
+    const bool res_six = RES == RES_TABLE && g.res_bits == 6;               // uniform: a 6-bit code may straddle two bytes
     const uint32_t qrow = (uint32_t)g.q_row_bytes;
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(g.q_out + m_strip * g.q_row_bytes, 0,
                                                                         (int)((uint32_t)rows * qrow), 0x00020000);
@@ -128,14 +172,33 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
     const float relu_floor = g.relu ? 0.0f : __builtin_nanf("");
     float mx = 0.0f;
     constexpr bool PREFETCH = HAS_RES && CB <= 4;
-    float res2[2][GV];
+    // fp32 shortcut: the value's bits; codes: the byte that holds the code (6-bit: that byte and the next one in
+    // the upper half), shifted and decoded when the value is used
+    uint32_t res2[2][GV];
     uint32_t roff = 0;                                                  // walks the shortcut's rows like `off` walks C's
-    auto load_shortcut = [&](int first_v, float (&r)[GV]) {
+    // position of the lane's code inside its byte: the same in every column block (32 codes are whole bytes)
+    const uint32_t rshift = RES_CODES ? (uint32_t)(((n0 + col) * g.res_bits) & 7) : 0u;
+    auto load_shortcut = [&](int first_v, uint32_t (&r)[GV]) {
 #pragma unroll
         for (int u = 0; u < GV; ++u) {
-            r[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, roff, 0, 0));
-            roff += ((first_v + u) & 3) == 3 ? 5u * ldc4 : ldc4;
+            if (RES_CODES) {
+                r[u] = __builtin_amdgcn_raw_buffer_load_b8(rres, roff, 0, 0);
+                if (res_six) r[u] |= (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rres, roff + 1u, 0, 0) << 8;
+            } else {
+                r[u] = __builtin_amdgcn_raw_buffer_load_b32(rres, roff, 0, 0);
+            }
+            roff += ((first_v + u) & 3) == 3 ? 5u * rrow : rrow;
         }
+    };
+    auto shortcut_offset = [&](int64_t n, bool n_ok) {                  // byte offset of column n in the lane's first row
+        const uint32_t first = RES_CODES ? ((uint32_t)n * (uint32_t)g.res_bits) >> 3 : (uint32_t)n * 4u;
+        return (n_ok ? first : 0x80000000u) + (uint32_t)(4 * kq) * rrow;
+    };
+    auto shortcut_value = [&](uint32_t raw) -> float {
+        if (RES == RES_F32) return __uint_as_float(raw);
+        const uint32_t code = (raw >> rshift) & rc.code_mask;
+        if (RES == RES_TABLE) return __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute((int)(code << 2), (int)rc.table));
+        return res_value(code, rc);
     };
 #pragma unroll
     for (int j = 0; j < CB; ++j) {
@@ -147,20 +210,20 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
         const PackSlot slot = pack_slot<BITS>(lane, (uint32_t)n);
         uint32_t qoff = ((n_ok && slot.stores && rqp.ok) ? slot.byte_off : 0x80000000u) + (uint32_t)(4 * kq) * qrow;
         uint32_t off = off0;
-        if (HAS_RES && (j == 0 || !PREFETCH)) { roff = off0; if (PREFETCH) load_shortcut(0, res2[0]); }
+        if (HAS_RES && (j == 0 || !PREFETCH)) { roff = shortcut_offset(n, n_ok); if (PREFETCH) load_shortcut(0, res2[0]); }
 #pragma unroll
         for (int h = 0; h < 16; h += GV) {                                   // GV values at a time: fewer live registers
             // the shortcut values of the next group are requested before this group is stored (see
             // store_strip) where the kernel has registers for them; else they are loaded here
             const int grp = (j * 16 + h) / GV;
-            float (&res)[GV] = res2[PREFETCH ? (grp & 1) : 0];
+            uint32_t (&res)[GV] = res2[PREFETCH ? (grp & 1) : 0];
             if (HAS_RES && !PREFETCH) load_shortcut(h, res);
             if (PREFETCH) {
                 if (h + GV < 16) {
                     load_shortcut(h + GV, res2[(grp + 1) & 1]);
                 } else if (j + 1 < CB) {
                     const int64_t n1 = n0 + (j + 1) * 32 + col;
-                    roff = (n1 < g.N ? (uint32_t)n1 * 4u : 0x80000000u) + (uint32_t)(4 * kq) * ldc4;
+                    roff = shortcut_offset(n1, n1 < g.N);
                     load_shortcut(0, res2[(grp + 1) & 1]);
                 }
             }
@@ -171,7 +234,7 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
             for (int u = 0; u < GV; ++u) {                                   // phase 1
                 const int v = h + u;
                 c[u] = acc_value<ACC_EXP>(acc[j][v]) * al + b;
-                if (HAS_RES) c[u] += res[u];
+                if (HAS_RES) c[u] += shortcut_value(res[u]);
                 c[u] = fmaxf(c[u], relu_floor);
                 __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(c[u]), rsrc, off, 0, 2);
                 off += (v & 3) == 3 ? 5u * ldc4 : ldc4;
@@ -222,16 +285,16 @@ __device__ __forceinline__ float epilogue_strip(const GemmArgs &g, const fast::f
     const int64_t rows_left = g.M - m_strip;                       // uniform over the wave
     const int rows = rows_left >= 32 ? 32 : rows_left > 0 ? (int)rows_left : 0;
     float mx = 0.0f;
-    if (WB) {                                                       // the host has checked ldc, N and the format
-        if (g.residual) {
-            mx = g.q_bits == 4 ? store_strip_wb<CB, true, 4, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
-               : g.q_bits == 8 ? store_strip_wb<CB, true, 8, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
-                               : store_strip_wb<CB, true, 6, ACC_EXP>(g, acc, m_strip, n0, rows, alpha);
-        } else {
-            mx = g.q_bits == 4 ? store_strip_wb<CB, false, 4, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
-               : g.q_bits == 8 ? store_strip_wb<CB, false, 8, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
-                               : store_strip_wb<CB, false, 6, ACC_EXP>(g, acc, m_strip, n0, rows, alpha);
-        }
+    if (WB) {                                                       // the host has checked ldc, N and the formats
+#define DYBIT_WB_STRIP(RES_) \
+        mx = g.q_bits == 4 ? store_strip_wb<CB, RES_, 4, ACC_EXP>(g, acc, m_strip, n0, rows, alpha) \
+           : g.q_bits == 8 ? store_strip_wb<CB, RES_, 8, ACC_EXP>(g, acc, m_strip, n0, rows, alpha) \
+                           : store_strip_wb<CB, RES_, 6, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
+        if (g.residual) { DYBIT_WB_STRIP(RES_F32); }
+        else if (!g.res_codes) { DYBIT_WB_STRIP(RES_NONE); }
+        else if (g.res_bits == 8) { DYBIT_WB_STRIP(RES_ARITH); }
+        else { DYBIT_WB_STRIP(RES_TABLE); }
+#undef DYBIT_WB_STRIP
     } else if (g.ldc < (1 << 23)) {
         mx = g.residual ? store_strip<CB, true, ACC_EXP>(g, acc, m_strip, n0, rows, alpha)
                         : store_strip<CB, false, ACC_EXP>(g, acc, m_strip, n0, rows, alpha);

@@ -23,6 +23,13 @@ behind the pooling layers.  The scales need not come from an offline calibration
 `forward(x, static=True, track=True)` every epilogue also takes max|result| of the pass, and
 `advance_scales()` turns those maxima into the scales of the next pass (previous-iteration scales).
 
+`code_shortcuts=True` removes the remaining fp32 tensors of the static chain: the identity shortcut of a
+residual block is read as the DyBit codes its tensor was stored as (dybit_conv2d_wb_rc adds
+scale * value(code), the number a decoder in front of the adder would deliver), and a max-pool whose readers
+all take codes of one format pools the codes themselves (dybit_maxpool2d_codes; the encoder is monotone, so
+this equals encoding the pooled fp32 tensor bit for bit).  fp32 then remains only in front of the average
+pool and at the output.
+
 `per_channel=True` gives every output channel of every layer its own weight scale (row-wise max-abs,
 dybit_quantize_rows; the convolutions then run through dybit_conv2d_pc; depthwise filters: one scale per
 channel, dybit_quantize_cols); activations keep one scale per tensor.
@@ -68,8 +75,10 @@ def _pad_few_channels(cin: int, kh: int, kw: int, bits_a: int, bits_w: int):
 
 
 class DybitNetwork:
-    def __init__(self, layers, weights, bitwidths, device="cuda", epilogue_absmax=True, per_channel=False):
+    def __init__(self, layers, weights, bitwidths, device="cuda", epilogue_absmax=True, per_channel=False,
+                 code_shortcuts=False):
         self.layers = layers
+        self.code_shortcuts = code_shortcuts and not per_channel   # static chain: shortcuts and max-pools on codes
         self.per_channel = per_channel           # True: one weight scale per output channel (dybit_quantize_rows, dybit_conv2d_pc)
         self.epilogue_absmax = epilogue_absmax   # False: every scale from a pass over the fp32 tensor
         self.bitwidths = bitwidths
@@ -119,7 +128,8 @@ class DybitNetwork:
 
     def _plan_write_back(self):
         """Per conv layer: the format its consumers want its output in (if they agree and the packed
-        rows are whole words) and whether anyone needs the fp32 tensor."""
+        rows are whole words), whether anyone needs the fp32 tensor, and (code_shortcuts) whether its
+        shortcut is read as codes; per max-pool: whether it pools codes."""
         nonneg = {"input": False}
         produced_by = {}
         coded = ("conv", "fc", "dwconv")             # layers that read codes
@@ -131,21 +141,69 @@ class DybitNetwork:
                 nonneg[l["name"]] = nonneg[l["src"]]
         self.a_fmt = {l["name"]: (self.params[l["name"]]["a_bits"], not nonneg[l["src"]])
                       for l in self.layers if l["op"] in coded}
-        self.plan = {}
         last = self.layers[-1]["name"]
-        for name, l in produced_by.items():
-            cout = self.params[name]["cout"]
-            users = [u for u in self.layers if u["src"] == name]
-            convs = [u for u in users if u["op"] in coded]
+        readers = lambda t: [u for u in self.layers if u["src"] == t]
+        adders = lambda t: [u for u in self.layers if u.get("add") == t]
+        pools = {l["name"]: l for l in self.layers if l["op"] == "maxpool"}
+
+        def common_format(convs, channels):
+            """The one format the coded readers of a tensor of `channels` channels agree on, or None."""
             fmts = {self.a_fmt[u["name"]] for u in convs}
-            fused = (len(fmts) == 1 and l["op"] in ("conv", "dwconv")
-                     and all(self.params[u["name"]]["cpad"] == cout for u in convs)
-                     and (cout * next(iter(fmts))[0]) % 32 == 0
-                     and (l["op"] == "conv" or next(iter(fmts))[0] in (4, 8)))     # the depthwise epilogue packs 4- and 8-bit codes
-            need_fp32 = (name == last or not fused or any(u["op"] not in coded for u in users)
-                         or any(u.get("add") == name for u in self.layers))
-            self.plan[name] = {"fmt": next(iter(fmts)) if fused else None,
-                               "scale_of": convs[0]["name"] if fused else None, "fp32": need_fp32}
+            if len(fmts) != 1 or not all(self.params[u["name"]]["cpad"] == channels for u in convs):
+                return None
+            f = next(iter(fmts))
+            return f if (channels * f[0]) % 32 == 0 else None
+
+        # a max-pool may pool codes when all its readers take codes of one 2-, 4- or 8-bit format
+        pool_fmt = {}
+        for name, l in pools.items():
+            src = produced_by.get(l["src"])
+            rd = readers(name)
+            f = common_format(rd, self.params[src["name"]]["cout"]) if src and rd and all(u["op"] in coded for u in rd) else None
+            pool_fmt[name] = f if (self.code_shortcuts and f and f[0] in (2, 4, 8) and src["op"] == "conv") else None
+        while True:
+            fmt_of = {}
+            for name, l in produced_by.items():
+                rd = readers(name)
+                convs = [u for u in rd if u["op"] in coded]
+                through = [pool_fmt[u["name"]] for u in rd if u["op"] == "maxpool" and pool_fmt[u["name"]]]
+                f = common_format(convs, self.params[name]["cout"]) if convs else (through[0] if through else None)
+                if f and any(t != f for t in through):
+                    f = None
+                if f and not (l["op"] == "conv" or (l["op"] == "dwconv" and f[0] in (4, 8))):   # the depthwise epilogue packs 4- and 8-bit codes
+                    f = None
+                fmt_of[name] = f
+            # a layer can read its shortcut as codes when it writes codes itself (the decoder sits in that epilogue)
+            takes_codes = lambda u: self.code_shortcuts and fmt_of.get(u["name"]) is not None
+            # a tensor that is only ever added as a shortcut (the projection of a downsampling block) has no reader
+            # to dictate a format: 8-bit codes under a scale of its own
+            own = set()
+            for name, l in produced_by.items():
+                if (self.code_shortcuts and l["op"] == "conv" and not readers(name) and adders(name) and name != last
+                        and all(takes_codes(u) for u in adders(name)) and (self.params[name]["cout"] * 8) % 32 == 0):
+                    own.add(name)
+            for name in own:
+                fmt_of[name] = (8, not produced_by[name].get("relu"))
+            dropped = [n for n, f in pool_fmt.items()
+                       if f and (fmt_of[pools[n]["src"]] != f or not all(takes_codes(u) for u in adders(n)))]
+            if not dropped:
+                break
+            for n in dropped:
+                pool_fmt[n] = None
+        self.pool_fmt = pool_fmt
+        self.plan = {}
+        for name, l in produced_by.items():
+            f = fmt_of[name]
+            rd = readers(name)
+            convs = [u for u in rd if u["op"] in coded] or [u for p in rd if p["op"] == "maxpool" for u in readers(p["name"])]
+            others = [u for u in rd if u["op"] not in coded and not (u["op"] == "maxpool" and pool_fmt[u["name"]])]
+            add_ok = f is not None and f[0] != 2 and all(takes_codes(u) for u in adders(name))
+            need_fp32 = name == last or f is None or bool(others) or (bool(adders(name)) and not add_ok)
+            shortcut = l.get("add")
+            src_fmt = (fmt_of.get(shortcut) if shortcut in produced_by else pool_fmt.get(shortcut)) if shortcut else None
+            self.plan[name] = {"fmt": f, "scale_of": ("out:" + name if name in own else convs[0]["name"]) if f else None,
+                               "fp32": need_fp32,
+                               "shortcut_codes": bool(shortcut) and takes_codes(l) and src_fmt is not None and src_fmt[0] != 2}
 
     def _layer_params(self, l, height: int, width: int):
         """Parameters of a conv layer for an input of the given size: the few-channel layout (filter
@@ -162,7 +220,14 @@ class DybitNetwork:
     def calibrate(self, x: torch.Tensor) -> None:
         """Fixes the scale of every activation tensor to the one a dynamic forward pass over x uses."""
         scales = {}
-        self.forward(x, record=lambda name, rec: scales.__setitem__(name, rec["a_scale"].clone()))
+
+        def keep(name, rec):
+            scales[name] = rec["a_scale"].clone()
+            plan = self.plan[name]
+            if plan["scale_of"] == "out:" + name:           # encoded under a scale of its own: that of this pass's values
+                scales[plan["scale_of"]] = B.dybit_absmax_scale(rec["y"].reshape(-1), *plan["fmt"])
+
+        self.forward(x, record=keep)
         self.static_scale = scales
 
     def forward(self, x: torch.Tensor, record=None, static: bool = False, track: bool = False) -> torch.Tensor:
@@ -298,6 +363,9 @@ class DybitNetwork:
         for l in self.layers:
             if l["op"] in ("conv", "fc", "dwconv") and l["src"] in origin:
                 B.dybit_scale_from_absmax(self._tracked[origin[l["src"]]], *self.a_fmt[l["name"]], out=self.static_scale[l["name"]])
+            own = self.plan.get(l["name"], {}).get("scale_of")
+            if own == "out:" + l["name"]:
+                B.dybit_scale_from_absmax(self._tracked[l["name"]], *self.plan[l["name"]]["fmt"], out=self.static_scale[own])
 
     def _forward_static(self, x: torch.Tensor, record=None, track: bool = False) -> torch.Tensor:
         if self.static_scale is None:
@@ -343,6 +411,17 @@ class DybitNetwork:
                                 (W + 2 * l["pad"] - p["kw"]) // l["stride"] + 1, C)
                 acts[name] = out
                 continue
+            if op == "maxpool" and self.pool_fmt[name]:
+                f, s_in, q_in = codes[l["src"]]                 # the codes the producer wrote, pooled as codes
+                Bn, H, W, C = shapes[l["src"]]
+                q = B.dybit_maxpool2d_codes(Bn, H, W, C, l["k"], l["stride"], l["pad"], q_in, f)
+                codes[name] = (f, s_in, q)
+                shapes[name] = (Bn, q.shape[1], q.shape[2], C)
+                acts[name] = None
+                if record is not None:
+                    record(name, {"op": "maxpool", "fmt": f, "x_codes": q_in, "y_codes": q, "in_shape": (Bn, H, W, C),
+                                  "k": l["k"], "stride": l["stride"], "pad": l["pad"]})
+                continue
             if op == "maxpool":
                 y = torch.nn.functional.max_pool2d(src.permute(0, 3, 1, 2), l["k"], l["stride"], l["pad"])
                 out = y.permute(0, 2, 3, 1).contiguous()
@@ -368,7 +447,16 @@ class DybitNetwork:
                 plan = self.plan[name]
                 y_codes = None
                 word = None if words is None else words[name]
-                if plan["fmt"] is not None:
+                if plan["shortcut_codes"]:
+                    r_fmt, r_scale, r_codes = codes[l["add"]]
+                    y_scale = self.static_scale[plan["scale_of"]]
+                    y, y_codes = B.dybit_conv2d_wb_rc(*conv_args, plan["fmt"], y_scale, r_codes, r_fmt, r_scale, p["bias"], relu,
+                                                      word, fp32=plan["fp32"])
+                    codes[name] = (plan["fmt"], y_scale, y_codes)
+                    if record is not None:                      # what the epilogue added: the decoded codes
+                        shortcut = B.dybit_dequantize(r_codes.reshape(-1), r_codes.numel() * 8 // r_fmt[0], r_scale, *r_fmt)
+                        shortcut = shortcut.reshape(y_codes.shape[0], y_codes.shape[1], y_codes.shape[2], p["cout"])
+                elif plan["fmt"] is not None:
                     y_scale = self.static_scale[plan["scale_of"]]
                     if self.per_channel:
                         y, y_codes = B.dybit_conv2d_pc(*conv_args, p["bias"], shortcut, relu, word, plan["fmt"], y_scale,

@@ -137,17 +137,35 @@ def run_chain(layers, bits, batch, hw, n_rows, n_codes):
     return logits
 
 
-def run_chain_static(layers, bits, batch, hw, n_rows):
+def check_pool_on_codes(rec, images):
+    """A max-pool that ran on codes: bit for bit the oracle's pooling of the codes it read (first `images` images)."""
+    f = rec["fmt"]
+    Bn, H, W, C = rec["in_shape"]
+    n = min(Bn, images)
+    px = H * W * C * f[0] // 8
+    qx = R.unpack(rec["x_codes"].reshape(Bn, -1)[:n].cpu().numpy().reshape(-1), n * H * W * C, f[0]).reshape(n, H, W, C)
+    want = R.maxpool2d_codes(qx, *f, rec["k"], rec["stride"], rec["pad"])
+    got = rec["y_codes"].reshape(Bn, -1)[:n].cpu().numpy().reshape(-1)
+    assert px and np.array_equal(got, R.pack_rows(want.reshape(-1, C), f[0]).reshape(-1))
+
+
+def run_chain_static(layers, bits, batch, hw, n_rows, code_shortcuts=False):
     weights = synth.network_weights(layers, seed=0)
-    net = DybitNetwork(layers, weights, bits)
+    net = DybitNetwork(layers, weights, bits, code_shortcuts=code_shortcuts)
     x = torch.from_numpy(synth.network_input(batch, hw, seed=0)).cuda()
     net.calibrate(x)
     rng = np.random.default_rng(1)
     seen, fused, codes_only = [], 0, 0
+    pooled_codes = shortcut_codes = 0
 
     def record(name, rec):
-        nonlocal fused, codes_only
+        nonlocal fused, codes_only, pooled_codes, shortcut_codes
         torch.cuda.synchronize()
+        if rec.get("op") == "maxpool":
+            check_pool_on_codes(rec, 2)
+            pooled_codes += 1
+            return
+        shortcut_codes += bool(net.plan[name]["shortcut_codes"])
         check_layer_static(name, rec, weights, rng, n_rows)
         seen.append(name)
         fused += rec["y_codes"] is not None
@@ -160,8 +178,14 @@ def run_chain_static(layers, bits, batch, hw, n_rows):
     assert len(seen) == len([l for l in layers if l["op"] in ("conv", "fc")])
     # on the calibration input the static chain encodes the same fp32 values with the same scales as the
     # dynamic chain, in the epilogue instead of in a pass of its own: the logits are the same bits
-    assert torch.equal(logits, net.forward(x))
-    return fused, codes_only
+    if not code_shortcuts:
+        assert torch.equal(logits, net.forward(x))
+        return fused, codes_only
+    # shortcuts read as codes carry the quantization error of their tensor: the logits move, a little
+    ref = net.forward(x)
+    cos = float(torch.nn.functional.cosine_similarity(logits.reshape(1, -1), ref.reshape(1, -1)))
+    assert cos > 0.5, cos
+    return fused, codes_only, pooled_codes, shortcut_codes
 
 
 def test_resnet18_fused_write_back_small_every_output():
@@ -174,6 +198,35 @@ def test_resnet50_mixed_fused_write_back_small_every_output():
     layers = synth.resnet50_layers()
     fused, codes_only = run_chain_static(layers, synth.bitwidths_mixed(layers, seed=0), batch=2, hw=64, n_rows=None)
     assert fused == 45 and codes_only == 33
+
+
+def test_resnet18_code_shortcuts_small_every_output():
+    """The static chain with shortcuts and the max-pool on codes: the stem writes codes only, the pool pools
+    them, and every shortcut but the last block's (whose layer writes no codes: the average pool reads fp32) is read
+    as codes -- four block inputs in their readers' 4-bit format and the three projections of the downsampling
+    blocks, which nothing else reads, as 8-bit codes under scales of their own."""
+    layers = synth.resnet18_layers()
+    fused, codes_only, pooled, shortcuts = run_chain_static(layers, synth.bitwidths_fixed(layers), batch=2, hw=64, n_rows=None,
+                                                            code_shortcuts=True)
+    assert pooled == 1 and shortcuts == 7
+    assert fused == 19 and codes_only == 18
+
+
+def test_resnet50_mixed_code_shortcuts_small_every_output():
+    layers = synth.resnet50_layers()
+    fused, codes_only, pooled, shortcuts = run_chain_static(layers, synth.bitwidths_mixed(layers, seed=0), batch=2, hw=64,
+                                                            n_rows=None, code_shortcuts=True)
+    assert shortcuts >= 6 and codes_only > 33
+
+
+def test_resnet18_config3_code_shortcuts_full_size_sampled():
+    layers = synth.resnet18_layers()
+    run_chain_static(layers, synth.bitwidths_fixed(layers), batch=64, hw=224, n_rows=96, code_shortcuts=True)
+
+
+def test_resnet50_config4_code_shortcuts_full_size_sampled():
+    layers = synth.resnet50_layers()
+    run_chain_static(layers, synth.bitwidths_mixed(layers, seed=0), batch=128, hw=224, n_rows=64, code_shortcuts=True)
 
 
 def test_resnet18_config3_fused_write_back_full_size_sampled():

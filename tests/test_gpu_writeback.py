@@ -159,3 +159,98 @@ def test_wb_unusable_scale_writes_no_codes_and_sets_the_flag(bad):
     assert bool((codes == 0xA5).all())
     want, den = R.gemm(qa, a_fmt, 1.0, qw, w_fmt, 1.0)
     assert_within(c.cpu().numpy(), want, den)
+
+
+R_FMTS = [(4, False), (4, True), (6, False), (6, True), (8, False), (8, True)]
+
+
+@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "mid64", "general"], indirect=True)
+@pytest.mark.parametrize("r_fmt", R_FMTS)
+@pytest.mark.parametrize("a_fmt", [(8, True), (4, False)])
+def test_gemm_wb_shortcut_as_codes(force_kernel, r_fmt, a_fmt):
+    """The shortcut tensor given as DyBit codes (dybit_gemm_wb_rc): against the oracle with the decoded
+    shortcut, and bit for bit the call that gets the same shortcut as the fp32 tensor dybit_dequantize
+    writes.  Ragged M and N tiles, every code of the shortcut's format present."""
+    rng = np.random.default_rng(53 + r_fmt[0])
+    w_fmt, c_fmt = (4, True), (8, True)
+    M, N, K = 290, 480, 128
+    qa = random_codes(rng, (M, K), a_fmt)
+    qw = random_codes(rng, (N, K), w_fmt)
+    qr = rng.integers(0, 1 << r_fmt[0], (M, N)).astype(np.uint8)
+    r_scale = np.float32(0.73)
+    res = R.dequantize(qr, r_scale, *r_fmt)
+    bias = rng.normal(0, 3, N).astype(np.float32)
+    want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, bias, True, res)
+    c_scale = np.float32(0.6 * np.abs(want).max() / R.vmax(*c_fmt))
+    args = (M, N, K, pack_rows_dev(qa, a_fmt[0]), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt, scalar(0.011),
+            c_fmt, scalar(c_scale))
+    mx = torch.zeros(1, dtype=torch.float32, device="cuda")
+    c, codes = B.dybit_gemm_wb_rc(*args, pack_rows_dev(qr, r_fmt[0]), r_fmt, scalar(r_scale), dev(bias), True, mx)
+    torch.cuda.synchronize()
+    c32 = c.cpu().numpy()
+    assert_within(c32, want, den, shortcut=True)
+    check_codes(codes, c32, c_scale, c_fmt)
+    assert mx.item() == np.abs(c32).max()
+    c_ref, codes_ref = B.dybit_gemm_wb(*args, dev(bias), dev(res), True)
+    none, codes_only = B.dybit_gemm_wb_rc(*args, pack_rows_dev(qr, r_fmt[0]), r_fmt, scalar(r_scale), dev(bias), True,
+                                          None, fp32=False)
+    torch.cuda.synchronize()
+    assert torch.equal(c, c_ref) and torch.equal(codes, codes_ref)
+    assert none is None and torch.equal(codes_only, codes)
+
+
+@pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
+@pytest.mark.parametrize("r_fmt", R_FMTS)
+def test_gemm_wb_shortcut_as_codes_weight_stationary(force_kernel, r_fmt):
+    rng = np.random.default_rng(59 + r_fmt[0])
+    a_fmt, w_fmt, c_fmt = (8, False), (4, True), (4, False)
+    M, N, K = 777, 96, 128
+    qa = random_codes(rng, (M, K), a_fmt)
+    qw = random_codes(rng, (N, K), w_fmt)
+    qr = rng.integers(0, 1 << r_fmt[0], (M, N)).astype(np.uint8)
+    res = R.dequantize(qr, np.float32(1.9), *r_fmt)
+    want, den = R.gemm(qa, a_fmt, 0.37, qw, w_fmt, 0.011, None, True, res)
+    c_scale = np.float32(0.8 * np.abs(want).max() / R.vmax(*c_fmt))
+    c, codes = B.dybit_gemm_wb_rc(M, N, K, pack_rows_dev(qa, 8), a_fmt, scalar(0.37), pack_rows_dev(qw, 4), w_fmt, scalar(0.011),
+                                  c_fmt, scalar(c_scale), pack_rows_dev(qr, r_fmt[0]), r_fmt, scalar(1.9), None, True)
+    torch.cuda.synchronize()
+    c32 = c.cpu().numpy()
+    assert_within(c32, want, den, shortcut=True)
+    check_codes(codes, c32, c_scale, c_fmt)
+
+
+@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "mid64", "mid1-f16", "general"], indirect=True)
+@pytest.mark.parametrize("r_fmt", [(4, False), (6, True), (8, False)])
+def test_conv2d_wb_shortcut_as_codes(force_kernel, r_fmt):
+    rng = np.random.default_rng(61)
+    x_fmt, w_fmt, y_fmt = (4, False), (4, True), (4, False)
+    Cout = 96
+    qx = random_codes(rng, (2, 9, 10, 64), x_fmt)
+    qw = random_codes(rng, (Cout, 3, 3, 64), w_fmt)
+    qr = rng.integers(0, 1 << r_fmt[0], (2, 9, 10, Cout)).astype(np.uint8)
+    res = R.dequantize(qr, np.float32(2.5), *r_fmt)
+    bias = rng.normal(0, 1, Cout).astype(np.float32)
+    want, den = R.conv2d(qx, x_fmt, 0.3, qw, w_fmt, 0.02, 1, 1, bias, True, res)
+    y_scale = np.float32(np.abs(want).max() / R.vmax(*y_fmt))
+    y, codes = B.dybit_conv2d_wb_rc(2, 9, 10, 64, Cout, 3, 3, 1, 1, pack_rows_dev(qx.reshape(-1, 64), 4), x_fmt, scalar(0.3),
+                                    pack_rows_dev(qw.reshape(-1, 64), 4), w_fmt, scalar(0.02), y_fmt, scalar(y_scale),
+                                    pack_rows_dev(qr.reshape(-1, Cout), r_fmt[0]), r_fmt, scalar(2.5), dev(bias), True)
+    torch.cuda.synchronize()
+    y32 = y.cpu().numpy()
+    assert_within(y32, want, den, shortcut=True)
+    check_codes(codes, y32.reshape(-1, Cout), y_scale, y_fmt)
+
+
+def test_wb_rc_argument_errors():
+    a = torch.zeros(64 * 64, dtype=torch.uint8, device="cuda")
+    one = scalar(1.0)
+    args = (64, 64, 64, a, (8, False), one, a, (8, True), one, (8, False), one)
+    with pytest.raises(B.DybitError) as e:
+        B.dybit_gemm_wb_rc(*args, a, (2, False), one)
+    assert e.value.status == B.ERR_UNSUPPORTED_BITS
+    with pytest.raises(B.DybitError) as e:
+        B.dybit_gemm_wb_rc(*args, None, (4, False), one)
+    assert e.value.status == B.ERR_NULL
+    with pytest.raises(B.DybitError) as e:
+        B.dybit_gemm_wb_rc(*args, a, (4, False), None)
+    assert e.value.status == B.ERR_NULL
