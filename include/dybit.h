@@ -314,6 +314,17 @@ dybit_status dybit_group_conv2d(int64_t B, int64_t H, int64_t W, int64_t Cin, in
 dybit_status dybit_quantize_cols(const float *x, int64_t rows, int64_t cols, dybit_fmt f, float *scales_out,
                                  uint8_t *codes_out, dybit_stream stream);
 
+/* dybit_quantize of a row-major matrix with every row padded with zero codes: row r of x holds `cols` floats,
+ * row r of codes_out `cols_padded` codes, of which the last cols_padded - cols are code 0 (value 0).  For a
+ * few-channel image whose pixels must end on a byte or word boundary for the convolution (3 -> 4 channels): the
+ * codes equal those of dybit_quantize on the zero-padded fp32 tensor, which then need not exist.
+ *   x [device]: rows * cols floats.  scale [device]: 1 float, as for dybit_quantize (an unusable scale writes
+ *   nothing and sets the asynchronous error flag); padding changes no maximum, so dybit_absmax_scale of x serves.
+ *   cols_padded: >= cols, a multiple of 4 (DYBIT_ERR_ALIGNMENT).  codes_out [device]: rows * cols_padded * bits / 8
+ *   bytes, written by the call. */
+dybit_status dybit_quantize_pad(const float *x, int64_t rows, int64_t cols, int64_t cols_padded, dybit_fmt f,
+                                const float *scale, uint8_t *codes_out, dybit_stream stream);
+
 /* *scale_out = *absmax / 2^(m-1), or 1.0 when *absmax == 0: the last step of dybit_absmax_scale,
  * for a maximum obtained otherwise.  absmax, scale_out [device]: 1 float each (may be the same word). */
 dybit_status dybit_scale_from_absmax(const float *absmax, dybit_fmt f, float *scale_out, dybit_stream stream);
@@ -380,6 +391,15 @@ dybit_status dybit_search(int32_t n_layers, const double *lat, const double *rms
  * device: *flag_out [host] is DYBIT_OK or DYBIT_ERR_BAD_SCALE (a dybit_quantize kernel since the
  * last call, or a write-back epilogue, found an unusable scale and wrote no codes). */
 dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream);
+
+/* A caller-owned error word for the calling host thread (for callers that run several streams at once and
+ * want to know which one met the error; the library's own flag is one word per device).
+ *   device_word [device]: one int32, 4-byte aligned (DYBIT_ERR_ALIGNMENT), zeroed by the caller.  From this
+ *   call on, kernels launched by this host thread's calls store DYBIT_ERR_BAD_SCALE there instead of into
+ *   the library's flag; the caller reads and clears it (after synchronising with the stream it used) and keeps
+ *   it alive until those kernels have finished.  NULL: back to the library's flag.
+ * dybit_get_last_async_error keeps reporting the library's flag only.  Host only, no device work. */
+dybit_status dybit_set_async_error_word(int32_t *device_word);
 
 /* Which kernel a matrix-product call ran on (Sec. III-B's array has one datapath; this library picks
  * among several kernels by shape and formats).  Host only, no device work.

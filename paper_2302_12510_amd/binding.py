@@ -57,6 +57,7 @@ def lib() -> C.CDLL:
         L.dybit_gemm_wb_rc.argtypes = [i64, i64, i64, vp, Fmt, vp, vp, Fmt, vp, vp, vp, Fmt, vp, i32, vp, i64, vp, Fmt, vp, vp, vp]
         L.dybit_conv2d_wb_rc.argtypes = [i64] * 5 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, vp, Fmt, vp, i32, vp, vp, Fmt, vp, vp, vp]
         L.dybit_maxpool2d_codes.argtypes = [i64] * 4 + [i32] * 3 + [vp, Fmt, vp, vp]
+        L.dybit_quantize_pad.argtypes = [vp, i64, i64, i64, Fmt, vp, vp, vp]
         L.dybit_scale_from_absmax.argtypes = [vp, Fmt, vp, vp]
         L.dybit_quantize_rows.argtypes = [vp, i64, i64, Fmt, vp, vp, vp]
         L.dybit_dwconv2d.argtypes = [i64] * 4 + [i32] * 4 + [vp, Fmt, vp, vp, Fmt, vp, vp, i32, vp, vp, vp]
@@ -70,6 +71,7 @@ def lib() -> C.CDLL:
         L.dybit_group_conv2d.argtypes = [i64] * 5 + [i32] * 5 + [vp, Fmt, vp, vp, Fmt, vp, i32, vp, vp, i32, vp, vp, vp]
         L.dybit_search.argtypes = [i32, vp, vp, vp, i32, C.c_double, i32, vp, vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.dybit_get_last_async_error.argtypes = [C.POINTER(i32), vp]
+        L.dybit_set_async_error_word.argtypes = [vp]
         L.dybit_last_gemm_kernel.argtypes = []
         L.dybit_last_gemm_kernel.restype = i32
         L.dybit_set_option.argtypes = [C.c_char_p, C.c_char_p]
@@ -443,6 +445,15 @@ def dybit_quantize_cols(x: torch.Tensor, bits: int, signed: bool, stream=None):
     return scales, codes
 
 
+def dybit_quantize_pad(x: torch.Tensor, cols_padded: int, scale: torch.Tensor, bits: int, signed: bool, stream=None):
+    """Codes of the [rows][cols] matrix x with every row padded to cols_padded codes (zero codes)."""
+    rows, cols = x.shape
+    out = torch.empty((rows, cols_padded * bits // 8), dtype=torch.uint8, device=x.device)
+    _check(lib().dybit_quantize_pad(_ptr(x), rows, cols, cols_padded, fmt(bits, signed), _ptr(scale), _ptr(out), _stream(stream)),
+           "dybit_quantize_pad")
+    return out
+
+
 def dybit_quantize_rows(x: torch.Tensor, bits: int, signed: bool, stream=None):
     """x: [rows][cols] float32.  Returns (scales [rows], codes [rows][cols*bits/8]): every row encoded under
     its own max-abs scale."""
@@ -506,6 +517,12 @@ def dybit_get_last_async_error(stream=None) -> int:
     flag = C.c_int32(0)
     _check(lib().dybit_get_last_async_error(C.byref(flag), _stream(stream)), "dybit_get_last_async_error")
     return int(flag.value)
+
+
+def dybit_set_async_error_word(word: torch.Tensor | None) -> None:
+    """Asynchronous errors of this host thread's calls go to `word` (device int32 tensor of one element, kept
+    alive by the caller) instead of the library's flag; None restores the library's flag."""
+    _check(lib().dybit_set_async_error_word(_ptr(word)), "dybit_set_async_error_word")
 
 
 def dybit_diag_mfma_f16(operands: torch.Tensor, workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> float:

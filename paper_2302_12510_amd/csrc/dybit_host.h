@@ -13,12 +13,14 @@ inline dybit_status check_fmt(dybit_fmt f)
     return DYBIT_OK;
 }
 
-// Device address of the asynchronous error flag of the current device, or NULL (quantize.hip).
+// Device word that receives the asynchronous errors of this host thread's calls: the caller's own
+// (dybit_set_async_error_word) or the library's flag on the current device; NULL on a HIP failure (quantize.hip).
 int *async_error_word();
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // A HIP error that a launch function met before its launch (gemm_dispatch.cpp keeps it per host thread).
+void note_hip(hipError_t e);
 hipError_t take_hip_error();
 
 inline dybit_status launch_status()

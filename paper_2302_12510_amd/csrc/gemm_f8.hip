@@ -30,6 +30,7 @@
 
 #include "dybit_codec.h"
 #include "gemm_args.h"
+#include "tile_common.h"
 #include "tile_epilogue.h"
 
 namespace dybit {
@@ -161,21 +162,10 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
     // ---- tile assignment: XCD x (workgroup id mod 8) takes a contiguous range of a tile order that
     // walks column panels of up to 8 tiles row by row
     int tile_m, tile_n;
-    {
-        const int per_xcd = (int)gridDim.x >> 3;
-        const int l = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-        if (l >= tiles_m * tiles_n) return;                       // uniform per workgroup
-        const int panel = l / (tiles_m * 8), r = l - panel * tiles_m * 8;
-        const int width = min(8, tiles_n - panel * 8);
-        tile_m = r / width;
-        tile_n = panel * 8 + (r - tile_m * width);
-    }
+    if (!panel_order_tile(xcd_contiguous_index(), tiles_m, tiles_n, tile_m, tile_n)) return;   // uniform per workgroup
     const int64_t m0 = (int64_t)tile_m * T, n0 = (int64_t)tile_n * T;
 
-    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.A), 0, (int)(g.a_bytes > 0x7fffffff ? 0x7fffffff : g.a_bytes), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcA = code_descriptor(g.A, g.a_bytes), rsrcW = code_descriptor(g.W, g.w_bytes);
 
     // ---- A: the lane's own row; per 64-wide block its 32 codes (16 bytes) at k-quarter kq
     const int a_row_bytes = (int)(g.K * BA / 8), w_row_bytes = (int)(g.K * BW / 8);
@@ -187,13 +177,10 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
         const int64_t m = m0 + wr * 32 + (lane & 31);
         okA = m < g.M;
         if (CONV) {
-            const int64_t mm = okA ? m : 0;
-            const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
-            const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
-            const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
-            hi0 = ho * g.stride - g.pad;
-            wi0 = wo * g.stride - g.pad;
-            offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * A_LOAD);
+            const PixelOrigin o = pixel_origin(g, okA ? m : 0);
+            hi0 = o.hi0;
+            wi0 = o.wi0;
+            offA = (u32)(o.first_pixel * pix_bytes + kq * A_LOAD);
         } else {
             offA = okA ? (u32)(m * a_row_bytes + kq * A_LOAD) : kOob;
         }
@@ -208,19 +195,13 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
     // K steps are loaded in order: the first k of the wave's next block, and for a convolution its
     // filter row, filter column and first channel, are counted up (uniform over the wave).
     int64_t a_k0 = kgp * 128;
-    int a_fr = 0, a_fs = 0, a_c0 = 0;
-    auto settle_tap = [&]() {
-        while (a_c0 >= g.Cin) {
-            a_c0 -= g.Cin;
-            if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
-        }
-    };
-    if (CONV) { a_c0 = kgp * 128; settle_tap(); }
+    TapCounter tap;
+    if (CONV) tap.advance(kgp * 128, g);
     auto load_A_block = [&](u32x4 &raw, int advance) {                  // one 64-wide block, then step on by `advance`
         u32 off;
         if (CONV) {
-            const bool in = okA && a_k0 < g.K && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
-            off = in ? offA + (u32)((a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * BA / 8) : kOob;   // padding reads code 0
+            const bool in = okA && a_k0 < g.K && tap.inside(g, hi0, wi0);
+            off = in ? offA + (u32)tap.byte_offset(g, pix_bytes, BA) : kOob;   // padding reads code 0
         } else {
             off = a_k0 < g.K ? offA + (u32)(a_k0 * BA / 8) : kOob;
         }
@@ -231,7 +212,7 @@ void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
             raw = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, off, 0, 0);
         }
         a_k0 += advance;
-        if (CONV) { a_c0 += advance; settle_tap(); }
+        if (CONV) tap.advance(advance, g);
     };
     auto load_A = [&](u32x4 *raw) {                                       // both blocks of the next K step
         load_A_block(raw[0], 64);

@@ -29,6 +29,7 @@
 
 #include "dybit_codec.h"
 #include "gemm_args.h"
+#include "tile_common.h"
 #include "tile_epilogue.h"
 
 #ifndef DYBIT_FAST_W
@@ -75,21 +76,10 @@ __global__ __launch_bounds__(512) void gemm_fast_kernel(const GemmArgs g, const 
     // 8 tiles row by row, so the 32 tiles it has in flight form a compact 4 x 8 patch whose
     // A and W strips are shared inside its own L2.  No workgroup is launched without a tile.
     int tile_m, tile_n;
-    {
-        const int per_xcd = (int)gridDim.x >> 3;
-        const int l = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-        if (l >= tiles_m * tiles_n) return;                       // uniform per workgroup
-        const int panel = l / (tiles_m * 8), r = l - panel * tiles_m * 8;
-        const int width = min(8, tiles_n - panel * 8);             // the last panel may be narrower
-        tile_m = r / width;
-        tile_n = panel * 8 + (r - tile_m * width);
-    }
+    if (!panel_order_tile(xcd_contiguous_index(), tiles_m, tiles_n, tile_m, tile_n)) return;   // uniform per workgroup
     const int64_t m0 = (int64_t)tile_m * TM, n0 = (int64_t)tile_n * TN;
 
-    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.A), 0, (int)(g.a_bytes > 0x7fffffff ? 0x7fffffff : g.a_bytes), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcA = code_descriptor(g.A, g.a_bytes), rsrcW = code_descriptor(g.W, g.w_bytes);
 
     // ---- A: the lane's own row, its k-group's half of the K step
     const int a_row_bytes = (int)(g.K * CA::BITS / 8), w_row_bytes = (int)(g.K * CW::BITS / 8);
@@ -99,13 +89,10 @@ __global__ __launch_bounds__(512) void gemm_fast_kernel(const GemmArgs g, const 
     const int64_t m_lane = m0 + wave * 32 + (lane & 31);
     const bool okA = m_lane < g.M;
     if (CONV) {
-        const int64_t mm = okA ? m_lane : 0;
-        const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
-        const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
-        const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
-        hi0 = ho * g.stride - g.pad;
-        wi0 = wo * g.stride - g.pad;
-        offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kg * 16 * NA);
+        const PixelOrigin o = pixel_origin(g, okA ? m_lane : 0);
+        hi0 = o.hi0;
+        wi0 = o.wi0;
+        offA = (u32)(o.first_pixel * pix_bytes + kg * 16 * NA);
     } else {
         offA = okA ? (u32)(m_lane * a_row_bytes + kg * 16 * NA) : kOob;   // rows past M stay out of range as k advances
     }
@@ -121,18 +108,13 @@ __global__ __launch_bounds__(512) void gemm_fast_kernel(const GemmArgs g, const 
     const int64_t ktiles = g.K / TK;
     // K steps are loaded in order, so for a convolution the filter row, filter column and first
     // channel of the next step are counted up instead of being divided out of k every time.
-    int a_fr = 0, a_fs = 0, a_c0 = 0;
+    TapCounter tap;
     auto load_A = [&](int64_t kt, u32x4 *raw) {
         u32 off;
         if (CONV) {
-            const int tap_off = (a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * CA::BITS / 8;
-            const bool in = okA && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
-            off = (in && kt < ktiles) ? offA + (u32)tap_off : kOob;            // padding reads code 0
-            a_c0 += TK;
-            while (a_c0 >= g.Cin) {
-                a_c0 -= g.Cin;
-                if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
-            }
+            const bool in = okA && tap.inside(g, hi0, wi0);
+            off = (in && kt < ktiles) ? offA + (u32)tap.byte_offset(g, pix_bytes, CA::BITS) : kOob;   // padding reads code 0
+            tap.advance(TK, g);
         } else {
             off = kt < ktiles ? offA + (u32)(kt * TK * CA::BITS / 8) : kOob;
         }

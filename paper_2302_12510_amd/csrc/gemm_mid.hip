@@ -28,6 +28,7 @@
 
 #include "dybit_codec.h"
 #include "gemm_args.h"
+#include "tile_common.h"
 #include "tile_epilogue.h"
 
 #ifndef DYBIT_MID_W
@@ -78,22 +79,12 @@ __global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_k
     // contiguous range of tiles (all column tiles of a row strip together), so that the A rows
     // it streams are shared inside its own L2.
     int tile_m, tile_n;
-    {
-        const int per_xcd = (int)gridDim.x >> 3;
-        const int l = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-        if (l >= tiles_m * tiles_n) return;                       // uniform per workgroup
-        tile_m = l / tiles_n;
-        tile_n = l - tile_m * tiles_n;
-    }
+    if (!row_order_tile(xcd_contiguous_index(), tiles_m, tiles_n, tile_m, tile_n)) return;   // uniform per workgroup
     const int64_t m0 = (int64_t)tile_m * TM, n0 = (int64_t)tile_n * TN;
 
     // ROWS reads aligned words; the dispatcher takes it only for tensors of a whole number of words, so
     // the descriptor ends exactly with the tensor and no word reaches past it
-    const int64_t a_span = g.a_bytes;
-    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.A), 0, (int)(a_span > 0x7fffffff ? 0x7fffffff : a_span), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcA = code_descriptor(g.A, g.a_bytes), rsrcW = code_descriptor(g.W, g.w_bytes);
 
     // ---- A: the lane's own row, the 32 codes kq of its k-group's 64
     const int a_row_bytes = (int)(g.K * CA::BITS / 8), w_row_bytes = (int)(g.K * CW::BITS / 8);
@@ -108,15 +99,12 @@ __global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_k
         const int64_t m = m0 + wr * 32 + (lane & 31);
         okA = m < g.M;
         if (CONV) {
-            const int64_t mm = okA ? m : 0;
-            const int b = (int)(mm / ((int64_t)g.Ho * g.Wo));
-            const int rem = (int)(mm - (int64_t)b * g.Ho * g.Wo);
-            const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
-            hi0 = ho * g.stride - g.pad;
-            wi0 = wo * g.stride - g.pad;
+            const PixelOrigin o = pixel_origin(g, okA ? m : 0);
+            hi0 = o.hi0;
+            wi0 = o.wi0;
             if (CONV == ROWS) {
                 // first byte of filter row 0 of the pixel (negative left of the first pixel of the tensor)
-                const int first = (int)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes);
+                const int first = (int)(o.first_pixel * pix_bytes);
                 row_shift = (u32)first & 3u;                     // Wd * pix_bytes may be odd: see load_A
                 offA = (u32)first;
                 const int taps = 32 / g.Cin, tap_bits = g.Cin * CA::BITS;
@@ -127,7 +115,7 @@ __global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_k
                     row_keep[i] = (u32)((1ull << up) - 1ull) & ~(u32)((1ull << lo) - 1ull);
                 }
             } else {
-                offA = (u32)((((int64_t)b * g.H + hi0) * g.Wd + wi0) * pix_bytes + kq * RUN_A);
+                offA = (u32)(o.first_pixel * pix_bytes + kq * RUN_A);
             }
         } else {
             offA = okA ? (u32)(m * a_row_bytes + kq * RUN_A) : kOob;
@@ -144,14 +132,8 @@ __global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_k
     // divided out of k every time: first k of the wave's k-group, and for a convolution its filter
     // row, filter column and first channel (all uniform over the wave, hence the readfirstlane above).
     int64_t a_k0 = kgp * 64;
-    int a_fr = 0, a_fs = 0, a_c0 = 0;
-    auto settle_tap = [&]() {
-        while (a_c0 >= g.Cin) {
-            a_c0 -= g.Cin;
-            if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
-        }
-    };
-    if (CONV == 1) { a_c0 = kgp * 64; settle_tap(); }
+    TapCounter tap;
+    if (CONV == 1) tap.advance(kgp * 64, g);
     auto load_A = [&](u32x4 *raw) {
         if constexpr (CONV == ROWS) {
             // filter row of this lane's run, its first byte, and the aligned words that hold it; the
@@ -177,14 +159,14 @@ __global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_k
         }
         u32 off;
         if (CONV) {
-            const bool in = okA && a_k0 < g.K && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
-            off = in ? offA + (u32)((a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * CA::BITS / 8) : kOob;   // padding reads code 0
+            const bool in = okA && a_k0 < g.K && tap.inside(g, hi0, wi0);
+            off = in ? offA + (u32)tap.byte_offset(g, pix_bytes, CA::BITS) : kOob;   // padding reads code 0
         } else {
             off = a_k0 < g.K ? offA + (u32)(a_k0 * CA::BITS / 8) : kOob;
         }
         load_run<CA::BITS>(rsrcA, off, raw);
         a_k0 += TK;
-        if (CONV == 1) { a_c0 += TK; settle_tap(); }
+        if (CONV == 1) tap.advance(TK, g);
     };
     auto load_W = [&](int64_t kt, u32x4 *raw) {
         const int64_t k0 = kt * TK + wq * 32;

@@ -22,6 +22,7 @@
 
 #include "dybit_codec.h"
 #include "gemm_args.h"
+#include "tile_common.h"
 #include "tile_epilogue.h"
 
 #ifndef DYBIT_WS_W
@@ -58,11 +59,7 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_ws_kernel(const GemmArgs g, c
     const int ktiles = (int)(g.K / 64);
 
     // ROWS reads aligned words; the dispatcher takes it only for tensors of a whole number of words
-    const int64_t a_span = g.a_bytes;
-    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.A), 0, (int)(a_span > 0x7fffffff ? 0x7fffffff : a_span), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(g.W), 0, (int)(g.w_bytes > 0x7fffffff ? 0x7fffffff : g.w_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcA = code_descriptor(g.A, g.a_bytes), rsrcW = code_descriptor(g.W, g.w_bytes);
 
     // ---- W: every run of 32 codes is decoded once and stays.  Row n of the tile is K halves plus 16
     // bytes of padding (fragment reads of 32 consecutive rows then fall into different banks); rows
@@ -130,7 +127,8 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_ws_kernel(const GemmArgs g, c
         }
         // position of the next K step to load: first k, and for a convolution its filter row, filter
         // column and first channel (uniform over the wave), counted up from step to step
-        int a_k0 = 0, a_fr = 0, a_fs = 0, a_c0 = 0;
+        int a_k0 = 0;
+        TapCounter tap;
         auto load_A = [&](u32x4 *raw) {
             if constexpr (CONV == ROWS) {
                 const int fr = (a_k0 >> 5) + kq;
@@ -154,19 +152,15 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_ws_kernel(const GemmArgs g, c
             }
             u32 off;
             if (CONV) {
-                const bool in = okA && a_k0 < g.K && (unsigned)(hi0 + a_fr) < (unsigned)g.H && (unsigned)(wi0 + a_fs) < (unsigned)g.Wd;
-                off = in ? offA + (u32)((a_fr * g.Wd + a_fs) * pix_bytes + a_c0 * CA::BITS / 8) : kOob;   // padding reads code 0
+                const bool in = okA && a_k0 < g.K && tap.inside(g, hi0, wi0);
+                off = in ? offA + (u32)tap.byte_offset(g, pix_bytes, CA::BITS) : kOob;   // padding reads code 0
             } else {
                 off = a_k0 < g.K ? offA + (u32)(a_k0 * CA::BITS / 8) : kOob;
             }
             load_run<CA::BITS>(rsrcA, off, raw);
             a_k0 += 64;
             if (CONV == 1) {
-                a_c0 += 64;
-                if (a_c0 >= g.Cin) {
-                    a_c0 = 0;
-                    if (++a_fs == g.kw) { a_fs = 0; ++a_fr; }
-                }
+                tap.advance(64, g);
             }
         };
         auto decode_A = [&](const u32x4 *raw, int q) -> f16x8 {

@@ -4,11 +4,12 @@
 // bit what quantizing the pooled fp32 tensor under the same scale would give, at 1/8 .. 1/4 of the bytes.
 //
 // Layout: NHWC, a pixel is C codes packed along C (C * bits a multiple of 32).  One thread owns one
-// 32-bit word of one output pixel (32 / bits channels): it walks the k x k window, skips the taps outside
-// the image (a window always has one inside: 2 pad <= k), and keeps per channel the largest key, where
-// key(code) = magnitude for a non-negative code and -magnitude for a negative one (sign-magnitude codes
-// order like their keys; unsigned formats are their own keys).  The result is written in canonical form:
-// value zero is always the all-zero code.
+// 32-bit word of one output pixel (32 / bits channels) and walks the k x k window, skipping the taps outside
+// the image (a window always has one inside: 2 pad <= k).  The word is split into planes that hold two fields
+// each in the halves of a register (plane p: fields p and p + 16 / bits), so that one packed 16-bit maximum
+// serves two channels.  Unsigned codes order like their values.  Sign-magnitude codes are first mapped to
+// offset keys (non-negative: code + 2^(bits-1); negative: 2^(bits-1) - 1 - magnitude), which order like the
+// values, and mapped back at the end; value zero is always written as the all-zero code.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -29,13 +30,16 @@ struct PoolArgs {
     int is_signed;
 };
 
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void maxpool_codes_kernel(const PoolArgs a)
 {
-    constexpr int FIELDS = 32 / BITS;
-    constexpr uint32_t kMask = (1u << BITS) - 1u;
-    const uint32_t sign_bit = a.is_signed ? 1u << (BITS - 1) : 0u;
-    const uint32_t mag_mask = a.is_signed ? kMask >> 1 : kMask;
+    constexpr int PLANES = 16 / BITS;                               // fields per 16-bit half
+    constexpr uint32_t kField = (1u << BITS) - 1u;
+    constexpr uint32_t kPlane = kField | (kField << 16);            // field 0 of both halves
+    constexpr uint32_t kSign = (1u << (BITS - 1)) * 0x00010001u, kMag = ((1u << (BITS - 1)) - 1u) * 0x00010001u;
+    const bool is_signed = a.is_signed != 0;                        // uniform
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a.total; i += (int64_t)gridDim.x * kThreads) {
         const int64_t pix = i / a.words;
         const int word = (int)(i - pix * a.words);
@@ -44,26 +48,39 @@ __global__ __launch_bounds__(kThreads) void maxpool_codes_kernel(const PoolArgs 
         const int ho = (int)(t % a.Ho);
         const int64_t b = t / a.Ho;
         const int h_lo = ho * a.stride - a.pad, w_lo = wo * a.stride - a.pad;
-        int best[FIELDS];
+        uint32_t best[PLANES];
 #pragma unroll
-        for (int f = 0; f < FIELDS; ++f) best[f] = INT32_MIN;
+        for (int p = 0; p < PLANES; ++p) best[p] = 0u;              // the smallest key
         for (int r = max(h_lo, 0); r < min(h_lo + a.k, a.H); ++r) {
             const uint32_t *row = a.x + ((b * a.H + r) * a.W) * a.words + word;
             for (int s = max(w_lo, 0); s < min(w_lo + a.k, a.W); ++s) {
                 const uint32_t w = row[(int64_t)s * a.words];
 #pragma unroll
-                for (int f = 0; f < FIELDS; ++f) {
-                    const uint32_t c = (w >> (f * BITS)) & kMask;
-                    const int mag = (int)(c & mag_mask);
-                    best[f] = max(best[f], (c & sign_bit) ? -mag : mag);
+                for (int p = 0; p < PLANES; ++p) {
+                    uint32_t c = (w >> (p * BITS)) & kPlane;
+                    if (is_signed) {
+                        const uint32_t sg = c & kSign;               // key = c ^ sign bit, magnitude inverted where the sign is set
+                        c ^= kSign ^ (sg - (sg >> (BITS - 1)));
+                    }
+                    const u16x2 m = __builtin_elementwise_max(__builtin_bit_cast(u16x2, best[p]), __builtin_bit_cast(u16x2, c));
+                    best[p] = __builtin_bit_cast(uint32_t, m);
                 }
             }
         }
         uint32_t out = 0;
 #pragma unroll
-        for (int f = 0; f < FIELDS; ++f) {
-            const int key = best[f] == INT32_MIN ? 0 : best[f];
-            out |= (key >= 0 ? (uint32_t)key : (sign_bit | (uint32_t)(-key))) << (f * BITS);
+        for (int p = 0; p < PLANES; ++p) {
+            uint32_t c = best[p];
+            if (is_signed) {
+                // keys >= 2^(bits-1) are the non-negative codes; below: negative, magnitude 2^(bits-1) - 1 - key,
+                // and magnitude 0 (the negative zero) becomes the all-zero code
+                const uint32_t pos = c & kSign;                      // set: non-negative
+                const uint32_t neg = (pos ^ kSign) - ((pos ^ kSign) >> (BITS - 1));   // kMag where negative
+                const uint32_t mag = (c ^ neg) & kMag;
+                const uint32_t nz = (mag | (mag >> 1) | (mag >> 2) | (mag >> 3) | (mag >> 4) | (mag >> 5) | (mag >> 6)) & 0x00010001u;
+                c = mag | ((pos ^ kSign) & (nz << (BITS - 1)));      // sign only with a non-zero magnitude
+            }
+            out |= c << (p * BITS);
         }
         a.y[i] = out;
     }

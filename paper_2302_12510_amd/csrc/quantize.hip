@@ -258,13 +258,13 @@ __device__ __forceinline__ ScaleInfo load_scale(const float *scale, float inv_vm
 template <int BITS, bool SIGNED, int UNROLL>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restrict__ x, size_t n4,
                                                             const float *__restrict__ scale,
-                                                            uint8_t *__restrict__ out, float inv_vmax, float *scale_out)
+                                                            uint8_t *__restrict__ out, float inv_vmax, float *scale_out, int *err)
 {
     using word_t = typename std::conditional<BITS == 8, uint32_t,
                    typename std::conditional<BITS == 4, uint16_t, uint8_t>::type>::type;
     const ScaleInfo si = load_scale(scale, inv_vmax, scale_out);
     if (!si.ok) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *err = DYBIT_ERR_BAD_SCALE;
         return;
     }
     const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
@@ -309,11 +309,11 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
 template <bool SIGNED, int UNROLL>
 __global__ __launch_bounds__(kThreads) void quantize6_kernel(const float *__restrict__ x, size_t n4,
                                                              const float *__restrict__ scale,
-                                                             uint8_t *__restrict__ out, float inv_vmax, float *scale_out)
+                                                             uint8_t *__restrict__ out, float inv_vmax, float *scale_out, int *err)
 {
     const ScaleInfo si = load_scale(scale, inv_vmax, scale_out);
     if (!si.ok) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *err = DYBIT_ERR_BAD_SCALE;
         return;
     }
     const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
@@ -356,11 +356,11 @@ __device__ __forceinline__ float code_to_value(uint32_t code, float s)
 
 template <int BITS, bool SIGNED, int UNROLL>
 __global__ __launch_bounds__(kThreads) void fake_quant_kernel(const float *__restrict__ x, size_t n,
-                                                              const float *__restrict__ scale, float *__restrict__ y)
+                                                              const float *__restrict__ scale, float *__restrict__ y, int *err)
 {
     const ScaleInfo si = load_scale(scale);
     if (!si.ok) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *err = DYBIT_ERR_BAD_SCALE;
         return;
     }
     const size_t n4 = n >> 2;
@@ -404,11 +404,12 @@ __global__ __launch_bounds__(kThreads) void fake_quant_kernel(const float *__res
 // Remainder: one thread per group of 4 elements starting at element `first`; exact path, byte stores.
 template <int BITS, bool SIGNED>
 __global__ void quantize_tail_kernel(const float *__restrict__ x, size_t first, size_t n,
-                                     const float *__restrict__ scale, uint8_t *__restrict__ out, float inv_vmax, float *scale_out)
+                                     const float *__restrict__ scale, uint8_t *__restrict__ out, float inv_vmax, float *scale_out,
+                                     int *err)
 {
     const ScaleInfo si = load_scale(scale, inv_vmax, scale_out);
     if (!si.ok) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *err = DYBIT_ERR_BAD_SCALE;
         return;
     }
     const size_t e0 = first + 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);
@@ -427,7 +428,7 @@ __global__ void quantize_tail_kernel(const float *__restrict__ x, size_t first, 
 // code, 4-bit: two, 2-bit: four, 6-bit: four codes in three bytes).
 template <int BITS, bool SIGNED>
 __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const float *__restrict__ x, int64_t cols, float inv_vmax,
-                                                                 float *__restrict__ scales, uint8_t *__restrict__ out)
+                                                                 float *__restrict__ scales, uint8_t *__restrict__ out, int *err)
 {
     constexpr int EPG = BITS == 8 ? 1 : BITS == 4 ? 2 : 4;             // elements per group of whole bytes
     constexpr int BPG = BITS == 6 ? 3 : 1;
@@ -444,7 +445,7 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const float *__
     if (threadIdx.x == 0) scales[blockIdx.x] = s;
     const uint32_t e = (__float_as_uint(s) >> 23) & 0xffu;
     if (!(s > 0.0f) || e == 0u || e == 255u) {                         // an infinite or subnormal maximum: no codes
-        if (threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        if (threadIdx.x == 0) *err = DYBIT_ERR_BAD_SCALE;
         return;
     }
     for (int64_t gi = threadIdx.x; gi < cols / EPG; gi += kThreads) {
@@ -480,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void col_scale_kernel(const float *__rest
 // quantize_rows_kernel), every element with the exact encoder under its own column's scale.
 template <int BITS, bool SIGNED>
 __global__ __launch_bounds__(kThreads) void quantize_cols_kernel(const float *__restrict__ x, int64_t cols, int64_t groups,
-                                                                 const float *__restrict__ scales, uint8_t *__restrict__ out)
+                                                                 const float *__restrict__ scales, uint8_t *__restrict__ out, int *err)
 {
     constexpr int EPG = BITS == 8 ? 1 : BITS == 4 ? 2 : 4;             // elements per group of whole bytes
     constexpr int BPG = BITS == 6 ? 3 : 1;
@@ -499,18 +500,46 @@ __global__ __launch_bounds__(kThreads) void quantize_cols_kernel(const float *__
     }
 #pragma unroll
     for (int b = 0; b < BPG; ++b) out[gi * BPG + b] = (uint8_t)(w >> (8 * b));
-    if (bad) g_async_error = DYBIT_ERR_BAD_SCALE;
+    if (bad) *err = DYBIT_ERR_BAD_SCALE;
+}
+
+// Encoder for a matrix whose rows are padded with zero codes on the way: row r of x holds `cols` floats, row r of
+// the output cols_padded codes (a few-channel image whose pixels must end on a byte or word boundary, e.g. 3 -> 4
+// channels).  One thread per group of four output codes (bits / 2 bytes), every element through the exact
+// encoder; consecutive threads read and write consecutive memory.
+template <int BITS, bool SIGNED>
+__global__ __launch_bounds__(kThreads) void quantize_pad_kernel(const float *__restrict__ x, int cols, int groups_per_row, int64_t groups,
+                                                                const float *__restrict__ scale, uint8_t *__restrict__ out, int *err)
+{
+    const float s = *scale;
+    const uint32_t e = (__float_as_uint(s) >> 23) & 0xffu;
+    if (!(s > 0.0f) || e == 0u || e == 255u) {                         // as dybit_quantize: nothing is written
+        if (blockIdx.x == 0 && threadIdx.x == 0) *err = DYBIT_ERR_BAD_SCALE;
+        return;
+    }
+    for (int64_t gi = (int64_t)blockIdx.x * kThreads + threadIdx.x; gi < groups; gi += (int64_t)gridDim.x * kThreads) {
+        const int64_t row = gi / groups_per_row;
+        const int c0 = (int)(gi - row * groups_per_row) * 4;
+        const float *src = x + row * cols;
+        uint32_t w = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (c0 + k < cols) w |= quantize_exact<BITS, SIGNED>(src[c0 + k], s) << (k * BITS);
+        uint8_t *dst = out + gi * (BITS / 2);
+#pragma unroll
+        for (int b = 0; b < BITS / 2; ++b) dst[b] = (uint8_t)(w >> (8 * b));
+    }
 }
 
 // Straight-through gradient of the quantize-then-decode operator: the incoming gradient where x lies
 // inside [lo, hi] (bounds included), zero elsewhere and for NaN.  12 bytes per element.
 __global__ __launch_bounds__(kThreads) void fake_quant_bwd_kernel(const float *__restrict__ x, const float *__restrict__ grad, size_t n,
                                                                   const float *__restrict__ scale, float vmax, int is_signed,
-                                                                  float *__restrict__ out)
+                                                                  float *__restrict__ out, int *err)
 {
     const float s = *scale;
     if (!(s > 0.0f) || ((__float_as_uint(s) >> 23) & 0xffu) == 255u) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) g_async_error = DYBIT_ERR_BAD_SCALE;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *err = DYBIT_ERR_BAD_SCALE;
         return;
     }
     // s * 2^(m-1) is exact; should it overflow, every finite x is inside and +Inf is not
@@ -616,23 +645,25 @@ template <int BITS, bool SIGNED, int UNROLL>
 static void launch_quantize_u(const float *x, size_t n, const float *scale, uint8_t *out, hipStream_t st,
                               float inv_vmax, float *scale_out)
 {
+    int *err = async_error_word();
+    if (!err) { note_hip(hipErrorInvalidSymbol); return; }         // the entry point then reports DYBIT_ERR_HIP
     if (BITS == 6) {
         const size_t n16 = n / 16;
         if (n16) hipLaunchKernelGGL((quantize6_kernel<SIGNED, UNROLL>),
                                     dim3(grid_for(4 * n16, kThreads * UNROLL, 256 * DYBIT_QUANT_BLOCKS_PER_CU)), dim3(kThreads), 0, st,
-                                    x, 4 * n16, scale, out, inv_vmax, scale_out);
+                                    x, 4 * n16, scale, out, inv_vmax, scale_out, err);
         const size_t first = n16 * 16;
         if (first < n) {
             const size_t groups = (n - first + 3) / 4;
             hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3((unsigned)groups), dim3(1), 0, st, x, first, n, scale, out,
-                               inv_vmax, scale_out);
+                               inv_vmax, scale_out, err);
         }
     } else {
         const size_t n4 = n / 4;
         if (n4) hipLaunchKernelGGL((quantize_kernel<BITS == 6 ? 8 : BITS, SIGNED, UNROLL>),
-                                   dim3(grid_for(n4, kThreads * UNROLL, 256 * DYBIT_QUANT_BLOCKS_PER_CU)), dim3(kThreads), 0, st, x, n4, scale, out, inv_vmax, scale_out);
+                                   dim3(grid_for(n4, kThreads * UNROLL, 256 * DYBIT_QUANT_BLOCKS_PER_CU)), dim3(kThreads), 0, st, x, n4, scale, out, inv_vmax, scale_out, err);
         if (n4 * 4 < n)
-            hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3(1), dim3(1), 0, st, x, n4 * 4, n, scale, out, inv_vmax, scale_out);
+            hipLaunchKernelGGL((quantize_tail_kernel<BITS, SIGNED>), dim3(1), dim3(1), 0, st, x, n4 * 4, n, scale, out, inv_vmax, scale_out, err);
     }
 }
 
@@ -729,8 +760,10 @@ extern "C" dybit_status dybit_quantize_rows(const float *x, int64_t rows, int64_
     if (rows == 0) return DYBIT_OK;
     if (!scales_out || ((!x || !codes_out) && cols)) return DYBIT_ERR_NULL;
     const float inv_vmax = 1.0f / (float)(1u << (mag_bits(f.bits, f.is_signed) - 1));
+    int *err = async_error_word();
+    if (!err) return DYBIT_ERR_HIP;
 #define DYBIT_QR(B, S) hipLaunchKernelGGL((quantize_rows_kernel<B, S>), dim3((unsigned)rows), dim3(kThreads), 0, (hipStream_t)stream, \
-                                          x, cols, inv_vmax, scales_out, codes_out)
+                                          x, cols, inv_vmax, scales_out, codes_out, err)
     switch (f.bits * 2 + f.is_signed) {
         case 4: DYBIT_QR(2, false); break;   case 5: DYBIT_QR(2, true); break;
         case 8: DYBIT_QR(4, false); break;   case 9: DYBIT_QR(4, true); break;
@@ -754,9 +787,11 @@ extern "C" dybit_status dybit_quantize_cols(const float *x, int64_t rows, int64_
     const float inv_vmax = 1.0f / (float)(1u << (mag_bits(f.bits, f.is_signed) - 1));
     hipLaunchKernelGGL(col_scale_kernel, dim3((unsigned)((cols + 63) / 64)), dim3(kThreads), 0, hs, x, rows, cols, inv_vmax, scales_out);
     const int64_t groups = rows * cols / (f.bits == 8 ? 1 : f.bits == 4 ? 2 : 4);
+    int *err = async_error_word();
+    if (!err) return DYBIT_ERR_HIP;
     if (groups) {
         const dim3 grid((unsigned)((groups + kThreads - 1) / kThreads));
-#define DYBIT_QC(B, S) hipLaunchKernelGGL((quantize_cols_kernel<B, S>), grid, dim3(kThreads), 0, hs, x, cols, groups, scales_out, codes_out)
+#define DYBIT_QC(B, S) hipLaunchKernelGGL((quantize_cols_kernel<B, S>), grid, dim3(kThreads), 0, hs, x, cols, groups, scales_out, codes_out, err)
         switch (f.bits * 2 + f.is_signed) {
             case 4: DYBIT_QC(2, false); break;   case 5: DYBIT_QC(2, true); break;
             case 8: DYBIT_QC(4, false); break;   case 9: DYBIT_QC(4, true); break;
@@ -765,6 +800,31 @@ extern "C" dybit_status dybit_quantize_cols(const float *x, int64_t rows, int64_
         }
 #undef DYBIT_QC
     }
+    return launch_status();
+}
+
+extern "C" dybit_status dybit_quantize_pad(const float *x, int64_t rows, int64_t cols, int64_t cols_padded, dybit_fmt f,
+                                           const float *scale, uint8_t *codes_out, dybit_stream stream)
+{
+    dybit_status st = check_fmt(f);
+    if (st != DYBIT_OK) return st;
+    if (rows < 0 || cols < 1 || cols_padded < cols || cols_padded > (1 << 24) || rows > ((int64_t)1 << 40)) return DYBIT_ERR_INVALID_ARG;
+    if (cols_padded % 4) return DYBIT_ERR_ALIGNMENT;
+    if (rows == 0) return DYBIT_OK;
+    if (!x || !scale || !codes_out) return DYBIT_ERR_NULL;
+    int *err = async_error_word();
+    if (!err) return DYBIT_ERR_HIP;
+    const int64_t groups = rows * (cols_padded / 4);
+    const dim3 grid((unsigned)((groups + kThreads - 1) / kThreads < 256 * 64 ? (groups + kThreads - 1) / kThreads : 256 * 64));
+#define DYBIT_QP(B, S) hipLaunchKernelGGL((quantize_pad_kernel<B, S>), grid, dim3(kThreads), 0, (hipStream_t)stream, \
+                                          x, (int)cols, (int)(cols_padded / 4), groups, scale, codes_out, err)
+    switch (f.bits * 2 + f.is_signed) {
+        case 4: DYBIT_QP(2, false); break;   case 5: DYBIT_QP(2, true); break;
+        case 8: DYBIT_QP(4, false); break;   case 9: DYBIT_QP(4, true); break;
+        case 12: DYBIT_QP(6, false); break;  case 13: DYBIT_QP(6, true); break;
+        case 16: DYBIT_QP(8, false); break;  case 17: DYBIT_QP(8, true); break;
+    }
+#undef DYBIT_QP
     return launch_status();
 }
 
@@ -778,8 +838,10 @@ extern "C" dybit_status dybit_fake_quant_bwd(const float *x, const float *grad_o
     if (n == 0) return DYBIT_OK;
     const float vmax = (float)(1u << (mag_bits(f.bits, f.is_signed) - 1));
     const int grid = grid_for(n / 4 + 1, kThreads * 2, 256 * 64);
+    int *err = async_error_word();
+    if (!err) return DYBIT_ERR_HIP;
     hipLaunchKernelGGL(fake_quant_bwd_kernel, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, x, grad_out, n, scale, vmax,
-                       f.is_signed, grad_in);
+                       f.is_signed, grad_in, err);
     return launch_status();
 }
 
@@ -793,7 +855,9 @@ extern "C" dybit_status dybit_fake_quant(const float *x, size_t n, dybit_fmt f, 
     if (n == 0) return DYBIT_OK;
     hipStream_t hs = (hipStream_t)stream;
     const int grid = grid_for(n / 4 + 1, kThreads * 4, 256 * DYBIT_QUANT_BLOCKS_PER_CU);
-#define DYBIT_FQ(B, S) hipLaunchKernelGGL((fake_quant_kernel<B, S, 4>), dim3(grid), dim3(kThreads), 0, hs, x, n, scale, y_out)
+    int *err = async_error_word();
+    if (!err) return DYBIT_ERR_HIP;
+#define DYBIT_FQ(B, S) hipLaunchKernelGGL((fake_quant_kernel<B, S, 4>), dim3(grid), dim3(kThreads), 0, hs, x, n, scale, y_out, err)
     switch (f.bits * 2 + f.is_signed) {
         case 4: DYBIT_FQ(2, false); break;   case 5: DYBIT_FQ(2, true); break;
         case 8: DYBIT_FQ(4, false); break;   case 9: DYBIT_FQ(4, true); break;
@@ -824,13 +888,33 @@ extern "C" dybit_status dybit_dequantize(const uint8_t *codes, size_t n, dybit_f
 }
 
 namespace dybit {
-// Device address of the asynchronous error flag on the current device (each device has its own copy).
+namespace {
+thread_local int *tl_error_word = nullptr;        // caller-owned word of this host thread, or NULL: the library's
+}
+// Device word that receives asynchronous errors of the calls this host thread makes: the caller's
+// (dybit_set_async_error_word), else the library's own on the current device (each device has its copy;
+// the address is looked up once per device).
 int *async_error_word()
 {
-    void *ptr = nullptr;
-    return hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_async_error)) == hipSuccess ? static_cast<int *>(ptr) : nullptr;
+    if (tl_error_word) return tl_error_word;
+    static int *cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    if (!cached[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_async_error)) != hipSuccess) return nullptr;
+        cached[dev] = static_cast<int *>(ptr);
+    }
+    return cached[dev];
 }
 }  // namespace dybit
+
+extern "C" dybit_status dybit_set_async_error_word(int32_t *device_word)
+{
+    if (reinterpret_cast<uintptr_t>(device_word) & 3u) return DYBIT_ERR_ALIGNMENT;
+    dybit::tl_error_word = device_word;
+    return DYBIT_OK;
+}
 
 extern "C" dybit_status dybit_get_last_async_error(int32_t *flag_out, dybit_stream stream)
 {

@@ -290,10 +290,21 @@ class DybitNetwork:
                 Bn, H, W, C = src.shape
                 p = self._layer_params(l, H, W) if op == "conv" else self.params[name]
                 a_fmt = (p["a_bits"], not nonneg[l["src"]])
-                if p["cpad"] != C:
+                key = (l["src"], a_fmt, p["cpad"])                  # two consumers of one tensor in one format share its codes
+                pad_kernel = p["cpad"] != C and p["cpad"] % 4 == 0 and key not in encoded
+                if pad_kernel:
+                    # channels padded with zero codes by the encoder itself (zero padding keeps the maximum)
+                    if l["src"] in known_max:
+                        sa = B.dybit_scale_from_absmax(known_max[l["src"]], *a_fmt)
+                    else:
+                        sa = B.dybit_absmax_scale(src.reshape(-1), *a_fmt)
+                    qa = B.dybit_quantize_pad(src.reshape(-1, C), p["cpad"], sa, *a_fmt)
+                    encoded[key] = (sa, qa)
+                    if record is not None:
+                        src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
+                elif p["cpad"] != C:
                     src = torch.nn.functional.pad(src, (0, p["cpad"] - C))
                 flat = src.reshape(-1)
-                key = (l["src"], a_fmt, p["cpad"])                  # two consumers of one tensor in one format share its codes
                 if key in encoded:
                     sa, qa = encoded[key]
                 elif l["src"] in known_max:                     # zero padding of channels keeps the maximum
@@ -434,6 +445,8 @@ class DybitNetwork:
                 p = self._layer_params(l, H, W) if op == "conv" else self.params[name]
                 if l["src"] in codes and codes[l["src"]][0] == a_fmt:
                     qa = codes[l["src"]][2]                         # written by the producer's epilogue
+                elif p["cpad"] != C and p["cpad"] % 4 == 0:
+                    qa = B.dybit_quantize_pad(src.reshape(-1, C), p["cpad"], sa, *a_fmt)
                 else:
                     if p["cpad"] != C:
                         src = torch.nn.functional.pad(src, (0, p["cpad"] - C))

@@ -237,3 +237,21 @@ def test_dwconv_argument_errors_without_gpu():
     assert dw(bias=C.c_void_p(0x1004)) == B.ERR_ALIGNMENT
     assert dw(Cn=0) == B.OK
 
+
+
+def test_code_chain_argument_errors_without_gpu():
+    """Shortcut as codes, pooling on codes, caller-owned error word: refusals on the host."""
+    L = B.lib()
+    f2, f4, f6, f8 = B.fmt(2, False), B.fmt(4, False), B.fmt(6, False), B.fmt(8, True)
+    p, null = C.c_void_p(0x1000), C.c_void_p(0)
+    rc = lambda r=p, rf=f4, rs=p, codes=p, N=64: L.dybit_gemm_wb_rc(64, N, 64, p, f4, p, p, f8, p, null, r, rf, rs, 1,
+                                                                     null, N, null, f4, p, codes, None)
+    assert rc(rf=f2) == B.ERR_UNSUPPORTED_BITS
+    assert rc(r=null) == B.ERR_NULL and rc(rs=null) == B.ERR_NULL and rc(codes=null) == B.ERR_NULL
+    pool = lambda Cn=8, f=f4, k=3, st=2, pad=1, x=p, y=p: L.dybit_maxpool2d_codes(1, 8, 8, Cn, k, st, pad, x, f, y, None)
+    assert pool(f=f6) == B.ERR_UNSUPPORTED_BITS
+    assert pool(Cn=4) == B.ERR_ALIGNMENT and pool(x=C.c_void_p(0x1002)) == B.ERR_ALIGNMENT
+    assert pool(pad=2) == B.ERR_INVALID_ARG and pool(st=0) == B.ERR_INVALID_ARG and pool(k=20, pad=3) == B.ERR_INVALID_ARG
+    assert pool(x=null) == B.ERR_NULL and pool(y=null) == B.ERR_NULL
+    assert L.dybit_set_async_error_word(C.c_void_p(0x1002)) == B.ERR_ALIGNMENT
+    assert L.dybit_set_async_error_word(null) == B.OK

@@ -212,3 +212,70 @@ def test_config5b_full_size():
             del y
         del codes, q, want, got
     assert B.dybit_get_last_async_error() == B.OK
+
+
+def test_caller_owned_error_word():
+    """dybit_set_async_error_word: this thread's kernels report into the caller's word, the library's flag stays
+    clear; NULL restores the library's flag."""
+    x = torch.randn(4096, device="cuda")
+    word = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert B.dybit_get_last_async_error() == B.OK
+    B.dybit_set_async_error_word(word)
+    try:
+        B.dybit_quantize(x, scalar(0.0), 4, True)
+        torch.cuda.synchronize()
+        assert word.item() == B.ERR_BAD_SCALE
+        word.zero_()
+        B.dybit_fake_quant(x, scalar(float("nan")), 8, True)
+        torch.cuda.synchronize()
+        assert word.item() == B.ERR_BAD_SCALE
+        word.zero_()
+        a = torch.zeros(64 * 64, dtype=torch.uint8, device="cuda")
+        B.dybit_gemm_wb(64, 64, 64, a, (8, False), scalar(1.0), a, (8, True), scalar(1.0), (8, False), scalar(-1.0))
+        torch.cuda.synchronize()
+        assert word.item() == B.ERR_BAD_SCALE
+        word.zero_()
+        B.dybit_quantize(x, scalar(0.5), 4, True)
+        torch.cuda.synchronize()
+        assert word.item() == B.OK
+        assert B.dybit_get_last_async_error() == B.OK
+    finally:
+        B.dybit_set_async_error_word(None)
+    B.dybit_quantize(x, scalar(0.0), 4, True)
+    assert B.dybit_get_last_async_error() == B.ERR_BAD_SCALE
+    assert B.dybit_get_last_async_error() == B.OK
+
+
+@pytest.mark.parametrize("fmt", [(2, False), (2, True), (4, False), (4, True), (6, False), (6, True), (8, False), (8, True)])
+@pytest.mark.parametrize("shape", [(1000, 3, 4), (37, 1, 4), (513, 5, 8), (64, 4, 4), (9, 7, 16)])
+def test_quantize_pad(fmt, shape):
+    """dybit_quantize_pad: the codes of dybit_quantize on the zero-padded tensor, byte for byte against the
+    oracle (special values and exact ties included)."""
+    rows, cols, cpad = shape
+    rng = np.random.default_rng(rows + fmt[0])
+    x = rng.laplace(0, 1.0, (rows, cols)).astype(np.float32)
+    x.reshape(-1)[:6] = [0.0, -0.0, np.inf, -np.inf, np.nan, 1e-30][: min(6, x.size)]
+    s = R.absmax_scale(np.where(np.isfinite(x), x, 0), *fmt)
+    mids = R.midpoints(R.magnitude_bits(*fmt)) * np.float64(s)
+    k = min(mids.size, x.size - 6)
+    if k > 0:
+        x.reshape(-1)[6:6 + k] = mids[:k].astype(np.float32)          # decision points (exact where representable)
+    xp = np.zeros((rows, cpad), dtype=np.float32)
+    xp[:, :cols] = x
+    want = R.pack_rows(R.quantize(xp, s, *fmt).reshape(rows, cpad), fmt[0])
+    got = B.dybit_quantize_pad(dev(x), cpad, scalar(s), *fmt)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want)
+    assert B.dybit_get_last_async_error() == B.OK
+
+
+def test_quantize_pad_refusals_and_bad_scale():
+    x = torch.randn(16, 3, device="cuda")
+    with pytest.raises(B.DybitError) as e:
+        B.dybit_quantize_pad(x, 6, scalar(1.0), 4, False)
+    assert e.value.status == B.ERR_ALIGNMENT
+    with pytest.raises(B.DybitError) as e:
+        B.dybit_quantize_pad(x, 0, scalar(1.0), 4, False)
+    assert e.value.status == B.ERR_INVALID_ARG
+    B.dybit_quantize_pad(x, 4, scalar(0.0), 4, False)
+    assert B.dybit_get_last_async_error() == B.ERR_BAD_SCALE
