@@ -432,7 +432,8 @@ typedef enum {
     DYBIT_KERNEL_F8_256 = 7,         /* e4m3 MFMA, 256 x 256 tile                                       */
     DYBIT_KERNEL_F8_128_KG1 = 8,     /* e4m3 MFMA, 128 x 128 tile, one k-group                          */
     DYBIT_KERNEL_F8_128_KG2 = 9,     /* e4m3 MFMA, 128 x 128 tile, two k-groups                         */
-    DYBIT_KERNEL_F8_64 = 10          /* e4m3 MFMA, 64 x 64 tile, two k-groups                           */
+    DYBIT_KERNEL_F8_64 = 10,         /* e4m3 MFMA, 64 x 64 tile, two k-groups                           */
+    DYBIT_KERNEL_F8_WS = 11          /* e4m3 MFMA, weight-stationary                                    */
 } dybit_kernel_id;
 int32_t dybit_last_gemm_kernel(void);
 dybit_status dybit_set_option(const char *name, const char *value);

@@ -112,7 +112,7 @@ def _ptr(t) -> int | None:
 
 # ---- host-only --------------------------------------------------------------
 KERNEL_NAMES = ("none", "general", "f16_256", "f16_128_kg1", "f16_128_kg2", "f16_128_rows", "f16_ws",
-                "f8_256", "f8_128_kg1", "f8_128_kg2", "f8_64")
+                "f8_256", "f8_128_kg1", "f8_128_kg2", "f8_64", "f8_ws")
 
 
 def dybit_last_gemm_kernel() -> str:

@@ -21,6 +21,7 @@
 #include <type_traits>
 
 #include "dybit_codec.h"
+#include "dybit_codec8.h"
 #include "gemm_args.h"
 #include "tile_common.h"
 #include "tile_epilogue.h"
@@ -45,7 +46,7 @@ constexpr int THREADS = 512, SLAB = 256;                           // eight wave
 constexpr int ROWS = 2;
 
 template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
-__global__ __launch_bounds__(THREADS, 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+__global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
@@ -232,6 +233,154 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_ws_kernel(const GemmArgs g, c
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same kernel on the fp8 matrix path, for pairs of 4- and 2-bit formats (every value exact in e4m3,
+// dybit_codec8.h): `v_mfma_f32_32x32x64_f8f6f4` contracts 64 k per instruction in the time the fp16 instruction
+// needs for 32, the resident weight tile holds bytes instead of halves (half the LDS, half the bytes per
+// fragment read: with one fragment read per MFMA, LDS bandwidth is what the fp16 form runs into at N = 64),
+// and a K step is one MFMA per column block.  Lane (row, kq) supplies k = 32 kq .. + 31 of the step: one
+// 128-bit (2-bit codes: 64-bit) load of its own row, decoded in registers into the 32-byte A fragment.
+// CONV: 0 matrix product, 1 convolution with Cin a multiple of 64.
+// ---------------------------------------------------------------------------
+#if DYBIT_WS_W == 0 || DYBIT_WS_W == 6
+template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
+__global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws8_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+{
+    using f8::i32x8;
+    constexpr int BA = f8::bits_of<FMT_A>(), BW = f8::bits_of<FMT_W>();
+    constexpr int RUN_A = 4 * BA, RUN_W = 4 * BW;                    // bytes of a run of 32 codes
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kq = lane >> 5;
+    const int ktiles = (int)(g.K / 64);
+    const __amdgpu_buffer_rsrc_t rsrcA = code_descriptor(g.A, g.a_bytes), rsrcW = code_descriptor(g.W, g.w_bytes);
+    auto load_run8 = [&](const __amdgpu_buffer_rsrc_t &rs, u32 off, auto bits_tag) -> u32x4 {
+        if constexpr (decltype(bits_tag)::value == 2) {
+            const f8::u32x2 two = __builtin_amdgcn_raw_buffer_load_b64(rs, off, 0, 0);
+            return u32x4{two.x, two.y, 0u, 0u};
+        } else {
+            return __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+        }
+    };
+
+    // ---- W: every run of 32 codes is decoded once into 32 bytes and stays.  Row n of the tile is K bytes plus
+    // 16 bytes of padding; rows N .. 32 CB - 1 hold zeros (fetched from the out-of-range offset).
+    {
+        const int runs_per_row = ktiles * 2, w_row_bytes = (int)(g.K * BW / 8);
+        const int total = CB * 32 * runs_per_row;
+        for (int r = tid; r < total; r += THREADS) {
+            const int row = r / runs_per_row, run = r - row * runs_per_row;
+            const u32x4 raw = load_run8(rsrcW, row < g.N ? (u32)(row * w_row_bytes + run * RUN_W) : kOob, std::integral_constant<int, BW>{});
+            const i32x8 f = f8::decode_fragment<FMT_W>(raw);
+            char *dst = lds + row * row_bytes + run * 32;
+            *reinterpret_cast<u32x4 *>(dst) = u32x4{(u32)f[0], (u32)f[1], (u32)f[2], (u32)f[3]};
+            *reinterpret_cast<u32x4 *>(dst + 16) = u32x4{(u32)f[4], (u32)f[5], (u32)f[6], (u32)f[7]};
+        }
+    }
+    __syncthreads();
+
+    const int a_row_bytes = (int)(g.K * BA / 8);
+    const int pix_bytes = CONV ? g.pix_bytes : 0;
+    const u32 rdW = (u32)(lane & 31) * (u32)row_bytes + (u32)kq * 32;   // K step adds 64 B, column block j 32 rows
+
+    float run_max = 0.0f;
+    for (int slab = blockIdx.x; slab < slabs; slab += gridDim.x) {
+        const int64_t m_strip = (int64_t)slab * SLAB + wave * 32;
+        if (m_strip >= g.M) continue;                                // uniform per wave; no barriers below
+        u32 offA;
+        int hi0 = 0, wi0 = 0;
+        const int64_t m = m_strip + (lane & 31);
+        const bool okA = m < g.M;
+        if (CONV) {
+            const PixelOrigin o = pixel_origin(g, okA ? m : 0);
+            hi0 = o.hi0;
+            wi0 = o.wi0;
+            offA = (u32)(o.first_pixel * pix_bytes + kq * RUN_A);    // the image is under 2 GiB
+        } else {
+            offA = okA ? (u32)(m * a_row_bytes + kq * RUN_A) : kOob;
+        }
+        int a_k0 = 0;
+        TapCounter tap;
+        auto load_A = [&]() -> u32x4 {
+            u32 off;
+            if (CONV) {
+                const bool in = okA && a_k0 < g.K && tap.inside(g, hi0, wi0);
+                off = in ? offA + (u32)tap.byte_offset(g, pix_bytes, BA) : kOob;   // padding reads code 0
+                tap.advance(64, g);
+            } else {
+                off = a_k0 < g.K ? offA + (u32)(a_k0 * BA / 8) : kOob;
+            }
+            a_k0 += 64;
+            return load_run8(rsrcA, off, std::integral_constant<int, BA>{});
+        };
+
+        f32x16 acc[CB];
+#pragma unroll
+        for (int j = 0; j < CB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+
+        u32x4 rawA[2];
+        rawA[0] = load_A();
+        rawA[1] = load_A();
+        i32x8 fa = f8::decode_fragment<FMT_A, true>(rawA[0]);
+        // One K step: CB MFMAs on the fragment decoded during the previous step; the codes of step kt + 2 are
+        // requested once step kt + 1's are decoded.
+        auto step = [&](int kt, auto stage_tag) {
+            constexpr int s = decltype(stage_tag)::value;
+            const char *wk = lds + rdW + kt * 64;
+            const i32x8 fa_cur = fa;
+            i32x8 fw[CB];
+#pragma unroll
+            for (int j = 0; j < CB; ++j) {
+                const u32x4 lo = *reinterpret_cast<const u32x4 *>(wk + j * 32 * row_bytes);
+                const u32x4 hi = *reinterpret_cast<const u32x4 *>(wk + j * 32 * row_bytes + 16);
+                fw[j] = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            }
+            fa = f8::decode_fragment<FMT_A, true>(rawA[s ^ 1]);
+#pragma unroll
+            for (int j = 0; j < CB; ++j)
+                acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa_cur, fw[j], acc[j], 0, 0, 0, 0, 0, 0);
+            rawA[s] = load_A();
+        };
+        for (int kt = 0; kt < ktiles; kt += 2) {
+            step(kt, std::integral_constant<int, 0>{});
+            if (kt + 1 < ktiles) step(kt + 1, std::integral_constant<int, 1>{});
+        }
+        run_max = fmaxf(run_max, epilogue_strip<CB, WB, false, 0>(g, acc, m_strip, 0));
+    }
+
+    if (g.absmax_bits) {                                            // one merge per workgroup, as in the fp16 form
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) run_max = fmaxf(run_max, __shfl_xor(run_max, off, 64));
+        __syncthreads();                                            // every wave is done with the weight tile
+        float *red = reinterpret_cast<float *>(lds);
+        if (lane == 0) red[wave] = run_max;
+        __syncthreads();
+        if (tid == 0) {
+            float mm = red[0];
+#pragma unroll
+            for (int w = 1; w < THREADS / 64; ++w) mm = fmaxf(mm, red[w]);
+            const uint32_t bits = __float_as_uint(mm);
+            if (bits > __hip_atomic_load(g.absmax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(g.absmax_bits, bits);
+        }
+    }
+}
+
+template <int FA, int FW, int CONV, int CB>
+static void launch_cb8(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
+{
+    const int slabs = (int)((g.M + SLAB - 1) / SLAB);
+    const int per_cu = (lds_bytes <= 80 * 1024 && CB == 2 && !kWriteBack) ? 2 : 1;   // workgroups that fit a compute unit (LDS, registers)
+    const int grid = slabs < 256 * per_cu ? slabs : 256 * per_cu;
+    auto k = gemm_ws8_kernel<FA, FW, CONV, CB, kWriteBack>;
+    note_kernel(DYBIT_KERNEL_F8_WS);
+    note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(THREADS), lds_bytes, st, g, slabs, row_bytes);
+}
+#endif
+
 template <int FA, int FW, int CONV, int CB>
 static void launch_cb(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
 {
@@ -250,10 +399,21 @@ static bool launch(const GemmArgs &g, bool conv, hipStream_t st)
     // Up to 128 columns: with more, a wave's accumulators leave no registers for the epilogue and the
     // 128 x 128 kernel is as fast or faster (measured).
     const int cb = g.N <= 64 ? 2 : 4;
+    const bool rows = conv && g.Cin < 64;                            // kw * Cin = 32 (checked by the dispatcher)
+#if DYBIT_WS_W == 0 || DYBIT_WS_W == 6
+    // both operands 4- or 2-bit: the fp8 matrix path, unless the "gemm_mfma" option asks for fp16
+    if constexpr (FA == F4S || FA == F4U || FA == F2S || FA == F2U) {
+        const int row8 = (int)g.K + 16, lds8 = cb * 32 * row8;
+        if (!rows && !dispatch_options().mfma_f16 && g.N <= 128 && lds8 <= 160 * 1024 && g.M <= 0x7fffffff) {
+            if (cb == 2) { if (conv) launch_cb8<FA, FW, 1, 2>(g, st, row8, lds8); else launch_cb8<FA, FW, 0, 2>(g, st, row8, lds8); }
+            else { if (conv) launch_cb8<FA, FW, 1, 4>(g, st, row8, lds8); else launch_cb8<FA, FW, 0, 4>(g, st, row8, lds8); }
+            return true;
+        }
+    }
+#endif
     const int row_bytes = (int)g.K * 2 + 16;
     const int lds_bytes = cb * 32 * row_bytes;
     if (g.N > 128 || lds_bytes > 160 * 1024 || g.M > 0x7fffffff) return false;
-    const bool rows = conv && g.Cin < 64;                            // kw * Cin = 32 (checked by the dispatcher)
 #define DYBIT_WS_CB(C_) \
     if (rows) launch_cb<FA, FW, ROWS, C_>(g, st, row_bytes, lds_bytes); \
     else if (conv) launch_cb<FA, FW, 1, C_>(g, st, row_bytes, lds_bytes); \

@@ -264,7 +264,7 @@ KERNELS = ["large", "mid1", "mid2", "mid64", "large-f16", "mid1-f16", "mid2-f16"
 # kernels (binding.KERNEL_NAMES) that a forced family may legitimately run on, by matrix path
 _FAMILY = {"large": ({"f16_256"}, {"f8_256"}), "mid1": ({"f16_128_kg1", "f16_128_rows"}, {"f8_128_kg1"}),
            "mid2": ({"f16_128_kg2", "f16_128_rows"}, {"f8_128_kg2"}), "mid": ({"f16_128_kg1", "f16_128_kg2", "f16_128_rows"}, set()),
-           "mid64": (set(), {"f8_64"}), "ws": ({"f16_ws"}, set()), "general": ({"general"}, {"general"})}
+           "mid64": (set(), {"f8_64"}), "ws": ({"f16_ws"}, {"f8_ws"}), "general": ({"general"}, {"general"})}
 _expected_kernels = None
 
 
