@@ -511,9 +511,8 @@ template <int BITS, bool SIGNED>
 __global__ __launch_bounds__(kThreads) void quantize_pad_kernel(const float *__restrict__ x, int cols, int groups_per_row, int64_t groups,
                                                                 const float *__restrict__ scale, uint8_t *__restrict__ out, int *err)
 {
-    const float s = *scale;
-    const uint32_t e = (__float_as_uint(s) >> 23) & 0xffu;
-    if (!(s > 0.0f) || e == 0u || e == 255u) {                         // as dybit_quantize: nothing is written
+    const ScaleInfo si = load_scale(scale);
+    if (!si.ok) {                                                      // as dybit_quantize: nothing is written
         if (blockIdx.x == 0 && threadIdx.x == 0) *err = DYBIT_ERR_BAD_SCALE;
         return;
     }
@@ -521,13 +520,23 @@ __global__ __launch_bounds__(kThreads) void quantize_pad_kernel(const float *__r
         const int64_t row = gi / groups_per_row;
         const int c0 = (int)(gi - row * groups_per_row) * 4;
         const float *src = x + row * cols;
-        uint32_t w = 0;
+        float e[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (c0 + k < cols) w |= quantize_exact<BITS, SIGNED>(src[c0 + k], s) << (k * BITS);
+        for (int k = 0; k < 4; ++k) e[k] = c0 + k < cols ? src[c0 + k] : 0.0f;   // the padding: value 0, code 0
+        bool redo;
+        uint32_t w = quantize_fast4<BITS, SIGNED>(e, si.rinv, redo);
+        if (redo | si.all_exact) {
+            w = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w |= quantize_exact<BITS, SIGNED>(e[k], si.s) << (k * BITS);
+        }
         uint8_t *dst = out + gi * (BITS / 2);
+        if constexpr (BITS == 8) *reinterpret_cast<uint32_t *>(dst) = w;       // groups are whole, aligned words / halves
+        else if constexpr (BITS == 4) *reinterpret_cast<uint16_t *>(dst) = (uint16_t)w;
+        else {
 #pragma unroll
-        for (int b = 0; b < BITS / 2; ++b) dst[b] = (uint8_t)(w >> (8 * b));
+            for (int b = 0; b < BITS / 2; ++b) dst[b] = (uint8_t)(w >> (8 * b));
+        }
     }
 }
 
