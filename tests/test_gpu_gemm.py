@@ -608,3 +608,37 @@ def test_scale_from_absmax_of_zero_is_one():
     v = torch.full((1,), 6.0, dtype=torch.float32, device="cuda")
     assert B.dybit_scale_from_absmax(v, 4, True).item() == 1.5       # 2^(m-1) = 4
     assert B.dybit_scale_from_absmax(v, 8, False).item() == 6.0 / 128
+
+
+@pytest.mark.parametrize("force_kernel", ["large", "mid1", "mid2", "mid64", "ws", "general"], indirect=True)
+@pytest.mark.parametrize("case", ["c_off4", "bias_off4", "res_off4", "ldc_odd", "n_mod4_2"])
+def test_epilogue_alignment_cases(force_kernel, case):
+    """The epilogue moves four neighbouring columns of a row as one 128-bit word only when every tensor it
+    touches allows it; each case breaks one condition (an output, bias or shortcut that starts 4 bytes past a
+    16-byte boundary, an odd leading dimension, N = 2 mod 4) and must give the same results element by element."""
+    rng = np.random.default_rng(77)
+    a_fmt, w_fmt = (4, False), (4, True)
+    M, K = 200, 128
+    N = 98 if case == "n_mod4_2" else 96
+    ldc = 101 if case == "ldc_odd" else (N + 8 if case != "n_mod4_2" else N)
+    qa = random_codes(rng, (M, K), a_fmt)
+    qw = random_codes(rng, (N, K), w_fmt)
+    bias = rng.normal(0, 2, N).astype(np.float32)
+    res = rng.normal(0, 20, (M, ldc)).astype(np.float32)
+    want, den = R.gemm(qa, a_fmt, 0.3, qw, w_fmt, 0.05, bias, True, res[:, :N])
+
+    def shifted(a, on):          # the same values in a buffer that starts 4 bytes past a 16-byte boundary
+        flat = torch.empty(a.size + 4, dtype=torch.float32, device="cuda")
+        view = flat[1 if on else 0:][:a.size].view(a.shape)
+        view.copy_(dev(a))
+        return view
+    out = shifted(np.full((M, ldc), -777.0, dtype=np.float32), case == "c_off4")
+    mx = torch.zeros(1, dtype=torch.float32, device="cuda")
+    c = B.dybit_gemm_ex(M, N, K, pack_rows_dev(qa, 4), a_fmt, scalar(0.3), pack_rows_dev(qw, 4), w_fmt, scalar(0.05),
+                        shifted(bias, case == "bias_off4"), shifted(res, case == "res_off4"), True, mx, out=out, ldc=ldc)
+    assert_forced_kernel_ran()
+    torch.cuda.synchronize()
+    got = c.cpu().numpy()
+    assert_within(got[:, :N], want, den, shortcut=True)
+    assert np.all(got[:, N:] == -777.0)                      # nothing written past column N
+    assert mx.item() == np.abs(got[:, :N]).max()
