@@ -35,7 +35,19 @@ namespace ws {
 
 using namespace fast;
 
-constexpr int THREADS = 512, SLAB = 256;                           // eight waves, 32 rows each
+// Waves per workgroup (32 rows each).  Eight; four in the write-back build of the two-block form, whose
+// epilogue needs about 170 registers: three four-wave workgroups then share a compute unit (three waves per
+// SIMD) where a single eight-wave one would fit, and the encoder of one overlaps the K loops of the others.
+template <int CB, bool WB> constexpr int waves_of() { return (WB && CB == 2) ? 4 : 8; }
+// Workgroups of the persistent grid per compute unit: what the weight tiles in LDS (160 KiB) and the registers
+// allow (two-block form: two eight-wave workgroups at 128 registers, three four-wave ones at 168 in the
+// write-back build; four-block form: one).
+template <int CB> inline int workgroups_per_cu(int lds_bytes)
+{
+    const int by_lds = (160 * 1024) / lds_bytes;
+    const int by_regs = CB == 2 ? (kWriteBack ? 3 : 2) : 1;
+    return by_lds < by_regs ? (by_lds < 1 ? 1 : by_lds) : by_regs;
+}
 
 // CONV: 0 matrix product; 1 convolution whose 64-code k groups lie inside one filter tap (Cin a
 // multiple of 64); 2 (ROWS) convolution with few channels where one filter row is exactly one 32-code
@@ -46,8 +58,9 @@ constexpr int THREADS = 512, SLAB = 256;                           // eight wave
 constexpr int ROWS = 2;
 
 template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
-__global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+__global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) : 2)) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
 {
+    constexpr int THREADS = 64 * waves_of<CB, WB>(), SLAB = 32 * waves_of<CB, WB>();
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;
     constexpr int WORDS_A = CA::BITS;                               // 32-bit words in a run of 32 codes
@@ -244,8 +257,9 @@ __global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws_ker
 // ---------------------------------------------------------------------------
 #if DYBIT_WS_W == 0 || DYBIT_WS_W == 6
 template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
-__global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws8_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+__global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) : 2)) void gemm_ws8_kernel(const GemmArgs g, const int slabs, const int row_bytes)
 {
+    constexpr int THREADS = 64 * waves_of<CB, WB>(), SLAB = 32 * waves_of<CB, WB>();
     using f8::i32x8;
     constexpr int BA = f8::bits_of<FMT_A>(), BW = f8::bits_of<FMT_W>();
     constexpr int RUN_A = 4 * BA, RUN_W = 4 * BW;                    // bytes of a run of 32 codes
@@ -371,9 +385,9 @@ __global__ __launch_bounds__(THREADS, (CB == 2 && !WB) ? 4 : 2) void gemm_ws8_ke
 template <int FA, int FW, int CONV, int CB>
 static void launch_cb8(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
 {
+    constexpr int THREADS = 64 * waves_of<CB, kWriteBack>(), SLAB = 32 * waves_of<CB, kWriteBack>();
     const int slabs = (int)((g.M + SLAB - 1) / SLAB);
-    const int per_cu = (lds_bytes <= 80 * 1024 && CB == 2 && !kWriteBack) ? 2 : 1;   // workgroups that fit a compute unit (LDS, registers)
-    const int grid = slabs < 256 * per_cu ? slabs : 256 * per_cu;
+    const int grid = slabs < 256 * workgroups_per_cu<CB>(lds_bytes) ? slabs : 256 * workgroups_per_cu<CB>(lds_bytes);
     auto k = gemm_ws8_kernel<FA, FW, CONV, CB, kWriteBack>;
     note_kernel(DYBIT_KERNEL_F8_WS);
     note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
@@ -384,9 +398,9 @@ static void launch_cb8(const GemmArgs &g, hipStream_t st, int row_bytes, int lds
 template <int FA, int FW, int CONV, int CB>
 static void launch_cb(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
 {
+    constexpr int THREADS = 64 * waves_of<CB, kWriteBack>(), SLAB = 32 * waves_of<CB, kWriteBack>();
     const int slabs = (int)((g.M + SLAB - 1) / SLAB);
-    const int per_cu = (lds_bytes <= 80 * 1024 && CB == 2 && !kWriteBack) ? 2 : 1;  // workgroups that fit a compute unit (LDS, registers; the write-back epilogue needs the registers of a second one)
-    const int grid = slabs < 256 * per_cu ? slabs : 256 * per_cu;
+    const int grid = slabs < 256 * workgroups_per_cu<CB>(lds_bytes) ? slabs : 256 * workgroups_per_cu<CB>(lds_bytes);
     auto k = gemm_ws_kernel<FA, FW, CONV, CB, kWriteBack>;
     note_kernel(DYBIT_KERNEL_F16_WS);
     note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
