@@ -124,9 +124,13 @@ bool launch_gemm_tiled(const GemmArgs &g, int a_bits, int w_bits, bool conv, hip
     const int force = opt.kernel;
     if (force == DYBIT_FORCE_GENERAL) return false;
 
-    // Weight-stationary kernel: the whole decoded weight matrix in LDS, for many rows against few
-    // weights (it declines when the weights do not fit).
-    if (force == DYBIT_FORCE_WS || (!force && !opt.ws_off && g.N <= 128 && g.M >= 16384)) {
+    // Weight-stationary kernel: the decoded weights of up to 128 columns (N > 128: of a group of 64) stay in
+    // LDS, for many rows against few weights (it declines when the weights do not fit).  Wider than 128 columns
+    // it is taken where it was measured faster than the 128 x 128 kernel (M x N x K from 401408 x 256 x 64 to
+    // 25088 x 1024 x 256): with the write-back epilogue and a short K, 1.05 to 1.25 times; with fp32 results
+    // only its 256-byte row segments lose to the tile's 512-byte ones.
+    const bool ws_wide = g.q_out != nullptr && g.K <= 256 && (g.C == nullptr || g.K >= 128);
+    if (force == DYBIT_FORCE_WS || (!force && !opt.ws_off && g.M >= 16384 && (g.N <= 128 || ws_wide))) {
         const bool wb_ = g.q_out != nullptr;
         bool done = false;
         switch (w_bits) {

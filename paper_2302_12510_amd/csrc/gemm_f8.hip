@@ -50,7 +50,7 @@ template <int NWM, int KG> struct Geom {
 };
 
 template <int FMT_A, int FMT_W, bool CONV, int NWM, int KG, bool WB>
-__global__ __launch_bounds__(64 * NWM * KG, NWM == 2 ? 4 : (NWM == 4 && KG == 1 && !WB) ? 3 : 2)
+__global__ __launch_bounds__(64 * NWM * KG, NWM == 2 ? 4 : (NWM == 4 && KG == 1) ? 3 : 2)
 void gemm_f8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using G = Geom<NWM, KG>;

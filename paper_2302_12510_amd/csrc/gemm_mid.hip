@@ -60,7 +60,7 @@ static_assert(Geom<2>::LDS_BYTES >= 4 * 4 * 16 * 64 * 4, "reduction buffer must 
 constexpr int ROWS = 2;
 
 template <int FMT_A, int FMT_W, int CONV, int KG, bool WB>
-__global__ __launch_bounds__(256 * KG, (KG == 1 && !WB) ? 3 : 2) void gemm_mid_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
+__global__ __launch_bounds__(256 * KG, (KG == 1) ? 3 : 2) void gemm_mid_kernel(const GemmArgs g, const int tiles_m, const int tiles_n)
 {
     using CA = Codec<FMT_A>;
     using CW = Codec<FMT_W>;

@@ -1,6 +1,8 @@
-// Weight-stationary DyBit matrix product for gfx950, for layers whose whole weight matrix fits the
-// LDS of a compute unit once decoded (N rows of K halves plus padding <= 160 KiB; N <= 128): the 1 x 1
-// and the early 3 x 3 convolutions of a network, where M (output pixels) is huge and N * K is small.
+// Weight-stationary DyBit matrix product for gfx950, for layers where a workgroup can keep its weights
+// in the LDS of a compute unit once decoded (64 or 128 rows of W of K halves plus padding, <= 160 KiB): the
+// 1 x 1 and the early 3 x 3 convolutions of a network, where M (output pixels) is huge and K is short.
+// Up to N = 128 a workgroup holds the whole weight matrix; a wider N is split into groups of 64 columns,
+// one per workgroup, and the workgroups of the groups walk over A side by side.
 //
 // The tiled kernels decode the weight tile of every K step again in every workgroup, and with a
 // small K that work, the barriers around it and the half-empty 128-column tile of an N = 64 layer
@@ -49,6 +51,36 @@ template <int CB> inline int workgroups_per_cu(int lds_bytes)
     return by_lds < by_regs ? (by_lds < 1 ? 1 : by_lds) : by_regs;
 }
 
+// N > 32 CB: the columns are split into groups of 32 CB and a workgroup keeps the weights of one group.  The
+// workgroups that walk over the same slabs of A, one per group, sit on the same XCD (workgroup ids that agree
+// modulo 8) and next to each other in its launch order, so that a slab read by the first comes out of that XCD's
+// L2 for the others.  walker: which slab sequence this workgroup follows, of `walkers` (gridDim.x / groups).
+struct ColumnGroup {
+    int n0, walker, walkers;
+};
+template <int CB> __device__ __forceinline__ ColumnGroup column_group(int groups)
+{
+    ColumnGroup c{0, (int)blockIdx.x, (int)gridDim.x};
+    if (groups > 1) {
+        const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+        c.n0 = (local % groups) * (CB * 32);
+        c.walker = (local / groups) * 8 + xcd;
+        c.walkers = (int)gridDim.x / groups;
+    }
+    return c;
+}
+// Persistent grid for `groups` column groups: a multiple of 8 * groups workgroups (0: more groups than the chip
+// holds workgroups), no more walkers than there are slabs (rounded up to the eight XCDs).
+inline int grid_for_groups(int slabs, int groups, int resident)
+{
+    if (groups == 1) return slabs < resident ? slabs : resident;
+    const int per = 8 * groups;
+    int walkers = resident / per * 8;
+    const int needed = (slabs + 7) / 8 * 8;
+    if (needed < walkers) walkers = needed;
+    return walkers * groups;
+}
+
 // CONV: 0 matrix product; 1 convolution whose 64-code k groups lie inside one filter tap (Cin a
 // multiple of 64); 2 (ROWS) convolution with few channels where one filter row is exactly one 32-code
 // run (kw * Cin = 32): the run of lane-half kq in K step t is filter row 2 t + kq of the lane's output
@@ -58,7 +90,7 @@ template <int CB> inline int workgroups_per_cu(int lds_bytes)
 constexpr int ROWS = 2;
 
 template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
-__global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) : 2)) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+__global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) : 2)) void gemm_ws_kernel(const GemmArgs g, const int slabs, const int row_bytes, const int groups)
 {
     constexpr int THREADS = 64 * waves_of<CB, WB>(), SLAB = 32 * waves_of<CB, WB>();
     using CA = Codec<FMT_A>;
@@ -71,6 +103,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kq = lane >> 5;
     const int ktiles = (int)(g.K / 64);
+    const ColumnGroup cg = column_group<CB>(groups);
 
     // ROWS reads aligned words; the dispatcher takes it only for tensors of a whole number of words
     const __amdgpu_buffer_rsrc_t rsrcA = code_descriptor(g.A, g.a_bytes), rsrcW = code_descriptor(g.W, g.w_bytes);
@@ -84,7 +117,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
         for (int r = tid; r < total; r += THREADS) {
             const int row = r / runs_per_row, run = r - row * runs_per_row;
             u32x4 raw[NW];
-            load_run<CW::BITS>(rsrcW, row < g.N ? (u32)(row * w_row_bytes + run * RUN_W) : kOob, raw);
+            load_run<CW::BITS>(rsrcW, cg.n0 + row < g.N ? (u32)((cg.n0 + row) * w_row_bytes + run * RUN_W) : kOob, raw);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 u32 d[4];
@@ -100,7 +133,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
     const u32 rdW = (u32)(lane & 31) * (u32)row_bytes + (u32)kq * 64;   // K step adds 128 B, block kk 16 B, column block j 32 rows
 
     float run_max = 0.0f;                                            // max |C| over every strip this lane stores
-    for (int slab = blockIdx.x; slab < slabs; slab += gridDim.x) {
+    for (int slab = cg.walker; slab < slabs; slab += cg.walkers) {
         const int64_t m_strip = (int64_t)slab * SLAB + wave * 32;
         if (m_strip >= g.M) continue;                                // uniform per wave; no barriers below
         // ---- A: the lane's own row, the 32 codes kq of every K step
@@ -224,7 +257,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
             step(kt, std::integral_constant<int, 0>{});
             if (kt + 1 < ktiles) step(kt + 1, std::integral_constant<int, 1>{});
         }
-        run_max = fmaxf(run_max, epilogue_strip<CB, WB, false, CA::ACC_EXP + CW::ACC_EXP>(g, acc, m_strip, 0));
+        run_max = fmaxf(run_max, epilogue_strip<CB, WB, false, CA::ACC_EXP + CW::ACC_EXP>(g, acc, m_strip, cg.n0));
     }
 
     // ---- running maximum: one merge per workgroup.  The persistent waves finish their strips in step,
@@ -257,7 +290,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
 // ---------------------------------------------------------------------------
 #if DYBIT_WS_W == 0 || DYBIT_WS_W == 6
 template <int FMT_A, int FMT_W, int CONV, int CB, bool WB>
-__global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) : 2)) void gemm_ws8_kernel(const GemmArgs g, const int slabs, const int row_bytes)
+__global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) : 2)) void gemm_ws8_kernel(const GemmArgs g, const int slabs, const int row_bytes, const int groups)
 {
     constexpr int THREADS = 64 * waves_of<CB, WB>(), SLAB = 32 * waves_of<CB, WB>();
     using f8::i32x8;
@@ -268,6 +301,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kq = lane >> 5;
     const int ktiles = (int)(g.K / 64);
+    const ColumnGroup cg = column_group<CB>(groups);
     const __amdgpu_buffer_rsrc_t rsrcA = code_descriptor(g.A, g.a_bytes), rsrcW = code_descriptor(g.W, g.w_bytes);
     auto load_run8 = [&](const __amdgpu_buffer_rsrc_t &rs, u32 off, auto bits_tag) -> u32x4 {
         if constexpr (decltype(bits_tag)::value == 2) {
@@ -285,7 +319,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
         const int total = CB * 32 * runs_per_row;
         for (int r = tid; r < total; r += THREADS) {
             const int row = r / runs_per_row, run = r - row * runs_per_row;
-            const u32x4 raw = load_run8(rsrcW, row < g.N ? (u32)(row * w_row_bytes + run * RUN_W) : kOob, std::integral_constant<int, BW>{});
+            const u32x4 raw = load_run8(rsrcW, cg.n0 + row < g.N ? (u32)((cg.n0 + row) * w_row_bytes + run * RUN_W) : kOob, std::integral_constant<int, BW>{});
             const i32x8 f = f8::decode_fragment<FMT_W>(raw);
             char *dst = lds + row * row_bytes + run * 32;
             *reinterpret_cast<u32x4 *>(dst) = u32x4{(u32)f[0], (u32)f[1], (u32)f[2], (u32)f[3]};
@@ -299,7 +333,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
     const u32 rdW = (u32)(lane & 31) * (u32)row_bytes + (u32)kq * 32;   // K step adds 64 B, column block j 32 rows
 
     float run_max = 0.0f;
-    for (int slab = blockIdx.x; slab < slabs; slab += gridDim.x) {
+    for (int slab = cg.walker; slab < slabs; slab += cg.walkers) {
         const int64_t m_strip = (int64_t)slab * SLAB + wave * 32;
         if (m_strip >= g.M) continue;                                // uniform per wave; no barriers below
         u32 offA;
@@ -362,7 +396,7 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
             step(kt, std::integral_constant<int, 0>{});
             if (kt + 1 < ktiles) step(kt + 1, std::integral_constant<int, 1>{});
         }
-        run_max = fmaxf(run_max, epilogue_strip<CB, WB, false, 0>(g, acc, m_strip, 0));
+        run_max = fmaxf(run_max, epilogue_strip<CB, WB, false, 0>(g, acc, m_strip, cg.n0));
     }
 
     if (g.absmax_bits) {                                            // one merge per workgroup, as in the fp16 form
@@ -383,59 +417,64 @@ __global__ __launch_bounds__((64 * waves_of<CB, WB>()), (CB == 2 ? (WB ? 3 : 4) 
 }
 
 template <int FA, int FW, int CONV, int CB>
-static void launch_cb8(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
+static bool launch_cb8(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
 {
     constexpr int THREADS = 64 * waves_of<CB, kWriteBack>(), SLAB = 32 * waves_of<CB, kWriteBack>();
     const int slabs = (int)((g.M + SLAB - 1) / SLAB);
-    const int grid = slabs < 256 * workgroups_per_cu<CB>(lds_bytes) ? slabs : 256 * workgroups_per_cu<CB>(lds_bytes);
+    const int groups = (int)((g.N + CB * 32 - 1) / (CB * 32));
+    const int grid = grid_for_groups(slabs, groups, 256 * workgroups_per_cu<CB>(lds_bytes));
+    if (grid < 1) return false;
     auto k = gemm_ws8_kernel<FA, FW, CONV, CB, kWriteBack>;
     note_kernel(DYBIT_KERNEL_F8_WS);
     note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
-    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(THREADS), lds_bytes, st, g, slabs, row_bytes);
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(THREADS), lds_bytes, st, g, slabs, row_bytes, groups);
+    return true;
 }
 #endif
 
 template <int FA, int FW, int CONV, int CB>
-static void launch_cb(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
+static bool launch_cb(const GemmArgs &g, hipStream_t st, int row_bytes, int lds_bytes)
 {
     constexpr int THREADS = 64 * waves_of<CB, kWriteBack>(), SLAB = 32 * waves_of<CB, kWriteBack>();
     const int slabs = (int)((g.M + SLAB - 1) / SLAB);
-    const int grid = slabs < 256 * workgroups_per_cu<CB>(lds_bytes) ? slabs : 256 * workgroups_per_cu<CB>(lds_bytes);
+    const int groups = (int)((g.N + CB * 32 - 1) / (CB * 32));
+    const int grid = grid_for_groups(slabs, groups, 256 * workgroups_per_cu<CB>(lds_bytes));
+    if (grid < 1) return false;
     auto k = gemm_ws_kernel<FA, FW, CONV, CB, kWriteBack>;
     note_kernel(DYBIT_KERNEL_F16_WS);
     note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
-    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(THREADS), lds_bytes, st, g, slabs, row_bytes);
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(THREADS), lds_bytes, st, g, slabs, row_bytes, groups);
+    return true;
 }
 
 template <int FA, int FW>
 static bool launch(const GemmArgs &g, bool conv, hipStream_t st)
 {
-    // Up to 128 columns: with more, a wave's accumulators leave no registers for the epilogue and the
-    // 128 x 128 kernel is as fast or faster (measured).
-    const int cb = g.N <= 64 ? 2 : 4;
+    // Up to 128 columns a wave takes all of them (two or four 32-column blocks): with more, its accumulators
+    // leave no registers for the epilogue.  Beyond that the columns go in groups of 64, one group per workgroup.
+    const int cb = (g.N <= 64 || g.N > 128) ? 2 : 4;
     const bool rows = conv && g.Cin < 64;                            // kw * Cin = 32 (checked by the dispatcher)
+    if (g.M > 0x7fffffff) return false;
 #if DYBIT_WS_W == 0 || DYBIT_WS_W == 6
     // both operands 4- or 2-bit: the fp8 matrix path, unless the "gemm_mfma" option asks for fp16
     if constexpr (FA == F4S || FA == F4U || FA == F2S || FA == F2U) {
         const int row8 = (int)g.K + 16, lds8 = cb * 32 * row8;
-        if (!rows && !dispatch_options().mfma_f16 && g.N <= 128 && lds8 <= 160 * 1024 && g.M <= 0x7fffffff) {
-            if (cb == 2) { if (conv) launch_cb8<FA, FW, 1, 2>(g, st, row8, lds8); else launch_cb8<FA, FW, 0, 2>(g, st, row8, lds8); }
-            else { if (conv) launch_cb8<FA, FW, 1, 4>(g, st, row8, lds8); else launch_cb8<FA, FW, 0, 4>(g, st, row8, lds8); }
-            return true;
+        if (!rows && !dispatch_options().mfma_f16 && lds8 <= 160 * 1024) {
+            if (cb == 2) return conv ? launch_cb8<FA, FW, 1, 2>(g, st, row8, lds8) : launch_cb8<FA, FW, 0, 2>(g, st, row8, lds8);
+            return conv ? launch_cb8<FA, FW, 1, 4>(g, st, row8, lds8) : launch_cb8<FA, FW, 0, 4>(g, st, row8, lds8);
         }
     }
 #endif
     const int row_bytes = (int)g.K * 2 + 16;
     const int lds_bytes = cb * 32 * row_bytes;
-    if (g.N > 128 || lds_bytes > 160 * 1024 || g.M > 0x7fffffff) return false;
+    if (lds_bytes > 160 * 1024) return false;
 #define DYBIT_WS_CB(C_) \
-    if (rows) launch_cb<FA, FW, ROWS, C_>(g, st, row_bytes, lds_bytes); \
-    else if (conv) launch_cb<FA, FW, 1, C_>(g, st, row_bytes, lds_bytes); \
-    else launch_cb<FA, FW, 0, C_>(g, st, row_bytes, lds_bytes)
+    return rows ? launch_cb<FA, FW, ROWS, C_>(g, st, row_bytes, lds_bytes) \
+         : conv ? launch_cb<FA, FW, 1, C_>(g, st, row_bytes, lds_bytes) \
+                : launch_cb<FA, FW, 0, C_>(g, st, row_bytes, lds_bytes)
     if (cb == 2) { DYBIT_WS_CB(2); }
-    else { DYBIT_WS_CB(4); }
+    DYBIT_WS_CB(4);
 #undef DYBIT_WS_CB
-    return true;
 }
 
 }  // namespace ws

@@ -463,11 +463,13 @@ WS_PAIRS = [((4, False), (4, True)), ((8, True), (4, True)), ((8, False), (8, Tr
 @pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
 @pytest.mark.parametrize("a_fmt,w_fmt", WS_PAIRS)
 @pytest.mark.parametrize("shape", [(1000, 64, 64), (300, 70, 192), (2049, 128, 576), (257, 100, 128), (5, 128, 256),
-                                   (70000, 33, 64)])
+                                   (70000, 33, 64), (3000, 256, 64), (1500, 200, 128), (70000, 320, 64), (257, 1000, 192)])
 def test_weight_stationary_kernel(force_kernel, a_fmt, w_fmt, shape):
     """The whole weight matrix decoded into LDS once, a persistent grid walking over the rows: N not a
     multiple of 32, ragged M, one to nine K steps, more slabs than workgroups (70000 rows), both
-    column-block counts (N <= 64, <= 128); bias + ReLU and a leading dimension larger than N."""
+    column-block counts (N <= 64, <= 128); N > 128 in column groups of 64 (a whole number of groups, a last
+    group of 8 columns, five groups with more slabs than slab walkers, sixteen groups with fewer);
+    bias + ReLU and a leading dimension larger than N."""
     M, N, K = shape
     rng = np.random.default_rng(M + 7 * N + K)
     qa = random_codes(rng, (M, K), a_fmt)
@@ -482,10 +484,12 @@ def test_weight_stationary_kernel(force_kernel, a_fmt, w_fmt, shape):
 @pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
 @pytest.mark.parametrize("x_fmt,w_fmt", WS_PAIRS[:6])
 @pytest.mark.parametrize("geom", [(3, 1, 1), (1, 1, 0), (3, 2, 1), (1, 2, 0)])
-def test_weight_stationary_kernel_conv(force_kernel, x_fmt, w_fmt, geom):
+@pytest.mark.parametrize("Cout", [96, 264])
+def test_weight_stationary_kernel_conv(force_kernel, x_fmt, w_fmt, geom, Cout):
+    """Cout = 264: five column groups, the last of 8 channels."""
     k, stride, pad = geom
     rng = np.random.default_rng(k * 11 + stride)
-    Bn, H, W, Cin, Cout = 3, 13, 11, 64, 96
+    Bn, H, W, Cin = 3, 13, 11, 64
     qx = random_codes(rng, (Bn, H, W, Cin), x_fmt)
     qw = random_codes(rng, (Cout, k, k, Cin), w_fmt)
     bias = rng.normal(0, 1, Cout).astype(np.float32)

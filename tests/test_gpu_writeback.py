@@ -103,10 +103,12 @@ def test_conv2d_wb(force_kernel, y_fmt):
 
 @pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
 @pytest.mark.parametrize("c_fmt", OUT_FMTS)
-def test_gemm_wb_weight_stationary(force_kernel, c_fmt):
+@pytest.mark.parametrize("N", [96, 320])
+def test_gemm_wb_weight_stationary(force_kernel, c_fmt, N):
+    """N = 320: five column groups of 64, each in a workgroup of its own."""
     rng = np.random.default_rng(47 + c_fmt[0])
     a_fmt, w_fmt = (8, False), (4, True)
-    M, N, K = 777, 96, 128
+    M, K = 777, 128
     qa = random_codes(rng, (M, K), a_fmt)
     qw = random_codes(rng, (N, K), w_fmt)
     bias = rng.normal(0, 3, N).astype(np.float32)
@@ -201,10 +203,11 @@ def test_gemm_wb_shortcut_as_codes(force_kernel, r_fmt, a_fmt):
 
 @pytest.mark.parametrize("force_kernel", ["ws"], indirect=True)
 @pytest.mark.parametrize("r_fmt", R_FMTS)
-def test_gemm_wb_shortcut_as_codes_weight_stationary(force_kernel, r_fmt):
+@pytest.mark.parametrize("N", [96, 320])
+def test_gemm_wb_shortcut_as_codes_weight_stationary(force_kernel, r_fmt, N):
     rng = np.random.default_rng(59 + r_fmt[0])
     a_fmt, w_fmt, c_fmt = (8, False), (4, True), (4, False)
-    M, N, K = 777, 96, 128
+    M, K = 777, 128
     qa = random_codes(rng, (M, K), a_fmt)
     qw = random_codes(rng, (N, K), w_fmt)
     qr = rng.integers(0, 1 << r_fmt[0], (M, N)).astype(np.uint8)
