@@ -502,8 +502,10 @@ def test_weight_stationary_kernel_conv(force_kernel, x_fmt, w_fmt, geom, Cout):
 @pytest.mark.parametrize("x_fmt,w_fmt,Cin,kw", [((8, True), (8, True), 4, 8), ((6, True), (4, True), 4, 8), ((4, False), (6, True), 8, 4),
                                                  ((2, True), (8, True), 4, 8), ((8, False), (4, True), 2, 16)])
 @pytest.mark.parametrize("kh,stride,pad,shape", [(8, 2, 3, (3, 23, 21)), (2, 3, 4, (2, 12, 16)), (4, 1, 2, (2, 9, 27)), (6, 2, 5, (1, 30, 17))])
-def test_weight_stationary_kernel_few_channels(force_kernel, x_fmt, w_fmt, Cin, kw, kh, stride, pad, shape):
-    """Filter rows of exactly 32 codes fetched row by row (see test_conv_few_channels), weights resident.
+@pytest.mark.parametrize("Cout", [100, 200])
+def test_weight_stationary_kernel_few_channels(force_kernel, x_fmt, w_fmt, Cin, kw, kh, stride, pad, shape, Cout):
+    """Filter rows of exactly 32 codes fetched row by row (see test_conv_few_channels), weights resident
+    (Cout = 200: in four column groups).
     The rows are fetched as aligned 32-bit words, so the kernel is only taken for image tensors of a
     whole number of words; the others must fall back to the general kernel (and still be right)."""
     global _expected_kernels
@@ -511,7 +513,6 @@ def test_weight_stationary_kernel_few_channels(force_kernel, x_fmt, w_fmt, Cin, 
     if (Bn * H * W * Cin * x_fmt[0] // 8) % 4:
         _expected_kernels = {"general"}
     rng = np.random.default_rng(Cin * 100 + kw * 10 + kh + 1)
-    Cout = 100
     qx = random_codes(rng, (Bn, H, W, Cin), x_fmt)
     qw = random_codes(rng, (Cout, kh, kw, Cin), w_fmt)
     bias = rng.normal(0, 1, Cout).astype(np.float32)
