@@ -23,11 +23,14 @@ namespace dybit {
 
 // G: fractional bits kept by the magic-number rounding.  The error of c is below 1.5 * 2^(m-24), so
 // G = 13 serves every format (m <= 8), and 2^m + magic stays inside the magic number's binade.
+// The magic number carries one half more than 1.5 * 2^(23-G): the rounded sum is the same number of units of
+// 2^-G plus that half (adding an even number of units changes neither the rounding nor its tie rule), so a
+// fraction of exactly one half reads as G zero bits and is found by one shift.
 struct Requant {
     static constexpr int G = 13;
-    static constexpr uint32_t kMagic = ((uint32_t)(127 + 23 - G) << 23) | 0x400000u;   // 1.5 * 2^(23-G)
+    static constexpr uint32_t kMagic = (((uint32_t)(127 + 23 - G) << 23) | 0x400000u) + (1u << (G - 1));   // 1.5 * 2^(23-G) + 1/2
     static constexpr uint32_t kRound = kMagic + (1u << (G - 1));
-    static constexpr uint32_t kFracMask = (1u << G) - 1u, kFracHalf = 1u << (G - 1);
+    static constexpr uint32_t kFracMask = (1u << G) - 1u;
     float rinv;         // fl(1 / s)
     float p, s2;        // power of two that brings s into [1, 2), and s * p
     float vmax;         // 2^(m-1): the largest magnitude
@@ -70,7 +73,7 @@ __device__ __forceinline__ Requant make_requant(const float *scale, int bits, in
 }
 
 // Fast path, first half: the bit pattern of (2^m - c) + magic for the value x.  The G low bits are the
-// rounded fraction of c; requant_needs_settling() says whether they read one half.  A NaN gives c = 0.
+// rounded fraction of c plus one half; requant_needs_settling() says whether the fraction is one half.  A NaN gives c = 0.
 __device__ __forceinline__ uint32_t requant_rounded(float x, const Requant &r)
 {
     const float t = __uint_as_float(__float_as_uint(x * r.rinv) & r.abs_mask);  // |x| / s, or x / s (negative: clamped to 0 below)
@@ -82,14 +85,14 @@ __device__ __forceinline__ uint32_t requant_rounded(float x, const Requant &r)
 
 __device__ __forceinline__ bool requant_needs_settling(uint32_t zb)
 {
-    return (zb & Requant::kFracMask) == Requant::kFracHalf;
+    return (zb & Requant::kFracMask) == 0u;
 }
 
-// The same test in a form that accumulates with an unsigned minimum: zero exactly when the G low
-// bits of zb read one half (the field moves to the top of the word and the addition flips its top bit).
+// The same test in a form that accumulates with an unsigned minimum: zero exactly when the fraction is
+// one half (the G low bits, moved to the top of the word, are all zero).
 __device__ __forceinline__ uint32_t requant_settle_key(uint32_t zb)
 {
-    return (zb << (32 - Requant::G)) + 0x80000000u;
+    return zb << (32 - Requant::G);
 }
 
 // Fast path, second half: the magnitude code, c rounded half up (the low m bits of the difference:

@@ -169,7 +169,9 @@ __device__ __forceinline__ float store_strip_wb(const GemmArgs &g, const fast::f
     const bool track = g.absmax_bits != nullptr;
     // ReLU as a maximum with a uniform floor (no select per value).  Without ReLU the floor is NaN:
     // the maximum of a number and NaN is the number, and a NaN result stays NaN (and becomes code 0)
-    const float relu_floor = g.relu ? 0.0f : __builtin_nanf("");
+    uint32_t floor_bits = (uint32_t)__builtin_amdgcn_readfirstlane(g.relu ? 0 : 0x7fc00000);
+    asm volatile("" : "+s"(floor_bits));                               // opaque: else the maximum becomes a maximum and a select per value
+    const float relu_floor = __uint_as_float(floor_bits);
     float mx = 0.0f;
     constexpr bool PREFETCH = HAS_RES && CB <= 4;
     // fp32 shortcut: the value's bits; codes: the byte that holds the code (6-bit: that byte and the next one in
