@@ -137,7 +137,8 @@ __device__ __forceinline__ uint32_t requant_code(float x, const Requant &r)
 // footprint as eight lanes storing words).  4-bit codes: a lane pair ORs its two nibbles together
 // with one data-parallel lane permute and the even lane stores the byte.  6-bit codes: each lane
 // shifts its code to its position inside a 32-bit word, the four lanes that share 24 bits OR their
-// parts together (two permutes), and 16 lanes' 96 bits leave as three words.  No LDS, no memory;
+// parts together (two permutes), a third permute fetches the next group's 24 bits (lanes 12 .. 15 of a row of 16
+// read zero there and store nothing), and 16 lanes' 96 bits leave as three words.  No LDS, no memory;
 // all 64 lanes must be active.
 __device__ __forceinline__ uint32_t or_quad(uint32_t w)
 {
@@ -181,7 +182,7 @@ __device__ __forceinline__ uint32_t pack_word(uint32_t code, int lane, const Pac
     if (BITS == 6) {
         // four lanes hold 24 bits; word k of the three takes the rest from the next group of four
         const uint32_t k = (lane >> 2) & 3;
-        const uint32_t next = (uint32_t)__shfl_down((int)w, 4, 16);
+        const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x104, 0xf, 0xf, true);   // row_shl:4: lane i reads lane i + 4 of its row of 16
         w = (w >> (8 * k)) | (next << (24 - 8 * k));
     }
     return w;
